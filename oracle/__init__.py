@@ -1,0 +1,148 @@
+"""ctypes access to the CPU oracle (oracle/*.cpp).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the GPU library and its Python binding never do.  The wrappers below only
+marshal numpy arrays; all arithmetic is in the C++ files.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "liboracle.so"
+SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp"]
+_lib = None
+
+NUM_BINS = 33
+PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge"}
+
+
+def build(force: bool = True) -> Path:
+    """Compile the oracle with the host compiler (no HIP involved)."""
+    if not force and LIB_PATH.exists() and all(LIB_PATH.stat().st_mtime >= s.stat().st_mtime for s in SOURCES):
+        return LIB_PATH
+    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra", "-ffp-contract=off",
+           "-o", str(LIB_PATH)] + [str(s) for s in SOURCES]
+    subprocess.run(cmd, check=True)
+    global _lib
+    _lib = None
+    return LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            build()
+        _lib = C.CDLL(str(LIB_PATH))
+        i64, i32, f32, vp = C.c_int64, C.c_int32, C.c_float, C.c_void_p
+        _lib.oracle_spmv_csr_f32.argtypes = [i64, i64, vp, vp, vp, vp, vp, f32, f32, vp, vp]
+        _lib.oracle_spmv_csr_f32.restype = C.c_int
+        _lib.oracle_spmv_csr_bf16.argtypes = [i64, i64, vp, vp, vp, vp, vp, f32, f32, vp, vp]
+        _lib.oracle_spmv_csr_bf16.restype = C.c_int
+        _lib.oracle_row_stats.argtypes = [i64, vp, vp]
+        _lib.oracle_row_stats.restype = None
+        _lib.oracle_row_bins.argtypes = [i64, vp, vp, vp, vp]
+        _lib.oracle_row_bins.restype = None
+        _lib.oracle_row_blocks.argtypes = [i64, vp, i32, i32, vp]
+        _lib.oracle_row_blocks.restype = i64
+        _lib.oracle_merge_path.argtypes = [i64, i64, vp, i32, vp, vp]
+        _lib.oracle_merge_path.restype = i64
+        _lib.oracle_plan.argtypes = [i64, i64, i64, i32]
+        _lib.oracle_plan.restype = i32
+        _lib.oracle_vector_lanes.argtypes = [i64, i64]
+        _lib.oracle_vector_lanes.restype = i32
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a, dtype, size=None):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags.c_contiguous, (type(a), getattr(a, "dtype", None))
+    if size is not None:
+        assert a.size == size, (a.size, size)
+    return a
+
+
+def spmv_csr(dtype, m, n, rowptr, colidx, vals, x, y0=None, alpha=1.0, beta=0.0):
+    """Returns (y_ref float64[m], S_ref float64[m]); S_ref[i] = sum_k |a_ik x_k|."""
+    lib = _load()
+    _chk(rowptr, np.int32, m + 1)
+    nnz = int(rowptr[-1]) if m >= 0 else 0
+    _chk(colidx, np.int32, nnz)
+    if dtype == "f32":
+        _chk(vals, np.float32, nnz), _chk(x, np.float32, n)
+        fn = lib.oracle_spmv_csr_f32
+    elif dtype == "bf16":
+        _chk(vals, np.uint16, nnz), _chk(x, np.uint16, n)
+        fn = lib.oracle_spmv_csr_bf16
+    else:
+        raise ValueError(dtype)
+    if beta != 0.0:
+        _chk(y0, np.float32, m)
+    else:
+        y0 = None
+    y = np.empty(m, dtype=np.float64)
+    S = np.empty(m, dtype=np.float64)
+    rc = fn(m, n, _p(rowptr), _p(colidx), _p(vals), _p(x), _p(y0), alpha, beta, _p(y), _p(S))
+    if rc != 0:
+        raise ValueError("malformed CSR input")
+    return y, S
+
+
+def spmv_problem(p):
+    """Oracle result for a workloads.CsrProblem-like object."""
+    return spmv_csr(p.dtype, p.m, p.n, p.rowptr, p.colidx, p.vals, p.x, p.y0, p.alpha, p.beta)
+
+
+def row_stats(rowptr):
+    lib = _load()
+    m = rowptr.size - 1
+    out = np.zeros(3, dtype=np.int64)
+    lib.oracle_row_stats(m, _p(_chk(rowptr, np.int32)), _p(out))
+    return {"min_len": int(out[0]), "max_len": int(out[1]), "n_empty": int(out[2])}
+
+
+def row_bins(rowptr):
+    lib = _load()
+    m = rowptr.size - 1
+    cnt = np.zeros(NUM_BINS, dtype=np.int32)
+    off = np.zeros(NUM_BINS + 1, dtype=np.int32)
+    rows = np.zeros(m, dtype=np.int32)
+    lib.oracle_row_bins(m, _p(_chk(rowptr, np.int32)), _p(cnt), _p(off), _p(rows))
+    return cnt, off, rows
+
+
+def row_blocks(rowptr, block_nnz, rows_max):
+    lib = _load()
+    m = rowptr.size - 1
+    out = np.zeros(m + 1, dtype=np.int32)
+    nb = lib.oracle_row_blocks(m, _p(_chk(rowptr, np.int32)), block_nnz, rows_max, _p(out))
+    return out[: nb + 1].copy()
+
+
+def merge_path(rowptr, ipc):
+    lib = _load()
+    m = rowptr.size - 1
+    nnz = int(rowptr[-1])
+    P = (m + nnz + ipc - 1) // ipc
+    mp_row = np.zeros(P + 1, dtype=np.int32)
+    mp_nz = np.zeros(P + 1, dtype=np.int32)
+    P2 = lib.oracle_merge_path(m, nnz, _p(_chk(rowptr, np.int32)), ipc, _p(mp_row), _p(mp_nz))
+    assert P2 == P
+    return mp_row, mp_nz
+
+
+def plan(m, nnz, max_len, block_nnz):
+    return int(_load().oracle_plan(m, nnz, max_len, block_nnz))
+
+
+def vector_lanes(m, nnz):
+    return int(_load().oracle_vector_lanes(m, nnz))

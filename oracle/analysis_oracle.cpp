@@ -1,0 +1,138 @@
+// CPU oracle for the integer outputs of the analysis step.  TEST INFRASTRUCTURE ONLY.
+//
+// The GPU library's spmv_csr_analyze() derives, from the CSR row offsets alone, the row
+// statistics, a length-binned row list, a row-block partition and a merge-path split.
+// The definitions are restated here in their most literal form (counting loops, a
+// sequential greedy scan, a step-by-step merge walk) so that each can be checked by eye.
+// Nothing here is shared with, or called by, the library; results must match bit for bit.
+//
+// The paper fixes only the CSR layout (App. C task 12: row_offsets holds "the starting
+// index of each row", length rows+1).  The partitions themselves are this project's
+// definitions; they are spelled out in the function comments below.
+
+#include <cstdint>
+
+extern "C" {
+
+// ---- row statistics ---------------------------------------------------------------
+// out[0] = min row length, out[1] = max row length, out[2] = number of empty rows.
+// m == 0 gives 0, 0, 0.
+void oracle_row_stats(int64_t m, const int32_t* rowptr, int64_t* out) {
+    int64_t mn = 0, mx = 0, empty = 0;
+    for (int64_t i = 0; i < m; ++i) {
+        const int64_t len = static_cast<int64_t>(rowptr[i + 1]) - rowptr[i];
+        if (i == 0 || len < mn) mn = len;
+        if (i == 0 || len > mx) mx = len;
+        if (len == 0) ++empty;
+    }
+    out[0] = mn;
+    out[1] = mx;
+    out[2] = empty;
+}
+
+// ---- length bins ------------------------------------------------------------------
+// bin(0) = 0; for len >= 1, bin(len) = the smallest b >= 1 with 2^(b-1) >= len
+// (1->1, 2->2, 3..4->3, 5..8->4, 9..16->5, ...).  33 bins cover every int32 length.
+static int bin_of(int64_t len) {
+    if (len == 0) return 0;
+    int b = 1;
+    int64_t cap = 1;
+    while (cap < len) {
+        cap *= 2;
+        ++b;
+    }
+    return b;
+}
+
+// bin_count[33], bin_offset[34] = exclusive prefix sums of bin_count,
+// bin_rows[m] = row ids grouped by bin, ascending row id inside every bin.
+void oracle_row_bins(int64_t m, const int32_t* rowptr, int32_t* bin_count, int32_t* bin_offset, int32_t* bin_rows) {
+    for (int b = 0; b < 33; ++b) bin_count[b] = 0;
+    for (int64_t i = 0; i < m; ++i) bin_count[bin_of(static_cast<int64_t>(rowptr[i + 1]) - rowptr[i])] += 1;
+    bin_offset[0] = 0;
+    for (int b = 0; b < 33; ++b) bin_offset[b + 1] = bin_offset[b] + bin_count[b];
+    // one pass per bin, rows visited in ascending order: trivially stable
+    int64_t w = 0;
+    for (int b = 0; b < 33; ++b)
+        for (int64_t i = 0; i < m; ++i)
+            if (bin_of(static_cast<int64_t>(rowptr[i + 1]) - rowptr[i]) == b) bin_rows[w++] = static_cast<int32_t>(i);
+}
+
+// ---- row blocks -------------------------------------------------------------------
+// Greedy left-to-right partition of the rows into contiguous blocks.  A block takes the
+// next row while it has fewer than rows_max rows and the row still fits under block_nnz
+// stored entries; a row longer than block_nnz forms a block of its own.
+// Writes block boundaries (first row of each block, then m) to out; returns the number
+// of blocks nb (out holds nb+1 entries; m == 0 gives nb = 0 and out = [0]).
+// `out` must have room for m+1 entries.
+int64_t oracle_row_blocks(int64_t m, const int32_t* rowptr, int32_t block_nnz, int32_t rows_max, int32_t* out) {
+    int64_t nb = 0;
+    out[0] = 0;
+    int64_t r = 0;
+    while (r < m) {
+        const int64_t first = r;
+        int64_t held = 0;
+        while (r < m) {
+            const int64_t len = static_cast<int64_t>(rowptr[r + 1]) - rowptr[r];
+            if (r - first >= rows_max) break;
+            if (held + len > block_nnz) break;
+            held += len;
+            ++r;
+        }
+        if (r == first) ++r;  // a single row that is longer than block_nnz
+        ++nb;
+        out[nb] = static_cast<int32_t>(r);
+    }
+    return nb;
+}
+
+// ---- merge path -------------------------------------------------------------------
+// The merge path interleaves two sorted lists: the m row ends (row i ends at rowptr[i+1])
+// and the nnz entry positions 0..nnz-1.  Standing at (i rows finished, j entries taken),
+// the next step takes entry j if it belongs to row i (i < m, j < nnz, rowptr[i+1] > j),
+// otherwise it finishes row i.  The path has T = m + nnz steps.  Split p (p = 0..P,
+// P = ceil(T / ipc)) is the point reached after min(p*ipc, T) steps.
+// Writes mp_row[P+1], mp_nz[P+1]; returns P.
+int64_t oracle_merge_path(int64_t m, int64_t nnz, const int32_t* rowptr, int32_t ipc, int32_t* mp_row, int32_t* mp_nz) {
+    const int64_t T = m + nnz;
+    const int64_t P = (T + ipc - 1) / ipc;
+    int64_t i = 0, j = 0, p = 0;
+    for (int64_t step = 0;; ++step) {
+        if (step == p * ipc || step == T) {
+            mp_row[p] = static_cast<int32_t>(i);
+            mp_nz[p] = static_cast<int32_t>(j);
+            ++p;
+        }
+        if (step == T) break;
+        if (i < m && j < nnz && rowptr[i + 1] > j)
+            ++j;
+        else
+            ++i;
+    }
+    return P;
+}
+
+// ---- plan -------------------------------------------------------------------------
+// Plans: 1 scalar (one lane per row), 2 vector (a group of lanes per row), 3 binned
+// (scalar/vector per length bin), 4 adaptive (row blocks through LDS), 5 merge (merge-path
+// chunks + carry fix-up).  The automatic choice is a pure integer function:
+//   no rows or no entries                    -> 1
+//   some row is longer than one row block    -> 5
+//   otherwise                                -> 4
+int32_t oracle_plan(int64_t m, int64_t nnz, int64_t max_len, int32_t block_nnz) {
+    if (m == 0 || nnz == 0) return 1;
+    if (max_len > block_nnz) return 5;
+    return 4;
+}
+
+// Lanes per row of the vector plan: the smallest power of two G in [2, 64] with
+// 4*G >= ceil(nnz / m)  (every lane then takes about four entries); 64 when none is.
+int32_t oracle_vector_lanes(int64_t m, int64_t nnz) {
+    if (m == 0) return 2;
+    const int64_t mean_up = (nnz + m - 1) / m;
+    int32_t G = 2;
+    while (G < 64 && 4 * static_cast<int64_t>(G) < mean_up) G *= 2;
+    return G;
+}
+
+}  // extern "C"

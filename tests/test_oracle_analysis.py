@@ -1,0 +1,163 @@
+"""Pins for the CPU oracle of the analysis outputs (row statistics, length bins, row blocks,
+merge-path splits, plan).  Checked against hand-worked fixtures, closed-form counts of the
+structured workloads, defining invariants, and tiny brute-force restatements in Python."""
+import json
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as w
+
+
+def rowptr_of(lens):
+    return np.concatenate(([0], np.cumsum(np.asarray(lens, dtype=np.int64)))).astype(np.int32)
+
+
+RAGGED = [
+    [],
+    [0],
+    [0, 0, 0],
+    [5],
+    [1, 0, 2, 0, 0, 7, 3],
+    list(range(40)),
+    [100, 1, 1, 1, 100, 0, 0, 250, 3],
+    [2] * 1000,
+]
+
+
+@pytest.fixture(scope="module")
+def hand(golden_dir):
+    return json.loads((golden_dir / "analysis_handworked.json").read_text())
+
+
+# ------------------------------------------------------------------ bins
+def test_bins_handworked(hand):
+    lens, want = hand["bins"]["lens"], hand["bins"]["bin"]
+    cnt, off, rows = oracle.row_bins(rowptr_of(lens))
+    got = np.empty(len(lens), dtype=int)
+    for b in range(oracle.NUM_BINS):
+        got[rows[off[b]:off[b + 1]]] = b
+    assert got.tolist() == want
+
+
+@pytest.mark.parametrize("lens", RAGGED + [np.random.default_rng(1).integers(0, 5000, 3000)])
+def test_bins_invariants(lens):
+    lens = np.asarray(lens, dtype=np.int64)
+    rp = rowptr_of(lens)
+    cnt, off, rows = oracle.row_bins(rp)
+    m = lens.size
+    assert cnt.sum() == m and off[0] == 0 and off[-1] == m
+    assert np.array_equal(off[1:] - off[:-1], cnt)
+    assert np.array_equal(np.sort(rows), np.arange(m))
+    for b in range(oracle.NUM_BINS):
+        seg = rows[off[b]:off[b + 1]]
+        assert np.all(np.diff(seg) > 0)                   # ascending row id inside the bin
+        L = lens[seg]
+        if b == 0:
+            assert np.all(L == 0)
+        else:                                             # 2^(b-2) < len <= 2^(b-1)
+            assert np.all(L <= 2 ** (b - 1)) and np.all(2 * L > 2 ** (b - 1))
+
+
+def test_bins_closed_form_of_structured_workloads():
+    g = 24
+    cnt, _, _ = oracle.row_bins(w.laplace2d(g).rowptr)        # lengths 3 (4 corners), 4 (edges), 5 (interior)
+    assert cnt[3] == 4 + 4 * (g - 2) and cnt[4] == (g - 2) ** 2 and cnt.sum() == g * g
+    cnt, _, _ = oracle.row_bins(w.uniform_rows(512, 512, 16).rowptr)
+    assert cnt[5] == 512
+    g = 10
+    cnt, _, _ = oracle.row_bins(w.stencil27(g).rowptr)        # 8 corners (len 8), edges 12, faces 18, interior 27
+    assert cnt[4] == 8 and cnt[5] == 12 * (g - 2) and cnt[6] == 6 * (g - 2) ** 2 + (g - 2) ** 3
+    cnt, _, _ = oracle.row_bins(w.block_clustered(2048).rowptr)
+    assert cnt[8] == 2048                                      # 128 = 2^7 -> bin 8
+
+
+def test_row_stats():
+    assert oracle.row_stats(rowptr_of([])) == {"min_len": 0, "max_len": 0, "n_empty": 0}
+    assert oracle.row_stats(rowptr_of([4, 0, 9, 0, 2])) == {"min_len": 0, "max_len": 9, "n_empty": 2}
+    assert oracle.row_stats(rowptr_of([3, 3])) == {"min_len": 3, "max_len": 3, "n_empty": 0}
+
+
+# ------------------------------------------------------------------ row blocks
+def test_row_blocks_handworked(hand):
+    h = hand["row_blocks"]
+    assert oracle.row_blocks(rowptr_of(h["lens"]), h["block_nnz"], h["rows_max"]).tolist() == h["boundaries"]
+
+
+@pytest.mark.parametrize("lens", RAGGED + [np.random.default_rng(2).integers(0, 300, 5000)])
+@pytest.mark.parametrize("block_nnz,rows_max", [(2048, 256), (6, 3), (1, 1), (64, 1000)])
+def test_row_blocks_invariants(lens, block_nnz, rows_max):
+    lens = np.asarray(lens, dtype=np.int64)
+    m = lens.size
+    rp = rowptr_of(lens)
+    rb = oracle.row_blocks(rp, block_nnz, rows_max)
+    assert rb[0] == 0 and rb[-1] == m
+    if m == 0:
+        assert rb.tolist() == [0]
+        return
+    assert np.all(np.diff(rb) > 0)
+    for b in range(rb.size - 1):
+        s, e = int(rb[b]), int(rb[b + 1])
+        held = int(rp[e] - rp[s])
+        assert e - s <= rows_max
+        assert held <= block_nnz or e - s == 1
+        if e < m:                                         # maximal: the next row would break a limit
+            assert e - s == rows_max or held + lens[e] > block_nnz
+
+
+def test_row_blocks_closed_form_counts():
+    assert oracle.row_blocks(w.uniform_rows(4096, 4096, 16).rowptr, 2048, 256).size - 1 == 32
+    g = 64                                                # 5 entries a row at most: the row cap binds
+    assert oracle.row_blocks(w.laplace2d(g).rowptr, 2048, 256).size - 1 == g * g // 256
+    assert oracle.row_blocks(w.block_clustered(4096).rowptr, 2048, 256).size - 1 == 4096 // 16
+
+
+# ------------------------------------------------------------------ merge path
+def test_merge_path_handworked(hand):
+    h = hand["merge_path"]
+    rp = np.array(h["rowptr"], dtype=np.int32)
+    for ipc, want in h["splits"].items():
+        r, z = oracle.merge_path(rp, int(ipc))
+        assert r.tolist() == want["row"] and z.tolist() == want["nz"], ipc
+
+
+def merge_split_by_definition(rp, d):
+    """Smallest i in [max(0,d-nnz), min(d,m)] that is min(d,m) or has rowptr[i+1] > d-i-1."""
+    m, nnz = rp.size - 1, int(rp[-1])
+    hi = min(d, m)
+    for i in range(max(0, d - nnz), hi + 1):
+        if i == hi or rp[i + 1] > d - i - 1:
+            return i, d - i
+    raise AssertionError
+
+
+@pytest.mark.parametrize("lens", RAGGED + [np.random.default_rng(3).integers(0, 40, 300)])
+@pytest.mark.parametrize("ipc", [1, 2, 7, 64, 4096])
+def test_merge_path_invariants_and_diagonal_search(lens, ipc):
+    rp = rowptr_of(lens)
+    m, nnz = rp.size - 1, int(rp[-1])
+    T = m + nnz
+    r, z = oracle.merge_path(rp, ipc)
+    P = math.ceil(T / ipc)
+    assert r.size == P + 1 == z.size
+    assert r[0] == 0 and z[0] == 0 and r[-1] == m and z[-1] == nnz
+    assert np.all(np.diff(r) >= 0) and np.all(np.diff(z) >= 0)
+    for p in range(P + 1):
+        d = min(p * ipc, T)
+        assert r[p] + z[p] == d
+        if r[p] < m:
+            assert rp[r[p]] <= z[p] <= rp[r[p] + 1]
+        assert (int(r[p]), int(z[p])) == merge_split_by_definition(rp, d)
+
+
+# ------------------------------------------------------------------ plan
+def test_plan_rule():
+    assert oracle.plan(0, 0, 0, 2048) == 1
+    assert oracle.plan(10, 0, 0, 2048) == 1
+    assert oracle.plan(10, 100, 2048, 2048) == 4
+    assert oracle.plan(10, 5000, 2049, 2048) == 5
+    assert [oracle.vector_lanes(1, k) for k in (1, 8, 9, 16, 17, 27, 128, 129, 255, 257, 100000)] == \
+        [2, 2, 4, 4, 8, 8, 32, 64, 64, 64, 64]
+    assert oracle.vector_lanes(0, 0) == 2
