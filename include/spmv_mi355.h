@@ -1,0 +1,166 @@
+/* spmv_mi355.h -- C ABI of the gfx950 CSR sparse matrix-vector product library.
+ *
+ * Operation.  The benchmark's "SpMV CSR" task (paper App. C, task 12) multiplies a sparse
+ * matrix A, held as three arrays
+ *     values[nnz], col_indices[nnz], row_offsets[rows+1]  (row_offsets[i] = index of the first
+ *     stored entry of row i),
+ * with a dense vector x of length cols and writes y of length rows.  This library computes
+ * the BLAS form of it,
+ *     y <- alpha * A * x + beta * y,
+ * with A and x stored either as IEEE binary32 or as bf16 (upper half of a binary32), products
+ * and sums always taken in binary32, y always binary32.  The paper classes this operation
+ * as bound by memory bandwidth (App. A, bottleneck distribution), so every kernel behind
+ * this interface is organised around streaming values/col_indices once with wide loads.
+ *
+ * Conventions.
+ *   - Indices are 0-based int32.  m, n, nnz are passed as int64 and must be < 2^31.
+ *   - Every array argument of create/run is a DEVICE pointer, BORROWED: the caller owns the
+ *     memory and must keep rowptr/colidx/vals alive and unchanged until spmv_destroy().
+ *     The library owns only the metadata it allocates in spmv_csr_analyze().
+ *   - Column indices inside a row may be in any order and may repeat (repeats add up).
+ *   - Every function returns a status; nothing throws, aborts or prints.
+ *   - spmv_csr_run() only enqueues kernels on the given stream: no synchronisation, no
+ *     allocation, no host<->device copy.  At most one run per handle may be in flight
+ *     (the merge plan keeps its carry-out buffers in the handle).
+ *   - Read-back functions copy to caller-owned HOST buffers and synchronise the device.
+ */
+#ifndef SPMV_MI355_H
+#define SPMV_MI355_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct spmv_csr_s* spmv_handle_t;
+
+/* Storage type of vals AND x.  y, alpha, beta are always float. */
+typedef enum { SPMV_F32 = 0, SPMV_BF16 = 1 } spmv_dtype_t;
+
+typedef enum {
+    SPMV_OK = 0,
+    SPMV_ERR_INVALID_ARG = 1,   /* null pointer, negative size, unknown enum, parameter out of range */
+    SPMV_ERR_BAD_STRUCTURE = 2, /* rowptr[0] != 0, rowptr decreasing, rowptr[m] != nnz, column outside [0,n) */
+    SPMV_ERR_UNSUPPORTED = 3,   /* a size >= 2^31, or pointers not aligned to the element size */
+    SPMV_ERR_NOT_ANALYZED = 4,  /* run or read-back before a successful analyze */
+    SPMV_ERR_ALLOC = 5,         /* host or device allocation failed */
+    SPMV_ERR_HIP = 6            /* a HIP runtime call failed; see spmv_last_hip_error() */
+} spmv_status_t;
+
+/* Execution plans.  AUTO lets analyze choose (rule documented at spmv_csr_analyze). */
+typedef enum {
+    SPMV_PLAN_AUTO = 0,
+    SPMV_PLAN_SCALAR = 1,   /* one lane per row                                                  */
+    SPMV_PLAN_VECTOR = 2,   /* a power-of-two group of lanes (2..64) per row, cross-lane reduce */
+    SPMV_PLAN_BINNED = 3,   /* rows grouped by length bin; scalar or vector kernel per bin      */
+    SPMV_PLAN_ADAPTIVE = 4, /* contiguous row blocks streamed through LDS (CSR-Adaptive)        */
+    SPMV_PLAN_MERGE = 5     /* equal-work merge-path chunks + carry fix-up                      */
+} spmv_plan_t;
+
+#define SPMV_NUM_BINS 33
+
+/* Analysis parameters.  Zero in any field selects that field's default. */
+typedef struct {
+    int32_t plan;             /* spmv_plan_t; default AUTO */
+    int32_t block_nnz;        /* row blocks: most stored entries per block; default 2048, 1..8192 */
+    int32_t rows_max;         /* row blocks: most rows per block;           default 256,  1..1024 */
+    int32_t items_per_chunk;  /* merge path: steps (row ends + entries) per chunk; default 4096, 1..8192 */
+    int32_t vector_lanes;     /* VECTOR plan: lanes per row, power of two 2..64; default: chosen from nnz/m */
+    int32_t skip_validation;  /* nonzero: do not scan colidx for out-of-range columns in analyze */
+    int32_t reserved[2];      /* must be zero */
+} spmv_analyze_params_t;
+
+typedef struct {
+    int64_t m, n, nnz;
+    int64_t min_len, max_len, n_empty; /* row length statistics (all 0 when m == 0) */
+    int64_t num_row_blocks;            /* nb: row_blocks holds nb+1 entries */
+    int64_t num_chunks;                /* P:  mp_row / mp_nz hold P+1 entries */
+    int32_t plan;                      /* the plan run() will use (never AUTO) */
+    int32_t vector_lanes;              /* lanes per row the VECTOR plan uses */
+    int32_t block_nnz, rows_max, items_per_chunk; /* parameters in effect */
+    int32_t reserved;
+} spmv_analysis_info_t;
+
+/* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
+typedef struct {
+    int32_t* bin_count;  /* [SPMV_NUM_BINS]                                   */
+    int32_t* bin_offset; /* [SPMV_NUM_BINS + 1] exclusive prefix of bin_count */
+    int32_t* bin_rows;   /* [m]    row ids grouped by bin, ascending in each bin */
+    int32_t* row_blocks; /* [nb+1] first row of each block, then m            */
+    int32_t* mp_row;     /* [P+1]  rows finished at each merge-path split     */
+    int32_t* mp_nz;      /* [P+1]  entries taken at each merge-path split     */
+} spmv_analysis_host_t;
+
+/* Records the matrix (paper App. C task 12: values / col_indices / row_offsets).
+ *   out      receives the handle; set to NULL on any error.
+ *   m, n     rows, columns (>= 0);  nnz  stored entries (>= 0).
+ *   rowptr   device int32[m+1];  colidx  device int32[nnz];
+ *   vals     device float[nnz] (SPMV_F32) or uint16 bf16 bit patterns [nnz] (SPMV_BF16).
+ *            colidx and vals may be NULL only when nnz == 0.
+ * Touches no device memory.  Errors: INVALID_ARG, UNSUPPORTED, ALLOC. */
+spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
+                              const int32_t* colidx, const void* vals, spmv_dtype_t dtype);
+
+/* One-time inspection of the row structure.  Copies rowptr to the host, checks it
+ * (rowptr[0] == 0, non-decreasing, rowptr[m] == nnz), optionally checks 0 <= colidx < n on the
+ * device, then derives and uploads:
+ *   - row statistics; bin(len) = 0 for len 0, else the smallest b >= 1 with 2^(b-1) >= len;
+ *     bin_rows = stable grouping of row ids by bin;
+ *   - row blocks: greedy left-to-right, a block takes the next row while it has < rows_max
+ *     rows and the row keeps it at <= block_nnz entries; a longer row stands alone;
+ *   - merge-path splits: the path over (row ends, entry positions) cut every items_per_chunk
+ *     steps;
+ *   - the plan: params->plan if not AUTO, else SCALAR when m == 0 or nnz == 0, MERGE when
+ *     some row is longer than block_nnz, else ADAPTIVE.
+ * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
+ * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */
+spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params);
+
+/* Enqueues y <- alpha*A*x + beta*y on `stream` (a hipStream_t passed as void*; NULL = the
+ * default stream).
+ *   x  device, n elements of the handle's dtype;   y  device float[m], read only if beta != 0.
+ *   x and y must not overlap.  beta == 0 never reads y (NaN/Inf there do not propagate).
+ * m == 0 is a no-op; nnz == 0 gives y <- beta*y.
+ * Errors: INVALID_ARG (null x or y with m, n > 0), NOT_ANALYZED, HIP (launch failure). */
+spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha, float beta, void* stream);
+
+/* Frees the handle and the library-owned device metadata.  spmv_destroy(NULL) is OK. */
+spmv_status_t spmv_destroy(spmv_handle_t h);
+
+/* Sizes and scalars of the analysis, so the caller can size read-back buffers. */
+spmv_status_t spmv_csr_get_analysis_info(spmv_handle_t h, spmv_analysis_info_t* out);
+
+/* Copies the integer analysis outputs from the device to the host buffers in `out`. */
+spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t* out);
+
+/* The analysis of spmv_csr_analyze() on a HOST copy of rowptr, with HOST outputs and no device
+ * involved (same definitions, same code path; the column check is skipped).  `info` is
+ * required; `out` may be NULL or have NULL members.  bin_rows needs m entries, row_blocks
+ * up to m+1, mp_row/mp_nz ceil((m+nnz)/items_per_chunk)+1.
+ * Errors: INVALID_ARG, UNSUPPORTED, BAD_STRUCTURE, ALLOC. */
+spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr_host,
+                                const spmv_analyze_params_t* params, spmv_analysis_info_t* info,
+                                const spmv_analysis_host_t* out);
+
+/* Self-check of the cross-lane reductions the kernels use (DPP quad/mirror steps, ds_swizzle,
+ * v_permlane32_swap).  in_dev: device float[64], one value per lane of a wavefront.
+ * out_dev: device float[14*64]: out[gi*64 + l] = sum over the aligned group of 2^gi lanes that
+ * contains lane l, gi = 0..6 (compile-time group size), then the same seven rows again from
+ * the run-time-group-size variant.  Enqueues one wavefront on `stream`. */
+spmv_status_t spmv_selftest_reduce(const float* in_dev, float* out_dev, void* stream);
+
+/* Name of the kernel that carries the nnz stream for the handle's current plan ("" before
+ * analyze); lets a profiler summary be matched to the plan. */
+const char* spmv_csr_main_kernel_name(spmv_handle_t h);
+
+const char* spmv_status_string(spmv_status_t s);
+
+/* hipError_t (as int) of the most recent failing HIP call made by this library on the calling
+ * thread; 0 if none. */
+int spmv_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPMV_MI355_H */

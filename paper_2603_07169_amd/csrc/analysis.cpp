@@ -1,0 +1,151 @@
+// Host-side analysis of the CSR row structure (row_offsets as laid out in App. C task 12).
+#include "analysis.h"
+
+#include <algorithm>
+#include <new>
+
+namespace spmv {
+
+namespace {
+
+inline bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+
+// bin index of a row length: 0 for an empty row, otherwise 1 + ceil(log2(len)).
+inline int length_bin(uint32_t len) {
+    if (len <= 1) return static_cast<int>(len);
+    return 33 - __builtin_clz(len - 1);
+}
+
+// Merge-path split on diagonal d: the number of finished rows i at the point where the path
+// has made d steps.  rowptr[i+1] + i is strictly increasing, so the first i with
+// rowptr[i+1] + i > d - 1 can be found by bisection inside the feasible window.
+inline int64_t split_rows_on_diagonal(int64_t d, int64_t m, int64_t nnz, const int32_t* rowptr) {
+    int64_t lo = std::max<int64_t>(0, d - nnz);
+    int64_t hi = std::min<int64_t>(d, m);
+    while (lo < hi) {
+        const int64_t mid = lo + (hi - lo) / 2;
+        if (static_cast<int64_t>(rowptr[mid + 1]) + mid > d - 1)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    return lo;
+}
+
+}  // namespace
+
+spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_params_t* out) {
+    spmv_analyze_params_t p{};
+    if (in) p = *in;
+    if (p.reserved[0] != 0 || p.reserved[1] != 0) return SPMV_ERR_INVALID_ARG;
+    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_MERGE) return SPMV_ERR_INVALID_ARG;
+    if (p.block_nnz == 0) p.block_nnz = kDefaultBlockNnz;
+    if (p.rows_max == 0) p.rows_max = kDefaultRowsMax;
+    if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
+    if (p.block_nnz < 1 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
+    if (p.rows_max < 1 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;
+    if (p.items_per_chunk < 1 || p.items_per_chunk > kMaxItemsPerChunk) return SPMV_ERR_INVALID_ARG;
+    if (p.vector_lanes != 0 && (!is_pow2(p.vector_lanes) || p.vector_lanes < 2 || p.vector_lanes > 64))
+        return SPMV_ERR_INVALID_ARG;
+    *out = p;
+    return SPMV_OK;
+}
+
+spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
+                             const spmv_analyze_params_t& params, Analysis* out) try {
+    Analysis& a = *out;
+    a = Analysis{};
+
+    // ---- structure check + statistics + bin histogram, one sweep
+    if (rowptr[0] != 0 || rowptr[m] != nnz) return SPMV_ERR_BAD_STRUCTURE;
+    int64_t min_len = m > 0 ? INT64_MAX : 0, max_len = 0, n_empty = 0;
+    for (int64_t i = 0; i < m; ++i) {
+        const int64_t len = static_cast<int64_t>(rowptr[i + 1]) - rowptr[i];
+        if (len < 0) return SPMV_ERR_BAD_STRUCTURE;
+        min_len = std::min(min_len, len);
+        max_len = std::max(max_len, len);
+        n_empty += (len == 0);
+        a.bin_count[length_bin(static_cast<uint32_t>(len))] += 1;
+    }
+
+    // ---- stable counting sort of the row ids by bin
+    for (int b = 0; b < SPMV_NUM_BINS; ++b) a.bin_offset[b + 1] = a.bin_offset[b] + a.bin_count[b];
+    a.bin_rows.resize(static_cast<size_t>(m));
+    {
+        int32_t cursor[SPMV_NUM_BINS];
+        std::copy(a.bin_offset, a.bin_offset + SPMV_NUM_BINS, cursor);
+        for (int64_t i = 0; i < m; ++i) {
+            const uint32_t len = static_cast<uint32_t>(rowptr[i + 1] - rowptr[i]);
+            a.bin_rows[static_cast<size_t>(cursor[length_bin(len)]++)] = static_cast<int32_t>(i);
+        }
+    }
+
+    // ---- greedy row blocks: close the open block when the next row would overflow it
+    a.row_blocks.clear();
+    a.row_blocks.push_back(0);
+    {
+        int64_t open_first = 0;  // first row of the open block
+        for (int64_t i = 0; i < m; ++i) {
+            const int64_t with_row = static_cast<int64_t>(rowptr[i + 1]) - rowptr[open_first];
+            const bool fits = (i - open_first) < params.rows_max && with_row <= params.block_nnz;
+            if (!fits && i > open_first) {
+                a.row_blocks.push_back(static_cast<int32_t>(i));
+                open_first = i;
+            }
+            // A row that alone exceeds block_nnz opens a block at i and is cut off by the next row:
+            // with_row for row i+1 is then > block_nnz as well, so the block closes at i+1.
+        }
+        if (m > 0) a.row_blocks.push_back(static_cast<int32_t>(m));
+    }
+
+    // ---- merge-path splits by bisection on each chunk's diagonal
+    const int64_t T = m + nnz;
+    const int64_t ipc = params.items_per_chunk;
+    const int64_t P = (T + ipc - 1) / ipc;
+    a.mp_row.resize(static_cast<size_t>(P + 1));
+    a.mp_nz.resize(static_cast<size_t>(P + 1));
+    for (int64_t p = 0; p <= P; ++p) {
+        const int64_t d = std::min(p * ipc, T);
+        const int64_t i = split_rows_on_diagonal(d, m, nnz, rowptr);
+        a.mp_row[static_cast<size_t>(p)] = static_cast<int32_t>(i);
+        a.mp_nz[static_cast<size_t>(p)] = static_cast<int32_t>(d - i);
+    }
+
+    // ---- plan
+    int32_t plan = params.plan;
+    if (plan == SPMV_PLAN_AUTO) {
+        if (m == 0 || nnz == 0)
+            plan = SPMV_PLAN_SCALAR;
+        else if (max_len > params.block_nnz)
+            plan = SPMV_PLAN_MERGE;
+        else
+            plan = SPMV_PLAN_ADAPTIVE;
+    }
+    int32_t lanes = params.vector_lanes;
+    if (lanes == 0) {
+        lanes = 2;
+        if (m > 0) {
+            const int64_t mean_up = (nnz + m - 1) / m;
+            while (lanes < 64 && 4 * static_cast<int64_t>(lanes) < mean_up) lanes <<= 1;
+        }
+    }
+
+    a.info.m = m;
+    a.info.n = n;
+    a.info.nnz = nnz;
+    a.info.min_len = min_len;
+    a.info.max_len = max_len;
+    a.info.n_empty = n_empty;
+    a.info.num_row_blocks = static_cast<int64_t>(a.row_blocks.size()) - 1;
+    a.info.num_chunks = P;
+    a.info.plan = plan;
+    a.info.vector_lanes = lanes;
+    a.info.block_nnz = params.block_nnz;
+    a.info.rows_max = params.rows_max;
+    a.info.items_per_chunk = params.items_per_chunk;
+    return SPMV_OK;
+} catch (const std::bad_alloc&) {
+    return SPMV_ERR_ALLOC;
+}
+
+}  // namespace spmv

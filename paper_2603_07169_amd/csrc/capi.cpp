@@ -1,0 +1,318 @@
+// C ABI of the library: handle life cycle, analysis upload, plan dispatch.
+// See include/spmv_mi355.h for the contract of every entry point.
+#include <hip/hip_runtime_api.h>
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "analysis.h"
+#include "kernels.h"
+#include "spmv_mi355.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool hip_failed(hipError_t e) {
+    if (e == hipSuccess) return false;
+    g_last_hip_error = static_cast<int>(e);
+    (void)hipGetLastError();  // clear the sticky per-thread error so later calls start clean
+    return true;
+}
+
+constexpr int64_t kMaxCount = (int64_t{1} << 31) - 1024;  // keeps k + vector width inside int32
+
+}  // namespace
+
+struct spmv_csr_s {
+    int64_t m = 0, n = 0, nnz = 0;
+    const int32_t* rowptr = nullptr;
+    const int32_t* colidx = nullptr;
+    const void* vals = nullptr;
+    spmv_dtype_t dtype = SPMV_F32;
+    bool vec_ok = false;
+
+    bool analyzed = false;
+    spmv_analysis_info_t info{};
+    int32_t bin_count[SPMV_NUM_BINS]{};
+    int32_t bin_offset[SPMV_NUM_BINS + 1]{};
+    // device metadata, owned
+    int32_t* d_bin_rows = nullptr;
+    int32_t* d_row_blocks = nullptr;
+    int32_t* d_mp_row = nullptr;
+    int32_t* d_mp_nz = nullptr;
+    int32_t* d_carry_row = nullptr;
+    float* d_carry_val = nullptr;
+};
+
+namespace {
+
+void free_metadata(spmv_csr_s* h) {
+    void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_mp_row, h->d_mp_nz, h->d_carry_row, h->d_carry_val};
+    for (void* p : ptrs)
+        if (p) (void)hipFree(p);
+    h->d_bin_rows = h->d_row_blocks = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
+    h->d_carry_val = nullptr;
+    h->analyzed = false;
+}
+
+template <typename T>
+spmv_status_t upload(const std::vector<T>& src, T** dst) {
+    const size_t bytes = sizeof(T) * (src.empty() ? 1 : src.size());
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(dst), bytes))) return SPMV_ERR_ALLOC;
+    if (!src.empty() && hip_failed(hipMemcpy(*dst, src.data(), sizeof(T) * src.size(), hipMemcpyHostToDevice)))
+        return SPMV_ERR_HIP;
+    return SPMV_OK;
+}
+
+spmv::MatrixView view_of(const spmv_csr_s* h) {
+    spmv::MatrixView A{};
+    A.m = static_cast<int32_t>(h->m);
+    A.n = static_cast<int32_t>(h->n);
+    A.nnz = static_cast<int32_t>(h->nnz);
+    A.rowptr = h->rowptr;
+    A.colidx = h->colidx;
+    A.vals = h->vals;
+    A.bf16 = h->dtype == SPMV_BF16;
+    A.vec_ok = h->vec_ok;
+    return A;
+}
+
+// Lanes per row the binned plan gives to length bin b (b >= 4: rows of 2^(b-2)+1 .. 2^(b-1) entries).
+inline int lanes_for_bin(int b) {
+    const int g = 1 << (b - 3);
+    return g > 64 ? 64 : g;
+}
+
+}  // namespace
+
+extern "C" {
+
+spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
+                              const int32_t* colidx, const void* vals, spmv_dtype_t dtype) {
+    if (!out) return SPMV_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (m < 0 || n < 0 || nnz < 0) return SPMV_ERR_INVALID_ARG;
+    if (dtype != SPMV_F32 && dtype != SPMV_BF16) return SPMV_ERR_INVALID_ARG;
+    if (!rowptr) return SPMV_ERR_INVALID_ARG;
+    if (nnz > 0 && (!colidx || !vals)) return SPMV_ERR_INVALID_ARG;
+    if (nnz > 0 && n == 0) return SPMV_ERR_INVALID_ARG;
+    if (m > kMaxCount || n > kMaxCount || nnz > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    const uintptr_t esz = dtype == SPMV_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(rowptr) % 4 || reinterpret_cast<uintptr_t>(colidx) % 4 ||
+        reinterpret_cast<uintptr_t>(vals) % esz)
+        return SPMV_ERR_UNSUPPORTED;
+    spmv_csr_s* h = new (std::nothrow) spmv_csr_s;
+    if (!h) return SPMV_ERR_ALLOC;
+    h->m = m;
+    h->n = n;
+    h->nnz = nnz;
+    h->rowptr = rowptr;
+    h->colidx = colidx;
+    h->vals = vals;
+    h->dtype = dtype;
+    h->vec_ok = reinterpret_cast<uintptr_t>(colidx) % 16 == 0 && reinterpret_cast<uintptr_t>(vals) % 16 == 0;
+    *out = h;
+    return SPMV_OK;
+}
+
+spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params) {
+    if (!h) return SPMV_ERR_INVALID_ARG;
+    spmv_analyze_params_t p{};
+    spmv_status_t st = spmv::resolve_params(params, &p);
+    if (st != SPMV_OK) return st;
+    free_metadata(h);
+
+    std::vector<int32_t> rowptr_host;
+    try {
+        rowptr_host.resize(static_cast<size_t>(h->m) + 1);
+    } catch (const std::bad_alloc&) {
+        return SPMV_ERR_ALLOC;
+    }
+    if (hip_failed(hipMemcpy(rowptr_host.data(), h->rowptr, sizeof(int32_t) * rowptr_host.size(), hipMemcpyDeviceToHost)))
+        return SPMV_ERR_HIP;
+
+    spmv::Analysis a;
+    st = spmv::analyze_rowptr(h->m, h->n, h->nnz, rowptr_host.data(), p, &a);
+    if (st != SPMV_OK) return st;
+
+    if (!p.skip_validation && h->nnz > 0) {
+        int32_t* d_flag = nullptr;
+        int32_t flag = 0;
+        if (hip_failed(hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t)))) return SPMV_ERR_ALLOC;
+        bool bad = hip_failed(hipMemcpy(d_flag, &flag, sizeof flag, hipMemcpyHostToDevice));
+        bad = bad || hip_failed(spmv::launch_validate_columns(view_of(h), d_flag, nullptr));
+        bad = bad || hip_failed(hipMemcpy(&flag, d_flag, sizeof flag, hipMemcpyDeviceToHost));
+        (void)hipFree(d_flag);
+        if (bad) return SPMV_ERR_HIP;
+        if (flag != 0) return SPMV_ERR_BAD_STRUCTURE;
+    }
+
+    st = upload(a.bin_rows, &h->d_bin_rows);
+    if (st == SPMV_OK) st = upload(a.row_blocks, &h->d_row_blocks);
+    if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
+    if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
+    if (st == SPMV_OK) {
+        const size_t P = static_cast<size_t>(a.info.num_chunks > 0 ? a.info.num_chunks : 1);
+        if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_carry_row), sizeof(int32_t) * P)) ||
+            hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_carry_val), sizeof(float) * P)))
+            st = SPMV_ERR_ALLOC;
+    }
+    if (st == SPMV_OK && hip_failed(hipDeviceSynchronize())) st = SPMV_ERR_HIP;
+    if (st != SPMV_OK) {
+        free_metadata(h);
+        return st;
+    }
+    h->info = a.info;
+    std::memcpy(h->bin_count, a.bin_count, sizeof h->bin_count);
+    std::memcpy(h->bin_offset, a.bin_offset, sizeof h->bin_offset);
+    h->analyzed = true;
+    return SPMV_OK;
+}
+
+spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha, float beta, void* stream) {
+    if (!h) return SPMV_ERR_INVALID_ARG;
+    if (!h->analyzed) return SPMV_ERR_NOT_ANALYZED;
+    if (h->m == 0) return SPMV_OK;
+    if (!y) return SPMV_ERR_INVALID_ARG;
+    if (h->nnz > 0 && !x) return SPMV_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(y) % 4 || reinterpret_cast<uintptr_t>(x) % (h->dtype == SPMV_F32 ? 4 : 2))
+        return SPMV_ERR_UNSUPPORTED;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const spmv::MatrixView A = view_of(h);
+    const spmv::Scalars s{alpha, beta};
+    const int32_t m = A.m;
+    hipError_t e = hipSuccess;
+    switch (h->info.plan) {
+        case SPMV_PLAN_SCALAR:
+            e = spmv::launch_scalar(A, nullptr, m, x, y, s, st);
+            break;
+        case SPMV_PLAN_VECTOR:
+            e = spmv::launch_vector(A, h->info.vector_lanes, nullptr, m, x, y, s, st);
+            break;
+        case SPMV_PLAN_BINNED: {
+            // bins 0..3 (at most 4 entries a row): one lane per row; every higher bin: a team per row
+            const int32_t short_rows = h->bin_offset[4];
+            e = spmv::launch_scalar(A, h->d_bin_rows, short_rows, x, y, s, st);
+            for (int b = 4; b < SPMV_NUM_BINS && e == hipSuccess; ++b) {
+                // bins whose team is the full wavefront are launched together
+                int last = b;
+                if (lanes_for_bin(b) == 64) last = SPMV_NUM_BINS - 1;
+                const int32_t first_row = h->bin_offset[b];
+                const int32_t count = h->bin_offset[last + 1] - first_row;
+                if (count > 0)
+                    e = spmv::launch_vector(A, lanes_for_bin(b), h->d_bin_rows + first_row, count, x, y, s, st);
+                b = last;
+            }
+            break;
+        }
+        case SPMV_PLAN_ADAPTIVE:
+            e = spmv::launch_adaptive(A, h->d_row_blocks, static_cast<int32_t>(h->info.num_row_blocks),
+                                      h->info.block_nnz, h->info.rows_max, x, y, s, st);
+            break;
+        case SPMV_PLAN_MERGE:
+            e = spmv::launch_merge(A, h->d_mp_row, h->d_mp_nz, static_cast<int32_t>(h->info.num_chunks),
+                                   h->info.items_per_chunk, h->d_carry_row, h->d_carry_val, x, y, s, st);
+            break;
+        default:
+            return SPMV_ERR_INVALID_ARG;
+    }
+    return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
+}
+
+spmv_status_t spmv_destroy(spmv_handle_t h) {
+    if (!h) return SPMV_OK;
+    free_metadata(h);
+    delete h;
+    return SPMV_OK;
+}
+
+spmv_status_t spmv_csr_get_analysis_info(spmv_handle_t h, spmv_analysis_info_t* out) {
+    if (!h || !out) return SPMV_ERR_INVALID_ARG;
+    if (!h->analyzed) return SPMV_ERR_NOT_ANALYZED;
+    *out = h->info;
+    return SPMV_OK;
+}
+
+spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t* out) {
+    if (!h || !out) return SPMV_ERR_INVALID_ARG;
+    if (!h->analyzed) return SPMV_ERR_NOT_ANALYZED;
+    if (out->bin_count) std::memcpy(out->bin_count, h->bin_count, sizeof h->bin_count);
+    if (out->bin_offset) std::memcpy(out->bin_offset, h->bin_offset, sizeof h->bin_offset);
+    struct Copy {
+        int32_t* dst;
+        const int32_t* src;
+        int64_t count;
+    } copies[] = {
+        {out->bin_rows, h->d_bin_rows, h->info.m},
+        {out->row_blocks, h->d_row_blocks, h->info.num_row_blocks + 1},
+        {out->mp_row, h->d_mp_row, h->info.num_chunks + 1},
+        {out->mp_nz, h->d_mp_nz, h->info.num_chunks + 1},
+    };
+    for (const Copy& c : copies)
+        if (c.dst && c.count > 0 &&
+            hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+    return SPMV_OK;
+}
+
+spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr_host,
+                                const spmv_analyze_params_t* params, spmv_analysis_info_t* info,
+                                const spmv_analysis_host_t* out) {
+    if (!rowptr_host || !info || m < 0 || n < 0 || nnz < 0) return SPMV_ERR_INVALID_ARG;
+    if (m > kMaxCount || n > kMaxCount || nnz > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    spmv_analyze_params_t p{};
+    spmv_status_t st = spmv::resolve_params(params, &p);
+    if (st != SPMV_OK) return st;
+    spmv::Analysis a;
+    st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
+    if (st != SPMV_OK) return st;
+    *info = a.info;
+    if (out) {
+        if (out->bin_count) std::memcpy(out->bin_count, a.bin_count, sizeof a.bin_count);
+        if (out->bin_offset) std::memcpy(out->bin_offset, a.bin_offset, sizeof a.bin_offset);
+        if (out->bin_rows && !a.bin_rows.empty())
+            std::memcpy(out->bin_rows, a.bin_rows.data(), sizeof(int32_t) * a.bin_rows.size());
+        if (out->row_blocks) std::memcpy(out->row_blocks, a.row_blocks.data(), sizeof(int32_t) * a.row_blocks.size());
+        if (out->mp_row) std::memcpy(out->mp_row, a.mp_row.data(), sizeof(int32_t) * a.mp_row.size());
+        if (out->mp_nz) std::memcpy(out->mp_nz, a.mp_nz.data(), sizeof(int32_t) * a.mp_nz.size());
+    }
+    return SPMV_OK;
+}
+
+spmv_status_t spmv_selftest_reduce(const float* in_dev, float* out_dev, void* stream) {
+    if (!in_dev || !out_dev) return SPMV_ERR_INVALID_ARG;
+    return hip_failed(spmv::launch_reduce_selftest(in_dev, out_dev, static_cast<hipStream_t>(stream))) ? SPMV_ERR_HIP
+                                                                                                       : SPMV_OK;
+}
+
+const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
+    if (!h || !h->analyzed) return "";
+    switch (h->info.plan) {
+        case SPMV_PLAN_SCALAR: return spmv::scalar_kernel_name();
+        case SPMV_PLAN_VECTOR:
+        case SPMV_PLAN_BINNED: return spmv::vector_kernel_name();
+        case SPMV_PLAN_ADAPTIVE: return spmv::adaptive_kernel_name();
+        case SPMV_PLAN_MERGE: return spmv::merge_kernel_name();
+        default: return "";
+    }
+}
+
+const char* spmv_status_string(spmv_status_t s) {
+    switch (s) {
+        case SPMV_OK: return "ok";
+        case SPMV_ERR_INVALID_ARG: return "invalid argument";
+        case SPMV_ERR_BAD_STRUCTURE: return "malformed CSR structure";
+        case SPMV_ERR_UNSUPPORTED: return "unsupported size or alignment";
+        case SPMV_ERR_NOT_ANALYZED: return "handle not analyzed";
+        case SPMV_ERR_ALLOC: return "allocation failed";
+        case SPMV_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+int spmv_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Launch interface between the C ABI (host) and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstdint>
+
+namespace spmv {
+
+struct MatrixView {
+    int32_t m, n, nnz;
+    const int32_t* rowptr;  // device [m+1]
+    const int32_t* colidx;  // device [nnz]
+    const void* vals;       // device [nnz] float or bf16 bits
+    bool bf16;
+    bool vec_ok;            // colidx and vals are 16-byte aligned: 128-bit loads allowed
+};
+
+struct Scalars {
+    float alpha, beta;
+};
+
+// rows == nullptr: rows 0..count-1; otherwise the `count` row ids listed in rows[].
+hipError_t launch_scalar(const MatrixView& A, const int32_t* rows, int32_t count, const void* x, float* y, Scalars s,
+                         hipStream_t st);
+// lanes: power of two in [2, 64].
+hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, int32_t count, const void* x, float* y,
+                         Scalars s, hipStream_t st);
+// row_blocks: device [nb+1].  block_nnz, rows_max: the limits the partition was built with.
+hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, int32_t nb, int32_t block_nnz,
+                           int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st);
+// mp_row, mp_nz: device [P+1]; carry_row/carry_val: device [P] scratch owned by the handle.
+hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
+                        int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
+                        Scalars s, hipStream_t st);
+// flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).
+hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st);
+
+// Cross-lane reduction self-check on one wavefront.  in: device float[64], lane l contributes in[l].
+// out: device float[14*64]; out[gi*64 + l] = sum over lane l's aligned group of G = 2^gi lanes,
+// gi = 0..6 from the compile-time variant, then the same seven again from the run-time variant.
+hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st);
+
+const char* scalar_kernel_name();
+const char* vector_kernel_name();
+const char* adaptive_kernel_name();
+const char* merge_kernel_name();
+
+}  // namespace spmv

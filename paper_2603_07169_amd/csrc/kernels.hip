@@ -1,0 +1,530 @@
+// gfx950 kernels for y <- alpha*A*x + beta*y with A in CSR (values / col_indices / row_offsets,
+// paper App. C task 12), FP32 or bf16 storage, FP32 products and sums.
+//
+// The operation moves 8 (FP32) or 6 (bf16) bytes per stored entry for 2 flops, so every kernel
+// is built around reading vals/colidx exactly once, as wide and as coalesced as the row layout
+// allows, while x is gathered through the caches.  Four kernels:
+//   spmv_scalar_kernel  one lane per row                     (short rows; the naive baseline)
+//   spmv_vector_kernel  G = 2..64 lanes per row, DPP/ds_swizzle/permlane reduction
+//   spmv_tile_kernel    a workgroup streams a contiguous entry range with 128-bit loads,
+//                       parks the products in LDS and reduces them per row; the range comes
+//                       either from a row block (rows whole) or from a merge-path chunk
+//                       (rows may be cut at both ends; the cut-off tail leaves as a carry)
+//   merge_fixup_kernel  adds the carries of cut rows to y, in chunk order, without atomics
+// No matrix cores: nothing here is a dense contraction.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace spmv {
+namespace {
+
+constexpr int kWG = 256;   // threads per workgroup = 4 wavefronts of 64
+constexpr int kXcds = 8;   // accelerator dies; workgroup ids are dealt round-robin over them
+constexpr int kMaxDeferred = 136;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct F32 {
+    using elem = float;
+    static constexpr int VEC = 4;  // elements per 128-bit load of vals
+};
+struct BF16 {
+    using elem = uint16_t;
+    static constexpr int VEC = 8;
+};
+
+__device__ __forceinline__ float widen(float v) { return v; }
+__device__ __forceinline__ float widen(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
+
+// ------------------------------------------------------------------------------------------
+// Cross-lane sums over aligned groups of G lanes; every lane of the group receives the total.
+// Steps 1 and 2 permute inside a quad, 4 and 8 mirror a half row / a row of 16 (valid because
+// the lanes being mirrored already agree), 16 swaps inside 32 lanes through the LDS crossbar
+// (ds_swizzle, no memory touched), 32 swaps the two wave halves (v_permlane32_swap).
+// All 64 lanes must be active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float add_xor1(float v) { return v + dpp_move<0xB1>(v); }    // quad_perm [1,0,3,2]
+__device__ __forceinline__ float add_xor2(float v) { return v + dpp_move<0x4E>(v); }    // quad_perm [2,3,0,1]
+__device__ __forceinline__ float add_half_mirror(float v) { return v + dpp_move<0x141>(v); }
+__device__ __forceinline__ float add_row_mirror(float v) { return v + dpp_move<0x140>(v); }
+__device__ __forceinline__ float add_swap16(float v) {
+    return v + __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));  // and 0x1f, xor 0x10
+}
+__device__ __forceinline__ float add_swap32(float v) {
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int G>
+__device__ __forceinline__ float group_sum(float v) {
+    if constexpr (G >= 2) v = add_xor1(v);
+    if constexpr (G >= 4) v = add_xor2(v);
+    if constexpr (G >= 8) v = add_half_mirror(v);
+    if constexpr (G >= 16) v = add_row_mirror(v);
+    if constexpr (G >= 32) v = add_swap16(v);
+    if constexpr (G >= 64) v = add_swap32(v);
+    return v;
+}
+
+// Same with G known only at run time (uniform over the workgroup).
+__device__ __forceinline__ float group_sum_rt(float v, int G) {
+    if (G >= 2) v = add_xor1(v);
+    if (G >= 4) v = add_xor2(v);
+    if (G >= 8) v = add_half_mirror(v);
+    if (G >= 16) v = add_row_mirror(v);
+    if (G >= 32) v = add_swap16(v);
+    if (G >= 64) v = add_swap32(v);
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Workgroup ids are handed to the 8 dies round-robin (id % 8).  Each die has its own L2, so
+// give die j one contiguous run of logical tiles: its x window then lives in one L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nb) {
+    const int q = nb / kXcds, r = nb % kXcds;
+    const int die = bid % kXcds, slot = bid / kXcds;
+    return die * q + (die < r ? die : r) + slot;
+}
+
+// ------------------------------------------------------------------------------------------
+// 128-bit streaming loads.  vals/colidx are read once: mark them non-temporal so they do not
+// push x out of the caches.
+__device__ __forceinline__ i32x4 load_idx4(const int32_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(p));
+}
+__device__ __forceinline__ f32x4 load_val4(const float* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+}
+__device__ __forceinline__ u32x4 load_val8(const uint16_t* p) {
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+
+// Products of VEC consecutive entries starting at k (k multiple of VEC, k + VEC <= nnz, arrays
+// 16-byte aligned).
+__device__ __forceinline__ void products_vec(const int32_t* colidx, const float* vals, const float* x, int k,
+                                             float (&p)[4]) {
+    const f32x4 v = load_val4(vals + k);
+    const i32x4 c = load_idx4(colidx + k);
+    p[0] = v[0] * x[c[0]];
+    p[1] = v[1] * x[c[1]];
+    p[2] = v[2] * x[c[2]];
+    p[3] = v[3] * x[c[3]];
+}
+__device__ __forceinline__ void products_vec(const int32_t* colidx, const uint16_t* vals, const uint16_t* x, int k,
+                                             float (&p)[8]) {
+    const u32x4 v = load_val8(vals + k);
+    const i32x4 c0 = load_idx4(colidx + k);
+    const i32x4 c1 = load_idx4(colidx + k + 4);
+    const int c[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        // little-endian: the low half of dword i is entry 2i, the high half entry 2i+1
+        p[2 * i] = __uint_as_float(v[i] << 16) * widen(x[c[2 * i]]);
+        p[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u) * widen(x[c[2 * i + 1]]);
+    }
+}
+
+template <typename E>
+__device__ __forceinline__ float product_one(const int32_t* colidx, const E* vals, const E* x, int k) {
+    return widen(vals[k]) * widen(x[colidx[k]]);
+}
+
+// Partial dot product of entries [k0, k1) taken by lane `lane` of a team of G lanes.
+// Long enough ranges are split into an unaligned head (< VEC entries), an aligned body read
+// with 128-bit loads, and a tail (< VEC entries).
+template <typename T, int G>
+__device__ __forceinline__ float team_dot(const int32_t* colidx, const typename T::elem* vals,
+                                          const typename T::elem* x, int k0, int k1, int lane, bool vec_ok) {
+    constexpr int VEC = T::VEC;
+    float acc = 0.f;
+    if constexpr (G >= 16) {
+        if (vec_ok && k1 - k0 >= 2 * VEC) {
+            const int ka = (k0 + VEC - 1) & ~(VEC - 1);
+            if (k0 + lane < ka) acc += product_one(colidx, vals, x, k0 + lane);
+            const int nvec = (k1 - ka) / VEC;
+            for (int v = lane; v < nvec; v += G) {
+                float p[VEC];
+                products_vec(colidx, vals, x, ka + v * VEC, p);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) acc += p[i];
+            }
+            const int kt = ka + nvec * VEC;
+            if (kt + lane < k1) acc += product_one(colidx, vals, x, kt + lane);
+            return acc;
+        }
+    }
+    for (int k = k0 + lane; k < k1; k += G) acc += product_one(colidx, vals, x, k);
+    return acc;
+}
+
+__device__ __forceinline__ float epilogue(float acc, float alpha, float beta, const float* y, int r) {
+    return beta == 0.f ? alpha * acc : alpha * acc + beta * y[r];
+}
+
+// ------------------------------------------------------------------------------------------
+// One lane per row.
+template <typename T>
+__global__ __launch_bounds__(kWG) void spmv_scalar_kernel(const int32_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ colidx,
+                                                          const typename T::elem* __restrict__ vals,
+                                                          const typename T::elem* __restrict__ x, float* y,
+                                                          const int32_t* __restrict__ rows, int count, float alpha,
+                                                          float beta) {
+    const int i = blockIdx.x * kWG + threadIdx.x;
+    if (i >= count) return;
+    const int r = rows ? rows[i] : i;
+    const int k1 = rowptr[r + 1];
+    float acc = 0.f;
+    for (int k = rowptr[r]; k < k1; ++k) acc += product_one(colidx, vals, x, k);
+    y[r] = epilogue(acc, alpha, beta, y, r);
+}
+
+// G lanes per row.
+template <typename T, int G>
+__global__ __launch_bounds__(kWG) void spmv_vector_kernel(const int32_t* __restrict__ rowptr,
+                                                          const int32_t* __restrict__ colidx,
+                                                          const typename T::elem* __restrict__ vals,
+                                                          const typename T::elem* __restrict__ x, float* y,
+                                                          const int32_t* __restrict__ rows, int count, float alpha,
+                                                          float beta, int vec_ok) {
+    const int team = static_cast<int>((static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x) / G);
+    const int lane = threadIdx.x % G;
+    const bool live = team < count;
+    int r = 0, k0 = 0, k1 = 0;
+    if (live) {
+        r = rows ? rows[team] : team;
+        k0 = rowptr[r];
+        k1 = rowptr[r + 1];
+    }
+    float acc = team_dot<T, G>(colidx, vals, x, k0, k1, lane, vec_ok != 0);
+    acc = group_sum<G>(acc);  // every lane of the wave takes part, also those without a row
+    if (live && lane == 0) y[r] = epilogue(acc, alpha, beta, y, r);
+}
+
+// ------------------------------------------------------------------------------------------
+struct TileArgs {
+    const int32_t* rowptr;
+    const int32_t* colidx;
+    const void* vals;
+    const void* x;
+    float* y;
+    const int32_t* part_row;  // row blocks [nparts+1]   | merge path: rows finished at each split
+    const int32_t* part_nz;   // unused                  | merge path: entries taken at each split
+    int32_t* carry_row;       // merge path only, [nparts]
+    float* carry_val;         // merge path only, [nparts]
+    int32_t nparts, m, nnz, tile_cap;
+    float alpha, beta;
+    int32_t vec_ok;
+};
+
+// One workgroup per tile.  A tile is a contiguous entry range [k0, k1) together with the rows
+// r0 .. r0+nr-1 whose last entry lies in it, plus (merge path only) the leading piece of row
+// r0+nr that the range cuts off, which leaves as a carry.
+//   1. segment bounds of those rows, relative to the aligned tile origin, go to LDS;
+//   2. the range is streamed with 128-bit loads, x gathered, products parked in LDS;
+//   3. rows are summed from LDS by teams of G lanes (G from the tile's mean row length);
+//      rows far longer than the mean are set aside and summed by whole wavefronts.
+template <typename T, bool MERGE>
+__global__ __launch_bounds__(kWG) void spmv_tile_kernel(const TileArgs a) {
+    using E = typename T::elem;
+    constexpr int VEC = T::VEC;
+    extern __shared__ __align__(16) float smem[];
+    __shared__ int deferred[kMaxDeferred];
+    __shared__ int n_deferred;
+    __shared__ float wave_part[kWG / 64];
+
+    const int tid = threadIdx.x;
+    const int part = xcd_remap(blockIdx.x, a.nparts);
+    const E* vals = static_cast<const E*>(a.vals);
+    const E* x = static_cast<const E*>(a.x);
+
+    int r0, r1, k0, k1;
+    if constexpr (MERGE) {
+        r0 = a.part_row[part];
+        r1 = a.part_row[part + 1];
+        k0 = a.part_nz[part];
+        k1 = a.part_nz[part + 1];
+    } else {
+        r0 = a.part_row[part];
+        r1 = a.part_row[part + 1];
+        k0 = a.rowptr[r0];
+        k1 = a.rowptr[r1];
+    }
+    const int nr = r1 - r0;
+
+    if constexpr (!MERGE) {
+        if (k1 - k0 > a.tile_cap) {
+            // A single row longer than a tile: the whole workgroup strides over it.
+            float acc = team_dot<T, kWG>(a.colidx, vals, x, k0, k1, tid, a.vec_ok != 0);
+            acc = group_sum<64>(acc);
+            if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
+            __syncthreads();
+            if (tid == 0) {
+                const float s = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
+                a.y[r0] = epilogue(s, a.alpha, a.beta, a.y, r0);
+            }
+            return;
+        }
+    }
+
+    int carry_len = 0;
+    if constexpr (MERGE) {
+        if (r1 < a.m) {
+            const int rs1 = a.rowptr[r1];
+            carry_len = k1 - (rs1 > k0 ? rs1 : k0);
+        }
+    }
+    const int nseg = nr + (carry_len > 0 ? 1 : 0);
+    const int k0a = k0 & ~(VEC - 1);
+    const int span = k1 - k0a;
+    int* seg = reinterpret_cast<int*>(smem + ((span + 3) & ~3));  // nseg + 1 bounds
+
+    if (tid == 0) {
+        n_deferred = 0;
+        if constexpr (MERGE) a.carry_row[part] = carry_len > 0 ? r1 : -1;
+    }
+    for (int i = tid; i <= nseg; i += kWG) {
+        int v = (i <= nr) ? a.rowptr[r0 + i] : k1;
+        v = v < k0 ? k0 : v;
+        v = v > k1 ? k1 : v;
+        seg[i] = v - k0a;
+    }
+
+    // ---- stream the entries
+    for (int off = tid * VEC; off < span; off += kWG * VEC) {
+        const int k = k0a + off;
+        float p[VEC];
+        if (a.vec_ok && k + VEC <= a.nnz) {
+            products_vec(a.colidx, vals, x, k, p);
+        } else {
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) p[i] = (k + i < a.nnz) ? product_one(a.colidx, vals, x, k + i) : 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < VEC; i += 4) {
+            f32x4 q = {p[i], p[i + 1], p[i + 2], p[i + 3]};
+            *reinterpret_cast<f32x4*>(smem + off + i) = q;
+        }
+    }
+    __syncthreads();
+
+    // ---- per-row sums out of LDS
+    int G = 1;
+    {
+        const int mean = nseg > 0 ? (k1 - k0) / nseg : 0;
+        while (G < 64 && 4 * G < mean) G <<= 1;
+    }
+    const int defer_len = 16 * G > 64 ? 16 * G : 64;
+    const int teams = kWG / G;
+    const int team = tid / G;
+    const int tl = tid & (G - 1);
+
+    auto emit = [&](int i, float s) {
+        if (i < nr) {
+            const int r = r0 + i;
+            a.y[r] = epilogue(s, a.alpha, a.beta, a.y, r);
+        } else {
+            a.carry_val[part] = s;
+        }
+    };
+
+    for (int base = 0; base < nseg; base += teams) {
+        const int i = base + team;
+        float acc = 0.f;
+        bool mine = false;
+        if (i < nseg) {
+            const int b = seg[i], e = seg[i + 1];
+            if (e - b <= defer_len) {
+                mine = true;
+                for (int j = b + tl; j < e; j += G) acc += smem[j];
+            } else if (tl == 0) {
+                deferred[atomicAdd(&n_deferred, 1)] = i;
+            }
+        }
+        acc = group_sum_rt(acc, G);
+        if (mine && tl == 0) emit(i, acc);
+    }
+    __syncthreads();
+
+    const int nd = n_deferred;
+    const int lane = tid & 63;
+    for (int d = tid >> 6; d < nd; d += kWG / 64) {
+        const int i = deferred[d];
+        const int b = seg[i], e = seg[i + 1];
+        float acc = 0.f;
+        for (int j = b + lane; j < e; j += 64) acc += smem[j];
+        acc = group_sum<64>(acc);
+        if (lane == 0) emit(i, acc);
+    }
+}
+
+// Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
+// are consecutive; the thread of the first of them sums the run in chunk order.
+__global__ __launch_bounds__(kWG) void merge_fixup_kernel(const int32_t* __restrict__ carry_row,
+                                                          const float* __restrict__ carry_val, int P, float* y,
+                                                          float alpha) {
+    const int p = blockIdx.x * kWG + threadIdx.x;
+    if (p >= P) return;
+    const int r = carry_row[p];
+    if (r < 0) return;
+    if (p > 0 && carry_row[p - 1] == r) return;
+    float s = 0.f;
+    for (int q = p; q < P && carry_row[q] == r; ++q) s += carry_val[q];
+    y[r] += alpha * s;
+}
+
+__global__ __launch_bounds__(kWG) void validate_columns_kernel(const int32_t* __restrict__ colidx, int nnz, int n,
+                                                               int32_t* flag) {
+    bool bad = false;
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; k < nnz;
+         k += static_cast<int64_t>(gridDim.x) * kWG) {
+        const int c = colidx[k];
+        bad |= (c < 0) | (c >= n);
+    }
+    if (bad) *flag = 1;
+}
+
+__global__ __launch_bounds__(64) void reduce_selftest_kernel(const float* in, float* out) {
+    const int l = threadIdx.x;
+    const float v = in[l];
+    out[0 * 64 + l] = group_sum<1>(v);
+    out[1 * 64 + l] = group_sum<2>(v);
+    out[2 * 64 + l] = group_sum<4>(v);
+    out[3 * 64 + l] = group_sum<8>(v);
+    out[4 * 64 + l] = group_sum<16>(v);
+    out[5 * 64 + l] = group_sum<32>(v);
+    out[6 * 64 + l] = group_sum<64>(v);
+    for (int gi = 0; gi < 7; ++gi) out[(7 + gi) * 64 + l] = group_sum_rt(v, 1 << gi);
+}
+
+inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
+
+template <typename T>
+hipError_t launch_scalar_t(const MatrixView& A, const int32_t* rows, int32_t count, const void* x, float* y, Scalars s,
+                           hipStream_t st) {
+    using E = typename T::elem;
+    hipLaunchKernelGGL((spmv_scalar_kernel<T>), dim3(ceil_div(count, kWG)), dim3(kWG), 0, st, A.rowptr, A.colidx,
+                       static_cast<const E*>(A.vals), static_cast<const E*>(x), y, rows, count, s.alpha, s.beta);
+    return hipGetLastError();
+}
+
+template <typename T, int G>
+hipError_t launch_vector_tg(const MatrixView& A, const int32_t* rows, int32_t count, const void* x, float* y,
+                            Scalars s, hipStream_t st) {
+    using E = typename T::elem;
+    const int grid = ceil_div(static_cast<int64_t>(count) * G, kWG);
+    hipLaunchKernelGGL((spmv_vector_kernel<T, G>), dim3(grid), dim3(kWG), 0, st, A.rowptr, A.colidx,
+                       static_cast<const E*>(A.vals), static_cast<const E*>(x), y, rows, count, s.alpha, s.beta,
+                       A.vec_ok ? 1 : 0);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_vector_t(const MatrixView& A, int lanes, const int32_t* rows, int32_t count, const void* x, float* y,
+                           Scalars s, hipStream_t st) {
+    switch (lanes) {
+        case 2: return launch_vector_tg<T, 2>(A, rows, count, x, y, s, st);
+        case 4: return launch_vector_tg<T, 4>(A, rows, count, x, y, s, st);
+        case 8: return launch_vector_tg<T, 8>(A, rows, count, x, y, s, st);
+        case 16: return launch_vector_tg<T, 16>(A, rows, count, x, y, s, st);
+        case 32: return launch_vector_tg<T, 32>(A, rows, count, x, y, s, st);
+        case 64: return launch_vector_tg<T, 64>(A, rows, count, x, y, s, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+TileArgs tile_args(const MatrixView& A, const void* x, float* y, Scalars s) {
+    TileArgs a{};
+    a.rowptr = A.rowptr;
+    a.colidx = A.colidx;
+    a.vals = A.vals;
+    a.x = x;
+    a.y = y;
+    a.m = A.m;
+    a.nnz = A.nnz;
+    a.alpha = s.alpha;
+    a.beta = s.beta;
+    a.vec_ok = A.vec_ok ? 1 : 0;
+    return a;
+}
+
+}  // namespace
+
+hipError_t launch_scalar(const MatrixView& A, const int32_t* rows, int32_t count, const void* x, float* y, Scalars s,
+                         hipStream_t st) {
+    if (count <= 0) return hipSuccess;
+    return A.bf16 ? launch_scalar_t<BF16>(A, rows, count, x, y, s, st) : launch_scalar_t<F32>(A, rows, count, x, y, s, st);
+}
+
+hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, int32_t count, const void* x, float* y,
+                         Scalars s, hipStream_t st) {
+    if (count <= 0) return hipSuccess;
+    return A.bf16 ? launch_vector_t<BF16>(A, lanes, rows, count, x, y, s, st)
+                  : launch_vector_t<F32>(A, lanes, rows, count, x, y, s, st);
+}
+
+hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, int32_t nb, int32_t block_nnz,
+                           int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st) {
+    if (nb <= 0) return hipSuccess;
+    TileArgs a = tile_args(A, x, y, s);
+    a.part_row = row_blocks;
+    a.nparts = nb;
+    a.tile_cap = block_nnz;
+    // products (tile + alignment slack) + segment bounds (rows + 1)
+    const size_t lds = sizeof(float) * static_cast<size_t>(block_nnz + 16 + rows_max + 4);
+    if (A.bf16)
+        hipLaunchKernelGGL((spmv_tile_kernel<BF16, false>), dim3(nb), dim3(kWG), lds, st, a);
+    else
+        hipLaunchKernelGGL((spmv_tile_kernel<F32, false>), dim3(nb), dim3(kWG), lds, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
+                        int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
+                        Scalars s, hipStream_t st) {
+    if (P <= 0) return hipSuccess;
+    TileArgs a = tile_args(A, x, y, s);
+    a.part_row = mp_row;
+    a.part_nz = mp_nz;
+    a.carry_row = carry_row;
+    a.carry_val = carry_val;
+    a.nparts = P;
+    a.tile_cap = items_per_chunk;
+    // entries + finished rows of a chunk add up to items_per_chunk; plus slack and the carry bound
+    const size_t lds = sizeof(float) * static_cast<size_t>(items_per_chunk + 24);
+    if (A.bf16)
+        hipLaunchKernelGGL((spmv_tile_kernel<BF16, true>), dim3(P), dim3(kWG), lds, st, a);
+    else
+        hipLaunchKernelGGL((spmv_tile_kernel<F32, true>), dim3(P), dim3(kWG), lds, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(merge_fixup_kernel, dim3(ceil_div(P, kWG)), dim3(kWG), 0, st, carry_row, carry_val, P, y, s.alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st) {
+    if (A.nnz <= 0) return hipSuccess;
+    int grid = ceil_div(A.nnz, kWG);
+    if (grid > 4096) grid = 4096;
+    hipLaunchKernelGGL(validate_columns_kernel, dim3(grid), dim3(kWG), 0, st, A.colidx, A.nnz, A.n, flag);
+    return hipGetLastError();
+}
+
+hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st) {
+    hipLaunchKernelGGL(reduce_selftest_kernel, dim3(1), dim3(64), 0, st, in, out);
+    return hipGetLastError();
+}
+
+const char* scalar_kernel_name() { return "spmv_scalar_kernel"; }
+const char* vector_kernel_name() { return "spmv_vector_kernel"; }
+const char* adaptive_kernel_name() { return "spmv_tile_kernel"; }
+const char* merge_kernel_name() { return "spmv_tile_kernel"; }
+
+}  // namespace spmv

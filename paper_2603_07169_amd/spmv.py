@@ -1,0 +1,225 @@
+"""ctypes binding of libspmv_mi355.so: same names and argument lists as include/spmv_mi355.h.
+
+Marshalling only.  Device arrays are passed as raw addresses (e.g. torch.Tensor.data_ptr()),
+streams as hipStream_t handles (torch.cuda.current_stream().cuda_stream).  There is no
+fallback: if the library is not built, importing the symbols raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from pathlib import Path
+
+import numpy as np
+
+from . import build as _build
+
+SPMV_F32, SPMV_BF16 = 0, 1
+SPMV_OK = 0
+(SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_STRUCTURE, SPMV_ERR_UNSUPPORTED, SPMV_ERR_NOT_ANALYZED, SPMV_ERR_ALLOC,
+ SPMV_ERR_HIP) = range(1, 7)
+SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE = range(6)
+PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge"}
+SPMV_NUM_BINS = 33
+
+EXPORTS = [
+    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+    "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce", "spmv_csr_main_kernel_name",
+    "spmv_status_string", "spmv_last_hip_error",
+]
+
+
+class spmv_analyze_params_t(C.Structure):
+    _fields_ = [("plan", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
+                ("items_per_chunk", C.c_int32), ("vector_lanes", C.c_int32), ("skip_validation", C.c_int32),
+                ("reserved", C.c_int32 * 2)]
+
+
+class spmv_analysis_info_t(C.Structure):
+    _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("nnz", C.c_int64), ("min_len", C.c_int64),
+                ("max_len", C.c_int64), ("n_empty", C.c_int64), ("num_row_blocks", C.c_int64),
+                ("num_chunks", C.c_int64), ("plan", C.c_int32), ("vector_lanes", C.c_int32),
+                ("block_nnz", C.c_int32), ("rows_max", C.c_int32), ("items_per_chunk", C.c_int32),
+                ("reserved", C.c_int32)]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
+
+
+class spmv_analysis_host_t(C.Structure):
+    _fields_ = [("bin_count", C.c_void_p), ("bin_offset", C.c_void_p), ("bin_rows", C.c_void_p),
+                ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p)]
+
+
+class SpmvError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = int(status)
+        super().__init__(f"{where}: {spmv_status_string(status)} (status {int(status)}, hip error {spmv_last_hip_error()})")
+
+
+_lib = None
+
+
+def library_path() -> Path:
+    return _build.LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _build.LIB_PATH.exists():
+        _build.build()
+    lib = C.CDLL(str(_build.LIB_PATH))
+    vp, i64, i32, f32 = C.c_void_p, C.c_int64, C.c_int32, C.c_float
+    lib.spmv_csr_create.argtypes = [C.POINTER(vp), i64, i64, i64, vp, vp, vp, C.c_int]
+    lib.spmv_csr_analyze.argtypes = [vp, C.POINTER(spmv_analyze_params_t)]
+    lib.spmv_csr_run.argtypes = [vp, vp, vp, f32, f32, vp]
+    lib.spmv_destroy.argtypes = [vp]
+    lib.spmv_csr_get_analysis_info.argtypes = [vp, C.POINTER(spmv_analysis_info_t)]
+    lib.spmv_csr_get_analysis.argtypes = [vp, C.POINTER(spmv_analysis_host_t)]
+    lib.spmv_analyze_host.argtypes = [i64, i64, i64, vp, C.POINTER(spmv_analyze_params_t),
+                                      C.POINTER(spmv_analysis_info_t), C.POINTER(spmv_analysis_host_t)]
+    lib.spmv_selftest_reduce.argtypes = [vp, vp, vp]
+    for name in ("spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+                 "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce"):
+        getattr(lib, name).restype = C.c_int
+    lib.spmv_csr_main_kernel_name.argtypes = [vp]
+    lib.spmv_csr_main_kernel_name.restype = C.c_char_p
+    lib.spmv_status_string.argtypes = [C.c_int]
+    lib.spmv_status_string.restype = C.c_char_p
+    lib.spmv_last_hip_error.argtypes = []
+    lib.spmv_last_hip_error.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _params(params):
+    if params is None:
+        return None
+    if isinstance(params, spmv_analyze_params_t):
+        return C.byref(params)
+    p = spmv_analyze_params_t()
+    for k, v in dict(params).items():
+        setattr(p, k, int(v))
+    return C.byref(p)
+
+
+# ------------------------------------------------------------------ the C entry points, one to one
+def spmv_status_string(status) -> str:
+    return _load().spmv_status_string(int(status)).decode()
+
+
+def spmv_last_hip_error() -> int:
+    return int(_load().spmv_last_hip_error())
+
+
+def spmv_csr_create(m, n, nnz, rowptr, colidx, vals, dtype):
+    """rowptr / colidx / vals: device addresses (int).  Returns (status, handle)."""
+    h = C.c_void_p()
+    st = _load().spmv_csr_create(C.byref(h), m, n, nnz, rowptr, colidx, vals, dtype)
+    return st, h
+
+
+def spmv_csr_analyze(handle, params=None):
+    return _load().spmv_csr_analyze(handle, _params(params))
+
+
+def spmv_csr_run(handle, x, y, alpha, beta, stream=None):
+    return _load().spmv_csr_run(handle, x, y, alpha, beta, stream)
+
+
+def spmv_destroy(handle):
+    return _load().spmv_destroy(handle)
+
+
+def spmv_csr_get_analysis_info(handle):
+    info = spmv_analysis_info_t()
+    st = _load().spmv_csr_get_analysis_info(handle, C.byref(info))
+    return st, info
+
+
+def _host_buffers(info):
+    bufs = {
+        "bin_count": np.zeros(SPMV_NUM_BINS, np.int32), "bin_offset": np.zeros(SPMV_NUM_BINS + 1, np.int32),
+        "bin_rows": np.zeros(info.m, np.int32), "row_blocks": np.zeros(info.num_row_blocks + 1, np.int32),
+        "mp_row": np.zeros(info.num_chunks + 1, np.int32), "mp_nz": np.zeros(info.num_chunks + 1, np.int32),
+    }
+    out = spmv_analysis_host_t(**{k: v.ctypes.data for k, v in bufs.items()})
+    return bufs, out
+
+
+def spmv_csr_get_analysis(handle):
+    """Returns (status, dict of numpy arrays)."""
+    st, info = spmv_csr_get_analysis_info(handle)
+    if st != SPMV_OK:
+        return st, None
+    bufs, out = _host_buffers(info)
+    st = _load().spmv_csr_get_analysis(handle, C.byref(out))
+    return st, bufs
+
+
+def spmv_analyze_host(m, n, nnz, rowptr_host: np.ndarray, params=None):
+    """Host-only analysis of a numpy rowptr.  Returns (status, info, dict of numpy arrays)."""
+    assert rowptr_host.dtype == np.int32 and rowptr_host.flags.c_contiguous and rowptr_host.size == m + 1
+    info = spmv_analysis_info_t()
+    lib = _load()
+    st = lib.spmv_analyze_host(m, n, nnz, rowptr_host.ctypes.data, _params(params), C.byref(info), None)
+    if st != SPMV_OK:
+        return st, None, None
+    bufs, out = _host_buffers(info)
+    st = lib.spmv_analyze_host(m, n, nnz, rowptr_host.ctypes.data, _params(params), C.byref(info), C.byref(out))
+    return st, info, bufs
+
+
+def spmv_selftest_reduce(in_dev, out_dev, stream=None):
+    return _load().spmv_selftest_reduce(in_dev, out_dev, stream)
+
+
+def spmv_csr_main_kernel_name(handle) -> str:
+    return _load().spmv_csr_main_kernel_name(handle).decode()
+
+
+def check(status, where="spmv"):
+    if status != SPMV_OK:
+        raise SpmvError(status, where)
+
+
+# ------------------------------------------------------------------ convenience wrapper (still marshalling only)
+class CsrMatrix:
+    """Owns a handle; keeps the torch tensors it borrows alive."""
+
+    def __init__(self, m, n, rowptr_t, colidx_t, vals_t, dtype, params=None):
+        self._keep = (rowptr_t, colidx_t, vals_t)
+        nnz = int(colidx_t.numel())
+        st, self.handle = spmv_csr_create(m, n, nnz, rowptr_t.data_ptr(), colidx_t.data_ptr() if nnz else None,
+                                          vals_t.data_ptr() if nnz else None, dtype)
+        check(st, "spmv_csr_create")
+        self.m, self.n, self.nnz, self.dtype = m, n, nnz, dtype
+        self.analyze(params)
+
+    def analyze(self, params=None):
+        check(spmv_csr_analyze(self.handle, params), "spmv_csr_analyze")
+        st, info = spmv_csr_get_analysis_info(self.handle)
+        check(st, "spmv_csr_get_analysis_info")
+        self.info = info
+        return info
+
+    def run(self, x_t, y_t, alpha=1.0, beta=0.0, stream=None):
+        check(spmv_csr_run(self.handle, x_t.data_ptr() if x_t is not None else None, y_t.data_ptr(), alpha, beta,
+                           stream), "spmv_csr_run")
+
+    def analysis(self):
+        st, bufs = spmv_csr_get_analysis(self.handle)
+        check(st, "spmv_csr_get_analysis")
+        return bufs
+
+    def close(self):
+        if getattr(self, "handle", None):
+            spmv_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

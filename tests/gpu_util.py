@@ -1,0 +1,88 @@
+"""Helpers of the GPU parity tests: move a workloads.CsrProblem to the device with torch
+(memory and streams only), run it through the C ABI, and compare with the oracle."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2603_07169_amd as s
+
+TOL = {"f32": 1e-5, "bf16": 8e-3}
+DTYPE_CODE = {"f32": s.SPMV_F32, "bf16": s.SPMV_BF16}
+ALL_PLANS = [s.SPMV_PLAN_SCALAR, s.SPMV_PLAN_VECTOR, s.SPMV_PLAN_BINNED, s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE]
+
+
+def to_dev(a: np.ndarray, offset_elems: int = 0) -> torch.Tensor:
+    """numpy -> cuda tensor with the same bits (uint16 travels as int16).  offset_elems > 0
+    places the data that many elements into a larger allocation (a misaligned view)."""
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if offset_elems:
+        buf = torch.empty(t.numel() + offset_elems, dtype=t.dtype, device="cuda")
+        view = buf[offset_elems:]
+        view.copy_(t)
+        return view
+    return t.cuda()
+
+
+class DeviceProblem:
+    def __init__(self, p, offset_elems=0):
+        self.p = p
+        self.rowptr = to_dev(p.rowptr)
+        self.colidx = to_dev(p.colidx, offset_elems)
+        self.vals = to_dev(p.vals, offset_elems)
+        self.x = to_dev(p.x, offset_elems)
+        self.y0 = to_dev(p.y0) if p.y0 is not None else torch.zeros(p.m, dtype=torch.float32, device="cuda")
+
+    def matrix(self, params=None) -> s.CsrMatrix:
+        p = self.p
+        return s.CsrMatrix(p.m, p.n, self.rowptr, self.colidx, self.vals, DTYPE_CODE[p.dtype], params)
+
+    def run(self, A, alpha=None, beta=None, y_init=None, stream=None) -> np.ndarray:
+        p = self.p
+        alpha = p.alpha if alpha is None else alpha
+        beta = p.beta if beta is None else beta
+        y = (self.y0 if y_init is None else y_init).clone()
+        A.run(self.x, y, alpha, beta, stream)
+        torch.cuda.synchronize()
+        return y.cpu().numpy()
+
+
+def reference(p, alpha=None, beta=None):
+    alpha = p.alpha if alpha is None else alpha
+    beta = p.beta if beta is None else beta
+    y0 = p.y0 if p.y0 is not None else np.zeros(p.m, dtype=np.float32)
+    return oracle.spmv_csr(p.dtype, p.m, p.n, p.rowptr, p.colidx, p.vals, p.x, y0, alpha, beta)
+
+
+def assert_close(p, y, y_ref, S_ref, alpha, beta, strict=False, what=""):
+    """|y - y_ref| <= tol * sum_j |a_ij x_j| per row (strict: exactly that bound).  Otherwise the
+    bound also carries |alpha| and the float32 rounding of beta*y0, which the stated bound
+    leaves out (it is zero for empty rows)."""
+    tol = TOL[p.dtype]
+    err = np.abs(y.astype(np.float64) - y_ref)
+    if strict:
+        bound = tol * S_ref
+    else:
+        y0 = p.y0 if (p.y0 is not None and beta != 0.0) else np.zeros(p.m, dtype=np.float32)
+        bound = tol * (abs(alpha) * S_ref + np.abs(np.float64(np.float32(beta)) * y0))
+    bad = np.flatnonzero(~(err <= bound))
+    if bad.size:
+        i = int(bad[0])
+        raise AssertionError(f"{what} {p.name}: {bad.size} rows off; first row {i}: y={y[i]!r} ref={y_ref[i]!r} "
+                             f"err={err[i]:.3e} bound={bound[i]:.3e} len={p.rowptr[i+1]-p.rowptr[i]}")
+    with np.errstate(divide="ignore", invalid="ignore"):
+        ratio = np.where(S_ref > 0, err / S_ref, 0.0)
+    return float(ratio.max(initial=0.0))
+
+
+def check_problem(p, params=None, strict=False, offset_elems=0, what=""):
+    d = DeviceProblem(p, offset_elems)
+    A = d.matrix(params)
+    y = d.run(A)
+    y_ref, S_ref = reference(p)
+    r = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict, what)
+    A.close()
+    return r

@@ -1,0 +1,134 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares, rejects bad
+arguments before touching the device, and its host analysis equals the oracle bit for bit."""
+import ctypes as C
+import re
+from pathlib import Path
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2603_07169_amd as s
+import workloads as w
+
+ROOT = Path(__file__).resolve().parents[1]
+
+
+def rowptr_of(lens):
+    return np.concatenate(([0], np.cumsum(np.asarray(lens, dtype=np.int64)))).astype(np.int32)
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "spmv_mi355.h").read_text()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(spmv_[a-z0-9_]+)\s*\(", header))
+    assert {"spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy"} <= declared
+    lib = C.CDLL(str(s.library_path()))
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert declared == set(s.spmv.EXPORTS)           # the binding mirrors the header, name for name
+
+
+def test_status_strings():
+    assert s.spmv_status_string(0) == "ok"
+    assert len({s.spmv_status_string(k) for k in range(7)}) == 7
+
+
+def test_create_argument_errors():
+    A = 4096  # any aligned fake address: create never dereferences
+    ok = lambda *a: s.spmv_csr_create(*a)[0]
+    assert ok(4, 4, 8, A, A, A, s.SPMV_F32) == s.SPMV_OK
+    assert ok(-1, 4, 8, A, A, A, 0) == s.SPMV_ERR_INVALID_ARG
+    assert ok(4, -1, 8, A, A, A, 0) == s.SPMV_ERR_INVALID_ARG
+    assert ok(4, 4, -8, A, A, A, 0) == s.SPMV_ERR_INVALID_ARG
+    assert ok(4, 4, 8, None, A, A, 0) == s.SPMV_ERR_INVALID_ARG
+    assert ok(4, 4, 8, A, None, A, 0) == s.SPMV_ERR_INVALID_ARG
+    assert ok(4, 4, 8, A, A, None, 0) == s.SPMV_ERR_INVALID_ARG
+    assert ok(4, 4, 0, A, None, None, 0) == s.SPMV_OK            # no entries: colidx/vals may be NULL
+    assert ok(4, 0, 3, A, A, A, 0) == s.SPMV_ERR_INVALID_ARG     # entries but no columns
+    assert ok(4, 4, 8, A, A, A, 7) == s.SPMV_ERR_INVALID_ARG     # unknown dtype
+    assert ok(2 ** 31, 4, 8, A, A, A, 0) == s.SPMV_ERR_UNSUPPORTED
+    assert ok(4, 4, 2 ** 31, A, A, A, 0) == s.SPMV_ERR_UNSUPPORTED
+    assert ok(4, 4, 8, A + 2, A, A, 0) == s.SPMV_ERR_UNSUPPORTED  # rowptr not int32-aligned
+    assert ok(4, 4, 8, A, A, A + 2, s.SPMV_F32) == s.SPMV_ERR_UNSUPPORTED
+    assert ok(4, 4, 8, A, A, A + 2, s.SPMV_BF16) == s.SPMV_OK
+    st, h = s.spmv_csr_create(4, 4, 8, A, A, A, 0)
+    assert s.spmv_csr_run(h, A, A, 1.0, 0.0) == s.SPMV_ERR_NOT_ANALYZED
+    assert s.spmv_csr_get_analysis_info(h)[0] == s.SPMV_ERR_NOT_ANALYZED
+    assert s.spmv_csr_main_kernel_name(h) == ""
+    assert s.spmv_destroy(h) == s.SPMV_OK
+    assert s.spmv_destroy(None) == s.SPMV_OK
+    assert s.spmv_csr_analyze(None) == s.SPMV_ERR_INVALID_ARG
+
+
+def test_analyze_parameter_ranges():
+    rp = rowptr_of([1, 2, 3])
+    def st(**kw):
+        return s.spmv_analyze_host(3, 4, 6, rp, kw)[0]
+    assert st() == s.SPMV_OK
+    assert st(block_nnz=8192, rows_max=1024, items_per_chunk=8192, vector_lanes=64, plan=5) == s.SPMV_OK
+    for bad in (dict(block_nnz=8193), dict(block_nnz=-1), dict(rows_max=1025), dict(rows_max=-3),
+                dict(items_per_chunk=8193), dict(items_per_chunk=-1), dict(vector_lanes=3), dict(vector_lanes=1),
+                dict(vector_lanes=128), dict(plan=6), dict(plan=-1)):
+        assert st(**bad) == s.SPMV_ERR_INVALID_ARG, bad
+
+
+def test_analyze_rejects_malformed_rowptr():
+    assert s.spmv_analyze_host(3, 4, 6, np.array([1, 2, 3, 6], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE
+    assert s.spmv_analyze_host(3, 4, 6, np.array([0, 4, 3, 6], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE
+    assert s.spmv_analyze_host(3, 4, 6, np.array([0, 2, 3, 5], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE
+
+
+def compare_with_oracle(rowptr, n, params):
+    m, nnz = rowptr.size - 1, int(rowptr[-1])
+    st, info, got = s.spmv_analyze_host(m, n, nnz, rowptr, params)
+    assert st == s.SPMV_OK
+    bn = params.get("block_nnz") or 2048
+    rm = params.get("rows_max") or 256
+    ipc = params.get("items_per_chunk") or 4096
+    stats = oracle.row_stats(rowptr)
+    assert (info.m, info.n, info.nnz) == (m, n, nnz)
+    assert (info.min_len, info.max_len, info.n_empty) == (stats["min_len"], stats["max_len"], stats["n_empty"])
+    cnt, off, rows = oracle.row_bins(rowptr)
+    assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_offset"], off)
+    assert np.array_equal(got["bin_rows"], rows)
+    rb = oracle.row_blocks(rowptr, bn, rm)
+    assert info.num_row_blocks == rb.size - 1 and np.array_equal(got["row_blocks"], rb)
+    mr, mz = oracle.merge_path(rowptr, ipc)
+    assert info.num_chunks == mr.size - 1
+    assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
+    want_plan = params.get("plan") or oracle.plan(m, nnz, stats["max_len"], bn)
+    assert info.plan == want_plan
+    assert info.vector_lanes == (params.get("vector_lanes") or oracle.vector_lanes(m, nnz))
+    assert (info.block_nnz, info.rows_max, info.items_per_chunk) == (bn, rm, ipc)
+    return info
+
+
+SHAPES = [
+    [], [0], [0, 0, 0], [5], [1, 0, 2, 0, 0, 7, 3], list(range(70)), [2049, 1, 2048, 0, 2047, 9000, 0, 0],
+    [2] * 3000, np.random.default_rng(5).integers(0, 40, 5000), np.random.default_rng(6).integers(0, 3000, 700),
+]
+PARAMS = [
+    {}, dict(block_nnz=1, rows_max=1, items_per_chunk=1), dict(block_nnz=6, rows_max=3, items_per_chunk=7),
+    dict(block_nnz=8192, rows_max=1024, items_per_chunk=8192), dict(block_nnz=100, rows_max=1000, items_per_chunk=64),
+    dict(plan=3, vector_lanes=16),
+]
+
+
+@pytest.mark.parametrize("lens", SHAPES)
+@pytest.mark.parametrize("params", PARAMS)
+def test_host_analysis_equals_oracle(lens, params):
+    compare_with_oracle(rowptr_of(lens), 10000, params)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_host_analysis_equals_oracle_on_full_configs(k):
+    """Only the row structure is needed, so the full-size configs are cheap here."""
+    p = w.config(k, 1.0 if k in (1, 2) else 0.25)
+    info = compare_with_oracle(p.rowptr, p.n, {})
+    if k == 1:
+        assert info.num_row_blocks == 32 and info.plan == s.SPMV_PLAN_ADAPTIVE
+    if k == 2:
+        assert info.num_row_blocks == 4096 and info.plan == s.SPMV_PLAN_ADAPTIVE
+    if k == 4:
+        assert info.plan == s.SPMV_PLAN_MERGE

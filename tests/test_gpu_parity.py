@@ -1,0 +1,207 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Floating point within the stated per-row bound (1e-5 * sum|a x| for FP32,
+8e-3 * sum|a x| for bf16 storage); integer-valued inputs and analysis outputs bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_07169_amd as s
+import workloads as w
+from gpu_util import ALL_PLANS, DeviceProblem, assert_close, check_problem, reference, to_dev
+
+pytestmark = pytest.mark.gpu
+
+PLAN_IDS = {p: s.PLAN_NAMES[p] for p in ALL_PLANS}
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+# ------------------------------------------------------------------ cross-lane reductions
+def test_cross_lane_group_sums():
+    rng = np.random.default_rng(11)
+    v = rng.integers(-1000, 1000, 64).astype(np.float32)     # integers: sums are exact in any order
+    d_in = to_dev(v)
+    d_out = torch.zeros(14 * 64, dtype=torch.float32, device="cuda")
+    s.check(s.spmv_selftest_reduce(d_in.data_ptr(), d_out.data_ptr(), None))
+    torch.cuda.synchronize()
+    out = d_out.cpu().numpy().reshape(14, 64)
+    for gi in range(7):
+        G = 1 << gi
+        want = np.repeat(v.reshape(64 // G, G).sum(axis=1), G)
+        assert np.array_equal(out[gi], want), f"compile-time G={G}"
+        assert np.array_equal(out[7 + gi], want), f"run-time G={G}"
+
+
+# ------------------------------------------------------------------ small adversarial shapes, every plan
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("plan", ALL_PLANS, ids=PLAN_IDS.get)
+def test_tiny_adversarial(dtype, plan):
+    for p in w.tiny_adversarial(dtype=dtype):
+        log("case", p.name, dtype, s.PLAN_NAMES[plan])
+        check_problem(p, dict(plan=plan), what=s.PLAN_NAMES[plan])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("plan", ALL_PLANS, ids=PLAN_IDS.get)
+def test_exact_integer_bit_for_bit(dtype, plan):
+    """Integer-valued inputs: every partial sum is an integer below 2^24, so the float32 result
+    does not depend on the summation order and must equal the oracle exactly."""
+    lens = [0, 1, 2, 3, 4, 5, 7, 8, 9, 63, 64, 65, 255, 256, 257, 2047, 2048, 2049, 0, 0, 4096, 4097, 10000, 1, 1, 200000, 3]
+    p = w.exact_integer(lens, 250000, dtype=dtype, alpha=3.0, beta=-2.0)
+    log("case exact_integer", dtype, s.PLAN_NAMES[plan])
+    d = DeviceProblem(p)
+    A = d.matrix(dict(plan=plan))
+    y = d.run(A)
+    y_ref, _ = reference(p)
+    assert np.array_equal(y.astype(np.float64), y_ref)
+    A.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_exact_integer_many_rows(dtype):
+    rng = np.random.default_rng(21)
+    lens = np.concatenate([rng.integers(0, 12, 20000), rng.integers(0, 400, 2000), [0] * 5000, rng.integers(0, 12, 3000)])
+    p = w.exact_integer(lens, 5000, dtype=dtype, alpha=1.0, beta=1.0)
+    y_ref, _ = reference(p)
+    d = DeviceProblem(p)
+    for plan in ALL_PLANS:
+        log("case exact_integer_many_rows", dtype, s.PLAN_NAMES[plan])
+        A = d.matrix(dict(plan=plan))
+        assert np.array_equal(d.run(A).astype(np.float64), y_ref), s.PLAN_NAMES[plan]
+        A.close()
+
+
+# ------------------------------------------------------------------ scaled configs, every plan
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("plan", ALL_PLANS, ids=PLAN_IDS.get)
+def test_scaled_configs_every_plan(k, plan):
+    p = w.config(k, 1.0 if k == 1 else 1 / 16)
+    log("case", p.name, s.PLAN_NAMES[plan])
+    check_problem(p, dict(plan=plan), strict=True, what=s.PLAN_NAMES[plan])
+
+
+# ------------------------------------------------------------------ tile-size parameters
+@pytest.mark.parametrize("params", [
+    dict(plan=4, block_nnz=1, rows_max=1), dict(plan=4, block_nnz=7, rows_max=3), dict(plan=4, block_nnz=8192, rows_max=1024),
+    dict(plan=4, block_nnz=64, rows_max=1024), dict(plan=4, block_nnz=8192, rows_max=2),
+    dict(plan=5, items_per_chunk=1), dict(plan=5, items_per_chunk=5), dict(plan=5, items_per_chunk=63),
+    dict(plan=5, items_per_chunk=8192), dict(plan=2, vector_lanes=2), dict(plan=2, vector_lanes=64),
+], ids=str)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tile_parameters(params, dtype):
+    rng = np.random.default_rng(31)
+    lens = np.concatenate([rng.integers(0, 30, 700), [9000, 0, 0, 1, 8193, 8192, 8191], rng.integers(0, 300, 150)])
+    p = w.from_row_lengths(lens, 20000, seed=77, dtype=dtype, alpha=1.5, beta=0.25)
+    log("case tile_parameters", params, dtype)
+    check_problem(p, params)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("plan", ALL_PLANS, ids=PLAN_IDS.get)
+def test_misaligned_arrays(dtype, plan):
+    """colidx / vals / x starting 1 element into an allocation: no 16-byte alignment, so the
+    128-bit load paths must not be taken."""
+    q = w.powerlaw(20000, dtype=dtype)
+    log("case misaligned", dtype, s.PLAN_NAMES[plan])
+    check_problem(q, dict(plan=plan), offset_elems=1)
+
+
+# ------------------------------------------------------------------ scalars, streams, reuse
+def test_beta_zero_ignores_nan_in_y():
+    p = w.config(2, 1 / 16)
+    d = DeviceProblem(p)
+    y_ref, S_ref = reference(p, 1.0, 0.0)
+    nan_y = torch.full((p.m,), float("nan"), dtype=torch.float32, device="cuda")
+    for plan in ALL_PLANS:
+        A = d.matrix(dict(plan=plan))
+        y = d.run(A, 1.0, 0.0, y_init=nan_y)
+        assert np.all(np.isfinite(y))
+        assert_close(p, y, y_ref, S_ref, 1.0, 0.0, strict=True)
+        A.close()
+
+
+def test_alpha_beta_grid_and_reuse_on_side_stream():
+    p = w.config(4, 1 / 100)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    st = torch.cuda.Stream()
+    for alpha, beta in [(1.0, 0.0), (0.0, 1.0), (-2.5, 0.75), (1.0, 1.0), (0.0, 0.0)]:
+        q = w.CsrProblem(p.name, p.dtype, p.m, p.n, p.rowptr, p.colidx, p.vals, p.x,
+                         np.random.default_rng(1).uniform(-1, 1, p.m).astype(np.float32), alpha, beta)
+        y0 = to_dev(q.y0)
+        with torch.cuda.stream(st):
+            y = y0.clone()
+            A.run(d.x, y, alpha, beta, st.cuda_stream)
+        st.synchronize()
+        y_ref, S_ref = reference(q)
+        assert_close(q, y.cpu().numpy(), y_ref, S_ref, alpha, beta)
+    A.close()
+
+
+def test_run_is_repeatable_bit_for_bit():
+    for k in (2, 4):
+        p = w.config(k, 1 / 16)
+        d = DeviceProblem(p)
+        A = d.matrix()
+        y1 = d.run(A)
+        y2 = d.run(A)
+        assert np.array_equal(y1, y2)
+        A.close()
+
+
+# ------------------------------------------------------------------ analysis read back from the device
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_device_analysis_equals_oracle(k):
+    p = w.config(k, 1.0 if k == 1 else 1 / 8)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    got = A.analysis()
+    cnt, off, rows = oracle.row_bins(p.rowptr)
+    assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_offset"], off)
+    assert np.array_equal(got["bin_rows"], rows)
+    assert np.array_equal(got["row_blocks"], oracle.row_blocks(p.rowptr, 2048, 256))
+    mr, mz = oracle.merge_path(p.rowptr, 4096)
+    assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
+    st = oracle.row_stats(p.rowptr)
+    assert A.info.plan == oracle.plan(p.m, p.nnz, st["max_len"], 2048)
+    assert (A.info.min_len, A.info.max_len, A.info.n_empty) == (st["min_len"], st["max_len"], st["n_empty"])
+    A.close()
+
+
+def test_analyze_rejects_bad_input_on_device():
+    p = w.config(1)
+    d = DeviceProblem(p)
+    bad_col = p.colidx.copy()
+    bad_col[1234] = p.n
+    st, h = s.spmv_csr_create(p.m, p.n, p.nnz, d.rowptr.data_ptr(), to_dev(bad_col).data_ptr(), d.vals.data_ptr(), 0)
+    assert st == s.SPMV_OK
+    assert s.spmv_csr_analyze(h) == s.SPMV_ERR_BAD_STRUCTURE
+    assert s.spmv_csr_run(h, d.x.data_ptr(), d.y0.data_ptr(), 1.0, 0.0) == s.SPMV_ERR_NOT_ANALYZED
+    s.spmv_destroy(h)
+    bad_rp = p.rowptr.copy()
+    bad_rp[10] = bad_rp[11] + 1
+    st, h = s.spmv_csr_create(p.m, p.n, p.nnz, to_dev(bad_rp).data_ptr(), d.colidx.data_ptr(), d.vals.data_ptr(), 0)
+    assert s.spmv_csr_analyze(h) == s.SPMV_ERR_BAD_STRUCTURE
+    s.spmv_destroy(h)
+
+
+def test_degenerate_shapes():
+    e32 = np.zeros(0, np.int32)
+    # m == 0: nothing to do
+    p = w.CsrProblem("m0", "f32", 0, 5, np.zeros(1, np.int32), e32, np.zeros(0, np.float32), np.ones(5, np.float32), None)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    A.run(d.x, d.y0, 1.0, 0.0)
+    A.close()
+    # nnz == 0: y <- beta*y for every plan
+    y0 = np.arange(7, dtype=np.float32)
+    p = w.CsrProblem("nnz0", "f32", 7, 5, np.zeros(8, np.int32), e32, np.zeros(0, np.float32), np.ones(5, np.float32), y0, 1.0, 3.0)
+    d = DeviceProblem(p)
+    for plan in [0] + ALL_PLANS:
+        A = d.matrix(dict(plan=plan))
+        assert np.array_equal(d.run(A), 3.0 * y0)
+        assert np.array_equal(d.run(A, 1.0, 0.0), np.zeros(7, np.float32))
+        A.close()
