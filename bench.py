@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the CSR sparse matrix-vector product  y <- alpha*A*x + beta*y  on one MI355X.
+
+One "step" is one spmv_csr_run() over one synthetic matrix (the whole hot path: every kernel of
+the plan that spmv_csr_analyze() chose).  Timing follows the paper's protocol for its kernel
+benchmark (section 3.3: warm-up runs, then the mean over the timed runs; defaults 3 and 50).
+
+Inputs are resident in HBM before the timed region.  Matrices smaller than the 256 MB
+last-level cache would be served from it when one copy is run back to back, so by default the
+steps rotate over several disjoint copies of {rowptr, colidx, vals, x, y} (more than 512 MB in
+total): `value` is that cold, HBM-bound rate; the cache-warm rate is reported beside it.
+
+Prints ONE JSON line.  metric = effective GB/s over the algorithmic bytes
+(vals + colidx + rowptr + x + y written, + y read when beta != 0); GFLOP/s = 2*nnz / time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+import numpy as np
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+LLC_BYTES = 256 << 20           # last-level (memory-side) cache
+ROTATE_TOTAL_BYTES = 640 << 20  # footprint the rotation must exceed
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="headline workload: 1..5 (BASELINE configs, 1-based)")
+    ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 scalar, 2 vector, 3 binned, 4 adaptive, 5 merge")
+    ap.add_argument("--block-nnz", type=int, default=0)
+    ap.add_argument("--rows-max", type=int, default=0)
+    ap.add_argument("--items-per-chunk", type=int, default=0)
+    ap.add_argument("--vector-lanes", type=int, default=0)
+    ap.add_argument("--only", action="store_true", help="measure the headline workload only (skip the other configs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copies", type=int, default=0, help="override the number of rotating copies")
+    return ap.parse_args()
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(a.view(np.int16) if a.dtype == np.uint16 else a).cuda()
+
+
+class Resident:
+    """`copies` disjoint device copies of one problem, each with its own handle."""
+
+    def __init__(self, p, copies, params):
+        import torch
+        import paper_2603_07169_amd as s
+        self.p = p
+        self.sets = []
+        for _ in range(copies):
+            rowptr, colidx, vals, x = dev(p.rowptr), dev(p.colidx), dev(p.vals), dev(p.x)
+            y = dev(p.y0) if p.y0 is not None else torch.zeros(p.m, dtype=torch.float32, device="cuda")
+            A = s.CsrMatrix(p.m, p.n, rowptr, colidx, vals, s.SPMV_F32 if p.dtype == "f32" else s.SPMV_BF16, params)
+            self.sets.append((A, x, y))
+        self.info = self.sets[0][0].info
+        self.kernel = s.spmv_csr_main_kernel_name(self.sets[0][0].handle)
+
+    def step(self, i, stream):
+        A, x, y = self.sets[i % len(self.sets)]
+        A.run(x, y, self.p.alpha, self.p.beta, stream)
+
+    def close(self):
+        for A, _, _ in self.sets:
+            A.close()
+        self.sets = []
+
+
+def time_steps(res, steps, warmup, rotate=True):
+    """Mean ms per step over `steps` steps, HIP events on the launch stream."""
+    import torch
+    stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+    idx = (lambda i: i) if rotate else (lambda i: 0)
+    for i in range(warmup):
+        res.step(idx(i), h)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record(stream)
+    for i in range(steps):
+        res.step(idx(warmup + i), h)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    return e0.elapsed_time(e1) / steps, wall_ms / steps
+
+
+def time_each(res, steps, rotate=True):
+    """Per-step durations (ms) from one event pair per step: median and min."""
+    import torch
+    stream = torch.cuda.current_stream()
+    h = stream.cuda_stream
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for i, (a, b) in enumerate(ev):
+        a.record(stream)
+        res.step(i if rotate else 0, h)
+        b.record(stream)
+    torch.cuda.synchronize()
+    t = np.array([a.elapsed_time(b) for a, b in ev])
+    return float(np.median(t)), float(t.min())
+
+
+def measure(k, args, params, with_parity=True):
+    import workloads as w
+    p = w.config(k)
+    bytes_alg = p.algorithmic_bytes()
+    copies = args.copies or (max(2, -(-ROTATE_TOTAL_BYTES // bytes_alg)) if bytes_alg < 2 * LLC_BYTES else 2)
+    copies = min(copies, 64)
+    res = Resident(p, copies, params)
+    ms, wall_ms = time_steps(res, args.steps, args.warmup, rotate=True)
+    med, mn = time_each(res, min(args.steps, 50), rotate=True)
+    ms_warm, _ = time_steps(res, args.steps, args.warmup, rotate=False)
+    import paper_2603_07169_amd as s
+    out = {
+        "workload": p.name, "dtype": p.dtype, "m": p.m, "n": p.n, "nnz": p.nnz, "alpha": p.alpha, "beta": p.beta,
+        "algorithmic_bytes": bytes_alg, "plan": s.PLAN_NAMES[res.info.plan], "kernel": res.kernel,
+        "copies_rotated": copies, "ms_per_step": ms, "ms_median": med, "ms_min": mn, "ms_per_step_wall": wall_ms,
+        "GBps": bytes_alg / ms / 1e6, "GFLOPs": p.flops() / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS,
+        "warm_ms_per_step": ms_warm, "warm_GBps": bytes_alg / ms_warm / 1e6,
+    }
+    res.close()
+    return p, out
+
+
+def cpu_baseline(p):
+    """The oracle as it stands, one thread, on the whole workload: 1 warm-up + best of 5."""
+    import oracle
+    best = float("inf")
+    for i in range(6):
+        t0 = time.perf_counter()
+        oracle.spmv_problem(p)
+        dt = time.perf_counter() - t0
+        if i > 0:
+            best = min(best, dt)
+    return {"value": p.algorithmic_bytes() / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"whole workload {p.name} ({p.nnz} nnz), single thread, best of 5 after 1 warm-up",
+            "ms": best * 1e3, "GFLOPs": p.flops() / best / 1e9, "host_cores_available": os.cpu_count()}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: the product has no multi-GPU path (run with --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    params = dict(plan=args.plan, block_nnz=args.block_nnz, rows_max=args.rows_max,
+                  items_per_chunk=args.items_per_chunk, vector_lanes=args.vector_lanes, skip_validation=0)
+    p, head = measure(args.config, args, params)
+    line = {
+        "metric": "CSR SpMV effective HBM bandwidth (algorithmic bytes / time)",
+        "value": head["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": head["workload"], "m": p.m, "n": p.n, "nnz": p.nnz, "alpha": p.alpha, "beta": p.beta,
+                   "storage": p.dtype, "plan": head["plan"], "cache_state": f"cold: rotating over {head['copies_rotated']} disjoint copies"},
+        "gflops": head["GFLOPs"], "warm_GBps": head["warm_GBps"],
+        "roofline": {"bound": "hbm", "achieved": head["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": head["hbm_frac"], "traffic": None, "kernel": head["kernel"],
+                     "algorithmic_bytes_per_launch": head["algorithmic_bytes"],
+                     "avg_launch_ms": head["ms_per_step"]},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(p)
+    del p
+    if not args.only:
+        per = [head]
+        for k in range(1, 6):
+            if k != args.config:
+                _, r = measure(k, args, params)
+                per.append(r)
+        line["per_config"] = sorted(per, key=lambda r: r["workload"])
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

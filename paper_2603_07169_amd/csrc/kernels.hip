@@ -284,7 +284,8 @@ __global__ __launch_bounds__(kWG) void spmv_tile_kernel(const TileArgs a) {
     const int nseg = nr + (carry_len > 0 ? 1 : 0);
     const int k0a = k0 & ~(VEC - 1);
     const int span = k1 - k0a;
-    int* seg = reinterpret_cast<int*>(smem + ((span + 3) & ~3));  // nseg + 1 bounds
+    // the stream below stores whole vectors, so the bounds start past the last (partial) one
+    int* seg = reinterpret_cast<int*>(smem + ((span + VEC - 1) & ~(VEC - 1)));  // nseg + 1 entries
 
     if (tid == 0) {
         n_deferred = 0;
