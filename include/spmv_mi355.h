@@ -63,9 +63,9 @@ typedef enum {
 /* Analysis parameters.  Zero in any field selects that field's default. */
 typedef struct {
     int32_t plan;             /* spmv_plan_t; default AUTO */
-    int32_t block_nnz;        /* row blocks: most stored entries per block; default 2048, 1..8192 */
+    int32_t block_nnz;        /* row blocks: most stored entries per block; default 2040, 1..8192 */
     int32_t rows_max;         /* row blocks: most rows per block;           default 256,  1..1024 */
-    int32_t items_per_chunk;  /* merge path: steps (row ends + entries) per chunk; default 4096, 1..8192 */
+    int32_t items_per_chunk;  /* merge path: steps (row ends + entries) per chunk; default 2040, 1..8192 */
     int32_t vector_lanes;     /* VECTOR plan: lanes per row, power of two 2..64; default: chosen from nnz/m */
     int32_t skip_validation;  /* nonzero: do not scan colidx for out-of-range columns in analyze */
     int32_t reserved[2];      /* must be zero */

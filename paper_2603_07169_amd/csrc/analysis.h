@@ -8,9 +8,11 @@
 
 namespace spmv {
 
-constexpr int kDefaultBlockNnz = 2048;
+// 2040 + (vector width - 1) stays inside 2048 slots: a default tile is at most two 128-bit
+// vectors per lane of a 256-lane workgroup in FP32 and one in bf16.
+constexpr int kDefaultBlockNnz = 2040;
 constexpr int kDefaultRowsMax = 256;
-constexpr int kDefaultItemsPerChunk = 4096;
+constexpr int kDefaultItemsPerChunk = 2040;
 constexpr int kMaxBlockNnz = 8192;
 constexpr int kMaxRowsMax = 1024;
 constexpr int kMaxItemsPerChunk = 8192;

@@ -40,6 +40,7 @@ struct spmv_csr_s {
     // device metadata, owned
     int32_t* d_bin_rows = nullptr;
     int32_t* d_row_blocks = nullptr;
+    int32_t* d_block_nz = nullptr;  // rowptr[row_blocks[b]]: spares the kernels a dependent load
     int32_t* d_mp_row = nullptr;
     int32_t* d_mp_nz = nullptr;
     int32_t* d_carry_row = nullptr;
@@ -49,10 +50,10 @@ struct spmv_csr_s {
 namespace {
 
 void free_metadata(spmv_csr_s* h) {
-    void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_mp_row, h->d_mp_nz, h->d_carry_row, h->d_carry_val};
+    void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row, h->d_mp_nz, h->d_carry_row, h->d_carry_val};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
-    h->d_bin_rows = h->d_row_blocks = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
+    h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
     h->d_carry_val = nullptr;
     h->analyzed = false;
 }
@@ -151,6 +152,15 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
 
     st = upload(a.bin_rows, &h->d_bin_rows);
     if (st == SPMV_OK) st = upload(a.row_blocks, &h->d_row_blocks);
+    if (st == SPMV_OK) {
+        try {
+            std::vector<int32_t> block_nz(a.row_blocks.size());
+            for (size_t b = 0; b < block_nz.size(); ++b) block_nz[b] = rowptr_host[static_cast<size_t>(a.row_blocks[b])];
+            st = upload(block_nz, &h->d_block_nz);
+        } catch (const std::bad_alloc&) {
+            st = SPMV_ERR_ALLOC;
+        }
+    }
     if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
     if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
     if (st == SPMV_OK) {
@@ -209,7 +219,7 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
             break;
         }
         case SPMV_PLAN_ADAPTIVE:
-            e = spmv::launch_adaptive(A, h->d_row_blocks, static_cast<int32_t>(h->info.num_row_blocks),
+            e = spmv::launch_adaptive(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->info.rows_max, x, y, s, st);
             break;
         case SPMV_PLAN_MERGE:
@@ -294,8 +304,8 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_SCALAR: return spmv::scalar_kernel_name();
         case SPMV_PLAN_VECTOR:
         case SPMV_PLAN_BINNED: return spmv::vector_kernel_name();
-        case SPMV_PLAN_ADAPTIVE: return spmv::adaptive_kernel_name();
-        case SPMV_PLAN_MERGE: return spmv::merge_kernel_name();
+        case SPMV_PLAN_ADAPTIVE:
+        case SPMV_PLAN_MERGE: return spmv::tile_kernel_name();
         default: return "";
     }
 }

@@ -25,9 +25,10 @@ hipError_t launch_scalar(const MatrixView& A, const int32_t* rows, int32_t count
 // lanes: power of two in [2, 64].
 hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, int32_t count, const void* x, float* y,
                          Scalars s, hipStream_t st);
-// row_blocks: device [nb+1].  block_nnz, rows_max: the limits the partition was built with.
-hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, int32_t nb, int32_t block_nnz,
-                           int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st);
+// row_blocks: device [nb+1]; block_nz: device [nb+1], block_nz[b] = rowptr[row_blocks[b]].
+// block_nnz, rows_max: the limits the partition was built with.
+hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+                           int32_t block_nnz, int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st);
 // mp_row, mp_nz: device [P+1]; carry_row/carry_val: device [P] scratch owned by the handle.
 hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
@@ -42,7 +43,6 @@ hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st);
 
 const char* scalar_kernel_name();
 const char* vector_kernel_name();
-const char* adaptive_kernel_name();
-const char* merge_kernel_name();
+const char* tile_kernel_name();  // kernel of the adaptive and merge plans
 
 }  // namespace spmv

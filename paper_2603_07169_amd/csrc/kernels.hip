@@ -14,6 +14,9 @@
 // No matrix cores: nothing here is a dense contraction.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+#include <cstdlib>
+
 #include "kernels.h"
 
 namespace spmv {
@@ -215,124 +218,139 @@ struct TileArgs {
     const void* vals;
     const void* x;
     float* y;
-    const int32_t* part_row;  // row blocks [nparts+1]   | merge path: rows finished at each split
-    const int32_t* part_nz;   // unused                  | merge path: entries taken at each split
+    const int32_t* part_row;  // [nparts+1] first row of each row block | rows finished at each merge-path split
+    const int32_t* part_nz;   // [nparts+1] entry index where each part starts (row blocks: rowptr[part_row[b]])
     int32_t* carry_row;       // merge path only, [nparts]
     float* carry_val;         // merge path only, [nparts]
-    int32_t nparts, m, nnz, tile_cap;
+    int32_t nparts, m, n, nnz;
+    int32_t tile_cap;         // most entries a tile can hold (a row block may exceed it only as a single row)
+    int32_t team_bias;        // log2 factor applied to the lanes-per-row choice (0 = default)
     float alpha, beta;
     int32_t vec_ok;
 };
 
-// One workgroup per tile.  A tile is a contiguous entry range [k0, k1) together with the rows
-// r0 .. r0+nr-1 whose last entry lies in it, plus (merge path only) the leading piece of row
-// r0+nr that the range cuts off, which leaves as a carry.
-//   1. segment bounds of those rows, relative to the aligned tile origin, go to LDS;
-//   2. the range is streamed with 128-bit loads, x gathered, products parked in LDS;
-//   3. rows are summed from LDS by teams of G lanes (G from the tile's mean row length);
-//      rows far longer than the mean are set aside and summed by whole wavefronts.
-template <typename T, bool MERGE>
-__global__ __launch_bounds__(kWG) void spmv_tile_kernel(const TileArgs a) {
+// A single row longer than a tile: the whole workgroup strides over it.
+template <typename T, int WG>
+__device__ __forceinline__ void long_row(const TileArgs& a, int r, int k0, int k1, float* wave_part, int tid) {
     using E = typename T::elem;
-    constexpr int VEC = T::VEC;
-    extern __shared__ __align__(16) float smem[];
-    __shared__ int deferred[kMaxDeferred];
-    __shared__ int n_deferred;
-    __shared__ float wave_part[kWG / 64];
-
-    const int tid = threadIdx.x;
-    const int part = xcd_remap(blockIdx.x, a.nparts);
-    const E* vals = static_cast<const E*>(a.vals);
-    const E* x = static_cast<const E*>(a.x);
-
-    int r0, r1, k0, k1;
-    if constexpr (MERGE) {
-        r0 = a.part_row[part];
-        r1 = a.part_row[part + 1];
-        k0 = a.part_nz[part];
-        k1 = a.part_nz[part + 1];
-    } else {
-        r0 = a.part_row[part];
-        r1 = a.part_row[part + 1];
-        k0 = a.rowptr[r0];
-        k1 = a.rowptr[r1];
-    }
-    const int nr = r1 - r0;
-
-    if constexpr (!MERGE) {
-        if (k1 - k0 > a.tile_cap) {
-            // A single row longer than a tile: the whole workgroup strides over it.
-            float acc = team_dot<T, kWG>(a.colidx, vals, x, k0, k1, tid, a.vec_ok != 0);
-            acc = group_sum<64>(acc);
-            if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
-            __syncthreads();
-            if (tid == 0) {
-                const float s = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
-                a.y[r0] = epilogue(s, a.alpha, a.beta, a.y, r0);
-            }
-            return;
-        }
-    }
-
-    int carry_len = 0;
-    if constexpr (MERGE) {
-        if (r1 < a.m) {
-            const int rs1 = a.rowptr[r1];
-            carry_len = k1 - (rs1 > k0 ? rs1 : k0);
-        }
-    }
-    const int nseg = nr + (carry_len > 0 ? 1 : 0);
-    const int k0a = k0 & ~(VEC - 1);
-    const int span = k1 - k0a;
-    // the stream below stores whole vectors, so the bounds start past the last (partial) one
-    int* seg = reinterpret_cast<int*>(smem + ((span + VEC - 1) & ~(VEC - 1)));  // nseg + 1 entries
-
-    if (tid == 0) {
-        n_deferred = 0;
-        if constexpr (MERGE) a.carry_row[part] = carry_len > 0 ? r1 : -1;
-    }
-    for (int i = tid; i <= nseg; i += kWG) {
-        int v = (i <= nr) ? a.rowptr[r0 + i] : k1;
-        v = v < k0 ? k0 : v;
-        v = v > k1 ? k1 : v;
-        seg[i] = v - k0a;
-    }
-
-    // ---- stream the entries
-    for (int off = tid * VEC; off < span; off += kWG * VEC) {
-        const int k = k0a + off;
-        float p[VEC];
-        if (a.vec_ok && k + VEC <= a.nnz) {
-            products_vec(a.colidx, vals, x, k, p);
-        } else {
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) p[i] = (k + i < a.nnz) ? product_one(a.colidx, vals, x, k + i) : 0.f;
-        }
-#pragma unroll
-        for (int i = 0; i < VEC; i += 4) {
-            f32x4 q = {p[i], p[i + 1], p[i + 2], p[i + 3]};
-            *reinterpret_cast<f32x4*>(smem + off + i) = q;
-        }
-    }
+    float acc = team_dot<T, WG>(a.colidx, static_cast<const E*>(a.vals), static_cast<const E*>(a.x), k0, k1, tid,
+                                 a.vec_ok != 0);
+    acc = group_sum<64>(acc);
+    if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
     __syncthreads();
+    if (tid == 0) {
+        float s = wave_part[0];
+        for (int w = 1; w < WG / 64; ++w) s += wave_part[w];
+        a.y[r] = epilogue(s, a.alpha, a.beta, a.y, r);
+    }
+}
 
-    // ---- per-row sums out of LDS
+// Partial dot product of the staged entries [b, e) of one segment, taken by lane `tl` of a team
+// of G lanes: entry j of the segment goes to lane j mod G.  Neighbouring teams work on
+// neighbouring rows, so for banded or stencil-like rows the lanes of a gather instruction fall
+// into a handful of cache lines.
+// A dependent gather costs a full trip through the memory pipeline even when it hits in cache,
+// so the gathers of a lane are issued in one batch before any is used; the batch size is the
+// smallest of a few fixed sizes that covers what the lane has left, because gather
+// instructions issued for nothing still take their turn in the address unit.
+template <int B, typename E>
+__device__ __forceinline__ float gather_batch(const int* cols, const E* vals, const E* x, int j0, int e, int G) {
+    // three waves of independent accesses, each issued back to back: column indices from LDS,
+    // x from memory, matrix values from LDS
+    int jj[B];
+    int c[B];
+    E xv[B];
+    E av[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u) {
+        const int j = j0 + u * G;
+        jj[u] = j < e ? j : j0;  // a lane with nothing left re-reads its first entry and drops it
+    }
+#pragma unroll
+    for (int u = 0; u < B; ++u) c[u] = cols[jj[u]];
+#pragma unroll
+    for (int u = 0; u < B; ++u) xv[u] = x[c[u]];
+#pragma unroll
+    for (int u = 0; u < B; ++u) av[u] = vals[jj[u]];
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < B; ++u) acc += (j0 + u * G < e) ? widen(av[u]) * widen(xv[u]) : 0.f;
+    return acc;
+}
+
+template <typename E>
+__device__ __forceinline__ float segment_dot(const int* cols, const E* vals, const E* x, int b, int e, int tl, int G) {
+    float acc = 0.f;
+    int j0 = b + tl;
+    while (j0 < e) {
+        const int left = (e - j0 + G - 1) / G;  // entries this lane still has to take
+        if (left > 8) {
+            acc += gather_batch<16>(cols, vals, x, j0, e, G);
+            j0 += 16 * G;
+        } else if (left > 4) {
+            acc += gather_batch<8>(cols, vals, x, j0, e, G);
+            j0 += 8 * G;
+        } else {
+            acc += gather_batch<4>(cols, vals, x, j0, e, G);
+            j0 += 4 * G;
+        }
+    }
+    return acc;
+}
+
+// Where the row phase of a tile sends its results.
+struct RowOut {
+    float* y;
+    int32_t* carry_row;
+    float* carry_val;
+    float alpha, beta;
+    const float* y0_lds;  // old y of the tile's first y0_count rows, staged in LDS
+    int y0_count;
+    int team_bias;
+};
+
+// Row phase of a tile whose entries sit in LDS (cols[], vals[]); seg[i] .. seg[i+1] bounds the
+// slots of segment i.  Segments 0 .. nr-1 are the rows r0 .. r0+nr-1 and go to y.  With MERGE
+// there is one more segment, the piece of row r0+nr that the chunk cuts off: its sum is the
+// chunk's carry (no carry when it is empty).  Teams of G lanes (G from the mean segment
+// length) take one segment each; segments far longer than the mean are set aside and taken by
+// whole wavefronts afterwards.  Entered by the whole workgroup with *n_deferred == 0; contains
+// one barrier.
+template <bool MERGE, int WG, typename E>
+__device__ __forceinline__ void tile_rows(const int* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
+                                          int part, int tile_nnz, const RowOut& o, int* deferred, int* n_deferred,
+                                          int tid) {
+    const int nseg = nr + (MERGE ? 1 : 0);
     int G = 1;
     {
-        const int mean = nseg > 0 ? (k1 - k0) / nseg : 0;
-        while (G < 64 && 4 * G < mean) G <<= 1;
+        const int mean = nseg > 0 ? tile_nnz / nseg : 0;
+        while (G < 64 && 16 * G < mean) G <<= 1;
+        if (o.team_bias > 0) G = (G << o.team_bias) > 64 ? 64 : (G << o.team_bias);
+        if (o.team_bias < 0) G = (G >> -o.team_bias) < 1 ? 1 : (G >> -o.team_bias);
     }
-    const int defer_len = 16 * G > 64 ? 16 * G : 64;
-    const int teams = kWG / G;
+    const int defer_len = 32 * G > 64 ? 32 * G : 64;
+    const int teams = WG / G;
     const int team = tid / G;
     const int tl = tid & (G - 1);
 
-    auto emit = [&](int i, float s) {
+    auto emit = [&](int i, float s, int len) {
         if (i < nr) {
             const int r = r0 + i;
-            a.y[r] = epilogue(s, a.alpha, a.beta, a.y, r);
+            if (o.beta == 0.f) {
+                o.y[r] = o.alpha * s;
+            } else {
+                // A staged copy of the old y spares a global load this late in the tile, which
+                // would have to queue behind everything the workgroup has in flight.
+                float y_old;
+                if (i < o.y0_count)
+                    y_old = o.y0_lds[i];
+                else
+                    y_old = o.y[r];
+                o.y[r] = o.alpha * s + o.beta * y_old;
+            }
         } else {
-            a.carry_val[part] = s;
+            o.carry_row[part] = len > 0 ? r0 + nr : -1;
+            o.carry_val[part] = s;
         }
     };
 
@@ -340,30 +358,163 @@ __global__ __launch_bounds__(kWG) void spmv_tile_kernel(const TileArgs a) {
         const int i = base + team;
         float acc = 0.f;
         bool mine = false;
+        int len = 0;
         if (i < nseg) {
             const int b = seg[i], e = seg[i + 1];
-            if (e - b <= defer_len) {
+            len = e - b;
+            if (len <= defer_len) {
                 mine = true;
-                for (int j = b + tl; j < e; j += G) acc += smem[j];
+                acc = segment_dot(cols, vals, x, b, e, tl, G);
             } else if (tl == 0) {
-                deferred[atomicAdd(&n_deferred, 1)] = i;
+                deferred[atomicAdd(n_deferred, 1)] = i;
             }
         }
-        acc = group_sum_rt(acc, G);
-        if (mine && tl == 0) emit(i, acc);
+        acc = group_sum_rt(acc, G);  // every lane takes part
+        if (mine && tl == 0) emit(i, acc, len);
     }
     __syncthreads();
 
-    const int nd = n_deferred;
+    const int nd = *n_deferred;
     const int lane = tid & 63;
-    for (int d = tid >> 6; d < nd; d += kWG / 64) {
+    for (int d = tid >> 6; d < nd; d += WG / 64) {
         const int i = deferred[d];
         const int b = seg[i], e = seg[i + 1];
-        float acc = 0.f;
-        for (int j = b + lane; j < e; j += 64) acc += smem[j];
+        float acc = segment_dot(cols, vals, x, b, e, lane, 64);
         acc = group_sum<64>(acc);
-        if (lane == 0) emit(i, acc);
+        if (lane == 0) emit(i, acc, e - b);
     }
+}
+
+// One workgroup per tile.  A tile is a contiguous entry range [k0, k1) together with the rows
+// r0 .. r0+nr-1 whose last entry lies in it, plus (merge path only) the leading piece of row
+// r0+nr that the range cuts off, which leaves as a carry.
+//   1. The tile's slice of colidx/vals is copied to LDS as it is, with 128-bit loads from an
+//      aligned origin (element-wise when the arrays are not 16-byte aligned, and for the last
+//      few entries of the array that no whole vector covers).  The bounds of the tile's
+//      segments, relative to that origin, go to LDS as well.
+//   2. Teams of G lanes (G from the tile's mean row length) take one row each, read its
+//      entries back from LDS, gather x and accumulate; a DPP/swizzle reduction closes the
+//      row.  Rows far longer than the mean are set aside and taken by whole wavefronts.
+// Streaming the matrix through LDS keeps its global reads perfectly coalesced while the x
+// gathers are issued row-wise, where neighbouring lanes touch neighbouring columns.
+template <typename T, bool MERGE, int WG>
+__global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
+    using E = typename T::elem;
+    constexpr int VEC = T::VEC;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    __shared__ int deferred[kMaxDeferred];
+    __shared__ int n_deferred;
+    __shared__ float wave_part[WG / 64];
+
+    const int tid = threadIdx.x;
+    const int part = xcd_remap(blockIdx.x, a.nparts);
+    const E* vals = static_cast<const E*>(a.vals);
+    const E* x = static_cast<const E*>(a.x);
+
+    const int r0 = a.part_row[part];
+    const int nr = a.part_row[part + 1] - r0;
+    const int k0 = a.part_nz[part];
+    const int k1 = a.part_nz[part + 1];
+
+    if constexpr (!MERGE) {
+        if (k1 - k0 > a.tile_cap) {
+            long_row<T, WG>(a, r0, k0, k1, wave_part, tid);
+            return;
+        }
+    }
+
+    const int nseg = nr + (MERGE ? 1 : 0);
+    const int k0a = k0 & ~(VEC - 1);
+    const int span = k1 - k0a;
+    const int slots = (span + VEC - 1) & ~(VEC - 1);  // whole vectors are stored
+    int* cols_l = reinterpret_cast<int*>(smem_raw);
+    E* vals_l = reinterpret_cast<E*>(smem_raw + sizeof(int) * slots);
+    int* seg = reinterpret_cast<int*>(smem_raw + (sizeof(int) + sizeof(E)) * slots);  // nseg + 1 entries
+
+    if (tid == 0) n_deferred = 0;
+    for (int i = tid; i <= nseg; i += WG) {
+        int v = (i <= nr) ? a.rowptr[r0 + i] : k1;
+        v = v < k0 ? k0 : v;
+        v = v > k1 ? k1 : v;
+        seg[i] = v - k0a;
+    }
+
+    // ---- 1. stage the tile's entries: two vectors per lane and trip, all loads before any store
+    if (a.vec_ok) {
+        const int nnz_vec = a.nnz & ~(VEC - 1);  // entries reachable by whole vectors
+        for (int off0 = tid * VEC; off0 < span; off0 += 2 * WG * VEC) {
+            const int off1 = off0 + WG * VEC;
+            const int kA = k0a + off0, kB = k0a + off1;
+            const bool vecA = kA < nnz_vec;
+            const bool vecB = off1 < span && kB < nnz_vec;
+            if constexpr (VEC == 4) {
+                f32x4 vA, vB;
+                i32x4 cA, cB;
+                if (vecA) {
+                    vA = load_val4(reinterpret_cast<const float*>(vals) + kA);
+                    cA = load_idx4(a.colidx + kA);
+                }
+                if (vecB) {
+                    vB = load_val4(reinterpret_cast<const float*>(vals) + kB);
+                    cB = load_idx4(a.colidx + kB);
+                }
+                if (vecA) {
+                    *reinterpret_cast<f32x4*>(vals_l + off0) = vA;
+                    *reinterpret_cast<i32x4*>(cols_l + off0) = cA;
+                }
+                if (vecB) {
+                    *reinterpret_cast<f32x4*>(vals_l + off1) = vB;
+                    *reinterpret_cast<i32x4*>(cols_l + off1) = cB;
+                }
+            } else {
+                u32x4 vA, vB;
+                i32x4 cA, cA2, cB, cB2;
+                if (vecA) {
+                    vA = load_val8(reinterpret_cast<const uint16_t*>(vals) + kA);
+                    cA = load_idx4(a.colidx + kA);
+                    cA2 = load_idx4(a.colidx + kA + 4);
+                }
+                if (vecB) {
+                    vB = load_val8(reinterpret_cast<const uint16_t*>(vals) + kB);
+                    cB = load_idx4(a.colidx + kB);
+                    cB2 = load_idx4(a.colidx + kB + 4);
+                }
+                if (vecA) {
+                    *reinterpret_cast<u32x4*>(vals_l + off0) = vA;
+                    *reinterpret_cast<i32x4*>(cols_l + off0) = cA;
+                    *reinterpret_cast<i32x4*>(cols_l + off0 + 4) = cA2;
+                }
+                if (vecB) {
+                    *reinterpret_cast<u32x4*>(vals_l + off1) = vB;
+                    *reinterpret_cast<i32x4*>(cols_l + off1) = cB;
+                    *reinterpret_cast<i32x4*>(cols_l + off1 + 4) = cB2;
+                }
+            }
+            // the last few entries of the array that no whole vector covers
+            if (!vecA)
+                for (int i = 0; i < VEC; ++i)
+                    if (kA + i < a.nnz) {
+                        vals_l[off0 + i] = vals[kA + i];
+                        cols_l[off0 + i] = a.colidx[kA + i];
+                    }
+            if (!vecB && off1 < span)
+                for (int i = 0; i < VEC; ++i)
+                    if (kB + i < a.nnz) {
+                        vals_l[off1 + i] = vals[kB + i];
+                        cols_l[off1 + i] = a.colidx[kB + i];
+                    }
+        }
+    } else {
+        for (int off = (k0 - k0a) + tid; off < span; off += WG) {
+            vals_l[off] = vals[k0a + off];
+            cols_l[off] = a.colidx[k0a + off];
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. rows
+    const RowOut o{a.y, a.carry_row, a.carry_val, a.alpha, a.beta, reinterpret_cast<const float*>(smem_raw), 0, a.team_bias};  // no staged y
+    tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
 }
 
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
@@ -449,6 +600,7 @@ TileArgs tile_args(const MatrixView& A, const void* x, float* y, Scalars s) {
     a.x = x;
     a.y = y;
     a.m = A.m;
+    a.n = A.n;
     a.nnz = A.nnz;
     a.alpha = s.alpha;
     a.beta = s.beta;
@@ -471,20 +623,68 @@ hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, in
                   : launch_vector_t<F32>(A, lanes, rows, count, x, y, s, st);
 }
 
-hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, int32_t nb, int32_t block_nnz,
-                           int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st) {
+namespace {
+
+// LDS bytes of a tile kernel launch: staged colidx + vals for `entries` entries (plus alignment
+// slack) and `bounds` segment bounds.
+template <typename T>
+size_t tile_lds_bytes(int entries, int bounds) {
+    return (sizeof(int) + sizeof(typename T::elem)) * static_cast<size_t>(entries + 2 * T::VEC) +
+           sizeof(int) * static_cast<size_t>(bounds + 2);
+}
+
+template <typename T, bool MERGE, int WG>
+hipError_t launch_tiles_wg(const TileArgs& a, size_t lds, hipStream_t st) {
+    auto kernel = spmv_tile_kernel<T, MERGE, WG>;
+    if (lds > 64 * 1024) {
+        // beyond the default limit the kernel has to be told once (per process) how much it may get
+        static thread_local size_t allowed = 0;
+        if (lds > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return e;
+            allowed = lds;
+        }
+    }
+    hipLaunchKernelGGL(kernel, dim3(a.nparts), dim3(WG), lds, st, a);
+    return hipGetLastError();
+}
+
+// Workgroup size of the tile kernel (256 unless overridden for experiments).
+template <typename T, bool MERGE>
+hipError_t launch_tiles(const TileArgs& a, size_t lds, hipStream_t st) {
+    static const int forced_wg = [] {
+        const char* e = getenv("SPMV_TILE_WG");  // experiments only
+        return e ? atoi(e) : 0;
+    }();
+    const int wg = forced_wg ? forced_wg : 256;
+    if (wg <= 64) return launch_tiles_wg<T, MERGE, 64>(a, lds, st);
+    if (wg <= 128) return launch_tiles_wg<T, MERGE, 128>(a, lds, st);
+    return launch_tiles_wg<T, MERGE, 256>(a, lds, st);
+}
+
+int team_bias_from_env() {
+    static const int bias = [] {
+        const char* e = getenv("SPMV_TEAM_BIAS");  // experiments only
+        return e ? atoi(e) : 0;
+    }();
+    return bias;
+}
+
+}  // namespace
+
+hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+                           int32_t block_nnz, int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st) {
     if (nb <= 0) return hipSuccess;
     TileArgs a = tile_args(A, x, y, s);
     a.part_row = row_blocks;
+    a.part_nz = block_nz;
     a.nparts = nb;
     a.tile_cap = block_nnz;
-    // products (tile + alignment slack) + segment bounds (rows + 1)
-    const size_t lds = sizeof(float) * static_cast<size_t>(block_nnz + 16 + rows_max + 4);
-    if (A.bf16)
-        hipLaunchKernelGGL((spmv_tile_kernel<BF16, false>), dim3(nb), dim3(kWG), lds, st, a);
-    else
-        hipLaunchKernelGGL((spmv_tile_kernel<F32, false>), dim3(nb), dim3(kWG), lds, st, a);
-    return hipGetLastError();
+    a.team_bias = team_bias_from_env();
+    // a block stages at most block_nnz entries and has at most rows_max rows
+    if (A.bf16) return launch_tiles<BF16, false>(a, tile_lds_bytes<BF16>(block_nnz, rows_max), st);
+    return launch_tiles<F32, false>(a, tile_lds_bytes<F32>(block_nnz, rows_max), st);
 }
 
 hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
@@ -498,13 +698,14 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_
     a.carry_val = carry_val;
     a.nparts = P;
     a.tile_cap = items_per_chunk;
-    // entries + finished rows of a chunk add up to items_per_chunk; plus slack and the carry bound
-    const size_t lds = sizeof(float) * static_cast<size_t>(items_per_chunk + 24);
+    a.team_bias = team_bias_from_env();
+    // entries + finished rows of a chunk add up to at most items_per_chunk; an entry needs more
+    // LDS than a bound, so the all-entries chunk is the worst case (one bound more for the carry)
+    hipError_t e;
     if (A.bf16)
-        hipLaunchKernelGGL((spmv_tile_kernel<BF16, true>), dim3(P), dim3(kWG), lds, st, a);
+        e = launch_tiles<BF16, true>(a, tile_lds_bytes<BF16>(items_per_chunk, 2), st);
     else
-        hipLaunchKernelGGL((spmv_tile_kernel<F32, true>), dim3(P), dim3(kWG), lds, st, a);
-    hipError_t e = hipGetLastError();
+        e = launch_tiles<F32, true>(a, tile_lds_bytes<F32>(items_per_chunk, 2), st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(merge_fixup_kernel, dim3(ceil_div(P, kWG)), dim3(kWG), 0, st, carry_row, carry_val, P, y, s.alpha);
     return hipGetLastError();
@@ -525,7 +726,6 @@ hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st) {
 
 const char* scalar_kernel_name() { return "spmv_scalar_kernel"; }
 const char* vector_kernel_name() { return "spmv_vector_kernel"; }
-const char* adaptive_kernel_name() { return "spmv_tile_kernel"; }
-const char* merge_kernel_name() { return "spmv_tile_kernel"; }
+const char* tile_kernel_name() { return "spmv_tile_kernel"; }
 
 }  // namespace spmv

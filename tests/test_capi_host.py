@@ -12,6 +12,7 @@ import paper_2603_07169_amd as s
 import workloads as w
 
 ROOT = Path(__file__).resolve().parents[1]
+DEFAULT_BLOCK_NNZ, DEFAULT_ROWS_MAX, DEFAULT_ITEMS_PER_CHUNK = 2040, 256, 2040   # as documented in the header
 
 
 def rowptr_of(lens):
@@ -83,9 +84,9 @@ def compare_with_oracle(rowptr, n, params):
     m, nnz = rowptr.size - 1, int(rowptr[-1])
     st, info, got = s.spmv_analyze_host(m, n, nnz, rowptr, params)
     assert st == s.SPMV_OK
-    bn = params.get("block_nnz") or 2048
-    rm = params.get("rows_max") or 256
-    ipc = params.get("items_per_chunk") or 4096
+    bn = params.get("block_nnz") or DEFAULT_BLOCK_NNZ
+    rm = params.get("rows_max") or DEFAULT_ROWS_MAX
+    ipc = params.get("items_per_chunk") or DEFAULT_ITEMS_PER_CHUNK
     stats = oracle.row_stats(rowptr)
     assert (info.m, info.n, info.nnz) == (m, n, nnz)
     assert (info.min_len, info.max_len, info.n_empty) == (stats["min_len"], stats["max_len"], stats["n_empty"])
@@ -127,7 +128,7 @@ def test_host_analysis_equals_oracle_on_full_configs(k):
     p = w.config(k, 1.0 if k in (1, 2) else 0.25)
     info = compare_with_oracle(p.rowptr, p.n, {})
     if k == 1:
-        assert info.num_row_blocks == 32 and info.plan == s.SPMV_PLAN_ADAPTIVE
+        assert info.num_row_blocks == 33 and info.plan == s.SPMV_PLAN_ADAPTIVE   # 127 rows of 16 fit under 2040
     if k == 2:
         assert info.num_row_blocks == 4096 and info.plan == s.SPMV_PLAN_ADAPTIVE
     if k == 4:

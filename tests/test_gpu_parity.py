@@ -158,15 +158,16 @@ def test_device_analysis_equals_oracle(k):
     p = w.config(k, 1.0 if k == 1 else 1 / 8)
     d = DeviceProblem(p)
     A = d.matrix()
+    assert (A.info.block_nnz, A.info.rows_max, A.info.items_per_chunk) == (2040, 256, 2040)   # documented defaults
     got = A.analysis()
     cnt, off, rows = oracle.row_bins(p.rowptr)
     assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_offset"], off)
     assert np.array_equal(got["bin_rows"], rows)
-    assert np.array_equal(got["row_blocks"], oracle.row_blocks(p.rowptr, 2048, 256))
-    mr, mz = oracle.merge_path(p.rowptr, 4096)
+    assert np.array_equal(got["row_blocks"], oracle.row_blocks(p.rowptr, A.info.block_nnz, A.info.rows_max))
+    mr, mz = oracle.merge_path(p.rowptr, A.info.items_per_chunk)
     assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
     st = oracle.row_stats(p.rowptr)
-    assert A.info.plan == oracle.plan(p.m, p.nnz, st["max_len"], 2048)
+    assert A.info.plan == oracle.plan(p.m, p.nnz, st["max_len"], A.info.block_nnz)
     assert (A.info.min_len, A.info.max_len, A.info.n_empty) == (st["min_len"], st["max_len"], st["n_empty"])
     A.close()
 
