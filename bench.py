@@ -47,7 +47,37 @@ def parse():
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (skip the other configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copies", type=int, default=0, help="override the number of rotating copies")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, used to scale "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run)")
     return ap.parse_args()
+
+
+def kernels_sha256():
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("kernels.hip", "capi.cpp", "analysis.cpp"):
+        h.update((ROOT / "paper_2603_07169_amd" / "csrc" / name).read_bytes())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload):
+    """HBM bytes per launch from the committed counter summary, or None when there is none or the
+    kernel sources have changed since it was taken."""
+    f = ROOT / "profiles" / f"traffic_{workload}.txt"
+    if not f.exists():
+        return None
+    kv = {}
+    for line in f.read_text().splitlines():
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            kv[k.strip()] = v.strip()
+    if kv.get("csrc_sha256") != kernels_sha256():
+        return None
+    try:
+        return float(kv["hbm_bytes_per_launch"])
+    except (KeyError, ValueError):
+        return None
 
 
 def dev(a):
@@ -175,10 +205,16 @@ def main():
                    "storage": p.dtype, "plan": head["plan"], "cache_state": f"cold: rotating over {head['copies_rotated']} disjoint copies"},
         "gflops": head["GFLOPs"], "warm_GBps": head["warm_GBps"],
         "roofline": {"bound": "hbm", "achieved": head["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": head["hbm_frac"], "traffic": None, "kernel": head["kernel"],
+                     "frac": head["hbm_frac"], "traffic": recorded_traffic(head["workload"]), "kernel": head["kernel"],
                      "algorithmic_bytes_per_launch": head["algorithmic_bytes"],
                      "avg_launch_ms": head["ms_per_step"]},
     }
+    if args.calibration_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(p)
     del p

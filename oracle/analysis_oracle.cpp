@@ -126,12 +126,13 @@ int32_t oracle_plan(int64_t m, int64_t nnz, int64_t max_len, int32_t block_nnz) 
 }
 
 // Lanes per row of the vector plan: the smallest power of two G in [2, 64] with
-// 4*G >= ceil(nnz / m)  (every lane then takes about four entries); 64 when none is.
+// 8*G >= ceil(nnz / m)  (every lane then takes about eight entries, one 128-bit load of bf16
+// values); 64 when none is.
 int32_t oracle_vector_lanes(int64_t m, int64_t nnz) {
     if (m == 0) return 2;
     const int64_t mean_up = (nnz + m - 1) / m;
     int32_t G = 2;
-    while (G < 64 && 4 * static_cast<int64_t>(G) < mean_up) G *= 2;
+    while (G < 64 && 8 * static_cast<int64_t>(G) < mean_up) G *= 2;
     return G;
 }
 

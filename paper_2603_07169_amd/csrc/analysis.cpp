@@ -126,7 +126,7 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
         lanes = 2;
         if (m > 0) {
             const int64_t mean_up = (nnz + m - 1) / m;
-            while (lanes < 64 && 4 * static_cast<int64_t>(lanes) < mean_up) lanes <<= 1;
+            while (lanes < 64 && 8 * static_cast<int64_t>(lanes) < mean_up) lanes <<= 1;
         }
     }
 

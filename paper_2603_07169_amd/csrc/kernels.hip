@@ -112,7 +112,7 @@ __device__ __forceinline__ u32x4 load_val8(const uint16_t* p) {
 // Products of VEC consecutive entries starting at k (k multiple of VEC, k + VEC <= nnz, arrays
 // 16-byte aligned).
 __device__ __forceinline__ void products_vec(const int32_t* colidx, const float* vals, const float* x, int k,
-                                             float (&p)[4]) {
+                                             float (&p)[4], int /*n*/, bool /*x_group_ok*/) {
     const f32x4 v = load_val4(vals + k);
     const i32x4 c = load_idx4(colidx + k);
     p[0] = v[0] * x[c[0]];
@@ -120,17 +120,42 @@ __device__ __forceinline__ void products_vec(const int32_t* colidx, const float*
     p[2] = v[2] * x[c[2]];
     p[3] = v[3] * x[c[3]];
 }
+// bf16: the eight x operands often sit together (a run of consecutive columns).  One aligned
+// 16-byte load fetches the 8-column group around the first column; columns inside that group
+// are served from registers, the others are gathered one by one, and a gather instruction is
+// skipped altogether when no lane of the wavefront needs it.  x_group_ok: x is 16-byte aligned.
 __device__ __forceinline__ void products_vec(const int32_t* colidx, const uint16_t* vals, const uint16_t* x, int k,
-                                             float (&p)[8]) {
+                                             float (&p)[8], int n, bool x_group_ok) {
     const u32x4 v = load_val8(vals + k);
     const i32x4 c0 = load_idx4(colidx + k);
     const i32x4 c1 = load_idx4(colidx + k + 4);
     const int c[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+    const int g = c[0] & ~7;
+    const bool group = x_group_ok && g + 8 <= n;
+    u32x4 w = {0u, 0u, 0u, 0u};
+    if (group) w = *reinterpret_cast<const u32x4*>(x + g);
+    unsigned lone[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        lone[i] = 0;
+        if (!(group && static_cast<unsigned>(c[i] - g) < 8u)) lone[i] = x[c[i]];
+    }
+    float xs[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const unsigned d = static_cast<unsigned>(c[i] - g);
+        if (group && d < 8u) {
+            const unsigned word = (d & 4u) ? ((d & 2u) ? w[3] : w[2]) : ((d & 2u) ? w[1] : w[0]);
+            xs[i] = __uint_as_float((d & 1u) ? (word & 0xFFFF0000u) : (word << 16));
+        } else {
+            xs[i] = __uint_as_float(lone[i] << 16);
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         // little-endian: the low half of dword i is entry 2i, the high half entry 2i+1
-        p[2 * i] = __uint_as_float(v[i] << 16) * widen(x[c[2 * i]]);
-        p[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u) * widen(x[c[2 * i + 1]]);
+        p[2 * i] = __uint_as_float(v[i] << 16) * xs[2 * i];
+        p[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u) * xs[2 * i + 1];
     }
 }
 
@@ -144,7 +169,8 @@ __device__ __forceinline__ float product_one(const int32_t* colidx, const E* val
 // with 128-bit loads, and a tail (< VEC entries).
 template <typename T, int G>
 __device__ __forceinline__ float team_dot(const int32_t* colidx, const typename T::elem* vals,
-                                          const typename T::elem* x, int k0, int k1, int lane, bool vec_ok) {
+                                          const typename T::elem* x, int k0, int k1, int lane, bool vec_ok, int n,
+                                          bool x_group_ok) {
     constexpr int VEC = T::VEC;
     float acc = 0.f;
     if constexpr (G >= 16) {
@@ -154,7 +180,7 @@ __device__ __forceinline__ float team_dot(const int32_t* colidx, const typename 
             const int nvec = (k1 - ka) / VEC;
             for (int v = lane; v < nvec; v += G) {
                 float p[VEC];
-                products_vec(colidx, vals, x, ka + v * VEC, p);
+                products_vec(colidx, vals, x, ka + v * VEC, p, n, x_group_ok);
 #pragma unroll
                 for (int i = 0; i < VEC; ++i) acc += p[i];
             }
@@ -196,7 +222,7 @@ __global__ __launch_bounds__(kWG) void spmv_vector_kernel(const int32_t* __restr
                                                           const typename T::elem* __restrict__ vals,
                                                           const typename T::elem* __restrict__ x, float* y,
                                                           const int32_t* __restrict__ rows, int count, float alpha,
-                                                          float beta, int vec_ok) {
+                                                          float beta, int vec_ok, int n, int x_group_ok) {
     const int team = static_cast<int>((static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x) / G);
     const int lane = threadIdx.x % G;
     const bool live = team < count;
@@ -206,7 +232,7 @@ __global__ __launch_bounds__(kWG) void spmv_vector_kernel(const int32_t* __restr
         k0 = rowptr[r];
         k1 = rowptr[r + 1];
     }
-    float acc = team_dot<T, G>(colidx, vals, x, k0, k1, lane, vec_ok != 0);
+    float acc = team_dot<T, G>(colidx, vals, x, k0, k1, lane, vec_ok != 0, n, x_group_ok != 0);
     acc = group_sum<G>(acc);  // every lane of the wave takes part, also those without a row
     if (live && lane == 0) y[r] = epilogue(acc, alpha, beta, y, r);
 }
@@ -234,7 +260,7 @@ template <typename T, int WG>
 __device__ __forceinline__ void long_row(const TileArgs& a, int r, int k0, int k1, float* wave_part, int tid) {
     using E = typename T::elem;
     float acc = team_dot<T, WG>(a.colidx, static_cast<const E*>(a.vals), static_cast<const E*>(a.x), k0, k1, tid,
-                                 a.vec_ok != 0);
+                                a.vec_ok != 0, a.n, reinterpret_cast<uintptr_t>(a.x) % 16 == 0);
     acc = group_sum<64>(acc);
     if ((tid & 63) == 0) wave_part[tid >> 6] = acc;
     __syncthreads();
@@ -245,56 +271,49 @@ __device__ __forceinline__ void long_row(const TileArgs& a, int r, int k0, int k
     }
 }
 
-// Partial dot product of the staged entries [b, e) of one segment, taken by lane `tl` of a team
-// of G lanes: entry j of the segment goes to lane j mod G.  Neighbouring teams work on
-// neighbouring rows, so for banded or stencil-like rows the lanes of a gather instruction fall
-// into a handful of cache lines.
-// A dependent gather costs a full trip through the memory pipeline even when it hits in cache,
-// so the gathers of a lane are issued in one batch before any is used; the batch size is the
-// smallest of a few fixed sizes that covers what the lane has left, because gather
-// instructions issued for nothing still take their turn in the address unit.
-template <int B, typename E>
-__device__ __forceinline__ float gather_batch(const int* cols, const E* vals, const E* x, int j0, int e, int G) {
-    // three waves of independent accesses, each issued back to back: column indices from LDS,
-    // x from memory, matrix values from LDS
-    int jj[B];
-    int c[B];
+// B entries of one segment for one lane of a team of G lanes: staged slots j, j+G, .., j+(B-1)G.
+// Three bursts of independent accesses, each issued back to back: column indices out of LDS,
+// x out of memory, matrix values out of LDS.  G and B are compile-time so that every LDS
+// access is the lane's base address plus an immediate offset, and nothing is predicated:
+// the row phase is bound by instruction issue, so instructions per entry are what counts.
+template <int B, int G, typename E>
+__device__ __forceinline__ float gather_batch(const int* cols, const E* vals, const E* x, int j) {
+    unsigned c[B];
     E xv[B];
     E av[B];
 #pragma unroll
-    for (int u = 0; u < B; ++u) {
-        const int j = j0 + u * G;
-        jj[u] = j < e ? j : j0;  // a lane with nothing left re-reads its first entry and drops it
-    }
-#pragma unroll
-    for (int u = 0; u < B; ++u) c[u] = cols[jj[u]];
+    for (int u = 0; u < B; ++u) c[u] = static_cast<unsigned>(cols[j + u * G]);
 #pragma unroll
     for (int u = 0; u < B; ++u) xv[u] = x[c[u]];
 #pragma unroll
-    for (int u = 0; u < B; ++u) av[u] = vals[jj[u]];
+    for (int u = 0; u < B; ++u) av[u] = vals[j + u * G];
     float acc = 0.f;
 #pragma unroll
-    for (int u = 0; u < B; ++u) acc += (j0 + u * G < e) ? widen(av[u]) * widen(xv[u]) : 0.f;
+    for (int u = 0; u < B; ++u) acc += widen(av[u]) * widen(xv[u]);
     return acc;
 }
 
-template <typename E>
-__device__ __forceinline__ float segment_dot(const int* cols, const E* vals, const E* x, int b, int e, int tl, int G) {
+// Partial dot product of the staged entries [b, e) of one segment, taken by lane `tl` of a team
+// of G lanes: entry j of the segment goes to lane j mod G.  Neighbouring teams work on
+// neighbouring rows, so for banded or stencil-like rows the lanes of a gather instruction fall
+// into a handful of cache lines.  The lane's entries are taken in batches of 8, then 4, 2, 1.
+template <int G, typename E>
+__device__ __forceinline__ float segment_dot(const int* cols, const E* vals, const E* x, int b, int e, int tl) {
     float acc = 0.f;
-    int j0 = b + tl;
-    while (j0 < e) {
-        const int left = (e - j0 + G - 1) / G;  // entries this lane still has to take
-        if (left > 8) {
-            acc += gather_batch<16>(cols, vals, x, j0, e, G);
-            j0 += 16 * G;
-        } else if (left > 4) {
-            acc += gather_batch<8>(cols, vals, x, j0, e, G);
-            j0 += 8 * G;
-        } else {
-            acc += gather_batch<4>(cols, vals, x, j0, e, G);
-            j0 += 4 * G;
-        }
+    int j = b + tl;
+    int cnt = (e - j + G - 1) / G;  // entries this lane takes (<= 0 when the segment is shorter than the team)
+    for (; cnt >= 8; cnt -= 8, j += 8 * G) acc += gather_batch<8, G>(cols, vals, x, j);
+    if (cnt >= 4) {
+        acc += gather_batch<4, G>(cols, vals, x, j);
+        j += 4 * G;
+        cnt -= 4;
     }
+    if (cnt >= 2) {
+        acc += gather_batch<2, G>(cols, vals, x, j);
+        j += 2 * G;
+        cnt -= 2;
+    }
+    if (cnt >= 1) acc += gather_batch<1, G>(cols, vals, x, j);
     return acc;
 }
 
@@ -304,50 +323,27 @@ struct RowOut {
     int32_t* carry_row;
     float* carry_val;
     float alpha, beta;
-    const float* y0_lds;  // old y of the tile's first y0_count rows, staged in LDS
-    int y0_count;
-    int team_bias;
 };
 
 // Row phase of a tile whose entries sit in LDS (cols[], vals[]); seg[i] .. seg[i+1] bounds the
 // slots of segment i.  Segments 0 .. nr-1 are the rows r0 .. r0+nr-1 and go to y.  With MERGE
 // there is one more segment, the piece of row r0+nr that the chunk cuts off: its sum is the
-// chunk's carry (no carry when it is empty).  Teams of G lanes (G from the mean segment
-// length) take one segment each; segments far longer than the mean are set aside and taken by
-// whole wavefronts afterwards.  Entered by the whole workgroup with *n_deferred == 0; contains
-// one barrier.
-template <bool MERGE, int WG, typename E>
-__device__ __forceinline__ void tile_rows(const int* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
-                                          int part, int tile_nnz, const RowOut& o, int* deferred, int* n_deferred,
-                                          int tid) {
+// chunk's carry (no carry when it is empty).  Teams of G lanes take one segment each;
+// segments longer than defer_len are set aside and taken by whole wavefronts afterwards.
+// Entered by the whole workgroup with *n_deferred == 0; contains one barrier.
+template <bool MERGE, int WG, int G, typename E>
+__device__ __forceinline__ void tile_rows_g(const int* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
+                                            int part, const RowOut& o, int* deferred, int* n_deferred, int tid) {
     const int nseg = nr + (MERGE ? 1 : 0);
-    int G = 1;
-    {
-        const int mean = nseg > 0 ? tile_nnz / nseg : 0;
-        while (G < 64 && 16 * G < mean) G <<= 1;
-        if (o.team_bias > 0) G = (G << o.team_bias) > 64 ? 64 : (G << o.team_bias);
-        if (o.team_bias < 0) G = (G >> -o.team_bias) < 1 ? 1 : (G >> -o.team_bias);
-    }
-    const int defer_len = 32 * G > 64 ? 32 * G : 64;
-    const int teams = WG / G;
+    constexpr int defer_len = 32 * G > 64 ? 32 * G : 64;
+    constexpr int teams = WG / G;
     const int team = tid / G;
-    const int tl = tid & (G - 1);
+    const int tl = tid % G;
 
     auto emit = [&](int i, float s, int len) {
         if (i < nr) {
             const int r = r0 + i;
-            if (o.beta == 0.f) {
-                o.y[r] = o.alpha * s;
-            } else {
-                // A staged copy of the old y spares a global load this late in the tile, which
-                // would have to queue behind everything the workgroup has in flight.
-                float y_old;
-                if (i < o.y0_count)
-                    y_old = o.y0_lds[i];
-                else
-                    y_old = o.y[r];
-                o.y[r] = o.alpha * s + o.beta * y_old;
-            }
+            o.y[r] = epilogue(s, o.alpha, o.beta, o.y, r);
         } else {
             o.carry_row[part] = len > 0 ? r0 + nr : -1;
             o.carry_val[part] = s;
@@ -364,12 +360,12 @@ __device__ __forceinline__ void tile_rows(const int* cols, const E* vals, const 
             len = e - b;
             if (len <= defer_len) {
                 mine = true;
-                acc = segment_dot(cols, vals, x, b, e, tl, G);
+                acc = segment_dot<G>(cols, vals, x, b, e, tl);
             } else if (tl == 0) {
                 deferred[atomicAdd(n_deferred, 1)] = i;
             }
         }
-        acc = group_sum_rt(acc, G);  // every lane takes part
+        acc = group_sum<G>(acc);  // every lane takes part
         if (mine && tl == 0) emit(i, acc, len);
     }
     __syncthreads();
@@ -379,9 +375,33 @@ __device__ __forceinline__ void tile_rows(const int* cols, const E* vals, const 
     for (int d = tid >> 6; d < nd; d += WG / 64) {
         const int i = deferred[d];
         const int b = seg[i], e = seg[i + 1];
-        float acc = segment_dot(cols, vals, x, b, e, lane, 64);
+        float acc = segment_dot<64>(cols, vals, x, b, e, lane);
         acc = group_sum<64>(acc);
         if (lane == 0) emit(i, acc, e - b);
+    }
+}
+
+// Lanes per row from the tile's mean segment length: the largest power of two G <= 64 with
+// 16*G <= mean + 15, shifted by team_bias.  Small teams keep the lanes of a gather on
+// neighbouring rows, which is what makes the gathers of banded matrices coalesce.
+template <bool MERGE, int WG, typename E>
+__device__ __forceinline__ void tile_rows(const int* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
+                                          int part, int tile_nnz, int team_bias, const RowOut& o, int* deferred,
+                                          int* n_deferred, int tid) {
+    const int nseg = nr + (MERGE ? 1 : 0);
+    int G = 1;
+    const int mean = nseg > 0 ? tile_nnz / nseg : 0;
+    while (G < 64 && 16 * G < mean) G <<= 1;
+    if (team_bias > 0) G = (G << team_bias) > 64 ? 64 : (G << team_bias);
+    if (team_bias < 0) G = (G >> -team_bias) < 1 ? 1 : (G >> -team_bias);
+    switch (G) {
+        case 1: tile_rows_g<MERGE, WG, 1>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
+        case 2: tile_rows_g<MERGE, WG, 2>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
+        case 4: tile_rows_g<MERGE, WG, 4>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
+        case 8: tile_rows_g<MERGE, WG, 8>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
+        case 16: tile_rows_g<MERGE, WG, 16>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
+        case 32: tile_rows_g<MERGE, WG, 32>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
+        default: tile_rows_g<MERGE, WG, 64>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
     }
 }
 
@@ -513,8 +533,8 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
     __syncthreads();
 
     // ---- 2. rows
-    const RowOut o{a.y, a.carry_row, a.carry_val, a.alpha, a.beta, reinterpret_cast<const float*>(smem_raw), 0, a.team_bias};  // no staged y
-    tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
+    const RowOut o{a.y, a.carry_row, a.carry_val, a.alpha, a.beta};
+    tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
 }
 
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
@@ -574,7 +594,7 @@ hipError_t launch_vector_tg(const MatrixView& A, const int32_t* rows, int32_t co
     const int grid = ceil_div(static_cast<int64_t>(count) * G, kWG);
     hipLaunchKernelGGL((spmv_vector_kernel<T, G>), dim3(grid), dim3(kWG), 0, st, A.rowptr, A.colidx,
                        static_cast<const E*>(A.vals), static_cast<const E*>(x), y, rows, count, s.alpha, s.beta,
-                       A.vec_ok ? 1 : 0);
+                       A.vec_ok ? 1 : 0, A.n, reinterpret_cast<uintptr_t>(x) % 16 == 0 ? 1 : 0);
     return hipGetLastError();
 }
 

@@ -159,5 +159,5 @@ def test_plan_rule():
     assert oracle.plan(10, 100, 2048, 2048) == 4
     assert oracle.plan(10, 5000, 2049, 2048) == 5
     assert [oracle.vector_lanes(1, k) for k in (1, 8, 9, 16, 17, 27, 128, 129, 255, 257, 100000)] == \
-        [2, 2, 4, 4, 8, 8, 32, 64, 64, 64, 64]
+        [2, 2, 2, 2, 4, 4, 16, 32, 32, 64, 64]
     assert oracle.vector_lanes(0, 0) == 2
