@@ -63,9 +63,9 @@ typedef enum {
 /* Analysis parameters.  Zero in any field selects that field's default. */
 typedef struct {
     int32_t plan;             /* spmv_plan_t; default AUTO */
-    int32_t block_nnz;        /* row blocks: most stored entries per block; default 2040, 1..8192 */
-    int32_t rows_max;         /* row blocks: most rows per block;           default 256,  1..1024 */
-    int32_t items_per_chunk;  /* merge path: steps (row ends + entries) per chunk; default 2040, 1..8192 */
+    int32_t block_nnz;        /* row blocks: most stored entries per block, 1..8192; default: see analyze */
+    int32_t rows_max;         /* row blocks: most rows per block, 1..1024;           default: see analyze */
+    int32_t items_per_chunk;  /* merge path: steps (row ends + entries) per chunk; default 2048, 1..8192 */
     int32_t vector_lanes;     /* VECTOR plan: lanes per row, power of two 2..64; default: chosen from nnz/m */
     int32_t skip_validation;  /* nonzero: do not scan colidx for out-of-range columns in analyze */
     int32_t reserved[2];      /* must be zero */
@@ -108,7 +108,11 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *   - row statistics; bin(len) = 0 for len 0, else the smallest b >= 1 with 2^(b-1) >= len;
  *     bin_rows = stable grouping of row ids by bin;
  *   - row blocks: greedy left-to-right, a block takes the next row while it has < rows_max
- *     rows and the row keeps it at <= block_nnz entries; a longer row stands alone;
+ *     rows and the row keeps it at <= block_nnz entries; a longer row stands alone.
+ *     Defaults (a field left 0): with mean = ceil(nnz/m) and G the largest power of two <= 64
+ *     with 16*G <= mean + 15, rows_max = 256/G and block_nnz = rows_max*mean rounded up to a
+ *     multiple of 8 and clamped to [2048, 8192]; matrices of at most 2^20 entries get
+ *     rows_max = 64, block_nnz = 1024;
  *   - merge-path splits: the path over (row ends, entry positions) cut every items_per_chunk
  *     steps;
  *   - the plan: params->plan if not AUTO, else SCALAR when m == 0 or nnz == 0, MERGE when

@@ -53,6 +53,8 @@ def _load():
         _lib.oracle_row_blocks.restype = i64
         _lib.oracle_merge_path.argtypes = [i64, i64, vp, i32, vp, vp]
         _lib.oracle_merge_path.restype = i64
+        _lib.oracle_tile_shape.argtypes = [i64, i64, vp, vp]
+        _lib.oracle_tile_shape.restype = None
         _lib.oracle_plan.argtypes = [i64, i64, i64, i32]
         _lib.oracle_plan.restype = i32
         _lib.oracle_vector_lanes.argtypes = [i64, i64]
@@ -138,6 +140,13 @@ def merge_path(rowptr, ipc):
     P2 = lib.oracle_merge_path(m, nnz, _p(_chk(rowptr, np.int32)), ipc, _p(mp_row), _p(mp_nz))
     assert P2 == P
     return mp_row, mp_nz
+
+
+def tile_shape(m, nnz):
+    """Default (block_nnz, rows_max) for a matrix of m rows and nnz entries."""
+    out = np.zeros(2, dtype=np.int32)
+    _load().oracle_tile_shape(m, nnz, out[0:1].ctypes.data_as(C.c_void_p), out[1:2].ctypes.data_as(C.c_void_p))
+    return int(out[0]), int(out[1])
 
 
 def plan(m, nnz, max_len, block_nnz):

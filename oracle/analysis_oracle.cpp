@@ -112,6 +112,30 @@ int64_t oracle_merge_path(int64_t m, int64_t nnz, const int32_t* rowptr, int32_t
     return P;
 }
 
+// ---- default row-block shape ---------------------------------------------------------
+// Used when the caller leaves block_nnz / rows_max at 0.  Matrices of at most 2^20 entries
+// (or no rows): 1024 entries, 64 rows.  Otherwise, with mean = ceil(nnz / m) and G the
+// largest power of two <= 64 such that 16*G <= mean + 15 (G doubles while 16*G < mean):
+// rows_max = 256 / G, block_nnz = rows_max * mean rounded up to a multiple of 8, then
+// clamped to [2048, 8192].
+void oracle_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* rows_max) {
+    if (m <= 0 || nnz <= 1048576) {
+        *block_nnz = 1024;
+        *rows_max = 64;
+        return;
+    }
+    const int64_t mean = (nnz + m - 1) / m;
+    int64_t G = 1;
+    while (G < 64 && 16 * G < mean) G *= 2;
+    const int64_t rows = 256 / G;
+    int64_t entries = rows * mean;
+    while (entries % 8 != 0) ++entries;
+    if (entries < 2048) entries = 2048;
+    if (entries > 8192) entries = 8192;
+    *block_nnz = static_cast<int32_t>(entries);
+    *rows_max = static_cast<int32_t>(rows);
+}
+
 // ---- plan -------------------------------------------------------------------------
 // Plans: 1 scalar (one lane per row), 2 vector (a group of lanes per row), 3 binned
 // (scalar/vector per length bin), 4 adaptive (row blocks through LDS), 5 merge (merge-path

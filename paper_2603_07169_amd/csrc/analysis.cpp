@@ -39,11 +39,9 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
     if (in) p = *in;
     if (p.reserved[0] != 0 || p.reserved[1] != 0) return SPMV_ERR_INVALID_ARG;
     if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_MERGE) return SPMV_ERR_INVALID_ARG;
-    if (p.block_nnz == 0) p.block_nnz = kDefaultBlockNnz;
-    if (p.rows_max == 0) p.rows_max = kDefaultRowsMax;
     if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
-    if (p.block_nnz < 1 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
-    if (p.rows_max < 1 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;
+    if (p.block_nnz < 0 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
+    if (p.rows_max < 0 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;
     if (p.items_per_chunk < 1 || p.items_per_chunk > kMaxItemsPerChunk) return SPMV_ERR_INVALID_ARG;
     if (p.vector_lanes != 0 && (!is_pow2(p.vector_lanes) || p.vector_lanes < 2 || p.vector_lanes > 64))
         return SPMV_ERR_INVALID_ARG;
@@ -51,10 +49,37 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
     return SPMV_OK;
 }
 
+// The tile kernel gives a row to a team of G lanes, G = the largest power of two with
+// 16*G <= mean row length + 15, and runs 256 lanes: a block of 256/G rows keeps every lane busy.
+// The entry limit is set so that the row limit is the one that binds on a regular matrix.
+// Small matrices get small blocks so that there are enough of them to spread over the chip.
+void default_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* rows_max) {
+    if (m <= 0 || nnz <= (int64_t{1} << 20)) {
+        *block_nnz = 1024;
+        *rows_max = 64;
+        return;
+    }
+    const int64_t mean_up = (nnz + m - 1) / m;
+    int lanes = 1;
+    while (lanes < 64 && 16 * static_cast<int64_t>(lanes) < mean_up) lanes <<= 1;
+    const int rows = 256 / lanes;
+    int64_t entries = (rows * mean_up + 7) & ~int64_t{7};
+    entries = std::max<int64_t>(2048, std::min<int64_t>(entries, kMaxBlockNnz));
+    *block_nnz = static_cast<int32_t>(entries);
+    *rows_max = rows;
+}
+
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
-                             const spmv_analyze_params_t& params, Analysis* out) try {
+                             const spmv_analyze_params_t& params_in, Analysis* out) try {
     Analysis& a = *out;
     a = Analysis{};
+    spmv_analyze_params_t params = params_in;
+    {
+        int32_t bn = 0, rm = 0;
+        default_tile_shape(m, nnz, &bn, &rm);
+        if (params.block_nnz == 0) params.block_nnz = bn;
+        if (params.rows_max == 0) params.rows_max = rm;
+    }
 
     // ---- structure check + statistics + bin histogram, one sweep
     if (rowptr[0] != 0 || rowptr[m] != nnz) return SPMV_ERR_BAD_STRUCTURE;

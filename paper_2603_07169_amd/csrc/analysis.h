@@ -8,11 +8,7 @@
 
 namespace spmv {
 
-// 2040 + (vector width - 1) stays inside 2048 slots: a default tile is at most two 128-bit
-// vectors per lane of a 256-lane workgroup in FP32 and one in bf16.
-constexpr int kDefaultBlockNnz = 2040;
-constexpr int kDefaultRowsMax = 256;
-constexpr int kDefaultItemsPerChunk = 2040;
+constexpr int kDefaultItemsPerChunk = 2048;
 constexpr int kMaxBlockNnz = 8192;
 constexpr int kMaxRowsMax = 1024;
 constexpr int kMaxItemsPerChunk = 8192;
@@ -27,8 +23,13 @@ struct Analysis {
     std::vector<int32_t> mp_nz;       // [P+1]
 };
 
-// Fills in defaults and range-checks the parameters.  Returns SPMV_OK or SPMV_ERR_INVALID_ARG.
+// Range-checks the parameters and fills in the defaults that do not depend on the matrix
+// (block_nnz / rows_max left at 0 are resolved by analyze_rowptr from the mean row length).
+// Returns SPMV_OK or SPMV_ERR_INVALID_ARG.
 spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_params_t* out);
+
+// Row-block shape for a matrix of m rows and nnz entries when the caller gives none.
+void default_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* rows_max);
 
 // rowptr is a HOST array of m+1 entries.  Returns SPMV_OK, SPMV_ERR_BAD_STRUCTURE or SPMV_ERR_ALLOC.
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,

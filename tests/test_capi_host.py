@@ -12,7 +12,7 @@ import paper_2603_07169_amd as s
 import workloads as w
 
 ROOT = Path(__file__).resolve().parents[1]
-DEFAULT_BLOCK_NNZ, DEFAULT_ROWS_MAX, DEFAULT_ITEMS_PER_CHUNK = 2040, 256, 2040   # as documented in the header
+DEFAULT_ITEMS_PER_CHUNK = 2048   # as documented in the header
 
 
 def rowptr_of(lens):
@@ -84,8 +84,9 @@ def compare_with_oracle(rowptr, n, params):
     m, nnz = rowptr.size - 1, int(rowptr[-1])
     st, info, got = s.spmv_analyze_host(m, n, nnz, rowptr, params)
     assert st == s.SPMV_OK
-    bn = params.get("block_nnz") or DEFAULT_BLOCK_NNZ
-    rm = params.get("rows_max") or DEFAULT_ROWS_MAX
+    auto_bn, auto_rm = oracle.tile_shape(m, nnz)
+    bn = params.get("block_nnz") or auto_bn
+    rm = params.get("rows_max") or auto_rm
     ipc = params.get("items_per_chunk") or DEFAULT_ITEMS_PER_CHUNK
     stats = oracle.row_stats(rowptr)
     assert (info.m, info.n, info.nnz) == (m, n, nnz)
@@ -128,8 +129,10 @@ def test_host_analysis_equals_oracle_on_full_configs(k):
     p = w.config(k, 1.0 if k in (1, 2) else 0.25)
     info = compare_with_oracle(p.rowptr, p.n, {})
     if k == 1:
-        assert info.num_row_blocks == 33 and info.plan == s.SPMV_PLAN_ADAPTIVE   # 127 rows of 16 fit under 2040
+        assert (info.block_nnz, info.rows_max) == (1024, 64)               # small matrix
+        assert info.num_row_blocks == 64 and info.plan == s.SPMV_PLAN_ADAPTIVE
     if k == 2:
+        assert (info.block_nnz, info.rows_max) == (2048, 256)              # mean 5 -> one lane per row
         assert info.num_row_blocks == 4096 and info.plan == s.SPMV_PLAN_ADAPTIVE
     if k == 4:
         assert info.plan == s.SPMV_PLAN_MERGE

@@ -158,7 +158,7 @@ def test_device_analysis_equals_oracle(k):
     p = w.config(k, 1.0 if k == 1 else 1 / 8)
     d = DeviceProblem(p)
     A = d.matrix()
-    assert (A.info.block_nnz, A.info.rows_max, A.info.items_per_chunk) == (2040, 256, 2040)   # documented defaults
+    assert (A.info.block_nnz, A.info.rows_max) == oracle.tile_shape(p.m, p.nnz) and A.info.items_per_chunk == 2048
     got = A.analysis()
     cnt, off, rows = oracle.row_bins(p.rowptr)
     assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_offset"], off)

@@ -152,6 +152,20 @@ def test_merge_path_invariants_and_diagonal_search(lens, ipc):
         assert (int(r[p]), int(z[p])) == merge_split_by_definition(rp, d)
 
 
+# ------------------------------------------------------------------ default tile shape
+def test_default_tile_shape():
+    """Worked by hand from the rule: small matrices (1024, 64); else 256/G rows with G the team
+    size for the mean length, entries = rows * mean rounded up to 8, clamped to [2048, 8192]."""
+    assert oracle.tile_shape(0, 0) == (1024, 64)
+    assert oracle.tile_shape(4096, 65536) == (1024, 64)                    # <= 2^20 entries
+    assert oracle.tile_shape(1048576, 5238784) == (2048, 256)              # mean 5: G 1, 256*5 = 1280 -> 2048
+    assert oracle.tile_shape(2097152, 55742968) == (3456, 128)             # mean 27: G 2, 128*27 = 3456
+    assert oracle.tile_shape(1000000, 128000000) == (4096, 32)             # mean 128: G 8, 32*128
+    assert oracle.tile_shape(4000000, 31913584) == (2048, 256)             # mean 8: G 1
+    assert oracle.tile_shape(1000, 3000000) == (8192, 4)                   # mean 3000: G 64, 4*3000 -> 8192
+    assert oracle.tile_shape(100000, 1700000) == (2176, 128)               # mean 17: 16*1 < 17 -> G 2, 128*17 = 2176
+
+
 # ------------------------------------------------------------------ plan
 def test_plan_rule():
     assert oracle.plan(0, 0, 0, 2048) == 1
