@@ -19,7 +19,8 @@ SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp"]
 _lib = None
 
 NUM_BINS = 33
-PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge"}
+PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed"}
+MAX_X_VECTORS = 1024
 
 
 def build(force: bool = True) -> Path:
@@ -59,6 +60,10 @@ def _load():
         _lib.oracle_plan.restype = i32
         _lib.oracle_vector_lanes.argtypes = [i64, i64]
         _lib.oracle_vector_lanes.restype = i32
+        _lib.oracle_x_windows.argtypes = [i64, vp, vp, vp, i32, i32, vp, vp, vp]
+        _lib.oracle_x_windows.restype = i64
+        _lib.oracle_window_choice.argtypes = [i64, vp, i64, i32]
+        _lib.oracle_window_choice.restype = i32
     return _lib
 
 
@@ -155,3 +160,24 @@ def plan(m, nnz, max_len, block_nnz):
 
 def vector_lanes(m, nnz):
     return int(_load().oracle_vector_lanes(m, nnz))
+
+
+def x_windows(rowptr, colidx, row_blocks, block_nnz, vec_elems):
+    """(nv[nb], xv_ptr[nb+1], xv_start[sum nv], lidx[nnz]) of the row blocks' x windows."""
+    lib = _load()
+    _chk(rowptr, np.int32), _chk(colidx, np.int32), _chk(row_blocks, np.int32)
+    nb = row_blocks.size - 1
+    nv = np.zeros(max(nb, 1), dtype=np.int32)
+    args = (nb, _p(row_blocks), _p(rowptr), _p(colidx), block_nnz, vec_elems, _p(nv))
+    total = lib.oracle_x_windows(*args, None, None)
+    xv_start = np.zeros(max(total, 1), dtype=np.int32)
+    lidx = np.zeros(max(colidx.size, 1), dtype=np.uint16)
+    assert lib.oracle_x_windows(*args, _p(xv_start), _p(lidx)) == total
+    nv = nv[:nb]
+    xv_ptr = np.concatenate([[0], np.cumsum(nv, dtype=np.int64)]).astype(np.int32)
+    return nv, xv_ptr, xv_start[:total], lidx[: colidx.size]
+
+
+def window_choice(nv, nnz, max_vectors=MAX_X_VECTORS):
+    nv = np.ascontiguousarray(nv, dtype=np.int32)
+    return bool(_load().oracle_window_choice(nv.size, _p(nv), nnz, max_vectors))

@@ -10,7 +10,9 @@
 // index of each row", length rows+1).  The partitions themselves are this project's
 // definitions; they are spelled out in the function comments below.
 
+#include <algorithm>
 #include <cstdint>
+#include <vector>
 
 extern "C" {
 
@@ -158,6 +160,61 @@ int32_t oracle_vector_lanes(int64_t m, int64_t nnz) {
     int32_t G = 2;
     while (G < 64 && 8 * static_cast<int64_t>(G) < mean_up) G *= 2;
     return G;
+}
+
+// ---- x windows of row blocks --------------------------------------------------------
+// A row block touches x only at its entries' columns.  Cut x into aligned vectors of
+// `vec_elems` elements (16 bytes: 4 binary32 or 8 bf16 values).  For block b,
+//   keys_b      = the distinct values of colidx[k] / vec_elems over the block's entries,
+//                 in ascending order;
+//   nv[b]       = how many there are;
+//   xv_start    = all blocks' key lists one after the other, each key times vec_elems
+//                 (the index of the vector's first element);
+//   lidx[k]     = rank(colidx[k] / vec_elems in keys_b) * vec_elems + colidx[k] % vec_elems,
+//                 the position of x[colidx[k]] once the block's vectors are laid out back to
+//                 back in that order.
+// A block with more than block_nnz entries (a single long row) takes no vectors and its
+// lidx entries are 0.  xv_start and lidx may be null (count only).  Returns sum of nv.
+int64_t oracle_x_windows(int64_t nb, const int32_t* row_blocks, const int32_t* rowptr, const int32_t* colidx,
+                         int32_t block_nnz, int32_t vec_elems, int32_t* nv, int32_t* xv_start, uint16_t* lidx) {
+    int64_t total = 0;
+    for (int64_t b = 0; b < nb; ++b) {
+        const int64_t k0 = rowptr[row_blocks[b]], k1 = rowptr[row_blocks[b + 1]];
+        if (k1 - k0 > block_nnz) {
+            nv[b] = 0;
+            if (lidx)
+                for (int64_t k = k0; k < k1; ++k) lidx[k] = 0;
+            continue;
+        }
+        std::vector<int32_t> keys;
+        for (int64_t k = k0; k < k1; ++k) keys.push_back(colidx[k] / vec_elems);
+        std::sort(keys.begin(), keys.end());
+        keys.erase(std::unique(keys.begin(), keys.end()), keys.end());
+        nv[b] = static_cast<int32_t>(keys.size());
+        if (xv_start)
+            for (size_t j = 0; j < keys.size(); ++j) xv_start[total + static_cast<int64_t>(j)] = keys[j] * vec_elems;
+        if (lidx)
+            for (int64_t k = k0; k < k1; ++k) {
+                const int32_t key = colidx[k] / vec_elems;
+                const int64_t rank = std::find(keys.begin(), keys.end(), key) - keys.begin();
+                lidx[k] = static_cast<uint16_t>(rank * vec_elems + colidx[k] % vec_elems);
+            }
+        total += static_cast<int64_t>(keys.size());
+    }
+    return total;
+}
+
+// Whether the automatic plan serves x from those windows: every block's vectors must fit the
+// kernel's buffer (at most max_vectors) and, summed over the matrix, a fetched vector must
+// serve at least four entries.
+int32_t oracle_window_choice(int64_t nb, const int32_t* nv, int64_t nnz, int32_t max_vectors) {
+    if (nnz == 0) return 0;
+    int64_t total = 0;
+    for (int64_t b = 0; b < nb; ++b) {
+        if (nv[b] > max_vectors) return 0;
+        total += nv[b];
+    }
+    return 4 * total <= nnz ? 1 : 0;
 }
 
 }  // extern "C"

@@ -175,3 +175,70 @@ def test_plan_rule():
     assert [oracle.vector_lanes(1, k) for k in (1, 8, 9, 16, 17, 27, 128, 129, 255, 257, 100000)] == \
         [2, 2, 2, 2, 4, 4, 16, 32, 32, 64, 64]
     assert oracle.vector_lanes(0, 0) == 2
+
+
+# ---- x windows of row blocks ------------------------------------------------------------
+def test_x_windows_handworked(hand):
+    h = hand["x_windows"]
+    rp, ci = np.array(h["rowptr"], np.int32), np.array(h["colidx"], np.int32)
+    for c in h["cases"]:
+        nv, xv_ptr, xv_start, lidx = oracle.x_windows(rp, ci, np.array(c["row_blocks"], np.int32), c["block_nnz"],
+                                                      c["vec_elems"])
+        assert nv.tolist() == c["nv"]
+        assert xv_ptr.tolist() == np.concatenate([[0], np.cumsum(c["nv"])]).tolist()
+        assert xv_start.tolist() == c["xv_start"]
+        assert lidx.tolist() == c["lidx"]
+
+
+def check_x_windows(p, block_nnz, rows_max, ve):
+    """Properties that pin the window outputs without restating how they are built: laying the
+    block's vectors out back to back and indexing with lidx gives back x[colidx]; the vectors of
+    a block are aligned, distinct, ascending and all used."""
+    rb = oracle.row_blocks(p.rowptr, block_nnz, rows_max)
+    nv, xv_ptr, xv_start, lidx = oracle.x_windows(p.rowptr, p.colidx, rb, block_nnz, ve)
+    assert nv.size == rb.size - 1 and xv_ptr[-1] == xv_start.size
+    assert np.all(xv_start % ve == 0)
+    xpad = np.concatenate([np.arange(p.n, dtype=np.int64), np.full(ve, -1, np.int64)])  # x[i] = i; padding never used
+    for b in range(rb.size - 1):
+        k0, k1 = p.rowptr[rb[b]], p.rowptr[rb[b + 1]]
+        if k1 - k0 > block_nnz:
+            assert nv[b] == 0 and not lidx[k0:k1].any()
+            continue
+        starts = xv_start[xv_ptr[b]:xv_ptr[b + 1]].astype(np.int64)
+        assert np.all(np.diff(starts) > 0)
+        buf = xpad[(starts[:, None] + np.arange(ve)[None, :]).ravel()] if starts.size else np.zeros(0, np.int64)
+        li = lidx[k0:k1].astype(np.int64)
+        assert np.array_equal(buf[li], p.colidx[k0:k1])
+        assert np.array_equal(np.unique(li // ve), np.arange(nv[b]))  # no vector without an entry
+    return nv
+
+
+@pytest.mark.parametrize("ve", [4, 8])
+def test_x_windows_properties(ve):
+    import workloads as w
+    cases = [(w.laplace2d(40), 256, 64), (w.stencil27(9), 512, 32), (w.uniform_rows(300, 300, 16), 128, 16),
+             (w.powerlaw(2000), 64, 64), (w.block_clustered(500, blocks_per_row=16, width=8), 1024, 8)]
+    cases += [(p, 8, 4) for p in w.tiny_adversarial()] + [(p, 8192, 1024) for p in w.tiny_adversarial()]
+    for p, bn, rm in cases:
+        check_x_windows(p, bn, rm, ve)
+
+
+def test_x_windows_closed_form_counts():
+    """5-point stencil on a g x g grid, blocks of whole grid lines: an interior block of L lines
+    touches the columns of L+2 consecutive lines, one contiguous range."""
+    import workloads as w
+    g, ve = 64, 4
+    p = w.laplace2d(g)
+    rb = np.arange(0, g * g + 1, 2 * g, dtype=np.int32)  # two grid lines per block
+    nv, _, xv_start, _ = oracle.x_windows(p.rowptr, p.colidx, rb, 1 << 20, ve)
+    assert nv[0] == 3 * g // ve and nv[-1] == 3 * g // ve
+    assert np.all(nv[1:-1] == 4 * g // ve)
+    assert xv_start[: nv[0]].tolist() == list(range(0, 3 * g, ve))
+
+
+def test_window_choice_rule():
+    assert oracle.window_choice([10, 10], 80)
+    assert not oracle.window_choice([10, 11], 80)          # fewer than four entries per vector
+    assert not oracle.window_choice([1025, 0], 1 << 20)    # a block's vectors exceed the buffer
+    assert oracle.window_choice([1024, 0], 1 << 20)
+    assert not oracle.window_choice([], 0)
