@@ -55,8 +55,12 @@ typedef enum {
     SPMV_PLAN_VECTOR = 2,   /* a power-of-two group of lanes (2..64) per row, cross-lane reduce */
     SPMV_PLAN_BINNED = 3,   /* rows grouped by length bin; scalar or vector kernel per bin      */
     SPMV_PLAN_ADAPTIVE = 4, /* contiguous row blocks streamed through LDS (CSR-Adaptive)        */
-    SPMV_PLAN_MERGE = 5     /* equal-work merge-path chunks + carry fix-up                      */
+    SPMV_PLAN_MERGE = 5,    /* equal-work merge-path chunks + carry fix-up                      */
+    SPMV_PLAN_WINDOWED = 6  /* ADAPTIVE row blocks whose x values are served from a per-block
+                               window in LDS, entries addressed by 16-bit window positions      */
 } spmv_plan_t;
+
+#define SPMV_MAX_X_VECTORS 1024 /* most 16-byte x vectors in one row block's window */
 
 #define SPMV_NUM_BINS 33
 
@@ -76,10 +80,11 @@ typedef struct {
     int64_t min_len, max_len, n_empty; /* row length statistics (all 0 when m == 0) */
     int64_t num_row_blocks;            /* nb: row_blocks holds nb+1 entries */
     int64_t num_chunks;                /* P:  mp_row / mp_nz hold P+1 entries */
+    int64_t num_x_vectors;             /* WINDOWED plan: length of xv_start; 0 otherwise */
     int32_t plan;                      /* the plan run() will use (never AUTO) */
     int32_t vector_lanes;              /* lanes per row the VECTOR plan uses */
     int32_t block_nnz, rows_max, items_per_chunk; /* parameters in effect */
-    int32_t reserved;
+    int32_t max_x_vectors;             /* most x vectors of any row block (0 when the windows were not counted) */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -90,6 +95,10 @@ typedef struct {
     int32_t* row_blocks; /* [nb+1] first row of each block, then m            */
     int32_t* mp_row;     /* [P+1]  rows finished at each merge-path split     */
     int32_t* mp_nz;      /* [P+1]  entries taken at each merge-path split     */
+    /* WINDOWED plan only (skipped otherwise): */
+    int32_t* xv_ptr;     /* [nb+1] exclusive prefix of the blocks' x vector counts   */
+    int32_t* xv_start;   /* [num_x_vectors] first x element of each vector           */
+    uint16_t* lidx;      /* [nnz]  window position of every entry's x value          */
 } spmv_analysis_host_t;
 
 /* Records the matrix (paper App. C task 12: values / col_indices / row_offsets).
@@ -116,7 +125,16 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *   - merge-path splits: the path over (row ends, entry positions) cut every items_per_chunk
  *     steps;
  *   - the plan: params->plan if not AUTO, else SCALAR when m == 0 or nnz == 0, MERGE when
- *     some row is longer than block_nnz, else ADAPTIVE.
+ *     some row is longer than block_nnz, else ADAPTIVE, upgraded to WINDOWED by the x windows:
+ *   - x windows (plan AUTO that arrived at ADAPTIVE, or plan WINDOWED; built on the device from
+ *     colidx).  x is cut into aligned 16-byte vectors (4 floats / 8 bf16).  For row block b,
+ *     keys_b = the distinct colidx/VE of its entries in ascending order (VE = elements per
+ *     vector); xv_start lists keys_b*VE block after block, xv_ptr its block boundaries;
+ *     lidx[k] = rank(colidx[k]/VE in keys_b)*VE + colidx[k]%VE.  A block that is one row longer
+ *     than block_nnz has no vectors and lidx 0.  AUTO picks WINDOWED when every block has at
+ *     most SPMV_MAX_X_VECTORS vectors and 4 * num_x_vectors <= nnz; a forced WINDOWED plan
+ *     fails with UNSUPPORTED when some block has more.  The library then holds 2 bytes per
+ *     stored entry of its own (lidx) and run() no longer reads colidx.
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
  * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */
 spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params);
@@ -139,7 +157,8 @@ spmv_status_t spmv_csr_get_analysis_info(spmv_handle_t h, spmv_analysis_info_t* 
 spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t* out);
 
 /* The analysis of spmv_csr_analyze() on a HOST copy of rowptr, with HOST outputs and no device
- * involved (same definitions, same code path; the column check is skipped).  `info` is
+ * involved (same definitions, same code path; the column check is skipped, and with no colidx
+ * there are no x windows: AUTO never yields WINDOWED here and WINDOWED is INVALID_ARG).  `info` is
  * required; `out` may be NULL or have NULL members.  bin_rows needs m entries, row_blocks
  * up to m+1, mp_row/mp_nz ceil((m+nnz)/items_per_chunk)+1.
  * Errors: INVALID_ARG, UNSUPPORTED, BAD_STRUCTURE, ALLOC. */

@@ -38,7 +38,7 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
     spmv_analyze_params_t p{};
     if (in) p = *in;
     if (p.reserved[0] != 0 || p.reserved[1] != 0) return SPMV_ERR_INVALID_ARG;
-    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_MERGE) return SPMV_ERR_INVALID_ARG;
+    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_WINDOWED) return SPMV_ERR_INVALID_ARG;
     if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
     if (p.block_nnz < 0 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
     if (p.rows_max < 0 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;
@@ -171,6 +171,22 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
     return SPMV_OK;
 } catch (const std::bad_alloc&) {
     return SPMV_ERR_ALLOC;
+}
+
+}  // namespace spmv
+
+namespace spmv {
+
+bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest) {
+    int64_t sum = 0;
+    int32_t mx = 0;
+    for (int64_t b = 0; b < nb; ++b) {
+        sum += nv[b];
+        if (nv[b] > mx) mx = nv[b];
+    }
+    *total = sum;
+    *largest = mx;
+    return nnz > 0 && mx <= SPMV_MAX_X_VECTORS && 4 * sum <= nnz;
 }
 
 }  // namespace spmv

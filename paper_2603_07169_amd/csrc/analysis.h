@@ -35,4 +35,8 @@ void default_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* row
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
                              const spmv_analyze_params_t& params, Analysis* out);
 
+// Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x
+// from the windows (every block within SPMV_MAX_X_VECTORS and at least four entries per vector).
+bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest);
+
 }  // namespace spmv

@@ -45,16 +45,22 @@ struct spmv_csr_s {
     int32_t* d_mp_nz = nullptr;
     int32_t* d_carry_row = nullptr;
     float* d_carry_val = nullptr;
+    int32_t* d_xv_ptr = nullptr;  // x windows (WINDOWED plan)
+    int32_t* d_xv_start = nullptr;
+    uint16_t* d_lidx = nullptr;
 };
 
 namespace {
 
 void free_metadata(spmv_csr_s* h) {
-    void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row, h->d_mp_nz, h->d_carry_row, h->d_carry_val};
+    void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
+                    h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
     h->d_carry_val = nullptr;
+    h->d_xv_ptr = h->d_xv_start = nullptr;
+    h->d_lidx = nullptr;
     h->analyzed = false;
 }
 
@@ -78,6 +84,51 @@ spmv::MatrixView view_of(const spmv_csr_s* h) {
     A.bf16 = h->dtype == SPMV_BF16;
     A.vec_ok = h->vec_ok;
     return A;
+}
+
+// Counts the x vectors of every row block on the device, settles the plan (AUTO: ADAPTIVE or
+// WINDOWED) and, for WINDOWED, builds xv_ptr / xv_start / lidx.  Needs d_block_nz.
+spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, spmv::Analysis* a) {
+    const int64_t nb = a->info.num_row_blocks;
+    const spmv::MatrixView A = view_of(h);
+    std::vector<int32_t> nv, xv_ptr;
+    try {
+        nv.assign(static_cast<size_t>(nb > 0 ? nb : 1), 0);
+        xv_ptr.assign(static_cast<size_t>(nb) + 1, 0);
+    } catch (const std::bad_alloc&) {
+        return SPMV_ERR_ALLOC;
+    }
+    int32_t* d_nv = nullptr;
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&d_nv), sizeof(int32_t) * nv.size()))) return SPMV_ERR_ALLOC;
+    bool bad = hip_failed(spmv::launch_window_build(A, h->d_block_nz, static_cast<int32_t>(nb), a->info.block_nnz, false,
+                                                    d_nv, nullptr, nullptr, nullptr, nullptr));
+    bad = bad || (nb > 0 && hip_failed(hipMemcpy(nv.data(), d_nv, sizeof(int32_t) * static_cast<size_t>(nb),
+                                                 hipMemcpyDeviceToHost)));
+    (void)hipFree(d_nv);
+    if (bad) return SPMV_ERR_HIP;
+
+    int64_t total = 0;
+    int32_t largest = 0;
+    const bool pays = spmv::window_choice(nv.data(), nb, h->nnz, &total, &largest);
+    a->info.max_x_vectors = largest;
+    if (forced && largest > SPMV_MAX_X_VECTORS) return SPMV_ERR_UNSUPPORTED;
+    if (!forced && !pays) return SPMV_OK;  // stays ADAPTIVE
+    if (total > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+
+    for (int64_t b = 0; b < nb; ++b) xv_ptr[static_cast<size_t>(b) + 1] = xv_ptr[static_cast<size_t>(b)] + nv[static_cast<size_t>(b)];
+    spmv_status_t st = upload(xv_ptr, &h->d_xv_ptr);
+    if (st != SPMV_OK) return st;
+    const size_t lidx_slots = (static_cast<size_t>(h->nnz) + 7) / 8 * 8 + 8;
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_xv_start), sizeof(int32_t) * static_cast<size_t>(total > 0 ? total : 1))) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_lidx), sizeof(uint16_t) * lidx_slots)))
+        return SPMV_ERR_ALLOC;
+    if (hip_failed(hipMemset(h->d_lidx, 0, sizeof(uint16_t) * lidx_slots))) return SPMV_ERR_HIP;
+    if (hip_failed(spmv::launch_window_build(A, h->d_block_nz, static_cast<int32_t>(nb), a->info.block_nnz, true, nullptr,
+                                             h->d_xv_ptr, h->d_xv_start, h->d_lidx, nullptr)))
+        return SPMV_ERR_HIP;
+    a->info.plan = SPMV_PLAN_WINDOWED;
+    a->info.num_x_vectors = total;
+    return SPMV_OK;
 }
 
 // Lanes per row the binned plan gives to length bin b (b >= 4: rows of 2^(b-2)+1 .. 2^(b-1) entries).
@@ -161,6 +212,10 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
             st = SPMV_ERR_ALLOC;
         }
     }
+    if (st == SPMV_OK) {
+        const bool forced = p.plan == SPMV_PLAN_WINDOWED;
+        if (forced || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE)) st = build_x_windows(h, forced, &a);
+    }
     if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
     if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
     if (st == SPMV_OK) {
@@ -222,6 +277,12 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
             e = spmv::launch_adaptive(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->info.rows_max, x, y, s, st);
             break;
+        case SPMV_PLAN_WINDOWED: {
+            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_lidx, h->info.max_x_vectors};
+            e = spmv::launch_windowed(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
+                                      h->info.block_nnz, h->info.rows_max, w, x, y, s, st);
+            break;
+        }
         case SPMV_PLAN_MERGE:
             e = spmv::launch_merge(A, h->d_mp_row, h->d_mp_nz, static_cast<int32_t>(h->info.num_chunks),
                                    h->info.items_per_chunk, h->d_carry_row, h->d_carry_val, x, y, s, st);
@@ -265,6 +326,17 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
         if (c.dst && c.count > 0 &&
             hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
             return SPMV_ERR_HIP;
+    if (h->info.plan == SPMV_PLAN_WINDOWED) {
+        const Copy wcopies[] = {{out->xv_ptr, h->d_xv_ptr, h->info.num_row_blocks + 1},
+                                {out->xv_start, h->d_xv_start, h->info.num_x_vectors}};
+        for (const Copy& c : wcopies)
+            if (c.dst && c.count > 0 &&
+                hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
+                return SPMV_ERR_HIP;
+        if (out->lidx && h->nnz > 0 &&
+            hip_failed(hipMemcpy(out->lidx, h->d_lidx, sizeof(uint16_t) * static_cast<size_t>(h->nnz), hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+    }
     return SPMV_OK;
 }
 
@@ -276,6 +348,7 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     spmv_analyze_params_t p{};
     spmv_status_t st = spmv::resolve_params(params, &p);
     if (st != SPMV_OK) return st;
+    if (p.plan == SPMV_PLAN_WINDOWED) return SPMV_ERR_INVALID_ARG;  // the windows need colidx, which is on the device
     spmv::Analysis a;
     st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
     if (st != SPMV_OK) return st;
@@ -306,6 +379,7 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_BINNED: return spmv::vector_kernel_name();
         case SPMV_PLAN_ADAPTIVE:
         case SPMV_PLAN_MERGE: return spmv::tile_kernel_name();
+        case SPMV_PLAN_WINDOWED: return spmv::window_kernel_name();
         default: return "";
     }
 }

@@ -15,6 +15,17 @@ struct MatrixView {
     bool vec_ok;            // colidx and vals are 16-byte aligned: 128-bit loads allowed
 };
 
+constexpr int kMaxXVectors = 1024;     // most 16-byte x vectors a row block may keep in LDS
+constexpr int kMaxTileEntries = 8192;  // most entries of a row block
+
+// x windows of the row blocks (device arrays owned by the handle).
+struct XWindows {
+    const int32_t* xv_ptr;    // [nb+1]
+    const int32_t* xv_start;  // [xv_ptr[nb]]
+    const uint16_t* lidx;     // [nnz rounded up to a multiple of 8]
+    int32_t max_vectors;      // largest xv_ptr[b+1] - xv_ptr[b]
+};
+
 struct Scalars {
     float alpha, beta;
 };
@@ -29,6 +40,14 @@ hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, in
 // block_nnz, rows_max: the limits the partition was built with.
 hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
                            int32_t block_nnz, int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st);
+// The adaptive plan with x served from per-block windows in LDS.
+hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+                           int32_t block_nnz, int32_t rows_max, const XWindows& w, const void* x, float* y, Scalars s,
+                           hipStream_t st);
+// Analysis-time construction of the x windows.  fill == false: nv[b] = distinct x vectors of
+// block b.  fill == true: writes xv_start and lidx given xv_ptr = exclusive prefix sums of nv.
+hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int32_t nb, int32_t block_nnz, bool fill,
+                               int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, uint16_t* lidx, hipStream_t st);
 // mp_row, mp_nz: device [P+1]; carry_row/carry_val: device [P] scratch owned by the handle.
 hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
@@ -44,5 +63,6 @@ hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st);
 const char* scalar_kernel_name();
 const char* vector_kernel_name();
 const char* tile_kernel_name();  // kernel of the adaptive and merge plans
+const char* window_kernel_name();
 
 }  // namespace spmv

@@ -253,6 +253,12 @@ struct TileArgs {
     int32_t team_bias;        // log2 factor applied to the lanes-per-row choice (0 = default)
     float alpha, beta;
     int32_t vec_ok;
+    // x windows (window kernel only)
+    const int32_t* xv_ptr;    // [nparts+1] first x vector of each row block in xv_start
+    const int32_t* xv_start;  // first element of each 16-byte x vector
+    const uint16_t* lidx;     // [nnz, padded to a multiple of 8] position of each entry's x value in the block's window
+    int32_t x_cap;            // most x vectors any row block has
+    int32_t x_vec_ok;         // x is 16-byte aligned
 };
 
 // A single row longer than a tile: the whole workgroup strides over it.
@@ -276,8 +282,8 @@ __device__ __forceinline__ void long_row(const TileArgs& a, int r, int k0, int k
 // x out of memory, matrix values out of LDS.  G and B are compile-time so that every LDS
 // access is the lane's base address plus an immediate offset, and nothing is predicated:
 // the row phase is bound by instruction issue, so instructions per entry are what counts.
-template <int B, int G, typename E>
-__device__ __forceinline__ float gather_batch(const int* cols, const E* vals, const E* x, int j) {
+template <int B, int G, typename I, typename E>
+__device__ __forceinline__ float gather_batch(const I* cols, const E* vals, const E* x, int j) {
     unsigned c[B];
     E xv[B];
     E av[B];
@@ -297,8 +303,8 @@ __device__ __forceinline__ float gather_batch(const int* cols, const E* vals, co
 // of G lanes: entry j of the segment goes to lane j mod G.  Neighbouring teams work on
 // neighbouring rows, so for banded or stencil-like rows the lanes of a gather instruction fall
 // into a handful of cache lines.  The lane's entries are taken in batches of 8, then 4, 2, 1.
-template <int G, typename E>
-__device__ __forceinline__ float segment_dot(const int* cols, const E* vals, const E* x, int b, int e, int tl) {
+template <int G, typename I, typename E>
+__device__ __forceinline__ float segment_dot(const I* cols, const E* vals, const E* x, int b, int e, int tl) {
     float acc = 0.f;
     int j = b + tl;
     int cnt = (e - j + G - 1) / G;  // entries this lane takes (<= 0 when the segment is shorter than the team)
@@ -326,13 +332,14 @@ struct RowOut {
 };
 
 // Row phase of a tile whose entries sit in LDS (cols[], vals[]); seg[i] .. seg[i+1] bounds the
-// slots of segment i.  Segments 0 .. nr-1 are the rows r0 .. r0+nr-1 and go to y.  With MERGE
+// slots of segment i.  cols[] indexes x[]: global column numbers into the x vector in memory,
+// or 16-bit positions into the tile's x window in LDS.  Segments 0 .. nr-1 are the rows r0 .. r0+nr-1 and go to y.  With MERGE
 // there is one more segment, the piece of row r0+nr that the chunk cuts off: its sum is the
 // chunk's carry (no carry when it is empty).  Teams of G lanes take one segment each;
 // segments longer than defer_len are set aside and taken by whole wavefronts afterwards.
 // Entered by the whole workgroup with *n_deferred == 0; contains one barrier.
-template <bool MERGE, int WG, int G, typename E>
-__device__ __forceinline__ void tile_rows_g(const int* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
+template <bool MERGE, int WG, int G, typename I, typename E>
+__device__ __forceinline__ void tile_rows_g(const I* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
                                             int part, const RowOut& o, int* deferred, int* n_deferred, int tid) {
     const int nseg = nr + (MERGE ? 1 : 0);
     constexpr int defer_len = 32 * G > 64 ? 32 * G : 64;
@@ -384,8 +391,8 @@ __device__ __forceinline__ void tile_rows_g(const int* cols, const E* vals, cons
 // Lanes per row from the tile's mean segment length: the largest power of two G <= 64 with
 // 16*G <= mean + 15, shifted by team_bias.  Small teams keep the lanes of a gather on
 // neighbouring rows, which is what makes the gathers of banded matrices coalesce.
-template <bool MERGE, int WG, typename E>
-__device__ __forceinline__ void tile_rows(const int* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
+template <bool MERGE, int WG, typename I, typename E>
+__device__ __forceinline__ void tile_rows(const I* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
                                           int part, int tile_nnz, int team_bias, const RowOut& o, int* deferred,
                                           int* n_deferred, int tid) {
     const int nseg = nr + (MERGE ? 1 : 0);
@@ -537,6 +544,226 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
     tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
 }
 
+// Row blocks with x served from LDS.  The analysis has listed, for every row block, the
+// distinct aligned 16-byte vectors of x that its entries touch (xv_start) and has replaced each
+// entry's 32-bit column by a 16-bit position in that list (lidx).  A workgroup
+//   1. copies its block's x vectors to LDS (one 128-bit load per vector, coalesced wherever
+//      the block's columns are contiguous) together with the block's slice of vals and lidx,
+//   2. runs the same row phase as the tile kernel, every operand now coming out of LDS.
+// Per entry the matrix stream shrinks from value + 4 bytes to value + 2 bytes, and the row
+// phase issues no global load at all.  A block that is one over-long row takes the global path.
+template <typename T, int WG>
+__global__ __launch_bounds__(WG, 8) void spmv_window_kernel(const TileArgs a) {
+    using E = typename T::elem;
+    constexpr int XE = 16 / sizeof(E);  // elements per x vector
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    __shared__ int deferred[kMaxDeferred];
+    __shared__ int n_deferred;
+    __shared__ float wave_part[WG / 64];
+
+    const int tid = threadIdx.x;
+    const int part = xcd_remap(blockIdx.x, a.nparts);
+    const E* vals = static_cast<const E*>(a.vals);
+    const E* x = static_cast<const E*>(a.x);
+
+    const int r0 = a.part_row[part];
+    const int nr = a.part_row[part + 1] - r0;
+    const int k0 = a.part_nz[part];
+    const int k1 = a.part_nz[part + 1];
+    if (k1 - k0 > a.tile_cap) {
+        long_row<T, WG>(a, r0, k0, k1, wave_part, tid);
+        return;
+    }
+    const int v0 = a.xv_ptr[part];
+    const int nv = a.xv_ptr[part + 1] - v0;
+
+    const int k0a = k0 & ~7;  // lidx vectors hold 8 entries
+    const int span = k1 - k0a;
+    const int slots = (span + 7) & ~7;
+    E* xbuf = reinterpret_cast<E*>(smem_raw);  // x_cap vectors
+    E* vals_l = reinterpret_cast<E*>(smem_raw + 16 * a.x_cap);
+    uint16_t* lidx_l = reinterpret_cast<uint16_t*>(smem_raw + 16 * a.x_cap + sizeof(E) * slots);
+    int* seg = reinterpret_cast<int*>(smem_raw + 16 * a.x_cap + (sizeof(E) + sizeof(uint16_t)) * slots);
+
+    // the first round of x vector addresses: the only dependent load chain of the kernel
+    int xs0 = tid < nv ? a.xv_start[v0 + tid] : 0;
+
+    if (tid == 0) n_deferred = 0;
+    for (int i = tid; i <= nr; i += WG) seg[i] = a.rowptr[r0 + i] - k0a;
+
+    // ---- 1a. the block's entries: vals and lidx, two 8-entry groups per lane and trip
+    if (a.vec_ok) {
+        const int nnz_vec = a.nnz & ~7;
+        for (int off0 = tid * 8; off0 < span; off0 += 2 * WG * 8) {
+            const int off1 = off0 + WG * 8;
+            const int kA = k0a + off0, kB = k0a + off1;
+            const bool vecA = kA < nnz_vec;
+            const bool vecB = off1 < span && kB < nnz_vec;
+            u32x4 lA, lB;
+            if constexpr (sizeof(E) == 4) {
+                f32x4 vA, vA2, vB, vB2;
+                if (vecA) {
+                    vA = load_val4(reinterpret_cast<const float*>(vals) + kA);
+                    vA2 = load_val4(reinterpret_cast<const float*>(vals) + kA + 4);
+                    lA = load_val8(a.lidx + kA);
+                }
+                if (vecB) {
+                    vB = load_val4(reinterpret_cast<const float*>(vals) + kB);
+                    vB2 = load_val4(reinterpret_cast<const float*>(vals) + kB + 4);
+                    lB = load_val8(a.lidx + kB);
+                }
+                if (vecA) {
+                    *reinterpret_cast<f32x4*>(vals_l + off0) = vA;
+                    *reinterpret_cast<f32x4*>(vals_l + off0 + 4) = vA2;
+                    *reinterpret_cast<u32x4*>(lidx_l + off0) = lA;
+                }
+                if (vecB) {
+                    *reinterpret_cast<f32x4*>(vals_l + off1) = vB;
+                    *reinterpret_cast<f32x4*>(vals_l + off1 + 4) = vB2;
+                    *reinterpret_cast<u32x4*>(lidx_l + off1) = lB;
+                }
+            } else {
+                u32x4 vA, vB;
+                if (vecA) {
+                    vA = load_val8(reinterpret_cast<const uint16_t*>(vals) + kA);
+                    lA = load_val8(a.lidx + kA);
+                }
+                if (vecB) {
+                    vB = load_val8(reinterpret_cast<const uint16_t*>(vals) + kB);
+                    lB = load_val8(a.lidx + kB);
+                }
+                if (vecA) {
+                    *reinterpret_cast<u32x4*>(vals_l + off0) = vA;
+                    *reinterpret_cast<u32x4*>(lidx_l + off0) = lA;
+                }
+                if (vecB) {
+                    *reinterpret_cast<u32x4*>(vals_l + off1) = vB;
+                    *reinterpret_cast<u32x4*>(lidx_l + off1) = lB;
+                }
+            }
+            // the last few entries of the array that no whole vector covers
+            if (!vecA)
+                for (int i = 0; i < 8; ++i)
+                    if (kA + i < a.nnz) {
+                        vals_l[off0 + i] = vals[kA + i];
+                        lidx_l[off0 + i] = a.lidx[kA + i];
+                    }
+            if (!vecB && off1 < span)
+                for (int i = 0; i < 8; ++i)
+                    if (kB + i < a.nnz) {
+                        vals_l[off1 + i] = vals[kB + i];
+                        lidx_l[off1 + i] = a.lidx[kB + i];
+                    }
+        }
+    } else {
+        for (int off = (k0 - k0a) + tid; off < span; off += WG) {
+            vals_l[off] = vals[k0a + off];
+            lidx_l[off] = a.lidx[k0a + off];
+        }
+    }
+
+    // ---- 1b. the block's x vectors
+    for (int i = tid; i < nv; i += WG) {
+        const int xs = i == tid ? xs0 : a.xv_start[v0 + i];
+        if (a.x_vec_ok && xs + XE <= a.n) {
+            *reinterpret_cast<u32x4*>(xbuf + i * XE) = *reinterpret_cast<const u32x4*>(x + xs);
+        } else {
+            for (int e = 0; e < XE; ++e) xbuf[i * XE + e] = xs + e < a.n ? x[xs + e] : E(0);
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. rows
+    const RowOut o{a.y, a.carry_row, a.carry_val, a.alpha, a.beta};
+    tile_rows<false, WG>(lidx_l, vals_l, xbuf, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
+}
+
+// Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
+// keys = colidx >> shift of the block's entries, sorted in LDS (bitonic network over the next
+// power of two), duplicates dropped.  count pass (fill == 0): nv[b] = number of distinct keys.
+// fill pass: xv_start[xv_ptr[b] + j] = j-th key << shift, and for every entry
+// lidx[k] = rank of its key * 2^shift + colidx[k] mod 2^shift.  A block with more than tile_cap
+// entries (one over-long row) gets nv = 0 and lidx = 0.  The fill pass is only launched when
+// every nv[b] <= kMaxXVectors.
+__global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __restrict__ block_nz,
+                                                           const int32_t* __restrict__ colidx, int tile_cap, int shift,
+                                                           int fill, int32_t* __restrict__ nv,
+                                                           const int32_t* __restrict__ xv_ptr,
+                                                           int32_t* __restrict__ xv_start, uint16_t* __restrict__ lidx) {
+    __shared__ uint32_t keys[kMaxTileEntries];
+    __shared__ uint32_t uniq[kMaxXVectors];
+    __shared__ int counts[256];
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int k0 = block_nz[b], k1 = block_nz[b + 1];
+    const int cnt = k1 - k0;
+    if (cnt > tile_cap || cnt > kMaxTileEntries || cnt == 0) {
+        if (!fill && tid == 0) nv[b] = 0;
+        if (fill)
+            for (int i = tid; i < cnt; i += 256) lidx[k0 + i] = 0;
+        return;
+    }
+    int P = 256;
+    while (P < cnt) P <<= 1;
+    for (int i = tid; i < P; i += 256) keys[i] = i < cnt ? static_cast<uint32_t>(colidx[k0 + i]) >> shift : 0xFFFFFFFFu;
+    __syncthreads();
+    for (int k = 2; k <= P; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < P; i += 256) {
+                const int l = i ^ j;
+                if (l > i) {
+                    const uint32_t lo = keys[i], hi = keys[l];
+                    const bool up = (i & k) == 0;
+                    if (up ? lo > hi : lo < hi) {
+                        keys[i] = hi;
+                        keys[l] = lo;
+                    }
+                }
+            }
+            __syncthreads();
+        }
+    // distinct keys: each lane owns P/256 consecutive sorted slots
+    const int C = P / 256;
+    const int base = tid * C;
+    int heads = 0;
+    for (int i = base; i < base + C; ++i) {
+        const uint32_t key = keys[i];
+        if (key != 0xFFFFFFFFu && (i == 0 || keys[i - 1] != key)) ++heads;
+    }
+    counts[tid] = heads;
+    __syncthreads();
+    int pre = 0, total = 0;
+    for (int t = 0; t < 256; ++t) {
+        const int c = counts[t];
+        pre += t < tid ? c : 0;
+        total += c;
+    }
+    if (!fill) {
+        if (tid == 0) nv[b] = total;
+        return;
+    }
+    if (total > kMaxXVectors) return;  // not reached: the host launches the fill pass only when all fit
+    for (int i = base; i < base + C; ++i) {
+        const uint32_t key = keys[i];
+        if (key != 0xFFFFFFFFu && (i == 0 || keys[i - 1] != key)) uniq[pre++] = key;
+    }
+    __syncthreads();
+    const int v0 = xv_ptr[b];
+    for (int i = tid; i < total; i += 256) xv_start[v0 + i] = static_cast<int32_t>(uniq[i] << shift);
+    const uint32_t low = (1u << shift) - 1u;
+    for (int i = tid; i < cnt; i += 256) {
+        const uint32_t c = static_cast<uint32_t>(colidx[k0 + i]);
+        const uint32_t key = c >> shift;
+        int lo = 0, hi = total;  // first position with uniq[pos] >= key
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (uniq[mid] < key) lo = mid + 1;
+            else hi = mid;
+        }
+        lidx[k0 + i] = static_cast<uint16_t>((static_cast<uint32_t>(lo) << shift) + (c & low));
+    }
+}
+
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
 // are consecutive; the thread of the first of them sums the run in chunk order.
 __global__ __launch_bounds__(kWG) void merge_fixup_kernel(const int32_t* __restrict__ carry_row,
@@ -683,6 +910,22 @@ hipError_t launch_tiles(const TileArgs& a, size_t lds, hipStream_t st) {
     return launch_tiles_wg<T, MERGE, 256>(a, lds, st);
 }
 
+template <typename T>
+hipError_t launch_window_t(const TileArgs& a, size_t lds, hipStream_t st) {
+    auto kernel = spmv_window_kernel<T, 256>;
+    if (lds > 64 * 1024) {
+        static thread_local size_t allowed = 0;
+        if (lds > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return e;
+            allowed = lds;
+        }
+    }
+    hipLaunchKernelGGL(kernel, dim3(a.nparts), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
 int team_bias_from_env() {
     static const int bias = [] {
         const char* e = getenv("SPMV_TEAM_BIAS");  // experiments only
@@ -705,6 +948,38 @@ hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const
     // a block stages at most block_nnz entries and has at most rows_max rows
     if (A.bf16) return launch_tiles<BF16, false>(a, tile_lds_bytes<BF16>(block_nnz, rows_max), st);
     return launch_tiles<F32, false>(a, tile_lds_bytes<F32>(block_nnz, rows_max), st);
+}
+
+hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+                           int32_t block_nnz, int32_t rows_max, const XWindows& w, const void* x, float* y, Scalars s,
+                           hipStream_t st) {
+    if (nb <= 0) return hipSuccess;
+    if (w.max_vectors > kMaxXVectors || block_nnz > kMaxTileEntries) return hipErrorInvalidValue;
+    TileArgs a = tile_args(A, x, y, s);
+    a.part_row = row_blocks;
+    a.part_nz = block_nz;
+    a.nparts = nb;
+    a.tile_cap = block_nnz;
+    a.team_bias = team_bias_from_env();
+    a.xv_ptr = w.xv_ptr;
+    a.xv_start = w.xv_start;
+    a.lidx = w.lidx;
+    a.x_cap = w.max_vectors > 0 ? w.max_vectors : 1;
+    a.x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 ? 1 : 0;
+    const size_t esz = A.bf16 ? 2 : 4;
+    const size_t lds = 16 * static_cast<size_t>(a.x_cap) + (esz + 2) * static_cast<size_t>(block_nnz + 16) +
+                       sizeof(int) * static_cast<size_t>(rows_max + 2);
+    if (A.bf16) return launch_window_t<BF16>(a, lds, st);
+    return launch_window_t<F32>(a, lds, st);
+}
+
+hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int32_t nb, int32_t block_nnz, bool fill,
+                               int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, uint16_t* lidx, hipStream_t st) {
+    if (nb <= 0) return hipSuccess;
+    const int shift = A.bf16 ? 3 : 2;
+    hipLaunchKernelGGL(window_build_kernel, dim3(nb), dim3(256), 0, st, block_nz, A.colidx, block_nnz, shift,
+                       fill ? 1 : 0, nv, xv_ptr, xv_start, lidx);
+    return hipGetLastError();
 }
 
 hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
@@ -747,5 +1022,6 @@ hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st) {
 const char* scalar_kernel_name() { return "spmv_scalar_kernel"; }
 const char* vector_kernel_name() { return "spmv_vector_kernel"; }
 const char* tile_kernel_name() { return "spmv_tile_kernel"; }
+const char* window_kernel_name() { return "spmv_window_kernel"; }
 
 }  // namespace spmv

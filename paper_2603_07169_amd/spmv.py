@@ -17,9 +17,11 @@ SPMV_F32, SPMV_BF16 = 0, 1
 SPMV_OK = 0
 (SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_STRUCTURE, SPMV_ERR_UNSUPPORTED, SPMV_ERR_NOT_ANALYZED, SPMV_ERR_ALLOC,
  SPMV_ERR_HIP) = range(1, 7)
-SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE = range(6)
-PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge"}
+(SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE,
+ SPMV_PLAN_WINDOWED) = range(7)
+PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed"}
 SPMV_NUM_BINS = 33
+SPMV_MAX_X_VECTORS = 1024
 
 EXPORTS = [
     "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
@@ -37,9 +39,9 @@ class spmv_analyze_params_t(C.Structure):
 class spmv_analysis_info_t(C.Structure):
     _fields_ = [("m", C.c_int64), ("n", C.c_int64), ("nnz", C.c_int64), ("min_len", C.c_int64),
                 ("max_len", C.c_int64), ("n_empty", C.c_int64), ("num_row_blocks", C.c_int64),
-                ("num_chunks", C.c_int64), ("plan", C.c_int32), ("vector_lanes", C.c_int32),
-                ("block_nnz", C.c_int32), ("rows_max", C.c_int32), ("items_per_chunk", C.c_int32),
-                ("reserved", C.c_int32)]
+                ("num_chunks", C.c_int64), ("num_x_vectors", C.c_int64), ("plan", C.c_int32),
+                ("vector_lanes", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
+                ("items_per_chunk", C.c_int32), ("max_x_vectors", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -47,7 +49,8 @@ class spmv_analysis_info_t(C.Structure):
 
 class spmv_analysis_host_t(C.Structure):
     _fields_ = [("bin_count", C.c_void_p), ("bin_offset", C.c_void_p), ("bin_rows", C.c_void_p),
-                ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p)]
+                ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
+                ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("lidx", C.c_void_p)]
 
 
 class SpmvError(RuntimeError):
@@ -144,6 +147,9 @@ def _host_buffers(info):
         "bin_rows": np.zeros(info.m, np.int32), "row_blocks": np.zeros(info.num_row_blocks + 1, np.int32),
         "mp_row": np.zeros(info.num_chunks + 1, np.int32), "mp_nz": np.zeros(info.num_chunks + 1, np.int32),
     }
+    if info.plan == SPMV_PLAN_WINDOWED:
+        bufs.update(xv_ptr=np.zeros(info.num_row_blocks + 1, np.int32), xv_start=np.zeros(info.num_x_vectors, np.int32),
+                    lidx=np.zeros(info.nnz, np.uint16))
     out = spmv_analysis_host_t(**{k: v.ctypes.data for k, v in bufs.items()})
     return bufs, out
 

@@ -10,7 +10,28 @@ import paper_2603_07169_amd as s
 
 TOL = {"f32": 1e-5, "bf16": 8e-3}
 DTYPE_CODE = {"f32": s.SPMV_F32, "bf16": s.SPMV_BF16}
-ALL_PLANS = [s.SPMV_PLAN_SCALAR, s.SPMV_PLAN_VECTOR, s.SPMV_PLAN_BINNED, s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE]
+ALL_PLANS = [s.SPMV_PLAN_SCALAR, s.SPMV_PLAN_VECTOR, s.SPMV_PLAN_BINNED, s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE,
+             s.SPMV_PLAN_WINDOWED]
+
+
+def plan_params(plan):
+    """Parameters that force `plan`.  A forced WINDOWED plan needs every row block to touch at
+    most 1024 x vectors; blocks of at most 1024 entries guarantee that for any matrix."""
+    if plan == s.SPMV_PLAN_WINDOWED:
+        return dict(plan=plan, block_nnz=1024, rows_max=64)
+    return dict(plan=plan)
+
+
+def expected_auto_plan(p, info):
+    """The plan AUTO must arrive at, from the oracle's rules."""
+    st = oracle.row_stats(p.rowptr)
+    plan = oracle.plan(p.m, p.nnz, st["max_len"], info.block_nnz)
+    if plan == s.SPMV_PLAN_ADAPTIVE:
+        rb = oracle.row_blocks(p.rowptr, info.block_nnz, info.rows_max)
+        nv, _, _, _ = oracle.x_windows(p.rowptr, p.colidx, rb, info.block_nnz, 8 if p.dtype == "bf16" else 4)
+        if oracle.window_choice(nv, p.nnz):
+            plan = s.SPMV_PLAN_WINDOWED
+    return plan
 
 
 def to_dev(a: np.ndarray, offset_elems: int = 0) -> torch.Tensor:

@@ -13,10 +13,10 @@ pytestmark = pytest.mark.gpu
 
 EXPECT = {   # nnz, algorithmic bytes, plan chosen by analyze
     1: (65536, 573444, "adaptive"),
-    2: (5238784, 58687492, "adaptive"),
-    3: (55742968, 355429332, "adaptive"),
+    2: (5238784, 58687492, "windowed"),
+    3: (55742968, 355429332, "windowed"),
     4: (None, None, "merge"),
-    5: (128000000, 778000004, "adaptive"),
+    5: (128000000, 778000004, "windowed"),
 }
 
 
@@ -44,6 +44,22 @@ def test_full_config_matches_oracle(k):
     assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
     cnt, off, rows = oracle.row_bins(p.rowptr)
     assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_rows"], rows)
+    if plan == "windowed":
+        # x windows: 300 sampled row blocks (first, last, random), each against the oracle run on that block alone
+        rb, xv_ptr = got["row_blocks"], got["xv_ptr"]
+        nb = rb.size - 1
+        ve = 8 if p.dtype == "bf16" else 4
+        pick = np.unique(np.concatenate([[0, nb - 1], np.random.default_rng(k).integers(0, nb, 300)]))
+        for b in pick:
+            nv, _, xs, li = oracle.x_windows(p.rowptr, p.colidx, rb[b:b + 2].copy(), A.info.block_nnz, ve)
+            k0, k1 = p.rowptr[rb[b]], p.rowptr[rb[b + 1]]
+            assert xv_ptr[b + 1] - xv_ptr[b] == nv[0], b
+            assert np.array_equal(got["xv_start"][xv_ptr[b]:xv_ptr[b + 1]], xs), b
+            assert np.array_equal(got["lidx"][k0:k1], li[k0:k1]), b
+        A.close()
+        # the tile kernel (global x gathers) on the same matrix, which AUTO no longer picks here
+        A = d.matrix(dict(plan=s.SPMV_PLAN_ADAPTIVE))
+        assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full adaptive")
     A.close()
 
 

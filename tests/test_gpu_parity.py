@@ -8,7 +8,8 @@ import torch
 import oracle
 import paper_2603_07169_amd as s
 import workloads as w
-from gpu_util import ALL_PLANS, DeviceProblem, assert_close, check_problem, reference, to_dev
+from gpu_util import (ALL_PLANS, DeviceProblem, assert_close, check_problem, expected_auto_plan, plan_params, reference,
+                      to_dev)
 
 pytestmark = pytest.mark.gpu
 
@@ -41,7 +42,7 @@ def test_cross_lane_group_sums():
 def test_tiny_adversarial(dtype, plan):
     for p in w.tiny_adversarial(dtype=dtype):
         log("case", p.name, dtype, s.PLAN_NAMES[plan])
-        check_problem(p, dict(plan=plan), what=s.PLAN_NAMES[plan])
+        check_problem(p, plan_params(plan), what=s.PLAN_NAMES[plan])
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -53,7 +54,7 @@ def test_exact_integer_bit_for_bit(dtype, plan):
     p = w.exact_integer(lens, 250000, dtype=dtype, alpha=3.0, beta=-2.0)
     log("case exact_integer", dtype, s.PLAN_NAMES[plan])
     d = DeviceProblem(p)
-    A = d.matrix(dict(plan=plan))
+    A = d.matrix(plan_params(plan))
     y = d.run(A)
     y_ref, _ = reference(p)
     assert np.array_equal(y.astype(np.float64), y_ref)
@@ -69,7 +70,7 @@ def test_exact_integer_many_rows(dtype):
     d = DeviceProblem(p)
     for plan in ALL_PLANS:
         log("case exact_integer_many_rows", dtype, s.PLAN_NAMES[plan])
-        A = d.matrix(dict(plan=plan))
+        A = d.matrix(plan_params(plan))
         assert np.array_equal(d.run(A).astype(np.float64), y_ref), s.PLAN_NAMES[plan]
         A.close()
 
@@ -80,7 +81,7 @@ def test_exact_integer_many_rows(dtype):
 def test_scaled_configs_every_plan(k, plan):
     p = w.config(k, 1.0 if k == 1 else 1 / 16)
     log("case", p.name, s.PLAN_NAMES[plan])
-    check_problem(p, dict(plan=plan), strict=True, what=s.PLAN_NAMES[plan])
+    check_problem(p, plan_params(plan), strict=True, what=s.PLAN_NAMES[plan])
 
 
 # ------------------------------------------------------------------ tile-size parameters
@@ -106,7 +107,7 @@ def test_misaligned_arrays(dtype, plan):
     128-bit load paths must not be taken."""
     q = w.powerlaw(20000, dtype=dtype)
     log("case misaligned", dtype, s.PLAN_NAMES[plan])
-    check_problem(q, dict(plan=plan), offset_elems=1)
+    check_problem(q, plan_params(plan), offset_elems=1)
 
 
 # ------------------------------------------------------------------ scalars, streams, reuse
@@ -116,7 +117,7 @@ def test_beta_zero_ignores_nan_in_y():
     y_ref, S_ref = reference(p, 1.0, 0.0)
     nan_y = torch.full((p.m,), float("nan"), dtype=torch.float32, device="cuda")
     for plan in ALL_PLANS:
-        A = d.matrix(dict(plan=plan))
+        A = d.matrix(plan_params(plan))
         y = d.run(A, 1.0, 0.0, y_init=nan_y)
         assert np.all(np.isfinite(y))
         assert_close(p, y, y_ref, S_ref, 1.0, 0.0, strict=True)
@@ -167,9 +168,65 @@ def test_device_analysis_equals_oracle(k):
     mr, mz = oracle.merge_path(p.rowptr, A.info.items_per_chunk)
     assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
     st = oracle.row_stats(p.rowptr)
-    assert A.info.plan == oracle.plan(p.m, p.nnz, st["max_len"], A.info.block_nnz)
+    assert A.info.plan == expected_auto_plan(p, A.info)
     assert (A.info.min_len, A.info.max_len, A.info.n_empty) == (st["min_len"], st["max_len"], st["n_empty"])
     A.close()
+
+
+def check_windows_equal_oracle(p, A):
+    got = A.analysis()
+    ve = 8 if p.dtype == "bf16" else 4
+    nv, xv_ptr, xv_start, lidx = oracle.x_windows(p.rowptr, p.colidx, got["row_blocks"], A.info.block_nnz, ve)
+    assert A.info.num_x_vectors == xv_start.size and A.info.max_x_vectors == (nv.max() if nv.size else 0)
+    assert np.array_equal(got["xv_ptr"], xv_ptr)
+    assert np.array_equal(got["xv_start"], xv_start)
+    assert np.array_equal(got["lidx"], lidx)
+
+
+@pytest.mark.parametrize("k", [1, 2, 3, 4, 5])
+def test_x_windows_equal_oracle(k):
+    """The device-built x windows, bit for bit, on every config (forced, with blocks small enough
+    for any column pattern) and under the automatic plan where it picks them."""
+    p = w.config(k, 1.0 if k == 1 else 1 / 8)
+    d = DeviceProblem(p)
+    log("case x windows forced", p.name)
+    A = d.matrix(plan_params(s.SPMV_PLAN_WINDOWED))
+    assert A.info.plan == s.SPMV_PLAN_WINDOWED
+    check_windows_equal_oracle(p, A)
+    A.close()
+    A = d.matrix()
+    log("case x windows auto", p.name, s.PLAN_NAMES[A.info.plan])
+    assert (A.info.plan == s.SPMV_PLAN_WINDOWED) == (k in (2, 3, 5))
+    if A.info.plan == s.SPMV_PLAN_WINDOWED:
+        check_windows_equal_oracle(p, A)
+    A.close()
+
+
+def test_x_windows_ragged_and_long_rows():
+    rng = np.random.default_rng(41)
+    lens = np.concatenate([rng.integers(0, 30, 700), [3000, 0, 0, 1, 1025, 1024, 1023], rng.integers(0, 300, 150)])
+    for dtype in ("f32", "bf16"):
+        p = w.from_row_lengths(lens, 20000, seed=78, dtype=dtype, allow_dup=True, sort_cols=False)
+        d = DeviceProblem(p)
+        for params in (dict(plan=6, block_nnz=1024, rows_max=64), dict(plan=6, block_nnz=300, rows_max=1024),
+                       dict(plan=6, block_nnz=5, rows_max=2)):
+            log("case x windows ragged", dtype, params)
+            A = d.matrix(params)
+            check_windows_equal_oracle(p, A)
+            A.close()
+
+
+def test_forced_windowed_rejects_blocks_with_too_many_vectors():
+    p = w.uniform_rows(4096, 1 << 20, 16)  # 8192-entry blocks of random columns: about 8000 distinct vectors
+    d = DeviceProblem(p)
+    st, h = s.spmv_csr_create(p.m, p.n, p.nnz, d.rowptr.data_ptr(), d.colidx.data_ptr(), d.vals.data_ptr(), 0)
+    assert st == s.SPMV_OK
+    assert s.spmv_csr_analyze(h, dict(plan=6, block_nnz=8192, rows_max=1024)) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_csr_run(h, d.x.data_ptr(), d.y0.data_ptr(), 1.0, 0.0) == s.SPMV_ERR_NOT_ANALYZED
+    assert s.spmv_csr_analyze(h) == s.SPMV_OK  # the automatic plan falls back to the tile kernel
+    st, info = s.spmv_csr_get_analysis_info(h)
+    assert info.plan == s.SPMV_PLAN_ADAPTIVE
+    s.spmv_destroy(h)
 
 
 def test_analyze_rejects_bad_input_on_device():
@@ -202,7 +259,7 @@ def test_degenerate_shapes():
     p = w.CsrProblem("nnz0", "f32", 7, 5, np.zeros(8, np.int32), e32, np.zeros(0, np.float32), np.ones(5, np.float32), y0, 1.0, 3.0)
     d = DeviceProblem(p)
     for plan in [0] + ALL_PLANS:
-        A = d.matrix(dict(plan=plan))
+        A = d.matrix(plan_params(plan))
         assert np.array_equal(d.run(A), 3.0 * y0)
         assert np.array_equal(d.run(A, 1.0, 0.0), np.zeros(7, np.float32))
         A.close()
