@@ -552,8 +552,10 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
 //   2. runs the same row phase as the tile kernel, every operand now coming out of LDS.
 // Per entry the matrix stream shrinks from value + 4 bytes to value + 2 bytes, and the row
 // phase issues no global load at all.  A block that is one over-long row takes the global path.
-template <typename T, int WG>
-__global__ __launch_bounds__(WG, 8) void spmv_window_kernel(const TileArgs a) {
+// XPL: x vectors a lane fetches (x_cap <= XPL*WG); NG: 8-entry groups a lane stages in the
+// first, branch-free round (blocks of up to NG*WG*8 - 7 entries need no second round).
+template <typename T, int WG, int XPL, int NG>
+__global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window_kernel(const TileArgs a) {
     using E = typename T::elem;
     constexpr int XE = 16 / sizeof(E);  // elements per x vector
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -570,12 +572,12 @@ __global__ __launch_bounds__(WG, 8) void spmv_window_kernel(const TileArgs a) {
     const int nr = a.part_row[part + 1] - r0;
     const int k0 = a.part_nz[part];
     const int k1 = a.part_nz[part + 1];
+    const int v0 = a.xv_ptr[part];
+    const int nv = a.xv_ptr[part + 1] - v0;
     if (k1 - k0 > a.tile_cap) {
         long_row<T, WG>(a, r0, k0, k1, wave_part, tid);
         return;
     }
-    const int v0 = a.xv_ptr[part];
-    const int nv = a.xv_ptr[part + 1] - v0;
 
     const int k0a = k0 & ~7;  // lidx vectors hold 8 entries
     const int span = k1 - k0a;
@@ -585,91 +587,88 @@ __global__ __launch_bounds__(WG, 8) void spmv_window_kernel(const TileArgs a) {
     uint16_t* lidx_l = reinterpret_cast<uint16_t*>(smem_raw + 16 * a.x_cap + sizeof(E) * slots);
     int* seg = reinterpret_cast<int*>(smem_raw + 16 * a.x_cap + (sizeof(E) + sizeof(uint16_t)) * slots);
 
-    // the first round of x vector addresses: the only dependent load chain of the kernel
-    int xs0 = tid < nv ? a.xv_start[v0 + tid] : 0;
+    // Every load of the common path below is unconditional, in straight-line code: a lane with
+    // nothing to fetch reads the start of lidx instead (always allocated, 16-byte aligned, at
+    // least 16 bytes).  Without branches around the loads the compiler can wait for the oldest
+    // loads only, so the order of issue is also the order of use:
+    //   x vector addresses -> row bounds -> entry stream -> x vectors (need the addresses)
+    //   -> LDS stores of the stream (while the x vectors are in flight) -> LDS stores of x.
+    const uint16_t* const dummy = a.lidx;
+    int xs[XPL];
+#pragma unroll
+    for (int u = 0; u < XPL; ++u) {
+        const int i = tid + u * WG;
+        const int32_t* src = i < nv ? a.xv_start + v0 + i : reinterpret_cast<const int32_t*>(dummy);
+        xs[u] = *src;
+        xs[u] = i < nv ? xs[u] : -1;
+    }
+    const int rp0 = a.rowptr[r0 + (tid < nr ? tid : nr)];
 
-    if (tid == 0) n_deferred = 0;
-    for (int i = tid; i <= nr; i += WG) seg[i] = a.rowptr[r0 + i] - k0a;
+    // A group is 8 consecutive entries: one 128-bit vector of lidx, one (bf16) or two (binary32)
+    // of vals.  Groups that reach past the last whole vector of the arrays, and everything when
+    // vals is not 16-byte aligned, are copied element by element afterwards.
+    struct Group {
+        u32x4 v0, v1, l;
+        bool live, vec;
+    };
+    const int nnz_vec = a.vec_ok ? a.nnz & ~7 : 0;
+    auto load_group = [&](int off, Group& g) {
+        const int k = k0a + off;
+        g.live = off < span;
+        g.vec = g.live && k < nnz_vec;
+        const uint16_t* vp = g.vec ? reinterpret_cast<const uint16_t*>(vals + k) : dummy;
+        const uint16_t* lp = g.vec ? a.lidx + k : dummy;
+        g.v0 = load_val8(vp);
+        if constexpr (sizeof(E) == 4) g.v1 = load_val8(g.vec ? vp + 8 : dummy);
+        g.l = load_val8(lp);
+    };
+    auto store_group = [&](int off, const Group& g) {
+        if (g.vec) {
+            *reinterpret_cast<u32x4*>(vals_l + off) = g.v0;
+            if constexpr (sizeof(E) == 4) *reinterpret_cast<u32x4*>(vals_l + off + 4) = g.v1;
+            *reinterpret_cast<u32x4*>(lidx_l + off) = g.l;
+        } else if (g.live) {
+            const int k = k0a + off;
+            for (int i = 0; i < 8; ++i)
+                if (k + i >= k0 && k + i < k1) {
+                    vals_l[off + i] = vals[k + i];
+                    lidx_l[off + i] = a.lidx[k + i];
+                }
+        }
+    };
 
-    // ---- 1a. the block's entries: vals and lidx, two 8-entry groups per lane and trip
-    if (a.vec_ok) {
-        const int nnz_vec = a.nnz & ~7;
-        for (int off0 = tid * 8; off0 < span; off0 += 2 * WG * 8) {
-            const int off1 = off0 + WG * 8;
-            const int kA = k0a + off0, kB = k0a + off1;
-            const bool vecA = kA < nnz_vec;
-            const bool vecB = off1 < span && kB < nnz_vec;
-            u32x4 lA, lB;
-            if constexpr (sizeof(E) == 4) {
-                f32x4 vA, vA2, vB, vB2;
-                if (vecA) {
-                    vA = load_val4(reinterpret_cast<const float*>(vals) + kA);
-                    vA2 = load_val4(reinterpret_cast<const float*>(vals) + kA + 4);
-                    lA = load_val8(a.lidx + kA);
-                }
-                if (vecB) {
-                    vB = load_val4(reinterpret_cast<const float*>(vals) + kB);
-                    vB2 = load_val4(reinterpret_cast<const float*>(vals) + kB + 4);
-                    lB = load_val8(a.lidx + kB);
-                }
-                if (vecA) {
-                    *reinterpret_cast<f32x4*>(vals_l + off0) = vA;
-                    *reinterpret_cast<f32x4*>(vals_l + off0 + 4) = vA2;
-                    *reinterpret_cast<u32x4*>(lidx_l + off0) = lA;
-                }
-                if (vecB) {
-                    *reinterpret_cast<f32x4*>(vals_l + off1) = vB;
-                    *reinterpret_cast<f32x4*>(vals_l + off1 + 4) = vB2;
-                    *reinterpret_cast<u32x4*>(lidx_l + off1) = lB;
-                }
-            } else {
-                u32x4 vA, vB;
-                if (vecA) {
-                    vA = load_val8(reinterpret_cast<const uint16_t*>(vals) + kA);
-                    lA = load_val8(a.lidx + kA);
-                }
-                if (vecB) {
-                    vB = load_val8(reinterpret_cast<const uint16_t*>(vals) + kB);
-                    lB = load_val8(a.lidx + kB);
-                }
-                if (vecA) {
-                    *reinterpret_cast<u32x4*>(vals_l + off0) = vA;
-                    *reinterpret_cast<u32x4*>(lidx_l + off0) = lA;
-                }
-                if (vecB) {
-                    *reinterpret_cast<u32x4*>(vals_l + off1) = vB;
-                    *reinterpret_cast<u32x4*>(lidx_l + off1) = lB;
-                }
-            }
-            // the last few entries of the array that no whole vector covers
-            if (!vecA)
-                for (int i = 0; i < 8; ++i)
-                    if (kA + i < a.nnz) {
-                        vals_l[off0 + i] = vals[kA + i];
-                        lidx_l[off0 + i] = a.lidx[kA + i];
-                    }
-            if (!vecB && off1 < span)
-                for (int i = 0; i < 8; ++i)
-                    if (kB + i < a.nnz) {
-                        vals_l[off1 + i] = vals[kB + i];
-                        lidx_l[off1 + i] = a.lidx[kB + i];
-                    }
-        }
-    } else {
-        for (int off = (k0 - k0a) + tid; off < span; off += WG) {
-            vals_l[off] = vals[k0a + off];
-            lidx_l[off] = a.lidx[k0a + off];
-        }
+    Group g[NG];
+#pragma unroll
+    for (int u = 0; u < NG; ++u) load_group((tid + u * WG) * 8, g[u]);
+
+    u32x4 xv[XPL];
+    bool xvec[XPL];
+#pragma unroll
+    for (int u = 0; u < XPL; ++u) {
+        xvec[u] = xs[u] >= 0 && a.x_vec_ok && xs[u] + XE <= a.n;
+        const E* src = xvec[u] ? x + xs[u] : reinterpret_cast<const E*>(dummy);
+        xv[u] = *reinterpret_cast<const u32x4*>(src);
     }
 
-    // ---- 1b. the block's x vectors
-    for (int i = tid; i < nv; i += WG) {
-        const int xs = i == tid ? xs0 : a.xv_start[v0 + i];
-        if (a.x_vec_ok && xs + XE <= a.n) {
-            *reinterpret_cast<u32x4*>(xbuf + i * XE) = *reinterpret_cast<const u32x4*>(x + xs);
-        } else {
-            for (int e = 0; e < XE; ++e) xbuf[i * XE + e] = xs + e < a.n ? x[xs + e] : E(0);
+    if (tid == 0) n_deferred = 0;
+    if (tid <= nr) seg[tid] = rp0 - k0a;
+#pragma unroll
+    for (int u = 0; u < NG; ++u) store_group((tid + u * WG) * 8, g[u]);
+#pragma unroll
+    for (int u = 0; u < XPL; ++u) {
+        const int i = tid + u * WG;
+        if (xvec[u]) {
+            *reinterpret_cast<u32x4*>(xbuf + i * XE) = xv[u];
+        } else if (xs[u] >= 0) {
+            for (int e = 0; e < XE; ++e) xbuf[i * XE + e] = xs[u] + e < a.n ? x[xs[u] + e] : E(0);
         }
+    }
+    // what the fixed-size first round did not cover (blocks of more than WG rows or NG*WG*8 entries)
+    for (int i = tid + WG; i <= nr; i += WG) seg[i] = a.rowptr[r0 + i] - k0a;
+    for (int off = (tid + NG * WG) * 8; off < span; off += WG * 8) {
+        Group h;
+        load_group(off, h);
+        store_group(off, h);
     }
     __syncthreads();
 
@@ -910,9 +909,9 @@ hipError_t launch_tiles(const TileArgs& a, size_t lds, hipStream_t st) {
     return launch_tiles_wg<T, MERGE, 256>(a, lds, st);
 }
 
-template <typename T>
-hipError_t launch_window_t(const TileArgs& a, size_t lds, hipStream_t st) {
-    auto kernel = spmv_window_kernel<T, 256>;
+template <typename T, int XPL, int NG>
+hipError_t launch_window_k(const TileArgs& a, size_t lds, hipStream_t st) {
+    auto kernel = spmv_window_kernel<T, 256, XPL, NG>;
     if (lds > 64 * 1024) {
         static thread_local size_t allowed = 0;
         if (lds > allowed) {
@@ -924,6 +923,17 @@ hipError_t launch_window_t(const TileArgs& a, size_t lds, hipStream_t st) {
     }
     hipLaunchKernelGGL(kernel, dim3(a.nparts), dim3(256), lds, st, a);
     return hipGetLastError();
+}
+
+// Picks the instantiation whose fixed first round of loads just covers the blocks.
+template <typename T>
+hipError_t launch_window_t(const TileArgs& a, size_t lds, hipStream_t st) {
+    const bool one_group = a.tile_cap + 7 <= 256 * 8;
+    if (a.x_cap <= 256)
+        return one_group ? launch_window_k<T, 1, 1>(a, lds, st) : launch_window_k<T, 1, 2>(a, lds, st);
+    if (a.x_cap <= 512)
+        return one_group ? launch_window_k<T, 2, 1>(a, lds, st) : launch_window_k<T, 2, 2>(a, lds, st);
+    return one_group ? launch_window_k<T, 4, 1>(a, lds, st) : launch_window_k<T, 4, 2>(a, lds, st);
 }
 
 int team_bias_from_env() {
