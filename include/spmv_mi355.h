@@ -98,6 +98,9 @@ typedef struct {
     /* WINDOWED plan only (skipped otherwise): */
     int32_t* xv_ptr;     /* [nb+1] exclusive prefix of the blocks' x vector counts   */
     int32_t* xv_start;   /* [num_x_vectors] first x element of each vector           */
+    int32_t* xv_pad;     /* [nb * max(1, max_x_vectors)] block b's part of xv_start at
+                            xv_pad[b*max_x_vectors ...], then -1 up to the next block:
+                            the fixed-stride copy the kernel reads                    */
     uint16_t* lidx;      /* [nnz]  window position of every entry's x value          */
 } spmv_analysis_host_t;
 
@@ -131,9 +134,10 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     keys_b = the distinct colidx/VE of its entries in ascending order (VE = elements per
  *     vector); xv_start lists keys_b*VE block after block, xv_ptr its block boundaries;
  *     lidx[k] = rank(colidx[k]/VE in keys_b)*VE + colidx[k]%VE.  A block that is one row longer
- *     than block_nnz has no vectors and lidx 0.  AUTO picks WINDOWED when every block has at
- *     most SPMV_MAX_X_VECTORS vectors and 4 * num_x_vectors <= nnz; a forced WINDOWED plan
- *     fails with UNSUPPORTED when some block has more.  The library then holds 2 bytes per
+ *     than block_nnz has no vectors and lidx 0.  With V = the largest vector count of any
+ *     block, AUTO picks WINDOWED when V <= SPMV_MAX_X_VECTORS and 4 * nb * V <= nnz (the kernel
+ *     reads the lists at a fixed stride of V per block); a forced WINDOWED plan fails with
+ *     UNSUPPORTED when V is larger.  The library then holds 2 bytes per
  *     stored entry of its own (lidx) and run() no longer reads colidx.
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
  * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */

@@ -204,17 +204,16 @@ int64_t oracle_x_windows(int64_t nb, const int32_t* row_blocks, const int32_t* r
     return total;
 }
 
-// Whether the automatic plan serves x from those windows: every block's vectors must fit the
-// kernel's buffer (at most max_vectors) and, summed over the matrix, a fetched vector must
-// serve at least four entries.
+// Whether the automatic plan serves x from those windows.  The kernel reads every block's list
+// at a fixed stride of V = the largest nv, so the lists cost nb * V words: V must fit the
+// kernel's buffer (at most max_vectors) and 4 * nb * V must not exceed the entry count.
 int32_t oracle_window_choice(int64_t nb, const int32_t* nv, int64_t nnz, int32_t max_vectors) {
     if (nnz == 0) return 0;
-    int64_t total = 0;
-    for (int64_t b = 0; b < nb; ++b) {
-        if (nv[b] > max_vectors) return 0;
-        total += nv[b];
-    }
-    return 4 * total <= nnz ? 1 : 0;
+    int64_t V = 0;
+    for (int64_t b = 0; b < nb; ++b)
+        if (nv[b] > V) V = nv[b];
+    if (V > max_vectors) return 0;
+    return 4 * nb * V <= nnz ? 1 : 0;
 }
 
 }  // extern "C"

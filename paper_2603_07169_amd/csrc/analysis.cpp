@@ -186,7 +186,7 @@ bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, i
     }
     *total = sum;
     *largest = mx;
-    return nnz > 0 && mx <= SPMV_MAX_X_VECTORS && 4 * sum <= nnz;
+    return nnz > 0 && mx <= SPMV_MAX_X_VECTORS && 4 * nb * static_cast<int64_t>(mx) <= nnz;
 }
 
 }  // namespace spmv

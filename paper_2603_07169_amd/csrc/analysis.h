@@ -36,7 +36,8 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
                              const spmv_analyze_params_t& params, Analysis* out);
 
 // Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x
-// from the windows (every block within SPMV_MAX_X_VECTORS and at least four entries per vector).
+// from the windows: every block within SPMV_MAX_X_VECTORS, and the fixed-stride address lists
+// (one slot per block and possible vector) no longer than a quarter of the entries.
 bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest);
 
 }  // namespace spmv

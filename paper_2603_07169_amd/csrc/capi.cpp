@@ -47,6 +47,7 @@ struct spmv_csr_s {
     float* d_carry_val = nullptr;
     int32_t* d_xv_ptr = nullptr;  // x windows (WINDOWED plan)
     int32_t* d_xv_start = nullptr;
+    int32_t* d_xv_pad = nullptr;
     uint16_t* d_lidx = nullptr;
 };
 
@@ -54,12 +55,13 @@ namespace {
 
 void free_metadata(spmv_csr_s* h) {
     void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
-                    h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx};
+                    h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
+                    h->d_xv_pad};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
     h->d_carry_val = nullptr;
-    h->d_xv_ptr = h->d_xv_start = nullptr;
+    h->d_xv_ptr = h->d_xv_start = h->d_xv_pad = nullptr;
     h->d_lidx = nullptr;
     h->analyzed = false;
 }
@@ -101,7 +103,7 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, spmv::Analysis* a) {
     int32_t* d_nv = nullptr;
     if (hip_failed(hipMalloc(reinterpret_cast<void**>(&d_nv), sizeof(int32_t) * nv.size()))) return SPMV_ERR_ALLOC;
     bool bad = hip_failed(spmv::launch_window_build(A, h->d_block_nz, static_cast<int32_t>(nb), a->info.block_nnz, false,
-                                                    d_nv, nullptr, nullptr, nullptr, nullptr));
+                                                    d_nv, nullptr, nullptr, nullptr, 0, nullptr, nullptr));
     bad = bad || (nb > 0 && hip_failed(hipMemcpy(nv.data(), d_nv, sizeof(int32_t) * static_cast<size_t>(nb),
                                                  hipMemcpyDeviceToHost)));
     (void)hipFree(d_nv);
@@ -113,18 +115,21 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, spmv::Analysis* a) {
     a->info.max_x_vectors = largest;
     if (forced && largest > SPMV_MAX_X_VECTORS) return SPMV_ERR_UNSUPPORTED;
     if (!forced && !pays) return SPMV_OK;  // stays ADAPTIVE
-    if (total > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    const int32_t x_cap = largest > 0 ? largest : 1;
+    const int64_t padded = nb * static_cast<int64_t>(x_cap);
+    if (padded > kMaxCount) return SPMV_ERR_UNSUPPORTED;
 
     for (int64_t b = 0; b < nb; ++b) xv_ptr[static_cast<size_t>(b) + 1] = xv_ptr[static_cast<size_t>(b)] + nv[static_cast<size_t>(b)];
     spmv_status_t st = upload(xv_ptr, &h->d_xv_ptr);
     if (st != SPMV_OK) return st;
     const size_t lidx_slots = (static_cast<size_t>(h->nnz) + 7) / 8 * 8 + 8;
     if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_xv_start), sizeof(int32_t) * static_cast<size_t>(total > 0 ? total : 1))) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_xv_pad), sizeof(int32_t) * static_cast<size_t>(padded > 0 ? padded : 1))) ||
         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_lidx), sizeof(uint16_t) * lidx_slots)))
         return SPMV_ERR_ALLOC;
     if (hip_failed(hipMemset(h->d_lidx, 0, sizeof(uint16_t) * lidx_slots))) return SPMV_ERR_HIP;
     if (hip_failed(spmv::launch_window_build(A, h->d_block_nz, static_cast<int32_t>(nb), a->info.block_nnz, true, nullptr,
-                                             h->d_xv_ptr, h->d_xv_start, h->d_lidx, nullptr)))
+                                             h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, x_cap, h->d_lidx, nullptr)))
         return SPMV_ERR_HIP;
     a->info.plan = SPMV_PLAN_WINDOWED;
     a->info.num_x_vectors = total;
@@ -278,7 +283,7 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
                                       h->info.block_nnz, h->info.rows_max, x, y, s, st);
             break;
         case SPMV_PLAN_WINDOWED: {
-            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_lidx, h->info.max_x_vectors};
+            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx, h->info.max_x_vectors};
             e = spmv::launch_windowed(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->info.rows_max, w, x, y, s, st);
             break;
@@ -328,7 +333,9 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
             return SPMV_ERR_HIP;
     if (h->info.plan == SPMV_PLAN_WINDOWED) {
         const Copy wcopies[] = {{out->xv_ptr, h->d_xv_ptr, h->info.num_row_blocks + 1},
-                                {out->xv_start, h->d_xv_start, h->info.num_x_vectors}};
+                                {out->xv_start, h->d_xv_start, h->info.num_x_vectors},
+                                {out->xv_pad, h->d_xv_pad,
+                                 h->info.num_row_blocks * (h->info.max_x_vectors > 0 ? h->info.max_x_vectors : 1)}};
         for (const Copy& c : wcopies)
             if (c.dst && c.count > 0 &&
                 hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))

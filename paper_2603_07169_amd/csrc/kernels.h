@@ -22,6 +22,7 @@ constexpr int kMaxTileEntries = 8192;  // most entries of a row block
 struct XWindows {
     const int32_t* xv_ptr;    // [nb+1]
     const int32_t* xv_start;  // [xv_ptr[nb]]
+    const int32_t* xv_pad;    // [nb * max_vectors] xv_start at a fixed stride per block, -1 padded: what the kernel reads
     const uint16_t* lidx;     // [nnz rounded up to a multiple of 8]
     int32_t max_vectors;      // largest xv_ptr[b+1] - xv_ptr[b]
 };
@@ -45,9 +46,11 @@ hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const
                            int32_t block_nnz, int32_t rows_max, const XWindows& w, const void* x, float* y, Scalars s,
                            hipStream_t st);
 // Analysis-time construction of the x windows.  fill == false: nv[b] = distinct x vectors of
-// block b.  fill == true: writes xv_start and lidx given xv_ptr = exclusive prefix sums of nv.
+// block b.  fill == true: writes xv_start, xv_pad (stride x_cap >= every nv[b]) and lidx given
+// xv_ptr = exclusive prefix sums of nv.
 hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int32_t nb, int32_t block_nnz, bool fill,
-                               int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, uint16_t* lidx, hipStream_t st);
+                               int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, int32_t* xv_pad, int32_t x_cap,
+                               uint16_t* lidx, hipStream_t st);
 // mp_row, mp_nz: device [P+1]; carry_row/carry_val: device [P] scratch owned by the handle.
 hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,

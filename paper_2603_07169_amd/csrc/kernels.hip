@@ -254,8 +254,7 @@ struct TileArgs {
     float alpha, beta;
     int32_t vec_ok;
     // x windows (window kernel only)
-    const int32_t* xv_ptr;    // [nparts+1] first x vector of each row block in xv_start
-    const int32_t* xv_start;  // first element of each 16-byte x vector
+    const int32_t* xv_pad;    // [nparts * x_cap] first element of each 16-byte x vector of a block, -1 padded
     const uint16_t* lidx;     // [nnz, padded to a multiple of 8] position of each entry's x value in the block's window
     int32_t x_cap;            // most x vectors any row block has
     int32_t x_vec_ok;         // x is 16-byte aligned
@@ -326,6 +325,7 @@ __device__ __forceinline__ float segment_dot(const I* cols, const E* vals, const
 // Where the row phase of a tile sends its results.
 struct RowOut {
     float* y;
+    const float* y0;  // LDS: y0[i] = old y of row r0+i when beta != 0 (fetched while the tile was loading)
     int32_t* carry_row;
     float* carry_val;
     float alpha, beta;
@@ -349,8 +349,7 @@ __device__ __forceinline__ void tile_rows_g(const I* cols, const E* vals, const 
 
     auto emit = [&](int i, float s, int len) {
         if (i < nr) {
-            const int r = r0 + i;
-            o.y[r] = epilogue(s, o.alpha, o.beta, o.y, r);
+            o.y[r0 + i] = epilogue(s, o.alpha, o.beta, o.y0, i);
         } else {
             o.carry_row[part] = len > 0 ? r0 + nr : -1;
             o.carry_val[part] = s;
@@ -458,13 +457,19 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
     E* vals_l = reinterpret_cast<E*>(smem_raw + sizeof(int) * slots);
     int* seg = reinterpret_cast<int*>(smem_raw + (sizeof(int) + sizeof(E)) * slots);  // nseg + 1 entries
 
-    if (tid == 0) n_deferred = 0;
-    for (int i = tid; i <= nseg; i += WG) {
-        int v = (i <= nr) ? a.rowptr[r0 + i] : k1;
+    float* y0_l = reinterpret_cast<float*>(seg + nseg + 1);  // nr entries
+
+    // row bounds and (beta != 0) old y of the first WG rows: issued ahead of the entry stream,
+    // stored to LDS after it, so that neither costs a memory round trip of its own
+    const int rp0 = a.rowptr[r0 + (tid < nr ? tid : nr)];
+    const int rp_nr = MERGE ? a.rowptr[r0 + nr] : k1;  // same address in every lane; row blocks end at k1
+    const float* const y_src = (a.beta != 0.f && tid < nr) ? a.y + r0 + tid : reinterpret_cast<const float*>(a.rowptr);
+    const float y0v = *y_src;
+    auto clamp_bound = [&](int v) {
         v = v < k0 ? k0 : v;
         v = v > k1 ? k1 : v;
-        seg[i] = v - k0a;
-    }
+        return v - k0a;
+    };
 
     // ---- 1. stage the tile's entries: two vectors per lane and trip, all loads before any store
     if (a.vec_ok) {
@@ -537,16 +542,25 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
             cols_l[off] = a.colidx[k0a + off];
         }
     }
+    if (tid == 0) n_deferred = 0;
+    if (tid < nr) seg[tid] = clamp_bound(rp0);
+    if (tid == 0) seg[nr] = clamp_bound(rp_nr);
+    if (tid < nr) y0_l[tid] = y0v;
+    for (int i = tid + WG; i < nr; i += WG) seg[i] = clamp_bound(a.rowptr[r0 + i]);
+    if (a.beta != 0.f)
+        for (int i = tid + WG; i < nr; i += WG) y0_l[i] = a.y[r0 + i];
+    if (MERGE && tid == 0) seg[nseg] = k1 - k0a;
     __syncthreads();
 
     // ---- 2. rows
-    const RowOut o{a.y, a.carry_row, a.carry_val, a.alpha, a.beta};
+    const RowOut o{a.y, y0_l, a.carry_row, a.carry_val, a.alpha, a.beta};
     tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
 }
 
 // Row blocks with x served from LDS.  The analysis has listed, for every row block, the
-// distinct aligned 16-byte vectors of x that its entries touch (xv_start) and has replaced each
-// entry's 32-bit column by a 16-bit position in that list (lidx).  A workgroup
+// distinct aligned 16-byte vectors of x that its entries touch (xv_pad: one fixed-size slice per
+// block, so a lane knows where its vector's address is before any descriptor has arrived) and
+// has replaced each entry's 32-bit column by a 16-bit position in that list (lidx).  A workgroup
 //   1. copies its block's x vectors to LDS (one 128-bit load per vector, coalesced wherever
 //      the block's columns are contiguous) together with the block's slice of vals and lidx,
 //   2. runs the same row phase as the tile kernel, every operand now coming out of LDS.
@@ -572,8 +586,6 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     const int nr = a.part_row[part + 1] - r0;
     const int k0 = a.part_nz[part];
     const int k1 = a.part_nz[part + 1];
-    const int v0 = a.xv_ptr[part];
-    const int nv = a.xv_ptr[part + 1] - v0;
     if (k1 - k0 > a.tile_cap) {
         long_row<T, WG>(a, r0, k0, k1, wave_part, tid);
         return;
@@ -585,7 +597,8 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     E* xbuf = reinterpret_cast<E*>(smem_raw);  // x_cap vectors
     E* vals_l = reinterpret_cast<E*>(smem_raw + 16 * a.x_cap);
     uint16_t* lidx_l = reinterpret_cast<uint16_t*>(smem_raw + 16 * a.x_cap + sizeof(E) * slots);
-    int* seg = reinterpret_cast<int*>(smem_raw + 16 * a.x_cap + (sizeof(E) + sizeof(uint16_t)) * slots);
+    int* seg = reinterpret_cast<int*>(smem_raw + 16 * a.x_cap + (sizeof(E) + sizeof(uint16_t)) * slots);  // nr + 1
+    float* y0_l = reinterpret_cast<float*>(seg + nr + 1);                                                   // nr
 
     // Every load of the common path below is unconditional, in straight-line code: a lane with
     // nothing to fetch reads the start of lidx instead (always allocated, 16-byte aligned, at
@@ -598,11 +611,13 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
 #pragma unroll
     for (int u = 0; u < XPL; ++u) {
         const int i = tid + u * WG;
-        const int32_t* src = i < nv ? a.xv_start + v0 + i : reinterpret_cast<const int32_t*>(dummy);
+        const int32_t* src = i < a.x_cap ? a.xv_pad + part * a.x_cap + i : reinterpret_cast<const int32_t*>(dummy);
         xs[u] = *src;
-        xs[u] = i < nv ? xs[u] : -1;
+        xs[u] = i < a.x_cap ? xs[u] : -1;
     }
-    const int rp0 = a.rowptr[r0 + (tid < nr ? tid : nr)];
+    const int rp0 = a.rowptr[r0 + (tid < nr ? tid : nr)];  // bound nr is k1: no load needed for it
+    const float* const y_src = (a.beta != 0.f && tid < nr) ? a.y + r0 + tid : reinterpret_cast<const float*>(dummy);
+    const float y0v = *y_src;
 
     // A group is 8 consecutive entries: one 128-bit vector of lidx, one (bf16) or two (binary32)
     // of vals.  Groups that reach past the last whole vector of the arrays, and everything when
@@ -651,7 +666,9 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     }
 
     if (tid == 0) n_deferred = 0;
-    if (tid <= nr) seg[tid] = rp0 - k0a;
+    if (tid < nr) seg[tid] = rp0 - k0a;
+    if (tid == 0) seg[nr] = k1 - k0a;
+    if (tid < nr) y0_l[tid] = y0v;
 #pragma unroll
     for (int u = 0; u < NG; ++u) store_group((tid + u * WG) * 8, g[u]);
 #pragma unroll
@@ -664,7 +681,9 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
         }
     }
     // what the fixed-size first round did not cover (blocks of more than WG rows or NG*WG*8 entries)
-    for (int i = tid + WG; i <= nr; i += WG) seg[i] = a.rowptr[r0 + i] - k0a;
+    for (int i = tid + WG; i < nr; i += WG) seg[i] = a.rowptr[r0 + i] - k0a;
+    if (a.beta != 0.f)
+        for (int i = tid + WG; i < nr; i += WG) y0_l[i] = a.y[r0 + i];
     for (int off = (tid + NG * WG) * 8; off < span; off += WG * 8) {
         Group h;
         load_group(off, h);
@@ -673,14 +692,15 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     __syncthreads();
 
     // ---- 2. rows
-    const RowOut o{a.y, a.carry_row, a.carry_val, a.alpha, a.beta};
+    const RowOut o{a.y, y0_l, a.carry_row, a.carry_val, a.alpha, a.beta};
     tile_rows<false, WG>(lidx_l, vals_l, xbuf, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
 }
 
 // Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
 // keys = colidx >> shift of the block's entries, sorted in LDS (bitonic network over the next
 // power of two), duplicates dropped.  count pass (fill == 0): nv[b] = number of distinct keys.
-// fill pass: xv_start[xv_ptr[b] + j] = j-th key << shift, and for every entry
+// fill pass: xv_start[xv_ptr[b] + j] = xv_pad[b * x_cap + j] = j-th key << shift (the rest of the
+// block's xv_pad slice is -1), and for every entry
 // lidx[k] = rank of its key * 2^shift + colidx[k] mod 2^shift.  A block with more than tile_cap
 // entries (one over-long row) gets nv = 0 and lidx = 0.  The fill pass is only launched when
 // every nv[b] <= kMaxXVectors.
@@ -688,7 +708,8 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
                                                            const int32_t* __restrict__ colidx, int tile_cap, int shift,
                                                            int fill, int32_t* __restrict__ nv,
                                                            const int32_t* __restrict__ xv_ptr,
-                                                           int32_t* __restrict__ xv_start, uint16_t* __restrict__ lidx) {
+                                                           int32_t* __restrict__ xv_start, int32_t* __restrict__ xv_pad,
+                                                           int x_cap, uint16_t* __restrict__ lidx) {
     __shared__ uint32_t keys[kMaxTileEntries];
     __shared__ uint32_t uniq[kMaxXVectors];
     __shared__ int counts[256];
@@ -698,8 +719,10 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
     const int cnt = k1 - k0;
     if (cnt > tile_cap || cnt > kMaxTileEntries || cnt == 0) {
         if (!fill && tid == 0) nv[b] = 0;
-        if (fill)
+        if (fill) {
             for (int i = tid; i < cnt; i += 256) lidx[k0 + i] = 0;
+            for (int i = tid; i < x_cap; i += 256) xv_pad[b * x_cap + i] = -1;
+        }
         return;
     }
     int P = 256;
@@ -749,6 +772,7 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
     __syncthreads();
     const int v0 = xv_ptr[b];
     for (int i = tid; i < total; i += 256) xv_start[v0 + i] = static_cast<int32_t>(uniq[i] << shift);
+    for (int i = tid; i < x_cap; i += 256) xv_pad[b * x_cap + i] = i < total ? static_cast<int32_t>(uniq[i] << shift) : -1;
     const uint32_t low = (1u << shift) - 1u;
     for (int i = tid; i < cnt; i += 256) {
         const uint32_t c = static_cast<uint32_t>(colidx[k0 + i]);
@@ -876,7 +900,14 @@ namespace {
 template <typename T>
 size_t tile_lds_bytes(int entries, int bounds) {
     return (sizeof(int) + sizeof(typename T::elem)) * static_cast<size_t>(entries + 2 * T::VEC) +
-           sizeof(int) * static_cast<size_t>(bounds + 2);
+           (sizeof(int) + sizeof(float)) * static_cast<size_t>(bounds + 2);
+}
+
+template <typename T>
+size_t merge_lds_bytes(int items) {
+    const size_t per_entry = sizeof(int) + sizeof(typename T::elem);
+    const size_t per_row = sizeof(int) + sizeof(float);
+    return (per_entry > per_row ? per_entry : per_row) * static_cast<size_t>(items + 2 * T::VEC) + 4 * per_row;
 }
 
 template <typename T, bool MERGE, int WG>
@@ -971,24 +1002,24 @@ hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const
     a.nparts = nb;
     a.tile_cap = block_nnz;
     a.team_bias = team_bias_from_env();
-    a.xv_ptr = w.xv_ptr;
-    a.xv_start = w.xv_start;
+    a.xv_pad = w.xv_pad;
     a.lidx = w.lidx;
     a.x_cap = w.max_vectors > 0 ? w.max_vectors : 1;
     a.x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 ? 1 : 0;
     const size_t esz = A.bf16 ? 2 : 4;
     const size_t lds = 16 * static_cast<size_t>(a.x_cap) + (esz + 2) * static_cast<size_t>(block_nnz + 16) +
-                       sizeof(int) * static_cast<size_t>(rows_max + 2);
+                       (sizeof(int) + sizeof(float)) * static_cast<size_t>(rows_max + 2);
     if (A.bf16) return launch_window_t<BF16>(a, lds, st);
     return launch_window_t<F32>(a, lds, st);
 }
 
 hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int32_t nb, int32_t block_nnz, bool fill,
-                               int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, uint16_t* lidx, hipStream_t st) {
+                               int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, int32_t* xv_pad, int32_t x_cap,
+                               uint16_t* lidx, hipStream_t st) {
     if (nb <= 0) return hipSuccess;
     const int shift = A.bf16 ? 3 : 2;
     hipLaunchKernelGGL(window_build_kernel, dim3(nb), dim3(256), 0, st, block_nz, A.colidx, block_nnz, shift,
-                       fill ? 1 : 0, nv, xv_ptr, xv_start, lidx);
+                       fill ? 1 : 0, nv, xv_ptr, xv_start, xv_pad, x_cap, lidx);
     return hipGetLastError();
 }
 
@@ -1004,13 +1035,13 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_
     a.nparts = P;
     a.tile_cap = items_per_chunk;
     a.team_bias = team_bias_from_env();
-    // entries + finished rows of a chunk add up to at most items_per_chunk; an entry needs more
-    // LDS than a bound, so the all-entries chunk is the worst case (one bound more for the carry)
+    // entries + finished rows of a chunk add up to at most items_per_chunk; size for whichever of
+    // the two needs more LDS per item (an entry: colidx + value; a row: bound + old y)
     hipError_t e;
     if (A.bf16)
-        e = launch_tiles<BF16, true>(a, tile_lds_bytes<BF16>(items_per_chunk, 2), st);
+        e = launch_tiles<BF16, true>(a, merge_lds_bytes<BF16>(items_per_chunk), st);
     else
-        e = launch_tiles<F32, true>(a, tile_lds_bytes<F32>(items_per_chunk, 2), st);
+        e = launch_tiles<F32, true>(a, merge_lds_bytes<F32>(items_per_chunk), st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(merge_fixup_kernel, dim3(ceil_div(P, kWG)), dim3(kWG), 0, st, carry_row, carry_val, P, y, s.alpha);
     return hipGetLastError();

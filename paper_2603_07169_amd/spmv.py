@@ -50,7 +50,7 @@ class spmv_analysis_info_t(C.Structure):
 class spmv_analysis_host_t(C.Structure):
     _fields_ = [("bin_count", C.c_void_p), ("bin_offset", C.c_void_p), ("bin_rows", C.c_void_p),
                 ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
-                ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("lidx", C.c_void_p)]
+                ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p)]
 
 
 class SpmvError(RuntimeError):
@@ -149,6 +149,7 @@ def _host_buffers(info):
     }
     if info.plan == SPMV_PLAN_WINDOWED:
         bufs.update(xv_ptr=np.zeros(info.num_row_blocks + 1, np.int32), xv_start=np.zeros(info.num_x_vectors, np.int32),
+                    xv_pad=np.zeros(info.num_row_blocks * max(1, info.max_x_vectors), np.int32),
                     lidx=np.zeros(info.nnz, np.uint16))
     out = spmv_analysis_host_t(**{k: v.ctypes.data for k, v in bufs.items()})
     return bufs, out

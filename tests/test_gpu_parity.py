@@ -181,6 +181,12 @@ def check_windows_equal_oracle(p, A):
     assert np.array_equal(got["xv_ptr"], xv_ptr)
     assert np.array_equal(got["xv_start"], xv_start)
     assert np.array_equal(got["lidx"], lidx)
+    # the fixed-stride copy: block b's vectors at b*V, then -1
+    V = max(1, int(A.info.max_x_vectors))
+    pad = np.full((nv.size, V), -1, np.int32)
+    for b in range(nv.size):
+        pad[b, :nv[b]] = xv_start[xv_ptr[b]:xv_ptr[b + 1]]
+    assert np.array_equal(got["xv_pad"].reshape(nv.size, V), pad)
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])

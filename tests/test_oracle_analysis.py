@@ -238,7 +238,9 @@ def test_x_windows_closed_form_counts():
 
 def test_window_choice_rule():
     assert oracle.window_choice([10, 10], 80)
-    assert not oracle.window_choice([10, 11], 80)          # fewer than four entries per vector
+    assert not oracle.window_choice([10, 11], 80)          # 4 * 2 blocks * 11 slots > 80 entries
     assert not oracle.window_choice([1025, 0], 1 << 20)    # a block's vectors exceed the buffer
     assert oracle.window_choice([1024, 0], 1 << 20)
     assert not oracle.window_choice([], 0)
+    assert not oracle.window_choice([1, 100], 500)         # the stride is the largest count: 4 * 2 * 100 > 500
+    assert oracle.window_choice([1, 100], 800)
