@@ -41,6 +41,7 @@ struct spmv_csr_s {
     int32_t* d_bin_rows = nullptr;
     int32_t* d_row_blocks = nullptr;
     int32_t* d_block_nz = nullptr;  // rowptr[row_blocks[b]]: spares the kernels a dependent load
+    int32_t max_block_entries = 0;  // most entries of any row block that is not a single over-long row
     int32_t* d_mp_row = nullptr;
     int32_t* d_mp_nz = nullptr;
     int32_t* d_carry_row = nullptr;
@@ -212,6 +213,11 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         try {
             std::vector<int32_t> block_nz(a.row_blocks.size());
             for (size_t b = 0; b < block_nz.size(); ++b) block_nz[b] = rowptr_host[static_cast<size_t>(a.row_blocks[b])];
+            h->max_block_entries = 0;
+            for (size_t b = 0; b + 1 < block_nz.size(); ++b) {
+                const int32_t entries = block_nz[b + 1] - block_nz[b];
+                if (entries <= a.info.block_nnz && entries > h->max_block_entries) h->max_block_entries = entries;
+            }
             st = upload(block_nz, &h->d_block_nz);
         } catch (const std::bad_alloc&) {
             st = SPMV_ERR_ALLOC;
@@ -285,7 +291,7 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
         case SPMV_PLAN_WINDOWED: {
             const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx, h->info.max_x_vectors};
             e = spmv::launch_windowed(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
-                                      h->info.block_nnz, h->info.rows_max, w, x, y, s, st);
+                                      h->info.block_nnz, h->max_block_entries, h->info.rows_max, w, x, y, s, st);
             break;
         }
         case SPMV_PLAN_MERGE:

@@ -41,10 +41,11 @@ hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, in
 // block_nnz, rows_max: the limits the partition was built with.
 hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
                            int32_t block_nnz, int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st);
-// The adaptive plan with x served from per-block windows in LDS.
+// The adaptive plan with x served from per-block windows in LDS.  staged_max: the most entries
+// of any block that is staged (i.e. not a single over-long row); <= block_nnz.
 hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
-                           int32_t block_nnz, int32_t rows_max, const XWindows& w, const void* x, float* y, Scalars s,
-                           hipStream_t st);
+                           int32_t block_nnz, int32_t staged_max, int32_t rows_max, const XWindows& w, const void* x,
+                           float* y, Scalars s, hipStream_t st);
 // Analysis-time construction of the x windows.  fill == false: nv[b] = distinct x vectors of
 // block b.  fill == true: writes xv_start, xv_pad (stride x_cap >= every nv[b]) and lidx given
 // xv_ptr = exclusive prefix sums of nv.

@@ -250,7 +250,6 @@ struct TileArgs {
     float* carry_val;         // merge path only, [nparts]
     int32_t nparts, m, n, nnz;
     int32_t tile_cap;         // most entries a tile can hold (a row block may exceed it only as a single row)
-    int32_t team_bias;        // log2 factor applied to the lanes-per-row choice (0 = default)
     float alpha, beta;
     int32_t vec_ok;
     // x windows (window kernel only)
@@ -388,18 +387,23 @@ __device__ __forceinline__ void tile_rows_g(const I* cols, const E* vals, const 
 }
 
 // Lanes per row from the tile's mean segment length: the largest power of two G <= 64 with
-// 16*G <= mean + 15, shifted by team_bias.  Small teams keep the lanes of a gather on
+// 16*G <= mean + 15.  Small teams keep the lanes of a gather on
 // neighbouring rows, which is what makes the gathers of banded matrices coalesce.
 template <bool MERGE, int WG, typename I, typename E>
 __device__ __forceinline__ void tile_rows(const I* cols, const E* vals, const E* x, const int* seg, int nr, int r0,
-                                          int part, int tile_nnz, int team_bias, const RowOut& o, int* deferred,
-                                          int* n_deferred, int tid) {
+                                          int part, int tile_nnz, const RowOut& o, int* deferred, int* n_deferred,
+                                          int tid) {
     const int nseg = nr + (MERGE ? 1 : 0);
     int G = 1;
     const int mean = nseg > 0 ? tile_nnz / nseg : 0;
     while (G < 64 && 16 * G < mean) G <<= 1;
-    if (team_bias > 0) G = (G << team_bias) > 64 ? 64 : (G << team_bias);
-    if (team_bias < 0) G = (G >> -team_bias) < 1 ? 1 : (G >> -team_bias);
+    if (sizeof(I) == 2 && mean >= 64) {
+        // x comes out of LDS (16-bit window positions): long rows get about four entries per lane.
+        // Fewer rows then share a wavefront, and rows whose length is a multiple of the 128-byte
+        // bank cycle would otherwise have all their teams on the same LDS banks.
+        G = 64;
+        while (4 * G > mean) G >>= 1;
+    }
     switch (G) {
         case 1: tile_rows_g<MERGE, WG, 1>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
         case 2: tile_rows_g<MERGE, WG, 2>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
@@ -554,7 +558,7 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
 
     // ---- 2. rows
     const RowOut o{a.y, y0_l, a.carry_row, a.carry_val, a.alpha, a.beta};
-    tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
+    tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
 }
 
 // Row blocks with x served from LDS.  The analysis has listed, for every row block, the
@@ -693,7 +697,7 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
 
     // ---- 2. rows
     const RowOut o{a.y, y0_l, a.carry_row, a.carry_val, a.alpha, a.beta};
-    tile_rows<false, WG>(lidx_l, vals_l, xbuf, seg, nr, r0, part, k1 - k0, a.team_bias, o, deferred, &n_deferred, tid);
+    tile_rows<false, WG>(lidx_l, vals_l, xbuf, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
 }
 
 // Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
@@ -927,16 +931,8 @@ hipError_t launch_tiles_wg(const TileArgs& a, size_t lds, hipStream_t st) {
     return hipGetLastError();
 }
 
-// Workgroup size of the tile kernel (256 unless overridden for experiments).
 template <typename T, bool MERGE>
 hipError_t launch_tiles(const TileArgs& a, size_t lds, hipStream_t st) {
-    static const int forced_wg = [] {
-        const char* e = getenv("SPMV_TILE_WG");  // experiments only
-        return e ? atoi(e) : 0;
-    }();
-    const int wg = forced_wg ? forced_wg : 256;
-    if (wg <= 64) return launch_tiles_wg<T, MERGE, 64>(a, lds, st);
-    if (wg <= 128) return launch_tiles_wg<T, MERGE, 128>(a, lds, st);
     return launch_tiles_wg<T, MERGE, 256>(a, lds, st);
 }
 
@@ -958,21 +954,13 @@ hipError_t launch_window_k(const TileArgs& a, size_t lds, hipStream_t st) {
 
 // Picks the instantiation whose fixed first round of loads just covers the blocks.
 template <typename T>
-hipError_t launch_window_t(const TileArgs& a, size_t lds, hipStream_t st) {
-    const bool one_group = a.tile_cap + 7 <= 256 * 8;
+hipError_t launch_window_t(const TileArgs& a, int staged_max, size_t lds, hipStream_t st) {
+    const bool one_group = staged_max + 7 <= 256 * 8;  // a block's span starts up to 7 entries early
     if (a.x_cap <= 256)
         return one_group ? launch_window_k<T, 1, 1>(a, lds, st) : launch_window_k<T, 1, 2>(a, lds, st);
     if (a.x_cap <= 512)
         return one_group ? launch_window_k<T, 2, 1>(a, lds, st) : launch_window_k<T, 2, 2>(a, lds, st);
     return one_group ? launch_window_k<T, 4, 1>(a, lds, st) : launch_window_k<T, 4, 2>(a, lds, st);
-}
-
-int team_bias_from_env() {
-    static const int bias = [] {
-        const char* e = getenv("SPMV_TEAM_BIAS");  // experiments only
-        return e ? atoi(e) : 0;
-    }();
-    return bias;
 }
 
 }  // namespace
@@ -985,32 +973,31 @@ hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const
     a.part_nz = block_nz;
     a.nparts = nb;
     a.tile_cap = block_nnz;
-    a.team_bias = team_bias_from_env();
     // a block stages at most block_nnz entries and has at most rows_max rows
     if (A.bf16) return launch_tiles<BF16, false>(a, tile_lds_bytes<BF16>(block_nnz, rows_max), st);
     return launch_tiles<F32, false>(a, tile_lds_bytes<F32>(block_nnz, rows_max), st);
 }
 
 hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
-                           int32_t block_nnz, int32_t rows_max, const XWindows& w, const void* x, float* y, Scalars s,
-                           hipStream_t st) {
+                           int32_t block_nnz, int32_t staged_max, int32_t rows_max, const XWindows& w, const void* x,
+                           float* y, Scalars s, hipStream_t st) {
     if (nb <= 0) return hipSuccess;
-    if (w.max_vectors > kMaxXVectors || block_nnz > kMaxTileEntries) return hipErrorInvalidValue;
+    if (w.max_vectors > kMaxXVectors || block_nnz > kMaxTileEntries || staged_max > block_nnz)
+        return hipErrorInvalidValue;
     TileArgs a = tile_args(A, x, y, s);
     a.part_row = row_blocks;
     a.part_nz = block_nz;
     a.nparts = nb;
     a.tile_cap = block_nnz;
-    a.team_bias = team_bias_from_env();
     a.xv_pad = w.xv_pad;
     a.lidx = w.lidx;
     a.x_cap = w.max_vectors > 0 ? w.max_vectors : 1;
     a.x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 ? 1 : 0;
     const size_t esz = A.bf16 ? 2 : 4;
-    const size_t lds = 16 * static_cast<size_t>(a.x_cap) + (esz + 2) * static_cast<size_t>(block_nnz + 16) +
+    const size_t lds = 16 * static_cast<size_t>(a.x_cap) + (esz + 2) * static_cast<size_t>(staged_max + 16) +
                        (sizeof(int) + sizeof(float)) * static_cast<size_t>(rows_max + 2);
-    if (A.bf16) return launch_window_t<BF16>(a, lds, st);
-    return launch_window_t<F32>(a, lds, st);
+    if (A.bf16) return launch_window_t<BF16>(a, staged_max, lds, st);
+    return launch_window_t<F32>(a, staged_max, lds, st);
 }
 
 hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int32_t nb, int32_t block_nnz, bool fill,
@@ -1034,7 +1021,6 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_
     a.carry_val = carry_val;
     a.nparts = P;
     a.tile_cap = items_per_chunk;
-    a.team_bias = team_bias_from_env();
     // entries + finished rows of a chunk add up to at most items_per_chunk; size for whichever of
     // the two needs more LDS per item (an entry: colidx + value; a row: bound + old y)
     hipError_t e;
