@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--vector-lanes", type=int, default=0)
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (skip the other configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the launch floor, the large uniform matrix and the paper-shaped sweep")
     ap.add_argument("--copies", type=int, default=0, help="override the number of rotating copies")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, used to scale "
@@ -146,9 +148,12 @@ def time_each(res, steps, rotate=True):
     return float(np.median(t)), float(t.min())
 
 
-def measure(k, args, params, with_parity=True):
+def measure(k, args, params):
     import workloads as w
-    p = w.config(k)
+    return measure_problem(w.config(k), args, params)
+
+
+def measure_problem(p, args, params):
     bytes_alg = p.algorithmic_bytes()
     copies = args.copies or (max(2, -(-ROTATE_TOTAL_BYTES // bytes_alg)) if bytes_alg < 2 * LLC_BYTES else 2)
     copies = min(copies, 64)
@@ -166,6 +171,48 @@ def measure(k, args, params, with_parity=True):
     }
     res.close()
     return p, out
+
+
+def launch_floor_us(n=200):
+    """Mean time of back-to-back launches of a one-wavefront kernel (the library's reduction
+    self-check): what any kernel pays before it moves a byte."""
+    import torch
+    import paper_2603_07169_amd as s
+    a = torch.zeros(64, dtype=torch.float32, device="cuda")
+    b = torch.zeros(14 * 64, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+    for _ in range(10):
+        s.spmv_selftest_reduce(a.data_ptr(), b.data_ptr(), stream.cuda_stream)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(stream)
+    for _ in range(n):
+        s.spmv_selftest_reduce(a.data_ptr(), b.data_ptr(), stream.cuda_stream)
+    e1.record(stream)
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n * 1e3
+
+
+def paper_sweep(args):
+    """The workload the paper defines for this task (App. C task 12: rows 2^10..2^15, 2048 columns,
+    density 0.01, random positions), FP32 and bf16: speed-up S_i of the planned path over the
+    library's own one-lane-per-row kernel, and the paper's weighted score P (section 3.3, Eq. 2)
+    with the task's complexity O(nnz) as weight: P = sum nnz_i S_i / sum nnz_i."""
+    import workloads as w
+    out = {"cases": []}
+    for dtype in ("f32", "bf16"):
+        num = den = 0.0
+        for e in range(10, 16):
+            p = w.density_random(1 << e, 2048, 0.01, dtype=dtype)
+            _, planned = measure_problem(p, args, dict(plan=0))
+            _, naive = measure_problem(p, args, dict(plan=1))
+            S = naive["ms_per_step"] / planned["ms_per_step"]
+            out["cases"].append({"rows": 1 << e, "dtype": dtype, "nnz": p.nnz, "plan": planned["plan"],
+                                 "us": planned["ms_per_step"] * 1e3, "naive_us": naive["ms_per_step"] * 1e3, "S": S})
+            num += p.nnz * S
+            den += p.nnz
+        out["P_" + dtype] = num / den
+    return out
 
 
 def cpu_baseline(p):
@@ -225,6 +272,16 @@ def main():
                 _, r = measure(k, args, params)
                 per.append(r)
         line["per_config"] = sorted(per, key=lambda r: r["workload"])
+    if not args.only and not args.no_extras:
+        import workloads as w
+        line["launch_floor_us"] = launch_floor_us()
+        # not a config: config 1's generator at a size where the kernel streams instead of waiting for its launch
+        big = w.uniform_rows(1 << 22, 1 << 22, 16)
+        big.name = "supplementary_uniform16_4M_f32"
+        _, r = measure_problem(big, args, params)
+        del big
+        line["supplementary"] = r
+        line["paper_sweep"] = paper_sweep(args)
     print(json.dumps(line))
 
 

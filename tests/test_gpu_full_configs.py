@@ -56,6 +56,8 @@ def test_full_config_matches_oracle(k):
             assert xv_ptr[b + 1] - xv_ptr[b] == nv[0], b
             assert np.array_equal(got["xv_start"][xv_ptr[b]:xv_ptr[b + 1]], xs), b
             assert np.array_equal(got["lidx"][k0:k1], li[k0:k1]), b
+            V = int(A.info.max_x_vectors)
+            assert np.array_equal(got["xv_pad"][b * V:b * V + nv[0]], xs) and np.all(got["xv_pad"][b * V + nv[0]:(b + 1) * V] == -1), b
         A.close()
         # the tile kernel (global x gathers) on the same matrix, which AUTO no longer picks here
         A = d.matrix(dict(plan=s.SPMV_PLAN_ADAPTIVE))

@@ -222,6 +222,23 @@ def test_x_windows_ragged_and_long_rows():
             A.close()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("block_nnz", [2048, 4096, 8192])
+def test_windowed_large_windows(dtype, block_nnz):
+    """Random columns over a narrow x: blocks of thousands of entries touch 850..1000 distinct x
+    vectors, so a lane fetches up to four of them and stages more than one round of entry groups."""
+    n = 4000 if dtype == "f32" else 8000
+    p = w.uniform_rows(6000, n, 24, dtype=dtype)
+    d = DeviceProblem(p)
+    log("case windowed large windows", dtype, block_nnz)
+    A = d.matrix(dict(plan=6, block_nnz=block_nnz, rows_max=1024))
+    assert 512 < A.info.max_x_vectors <= 1024
+    y_ref, S_ref = reference(p)
+    assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True)
+    check_windows_equal_oracle(p, A)
+    A.close()
+
+
 def test_forced_windowed_rejects_blocks_with_too_many_vectors():
     p = w.uniform_rows(4096, 1 << 20, 16)  # 8192-entry blocks of random columns: about 8000 distinct vectors
     d = DeviceProblem(p)
