@@ -41,6 +41,8 @@ struct spmv_csr_s {
     int32_t* d_bin_rows = nullptr;
     int32_t* d_row_blocks = nullptr;
     int32_t* d_block_nz = nullptr;  // rowptr[row_blocks[b]]: spares the kernels a dependent load
+    int32_t* d_block_desc = nullptr;  // pairs (row_blocks[b], block_nz[b]): one scalar load per workgroup
+    int32_t* d_chunk_desc = nullptr;  // pairs (mp_row[p], mp_nz[p])
     int32_t max_block_entries = 0;  // most entries of any row block that is not a single over-long row
     int32_t* d_mp_row = nullptr;
     int32_t* d_mp_nz = nullptr;
@@ -57,12 +59,12 @@ namespace {
 void free_metadata(spmv_csr_s* h) {
     void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
                     h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
-                    h->d_xv_pad};
+                    h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
     h->d_carry_val = nullptr;
-    h->d_xv_ptr = h->d_xv_start = h->d_xv_pad = nullptr;
+    h->d_xv_ptr = h->d_xv_start = h->d_xv_pad = h->d_block_desc = h->d_chunk_desc = nullptr;
     h->d_lidx = nullptr;
     h->analyzed = false;
 }
@@ -219,6 +221,18 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
                 if (entries <= a.info.block_nnz && entries > h->max_block_entries) h->max_block_entries = entries;
             }
             st = upload(block_nz, &h->d_block_nz);
+            std::vector<int32_t> desc(2 * block_nz.size());
+            for (size_t b = 0; b < block_nz.size(); ++b) {
+                desc[2 * b] = a.row_blocks[b];
+                desc[2 * b + 1] = block_nz[b];
+            }
+            if (st == SPMV_OK) st = upload(desc, &h->d_block_desc);
+            desc.resize(2 * a.mp_row.size());
+            for (size_t q = 0; q < a.mp_row.size(); ++q) {
+                desc[2 * q] = a.mp_row[q];
+                desc[2 * q + 1] = a.mp_nz[q];
+            }
+            if (st == SPMV_OK) st = upload(desc, &h->d_chunk_desc);
         } catch (const std::bad_alloc&) {
             st = SPMV_ERR_ALLOC;
         }
@@ -285,17 +299,17 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
             break;
         }
         case SPMV_PLAN_ADAPTIVE:
-            e = spmv::launch_adaptive(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
+            e = spmv::launch_adaptive(A, h->d_block_desc, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->info.rows_max, x, y, s, st);
             break;
         case SPMV_PLAN_WINDOWED: {
             const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx, h->info.max_x_vectors};
-            e = spmv::launch_windowed(A, h->d_row_blocks, h->d_block_nz, static_cast<int32_t>(h->info.num_row_blocks),
+            e = spmv::launch_windowed(A, h->d_block_desc, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->max_block_entries, h->info.rows_max, w, x, y, s, st);
             break;
         }
         case SPMV_PLAN_MERGE:
-            e = spmv::launch_merge(A, h->d_mp_row, h->d_mp_nz, static_cast<int32_t>(h->info.num_chunks),
+            e = spmv::launch_merge(A, h->d_chunk_desc, static_cast<int32_t>(h->info.num_chunks),
                                    h->info.items_per_chunk, h->d_carry_row, h->d_carry_val, x, y, s, st);
             break;
         default:

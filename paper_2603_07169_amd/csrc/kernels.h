@@ -37,13 +37,13 @@ hipError_t launch_scalar(const MatrixView& A, const int32_t* rows, int32_t count
 // lanes: power of two in [2, 64].
 hipError_t launch_vector(const MatrixView& A, int lanes, const int32_t* rows, int32_t count, const void* x, float* y,
                          Scalars s, hipStream_t st);
-// row_blocks: device [nb+1]; block_nz: device [nb+1], block_nz[b] = rowptr[row_blocks[b]].
+// block_desc: device [2*(nb+1)], pairs (row_blocks[b], rowptr[row_blocks[b]]).
 // block_nnz, rows_max: the limits the partition was built with.
-hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+hipError_t launch_adaptive(const MatrixView& A, const int32_t* block_desc, int32_t nb,
                            int32_t block_nnz, int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st);
 // The adaptive plan with x served from per-block windows in LDS.  staged_max: the most entries
 // of any block that is staged (i.e. not a single over-long row); <= block_nnz.
-hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+hipError_t launch_windowed(const MatrixView& A, const int32_t* block_desc, int32_t nb,
                            int32_t block_nnz, int32_t staged_max, int32_t rows_max, const XWindows& w, const void* x,
                            float* y, Scalars s, hipStream_t st);
 // Analysis-time construction of the x windows.  fill == false: nv[b] = distinct x vectors of
@@ -52,8 +52,8 @@ hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const
 hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int32_t nb, int32_t block_nnz, bool fill,
                                int32_t* nv, const int32_t* xv_ptr, int32_t* xv_start, int32_t* xv_pad, int32_t x_cap,
                                uint16_t* lidx, hipStream_t st);
-// mp_row, mp_nz: device [P+1]; carry_row/carry_val: device [P] scratch owned by the handle.
-hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
+// chunk_desc: device [2*(P+1)], pairs (mp_row[p], mp_nz[p]); carry_row/carry_val: device [P] scratch owned by the handle.
+hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t P,
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
                         Scalars s, hipStream_t st);
 // flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).

@@ -239,24 +239,23 @@ __global__ __launch_bounds__(kWG) void spmv_vector_kernel(const int32_t* __restr
 
 // ------------------------------------------------------------------------------------------
 struct TileArgs {
+    // what a workgroup needs before its first vector load comes first, in one stretch
+    int32_t nparts, x_cap, tile_cap, nnz;
+    const int32_t* xv_pad;     // window kernel: [nparts * x_cap] first element of each 16-byte x vector of a block, -1 padded
+    const uint16_t* lidx;      // window kernel: [nnz, padded to a multiple of 8] position of each entry's x value in the block's window
+    const int32_t* part_desc;  // [2*(nparts+1)] pairs (row, entry): first row and first entry of each row block, or rows
+                               // finished and entries taken at each merge-path split
     const int32_t* rowptr;
-    const int32_t* colidx;
     const void* vals;
     const void* x;
     float* y;
-    const int32_t* part_row;  // [nparts+1] first row of each row block | rows finished at each merge-path split
-    const int32_t* part_nz;   // [nparts+1] entry index where each part starts (row blocks: rowptr[part_row[b]])
-    int32_t* carry_row;       // merge path only, [nparts]
-    float* carry_val;         // merge path only, [nparts]
-    int32_t nparts, m, n, nnz;
-    int32_t tile_cap;         // most entries a tile can hold (a row block may exceed it only as a single row)
+    int32_t n, m;
     float alpha, beta;
-    int32_t vec_ok;
-    // x windows (window kernel only)
-    const int32_t* xv_pad;    // [nparts * x_cap] first element of each 16-byte x vector of a block, -1 padded
-    const uint16_t* lidx;     // [nnz, padded to a multiple of 8] position of each entry's x value in the block's window
-    int32_t x_cap;            // most x vectors any row block has
-    int32_t x_vec_ok;         // x is 16-byte aligned
+    int32_t vec_ok;            // colidx and vals are 16-byte aligned
+    int32_t x_vec_ok;          // x is 16-byte aligned
+    const int32_t* colidx;
+    int32_t* carry_row;        // merge path only, [nparts]
+    float* carry_val;          // merge path only, [nparts]
 };
 
 // A single row longer than a tile: the whole workgroup strides over it.
@@ -394,15 +393,16 @@ __device__ __forceinline__ void tile_rows(const I* cols, const E* vals, const E*
                                           int part, int tile_nnz, const RowOut& o, int* deferred, int* n_deferred,
                                           int tid) {
     const int nseg = nr + (MERGE ? 1 : 0);
+    // With mean = floor(tile_nnz / nseg):  k < mean  <=>  (k + 1) * nseg <= tile_nnz  and
+    // k > mean  <=>  k * nseg > tile_nnz, so the choice needs no division.
     int G = 1;
-    const int mean = nseg > 0 ? tile_nnz / nseg : 0;
-    while (G < 64 && 16 * G < mean) G <<= 1;
-    if (sizeof(I) == 2 && mean >= 64) {
-        // x comes out of LDS (16-bit window positions): long rows get about four entries per lane.
-        // Fewer rows then share a wavefront, and rows whose length is a multiple of the 128-byte
-        // bank cycle would otherwise have all their teams on the same LDS banks.
+    while (G < 64 && nseg > 0 && (16 * G + 1) * nseg <= tile_nnz) G <<= 1;
+    if (sizeof(I) == 2 && nseg > 0 && tile_nnz >= 64 * nseg) {
+        // x comes out of LDS (16-bit window positions) and mean >= 64: long rows get about four
+        // entries per lane.  Fewer rows then share a wavefront, and rows whose length is a multiple
+        // of the 128-byte bank cycle would otherwise have all their teams on the same LDS banks.
         G = 64;
-        while (4 * G > mean) G >>= 1;
+        while (4 * G * nseg > tile_nnz) G >>= 1;
     }
     switch (G) {
         case 1: tile_rows_g<MERGE, WG, 1>(cols, vals, x, seg, nr, r0, part, o, deferred, n_deferred, tid); break;
@@ -441,10 +441,10 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
     const E* vals = static_cast<const E*>(a.vals);
     const E* x = static_cast<const E*>(a.x);
 
-    const int r0 = a.part_row[part];
-    const int nr = a.part_row[part + 1] - r0;
-    const int k0 = a.part_nz[part];
-    const int k1 = a.part_nz[part + 1];
+    const int r0 = a.part_desc[2 * part];  // one 16-byte scalar load: (r0, k0, r1, k1)
+    const int k0 = a.part_desc[2 * part + 1];
+    const int nr = a.part_desc[2 * part + 2] - r0;
+    const int k1 = a.part_desc[2 * part + 3];
 
     if constexpr (!MERGE) {
         if (k1 - k0 > a.tile_cap) {
@@ -586,17 +586,34 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     const E* vals = static_cast<const E*>(a.vals);
     const E* x = static_cast<const E*>(a.x);
 
-    const int r0 = a.part_row[part];
-    const int nr = a.part_row[part + 1] - r0;
-    const int k0 = a.part_nz[part];
-    const int k1 = a.part_nz[part + 1];
-    if (k1 - k0 > a.tile_cap) {
-        long_row<T, WG>(a, r0, k0, k1, wave_part, tid);
-        return;
-    }
+    // x vector addresses need only the block number.  With small windows (one vector per lane)
+    // they go out before the block's descriptor has arrived; with large windows the x gathers
+    // that follow them keep the address units busy for long, and measured best when they start
+    // after the entry stream has been requested, so there the addresses are fetched with the stream.
+    const uint16_t* const dummy = a.lidx;
+    int xs[XPL];
+    auto load_x_addresses = [&](int after) {  // after: 0, possibly obtained from a value the loads are to follow
+#pragma unroll
+        for (int u = 0; u < XPL; ++u) {
+            const int i = tid + u * WG;
+            const int32_t* src =
+                i < a.x_cap ? a.xv_pad + part * a.x_cap + i + after : reinterpret_cast<const int32_t*>(dummy);
+            xs[u] = *src;
+            xs[u] = i < a.x_cap ? xs[u] : -1;
+        }
+    };
+    if constexpr (XPL == 1) load_x_addresses(0);
+
+    const int r0 = a.part_desc[2 * part];  // one 16-byte scalar load: (r0, k0, r1, k1)
+    const int k0 = a.part_desc[2 * part + 1];
+    const int nr = a.part_desc[2 * part + 2] - r0;
+    const int k1 = a.part_desc[2 * part + 3];
+    // A block that is one over-long row stages nothing (span 0) and is taken from global memory
+    // after the barrier: no branch stands between the kernel's start and its loads.
+    const bool long_block = k1 - k0 > a.tile_cap;
 
     const int k0a = k0 & ~7;  // lidx vectors hold 8 entries
-    const int span = k1 - k0a;
+    const int span = long_block ? 0 : k1 - k0a;
     const int slots = (span + 7) & ~7;
     E* xbuf = reinterpret_cast<E*>(smem_raw);  // x_cap vectors
     E* vals_l = reinterpret_cast<E*>(smem_raw + 16 * a.x_cap);
@@ -610,14 +627,12 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     // loads only, so the order of issue is also the order of use:
     //   x vector addresses -> row bounds -> entry stream -> x vectors (need the addresses)
     //   -> LDS stores of the stream (while the x vectors are in flight) -> LDS stores of x.
-    const uint16_t* const dummy = a.lidx;
-    int xs[XPL];
-#pragma unroll
-    for (int u = 0; u < XPL; ++u) {
-        const int i = tid + u * WG;
-        const int32_t* src = i < a.x_cap ? a.xv_pad + part * a.x_cap + i : reinterpret_cast<const int32_t*>(dummy);
-        xs[u] = *src;
-        xs[u] = i < a.x_cap ? xs[u] : -1;
+    if constexpr (XPL > 1) {
+        // a zero the compiler cannot see through, produced from the descriptor: the address loads
+        // then really wait for it instead of being scheduled back to the top
+        int zero;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(zero) : "s"(k1));
+        load_x_addresses(zero);
     }
     const int rp0 = a.rowptr[r0 + (tid < nr ? tid : nr)];  // bound nr is k1: no load needed for it
     const float* const y_src = (a.beta != 0.f && tid < nr) ? a.y + r0 + tid : reinterpret_cast<const float*>(dummy);
@@ -660,6 +675,9 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
 #pragma unroll
     for (int u = 0; u < NG; ++u) load_group((tid + u * WG) * 8, g[u]);
 
+    // the instruction scheduler must not pull the address arithmetic of the x vectors (and the
+    // wait for xs that it needs) ahead of the stream loads
+    __builtin_amdgcn_sched_barrier(0);
     u32x4 xv[XPL];
     bool xvec[XPL];
 #pragma unroll
@@ -669,6 +687,7 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
         xv[u] = *reinterpret_cast<const u32x4*>(src);
     }
 
+    __builtin_amdgcn_sched_barrier(0);
     if (tid == 0) n_deferred = 0;
     if (tid < nr) seg[tid] = rp0 - k0a;
     if (tid == 0) seg[nr] = k1 - k0a;
@@ -696,6 +715,10 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     __syncthreads();
 
     // ---- 2. rows
+    if (long_block) {
+        long_row<T, WG>(a, r0, k0, k1, wave_part, tid);
+        return;
+    }
     const RowOut o{a.y, y0_l, a.carry_row, a.carry_val, a.alpha, a.beta};
     tile_rows<false, WG>(lidx_l, vals_l, xbuf, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
 }
@@ -965,12 +988,11 @@ hipError_t launch_window_t(const TileArgs& a, int staged_max, size_t lds, hipStr
 
 }  // namespace
 
-hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+hipError_t launch_adaptive(const MatrixView& A, const int32_t* block_desc, int32_t nb,
                            int32_t block_nnz, int32_t rows_max, const void* x, float* y, Scalars s, hipStream_t st) {
     if (nb <= 0) return hipSuccess;
     TileArgs a = tile_args(A, x, y, s);
-    a.part_row = row_blocks;
-    a.part_nz = block_nz;
+    a.part_desc = block_desc;
     a.nparts = nb;
     a.tile_cap = block_nnz;
     // a block stages at most block_nnz entries and has at most rows_max rows
@@ -978,15 +1000,14 @@ hipError_t launch_adaptive(const MatrixView& A, const int32_t* row_blocks, const
     return launch_tiles<F32, false>(a, tile_lds_bytes<F32>(block_nnz, rows_max), st);
 }
 
-hipError_t launch_windowed(const MatrixView& A, const int32_t* row_blocks, const int32_t* block_nz, int32_t nb,
+hipError_t launch_windowed(const MatrixView& A, const int32_t* block_desc, int32_t nb,
                            int32_t block_nnz, int32_t staged_max, int32_t rows_max, const XWindows& w, const void* x,
                            float* y, Scalars s, hipStream_t st) {
     if (nb <= 0) return hipSuccess;
     if (w.max_vectors > kMaxXVectors || block_nnz > kMaxTileEntries || staged_max > block_nnz)
         return hipErrorInvalidValue;
     TileArgs a = tile_args(A, x, y, s);
-    a.part_row = row_blocks;
-    a.part_nz = block_nz;
+    a.part_desc = block_desc;
     a.nparts = nb;
     a.tile_cap = block_nnz;
     a.xv_pad = w.xv_pad;
@@ -1010,13 +1031,12 @@ hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int
     return hipGetLastError();
 }
 
-hipError_t launch_merge(const MatrixView& A, const int32_t* mp_row, const int32_t* mp_nz, int32_t P,
+hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t P,
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
                         Scalars s, hipStream_t st) {
     if (P <= 0) return hipSuccess;
     TileArgs a = tile_args(A, x, y, s);
-    a.part_row = mp_row;
-    a.part_nz = mp_nz;
+    a.part_desc = chunk_desc;
     a.carry_row = carry_row;
     a.carry_val = carry_val;
     a.nparts = P;
