@@ -15,7 +15,7 @@ import numpy as np
 
 _HERE = Path(__file__).resolve().parent
 LIB_PATH = _HERE / "liboracle.so"
-SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp"]
+SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp", _HERE / "spmm_oracle.cpp"]
 _lib = None
 
 NUM_BINS = 33
@@ -46,6 +46,8 @@ def _load():
         _lib.oracle_spmv_csr_f32.restype = C.c_int
         _lib.oracle_spmv_csr_bf16.argtypes = [i64, i64, vp, vp, vp, vp, vp, f32, f32, vp, vp]
         _lib.oracle_spmv_csr_bf16.restype = C.c_int
+        _lib.oracle_spmm_csr_f32.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, f32, f32, vp, vp]
+        _lib.oracle_spmm_csr_f32.restype = C.c_int
         _lib.oracle_row_stats.argtypes = [i64, vp, vp]
         _lib.oracle_row_stats.restype = None
         _lib.oracle_row_bins.argtypes = [i64, vp, vp, vp, vp]
@@ -107,6 +109,29 @@ def spmv_csr(dtype, m, n, rowptr, colidx, vals, x, y0=None, alpha=1.0, beta=0.0)
 def spmv_problem(p):
     """Oracle result for a workloads.CsrProblem-like object."""
     return spmv_csr(p.dtype, p.m, p.n, p.rowptr, p.colidx, p.vals, p.x, p.y0, p.alpha, p.beta)
+
+
+def spmm_csr(m, n, rowptr, colidx, vals, B, C0=None, alpha=1.0, beta=0.0):
+    """C <- alpha*A*B + beta*C0 for FP32 CSR A (m x n) and dense row-major B (n x K), possibly a
+    column slice of a wider array.  Returns (C_ref float64[m, K], S_ref float64[m, K])."""
+    lib = _load()
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32), _chk(vals, np.float32)
+    assert B.dtype == np.float32 and B.ndim == 2 and B.shape[0] == n and B.strides[1] == 4
+    K = B.shape[1]
+    ldb = B.strides[0] // 4
+    ldc = 0
+    if beta != 0.0:
+        assert C0.dtype == np.float32 and C0.shape == (m, K) and C0.strides[1] == 4
+        ldc = C0.strides[0] // 4
+    else:
+        C0 = None
+    Cr = np.empty((m, K), dtype=np.float64)
+    S = np.empty((m, K), dtype=np.float64)
+    rc = lib.oracle_spmm_csr_f32(m, n, K, _p(rowptr), _p(colidx), _p(vals), B.ctypes.data_as(C.c_void_p), ldb,
+                                 None if C0 is None else C0.ctypes.data_as(C.c_void_p), ldc, alpha, beta, _p(Cr), _p(S))
+    if rc != 0:
+        raise ValueError("malformed CSR input")
+    return Cr, S
 
 
 def row_stats(rowptr):

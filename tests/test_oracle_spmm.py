@@ -1,0 +1,87 @@
+"""Pins of the SpMM oracle (oracle/spmm_oracle.cpp): values fixed by a hand-worked example, by a
+dense matrix product, by the already pinned SpMV oracle (K = 1) and by algebraic identities."""
+import json
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as w
+
+
+def dense_of(p):
+    A = np.zeros((p.m, p.n), dtype=np.float64)
+    for i in range(p.m):
+        for e in range(p.rowptr[i], p.rowptr[i + 1]):
+            A[i, p.colidx[e]] += np.float64(p.vals[e])   # repeated columns add up
+    return A
+
+
+def rand_B(n, K, seed=0):
+    return np.random.default_rng(seed).uniform(-1, 1, (n, K)).astype(np.float32)
+
+
+def test_handworked(golden_dir):
+    h = json.loads((golden_dir / "spmm_3x4x2_handworked.json").read_text())
+    rp, ci = np.array(h["rowptr"], np.int32), np.array(h["colidx"], np.int32)
+    va, B, C0 = np.array(h["vals"], np.float32), np.array(h["B"], np.float32), np.array(h["C0"], np.float32)
+    C, S = oracle.spmm_csr(h["m"], h["n"], rp, ci, va, B)
+    assert np.array_equal(C, np.array(h["AB"])) and np.array_equal(S, np.array(h["S"]))
+    C, S = oracle.spmm_csr(h["m"], h["n"], rp, ci, va, B, C0, h["alpha"], h["beta"])
+    assert np.array_equal(C, np.array(h["C"])) and np.array_equal(S, np.array(h["S"]))
+    # beta == 0 must not read C0: NaN there does not propagate
+    C, _ = oracle.spmm_csr(h["m"], h["n"], rp, ci, va, B, np.full((3, 2), np.nan, np.float32), 1.0, 0.0)
+    assert np.array_equal(C, np.array(h["AB"]))
+
+
+@pytest.mark.parametrize("K", [1, 3, 16, 37])
+def test_against_dense_product(K):
+    for p in [w.uniform_rows(40, 30, 5), w.powerlaw(60), w.laplace2d(6)] + w.tiny_adversarial()[:5]:
+        B = rand_B(p.n, K, seed=K)
+        C0 = rand_B(p.m, K, seed=K + 100)
+        C, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B, C0, 1.5, -0.25)
+        A = dense_of(p)
+        want = 1.5 * (A @ B.astype(np.float64)) - 0.25 * C0.astype(np.float64)
+        assert np.allclose(C, want, rtol=0, atol=1e-12 * (1 + np.abs(want).max())), p.name
+        assert np.all(S + 1e-300 >= np.abs(A @ B.astype(np.float64)) - 1e-12)   # triangle inequality
+
+
+def test_single_column_is_the_spmv_oracle():
+    p = w.powerlaw(300)
+    B = p.x.reshape(-1, 1).copy()
+    y0 = p.y0 if p.y0 is not None else np.zeros(p.m, np.float32)
+    C, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B, y0.reshape(-1, 1).copy(), 0.75, 2.0)
+    y, Sy = oracle.spmv_csr("f32", p.m, p.n, p.rowptr, p.colidx, p.vals, p.x, y0, 0.75, 2.0)
+    assert np.array_equal(C[:, 0], y) and np.array_equal(S[:, 0], Sy)
+
+
+def test_identity_matrix_copies_B_and_slices_use_ldb():
+    n, K = 17, 9
+    rp = np.arange(n + 1, dtype=np.int32)
+    ci = np.arange(n, dtype=np.int32)
+    va = np.ones(n, np.float32)
+    wide = rand_B(n, 3 * K, seed=5)
+    B = wide[:, K:2 * K]                       # a column slice: leading dimension 3K
+    C, S = oracle.spmm_csr(n, n, rp, ci, va, B)
+    assert np.array_equal(C, B.astype(np.float64)) and np.array_equal(S, np.abs(B.astype(np.float64)))
+    # a permutation matrix permutes the rows of B
+    perm = np.random.default_rng(2).permutation(n).astype(np.int32)
+    C, _ = oracle.spmm_csr(n, n, rp, perm, va, B)
+    assert np.array_equal(C, B[perm].astype(np.float64))
+
+
+def test_linearity_in_B_and_rejects_bad_columns():
+    p = w.uniform_rows(50, 64, 7)
+    B1, B2 = rand_B(p.n, 5, 1), rand_B(p.n, 5, 2)
+    # exactly representable combination: B1 + 2*B2 computed in float64 then checked on the double results
+    C1, _ = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B1)
+    C2, _ = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B2)
+    B3 = (B1.astype(np.float64) + 2 * B2.astype(np.float64)).astype(np.float32)
+    exact = B3.astype(np.float64) == B1.astype(np.float64) + 2 * B2.astype(np.float64)
+    C3, _ = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B3)
+    cols_exact = exact.all(axis=0)
+    assert np.allclose(C3[:, cols_exact], (C1 + 2 * C2)[:, cols_exact], rtol=0, atol=1e-12)
+    bad = p.colidx.copy()
+    bad[3] = p.n
+    with pytest.raises(ValueError):
+        oracle.spmm_csr(p.m, p.n, p.rowptr, bad, p.vals, B1)
