@@ -151,6 +151,21 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
  * Errors: INVALID_ARG (null x or y with m, n > 0), NOT_ANALYZED, HIP (launch failure). */
 spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha, float beta, void* stream);
 
+/* Sparse times dense (paper App. C task 13: C = A B, A in CSR, B of shape cols x K), in the BLAS
+ * form  C <- alpha * A * B + beta * C,  enqueued on `stream`.
+ *   h    a handle created with SPMV_F32 and analyzed (the analysis validates the structure; the
+ *        product itself uses rowptr / colidx / vals as they are).
+ *   B    device float, n rows of K used columns, row-major, leading dimension ldb >= K.
+ *   C    device float, m rows of K used columns, row-major, leading dimension ldc >= K; read only
+ *        if beta != 0 (or when n exceeds 2048, where B is taken in several passes that accumulate
+ *        into C).  B and C must not overlap.
+ * 128-bit accesses are used when B and C are 16-byte aligned and ldb, ldc are multiples of 4;
+ * any other layout works element by element.  m == 0 or K == 0 is a no-op.
+ * Errors: INVALID_ARG (null B or C, K < 0, ldb or ldc < K), UNSUPPORTED (bf16 handle, K >= 2^31,
+ * pointers not 4-byte aligned), NOT_ANALYZED, HIP. */
+spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
+                           float beta, void* stream);
+
 /* Frees the handle and the library-owned device metadata.  spmv_destroy(NULL) is OK. */
 spmv_status_t spmv_destroy(spmv_handle_t h);
 

@@ -318,6 +318,21 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
 
+spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
+                           float beta, void* stream) {
+    if (!h) return SPMV_ERR_INVALID_ARG;
+    if (!h->analyzed) return SPMV_ERR_NOT_ANALYZED;
+    if (K < 0) return SPMV_ERR_INVALID_ARG;
+    if (h->dtype != SPMV_F32 || K > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    if (h->m == 0 || K == 0) return SPMV_OK;
+    if (!C || ldc < K) return SPMV_ERR_INVALID_ARG;
+    if (h->n > 0 && (!B || ldb < K)) return SPMV_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(B) % 4 || reinterpret_cast<uintptr_t>(C) % 4) return SPMV_ERR_UNSUPPORTED;
+    const hipError_t e = spmv::launch_spmm(view_of(h), B, ldb, C, ldc, static_cast<int32_t>(K), spmv::Scalars{alpha, beta},
+                                           static_cast<hipStream_t>(stream));
+    return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
+}
+
 spmv_status_t spmv_destroy(spmv_handle_t h) {
     if (!h) return SPMV_OK;
     free_metadata(h);

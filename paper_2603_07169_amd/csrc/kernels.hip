@@ -25,6 +25,10 @@ namespace {
 constexpr int kWG = 256;   // threads per workgroup = 4 wavefronts of 64
 constexpr int kXcds = 8;   // accelerator dies; workgroup ids are dealt round-robin over them
 constexpr int kMaxDeferred = 136;
+constexpr int kSpmmWG = 512;     // SpMM: 8 wavefronts per workgroup
+constexpr int kSpmmKT = 16;      // SpMM: columns of B and C a workgroup owns (4 lanes x float4 per row)
+constexpr int kSpmmNB = 2048;    // SpMM: rows of B held in LDS at a time (2048 x 16 floats = 128 KB)
+constexpr int kSpmmPiece = 256;  // SpMM: entries of A a wavefront stages at a time
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -814,6 +818,120 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// C <- alpha*A*B + beta*C with A in CSR (FP32), B (n x K) and C (m x K) dense, row-major
+// (paper App. C task 13).  Every stored entry a_ij adds a_ij * B[j, :] to C[i, :], so the
+// operation reads a K-wide row of B per entry: nnz * K * 4 bytes in all, far more than B itself
+// or than C.  Those reads are kept on chip: a workgroup owns kSpmmKT = 16 columns of B and C,
+// copies that slice of B (up to kSpmmNB = 2048 rows: 128 KB) into LDS once and then walks over
+// all its rows of A.  Four lanes serve a row (one float4 of the slice each), a wavefront
+// serves 16 rows at a time; the rows' entries are staged through a small per-wavefront LDS
+// buffer with coalesced loads so that no lane reads colidx/vals from memory entry by entry.
+// B wider than the LDS block is taken in several passes over A, accumulating into C.
+struct SpmmArgs {
+    const int32_t* rowptr;
+    const int32_t* colidx;
+    const float* vals;
+    const float* B;
+    float* C;
+    int64_t ldb, ldc;
+    int32_t m, n, K;
+    int32_t row_splits;  // gridDim.y: each takes an equal share of the rows
+    int32_t vec_ok;      // B and C 16-byte aligned, ldb and ldc multiples of 4
+    float alpha, beta;
+};
+
+__global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
+    constexpr int KT = kSpmmKT, NB = kSpmmNB, PIECE = kSpmmPiece, RPW = 64 / (KT / 4);
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* Bs = reinterpret_cast<float*>(smem_raw);                                        // [NB][KT]
+    int2* Ae = reinterpret_cast<int2*>(smem_raw + sizeof(float) * NB * KT);                // [waves][PIECE]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = lane & (KT / 4 - 1);  // which float4 of the slice
+    const int rsub = lane / (KT / 4);   // which of the wavefront's rows
+    int2* Aw = Ae + wave * PIECE;
+
+    const int k0 = blockIdx.x * KT;
+    const int kw = a.K - k0 < KT ? a.K - k0 : KT;  // live columns of this slice
+    const int row_lo = static_cast<int>(static_cast<int64_t>(a.m) * blockIdx.y / a.row_splits);
+    const int row_hi = static_cast<int>(static_cast<int64_t>(a.m) * (blockIdx.y + 1) / a.row_splits);
+    const bool full4 = a.vec_ok && 4 * q + 4 <= kw;  // this lane's float4 lies wholly inside the slice
+
+    for (int cb0 = 0; cb0 == 0 || cb0 < a.n; cb0 += NB) {
+        const int nbk = a.n - cb0 < NB ? a.n - cb0 : NB;  // rows of B in this block (0 when n == 0)
+        const bool one_block = a.n <= NB;
+        if (cb0 > 0) __syncthreads();  // the previous block is no longer read
+        for (int idx = tid; idx < nbk * (KT / 4); idx += kSpmmWG) {
+            const int j = idx / (KT / 4), qq = idx % (KT / 4);
+            const float* src = a.B + static_cast<size_t>(cb0 + j) * a.ldb + k0 + 4 * qq;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (a.vec_ok && 4 * qq + 4 <= kw) {
+                v = *reinterpret_cast<const f32x4*>(src);
+            } else {
+                for (int t = 0; t < 4; ++t)
+                    if (4 * qq + t < kw) v[t] = src[t];
+            }
+            *reinterpret_cast<f32x4*>(Bs + j * KT + 4 * qq) = v;
+        }
+        __syncthreads();
+
+        for (int base = row_lo + wave * RPW; base < row_hi; base += (kSpmmWG / 64) * RPW) {
+            const int r = base + rsub;
+            const bool live = r < row_hi;
+            const int rs = live ? a.rowptr[r] : 0;
+            const int re = live ? a.rowptr[r + 1] : 0;
+            const int e_lo = a.rowptr[base];  // the wavefront's rows cover one contiguous entry range
+            const int e_hi = a.rowptr[base + RPW < row_hi ? base + RPW : row_hi];
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int p0 = e_lo; p0 < e_hi; p0 += PIECE) {
+                const int pn = e_hi - p0 < PIECE ? e_hi - p0 : PIECE;
+                // LDS operations of one wavefront complete in order, so the reads below see these
+                // writes and the next piece's writes come after this piece's reads
+                for (int i = lane; i < pn; i += 64)
+                    Aw[i] = make_int2(a.colidx[p0 + i] - cb0, __float_as_int(a.vals[p0 + i]));
+                int e = (rs > p0 ? rs : p0) - p0;
+                const int hi = (re < p0 + pn ? re : p0 + pn) - p0;  // this row's entries inside the piece
+                if (one_block) {
+                    for (; e + 4 <= hi; e += 4) {  // four entries in flight
+                        int2 cv[4];
+                        f32x4 b[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) cv[u] = Aw[e + u];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) b[u] = *reinterpret_cast<const f32x4*>(Bs + cv[u].x * KT + 4 * q);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) acc += __int_as_float(cv[u].y) * b[u];
+                    }
+                    for (; e < hi; ++e) {
+                        const int2 cv = Aw[e];
+                        acc += __int_as_float(cv.y) * *reinterpret_cast<const f32x4*>(Bs + cv.x * KT + 4 * q);
+                    }
+                } else {
+                    for (; e < hi; ++e) {  // entries outside this block of columns are skipped
+                        const int2 cv = Aw[e];
+                        if (static_cast<unsigned>(cv.x) < static_cast<unsigned>(nbk))
+                            acc += __int_as_float(cv.y) * *reinterpret_cast<const f32x4*>(Bs + cv.x * KT + 4 * q);
+                    }
+                }
+            }
+            if (live && 4 * q < kw) {
+                float* dst = a.C + static_cast<size_t>(r) * a.ldc + k0 + 4 * q;
+                const bool first = cb0 == 0;
+                const bool reads_c = !first || a.beta != 0.f;
+                const float scale_c = first ? a.beta : 1.f;
+                if (full4) {
+                    f32x4 out = a.alpha * acc;
+                    if (reads_c) out += scale_c * *reinterpret_cast<const f32x4*>(dst);
+                    *reinterpret_cast<f32x4*>(dst) = out;
+                } else {
+                    for (int t = 0; t < 4; ++t)
+                        if (4 * q + t < kw) dst[t] = a.alpha * acc[t] + (reads_c ? scale_c * dst[t] : 0.f);
+                }
+            }
+        }
+    }
+}
+
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
 // are consecutive; the thread of the first of them sums the run in chunk order.
 __global__ __launch_bounds__(kWG) void merge_fixup_kernel(const int32_t* __restrict__ carry_row,
@@ -1053,6 +1171,45 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t 
     return hipGetLastError();
 }
 
+hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* C, int64_t ldc, int32_t K, Scalars s,
+                       hipStream_t st) {
+    if (A.m <= 0 || K <= 0) return hipSuccess;
+    if (A.bf16) return hipErrorInvalidValue;
+    SpmmArgs a{};
+    a.rowptr = A.rowptr;
+    a.colidx = A.colidx;
+    a.vals = static_cast<const float*>(A.vals);
+    a.B = B;
+    a.C = C;
+    a.ldb = ldb;
+    a.ldc = ldc;
+    a.m = A.m;
+    a.n = A.n;
+    a.K = K;
+    a.alpha = s.alpha;
+    a.beta = s.beta;
+    a.vec_ok = (reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldb % 4 == 0 &&
+                ldc % 4 == 0)
+                   ? 1
+                   : 0;
+    const int slices = ceil_div(K, kSpmmKT);
+    // one workgroup fits a CU (its B slice takes most of the LDS): aim at one per CU or more
+    int splits = slices >= 256 ? 1 : ceil_div(256, slices);
+    const int max_splits = ceil_div(A.m, 64 / (kSpmmKT / 4));
+    if (splits > max_splits) splits = max_splits;
+    a.row_splits = splits;
+    const size_t lds = sizeof(float) * kSpmmNB * kSpmmKT + sizeof(int2) * (kSpmmWG / 64) * kSpmmPiece;
+    static thread_local bool allowed = false;
+    if (!allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(spmm_csr_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+        if (e != hipSuccess) return e;
+        allowed = true;
+    }
+    hipLaunchKernelGGL(spmm_csr_kernel, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st) {
     if (A.nnz <= 0) return hipSuccess;
     int grid = ceil_div(A.nnz, kWG);
@@ -1070,5 +1227,6 @@ const char* scalar_kernel_name() { return "spmv_scalar_kernel"; }
 const char* vector_kernel_name() { return "spmv_vector_kernel"; }
 const char* tile_kernel_name() { return "spmv_tile_kernel"; }
 const char* window_kernel_name() { return "spmv_window_kernel"; }
+const char* spmm_kernel_name() { return "spmm_csr_kernel"; }
 
 }  // namespace spmv

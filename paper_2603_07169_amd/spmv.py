@@ -24,7 +24,7 @@ SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 
 EXPORTS = [
-    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmm_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
     "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce", "spmv_csr_main_kernel_name",
     "spmv_status_string", "spmv_last_hip_error",
 ]
@@ -77,6 +77,8 @@ def _load():
     lib.spmv_csr_create.argtypes = [C.POINTER(vp), i64, i64, i64, vp, vp, vp, C.c_int]
     lib.spmv_csr_analyze.argtypes = [vp, C.POINTER(spmv_analyze_params_t)]
     lib.spmv_csr_run.argtypes = [vp, vp, vp, f32, f32, vp]
+    lib.spmm_csr_run.argtypes = [vp, vp, i64, vp, i64, i64, f32, f32, vp]
+    lib.spmm_csr_run.restype = C.c_int
     lib.spmv_destroy.argtypes = [vp]
     lib.spmv_csr_get_analysis_info.argtypes = [vp, C.POINTER(spmv_analysis_info_t)]
     lib.spmv_csr_get_analysis.argtypes = [vp, C.POINTER(spmv_analysis_host_t)]
@@ -129,6 +131,11 @@ def spmv_csr_analyze(handle, params=None):
 
 def spmv_csr_run(handle, x, y, alpha, beta, stream=None):
     return _load().spmv_csr_run(handle, x, y, alpha, beta, stream)
+
+
+def spmm_csr_run(handle, B, ldb, C_, ldc, K, alpha, beta, stream=None):
+    """B, C_: device addresses of row-major float arrays with leading dimensions ldb, ldc."""
+    return _load().spmm_csr_run(handle, B, ldb, C_, ldc, K, alpha, beta, stream)
 
 
 def spmv_destroy(handle):
@@ -214,6 +221,12 @@ class CsrMatrix:
     def run(self, x_t, y_t, alpha=1.0, beta=0.0, stream=None):
         check(spmv_csr_run(self.handle, x_t.data_ptr() if x_t is not None else None, y_t.data_ptr(), alpha, beta,
                            stream), "spmv_csr_run")
+
+    def spmm(self, B_t, C_t, alpha=1.0, beta=0.0, stream=None):
+        """C_t <- alpha*A*B_t + beta*C_t for 2-D row-major torch tensors (column slices allowed)."""
+        assert B_t.stride(1) == 1 and C_t.stride(1) == 1 and B_t.shape[1] == C_t.shape[1]
+        check(spmm_csr_run(self.handle, B_t.data_ptr(), B_t.stride(0), C_t.data_ptr(), C_t.stride(0), B_t.shape[1],
+                           alpha, beta, stream), "spmm_csr_run")
 
     def analysis(self):
         st, bufs = spmv_csr_get_analysis(self.handle)

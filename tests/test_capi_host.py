@@ -22,8 +22,8 @@ def rowptr_of(lens):
 def test_library_exports_every_declared_symbol():
     header = (ROOT / "include" / "spmv_mi355.h").read_text()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(spmv_[a-z0-9_]+)\s*\(", header))
-    assert {"spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy"} <= declared
+    declared = set(re.findall(r"\b(sp(?:mv|mm)_[a-z0-9_]+)\s*\(", header))
+    assert {"spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmm_csr_run", "spmv_destroy"} <= declared
     lib = C.CDLL(str(s.library_path()))
     for name in sorted(declared):
         assert hasattr(lib, name), name

@@ -1,0 +1,139 @@
+"""GPU parity of spmm_csr_run (C <- alpha*A*B + beta*C, paper App. C task 13) against the oracle,
+element by element: |C - C_ref| <= 1e-5 * sum_e |a_ie b_ek| (plus the rounding of beta*C0 when beta != 0)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2603_07169_amd as s
+import workloads as w
+from gpu_util import DeviceProblem, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-5
+
+
+def log(*a):
+    print(*a, flush=True)
+
+
+def rand(shape, seed):
+    return np.random.default_rng(seed).uniform(-1, 1, shape).astype(np.float32)
+
+
+def run_spmm(p, B, C0, alpha, beta, lead_pad=0, offset=0, matrix_params=None):
+    """Runs the product on the device; B and C live in wider allocations (leading dimension K + lead_pad)
+    starting `offset` elements in, so that strided and misaligned layouts are exercised."""
+    d = DeviceProblem(p)
+    A = d.matrix(matrix_params)
+    K = B.shape[1]
+    ld = K + lead_pad
+    Bbuf = torch.zeros(p.n * ld + offset + 8, dtype=torch.float32, device="cuda")
+    Cbuf = torch.full((p.m * ld + offset + 8,), 7.0, dtype=torch.float32, device="cuda")
+    Bv = Bbuf[offset:offset + p.n * ld].view(p.n, ld)[:, :K]
+    Cv = Cbuf[offset:offset + p.m * ld].view(p.m, ld)[:, :K]
+    Bv.copy_(torch.from_numpy(B))
+    Cv.copy_(torch.from_numpy(C0))
+    A.spmm(Bv, Cv, alpha, beta)
+    torch.cuda.synchronize()
+    out = Cv.cpu().numpy()
+    if lead_pad:  # the padding columns of C are not touched
+        pad = Cbuf[offset:offset + p.m * ld].view(p.m, ld)[:, K:].cpu().numpy()
+        assert np.all(pad == 7.0)
+    A.close()
+    return out
+
+
+def check(p, K, alpha=1.0, beta=0.0, seed=0, **kw):
+    B, C0 = rand((p.n, K), seed), rand((p.m, K), seed + 1)
+    C = run_spmm(p, B, C0, alpha, beta, **kw)
+    C_ref, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B, C0, alpha, beta)
+    bound = TOL * (abs(alpha) * S + (np.abs(np.float64(np.float32(beta)) * C0) if beta != 0 else 0.0))
+    err = np.abs(C.astype(np.float64) - C_ref)
+    bad = np.argwhere(~(err <= bound))
+    assert bad.size == 0, (p.name, K, bad[:3].tolist(), err[tuple(bad[0])], bound[tuple(bad[0])])
+
+
+@pytest.mark.parametrize("K", [1, 3, 4, 15, 16, 17, 40, 64, 100])
+def test_small_shapes_every_k(K):
+    for p in w.tiny_adversarial() + [w.uniform_rows(300, 200, 9), w.powerlaw(2000), w.laplace2d(20)]:
+        log("case spmm", p.name, K)
+        check(p, K, alpha=p.alpha, beta=p.beta, seed=K)
+
+
+@pytest.mark.parametrize("lead_pad,offset", [(0, 0), (4, 0), (3, 0), (0, 1), (5, 3)])
+def test_strided_and_misaligned_layouts(lead_pad, offset):
+    p = w.powerlaw(1500)
+    for K in (16, 33):
+        log("case spmm layout", lead_pad, offset, K)
+        check(p, K, alpha=-1.5, beta=0.75, seed=3, lead_pad=lead_pad, offset=offset)
+
+
+def test_more_columns_than_one_lds_block():
+    """n > 2048: B is taken in several passes that accumulate into C."""
+    for p in (w.uniform_rows(700, 5000, 12), w.powerlaw(3000, n=7001), w.from_row_lengths([0, 5000, 3, 0, 9000], 9000, seed=4)):
+        for beta in (0.0, 0.5):
+            log("case spmm wide", p.name, beta)
+            check(p, 24, alpha=2.0, beta=beta, seed=5)
+
+
+def test_exact_integer_bit_for_bit():
+    lens = [0, 1, 2, 3, 17, 64, 255, 256, 257, 0, 0, 1000, 5]
+    p = w.exact_integer(lens, 1500, alpha=3.0, beta=-2.0)
+    rng = np.random.default_rng(8)
+    B = rng.integers(-3, 4, (p.n, 20)).astype(np.float32)
+    C0 = rng.integers(-5, 6, (p.m, 20)).astype(np.float32)
+    C = run_spmm(p, B, C0, p.alpha, p.beta)
+    C_ref, _ = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B, C0, p.alpha, p.beta)
+    assert np.array_equal(C.astype(np.float64), C_ref)
+
+
+def test_beta_zero_ignores_nan_in_c_and_errors():
+    p = w.uniform_rows(100, 80, 6)
+    B = rand((p.n, 16), 1)
+    C = run_spmm(p, B, np.full((p.m, 16), np.nan, np.float32), 1.0, 0.0)
+    C_ref, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B)
+    assert np.all(np.abs(C - C_ref) <= TOL * S)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    Bt, Ct = torch.zeros(p.n, 16, device="cuda"), torch.zeros(p.m, 16, device="cuda")
+    assert s.spmm_csr_run(A.handle, Bt.data_ptr(), 8, Ct.data_ptr(), 16, 16, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    assert s.spmm_csr_run(A.handle, Bt.data_ptr(), 16, Ct.data_ptr(), 15, 16, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    assert s.spmm_csr_run(A.handle, None, 16, Ct.data_ptr(), 16, 16, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    assert s.spmm_csr_run(A.handle, Bt.data_ptr(), 16, Ct.data_ptr(), 16, -1, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    assert s.spmm_csr_run(A.handle, Bt.data_ptr(), 16, Ct.data_ptr(), 16, 0, 1.0, 0.0) == s.SPMV_OK
+    A.close()
+    q = w.uniform_rows(100, 80, 6, dtype="bf16")
+    d = DeviceProblem(q)
+    A = d.matrix()
+    assert s.spmm_csr_run(A.handle, Bt.data_ptr(), 16, Ct.data_ptr(), 16, 16, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    A.close()
+
+
+@pytest.mark.parametrize("rows_log2", [10, 12, 14])
+def test_paper_shapes_full_compare(rows_log2):
+    """Task 13's shapes: cols 2048, K 4096, density 0.01; every element of C."""
+    p = w.density_random(1 << rows_log2, 2048, 0.01)
+    log("case spmm paper shape", p.m, p.nnz)
+    check(p, 4096, seed=rows_log2)
+
+
+def test_paper_shape_2_16_sampled_rows():
+    """rows = 2^16 (C = 1 GiB): 300 sampled rows of C against the oracle run on just those rows."""
+    p = w.density_random(1 << 16, 2048, 0.01)
+    K = 4096
+    B = rand((p.n, K), 21)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    Bt = torch.from_numpy(B).cuda()
+    Ct = torch.empty(p.m, K, dtype=torch.float32, device="cuda")
+    A.spmm(Bt, Ct)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([[0, p.m - 1], np.random.default_rng(2).integers(0, p.m, 300)]))
+    lens = (p.rowptr[rows + 1] - p.rowptr[rows]).astype(np.int64)
+    sub_rp = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    take = np.concatenate([np.arange(p.rowptr[r], p.rowptr[r + 1]) for r in rows])
+    C_ref, S = oracle.spmm_csr(rows.size, p.n, sub_rp, p.colidx[take].copy(), p.vals[take].copy(), B)
+    got = Ct[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+    assert np.all(np.abs(got - C_ref) <= TOL * S)
+    A.close()
