@@ -215,6 +215,42 @@ def paper_sweep(args):
     return out
 
 
+def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
+    """The paper's SpMM CSR workload (App. C task 13: cols 2048, K 4096, density 0.01): time of
+    C <- A*B per size, GFLOP/s = 2*nnz*K / time, effective GB/s over the algorithmic bytes
+    (A's three arrays + B once + C written once)."""
+    import torch
+    import paper_2603_07169_amd as s
+    import workloads as w
+    out = []
+    K = 4096
+    stream = torch.cuda.current_stream()
+    for e in rows_log2:
+        p = w.density_random(1 << e, 2048, 0.01)
+        rowptr, colidx, vals = dev(p.rowptr), dev(p.colidx), dev(p.vals)
+        A = s.CsrMatrix(p.m, p.n, rowptr, colidx, vals, s.SPMV_F32)
+        B = torch.rand(p.n, K, dtype=torch.float32, device="cuda")
+        C = torch.empty(p.m, K, dtype=torch.float32, device="cuda")
+        steps = max(5, min(args.steps, int(2e9 // (p.m * K * 4)) or 5))
+        for _ in range(2):
+            A.spmm(B, C, 1.0, 0.0, stream.cuda_stream)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            A.spmm(B, C, 1.0, 0.0, stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        bytes_alg = 8 * p.nnz + 4 * (p.m + 1) + 4 * p.n * K + 4 * p.m * K
+        out.append({"rows": p.m, "cols": p.n, "K": K, "nnz": p.nnz, "steps": steps, "ms": ms,
+                    "GFLOPs": 2.0 * p.nnz * K / ms / 1e6, "algorithmic_bytes": bytes_alg,
+                    "GBps": bytes_alg / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS})
+        A.close()
+        del B, C
+    return out
+
+
 def cpu_baseline(p):
     """The oracle as it stands, one thread, on the whole workload: 1 warm-up + best of 5."""
     import oracle
@@ -282,6 +318,7 @@ def main():
         del big
         line["supplementary"] = r
         line["paper_sweep"] = paper_sweep(args)
+        line["spmm_csr"] = spmm_sweep(args)
     print(json.dumps(line))
 
 
