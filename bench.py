@@ -245,7 +245,10 @@ def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
         bytes_alg = 8 * p.nnz + 4 * (p.m + 1) + 4 * p.n * K + 4 * p.m * K
         out.append({"rows": p.m, "cols": p.n, "K": K, "nnz": p.nnz, "steps": steps, "ms": ms,
                     "GFLOPs": 2.0 * p.nnz * K / ms / 1e6, "algorithmic_bytes": bytes_alg,
-                    "GBps": bytes_alg / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS})
+                    "GBps": bytes_alg / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS,
+                    # bound by vector FMA issue: 256 CUs x 64 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s without
+                    # packed FP32 instructions (which this build keeps out), half of the published 157.3
+                    "alu_frac": 2.0 * p.nnz * K / ms / 1e6 / 78600.0})
         A.close()
         del B, C
     return out

@@ -854,6 +854,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
     static_assert(KT == 16, "four lanes per row, one float4 each");
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float* Bs = reinterpret_cast<float*>(smem_raw);  // [NB + 1][KT]; row NB stays zero
+    const unsigned char* const Bq = smem_raw + 16 * (threadIdx.x & 3);  // this lane's float4 of row 0
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q = lane & 3;      // which float4 of the slice, and which entries of the row (q, q+4, ..)
     const int rsub = lane >> 2;  // which of the wavefront's 16 rows
@@ -917,7 +918,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int t = c0 + q + 4 * u;
-                const int k = t < len ? rs + t : a.nnz - 1;
+                const unsigned k = t < len ? rs + t : a.nnz - 1;  // unsigned: base + 32-bit offset addressing
                 col[u] = a.colidx[k];
                 val[u] = a.vals[k];
             }
@@ -926,7 +927,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                 const int t = c0 + q + 4 * u;
                 const int c = col[u] - cb0;
                 const bool ok = t < len && static_cast<unsigned>(c) < static_cast<unsigned>(nbk);
-                col[u] = (ok ? c : NB) * KT;  // float offset of the B row
+                col[u] = (ok ? c : NB) * (KT * 4);  // byte offset of the B row in the LDS block
                 val[u] = ok ? val[u] : 0.f;
             }
         };
@@ -956,7 +957,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                                          __int_as_float(quad_bcast<2>(vbits)), __int_as_float(quad_bcast<3>(vbits))};
                     f32x4 b[4];
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const f32x4*>(Bs + cc[s] + 4 * q);
+                    for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const f32x4*>(Bq + cc[s]);
 #pragma unroll
                     for (int s = 0; s < 4; ++s) acc += vv[s] * b[s];
                 }
