@@ -46,6 +46,8 @@ def parse():
     ap.add_argument("--vector-lanes", type=int, default=0)
     ap.add_argument("--only", action="store_true", help="measure the headline workload only (skip the other configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--spmm", type=int, default=0, metavar="LOG2ROWS",
+                    help="run only the SpMM CSR product of the paper's shape with 2^LOG2ROWS rows and print its line")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the launch floor, the large uniform matrix and the paper-shaped sweep")
     ap.add_argument("--copies", type=int, default=0, help="override the number of rotating copies")
@@ -279,6 +281,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.spmm:
+        print(json.dumps({"spmm_csr": spmm_sweep(args, rows_log2=(args.spmm,))}))
+        return
     params = dict(plan=args.plan, block_nnz=args.block_nnz, rows_max=args.rows_max,
                   items_per_chunk=args.items_per_chunk, vector_lanes=args.vector_lanes, skip_validation=0)
     p, head = measure(args.config, args, params)

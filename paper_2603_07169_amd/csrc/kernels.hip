@@ -1,16 +1,18 @@
 // gfx950 kernels for y <- alpha*A*x + beta*y with A in CSR (values / col_indices / row_offsets,
-// paper App. C task 12), FP32 or bf16 storage, FP32 products and sums.
+// paper App. C task 12), FP32 or bf16 storage, FP32 products and sums, and for the sparse-times-
+// dense product C <- alpha*A*B + beta*C (task 13).
 //
-// The operation moves 8 (FP32) or 6 (bf16) bytes per stored entry for 2 flops, so every kernel
-// is built around reading vals/colidx exactly once, as wide and as coalesced as the row layout
-// allows, while x is gathered through the caches.  Four kernels:
+// SpMV moves 8 (FP32) or 6 (bf16) bytes per stored entry for 2 flops, so every kernel is built
+// around reading vals/colidx exactly once, as wide and as coalesced as the row layout allows:
 //   spmv_scalar_kernel  one lane per row                     (short rows; the naive baseline)
 //   spmv_vector_kernel  G = 2..64 lanes per row, DPP/ds_swizzle/permlane reduction
-//   spmv_tile_kernel    a workgroup streams a contiguous entry range with 128-bit loads,
-//                       parks the products in LDS and reduces them per row; the range comes
-//                       either from a row block (rows whole) or from a merge-path chunk
-//                       (rows may be cut at both ends; the cut-off tail leaves as a carry)
+//   spmv_tile_kernel    a workgroup copies a contiguous entry range (a row block, or a merge-path
+//                       chunk whose cut-off tail leaves as a carry) to LDS with 128-bit loads and
+//                       lets teams of lanes take one row each, gathering x through the caches
+//   spmv_window_kernel  the same with the block's window of x in LDS and 16-bit window positions
+//                       in place of the column indices (built by window_build_kernel at analysis)
 //   merge_fixup_kernel  adds the carries of cut rows to y, in chunk order, without atomics
+//   spmm_csr_kernel     a workgroup keeps a 16-column slice of B in LDS and walks over all rows
 // No matrix cores: nothing here is a dense contraction.
 #include <hip/hip_runtime.h>
 
