@@ -251,9 +251,22 @@ def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
                     # bound by vector FMA issue: 256 CUs x 64 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s without
                     # packed FP32 instructions (which this build keeps out), half of the published 157.3
                     "alu_frac": 2.0 * p.nnz * K / ms / 1e6 / 78600.0})
+        if e <= 12 and not args_no_cpu(args):
+            # the oracle beside it (one host thread), on the sizes it finishes in seconds
+            import oracle
+            Bh = B.cpu().numpy()
+            t0 = time.perf_counter()
+            oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, Bh)
+            dt = time.perf_counter() - t0
+            out[-1]["cpu_oracle"] = {"ms": dt * 1e3, "GFLOPs": 2.0 * p.nnz * K / dt / 1e9, "cores": 1, "kind": "oracle",
+                                     "sample": "whole product, single thread, one run"}
         A.close()
         del B, C
     return out
+
+
+def args_no_cpu(args):
+    return bool(getattr(args, "no_cpu_baseline", False))
 
 
 def cpu_baseline(p):
