@@ -15,7 +15,7 @@ import numpy as np
 
 _HERE = Path(__file__).resolve().parent
 LIB_PATH = _HERE / "liboracle.so"
-SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp", _HERE / "spmm_oracle.cpp"]
+SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp", _HERE / "spmm_oracle.cpp", _HERE / "formats_oracle.cpp"]
 _lib = None
 
 NUM_BINS = 33
@@ -48,6 +48,11 @@ def _load():
         _lib.oracle_spmv_csr_bf16.restype = C.c_int
         _lib.oracle_spmm_csr_f32.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, f32, f32, vp, vp]
         _lib.oracle_spmm_csr_f32.restype = C.c_int
+        _lib.oracle_spmv_coo.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
+        _lib.oracle_spmv_csc.argtypes = [i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
+        _lib.oracle_spmv_ell.argtypes = [i64, i64, i64, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
+        for fn in (_lib.oracle_spmv_coo, _lib.oracle_spmv_csc, _lib.oracle_spmv_ell):
+            fn.restype = C.c_int
         _lib.oracle_row_stats.argtypes = [i64, vp, vp]
         _lib.oracle_row_stats.restype = None
         _lib.oracle_row_bins.argtypes = [i64, vp, vp, vp, vp]
@@ -132,6 +137,49 @@ def spmm_csr(m, n, rowptr, colidx, vals, B, C0=None, alpha=1.0, beta=0.0):
     if rc != 0:
         raise ValueError("malformed CSR input")
     return Cr, S
+
+
+def _dt(dtype, vals, x):
+    want = np.float32 if dtype == "f32" else np.uint16
+    assert vals.dtype == want and x.dtype == want and vals.flags.c_contiguous and x.flags.c_contiguous, (vals.dtype, x.dtype)
+    return 0 if dtype == "f32" else 1
+
+
+def _y0(y0, m, beta):
+    if beta == 0.0:
+        return None
+    return _chk(y0, np.float32, m)
+
+
+def spmv_coo(dtype, m, n, row, col, vals, x, y0=None, alpha=1.0, beta=0.0):
+    _chk(row, np.int32), _chk(col, np.int32, row.size)
+    y, S = np.empty(m, np.float64), np.empty(m, np.float64)
+    rc = _load().oracle_spmv_coo(m, n, row.size, _p(row), _p(col), _p(vals), _dt(dtype, vals, x), _p(x),
+                                 _p(_y0(y0, m, beta)), alpha, beta, _p(y), _p(S))
+    if rc:
+        raise ValueError("index out of range")
+    return y, S
+
+
+def spmv_csc(dtype, m, n, col_offsets, row, vals, x, y0=None, alpha=1.0, beta=0.0):
+    _chk(col_offsets, np.int32, n + 1), _chk(row, np.int32)
+    y, S = np.empty(m, np.float64), np.empty(m, np.float64)
+    rc = _load().oracle_spmv_csc(m, n, _p(col_offsets), _p(row), _p(vals), _dt(dtype, vals, x), _p(x),
+                                 _p(_y0(y0, m, beta)), alpha, beta, _p(y), _p(S))
+    if rc:
+        raise ValueError("malformed CSC input")
+    return y, S
+
+
+def spmv_ell(dtype, m, n, width, col_ids, vals, x, y0=None, alpha=1.0, beta=0.0):
+    _chk(col_ids, np.int32, m * width)
+    assert vals.size == m * width
+    y, S = np.empty(m, np.float64), np.empty(m, np.float64)
+    rc = _load().oracle_spmv_ell(m, n, width, _p(col_ids), _p(vals), _dt(dtype, vals, x), _p(x),
+                                 _p(_y0(y0, m, beta)), alpha, beta, _p(y), _p(S))
+    if rc:
+        raise ValueError("column out of range")
+    return y, S
 
 
 def row_stats(rowptr):

@@ -28,7 +28,7 @@ __all__ = [
     "CsrProblem", "SEED_BASE", "f32_to_bf16_bits", "bf16_bits_to_f32",
     "uniform_rows", "laplace2d", "stencil27", "powerlaw", "block_clustered",
     "density_random", "from_row_lengths", "exact_integer", "tiny_adversarial",
-    "config", "CONFIG_NAMES",
+    "config", "CONFIG_NAMES", "to_coo", "to_csc", "to_ell",
 ]
 
 
@@ -364,3 +364,41 @@ def config(k: int, scale: float = 1.0) -> CsrProblem:
     if scale == 1.0:
         p.name = CONFIG_NAMES[k]
     return p
+
+
+# ----------------------------------------------------------------------------- other storage layouts
+# Pure re-layouts of a CsrProblem (no arithmetic of the method): App. C tasks 8 (COO), 10 (CSC), 14 (ELL).
+def to_coo(p: CsrProblem, shuffle_seed=None):
+    """(row_indices, col_indices, values) in CSR order, or scrambled with the given seed."""
+    row = np.repeat(np.arange(p.m, dtype=np.int32), np.diff(p.rowptr))
+    col, vals = p.colidx.copy(), p.vals.copy()
+    if shuffle_seed is not None:
+        perm = np.random.default_rng(shuffle_seed).permutation(p.nnz)
+        row, col, vals = row[perm], col[perm], vals[perm]
+    return np.ascontiguousarray(row), np.ascontiguousarray(col), np.ascontiguousarray(vals)
+
+
+def to_csc(p: CsrProblem):
+    """(col_offsets[n+1], row_indices, values), entries of a column in ascending row order."""
+    row = np.repeat(np.arange(p.m, dtype=np.int32), np.diff(p.rowptr))
+    order = np.argsort(p.colidx, kind="stable")
+    counts = np.bincount(p.colidx, minlength=p.n)
+    col_offsets = np.concatenate(([0], np.cumsum(counts))).astype(np.int32)
+    return col_offsets, np.ascontiguousarray(row[order]), np.ascontiguousarray(p.vals[order])
+
+
+def to_ell(p: CsrProblem, width=None):
+    """(width, col_ids[m*width], values[m*width]) row-major; padding slots have col_id -1 and value -1."""
+    lens = np.diff(p.rowptr)
+    width = int(lens.max(initial=0)) if width is None else int(width)
+    assert width >= lens.max(initial=0)
+    col_ids = np.full((p.m, max(width, 0)), -1, dtype=np.int32)
+    if p.dtype == "f32":
+        vals = np.full((p.m, width), -1.0, dtype=np.float32)
+    else:
+        vals = np.full((p.m, width), f32_to_bf16_bits(np.array([-1.0], np.float32))[0], dtype=np.uint16)
+    slot = np.arange(p.nnz) - np.repeat(p.rowptr[:-1], lens)
+    rows = np.repeat(np.arange(p.m), lens)
+    col_ids[rows, slot] = p.colidx
+    vals[rows, slot] = p.vals
+    return width, col_ids.ravel().copy(), vals.ravel().copy()
