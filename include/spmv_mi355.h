@@ -166,6 +166,28 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
 spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
                            float beta, void* stream);
 
+/* The same product y <- alpha*A*x + beta*y with A in the benchmark's other storage layouts
+ * (paper App. C tasks 8, 10, 14).  Stateless: every call takes the arrays (all DEVICE pointers,
+ * borrowed for the duration of the enqueued work) and enqueues its kernels on `stream`.
+ * dtype is the storage type of vals and x as for CSR.  Indices are NOT checked: rows must lie in
+ * [0, m) and columns in [0, n), except for ELL padding slots.
+ *   COO  vals[nnz], row_indices[nnz], col_indices[nnz] in any order; repeated coordinates add up.
+ *   CSC  vals[nnz], row_indices[nnz], col_offsets[n+1] (col_offsets[j] = first entry of column j).
+ *   ELL  vals[m*width], col_ids[m*width], row-major; a slot with col_id -1 is padding (its value
+ *        is ignored).  width >= 0.
+ * COO and CSC add the entries' contributions to y with float atomics (after y <- beta*y), so
+ * their results are reproducible to rounding but not bit for bit; ELL is bit-reproducible.
+ * beta == 0 never reads y.  Errors: INVALID_ARG (null pointer with a non-empty array, negative
+ * size, unknown dtype), UNSUPPORTED (a size >= 2^31, misaligned pointer), HIP. */
+spmv_status_t spmv_coo_run(int64_t m, int64_t n, int64_t nnz, const int32_t* row_indices, const int32_t* col_indices,
+                           const void* vals, spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta,
+                           void* stream);
+spmv_status_t spmv_csc_run(int64_t m, int64_t n, int64_t nnz, const int32_t* col_offsets, const int32_t* row_indices,
+                           const void* vals, spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta,
+                           void* stream);
+spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* col_ids, const void* vals,
+                           spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta, void* stream);
+
 /* Frees the handle and the library-owned device metadata.  spmv_destroy(NULL) is OK. */
 spmv_status_t spmv_destroy(spmv_handle_t h);
 

@@ -333,6 +333,61 @@ spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* 
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
 
+namespace {
+
+// Common argument checks of the stateless layouts: sizes, dtype, pointer alignment.
+spmv_status_t check_stateless(int64_t m, int64_t n, int64_t count, spmv_dtype_t dtype, const void* idx_a,
+                              const void* idx_b, const void* vals, const void* x, const float* y) {
+    if (m < 0 || n < 0 || count < 0) return SPMV_ERR_INVALID_ARG;
+    if (dtype != SPMV_F32 && dtype != SPMV_BF16) return SPMV_ERR_INVALID_ARG;
+    if (m > kMaxCount || n > kMaxCount || count > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    if (m > 0 && !y) return SPMV_ERR_INVALID_ARG;
+    if (count > 0 && (!idx_a || !idx_b || !vals || !x)) return SPMV_ERR_INVALID_ARG;
+    const uintptr_t esz = dtype == SPMV_F32 ? 4 : 2;
+    if (reinterpret_cast<uintptr_t>(idx_a) % 4 || reinterpret_cast<uintptr_t>(idx_b) % 4 ||
+        reinterpret_cast<uintptr_t>(vals) % esz || reinterpret_cast<uintptr_t>(x) % esz ||
+        reinterpret_cast<uintptr_t>(y) % 4)
+        return SPMV_ERR_UNSUPPORTED;
+    return SPMV_OK;
+}
+
+}  // namespace
+
+spmv_status_t spmv_coo_run(int64_t m, int64_t n, int64_t nnz, const int32_t* row_indices, const int32_t* col_indices,
+                           const void* vals, spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta,
+                           void* stream) {
+    const spmv_status_t st = check_stateless(m, n, nnz, dtype, row_indices, col_indices, vals, x, y);
+    if (st != SPMV_OK) return st;
+    const hipError_t e = spmv::launch_coo(dtype == SPMV_BF16, static_cast<int32_t>(m), static_cast<int32_t>(nnz),
+                                          row_indices, col_indices, vals, x, y, spmv::Scalars{alpha, beta},
+                                          static_cast<hipStream_t>(stream));
+    return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
+}
+
+spmv_status_t spmv_csc_run(int64_t m, int64_t n, int64_t nnz, const int32_t* col_offsets, const int32_t* row_indices,
+                           const void* vals, spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta,
+                           void* stream) {
+    const spmv_status_t st = check_stateless(m, n, nnz, dtype, row_indices, row_indices, vals, x, y);
+    if (st != SPMV_OK) return st;
+    if (!col_offsets || reinterpret_cast<uintptr_t>(col_offsets) % 4) return SPMV_ERR_INVALID_ARG;
+    if (n > 0 && !x) return SPMV_ERR_INVALID_ARG;
+    const hipError_t e = spmv::launch_csc(dtype == SPMV_BF16, static_cast<int32_t>(m), static_cast<int32_t>(n),
+                                          static_cast<int32_t>(nnz), col_offsets, row_indices, vals, x, y,
+                                          spmv::Scalars{alpha, beta}, static_cast<hipStream_t>(stream));
+    return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
+}
+
+spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* col_ids, const void* vals,
+                           spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta, void* stream) {
+    if (width < 0 || width > kMaxCount) return SPMV_ERR_INVALID_ARG;
+    const int64_t slots = m > 0 ? m * width : 0;
+    const spmv_status_t st = check_stateless(m, n, slots > kMaxCount ? kMaxCount : slots, dtype, col_ids, col_ids, vals, x, y);
+    if (st != SPMV_OK) return st;
+    const hipError_t e = spmv::launch_ell(dtype == SPMV_BF16, static_cast<int32_t>(m), static_cast<int32_t>(width), col_ids,
+                                          vals, x, y, spmv::Scalars{alpha, beta}, static_cast<hipStream_t>(stream));
+    return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
+}
+
 spmv_status_t spmv_destroy(spmv_handle_t h) {
     if (!h) return SPMV_OK;
     free_metadata(h);

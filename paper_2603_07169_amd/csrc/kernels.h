@@ -62,6 +62,15 @@ hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* 
 // flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st);
 
+// y <- alpha*A*x + beta*y for A in COO / CSC / ELL storage (stateless; indices are not checked).
+// COO and CSC first scale y by beta, then add every entry's contribution with float atomics.
+hipError_t launch_coo(bool bf16, int32_t m, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
+                      const void* x, float* y, Scalars s, hipStream_t st);
+hipError_t launch_csc(bool bf16, int32_t m, int32_t n, int32_t nnz, const int32_t* col_offsets, const int32_t* row,
+                      const void* vals, const void* x, float* y, Scalars s, hipStream_t st);
+hipError_t launch_ell(bool bf16, int32_t m, int32_t width, const int32_t* col_ids, const void* vals, const void* x,
+                      float* y, Scalars s, hipStream_t st);
+
 // Cross-lane reduction self-check on one wavefront.  in: device float[64], lane l contributes in[l].
 // out: device float[14*64]; out[gi*64 + l] = sum over lane l's aligned group of G = 2^gi lanes,
 // gi = 0..6 from the compile-time variant, then the same seven again from the run-time variant.

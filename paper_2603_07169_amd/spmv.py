@@ -24,7 +24,7 @@ SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 
 EXPORTS = [
-    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmm_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmm_csr_run", "spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_destroy", "spmv_csr_get_analysis_info",
     "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce", "spmv_csr_main_kernel_name",
     "spmv_status_string", "spmv_last_hip_error",
 ]
@@ -79,6 +79,11 @@ def _load():
     lib.spmv_csr_run.argtypes = [vp, vp, vp, f32, f32, vp]
     lib.spmm_csr_run.argtypes = [vp, vp, i64, vp, i64, i64, f32, f32, vp]
     lib.spmm_csr_run.restype = C.c_int
+    lib.spmv_coo_run.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp]
+    lib.spmv_csc_run.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp]
+    lib.spmv_ell_run.argtypes = [i64, i64, i64, vp, vp, C.c_int, vp, vp, f32, f32, vp]
+    for name in ("spmv_coo_run", "spmv_csc_run", "spmv_ell_run"):
+        getattr(lib, name).restype = C.c_int
     lib.spmv_destroy.argtypes = [vp]
     lib.spmv_csr_get_analysis_info.argtypes = [vp, C.POINTER(spmv_analysis_info_t)]
     lib.spmv_csr_get_analysis.argtypes = [vp, C.POINTER(spmv_analysis_host_t)]
@@ -136,6 +141,18 @@ def spmv_csr_run(handle, x, y, alpha, beta, stream=None):
 def spmm_csr_run(handle, B, ldb, C_, ldc, K, alpha, beta, stream=None):
     """B, C_: device addresses of row-major float arrays with leading dimensions ldb, ldc."""
     return _load().spmm_csr_run(handle, B, ldb, C_, ldc, K, alpha, beta, stream)
+
+
+def spmv_coo_run(m, n, nnz, row_indices, col_indices, vals, dtype, x, y, alpha, beta, stream=None):
+    return _load().spmv_coo_run(m, n, nnz, row_indices, col_indices, vals, dtype, x, y, alpha, beta, stream)
+
+
+def spmv_csc_run(m, n, nnz, col_offsets, row_indices, vals, dtype, x, y, alpha, beta, stream=None):
+    return _load().spmv_csc_run(m, n, nnz, col_offsets, row_indices, vals, dtype, x, y, alpha, beta, stream)
+
+
+def spmv_ell_run(m, n, width, col_ids, vals, dtype, x, y, alpha, beta, stream=None):
+    return _load().spmv_ell_run(m, n, width, col_ids, vals, dtype, x, y, alpha, beta, stream)
 
 
 def spmv_destroy(handle):
