@@ -48,6 +48,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm", type=int, default=0, metavar="LOG2ROWS",
                     help="run only the SpMM CSR product of the paper's shape with 2^LOG2ROWS rows and print its line")
+    ap.add_argument("--formats", action="store_true", help="run only the COO / CSC / ELL products and print their lines")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the launch floor, the large uniform matrix and the paper-shaped sweep")
     ap.add_argument("--copies", type=int, default=0, help="override the number of rotating copies")
@@ -269,6 +270,58 @@ def args_no_cpu(args):
     return bool(getattr(args, "no_cpu_baseline", False))
 
 
+def formats_sweep(args):
+    """SpMV in the benchmark's other layouts (App. C tasks 8, 10, 14): the largest paper shape of each
+    task and config 3's stencil as a size where the kernels stream.  GB/s over each layout's own bytes."""
+    import torch
+    import paper_2603_07169_amd as s
+    import workloads as w
+    stream = torch.cuda.current_stream()
+    out = []
+
+    def timed(call, steps):
+        for _ in range(3):
+            call()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(steps):
+            call()
+        e1.record(stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / steps
+
+    cases = [("coo", w.density_random(1 << 15, 2048, 0.01)), ("csc", w.density_random(2048, 1 << 15, 0.01)),
+             ("ell", w.density_random(2048, 1 << 15, 0.01)), ("coo", w.config(3)), ("ell", w.config(3))]
+    for layout, p in cases:
+        e = 4 if p.dtype == "f32" else 2
+        code = s.SPMV_F32 if p.dtype == "f32" else s.SPMV_BF16
+        x = dev(p.x)
+        y = torch.zeros(p.m, dtype=torch.float32, device="cuda")
+        h = stream.cuda_stream
+        if layout == "coo":
+            row, col, vals = [dev(a) for a in w.to_coo(p)]
+            nbytes = p.nnz * (e + 8) + e * p.n + 4 * p.m
+            call = lambda: s.check(s.spmv_coo_run(p.m, p.n, p.nnz, row.data_ptr(), col.data_ptr(), vals.data_ptr(), code,
+                                                  x.data_ptr(), y.data_ptr(), 1.0, 0.0, h))
+        elif layout == "csc":
+            co, row, vals = [dev(a) for a in w.to_csc(p)]
+            nbytes = p.nnz * (e + 4) + 4 * (p.n + 1) + e * p.n + 4 * p.m
+            call = lambda: s.check(s.spmv_csc_run(p.m, p.n, p.nnz, co.data_ptr(), row.data_ptr(), vals.data_ptr(), code,
+                                                  x.data_ptr(), y.data_ptr(), 1.0, 0.0, h))
+        else:
+            width, ci, vals = w.to_ell(p)
+            ci, vals = dev(ci), dev(vals)
+            nbytes = p.m * width * (e + 4) + e * p.n + 4 * p.m
+            call = lambda: s.check(s.spmv_ell_run(p.m, p.n, width, ci.data_ptr(), vals.data_ptr(), code, x.data_ptr(),
+                                                  y.data_ptr(), 1.0, 0.0, h))
+        ms = timed(call, min(args.steps, 50))
+        out.append({"layout": layout, "workload": p.name, "dtype": p.dtype, "m": p.m, "n": p.n, "nnz": p.nnz,
+                    "ms": ms, "algorithmic_bytes": nbytes, "GBps": nbytes / ms / 1e6,
+                    "hbm_frac": nbytes / ms / 1e6 / HBM_PEAK_GBPS, "GFLOPs": 2.0 * p.nnz / ms / 1e6})
+    return out
+
+
 def cpu_baseline(p):
     """The oracle as it stands, one thread, on the whole workload: 1 warm-up + best of 5."""
     import oracle
@@ -294,6 +347,9 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.formats:
+        print(json.dumps({"formats": formats_sweep(args)}))
+        return
     if args.spmm:
         print(json.dumps({"spmm_csr": spmm_sweep(args, rows_log2=(args.spmm,))}))
         return
@@ -340,6 +396,7 @@ def main():
         line["supplementary"] = r
         line["paper_sweep"] = paper_sweep(args)
         line["spmm_csr"] = spmm_sweep(args)
+        line["formats"] = formats_sweep(args)
     print(json.dumps(line))
 
 

@@ -27,6 +27,7 @@ namespace {
 constexpr int kWG = 256;   // threads per workgroup = 4 wavefronts of 64
 constexpr int kXcds = 8;   // accelerator dies; workgroup ids are dealt round-robin over them
 constexpr int kMaxDeferred = 136;
+constexpr int kCscLdsRows = 16384;  // CSC: up to this many rows a workgroup keeps a private y in LDS (64 KB)
 constexpr int kSpmmWG = 1024;    // SpMM: 16 wavefronts per workgroup (one workgroup per CU: its B slice fills the LDS)
 constexpr int kSpmmKT = 16;      // SpMM: columns of B and C a workgroup owns (4 lanes x float4 per row)
 constexpr int kSpmmNB = 2048;    // SpMM: rows of B held in LDS at a time (2048 x 16 floats = 128 KB)
@@ -1067,6 +1068,32 @@ __global__ __launch_bounds__(kWG) void spmv_csc_kernel(const int32_t* __restrict
     for (int e = col_offsets[j] + tl; e < e1; e += G) unsafeAtomicAdd(y + row[e], widen(vals[e]) * xj);
 }
 
+// The same for matrices with few rows, where the atomics of thousands of columns would queue up
+// on the same few addresses of y: a workgroup adds its columns into a private copy of y in LDS
+// and sends every row's total to memory once.  Few workgroups, so few atomics per address.
+template <typename T, int G>
+__global__ __launch_bounds__(kWG) void spmv_csc_lds_kernel(const int32_t* __restrict__ col_offsets,
+                                                           const int32_t* __restrict__ row,
+                                                           const typename T::elem* __restrict__ vals,
+                                                           const typename T::elem* __restrict__ x, float* y, int m, int n,
+                                                           float alpha) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* ly = reinterpret_cast<float*>(smem_raw);  // [m]
+    for (int i = threadIdx.x; i < m; i += kWG) ly[i] = 0.f;
+    __syncthreads();
+    const int tl = threadIdx.x % G;
+    for (int j = (blockIdx.x * kWG + threadIdx.x) / G; j < n; j += gridDim.x * (kWG / G)) {
+        const float xj = alpha * widen(x[j]);
+        const int e1 = col_offsets[j + 1];
+        for (int e = col_offsets[j] + tl; e < e1; e += G) atomicAdd(ly + row[e], widen(vals[e]) * xj);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < m; i += kWG) {
+        const float v = ly[i];
+        if (v != 0.f) unsafeAtomicAdd(y + i, v);
+    }
+}
+
 // A team of G lanes per row of `width` slots; a slot with col_id -1 is padding.
 template <typename T, int G>
 __global__ __launch_bounds__(kWG) void spmv_ell_kernel(const int32_t* __restrict__ col_ids,
@@ -1388,9 +1415,17 @@ hipError_t launch_csc_tg(int32_t m, int32_t n, const int32_t* col_offsets, const
     using E = typename T::elem;
     const int grid = ceil_div(m, kWG);
     hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, s.beta);
-    if (n > 0)
-        hipLaunchKernelGGL((spmv_csc_kernel<T, G>), dim3(ceil_div(static_cast<int64_t>(n) * G, kWG)), dim3(kWG), 0, st,
-                           col_offsets, row, static_cast<const E*>(vals), static_cast<const E*>(x), y, n, s.alpha);
+    if (n <= 0) return hipGetLastError();
+    const int blocks = ceil_div(static_cast<int64_t>(n) * G, kWG);
+    if (m <= kCscLdsRows) {
+        // a private y per workgroup: 64 workgroups keep the chip busy enough for these small problems
+        // and leave at most 64 atomics per row
+        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(blocks > 64 ? 64 : blocks), dim3(kWG), sizeof(float) * m, st,
+                           col_offsets, row, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, n, s.alpha);
+    } else {
+        hipLaunchKernelGGL((spmv_csc_kernel<T, G>), dim3(blocks), dim3(kWG), 0, st, col_offsets, row,
+                           static_cast<const E*>(vals), static_cast<const E*>(x), y, n, s.alpha);
+    }
     return hipGetLastError();
 }
 
