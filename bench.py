@@ -61,7 +61,7 @@ def parse():
 def kernels_sha256():
     import hashlib
     h = hashlib.sha256()
-    for name in ("kernels.hip", "capi.cpp", "analysis.cpp"):
+    for name in ("kernels.hip", "device_common.h", "capi.cpp", "analysis.cpp"):   # what the CSR product runs
         h.update((ROOT / "paper_2603_07169_amd" / "csrc" / name).read_bytes())
     return h.hexdigest()
 

@@ -8,8 +8,8 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB_PATH = PKG / "libspmv_mi355.so"
-SOURCES = [CSRC / "kernels.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
-HEADERS = [CSRC / "kernels.h", CSRC / "analysis.h", INCLUDE / "spmv_mi355.h"]
+SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
+HEADERS = [CSRC / "kernels.h", CSRC / "device_common.h", CSRC / "analysis.h", INCLUDE / "spmv_mi355.h"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

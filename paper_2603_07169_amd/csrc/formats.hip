@@ -1,0 +1,204 @@
+// gfx950 kernels for y <- alpha*A*x + beta*y with A in COO, CSC and ELL storage (paper App. C
+// tasks 8, 10, 14).
+#include <hip/hip_runtime.h>
+
+#include "device_common.h"
+#include "kernels.h"
+
+namespace spmv {
+namespace {
+
+constexpr int kCscLdsRows = 16384;  // CSC: up to this many rows a workgroup keeps a private y in LDS (64 KB)
+
+// ------------------------------------------------------------------------------------------
+// y <- alpha*A*x + beta*y for A in the other storage layouts of the benchmark (App. C tasks 8,
+// 10, 14).  ELL rows are independent and are reduced like CSR rows.  COO and CSC entries arrive
+// grouped by nothing (COO) or by column (CSC), so their contributions are added to y with
+// hardware float atomics after y has been scaled by beta in a kernel of its own; sums therefore
+// depend on the order in which the atomics land (results agree to rounding, not bit for bit).
+__global__ __launch_bounds__(kWG) void scale_y_kernel(float* __restrict__ y, int m, float beta) {
+    for (int i = blockIdx.x * kWG + threadIdx.x; i < m; i += gridDim.x * kWG) y[i] = beta == 0.f ? 0.f : beta * y[i];
+}
+
+// One entry per lane and trip.  Runs of equal row numbers in consecutive lanes (the whole
+// wavefront when the entries are sorted by row) are summed first with a segmented scan, so a
+// run costs one atomic instead of one per entry.
+template <typename T>
+__global__ __launch_bounds__(kWG) void spmv_coo_kernel(const int32_t* __restrict__ row, const int32_t* __restrict__ col,
+                                                       const typename T::elem* __restrict__ vals,
+                                                       const typename T::elem* __restrict__ x, float* y, int nnz,
+                                                       float alpha) {
+    const int lane = threadIdx.x & 63;
+    const int wave = (blockIdx.x * kWG + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * kWG) >> 6;
+    for (int base = wave * 64; base < nnz; base += n_waves * 64) {  // the same trip count for all lanes of a wavefront
+        const int e = base + lane;
+        const bool live = e < nnz;
+        const int r = live ? row[e] : -1;
+        float p = live ? alpha * (widen(vals[e]) * widen(x[col[e]])) : 0.f;
+        const int r_prev = __shfl_up(r, 1, 64);
+        bool head = lane == 0 || r_prev != r;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const float pp = __shfl_up(p, d, 64);
+            const int hh = __shfl_up(static_cast<int>(head), d, 64);
+            if (lane >= d && !head) {
+                p += pp;
+                head = hh != 0;
+            }
+        }
+        const int r_next = __shfl_down(r, 1, 64);
+        if (live && (lane == 63 || r_next != r)) unsafeAtomicAdd(y + r, p);
+    }
+}
+
+// A team of G lanes per column: its entries all multiply the same x[j] and go to different rows.
+template <typename T, int G>
+__global__ __launch_bounds__(kWG) void spmv_csc_kernel(const int32_t* __restrict__ col_offsets,
+                                                       const int32_t* __restrict__ row,
+                                                       const typename T::elem* __restrict__ vals,
+                                                       const typename T::elem* __restrict__ x, float* y, int n, float alpha) {
+    const int j = (blockIdx.x * kWG + threadIdx.x) / G;
+    const int tl = threadIdx.x % G;
+    if (j >= n) return;
+    const float xj = alpha * widen(x[j]);
+    const int e1 = col_offsets[j + 1];
+    for (int e = col_offsets[j] + tl; e < e1; e += G) unsafeAtomicAdd(y + row[e], widen(vals[e]) * xj);
+}
+
+// The same for matrices with few rows, where the atomics of thousands of columns would queue up
+// on the same few addresses of y: a workgroup adds its columns into a private copy of y in LDS
+// and sends every row's total to memory once.  Few workgroups, so few atomics per address.
+template <typename T, int G>
+__global__ __launch_bounds__(kWG) void spmv_csc_lds_kernel(const int32_t* __restrict__ col_offsets,
+                                                           const int32_t* __restrict__ row,
+                                                           const typename T::elem* __restrict__ vals,
+                                                           const typename T::elem* __restrict__ x, float* y, int m, int n,
+                                                           float alpha) {
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* ly = reinterpret_cast<float*>(smem_raw);  // [m]
+    for (int i = threadIdx.x; i < m; i += kWG) ly[i] = 0.f;
+    __syncthreads();
+    const int tl = threadIdx.x % G;
+    for (int j = (blockIdx.x * kWG + threadIdx.x) / G; j < n; j += gridDim.x * (kWG / G)) {
+        const float xj = alpha * widen(x[j]);
+        const int e1 = col_offsets[j + 1];
+        for (int e = col_offsets[j] + tl; e < e1; e += G) atomicAdd(ly + row[e], widen(vals[e]) * xj);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < m; i += kWG) {
+        const float v = ly[i];
+        if (v != 0.f) unsafeAtomicAdd(y + i, v);
+    }
+}
+
+// A team of G lanes per row of `width` slots; a slot with col_id -1 is padding.
+template <typename T, int G>
+__global__ __launch_bounds__(kWG) void spmv_ell_kernel(const int32_t* __restrict__ col_ids,
+                                                       const typename T::elem* __restrict__ vals,
+                                                       const typename T::elem* __restrict__ x, float* y, int m, int width,
+                                                       float alpha, float beta) {
+    const int i = (blockIdx.x * kWG + threadIdx.x) / G;
+    const int tl = threadIdx.x % G;
+    const bool live = i < m;
+    float acc = 0.f;
+    if (live) {
+        const size_t base = static_cast<size_t>(i) * width;
+        for (int s = tl; s < width; s += G) {
+            const int c = col_ids[base + s];
+            if (c >= 0) acc += widen(vals[base + s]) * widen(x[c]);
+        }
+    }
+    acc = group_sum<G>(acc);  // every lane of the wavefront takes part
+    if (live && tl == 0) y[i] = epilogue(acc, alpha, beta, y, i);
+}
+
+}  // namespace
+
+namespace {
+
+int lanes_for_length(int64_t len) {  // smallest power of two G in [2, 64] with 8*G >= len
+    int G = 2;
+    while (G < 64 && 8 * G < len) G <<= 1;
+    return G;
+}
+
+template <typename T>
+hipError_t launch_coo_t(int32_t m, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals, const void* x,
+                        float* y, Scalars s, hipStream_t st) {
+    using E = typename T::elem;
+    int grid = ceil_div(m, kWG);
+    hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, s.beta);
+    if (nnz > 0) {
+        grid = ceil_div(nnz, kWG);
+        hipLaunchKernelGGL((spmv_coo_kernel<T>), dim3(grid > 8192 ? 8192 : grid), dim3(kWG), 0, st, row, col,
+                           static_cast<const E*>(vals), static_cast<const E*>(x), y, nnz, s.alpha);
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int G>
+hipError_t launch_csc_tg(int32_t m, int32_t n, const int32_t* col_offsets, const int32_t* row, const void* vals,
+                         const void* x, float* y, Scalars s, hipStream_t st) {
+    using E = typename T::elem;
+    const int grid = ceil_div(m, kWG);
+    hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, s.beta);
+    if (n <= 0) return hipGetLastError();
+    const int blocks = ceil_div(static_cast<int64_t>(n) * G, kWG);
+    if (m <= kCscLdsRows) {
+        // a private y per workgroup: 64 workgroups keep the chip busy enough for these small problems
+        // and leave at most 64 atomics per row
+        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(blocks > 64 ? 64 : blocks), dim3(kWG), sizeof(float) * m, st,
+                           col_offsets, row, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, n, s.alpha);
+    } else {
+        hipLaunchKernelGGL((spmv_csc_kernel<T, G>), dim3(blocks), dim3(kWG), 0, st, col_offsets, row,
+                           static_cast<const E*>(vals), static_cast<const E*>(x), y, n, s.alpha);
+    }
+    return hipGetLastError();
+}
+
+template <typename T, int G>
+hipError_t launch_ell_tg(int32_t m, int32_t width, const int32_t* col_ids, const void* vals, const void* x, float* y,
+                         Scalars s, hipStream_t st) {
+    using E = typename T::elem;
+    hipLaunchKernelGGL((spmv_ell_kernel<T, G>), dim3(ceil_div(static_cast<int64_t>(m) * G, kWG)), dim3(kWG), 0, st,
+                       col_ids, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, width, s.alpha, s.beta);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_coo(bool bf16, int32_t m, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
+                      const void* x, float* y, Scalars s, hipStream_t st) {
+    if (m <= 0) return hipSuccess;
+    return bf16 ? launch_coo_t<BF16>(m, nnz, row, col, vals, x, y, s, st)
+                : launch_coo_t<F32>(m, nnz, row, col, vals, x, y, s, st);
+}
+
+hipError_t launch_csc(bool bf16, int32_t m, int32_t n, int32_t nnz, const int32_t* col_offsets, const int32_t* row,
+                      const void* vals, const void* x, float* y, Scalars s, hipStream_t st) {
+    if (m <= 0) return hipSuccess;
+#define SPMV_CSC_CASE(G) \
+    case G: return bf16 ? launch_csc_tg<BF16, G>(m, n, col_offsets, row, vals, x, y, s, st) \
+                        : launch_csc_tg<F32, G>(m, n, col_offsets, row, vals, x, y, s, st);
+    switch (lanes_for_length(n > 0 ? (nnz + n - 1) / n : 0)) {
+        SPMV_CSC_CASE(2) SPMV_CSC_CASE(4) SPMV_CSC_CASE(8) SPMV_CSC_CASE(16) SPMV_CSC_CASE(32) SPMV_CSC_CASE(64)
+    }
+#undef SPMV_CSC_CASE
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_ell(bool bf16, int32_t m, int32_t width, const int32_t* col_ids, const void* vals, const void* x,
+                      float* y, Scalars s, hipStream_t st) {
+    if (m <= 0) return hipSuccess;
+#define SPMV_ELL_CASE(G) \
+    case G: return bf16 ? launch_ell_tg<BF16, G>(m, width, col_ids, vals, x, y, s, st) \
+                        : launch_ell_tg<F32, G>(m, width, col_ids, vals, x, y, s, st);
+    switch (lanes_for_length(width)) {
+        SPMV_ELL_CASE(2) SPMV_ELL_CASE(4) SPMV_ELL_CASE(8) SPMV_ELL_CASE(16) SPMV_ELL_CASE(32) SPMV_ELL_CASE(64)
+    }
+#undef SPMV_ELL_CASE
+    return hipErrorInvalidValue;
+}
+
+}  // namespace spmv

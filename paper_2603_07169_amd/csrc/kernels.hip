@@ -1,6 +1,5 @@
 // gfx950 kernels for y <- alpha*A*x + beta*y with A in CSR (values / col_indices / row_offsets,
-// paper App. C task 12), FP32 or bf16 storage, FP32 products and sums, and for the sparse-times-
-// dense product C <- alpha*A*B + beta*C (task 13).
+// paper App. C task 12), FP32 or bf16 storage, FP32 products and sums.
 //
 // SpMV moves 8 (FP32) or 6 (bf16) bytes per stored entry for 2 flops, so every kernel is built
 // around reading vals/colidx exactly once, as wide and as coalesced as the row layout allows:
@@ -12,86 +11,19 @@
 //   spmv_window_kernel  the same with the block's window of x in LDS and 16-bit window positions
 //                       in place of the column indices (built by window_build_kernel at analysis)
 //   merge_fixup_kernel  adds the carries of cut rows to y, in chunk order, without atomics
-//   spmm_csr_kernel     a workgroup keeps a 16-column slice of B in LDS and walks over all rows
 // No matrix cores: nothing here is a dense contraction.
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
 #include <cstdlib>
 
+#include "device_common.h"
 #include "kernels.h"
 
 namespace spmv {
 namespace {
 
-constexpr int kWG = 256;   // threads per workgroup = 4 wavefronts of 64
-constexpr int kXcds = 8;   // accelerator dies; workgroup ids are dealt round-robin over them
 constexpr int kMaxDeferred = 136;
-constexpr int kCscLdsRows = 16384;  // CSC: up to this many rows a workgroup keeps a private y in LDS (64 KB)
-constexpr int kSpmmWG = 1024;    // SpMM: 16 wavefronts per workgroup (one workgroup per CU: its B slice fills the LDS)
-constexpr int kSpmmKT = 16;      // SpMM: columns of B and C a workgroup owns (4 lanes x float4 per row)
-constexpr int kSpmmNB = 2048;    // SpMM: rows of B held in LDS at a time (2048 x 16 floats = 128 KB)
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
-struct F32 {
-    using elem = float;
-    static constexpr int VEC = 4;  // elements per 128-bit load of vals
-};
-struct BF16 {
-    using elem = uint16_t;
-    static constexpr int VEC = 8;
-};
-
-__device__ __forceinline__ float widen(float v) { return v; }
-__device__ __forceinline__ float widen(uint16_t b) { return __uint_as_float(static_cast<uint32_t>(b) << 16); }
-
-// ------------------------------------------------------------------------------------------
-// Cross-lane sums over aligned groups of G lanes; every lane of the group receives the total.
-// Steps 1 and 2 permute inside a quad, 4 and 8 mirror a half row / a row of 16 (valid because
-// the lanes being mirrored already agree), 16 swaps inside 32 lanes through the LDS crossbar
-// (ds_swizzle, no memory touched), 32 swaps the two wave halves (v_permlane32_swap).
-// All 64 lanes must be active.
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float add_xor1(float v) { return v + dpp_move<0xB1>(v); }    // quad_perm [1,0,3,2]
-__device__ __forceinline__ float add_xor2(float v) { return v + dpp_move<0x4E>(v); }    // quad_perm [2,3,0,1]
-__device__ __forceinline__ float add_half_mirror(float v) { return v + dpp_move<0x141>(v); }
-__device__ __forceinline__ float add_row_mirror(float v) { return v + dpp_move<0x140>(v); }
-__device__ __forceinline__ float add_swap16(float v) {
-    return v + __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));  // and 0x1f, xor 0x10
-}
-__device__ __forceinline__ float add_swap32(float v) {
-    const unsigned u = __float_as_uint(v);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
-
-template <int G>
-__device__ __forceinline__ float group_sum(float v) {
-    if constexpr (G >= 2) v = add_xor1(v);
-    if constexpr (G >= 4) v = add_xor2(v);
-    if constexpr (G >= 8) v = add_half_mirror(v);
-    if constexpr (G >= 16) v = add_row_mirror(v);
-    if constexpr (G >= 32) v = add_swap16(v);
-    if constexpr (G >= 64) v = add_swap32(v);
-    return v;
-}
-
-// Same with G known only at run time (uniform over the workgroup).
-__device__ __forceinline__ float group_sum_rt(float v, int G) {
-    if (G >= 2) v = add_xor1(v);
-    if (G >= 4) v = add_xor2(v);
-    if (G >= 8) v = add_half_mirror(v);
-    if (G >= 16) v = add_row_mirror(v);
-    if (G >= 32) v = add_swap16(v);
-    if (G >= 64) v = add_swap32(v);
-    return v;
-}
 
 // ------------------------------------------------------------------------------------------
 // Workgroup ids are handed to the 8 dies round-robin (id % 8).  Each die has its own L2, so
@@ -197,10 +129,6 @@ __device__ __forceinline__ float team_dot(const int32_t* colidx, const typename 
     }
     for (int k = k0 + lane; k < k1; k += G) acc += product_one(colidx, vals, x, k);
     return acc;
-}
-
-__device__ __forceinline__ float epilogue(float acc, float alpha, float beta, const float* y, int r) {
-    return beta == 0.f ? alpha * acc : alpha * acc + beta * y[r];
 }
 
 // ------------------------------------------------------------------------------------------
@@ -820,183 +748,6 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// C <- alpha*A*B + beta*C with A in CSR (FP32), B (n x K) and C (m x K) dense, row-major
-// (paper App. C task 13).  Every stored entry a_ij adds a_ij * B[j, :] to C[i, :], so the
-// operation reads a K-wide row of B per entry: nnz * K * 4 bytes in all, far more than B itself
-// or than C.  Those reads are kept on chip: a workgroup owns kSpmmKT = 16 columns of B and C,
-// copies that slice of B (up to kSpmmNB = 2048 rows: 128 KB) into LDS once and then walks over
-// all its rows of A.  Four lanes (a DPP quad) serve a row, one float4 of the slice each; a
-// wavefront serves 16 rows at a time.  The quad reads its row's entries straight from memory,
-// lane q taking entries q, q+4, ..: neighbouring quads hold neighbouring rows, so a load
-// instruction of the wavefront covers one contiguous stretch of colidx / vals.  An entry is then
-// handed to the other three lanes with a quad broadcast, and each lane adds value * B-row piece
-// out of LDS.  Rows and entries of the next group are fetched while the current one is multiplied.
-// B wider than the LDS block is taken in several passes over A, accumulating into C.
-struct SpmmArgs {
-    const int32_t* rowptr;
-    const int32_t* colidx;
-    const float* vals;
-    const float* B;
-    float* C;
-    int64_t ldb, ldc;
-    int32_t m, n, K, nnz;
-    int32_t row_splits;  // gridDim.y: each takes an equal share of the rows
-    int32_t vec_ok;      // B and C 16-byte aligned, ldb and ldc multiples of 4
-    float alpha, beta;
-};
-
-template <int S>
-__device__ __forceinline__ int quad_bcast(int v) {  // every lane gets the value of lane S of its quad
-    return __builtin_amdgcn_update_dpp(0, v, S * 0x55, 0xF, 0xF, true);
-}
-
-__global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
-    constexpr int KT = kSpmmKT, NB = kSpmmNB, RPW = 16, WAVES = kSpmmWG / 64;
-    constexpr int U = 8;  // entries per lane and chunk: a chunk covers 32 entries of a row
-    static_assert(KT == 16, "four lanes per row, one float4 each");
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    float* Bs = reinterpret_cast<float*>(smem_raw);  // [NB + 1][KT]; row NB stays zero
-    const unsigned char* const Bq = smem_raw + 16 * (threadIdx.x & 3);  // this lane's float4 of row 0
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int q = lane & 3;      // which float4 of the slice, and which entries of the row (q, q+4, ..)
-    const int rsub = lane >> 2;  // which of the wavefront's 16 rows
-
-    const int k0 = blockIdx.x * KT;
-    const int kw = a.K - k0 < KT ? a.K - k0 : KT;  // live columns of this slice
-    const int row_lo = static_cast<int>(static_cast<int64_t>(a.m) * blockIdx.y / a.row_splits);
-    const int row_hi = static_cast<int>(static_cast<int64_t>(a.m) * (blockIdx.y + 1) / a.row_splits);
-    const bool full4 = a.vec_ok && 4 * q + 4 <= kw;  // this lane's float4 lies wholly inside the slice
-
-    if (a.nnz == 0) {  // C <- beta*C; the main path below may then assume that A has entries
-        for (int r = row_lo + tid / 4; r < row_hi; r += kSpmmWG / 4) {
-            float* dst = a.C + static_cast<size_t>(r) * a.ldc + k0 + 4 * q;
-            for (int t = 0; t < 4; ++t)
-                if (4 * q + t < kw) dst[t] = a.beta != 0.f ? a.beta * dst[t] : 0.f;
-        }
-        return;
-    }
-    if (tid < KT) Bs[NB * KT + tid] = 0.f;  // the row that entries without a partner in this block point to
-
-    // Group number gi of a wavefront -> first row.  Every workgroup walks over all rows of A;
-    // starting each at a different place keeps them from asking for the same lines together.
-    const int n_groups = (row_hi - row_lo + RPW - 1) / RPW;
-    const int rot = static_cast<int>((static_cast<int64_t>(blockIdx.x) * n_groups) / gridDim.x);
-    auto base_of = [&](int gi) {
-        if (gi >= n_groups) return row_hi;
-        int g = gi + rot;
-        if (g >= n_groups) g -= n_groups;
-        return row_lo + g * RPW;
-    };
-
-    for (int cb0 = 0; cb0 < a.n; cb0 += NB) {
-        const int nbk = a.n - cb0 < NB ? a.n - cb0 : NB;  // rows of B in this block
-        if (cb0 > 0) __syncthreads();                     // the previous block is no longer read
-        for (int idx = tid; idx < nbk * 4; idx += kSpmmWG) {
-            const int j = idx >> 2, qq = idx & 3;
-            const float* src = a.B + static_cast<size_t>(cb0 + j) * a.ldb + k0 + 4 * qq;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (a.vec_ok && 4 * qq + 4 <= kw) {
-                v = *reinterpret_cast<const f32x4*>(src);
-            } else {
-                for (int t = 0; t < 4; ++t)
-                    if (4 * qq + t < kw) v[t] = src[t];
-            }
-            *reinterpret_cast<f32x4*>(Bs + j * KT + 4 * qq) = v;
-        }
-        __syncthreads();
-
-        // (first entry, length) of this lane's row in group gi; length 0 past the end
-        auto load_row = [&](int gi, int& rs, int& len) {
-            const int r = base_of(gi) + rsub;
-            const bool live = r < row_hi;
-            rs = a.rowptr[live ? r : 0];
-            const int re = a.rowptr[live ? r + 1 : 0];
-            len = live ? re - rs : 0;
-        };
-        // entries c0 + q, c0 + q + 4, .. of the row: LDS offset of the B row (in floats) and value.
-        // The loads are unconditional (no branch, so all are in flight together); a lane past its
-        // row's end reads the last entry of the array and then points at the zero row.
-        auto load_chunk = [&](int rs, int len, int c0, int* col, float* val) {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = c0 + q + 4 * u;
-                const unsigned k = t < len ? rs + t : a.nnz - 1;  // unsigned: base + 32-bit offset addressing
-                col[u] = a.colidx[k];
-                val[u] = a.vals[k];
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = c0 + q + 4 * u;
-                const int c = col[u] - cb0;
-                const bool ok = t < len && static_cast<unsigned>(c) < static_cast<unsigned>(nbk);
-                col[u] = (ok ? c : NB) * (KT * 4);  // byte offset of the B row in the LDS block
-                val[u] = ok ? val[u] : 0.f;
-            }
-        };
-
-        int gi = wave;
-        int rs, len, rs_n, len_n;
-        load_row(gi, rs, len);
-        load_row(gi + WAVES, rs_n, len_n);
-        int col[U], coln[U];
-        float val[U], valn[U];
-        load_chunk(rs, len, 0, col, val);
-        while (gi < n_groups) {
-            // the next group's first chunk and the rows of the group after it: in flight during the multiply
-            load_chunk(rs_n, len_n, 0, coln, valn);
-            int rs_nn, len_nn;
-            load_row(gi + 2 * WAVES, rs_nn, len_nn);
-
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-            for (int c0 = 0;; c0 += 4 * U) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (!__builtin_amdgcn_ballot_w64(c0 + 4 * u < len)) break;  // no row of the wavefront reaches this far
-                    const int cc[4] = {quad_bcast<0>(col[u]), quad_bcast<1>(col[u]), quad_bcast<2>(col[u]),
-                                       quad_bcast<3>(col[u])};
-                    const int vbits = __float_as_int(val[u]);
-                    const float vv[4] = {__int_as_float(quad_bcast<0>(vbits)), __int_as_float(quad_bcast<1>(vbits)),
-                                         __int_as_float(quad_bcast<2>(vbits)), __int_as_float(quad_bcast<3>(vbits))};
-                    f32x4 b[4];
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const f32x4*>(Bq + cc[s]);
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) acc += vv[s] * b[s];
-                }
-                if (!__builtin_amdgcn_ballot_w64(c0 + 4 * U < len)) break;
-                load_chunk(rs, len, c0 + 4 * U, col, val);  // rows longer than a chunk: fetched on demand
-            }
-
-            const int r = base_of(gi) + rsub;
-            if (r < row_hi && 4 * q < kw) {
-                float* dst = a.C + static_cast<size_t>(r) * a.ldc + k0 + 4 * q;
-                const bool first = cb0 == 0;
-                const bool reads_c = !first || a.beta != 0.f;
-                const float scale_c = first ? a.beta : 1.f;
-                if (full4) {
-                    f32x4 out = a.alpha * acc;
-                    if (reads_c) out += scale_c * *reinterpret_cast<const f32x4*>(dst);
-                    *reinterpret_cast<f32x4*>(dst) = out;
-                } else {
-                    for (int t = 0; t < 4; ++t)
-                        if (4 * q + t < kw) dst[t] = a.alpha * acc[t] + (reads_c ? scale_c * dst[t] : 0.f);
-                }
-            }
-            gi += WAVES;
-            rs = rs_n;
-            len = len_n;
-            rs_n = rs_nn;
-            len_n = len_nn;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                col[u] = coln[u];
-                val[u] = valn[u];
-            }
-        }
-    }
-}
-
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
 // are consecutive; the thread of the first of them sums the run in chunk order.
 __global__ __launch_bounds__(kWG) void merge_fixup_kernel(const int32_t* __restrict__ carry_row,
@@ -1010,109 +761,6 @@ __global__ __launch_bounds__(kWG) void merge_fixup_kernel(const int32_t* __restr
     float s = 0.f;
     for (int q = p; q < P && carry_row[q] == r; ++q) s += carry_val[q];
     y[r] += alpha * s;
-}
-
-// ------------------------------------------------------------------------------------------
-// y <- alpha*A*x + beta*y for A in the other storage layouts of the benchmark (App. C tasks 8,
-// 10, 14).  ELL rows are independent and are reduced like CSR rows.  COO and CSC entries arrive
-// grouped by nothing (COO) or by column (CSC), so their contributions are added to y with
-// hardware float atomics after y has been scaled by beta in a kernel of its own; sums therefore
-// depend on the order in which the atomics land (results agree to rounding, not bit for bit).
-__global__ __launch_bounds__(kWG) void scale_y_kernel(float* __restrict__ y, int m, float beta) {
-    for (int i = blockIdx.x * kWG + threadIdx.x; i < m; i += gridDim.x * kWG) y[i] = beta == 0.f ? 0.f : beta * y[i];
-}
-
-// One entry per lane and trip.  Runs of equal row numbers in consecutive lanes (the whole
-// wavefront when the entries are sorted by row) are summed first with a segmented scan, so a
-// run costs one atomic instead of one per entry.
-template <typename T>
-__global__ __launch_bounds__(kWG) void spmv_coo_kernel(const int32_t* __restrict__ row, const int32_t* __restrict__ col,
-                                                       const typename T::elem* __restrict__ vals,
-                                                       const typename T::elem* __restrict__ x, float* y, int nnz,
-                                                       float alpha) {
-    const int lane = threadIdx.x & 63;
-    const int wave = (blockIdx.x * kWG + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * kWG) >> 6;
-    for (int base = wave * 64; base < nnz; base += n_waves * 64) {  // the same trip count for all lanes of a wavefront
-        const int e = base + lane;
-        const bool live = e < nnz;
-        const int r = live ? row[e] : -1;
-        float p = live ? alpha * (widen(vals[e]) * widen(x[col[e]])) : 0.f;
-        const int r_prev = __shfl_up(r, 1, 64);
-        bool head = lane == 0 || r_prev != r;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const float pp = __shfl_up(p, d, 64);
-            const int hh = __shfl_up(static_cast<int>(head), d, 64);
-            if (lane >= d && !head) {
-                p += pp;
-                head = hh != 0;
-            }
-        }
-        const int r_next = __shfl_down(r, 1, 64);
-        if (live && (lane == 63 || r_next != r)) unsafeAtomicAdd(y + r, p);
-    }
-}
-
-// A team of G lanes per column: its entries all multiply the same x[j] and go to different rows.
-template <typename T, int G>
-__global__ __launch_bounds__(kWG) void spmv_csc_kernel(const int32_t* __restrict__ col_offsets,
-                                                       const int32_t* __restrict__ row,
-                                                       const typename T::elem* __restrict__ vals,
-                                                       const typename T::elem* __restrict__ x, float* y, int n, float alpha) {
-    const int j = (blockIdx.x * kWG + threadIdx.x) / G;
-    const int tl = threadIdx.x % G;
-    if (j >= n) return;
-    const float xj = alpha * widen(x[j]);
-    const int e1 = col_offsets[j + 1];
-    for (int e = col_offsets[j] + tl; e < e1; e += G) unsafeAtomicAdd(y + row[e], widen(vals[e]) * xj);
-}
-
-// The same for matrices with few rows, where the atomics of thousands of columns would queue up
-// on the same few addresses of y: a workgroup adds its columns into a private copy of y in LDS
-// and sends every row's total to memory once.  Few workgroups, so few atomics per address.
-template <typename T, int G>
-__global__ __launch_bounds__(kWG) void spmv_csc_lds_kernel(const int32_t* __restrict__ col_offsets,
-                                                           const int32_t* __restrict__ row,
-                                                           const typename T::elem* __restrict__ vals,
-                                                           const typename T::elem* __restrict__ x, float* y, int m, int n,
-                                                           float alpha) {
-    extern __shared__ __align__(16) unsigned char smem_raw[];
-    float* ly = reinterpret_cast<float*>(smem_raw);  // [m]
-    for (int i = threadIdx.x; i < m; i += kWG) ly[i] = 0.f;
-    __syncthreads();
-    const int tl = threadIdx.x % G;
-    for (int j = (blockIdx.x * kWG + threadIdx.x) / G; j < n; j += gridDim.x * (kWG / G)) {
-        const float xj = alpha * widen(x[j]);
-        const int e1 = col_offsets[j + 1];
-        for (int e = col_offsets[j] + tl; e < e1; e += G) atomicAdd(ly + row[e], widen(vals[e]) * xj);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < m; i += kWG) {
-        const float v = ly[i];
-        if (v != 0.f) unsafeAtomicAdd(y + i, v);
-    }
-}
-
-// A team of G lanes per row of `width` slots; a slot with col_id -1 is padding.
-template <typename T, int G>
-__global__ __launch_bounds__(kWG) void spmv_ell_kernel(const int32_t* __restrict__ col_ids,
-                                                       const typename T::elem* __restrict__ vals,
-                                                       const typename T::elem* __restrict__ x, float* y, int m, int width,
-                                                       float alpha, float beta) {
-    const int i = (blockIdx.x * kWG + threadIdx.x) / G;
-    const int tl = threadIdx.x % G;
-    const bool live = i < m;
-    float acc = 0.f;
-    if (live) {
-        const size_t base = static_cast<size_t>(i) * width;
-        for (int s = tl; s < width; s += G) {
-            const int c = col_ids[base + s];
-            if (c >= 0) acc += widen(vals[base + s]) * widen(x[c]);
-        }
-    }
-    acc = group_sum<G>(acc);  // every lane of the wavefront takes part
-    if (live && tl == 0) y[i] = epilogue(acc, alpha, beta, y, i);
 }
 
 __global__ __launch_bounds__(kWG) void validate_columns_kernel(const int32_t* __restrict__ colidx, int nnz, int n,
@@ -1139,7 +787,6 @@ __global__ __launch_bounds__(64) void reduce_selftest_kernel(const float* in, fl
     for (int gi = 0; gi < 7; ++gi) out[(7 + gi) * 64 + l] = group_sum_rt(v, 1 << gi);
 }
 
-inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
 template <typename T>
 hipError_t launch_scalar_t(const MatrixView& A, const int32_t* rows, int32_t count, const void* x, float* y, Scalars s,
@@ -1339,138 +986,12 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t 
     return hipGetLastError();
 }
 
-hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* C, int64_t ldc, int32_t K, Scalars s,
-                       hipStream_t st) {
-    if (A.m <= 0 || K <= 0) return hipSuccess;
-    if (A.bf16) return hipErrorInvalidValue;
-    SpmmArgs a{};
-    a.rowptr = A.rowptr;
-    a.colidx = A.colidx;
-    a.vals = static_cast<const float*>(A.vals);
-    a.B = B;
-    a.C = C;
-    a.ldb = ldb;
-    a.ldc = ldc;
-    a.m = A.m;
-    a.n = A.n;
-    a.K = K;
-    a.nnz = A.nnz;
-    a.alpha = s.alpha;
-    a.beta = s.beta;
-    a.vec_ok = (reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldb % 4 == 0 &&
-                ldc % 4 == 0)
-                   ? 1
-                   : 0;
-    const int slices = ceil_div(K, kSpmmKT);
-    // one workgroup fits a CU (its B slice takes most of the LDS): aim at one per CU or more
-    int splits = slices >= 256 ? 1 : ceil_div(256, slices);
-    const int max_splits = ceil_div(A.m, 16);
-    if (splits > max_splits) splits = max_splits;
-    a.row_splits = splits;
-    const size_t lds = sizeof(float) * (kSpmmNB + 1) * kSpmmKT;  // the B block and one zero row
-    static thread_local bool allowed = false;
-    if (!allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(spmm_csr_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return e;
-        allowed = true;
-    }
-    hipLaunchKernelGGL(spmm_csr_kernel, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
-    return hipGetLastError();
-}
-
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st) {
     if (A.nnz <= 0) return hipSuccess;
     int grid = ceil_div(A.nnz, kWG);
     if (grid > 4096) grid = 4096;
     hipLaunchKernelGGL(validate_columns_kernel, dim3(grid), dim3(kWG), 0, st, A.colidx, A.nnz, A.n, flag);
     return hipGetLastError();
-}
-
-namespace {
-
-int lanes_for_length(int64_t len) {  // smallest power of two G in [2, 64] with 8*G >= len
-    int G = 2;
-    while (G < 64 && 8 * G < len) G <<= 1;
-    return G;
-}
-
-template <typename T>
-hipError_t launch_coo_t(int32_t m, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals, const void* x,
-                        float* y, Scalars s, hipStream_t st) {
-    using E = typename T::elem;
-    int grid = ceil_div(m, kWG);
-    hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, s.beta);
-    if (nnz > 0) {
-        grid = ceil_div(nnz, kWG);
-        hipLaunchKernelGGL((spmv_coo_kernel<T>), dim3(grid > 8192 ? 8192 : grid), dim3(kWG), 0, st, row, col,
-                           static_cast<const E*>(vals), static_cast<const E*>(x), y, nnz, s.alpha);
-    }
-    return hipGetLastError();
-}
-
-template <typename T, int G>
-hipError_t launch_csc_tg(int32_t m, int32_t n, const int32_t* col_offsets, const int32_t* row, const void* vals,
-                         const void* x, float* y, Scalars s, hipStream_t st) {
-    using E = typename T::elem;
-    const int grid = ceil_div(m, kWG);
-    hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, s.beta);
-    if (n <= 0) return hipGetLastError();
-    const int blocks = ceil_div(static_cast<int64_t>(n) * G, kWG);
-    if (m <= kCscLdsRows) {
-        // a private y per workgroup: 64 workgroups keep the chip busy enough for these small problems
-        // and leave at most 64 atomics per row
-        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(blocks > 64 ? 64 : blocks), dim3(kWG), sizeof(float) * m, st,
-                           col_offsets, row, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, n, s.alpha);
-    } else {
-        hipLaunchKernelGGL((spmv_csc_kernel<T, G>), dim3(blocks), dim3(kWG), 0, st, col_offsets, row,
-                           static_cast<const E*>(vals), static_cast<const E*>(x), y, n, s.alpha);
-    }
-    return hipGetLastError();
-}
-
-template <typename T, int G>
-hipError_t launch_ell_tg(int32_t m, int32_t width, const int32_t* col_ids, const void* vals, const void* x, float* y,
-                         Scalars s, hipStream_t st) {
-    using E = typename T::elem;
-    hipLaunchKernelGGL((spmv_ell_kernel<T, G>), dim3(ceil_div(static_cast<int64_t>(m) * G, kWG)), dim3(kWG), 0, st,
-                       col_ids, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, width, s.alpha, s.beta);
-    return hipGetLastError();
-}
-
-}  // namespace
-
-hipError_t launch_coo(bool bf16, int32_t m, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
-                      const void* x, float* y, Scalars s, hipStream_t st) {
-    if (m <= 0) return hipSuccess;
-    return bf16 ? launch_coo_t<BF16>(m, nnz, row, col, vals, x, y, s, st)
-                : launch_coo_t<F32>(m, nnz, row, col, vals, x, y, s, st);
-}
-
-hipError_t launch_csc(bool bf16, int32_t m, int32_t n, int32_t nnz, const int32_t* col_offsets, const int32_t* row,
-                      const void* vals, const void* x, float* y, Scalars s, hipStream_t st) {
-    if (m <= 0) return hipSuccess;
-#define SPMV_CSC_CASE(G) \
-    case G: return bf16 ? launch_csc_tg<BF16, G>(m, n, col_offsets, row, vals, x, y, s, st) \
-                        : launch_csc_tg<F32, G>(m, n, col_offsets, row, vals, x, y, s, st);
-    switch (lanes_for_length(n > 0 ? (nnz + n - 1) / n : 0)) {
-        SPMV_CSC_CASE(2) SPMV_CSC_CASE(4) SPMV_CSC_CASE(8) SPMV_CSC_CASE(16) SPMV_CSC_CASE(32) SPMV_CSC_CASE(64)
-    }
-#undef SPMV_CSC_CASE
-    return hipErrorInvalidValue;
-}
-
-hipError_t launch_ell(bool bf16, int32_t m, int32_t width, const int32_t* col_ids, const void* vals, const void* x,
-                      float* y, Scalars s, hipStream_t st) {
-    if (m <= 0) return hipSuccess;
-#define SPMV_ELL_CASE(G) \
-    case G: return bf16 ? launch_ell_tg<BF16, G>(m, width, col_ids, vals, x, y, s, st) \
-                        : launch_ell_tg<F32, G>(m, width, col_ids, vals, x, y, s, st);
-    switch (lanes_for_length(width)) {
-        SPMV_ELL_CASE(2) SPMV_ELL_CASE(4) SPMV_ELL_CASE(8) SPMV_ELL_CASE(16) SPMV_ELL_CASE(32) SPMV_ELL_CASE(64)
-    }
-#undef SPMV_ELL_CASE
-    return hipErrorInvalidValue;
 }
 
 hipError_t launch_reduce_selftest(const float* in, float* out, hipStream_t st) {
@@ -1482,6 +1003,5 @@ const char* scalar_kernel_name() { return "spmv_scalar_kernel"; }
 const char* vector_kernel_name() { return "spmv_vector_kernel"; }
 const char* tile_kernel_name() { return "spmv_tile_kernel"; }
 const char* window_kernel_name() { return "spmv_window_kernel"; }
-const char* spmm_kernel_name() { return "spmm_csr_kernel"; }
 
 }  // namespace spmv
