@@ -322,6 +322,42 @@ def formats_sweep(args):
     return out
 
 
+def graph_replay(args, configs=(1, 2)):
+    """The same steps recorded once into a HIP graph and replayed (stream capture of spmv_csr_run):
+    what the launch-bound configs cost when the host's launch path is taken out."""
+    import torch
+    import workloads as w
+    out = []
+    params = dict(plan=0)
+    for k in configs:
+        p = w.config(k)
+        bytes_alg = p.algorithmic_bytes()
+        copies = min(64, max(2, -(-ROTATE_TOTAL_BYTES // bytes_alg)))
+        res = Resident(p, copies, params)
+        side = torch.cuda.Stream()
+        for i in range(copies):                       # eager pass first: nothing but launches may happen under capture
+            res.step(i, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            h = torch.cuda.current_stream().cuda_stream
+            for i in range(args.steps):
+                res.step(i, h)
+        for _ in range(2):
+            g.replay()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        out.append({"workload": p.name, "steps_in_graph": args.steps, "copies_rotated": copies, "ms_per_step": ms,
+                    "GBps": bytes_alg / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS})
+        res.close()
+    return out
+
+
 def cpu_baseline(p):
     """The oracle as it stands, one thread, on the whole workload: 1 warm-up + best of 5."""
     import oracle
@@ -397,6 +433,7 @@ def main():
         line["paper_sweep"] = paper_sweep(args)
         line["spmm_csr"] = spmm_sweep(args)
         line["formats"] = formats_sweep(args)
+        line["graph_replay"] = graph_replay(args)
     print(json.dumps(line))
 
 

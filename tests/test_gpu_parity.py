@@ -286,3 +286,30 @@ def test_degenerate_shapes():
         assert np.array_equal(d.run(A), 3.0 * y0)
         assert np.array_equal(d.run(A, 1.0, 0.0), np.zeros(7, np.float32))
         A.close()
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("k,plan", [(2, 0), (4, 0), (1, 0), (5, 3)])
+def test_run_can_be_captured_in_a_graph_and_replayed(k, plan):
+    """spmv_csr_run only enqueues kernels (no allocation, copy, memset or synchronisation), so a stream
+    capture records it as it is.  Every replay is checked against the eager result, with eager work and
+    synchronisations of the program's own in between."""
+    p = w.config(k, 1.0 if k == 1 else 1 / 16)
+    d = DeviceProblem(p)
+    A = d.matrix(dict(plan=plan))
+    y_eager = d.run(A)                                   # also sets any per-kernel attribute before the capture
+    y = d.y0.clone()
+    y_in = d.y0.clone()
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        y.copy_(y_in)                                    # beta != 0 reads y: restore it inside the graph
+        A.run(d.x, y, p.alpha, p.beta, torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        y.fill_(float("nan"))
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy(), y_eager), (p.name, rep)
+        assert np.array_equal(d.run(A), y_eager)         # eager work between replays
+    A.close()
