@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="headline workload: 1..5 (BASELINE configs, 1-based)")
+    ap.add_argument("--config", type=int, default=2, help="headline workload: one of the five configurations, 1..5")
     ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 scalar, 2 vector, 3 binned, 4 adaptive, 5 merge")
     ap.add_argument("--block-nnz", type=int, default=0)
     ap.add_argument("--rows-max", type=int, default=0)
