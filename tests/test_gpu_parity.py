@@ -313,3 +313,35 @@ def test_run_can_be_captured_in_a_graph_and_replayed(k, plan):
         assert np.array_equal(y.cpu().numpy(), y_eager), (p.name, rep)
         assert np.array_equal(d.run(A), y_eager)         # eager work between replays
     A.close()
+
+
+# ------------------------------------------------------------------ seeded random shapes, every plan, random tile parameters
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_shapes_and_parameters(seed):
+    rng = np.random.default_rng(1000 + seed)
+    dtype = "f32" if seed % 2 == 0 else "bf16"
+    m = int(rng.integers(1, 6000))
+    n = int(rng.integers(1, 9000))
+    kind = seed % 4
+    if kind == 0:
+        lens = rng.integers(0, min(n, 40) + 1, m)
+    elif kind == 1:
+        lens = np.minimum(w.powerlaw_lengths(rng, m), n)
+    elif kind == 2:
+        lens = np.where(rng.random(m) < 0.7, 0, rng.integers(0, min(n, 700) + 1, m))     # mostly empty rows
+    else:
+        lens = np.full(m, min(n, int(rng.integers(1, 130))))
+    p = w.from_row_lengths(lens, n, seed=seed, dtype=dtype, alpha=float(rng.choice([1.0, -2.0, 0.5])),
+                           beta=float(rng.choice([0.0, 1.0, -0.75])), sort_cols=bool(seed % 3), allow_dup=bool(seed % 5 == 0))
+    y_ref, S_ref = reference(p)
+    d = DeviceProblem(p)
+    trials = [dict(plan=pl) for pl in (0, 1, 2, 3, 5)]
+    for _ in range(3):
+        trials.append(dict(plan=4, block_nnz=int(rng.integers(1, 8193)), rows_max=int(rng.integers(1, 1025))))
+        trials.append(dict(plan=6, block_nnz=int(rng.integers(1, 1025)), rows_max=int(rng.integers(1, 1025))))
+        trials.append(dict(plan=5, items_per_chunk=int(rng.integers(1, 8193))))
+    for params in trials:
+        log("case random", seed, p.name, dtype, m, n, params)
+        A = d.matrix(params)
+        assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, what=str(params))
+        A.close()
