@@ -19,7 +19,7 @@ SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp", _HERE / "sp
 _lib = None
 
 NUM_BINS = 33
-PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed"}
+PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock"}
 MAX_X_VECTORS = 1024
 
 
@@ -71,6 +71,12 @@ def _load():
         _lib.oracle_x_windows.restype = i64
         _lib.oracle_window_choice.argtypes = [i64, vp, i64, i32]
         _lib.oracle_window_choice.restype = i32
+        _lib.oracle_column_blocks.argtypes = [i64, i64, vp, vp, i64, vp, vp, vp, vp]
+        _lib.oracle_column_blocks.restype = i64
+        _lib.oracle_column_block_width.argtypes = [i32]
+        _lib.oracle_column_block_width.restype = i64
+        _lib.oracle_column_block_choice.argtypes = [i64, i64, i32, i32]
+        _lib.oracle_column_block_choice.restype = i32
     return _lib
 
 
@@ -254,3 +260,22 @@ def x_windows(rowptr, colidx, row_blocks, block_nnz, vec_elems):
 def window_choice(nv, nnz, max_vectors=MAX_X_VECTORS):
     nv = np.ascontiguousarray(nv, dtype=np.int32)
     return bool(_load().oracle_window_choice(nv.size, _p(nv), nnz, max_vectors))
+
+
+def column_blocks(m, n, rowptr, colidx, width):
+    """(cb_ptr[C+1], cb_row[nnz], cb_col[nnz], cb_src[nnz]) of the column-blocked regrouping."""
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
+    C = (n + width - 1) // width
+    nnz = colidx.size
+    ptr = np.zeros(C + 1, np.int32)
+    row, col, src = (np.zeros(max(nnz, 1), np.int32) for _ in range(3))
+    assert _load().oracle_column_blocks(m, n, _p(rowptr), _p(colidx), width, _p(ptr), _p(row), _p(col), _p(src)) == C
+    return ptr, row[:nnz], col[:nnz], src[:nnz]
+
+
+def column_block_width(dtype):
+    return int(_load().oracle_column_block_width(4 if dtype == "f32" else 2))
+
+
+def column_block_choice(n, nnz, dtype, plan):
+    return bool(_load().oracle_column_block_choice(n, nnz, 4 if dtype == "f32" else 2, plan))

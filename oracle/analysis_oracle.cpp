@@ -216,4 +216,44 @@ int32_t oracle_window_choice(int64_t nb, const int32_t* nv, int64_t nnz, int32_t
     return 4 * nb * V <= nnz ? 1 : 0;
 }
 
+// ---- column blocks ----------------------------------------------------------------------
+// Columns are cut into blocks of `width` consecutive columns (block b = columns b*width ..
+// (b+1)*width - 1).  The entries are regrouped block after block; inside a block they keep the
+// order they have in the row-major arrays (row after row, and inside a row the stored order).
+//   cb_ptr[b]  = number of entries in blocks before b  (C + 1 values, C = ceil(n / width))
+//   cb_row[k]  = row of the k-th regrouped entry
+//   cb_col[k]  = its column minus the first column of its block
+//   cb_src[k]  = its position in the original arrays (so its value is vals[cb_src[k]])
+// Returns C.
+int64_t oracle_column_blocks(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int64_t width,
+                             int32_t* cb_ptr, int32_t* cb_row, int32_t* cb_col, int32_t* cb_src) {
+    const int64_t C = (n + width - 1) / width;
+    int64_t k = 0;
+    for (int64_t b = 0; b < C; ++b) {
+        cb_ptr[b] = static_cast<int32_t>(k);
+        for (int64_t i = 0; i < m; ++i)
+            for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e)
+                if (colidx[e] / width == b) {
+                    cb_row[k] = static_cast<int32_t>(i);
+                    cb_col[k] = static_cast<int32_t>(colidx[e] - b * width);
+                    cb_src[k] = static_cast<int32_t>(e);
+                    ++k;
+                }
+    }
+    cb_ptr[C] = static_cast<int32_t>(k);
+    return C;
+}
+
+// Block width and the automatic choice.  A block of x is 4 MiB (2^20 binary32 or 2^21 bf16
+// columns: what one die's L2 holds).  The column-blocked plan is taken when the matrix would
+// otherwise run on row blocks or merge-path chunks with x gathered from memory (plan 4 or 5),
+// x is larger than two blocks, there are at most 16 blocks and at least 2^22 entries.
+int64_t oracle_column_block_width(int32_t elem_bytes) { return (int64_t{4} << 20) / elem_bytes; }
+
+int32_t oracle_column_block_choice(int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan) {
+    const int64_t width = oracle_column_block_width(elem_bytes);
+    const int64_t C = (n + width - 1) / width;
+    return ((plan == 4 || plan == 5) && n > 2 * width && C <= 16 && nnz >= (int64_t{1} << 22)) ? 1 : 0;
+}
+
 }  // extern "C"

@@ -244,3 +244,48 @@ def test_window_choice_rule():
     assert not oracle.window_choice([], 0)
     assert not oracle.window_choice([1, 100], 500)         # the stride is the largest count: 4 * 2 * 100 > 500
     assert oracle.window_choice([1, 100], 800)
+
+
+# ---- column blocks ----------------------------------------------------------------------
+def test_column_blocks_handworked(hand):
+    """rowptr [0,3,5,9], columns [1,9,17 | 8,3 | 40,16,2,41], width 16: block 0 holds columns 0..15
+    (entries 0,1 of row 0; 3,4 of row 1; 7 of row 2), block 1 columns 16..31 (entry 2; entry 6),
+    block 2 columns 32..47 (entries 5, 8)."""
+    h = hand["x_windows"]
+    rp, ci = np.array(h["rowptr"], np.int32), np.array(h["colidx"], np.int32)
+    ptr, row, col, src = oracle.column_blocks(3, 42, rp, ci, 16)
+    assert ptr.tolist() == [0, 5, 7, 9]
+    assert src.tolist() == [0, 1, 3, 4, 7, 2, 6, 5, 8]
+    assert row.tolist() == [0, 0, 1, 1, 2, 0, 2, 2, 2]
+    assert col.tolist() == [1, 9, 8, 3, 2, 1, 0, 8, 9]
+
+
+@pytest.mark.parametrize("width", [1, 7, 64, 1 << 20])
+def test_column_blocks_properties(width):
+    import workloads as w
+    for p in [w.uniform_rows(200, 300, 9), w.powerlaw(1500), w.from_row_lengths([6] * 50, 40, allow_dup=True, sort_cols=False)] + w.tiny_adversarial():
+        if (p.n + width - 1) // width > 5000:
+            continue
+        ptr, row, col, src = oracle.column_blocks(p.m, p.n, p.rowptr, p.colidx, width)
+        C = ptr.size - 1
+        assert ptr[0] == 0 and ptr[-1] == p.nnz and np.all(np.diff(ptr) >= 0)
+        assert np.array_equal(np.sort(src), np.arange(p.nnz))                       # a permutation of the entries
+        rows_of = np.repeat(np.arange(p.m, dtype=np.int32), np.diff(p.rowptr))
+        assert np.array_equal(row, rows_of[src])
+        blk = np.repeat(np.arange(C), np.diff(ptr))
+        assert np.array_equal(col + blk * width, p.colidx[src]) and np.all((0 <= col) & (col < width))
+        for b in range(C):
+            assert np.all(np.diff(src[ptr[b]:ptr[b + 1]]) > 0)                       # original order kept inside a block
+
+
+def test_column_block_choice_rule():
+    assert oracle.column_block_width("f32") == 1 << 20 and oracle.column_block_width("bf16") == 1 << 21
+    big = 1 << 22
+    assert oracle.column_block_choice(4_000_000, 31_000_000, "f32", 5)
+    assert oracle.column_block_choice(4_000_000, 31_000_000, "f32", 4)
+    assert not oracle.column_block_choice(4_000_000, 31_000_000, "f32", 6)          # windows already keep x on chip
+    assert not oracle.column_block_choice(2 << 20, 31_000_000, "f32", 5)            # x is exactly two blocks
+    assert oracle.column_block_choice((2 << 20) + 1, big, "f32", 5)
+    assert not oracle.column_block_choice((2 << 20) + 1, big - 1, "f32", 5)         # too few entries to pay for the passes
+    assert not oracle.column_block_choice(4_000_000, 31_000_000, "bf16", 5)         # 8 MB of bf16 x: two blocks
+    assert not oracle.column_block_choice(17 << 20, 1 << 30, "f32", 5)              # more than 16 blocks
