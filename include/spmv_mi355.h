@@ -56,8 +56,10 @@ typedef enum {
     SPMV_PLAN_BINNED = 3,   /* rows grouped by length bin; scalar or vector kernel per bin      */
     SPMV_PLAN_ADAPTIVE = 4, /* contiguous row blocks streamed through LDS (CSR-Adaptive)        */
     SPMV_PLAN_MERGE = 5,    /* equal-work merge-path chunks + carry fix-up                      */
-    SPMV_PLAN_WINDOWED = 6  /* ADAPTIVE row blocks whose x values are served from a per-block
+    SPMV_PLAN_WINDOWED = 6, /* ADAPTIVE row blocks whose x values are served from a per-block
                                window in LDS, entries addressed by 16-bit window positions      */
+    SPMV_PLAN_COLBLOCK = 7  /* entries regrouped by blocks of columns (one 4 MiB stretch of x per
+                               block), each block multiplied in coordinate form with atomics    */
 } spmv_plan_t;
 
 #define SPMV_MAX_X_VECTORS 1024 /* most 16-byte x vectors in one row block's window */
@@ -85,6 +87,8 @@ typedef struct {
     int32_t vector_lanes;              /* lanes per row the VECTOR plan uses */
     int32_t block_nnz, rows_max, items_per_chunk; /* parameters in effect */
     int32_t max_x_vectors;             /* most x vectors of any row block (0 when the windows were not counted) */
+    int32_t num_col_blocks;            /* COLBLOCK plan: C, the number of column blocks; 0 otherwise */
+    int32_t col_block_width;           /* COLBLOCK plan: columns per block (a power of two); 0 otherwise */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -102,6 +106,11 @@ typedef struct {
                             xv_pad[b*max_x_vectors ...], then -1 up to the next block:
                             the fixed-stride copy the kernel reads                    */
     uint16_t* lidx;      /* [nnz]  window position of every entry's x value          */
+    /* COLBLOCK plan only (skipped otherwise): */
+    int32_t* cb_ptr;     /* [C+1]  entries in the blocks before block b              */
+    int32_t* cb_row;     /* [nnz]  row of every regrouped entry                      */
+    int32_t* cb_col;     /* [nnz]  its column minus the block's first column         */
+    int32_t* cb_src;     /* [nnz]  its position in the caller's colidx / vals        */
 } spmv_analysis_host_t;
 
 /* Records the matrix (paper App. C task 12: values / col_indices / row_offsets).
@@ -139,6 +148,16 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     reads the lists at a fixed stride of V per block); a forced WINDOWED plan fails with
  *     UNSUPPORTED when V is larger.  The library then holds 2 bytes per
  *     stored entry of its own (lidx) and run() no longer reads colidx.
+ *   - column blocks (plan AUTO that arrived at ADAPTIVE or MERGE, or plan COLBLOCK; built on the
+ *     device).  Columns are cut into blocks of W = 4 MiB / element size columns; the entries are
+ *     regrouped block after block, keeping their row-major order inside a block, each with its
+ *     row (cb_row), its column within the block (cb_col) and its source position (cb_src); the
+ *     library keeps a copy of the values in that order.  AUTO picks COLBLOCK when n > 2 W, there
+ *     are at most 16 blocks and nnz >= 2^22: x then no longer fits the L2s and the row-wise
+ *     kernels would fetch a cache line per entry.  run() multiplies block after block with
+ *     float atomics into y: results are reproducible to rounding, not bit for bit.  The copy is
+ *     taken at analyze time: changing vals afterwards needs a new analyze.  A forced COLBLOCK
+ *     plan fails with UNSUPPORTED when there would be more than 16 blocks.
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
  * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */
 spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params);
@@ -199,7 +218,8 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
 
 /* The analysis of spmv_csr_analyze() on a HOST copy of rowptr, with HOST outputs and no device
  * involved (same definitions, same code path; the column check is skipped, and with no colidx
- * there are no x windows: AUTO never yields WINDOWED here and WINDOWED is INVALID_ARG).  `info` is
+ * there are no x windows and no column blocks: AUTO never yields WINDOWED or COLBLOCK here, and
+ * asking for them is INVALID_ARG).  `info` is
  * required; `out` may be NULL or have NULL members.  bin_rows needs m entries, row_blocks
  * up to m+1, mp_row/mp_nz ceil((m+nnz)/items_per_chunk)+1.
  * Errors: INVALID_ARG, UNSUPPORTED, BAD_STRUCTURE, ALLOC. */

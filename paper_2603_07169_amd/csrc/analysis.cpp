@@ -38,7 +38,7 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
     spmv_analyze_params_t p{};
     if (in) p = *in;
     if (p.reserved[0] != 0 || p.reserved[1] != 0) return SPMV_ERR_INVALID_ARG;
-    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_WINDOWED) return SPMV_ERR_INVALID_ARG;
+    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_COLBLOCK) return SPMV_ERR_INVALID_ARG;
     if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
     if (p.block_nnz < 0 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
     if (p.rows_max < 0 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;
@@ -176,6 +176,14 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
 }  // namespace spmv
 
 namespace spmv {
+
+int64_t column_block_width(spmv_dtype_t dtype) { return (int64_t{4} << 20) / (dtype == SPMV_F32 ? 4 : 2); }
+
+bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan) {
+    const int64_t width = column_block_width(dtype);
+    const int64_t blocks = (n + width - 1) / width;
+    return (plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE) && n > 2 * width && blocks <= 16 && nnz >= (int64_t{1} << 22);
+}
 
 bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest) {
     int64_t sum = 0;

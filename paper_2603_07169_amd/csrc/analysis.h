@@ -35,6 +35,12 @@ void default_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* row
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
                              const spmv_analyze_params_t& params, Analysis* out);
 
+// Columns per block of the column-blocked plan (4 MiB of x), and whether the automatic plan
+// takes it: only in place of ADAPTIVE / MERGE, with x beyond two blocks, at most 16 blocks and
+// at least 2^22 entries.
+int64_t column_block_width(spmv_dtype_t dtype);
+bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan);
+
 // Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x
 // from the windows: every block within SPMV_MAX_X_VECTORS, and the fixed-stride address lists
 // (one slot per block and possible vector) no longer than a quarter of the entries.

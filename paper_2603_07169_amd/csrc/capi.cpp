@@ -43,6 +43,11 @@ struct spmv_csr_s {
     int32_t* d_block_nz = nullptr;  // rowptr[row_blocks[b]]: spares the kernels a dependent load
     int32_t* d_block_desc = nullptr;  // pairs (row_blocks[b], block_nz[b]): one scalar load per workgroup
     int32_t* d_chunk_desc = nullptr;  // pairs (mp_row[p], mp_nz[p])
+    int32_t* d_cb_row = nullptr;   // column blocks (COLBLOCK plan)
+    int32_t* d_cb_col = nullptr;
+    int32_t* d_cb_src = nullptr;
+    void* d_cb_vals = nullptr;
+    std::vector<int32_t> cb_ptr;   // host: [C+1]
     int32_t max_block_entries = 0;  // most entries of any row block that is not a single over-long row
     int32_t* d_mp_row = nullptr;
     int32_t* d_mp_nz = nullptr;
@@ -59,12 +64,16 @@ namespace {
 void free_metadata(spmv_csr_s* h) {
     void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
                     h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
-                    h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc};
+                    h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc, h->d_cb_row, h->d_cb_col,
+                    h->d_cb_src,    h->d_cb_vals};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
     h->d_carry_val = nullptr;
     h->d_xv_ptr = h->d_xv_start = h->d_xv_pad = h->d_block_desc = h->d_chunk_desc = nullptr;
+    h->d_cb_row = h->d_cb_col = h->d_cb_src = nullptr;
+    h->d_cb_vals = nullptr;
+    h->cb_ptr.clear();
     h->d_lidx = nullptr;
     h->analyzed = false;
 }
@@ -136,6 +145,63 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, spmv::Analysis* a) {
         return SPMV_ERR_HIP;
     a->info.plan = SPMV_PLAN_WINDOWED;
     a->info.num_x_vectors = total;
+    return SPMV_OK;
+}
+
+// Regroups the entries by blocks of columns on the device (two kernel passes with a prefix sum on
+// the host in between) and switches the plan to COLBLOCK.
+spmv_status_t build_column_blocks(spmv_csr_s* h, spmv::Analysis* a) {
+    const int64_t width = spmv::column_block_width(h->dtype);
+    const int64_t C64 = h->n > 0 ? (h->n + width - 1) / width : 1;
+    if (C64 > spmv::kMaxColBlocks) return SPMV_ERR_UNSUPPORTED;
+    const int C = static_cast<int>(C64);
+    int shift = 0;
+    while ((int64_t{1} << shift) < width) ++shift;
+    const spmv::MatrixView A = view_of(h);
+    const int32_t ntiles = spmv::column_block_tiles(A.nnz);
+    std::vector<int32_t> counts;
+    try {
+        counts.assign(static_cast<size_t>(C) * static_cast<size_t>(ntiles > 0 ? ntiles : 1), 0);
+        h->cb_ptr.assign(static_cast<size_t>(C) + 1, 0);
+    } catch (const std::bad_alloc&) {
+        return SPMV_ERR_ALLOC;
+    }
+    int32_t* d_counts = nullptr;
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&d_counts), sizeof(int32_t) * counts.size()))) return SPMV_ERR_ALLOC;
+    spmv_status_t st = SPMV_OK;
+    if (hip_failed(spmv::launch_column_block_count(A, shift, C, d_counts, nullptr)) ||
+        hip_failed(hipMemcpy(counts.data(), d_counts, sizeof(int32_t) * counts.size(), hipMemcpyDeviceToHost)))
+        st = SPMV_ERR_HIP;
+    if (st == SPMV_OK) {
+        int64_t run = 0;  // exclusive prefix in (block, tile) order; cb_ptr picks up the block starts
+        for (int b = 0; b < C; ++b) {
+            h->cb_ptr[static_cast<size_t>(b)] = static_cast<int32_t>(run);
+            for (int32_t t = 0; t < ntiles; ++t) {
+                int32_t& c = counts[static_cast<size_t>(b) * static_cast<size_t>(ntiles) + static_cast<size_t>(t)];
+                const int32_t n_here = c;
+                c = static_cast<int32_t>(run);
+                run += n_here;
+            }
+        }
+        h->cb_ptr[static_cast<size_t>(C)] = static_cast<int32_t>(run);
+        const size_t slots = static_cast<size_t>(h->nnz > 0 ? h->nnz : 1);
+        if (hip_failed(hipMemcpy(d_counts, counts.data(), sizeof(int32_t) * counts.size(), hipMemcpyHostToDevice)))
+            st = SPMV_ERR_HIP;
+        else if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_cb_row), sizeof(int32_t) * slots)) ||
+                 hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_cb_col), sizeof(int32_t) * slots)) ||
+                 hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_cb_src), sizeof(int32_t) * slots)) ||
+                 hip_failed(hipMalloc(&h->d_cb_vals, (h->dtype == SPMV_F32 ? 4 : 2) * slots)))
+            st = SPMV_ERR_ALLOC;
+        else if (hip_failed(spmv::launch_column_block_scatter(A, shift, C, d_counts, h->d_cb_row, h->d_cb_col, h->d_cb_src,
+                                                              h->d_cb_vals, nullptr)) ||
+                 hip_failed(hipDeviceSynchronize()))
+            st = SPMV_ERR_HIP;
+    }
+    (void)hipFree(d_counts);
+    if (st != SPMV_OK) return st;
+    a->info.plan = SPMV_PLAN_COLBLOCK;
+    a->info.num_col_blocks = C;
+    a->info.col_block_width = static_cast<int32_t>(width);
     return SPMV_OK;
 }
 
@@ -241,6 +307,10 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         const bool forced = p.plan == SPMV_PLAN_WINDOWED;
         if (forced || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE)) st = build_x_windows(h, forced, &a);
     }
+    if (st == SPMV_OK) {
+        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::column_block_choice(h->n, h->nnz, h->dtype, a.info.plan);
+        if (p.plan == SPMV_PLAN_COLBLOCK || automatic) st = build_column_blocks(h, &a);
+    }
     if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
     if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
     if (st == SPMV_OK) {
@@ -306,6 +376,19 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
             const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx, h->info.max_x_vectors};
             e = spmv::launch_windowed(A, h->d_block_desc, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->max_block_entries, h->info.rows_max, w, x, y, s, st);
+            break;
+        }
+        case SPMV_PLAN_COLBLOCK: {
+            // y <- beta*y once, then every block adds its part; block b reads x from its first column on
+            e = spmv::launch_scale_y(y, m, beta, st);
+            const size_t esz = A.bf16 ? 2 : 4;
+            for (int b = 0; b < h->info.num_col_blocks && e == hipSuccess; ++b) {
+                const int32_t k0 = h->cb_ptr[static_cast<size_t>(b)], k1 = h->cb_ptr[static_cast<size_t>(b) + 1];
+                e = spmv::launch_coo_accumulate(A.bf16, k1 - k0, h->d_cb_row + k0, h->d_cb_col + k0,
+                                                static_cast<const char*>(h->d_cb_vals) + esz * static_cast<size_t>(k0),
+                                                static_cast<const char*>(x) + esz * static_cast<size_t>(b) * h->info.col_block_width,
+                                                y, alpha, st);
+            }
             break;
         }
         case SPMV_PLAN_MERGE:
@@ -421,6 +504,15 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
         if (c.dst && c.count > 0 &&
             hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
             return SPMV_ERR_HIP;
+    if (h->info.plan == SPMV_PLAN_COLBLOCK) {
+        if (out->cb_ptr) std::memcpy(out->cb_ptr, h->cb_ptr.data(), sizeof(int32_t) * h->cb_ptr.size());
+        const Copy ccopies[] = {{out->cb_row, h->d_cb_row, h->info.nnz}, {out->cb_col, h->d_cb_col, h->info.nnz},
+                                {out->cb_src, h->d_cb_src, h->info.nnz}};
+        for (const Copy& c : ccopies)
+            if (c.dst && c.count > 0 &&
+                hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
+                return SPMV_ERR_HIP;
+    }
     if (h->info.plan == SPMV_PLAN_WINDOWED) {
         const Copy wcopies[] = {{out->xv_ptr, h->d_xv_ptr, h->info.num_row_blocks + 1},
                                 {out->xv_start, h->d_xv_start, h->info.num_x_vectors},
@@ -445,7 +537,7 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     spmv_analyze_params_t p{};
     spmv_status_t st = spmv::resolve_params(params, &p);
     if (st != SPMV_OK) return st;
-    if (p.plan == SPMV_PLAN_WINDOWED) return SPMV_ERR_INVALID_ARG;  // the windows need colidx, which is on the device
+    if (p.plan == SPMV_PLAN_WINDOWED || p.plan == SPMV_PLAN_COLBLOCK) return SPMV_ERR_INVALID_ARG;  // they need colidx: device only
     spmv::Analysis a;
     st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
     if (st != SPMV_OK) return st;
@@ -477,6 +569,7 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_ADAPTIVE:
         case SPMV_PLAN_MERGE: return spmv::tile_kernel_name();
         case SPMV_PLAN_WINDOWED: return spmv::window_kernel_name();
+        case SPMV_PLAN_COLBLOCK: return "spmv_coo_kernel";
         default: return "";
     }
 }

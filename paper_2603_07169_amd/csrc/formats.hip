@@ -168,6 +168,27 @@ hipError_t launch_ell_tg(int32_t m, int32_t width, const int32_t* col_ids, const
 
 }  // namespace
 
+hipError_t launch_scale_y(float* y, int32_t m, float beta, hipStream_t st) {
+    if (m <= 0) return hipSuccess;
+    const int grid = ceil_div(m, kWG);
+    hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_coo_accumulate(bool bf16, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
+                                 const void* x, float* y, float alpha, hipStream_t st) {
+    if (nnz <= 0) return hipSuccess;
+    int grid = ceil_div(nnz, kWG);
+    if (grid > 8192) grid = 8192;
+    if (bf16)
+        hipLaunchKernelGGL((spmv_coo_kernel<BF16>), dim3(grid), dim3(kWG), 0, st, row, col, static_cast<const uint16_t*>(vals),
+                           static_cast<const uint16_t*>(x), y, nnz, alpha);
+    else
+        hipLaunchKernelGGL((spmv_coo_kernel<F32>), dim3(grid), dim3(kWG), 0, st, row, col, static_cast<const float*>(vals),
+                           static_cast<const float*>(x), y, nnz, alpha);
+    return hipGetLastError();
+}
+
 hipError_t launch_coo(bool bf16, int32_t m, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
                       const void* x, float* y, Scalars s, hipStream_t st) {
     if (m <= 0) return hipSuccess;

@@ -15,6 +15,8 @@ struct MatrixView {
     bool vec_ok;            // colidx and vals are 16-byte aligned: 128-bit loads allowed
 };
 
+constexpr int kMaxColBlocks = 16;  // most column blocks of the column-blocked plan
+constexpr int kCbTile = 2048;      // entries a wavefront regroups at a time
 constexpr int kMaxXVectors = 1024;     // most 16-byte x vectors a row block may keep in LDS
 constexpr int kMaxTileEntries = 8192;  // most entries of a row block
 
@@ -70,6 +72,20 @@ hipError_t launch_csc(bool bf16, int32_t m, int32_t n, int32_t nnz, const int32_
                       const void* vals, const void* x, float* y, Scalars s, hipStream_t st);
 hipError_t launch_ell(bool bf16, int32_t m, int32_t width, const int32_t* col_ids, const void* vals, const void* x,
                       float* y, Scalars s, hipStream_t st);
+
+// Pieces of the COO product for callers that run several of them into one y.
+hipError_t launch_scale_y(float* y, int32_t m, float beta, hipStream_t st);  // y <- beta*y (0 when beta == 0)
+hipError_t launch_coo_accumulate(bool bf16, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
+                                 const void* x, float* y, float alpha, hipStream_t st);  // y += alpha*A*x, atomics
+
+// Column-blocked regrouping (analysis).  Block of column c = c >> shift; C blocks.  ntiles =
+// column_block_tiles(nnz).  count: tile_counts[b*ntiles + t].  scatter: tile_base = exclusive
+// prefix sums of tile_counts in that order; writes row, column within block, source position
+// and value of every regrouped entry.
+int32_t column_block_tiles(int32_t nnz);
+hipError_t launch_column_block_count(const MatrixView& A, int shift, int C, int32_t* tile_counts, hipStream_t st);
+hipError_t launch_column_block_scatter(const MatrixView& A, int shift, int C, const int32_t* tile_base, int32_t* cb_row,
+                                       int32_t* cb_col, int32_t* cb_src, void* cb_vals, hipStream_t st);
 
 // Cross-lane reduction self-check on one wavefront.  in: device float[64], lane l contributes in[l].
 // out: device float[14*64]; out[gi*64 + l] = sum over lane l's aligned group of G = 2^gi lanes,

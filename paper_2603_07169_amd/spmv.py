@@ -18,8 +18,8 @@ SPMV_OK = 0
 (SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_STRUCTURE, SPMV_ERR_UNSUPPORTED, SPMV_ERR_NOT_ANALYZED, SPMV_ERR_ALLOC,
  SPMV_ERR_HIP) = range(1, 7)
 (SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE,
- SPMV_PLAN_WINDOWED) = range(7)
-PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed"}
+ SPMV_PLAN_WINDOWED, SPMV_PLAN_COLBLOCK) = range(8)
+PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock"}
 SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 
@@ -41,7 +41,8 @@ class spmv_analysis_info_t(C.Structure):
                 ("max_len", C.c_int64), ("n_empty", C.c_int64), ("num_row_blocks", C.c_int64),
                 ("num_chunks", C.c_int64), ("num_x_vectors", C.c_int64), ("plan", C.c_int32),
                 ("vector_lanes", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
-                ("items_per_chunk", C.c_int32), ("max_x_vectors", C.c_int32)]
+                ("items_per_chunk", C.c_int32), ("max_x_vectors", C.c_int32), ("num_col_blocks", C.c_int32),
+                ("col_block_width", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -50,7 +51,8 @@ class spmv_analysis_info_t(C.Structure):
 class spmv_analysis_host_t(C.Structure):
     _fields_ = [("bin_count", C.c_void_p), ("bin_offset", C.c_void_p), ("bin_rows", C.c_void_p),
                 ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
-                ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p)]
+                ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p),
+                ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p)]
 
 
 class SpmvError(RuntimeError):
@@ -175,6 +177,9 @@ def _host_buffers(info):
         bufs.update(xv_ptr=np.zeros(info.num_row_blocks + 1, np.int32), xv_start=np.zeros(info.num_x_vectors, np.int32),
                     xv_pad=np.zeros(info.num_row_blocks * max(1, info.max_x_vectors), np.int32),
                     lidx=np.zeros(info.nnz, np.uint16))
+    if info.plan == SPMV_PLAN_COLBLOCK:
+        bufs.update(cb_ptr=np.zeros(info.num_col_blocks + 1, np.int32), cb_row=np.zeros(info.nnz, np.int32),
+                    cb_col=np.zeros(info.nnz, np.int32), cb_src=np.zeros(info.nnz, np.int32))
     out = spmv_analysis_host_t(**{k: v.ctypes.data for k, v in bufs.items()})
     return bufs, out
 

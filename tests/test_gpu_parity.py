@@ -143,10 +143,12 @@ def test_alpha_beta_grid_and_reuse_on_side_stream():
 
 
 def test_run_is_repeatable_bit_for_bit():
+    """Every plan but COLBLOCK (float atomics) gives the same bits on every run."""
     for k in (2, 4):
         p = w.config(k, 1 / 16)
         d = DeviceProblem(p)
         A = d.matrix()
+        assert A.info.plan != s.SPMV_PLAN_COLBLOCK
         y1 = d.run(A)
         y2 = d.run(A)
         assert np.array_equal(y1, y2)
@@ -252,6 +254,38 @@ def test_forced_windowed_rejects_blocks_with_too_many_vectors():
     s.spmv_destroy(h)
 
 
+@pytest.mark.parametrize("dtype,n", [("f32", 3_500_000), ("bf16", 5_000_000), ("f32", 4000)])
+def test_column_blocks_equal_oracle_and_multiply(dtype, n):
+    """Forced COLBLOCK plan on matrices wide enough for several column blocks (and one that has a single
+    block): the regrouping read back bit for bit, and the product within tolerance."""
+    rng = np.random.default_rng(77)
+    lens = np.concatenate([rng.integers(0, 40, 20000), [3000, 0, 0, 1], rng.integers(0, 5, 5000)])
+    p = w.from_row_lengths(lens, n, seed=5, dtype=dtype, alpha=1.5, beta=-0.5, sort_cols=(dtype == "f32"))
+    d = DeviceProblem(p)
+    log("case column blocks", dtype, n, p.nnz)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_COLBLOCK))
+    width = oracle.column_block_width(dtype)
+    assert A.info.plan == s.SPMV_PLAN_COLBLOCK and A.info.col_block_width == width
+    assert A.info.num_col_blocks == -(-n // width)
+    got = A.analysis()
+    ptr, row, col, src = oracle.column_blocks(p.m, p.n, p.rowptr, p.colidx, width)
+    assert np.array_equal(got["cb_ptr"], ptr) and np.array_equal(got["cb_src"], src)
+    assert np.array_equal(got["cb_row"], row) and np.array_equal(got["cb_col"], col)
+    y_ref, S_ref = reference(p)
+    assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta)
+    A.close()
+
+
+def test_forced_column_blocks_reject_too_many_blocks():
+    p = w.from_row_lengths([3, 0, 5], 17 * (1 << 20) + 1, seed=1)      # 18 blocks of binary32 columns
+    d = DeviceProblem(p)
+    st, h = s.spmv_csr_create(p.m, p.n, p.nnz, d.rowptr.data_ptr(), d.colidx.data_ptr(), d.vals.data_ptr(), 0)
+    assert st == s.SPMV_OK
+    assert s.spmv_csr_analyze(h, dict(plan=s.SPMV_PLAN_COLBLOCK)) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_csr_analyze(h) == s.SPMV_OK
+    s.spmv_destroy(h)
+
+
 def test_analyze_rejects_bad_input_on_device():
     p = w.config(1)
     d = DeviceProblem(p)
@@ -335,7 +369,7 @@ def test_seeded_random_shapes_and_parameters(seed):
                            beta=float(rng.choice([0.0, 1.0, -0.75])), sort_cols=bool(seed % 3), allow_dup=bool(seed % 5 == 0))
     y_ref, S_ref = reference(p)
     d = DeviceProblem(p)
-    trials = [dict(plan=pl) for pl in (0, 1, 2, 3, 5)]
+    trials = [dict(plan=pl) for pl in (0, 1, 2, 3, 5, 7)]
     for _ in range(3):
         trials.append(dict(plan=4, block_nnz=int(rng.integers(1, 8193)), rows_max=int(rng.integers(1, 1025))))
         trials.append(dict(plan=6, block_nnz=int(rng.integers(1, 1025)), rows_max=int(rng.integers(1, 1025))))
