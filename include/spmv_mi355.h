@@ -13,7 +13,9 @@
  * this interface is organised around streaming values/col_indices once with wide loads.
  *
  * Conventions.
- *   - Indices are 0-based int32.  m, n, nnz are passed as int64 and must be < 2^31.
+ *   - Indices are 0-based int32.  m, n, nnz (and K, width) are passed as int64 and must not
+ *     exceed SPMV_MAX_SIZE = 2^31 - 2^22: index arithmetic in the kernels is 32-bit, and the
+ *     margin keeps an index plus one grid stride inside int32.
  *   - Every array argument of create/run is a DEVICE pointer, BORROWED: the caller owns the
  *     memory and must keep rowptr/colidx/vals alive and unchanged until spmv_destroy().
  *     The library owns only the metadata it allocates in spmv_csr_analyze().
@@ -35,6 +37,9 @@ extern "C" {
 
 typedef struct spmv_csr_s* spmv_handle_t;
 
+/* Largest m, n, nnz, K or ELL width any entry point accepts. */
+#define SPMV_MAX_SIZE ((int64_t)2147483647 - 4194303)
+
 /* Storage type of vals AND x.  y, alpha, beta are always float. */
 typedef enum { SPMV_F32 = 0, SPMV_BF16 = 1 } spmv_dtype_t;
 
@@ -42,7 +47,7 @@ typedef enum {
     SPMV_OK = 0,
     SPMV_ERR_INVALID_ARG = 1,   /* null pointer, negative size, unknown enum, parameter out of range */
     SPMV_ERR_BAD_STRUCTURE = 2, /* rowptr[0] != 0, rowptr decreasing, rowptr[m] != nnz, column outside [0,n) */
-    SPMV_ERR_UNSUPPORTED = 3,   /* a size >= 2^31, or pointers not aligned to the element size */
+    SPMV_ERR_UNSUPPORTED = 3,   /* a size > SPMV_MAX_SIZE, or pointers not aligned to the element size */
     SPMV_ERR_NOT_ANALYZED = 4,  /* run or read-back before a successful analyze */
     SPMV_ERR_ALLOC = 5,         /* host or device allocation failed */
     SPMV_ERR_HIP = 6            /* a HIP runtime call failed; see spmv_last_hip_error() */
@@ -180,7 +185,7 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
  *        into C).  B and C must not overlap.
  * 128-bit accesses are used when B and C are 16-byte aligned and ldb, ldc are multiples of 4;
  * any other layout works element by element.  m == 0 or K == 0 is a no-op.
- * Errors: INVALID_ARG (null B or C, K < 0, ldb or ldc < K), UNSUPPORTED (bf16 handle, K >= 2^31,
+ * Errors: INVALID_ARG (null B or C, K < 0, ldb or ldc < K), UNSUPPORTED (bf16 handle, K > SPMV_MAX_SIZE,
  * pointers not 4-byte aligned), NOT_ANALYZED, HIP. */
 spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
                            float beta, void* stream);
@@ -193,11 +198,12 @@ spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* 
  *   COO  vals[nnz], row_indices[nnz], col_indices[nnz] in any order; repeated coordinates add up.
  *   CSC  vals[nnz], row_indices[nnz], col_offsets[n+1] (col_offsets[j] = first entry of column j).
  *   ELL  vals[m*width], col_ids[m*width], row-major; a slot with col_id -1 is padding (its value
- *        is ignored).  width >= 0.
+ *        is ignored).  width >= 0; m*width may exceed SPMV_MAX_SIZE (slots are addressed with
+ *        64-bit offsets).
  * COO and CSC add the entries' contributions to y with float atomics (after y <- beta*y), so
  * their results are reproducible to rounding but not bit for bit; ELL is bit-reproducible.
  * beta == 0 never reads y.  Errors: INVALID_ARG (null pointer with a non-empty array, negative
- * size, unknown dtype), UNSUPPORTED (a size >= 2^31, misaligned pointer), HIP. */
+ * size, unknown dtype), UNSUPPORTED (a size > SPMV_MAX_SIZE, misaligned pointer), HIP. */
 spmv_status_t spmv_coo_run(int64_t m, int64_t n, int64_t nnz, const int32_t* row_indices, const int32_t* col_indices,
                            const void* vals, spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta,
                            void* stream);

@@ -21,7 +21,7 @@ inline bool hip_failed(hipError_t e) {
     return true;
 }
 
-constexpr int64_t kMaxCount = (int64_t{1} << 31) - 1024;  // keeps k + vector width inside int32
+constexpr int64_t kMaxCount = SPMV_MAX_SIZE;  // an index plus a grid stride (at most 2^21) stays inside int32
 
 }  // namespace
 
@@ -462,9 +462,10 @@ spmv_status_t spmv_csc_run(int64_t m, int64_t n, int64_t nnz, const int32_t* col
 
 spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* col_ids, const void* vals,
                            spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta, void* stream) {
-    if (width < 0 || width > kMaxCount) return SPMV_ERR_INVALID_ARG;
-    const int64_t slots = m > 0 ? m * width : 0;
-    const spmv_status_t st = check_stateless(m, n, slots > kMaxCount ? kMaxCount : slots, dtype, col_ids, col_ids, vals, x, y);
+    if (width < 0) return SPMV_ERR_INVALID_ARG;
+    if (width > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    // m * width itself may exceed the limit: slots are addressed with 64-bit offsets
+    const spmv_status_t st = check_stateless(m, n, m > 0 ? width : 0, dtype, col_ids, col_ids, vals, x, y);
     if (st != SPMV_OK) return st;
     const hipError_t e = spmv::launch_ell(dtype == SPMV_BF16, static_cast<int32_t>(m), static_cast<int32_t>(width), col_ids,
                                           vals, x, y, spmv::Scalars{alpha, beta}, static_cast<hipStream_t>(stream));

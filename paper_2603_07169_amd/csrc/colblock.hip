@@ -27,31 +27,35 @@ __global__ __launch_bounds__(64) void cb_tile_kernel(const int32_t* __restrict__
                                                      const int32_t* __restrict__ tile_base, int32_t* __restrict__ cb_row,
                                                      int32_t* __restrict__ cb_col, int32_t* __restrict__ cb_src,
                                                      void* __restrict__ cb_vals) {
-    __shared__ int running[kMaxColBlocks];  // entries of this tile seen so far, per block
+    // Entries of this tile seen so far, per block.  Ballots are uniform over the wavefront, so every
+    // lane keeps the same counts in its own registers (the loops over blocks are fully unrolled).
+    int running[kMaxColBlocks];
+#pragma unroll
+    for (int b = 0; b < kMaxColBlocks; ++b) running[b] = 0;
     const int lane = threadIdx.x;
     const int tile = blockIdx.x;
-    if (lane < kMaxColBlocks) running[lane] = 0;
     const unsigned long long below = (1ull << lane) - 1ull;
-    for (int step = 0; step < kCbTile / 64; ++step) {  // LDS operations of the one wavefront complete in order
+    for (int step = 0; step < kCbTile / 64; ++step) {
         const int e = tile * kCbTile + step * 64 + lane;
         const bool live = e < nnz;
         const int c = live ? colidx[e] : 0;
         int blk = live ? c >> shift : -1;
         if (blk >= C) blk = -1;  // a column beyond n (only possible when the caller skipped validation): dropped
         int rank = 0;
-        for (int b = 0; b < C; ++b) {
-            const unsigned long long mask = __builtin_amdgcn_ballot_w64(blk == b);
-            if (mask == 0) continue;
-            const int before = running[b];
-            if (blk == b) rank = before + __popcll(mask & below);
-            if (lane == 0) running[b] = before + __popcll(mask);
+#pragma unroll
+        for (int b = 0; b < kMaxColBlocks; ++b) {
+            if (b < C) {
+                const unsigned long long mask = __builtin_amdgcn_ballot_w64(blk == b);
+                if (blk == b) rank = running[b] + __popcll(mask & below);
+                running[b] += __popcll(mask);
+            }
         }
         if constexpr (SCATTER) {
             if (blk >= 0) {
                 const int dest = tile_base[blk * ntiles + tile] + rank;
                 int lo = 0, hi = m;  // the row of entry e: the last i with rowptr[i] <= e
                 while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
+                    const int mid = lo + ((hi - lo + 1) >> 1);
                     if (rowptr[mid] <= e) lo = mid;
                     else hi = mid - 1;
                 }
@@ -64,7 +68,9 @@ __global__ __launch_bounds__(64) void cb_tile_kernel(const int32_t* __restrict__
         }
     }
     if constexpr (!SCATTER) {
-        if (lane < C) tile_counts[lane * ntiles + tile] = running[lane];
+#pragma unroll
+        for (int b = 0; b < kMaxColBlocks; ++b)
+            if (lane == b && b < C) tile_counts[b * ntiles + tile] = running[b];
     }
 }
 

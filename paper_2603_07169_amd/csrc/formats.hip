@@ -58,9 +58,10 @@ __global__ __launch_bounds__(kWG) void spmv_csc_kernel(const int32_t* __restrict
                                                        const int32_t* __restrict__ row,
                                                        const typename T::elem* __restrict__ vals,
                                                        const typename T::elem* __restrict__ x, float* y, int n, float alpha) {
-    const int j = (blockIdx.x * kWG + threadIdx.x) / G;
+    const int64_t j64 = (static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x) / G;
     const int tl = threadIdx.x % G;
-    if (j >= n) return;
+    if (j64 >= n) return;
+    const int j = static_cast<int>(j64);
     const float xj = alpha * widen(x[j]);
     const int e1 = col_offsets[j + 1];
     for (int e = col_offsets[j] + tl; e < e1; e += G) unsafeAtomicAdd(y + row[e], widen(vals[e]) * xj);
@@ -98,9 +99,11 @@ __global__ __launch_bounds__(kWG) void spmv_ell_kernel(const int32_t* __restrict
                                                        const typename T::elem* __restrict__ vals,
                                                        const typename T::elem* __restrict__ x, float* y, int m, int width,
                                                        float alpha, float beta) {
-    const int i = (blockIdx.x * kWG + threadIdx.x) / G;
+    // m * G can pass 2^32 lanes: 64-bit lane number
+    const int64_t i64 = (static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x) / G;
     const int tl = threadIdx.x % G;
-    const bool live = i < m;
+    const bool live = i64 < m;
+    const int i = static_cast<int>(i64);
     float acc = 0.f;
     if (live) {
         const size_t base = static_cast<size_t>(i) * width;

@@ -22,6 +22,7 @@ SPMV_OK = 0
 PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock"}
 SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
+SPMV_MAX_SIZE = 2 ** 31 - 2 ** 22
 
 EXPORTS = [
     "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmm_csr_run", "spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_destroy", "spmv_csr_get_analysis_info",

@@ -50,6 +50,10 @@ def test_create_argument_errors():
     assert ok(4, 4, 8, A, A, A, 7) == s.SPMV_ERR_INVALID_ARG     # unknown dtype
     assert ok(2 ** 31, 4, 8, A, A, A, 0) == s.SPMV_ERR_UNSUPPORTED
     assert ok(4, 4, 2 ** 31, A, A, A, 0) == s.SPMV_ERR_UNSUPPORTED
+    big = s.SPMV_MAX_SIZE
+    for sizes in ((big, 4, 8), (4, big, 8), (4, 4, big)):
+        assert ok(*sizes, A, A, A, 0) == s.SPMV_OK
+        assert ok(*(v + (v == big) for v in sizes), A, A, A, 0) == s.SPMV_ERR_UNSUPPORTED
     assert ok(4, 4, 8, A + 2, A, A, 0) == s.SPMV_ERR_UNSUPPORTED  # rowptr not int32-aligned
     assert ok(4, 4, 8, A, A, A + 2, s.SPMV_F32) == s.SPMV_ERR_UNSUPPORTED
     assert ok(4, 4, 8, A, A, A + 2, s.SPMV_BF16) == s.SPMV_OK
@@ -60,6 +64,24 @@ def test_create_argument_errors():
     assert s.spmv_destroy(h) == s.SPMV_OK
     assert s.spmv_destroy(None) == s.SPMV_OK
     assert s.spmv_csr_analyze(None) == s.SPMV_ERR_INVALID_ARG
+
+
+def test_size_limit_matches_the_header_and_binds_every_entry_point():
+    header = (ROOT / "include" / "spmv_mi355.h").read_text()
+    mm = re.search(r"#define SPMV_MAX_SIZE \(\(int64_t\)(\d+) - (\d+)\)", header)
+    assert int(mm.group(1)) - int(mm.group(2)) == s.SPMV_MAX_SIZE == 2 ** 31 - 2 ** 22
+    big, A = s.SPMV_MAX_SIZE, 4096
+    # one row holding the largest entry count: the host analysis takes it, one more is refused
+    st, info, _ = s.spmv_analyze_host(1, 8, big, np.array([0, big], np.int32), dict(plan=5))
+    assert st == s.SPMV_OK and (info.nnz, info.max_len) == (big, big)
+    assert info.num_chunks == -(-(big + 1) // DEFAULT_ITEMS_PER_CHUNK)
+    assert s.spmv_analyze_host(1, 8, big + 1, np.array([0, 0], np.int32))[0] == s.SPMV_ERR_UNSUPPORTED
+    # the stateless layouts check sizes before anything touches the device
+    assert s.spmv_coo_run(4, 4, big + 1, A, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_coo_run(big + 1, 4, 8, A, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_csc_run(4, big + 1, 8, A, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_ell_run(4, 4, big + 1, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_ell_run(4, 4, -1, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
 
 
 def test_analyze_parameter_ranges():

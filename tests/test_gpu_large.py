@@ -1,0 +1,63 @@
+"""Entry counts beyond 2^30: every plan on a matrix of 1.14 * 10^9 stored entries, compared with
+the oracle row by row, every row.  The kernels index entries with 32-bit integers; this is the
+case that shows an index, or a byte offset formed from one, leaving the 31-bit range."""
+import numpy as np
+import pytest
+
+import oracle
+import paper_2603_07169_amd as s
+import workloads as w
+from gpu_util import DeviceProblem, assert_close, reference
+
+pytestmark = pytest.mark.gpu
+
+
+def test_more_than_2_to_30_entries_every_plan():
+    p = w.clustered_arithmetic()
+    assert 2 ** 30 < p.nnz <= s.SPMV_MAX_SIZE and p.nnz == 1_140_850_688
+    print("case", p.name, p.nnz, flush=True)
+    y_ref, S_ref = reference(p)
+    d = DeviceProblem(p)
+
+    A = d.matrix()
+    print("  analyzed: plan", s.PLAN_NAMES[A.info.plan], flush=True)
+    assert s.PLAN_NAMES[A.info.plan] == "windowed"
+    y = d.run(A)
+    worst = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict=True, what="auto")
+    print(f"  windowed: max |err| / sum|a x| = {worst:.3e}", flush=True)
+    assert np.array_equal(d.run(A), y)
+
+    # analysis outputs, bit for bit where the oracle's literal definitions finish in seconds
+    got = A.analysis()
+    rb = oracle.row_blocks(p.rowptr, A.info.block_nnz, A.info.rows_max)
+    assert np.array_equal(got["row_blocks"], rb)
+    mr, mz = oracle.merge_path(p.rowptr, A.info.items_per_chunk)
+    assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
+    cnt, off, rows = oracle.row_bins(p.rowptr)
+    assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_rows"], rows)
+    # x windows: sampled row blocks (first, last, around entry 2^30, random), each against the
+    # oracle run on that block alone
+    nb = rb.size - 1
+    xv_ptr = got["xv_ptr"]
+    V = int(A.info.max_x_vectors)
+    across = int(np.searchsorted(p.rowptr[rb], 2 ** 30))
+    pick = np.unique(np.concatenate([[0, 1, nb - 2, nb - 1], np.arange(across - 3, across + 3),
+                                     np.random.default_rng(31).integers(0, nb, 200)]))
+    for b in pick:
+        nv, _, xs, li = oracle.x_windows(p.rowptr, p.colidx, rb[b:b + 2].copy(), A.info.block_nnz, 8)
+        k0, k1 = p.rowptr[rb[b]], p.rowptr[rb[b + 1]]
+        assert xv_ptr[b + 1] - xv_ptr[b] == nv[0], b
+        assert np.array_equal(got["xv_start"][xv_ptr[b]:xv_ptr[b + 1]], xs), b
+        assert np.array_equal(got["lidx"][k0:k1], li[k0:k1]), b
+        assert np.array_equal(got["xv_pad"][b * V:b * V + nv[0]], xs) and np.all(got["xv_pad"][b * V + nv[0]:(b + 1) * V] == -1), b
+    del got
+    A.close()
+
+    for plan in (s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE, s.SPMV_PLAN_BINNED, s.SPMV_PLAN_VECTOR, s.SPMV_PLAN_SCALAR,
+                 s.SPMV_PLAN_COLBLOCK):
+        print("  plan", s.PLAN_NAMES[plan], flush=True)
+        A = d.matrix(dict(plan=plan))
+        assert A.info.plan == plan
+        worst = assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what=s.PLAN_NAMES[plan])
+        print(f"    max |err| / sum|a x| = {worst:.3e}", flush=True)
+        A.close()

@@ -27,7 +27,7 @@ SEED_BASE = 260307169  # seed of config k (1-based) is SEED_BASE + k
 __all__ = [
     "CsrProblem", "SEED_BASE", "f32_to_bf16_bits", "bf16_bits_to_f32",
     "uniform_rows", "laplace2d", "stencil27", "powerlaw", "block_clustered",
-    "density_random", "from_row_lengths", "exact_integer", "tiny_adversarial",
+    "density_random", "clustered_arithmetic", "from_row_lengths", "exact_integer", "tiny_adversarial",
     "config", "CONFIG_NAMES", "to_coo", "to_csc", "to_ell",
 ]
 
@@ -271,6 +271,31 @@ def density_random(rows=1024, cols=2048, density=0.01, seed=SEED_BASE + 12, dtyp
     y0 = _uniform_pm1(rng, rows) if beta != 0.0 else None
     return _finish(f"density{density}_{rows}x{cols}", dtype, rows, cols, rowptr, colidx, vals, x, y0, alpha, beta,
                    {"density": density})
+
+
+def clustered_arithmetic(m=2 ** 23, runs=17, width=8, n=2 ** 22, seed=SEED_BASE + 31, alpha=1.0, beta=0.5) -> CsrProblem:
+    """A bf16 matrix of more than 2^30 stored entries at the default size (m * runs * width =
+    1 140 850 688), laid out in seconds and without large temporaries: run j of row r covers the
+    `width` columns from width * ((3 r + 24671 j) mod (n / width)) on (24671 is odd, so the runs
+    of a row are distinct while runs <= n / width <= 2^31 / width).  Values are a seeded N(0,1)
+    pattern of 1 000 003 numbers repeated over the entries: the period shares no factor with a
+    power of two, so an entry index that is off by 2^k meets a different value.  x, y0 ~ N(0,1)."""
+    rng = _rng(seed)
+    slots = n // width
+    assert slots >= runs and 3 * m + 24671 * runs < 2 ** 31 and m * runs * width < 2 ** 31
+    r = np.arange(m, dtype=np.int32).reshape(m, 1)
+    j = np.arange(runs, dtype=np.int32).reshape(1, runs)
+    starts = ((3 * r + 24671 * j) % np.int32(slots)) * np.int32(width)          # int32 [m, runs]
+    colidx = np.empty((m, runs, width), dtype=np.int32)
+    np.add(starts.reshape(m, runs, 1), np.arange(width, dtype=np.int32), out=colidx)
+    per_row = runs * width
+    rowptr = (np.arange(m + 1, dtype=np.int64) * per_row).astype(np.int32)
+    pattern = f32_to_bf16_bits(rng.standard_normal(1_000_003, dtype=np.float32))
+    vals = np.resize(pattern, m * per_row)
+    x = f32_to_bf16_bits(rng.standard_normal(n, dtype=np.float32))
+    y0 = rng.standard_normal(m, dtype=np.float32) if beta != 0.0 else None
+    return CsrProblem(f"clustered_arithmetic_{m}x{per_row}", "bf16", int(m), int(n), rowptr, colidx.reshape(-1), vals, x, y0,
+                      float(alpha), float(beta), {"runs": runs, "width": width})
 
 
 def from_row_lengths(lens, n, seed=1, dtype="f32", alpha=1.0, beta=0.0, sort_cols=True, allow_dup=False,
