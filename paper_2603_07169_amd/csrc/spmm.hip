@@ -42,6 +42,22 @@ __device__ __forceinline__ int quad_bcast(int v) {  // every lane gets the value
     return __builtin_amdgcn_update_dpp(0, v, S * 0x55, 0xF, 0xF, true);
 }
 
+// acc += (val of lane S of the quad) * b: the quad broadcast rides on the multiply-add itself.
+// All 64 lanes are active wherever this is used.
+template <int S>
+__device__ __forceinline__ void fma_quad(float& acc, float val, float b) {
+    if constexpr (S == 0)
+        asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[0,0,0,0] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(val), "v"(b));
+    else if constexpr (S == 1)
+        asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[1,1,1,1] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(val), "v"(b));
+    else if constexpr (S == 2)
+        asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[2,2,2,2] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(val), "v"(b));
+    else
+        asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(val), "v"(b));
+}
+
+// SINGLE: B has at most kSpmmNB rows, so one block holds all of it and cb0 is 0 throughout.
+template <bool SINGLE>
 __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
     constexpr int KT = kSpmmKT, NB = kSpmmNB, RPW = 16, WAVES = kSpmmWG / 64;
     constexpr int U = 8;  // entries per lane and chunk: a chunk covers 32 entries of a row
@@ -80,7 +96,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
         return row_lo + g * RPW;
     };
 
-    for (int cb0 = 0; cb0 < a.n; cb0 += NB) {
+    for (int cb0 = 0; cb0 < (SINGLE ? 1 : a.n); cb0 += NB) {
         const int nbk = a.n - cb0 < NB ? a.n - cb0 : NB;  // rows of B in this block
         if (cb0 > 0) __syncthreads();                     // the previous block is no longer read
         for (int idx = tid; idx < nbk * 4; idx += kSpmmWG) {
@@ -97,32 +113,52 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
         }
         __syncthreads();
 
-        // (first entry, length) of this lane's row in group gi; length 0 past the end
+        // (first entry, length) of this lane's row in group gi.  A lane past the last row takes the last
+        // row again (and stores nothing): two unconditional loads and no select, so nothing here
+        // tempts the compiler into a branch with a wait behind it.
         auto load_row = [&](int gi, int& rs, int& len) {
-            const int r = base_of(gi) + rsub;
-            const bool live = r < row_hi;
-            rs = a.rowptr[live ? r : 0];
-            const int re = a.rowptr[live ? r + 1 : 0];
-            len = live ? re - rs : 0;
+            int r = base_of(gi) + rsub;
+            r = r < row_hi ? r : row_hi - 1;
+            const int32_t* rp = a.rowptr + (r > 0 ? r : 0);
+            rs = rp[0];
+            len = rp[1] - rs;
         };
-        // entries c0 + q, c0 + q + 4, .. of the row: LDS offset of the B row (in floats) and value.
-        // The loads are unconditional (no branch, so all are in flight together); a lane past its
-        // row's end reads the last entry of the array and then points at the zero row.
-        auto load_chunk = [&](int rs, int len, int c0, int* col, float* val) {
+        // A chunk is entries c0 + q, c0 + q + 4, .. (U of them) of the lane's row.  issue() only
+        // requests them, so the loads stay in flight while something else is multiplied; a lane
+        // reads on past the end of its row (into the next rows) and finish() sorts that out.
+        // Where every lane's last read lies inside the arrays (all but the last rows of the matrix)
+        // the loads share one address and differ in their immediate offsets.
+        auto issue = [&](int rs, int c0, int (&col)[U], float (&val)[U]) {
+            const int kq = rs + c0 + q;
+            if (!__builtin_amdgcn_ballot_w64(kq + 4 * (U - 1) >= a.nnz)) {
+                const int32_t* cp = a.colidx + kq;
+                const float* vp = a.vals + kq;
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int t = c0 + q + 4 * u;
-                const unsigned k = t < len ? rs + t : a.nnz - 1;  // unsigned: base + 32-bit offset addressing
-                col[u] = a.colidx[k];
-                val[u] = a.vals[k];
+                for (int u = 0; u < U; ++u) {
+                    col[u] = cp[4 * u];
+                    val[u] = vp[4 * u];
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int k = kq + 4 * u < a.nnz ? kq + 4 * u : a.nnz - 1;
+                    col[u] = a.colidx[k];
+                    val[u] = a.vals[k];
+                }
             }
+        };
+        // Column -> byte offset of the B row in the LDS block.  Entries past the row's end, or with a
+        // column outside this block, point at the zero row; the former also get the value 0 (they
+        // belong to another row, whose value need not be finite).
+        auto finish = [&](int len, int c0, int (&col)[U], float (&val)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int t = c0 + q + 4 * u;
-                const int c = col[u] - cb0;
-                const bool ok = t < len && static_cast<unsigned>(c) < static_cast<unsigned>(nbk);
-                col[u] = (ok ? c : NB) * (KT * 4);  // byte offset of the B row in the LDS block
-                val[u] = ok ? val[u] : 0.f;
+                const bool live = c0 + q + 4 * u < len;
+                unsigned c = static_cast<unsigned>(col[u] - (SINGLE ? 0 : cb0));  // a column before the block wraps to a huge number
+                c = c < static_cast<unsigned>(NB) ? c : static_cast<unsigned>(NB);
+                c = live ? c : static_cast<unsigned>(NB);
+                col[u] = static_cast<int>(c * (KT * 4));
+                val[u] = live ? val[u] : 0.f;
             }
         };
 
@@ -132,32 +168,45 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
         load_row(gi + WAVES, rs_n, len_n);
         int col[U], coln[U];
         float val[U], valn[U];
-        load_chunk(rs, len, 0, col, val);
+        issue(rs, 0, col, val);
+        finish(len, 0, col, val);
         while (gi < n_groups) {
             // the next group's first chunk and the rows of the group after it: in flight during the multiply
-            load_chunk(rs_n, len_n, 0, coln, valn);
+            issue(rs_n, 0, coln, valn);
             int rs_nn, len_nn;
             load_row(gi + 2 * WAVES, rs_nn, len_nn);
 
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+            float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
             for (int c0 = 0;; c0 += 4 * U) {
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
+                for (int u = 0; u < U; u += 2) {
                     if (!__builtin_amdgcn_ballot_w64(c0 + 4 * u < len)) break;  // no row of the wavefront reaches this far
-                    const int cc[4] = {quad_bcast<0>(col[u]), quad_bcast<1>(col[u]), quad_bcast<2>(col[u]),
-                                       quad_bcast<3>(col[u])};
-                    const int vbits = __float_as_int(val[u]);
-                    const float vv[4] = {__int_as_float(quad_bcast<0>(vbits)), __int_as_float(quad_bcast<1>(vbits)),
-                                         __int_as_float(quad_bcast<2>(vbits)), __int_as_float(quad_bcast<3>(vbits))};
-                    f32x4 b[4];
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) b[s] = *reinterpret_cast<const f32x4*>(Bq + cc[s]);
-#pragma unroll
-                    for (int s = 0; s < 4; ++s) acc += vv[s] * b[s];
+                    // eight entries of the row: two from each lane of the quad
+                    f32x4 b[8];
+                    b[0] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<0>(col[u]));
+                    b[1] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<1>(col[u]));
+                    b[2] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<2>(col[u]));
+                    b[3] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<3>(col[u]));
+                    b[4] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<0>(col[u + 1]));
+                    b[5] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<1>(col[u + 1]));
+                    b[6] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<2>(col[u + 1]));
+                    b[7] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<3>(col[u + 1]));
+#define SPMM_FMA4(S, V, BV) \
+    fma_quad<S>(acc0, V, BV[0]); fma_quad<S>(acc1, V, BV[1]); fma_quad<S>(acc2, V, BV[2]); fma_quad<S>(acc3, V, BV[3]);
+                    SPMM_FMA4(0, val[u], b[0]) SPMM_FMA4(1, val[u], b[1]) SPMM_FMA4(2, val[u], b[2]) SPMM_FMA4(3, val[u], b[3])
+                    SPMM_FMA4(0, val[u + 1], b[4]) SPMM_FMA4(1, val[u + 1], b[5]) SPMM_FMA4(2, val[u + 1], b[6])
+                    SPMM_FMA4(3, val[u + 1], b[7])
+#undef SPMM_FMA4
                 }
                 if (!__builtin_amdgcn_ballot_w64(c0 + 4 * U < len)) break;
-                load_chunk(rs, len, c0 + 4 * U, col, val);  // rows longer than a chunk: fetched on demand
+                issue(rs, c0 + 4 * U, col, val);  // rows longer than a chunk: fetched on demand
+                finish(len, c0 + 4 * U, col, val);
             }
+
+            // What the next round needs is settled before C is touched: nothing that is loaded is
+            // then still awaited when the loop comes round, and the store below stays in flight.
+            finish(len_n, 0, coln, valn);
+            asm volatile("" : "+v"(rs_nn), "+v"(len_nn));
 
             const int r = base_of(gi) + rsub;
             if (r < row_hi && 4 * q < kw) {
@@ -165,6 +214,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                 const bool first = cb0 == 0;
                 const bool reads_c = !first || a.beta != 0.f;
                 const float scale_c = first ? a.beta : 1.f;
+                const f32x4 acc = {acc0, acc1, acc2, acc3};
                 if (full4) {
                     f32x4 out = a.alpha * acc;
                     if (reads_c) out += scale_c * *reinterpret_cast<const f32x4*>(dst);
@@ -221,12 +271,17 @@ hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* 
     const size_t lds = sizeof(float) * (kSpmmNB + 1) * kSpmmKT;  // the B block and one zero row
     static thread_local bool allowed = false;
     if (!allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(spmm_csr_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-        if (e != hipSuccess) return e;
+        for (const void* k : {reinterpret_cast<const void*>(spmm_csr_kernel<true>),
+                              reinterpret_cast<const void*>(spmm_csr_kernel<false>)}) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return e;
+        }
         allowed = true;
     }
-    hipLaunchKernelGGL(spmm_csr_kernel, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
+    if (A.n <= kSpmmNB)
+        hipLaunchKernelGGL(spmm_csr_kernel<true>, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
+    else
+        hipLaunchKernelGGL(spmm_csr_kernel<false>, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
     return hipGetLastError();
 }
 
