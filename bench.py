@@ -236,7 +236,7 @@ def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
     for e in rows_log2:
         p = w.density_random(1 << e, 2048, 0.01)
         rowptr, colidx, vals = dev(p.rowptr), dev(p.colidx), dev(p.vals)
-        A = s.CsrMatrix(p.m, p.n, rowptr, colidx, vals, s.SPMV_F32)
+        A = s.CsrMatrix(p.m, p.n, rowptr, colidx, vals, s.SPMV_F32, dict(prepare_spmm=1))
         B = torch.rand(p.n, K, dtype=torch.float32, device="cuda")
         C = torch.empty(p.m, K, dtype=torch.float32, device="cuda")
         steps = max(5, min(args.steps, int(2e9 // (p.m * K * 4)) or 5))

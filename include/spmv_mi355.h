@@ -71,6 +71,8 @@ typedef enum {
 
 #define SPMV_NUM_BINS 33
 
+#define SPMV_SPMM_WINDOW 4096 /* rows per window of the spmm_rows order */
+
 /* Analysis parameters.  Zero in any field selects that field's default. */
 typedef struct {
     int32_t plan;             /* spmv_plan_t; default AUTO */
@@ -79,7 +81,9 @@ typedef struct {
     int32_t items_per_chunk;  /* merge path: steps (row ends + entries) per chunk; default 2048, 1..8192 */
     int32_t vector_lanes;     /* VECTOR plan: lanes per row, power of two 2..64; default: chosen from nnz/m */
     int32_t skip_validation;  /* nonzero: do not scan colidx for out-of-range columns in analyze */
-    int32_t reserved[2];      /* must be zero */
+    int32_t prepare_spmm;     /* 1: also build spmm_rows, the row order spmm_csr_run() then works in
+                                 (SPMV_F32 handles only); 0: spmm_csr_run() takes the rows as they come */
+    int32_t reserved;         /* must be zero */
 } spmv_analyze_params_t;
 
 typedef struct {
@@ -94,6 +98,8 @@ typedef struct {
     int32_t max_x_vectors;             /* most x vectors of any row block (0 when the windows were not counted) */
     int32_t num_col_blocks;            /* COLBLOCK plan: C, the number of column blocks; 0 otherwise */
     int32_t col_block_width;           /* COLBLOCK plan: columns per block (a power of two); 0 otherwise */
+    int32_t spmm_prepared;             /* 1 when spmm_rows was built (prepare_spmm), else 0 */
+    int32_t reserved;                  /* 0 */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -116,6 +122,9 @@ typedef struct {
     int32_t* cb_row;     /* [nnz]  row of every regrouped entry                      */
     int32_t* cb_col;     /* [nnz]  its column minus the block's first column         */
     int32_t* cb_src;     /* [nnz]  its position in the caller's colidx / vals        */
+    /* With prepare_spmm only (skipped otherwise): */
+    int32_t* spmm_rows;  /* [m]    inside each window of SPMV_SPMM_WINDOW consecutive rows:
+                            row ids by decreasing min(ceil(len / 4), 64), ties ascending */
 } spmv_analysis_host_t;
 
 /* Records the matrix (paper App. C task 12: values / col_indices / row_offsets).
@@ -163,6 +172,12 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     float atomics into y: results are reproducible to rounding, not bit for bit.  The copy is
  *     taken at analyze time: changing vals afterwards needs a new analyze.  A forced COLBLOCK
  *     plan fails with UNSUPPORTED when there would be more than 16 blocks.
+ *   - with prepare_spmm = 1 (SPMV_F32 handles; UNSUPPORTED on bf16 ones): spmm_rows.  The rows
+ *     are cut into windows of SPMV_SPMM_WINDOW consecutive rows; inside a window the row ids are
+ *     sorted by decreasing key(len) = min(ceil(len / 4), 64), rows of equal key in ascending
+ *     order.  spmm_csr_run() advances through a row four entries at a time, so rows of equal
+ *     key keep a wavefront busy for the same number of steps; the windows keep the rows of C
+ *     that are written at about the same time close together.
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
  * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */
 spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params);
@@ -178,7 +193,10 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
 /* Sparse times dense (paper App. C task 13: C = A B, A in CSR, B of shape cols x K), in the BLAS
  * form  C <- alpha * A * B + beta * C,  enqueued on `stream`.
  *   h    a handle created with SPMV_F32 and analyzed (the analysis validates the structure; the
- *        product itself uses rowptr / colidx / vals as they are).
+ *        product itself uses rowptr / colidx / vals as they are).  A wavefront works on 16 rows
+ *        at a time, for as long as the longest of them lasts: analysed with prepare_spmm = 1
+ *        it takes them from spmm_rows, where rows of like length are neighbours; otherwise in
+ *        their natural order.  The result is the same either way.
  *   B    device float, n rows of K used columns, row-major, leading dimension ldb >= K.
  *   C    device float, m rows of K used columns, row-major, leading dimension ldc >= K; read only
  *        if beta != 0 (or when n exceeds 2048, where B is taken in several passes that accumulate

@@ -48,6 +48,8 @@ def _load():
         _lib.oracle_spmv_csr_bf16.restype = C.c_int
         _lib.oracle_spmm_csr_f32.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, f32, f32, vp, vp]
         _lib.oracle_spmm_csr_f32.restype = C.c_int
+        _lib.oracle_spmm_row_order.argtypes = [i64, vp, i64, vp]
+        _lib.oracle_spmm_row_order.restype = None
         _lib.oracle_spmv_coo.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
         _lib.oracle_spmv_csc.argtypes = [i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
         _lib.oracle_spmv_ell.argtypes = [i64, i64, i64, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
@@ -275,6 +277,17 @@ def column_blocks(m, n, rowptr, colidx, width):
 
 def column_block_width(dtype):
     return int(_load().oracle_column_block_width(4 if dtype == "f32" else 2))
+
+
+def spmm_row_order(rowptr, window=4096):
+    """Inside every window of `window` consecutive rows: row ids by decreasing
+    min(ceil(len / 4), 64), rows of equal key ascending (int32[m])."""
+    m = rowptr.size - 1
+    _chk(rowptr, np.int32, m + 1)
+    assert window >= 1
+    rows = np.empty(m, dtype=np.int32)
+    _load().oracle_spmm_row_order(m, _p(rowptr), window, _p(rows))
+    return rows
 
 
 def column_block_choice(n, nnz, dtype, plan):

@@ -9,9 +9,15 @@
 //
 // Pins (tests/test_oracle_spmm.py): a dense matrix product on small matrices (numpy), K = 1
 // against the pinned SpMV oracle, identity A (C = B), a hand-worked fixture, linearity in B.
+//
+// Also the order in which the GPU kernel is handed the rows (its own scheduling aid, not part of
+// the paper's task): the definition written out as a stable sort.  Pins: a hand-worked fixture,
+// and the defining properties checked with numpy on random lengths.
 
+#include <algorithm>
 #include <cmath>
 #include <cstdint>
+#include <numeric>
 
 extern "C" {
 
@@ -39,6 +45,20 @@ int oracle_spmm_csr_f32(int64_t m, int64_t n, int64_t K, const int32_t* rowptr, 
         }
     }
     return 0;
+}
+
+// The rows are cut into windows of `window` consecutive rows (the last one may be shorter).
+// rows[0..m) lists, window after window, the window's row ids sorted by decreasing
+// key(i) = min(ceil(len_i / 4), 64), len_i = rowptr[i+1] - rowptr[i]; rows of equal key keep
+// their ascending order.
+void oracle_spmm_row_order(int64_t m, const int32_t* rowptr, int64_t window, int32_t* rows) {
+    auto key = [&](int32_t i) {
+        const int64_t len = static_cast<int64_t>(rowptr[i + 1]) - rowptr[i];
+        return std::min<int64_t>((len + 3) / 4, 64);
+    };
+    std::iota(rows, rows + m, 0);
+    for (int64_t w0 = 0; w0 < m; w0 += window)
+        std::stable_sort(rows + w0, rows + std::min(w0 + window, m), [&](int32_t a, int32_t b) { return key(a) > key(b); });
 }
 
 }  // extern "C"

@@ -37,7 +37,7 @@ inline int64_t split_rows_on_diagonal(int64_t d, int64_t m, int64_t nnz, const i
 spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_params_t* out) {
     spmv_analyze_params_t p{};
     if (in) p = *in;
-    if (p.reserved[0] != 0 || p.reserved[1] != 0) return SPMV_ERR_INVALID_ARG;
+    if (p.reserved != 0 || (p.prepare_spmm != 0 && p.prepare_spmm != 1)) return SPMV_ERR_INVALID_ARG;
     if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_COLBLOCK) return SPMV_ERR_INVALID_ARG;
     if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
     if (p.block_nnz < 0 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
@@ -195,6 +195,28 @@ bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, i
     *total = sum;
     *largest = mx;
     return nnz > 0 && mx <= SPMV_MAX_X_VECTORS && 4 * nb * static_cast<int64_t>(mx) <= nnz;
+}
+
+void spmm_row_order(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows) {
+    // window after window, a counting sort: one pass to size the classes, one to place the rows
+    // (ascending inside a class)
+    auto key_of = [&](int64_t i) {
+        const int64_t steps = (static_cast<int64_t>(rowptr[i + 1]) - rowptr[i] + 3) / 4;
+        return static_cast<int>(steps < kSpmmMaxKey ? steps : kSpmmMaxKey);
+    };
+    rows->resize(static_cast<size_t>(m));
+    for (int64_t w0 = 0; w0 < m; w0 += SPMV_SPMM_WINDOW) {
+        const int64_t w1 = w0 + SPMV_SPMM_WINDOW < m ? w0 + SPMV_SPMM_WINDOW : m;
+        int64_t count[kSpmmMaxKey + 1] = {};
+        for (int64_t i = w0; i < w1; ++i) count[key_of(i)] += 1;
+        int64_t cursor[kSpmmMaxKey + 1];
+        int64_t run = w0;
+        for (int k = kSpmmMaxKey; k >= 0; --k) {  // the largest key comes first
+            cursor[k] = run;
+            run += count[k];
+        }
+        for (int64_t i = w0; i < w1; ++i) (*rows)[static_cast<size_t>(cursor[key_of(i)]++)] = static_cast<int32_t>(i);
+    }
 }
 
 }  // namespace spmv

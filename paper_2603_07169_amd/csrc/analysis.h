@@ -46,4 +46,10 @@ bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t pla
 // (one slot per block and possible vector) no longer than a quarter of the entries.
 bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest);
 
+// Row order of the sparse-times-dense kernel: inside every window of SPMV_SPMM_WINDOW consecutive
+// rows, the row ids by decreasing min(ceil(len / 4), 64), rows of equal key ascending.  rowptr is
+// a HOST array of m+1 checked entries.  May throw std::bad_alloc.
+constexpr int kSpmmMaxKey = 64;
+void spmm_row_order(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows);
+
 }  // namespace spmv

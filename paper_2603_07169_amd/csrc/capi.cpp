@@ -57,6 +57,7 @@ struct spmv_csr_s {
     int32_t* d_xv_start = nullptr;
     int32_t* d_xv_pad = nullptr;
     uint16_t* d_lidx = nullptr;
+    int32_t* d_spmm_rows = nullptr;  // row order of spmm_csr_run (prepare_spmm)
 };
 
 namespace {
@@ -65,7 +66,7 @@ void free_metadata(spmv_csr_s* h) {
     void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
                     h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
                     h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc, h->d_cb_row, h->d_cb_col,
-                    h->d_cb_src,    h->d_cb_vals};
+                    h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
@@ -75,6 +76,7 @@ void free_metadata(spmv_csr_s* h) {
     h->d_cb_vals = nullptr;
     h->cb_ptr.clear();
     h->d_lidx = nullptr;
+    h->d_spmm_rows = nullptr;
     h->analyzed = false;
 }
 
@@ -248,6 +250,7 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     spmv_analyze_params_t p{};
     spmv_status_t st = spmv::resolve_params(params, &p);
     if (st != SPMV_OK) return st;
+    if (p.prepare_spmm && h->dtype != SPMV_F32) return SPMV_ERR_UNSUPPORTED;
     free_metadata(h);
 
     std::vector<int32_t> rowptr_host;
@@ -313,6 +316,16 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     }
     if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
     if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
+    if (st == SPMV_OK && p.prepare_spmm) {
+        try {
+            std::vector<int32_t> order;
+            spmv::spmm_row_order(h->m, rowptr_host.data(), &order);
+            st = upload(order, &h->d_spmm_rows);
+            a.info.spmm_prepared = 1;
+        } catch (const std::bad_alloc&) {
+            st = SPMV_ERR_ALLOC;
+        }
+    }
     if (st == SPMV_OK) {
         const size_t P = static_cast<size_t>(a.info.num_chunks > 0 ? a.info.num_chunks : 1);
         if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_carry_row), sizeof(int32_t) * P)) ||
@@ -411,7 +424,7 @@ spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* 
     if (!C || ldc < K) return SPMV_ERR_INVALID_ARG;
     if (h->n > 0 && (!B || ldb < K)) return SPMV_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(B) % 4 || reinterpret_cast<uintptr_t>(C) % 4) return SPMV_ERR_UNSUPPORTED;
-    const hipError_t e = spmv::launch_spmm(view_of(h), B, ldb, C, ldc, static_cast<int32_t>(K), spmv::Scalars{alpha, beta},
+    const hipError_t e = spmv::launch_spmm(view_of(h), h->d_spmm_rows, B, ldb, C, ldc, static_cast<int32_t>(K), spmv::Scalars{alpha, beta},
                                            static_cast<hipStream_t>(stream));
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
@@ -505,6 +518,9 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
         if (c.dst && c.count > 0 &&
             hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
             return SPMV_ERR_HIP;
+    if (h->info.spmm_prepared && out->spmm_rows && h->info.m > 0 &&
+        hip_failed(hipMemcpy(out->spmm_rows, h->d_spmm_rows, sizeof(int32_t) * static_cast<size_t>(h->info.m), hipMemcpyDeviceToHost)))
+        return SPMV_ERR_HIP;
     if (h->info.plan == SPMV_PLAN_COLBLOCK) {
         if (out->cb_ptr) std::memcpy(out->cb_ptr, h->cb_ptr.data(), sizeof(int32_t) * h->cb_ptr.size());
         const Copy ccopies[] = {{out->cb_row, h->d_cb_row, h->info.nnz}, {out->cb_col, h->d_cb_col, h->info.nnz},
@@ -542,8 +558,18 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     spmv::Analysis a;
     st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
     if (st != SPMV_OK) return st;
+    std::vector<int32_t> order;
+    if (p.prepare_spmm) {
+        try {
+            spmv::spmm_row_order(m, rowptr_host, &order);
+        } catch (const std::bad_alloc&) {
+            return SPMV_ERR_ALLOC;
+        }
+        a.info.spmm_prepared = 1;
+    }
     *info = a.info;
     if (out) {
+        if (out->spmm_rows && !order.empty()) std::memcpy(out->spmm_rows, order.data(), sizeof(int32_t) * order.size());
         if (out->bin_count) std::memcpy(out->bin_count, a.bin_count, sizeof a.bin_count);
         if (out->bin_offset) std::memcpy(out->bin_offset, a.bin_offset, sizeof a.bin_offset);
         if (out->bin_rows && !a.bin_rows.empty())

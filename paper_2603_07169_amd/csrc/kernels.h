@@ -59,8 +59,10 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t 
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
                         Scalars s, hipStream_t st);
 // C <- alpha*A*B + beta*C; A FP32 CSR, B device float[n x ldb], C device float[m x ldc], row-major, K columns used.
-hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* C, int64_t ldc, int32_t K, Scalars s,
-                       hipStream_t st);
+// rows: device int32[m], the order in which the rows are handed to the wavefronts (a permutation
+// of 0..m-1), or NULL for the natural order.
+hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B, int64_t ldb, float* C, int64_t ldc,
+                       int32_t K, Scalars s, hipStream_t st);
 // flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st);
 

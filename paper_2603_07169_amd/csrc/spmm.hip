@@ -18,21 +18,23 @@ constexpr int kSpmmNB = 2048;  // rows of B held in LDS at a time (2048 x 16 flo
 // or than C.  Those reads are kept on chip: a workgroup owns kSpmmKT = 16 columns of B and C,
 // copies that slice of B (up to kSpmmNB = 2048 rows: 128 KB) into LDS once and then walks over
 // all its rows of A.  Four lanes (a DPP quad) serve a row, one float4 of the slice each; a
-// wavefront serves 16 rows at a time.  The quad reads its row's entries straight from memory,
-// lane q taking entries q, q+4, ..: neighbouring quads hold neighbouring rows, so a load
-// instruction of the wavefront covers one contiguous stretch of colidx / vals.  An entry is then
-// handed to the other three lanes with a quad broadcast, and each lane adds value * B-row piece
-// out of LDS.  Rows and entries of the next group are fetched while the current one is multiplied.
+// wavefront serves 16 rows at a time, for as long as the longest of them lasts: the rows can be
+// handed out in an order that puts rows of like length side by side (built at analysis time on
+// request).  The quad reads its row's entries straight from memory, 16 bytes per lane and load;
+// an entry is then handed to the other three lanes with a quad broadcast that rides on the
+// multiply-add, and each lane adds value * B-row piece out of LDS.  Row ids, row bounds and
+// entries of the coming groups are fetched while the current one is multiplied.
 // B wider than the LDS block is taken in several passes over A, accumulating into C.
 struct SpmmArgs {
     const int32_t* rowptr;
     const int32_t* colidx;
     const float* vals;
+    const int32_t* rows;  // row order (SORTED kernels), else unused
     const float* B;
     float* C;
     int64_t ldb, ldc;
     int32_t m, n, K, nnz;
-    int32_t row_splits;  // gridDim.y: each takes an equal share of the rows
+    int32_t row_splits;  // split y takes every row_splits-th group of 16 rows, from group y on
     int32_t vec_ok;      // B and C 16-byte aligned, ldb and ldc multiples of 4
     float alpha, beta;
 };
@@ -56,8 +58,14 @@ __device__ __forceinline__ void fma_quad(float& acc, float val, float b) {
         asm("v_fmac_f32_dpp %0, %1, %2 quad_perm:[3,3,3,3] row_mask:0xf bank_mask:0xf bound_ctrl:1" : "+v"(acc) : "v"(val), "v"(b));
 }
 
+// 4-byte aligned vectors of four: a row's entries start anywhere in colidx / vals.
+typedef int32_t i32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+
 // SINGLE: B has at most kSpmmNB rows, so one block holds all of it and cb0 is 0 throughout.
-template <bool SINGLE>
+// SORTED: the wavefronts take their rows from a.rows (rows of like length side by side) instead
+// of in natural order.
+template <bool SINGLE, bool SORTED>
 __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
     constexpr int KT = kSpmmKT, NB = kSpmmNB, RPW = 16, WAVES = kSpmmWG / 64;
     constexpr int U = 8;  // entries per lane and chunk: a chunk covers 32 entries of a row
@@ -66,16 +74,27 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
     float* Bs = reinterpret_cast<float*>(smem_raw);  // [NB + 1][KT]; row NB stays zero
     const unsigned char* const Bq = smem_raw + 16 * (threadIdx.x & 3);  // this lane's float4 of row 0
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int q = lane & 3;      // which float4 of the slice, and which entries of the row (q, q+4, ..)
+    const int q = lane & 3;      // which float4 of the slice, and which entries of the row (4q .. 4q+3, 16+4q .. 16+4q+3)
     const int rsub = lane >> 2;  // which of the wavefront's 16 rows
 
-    const int k0 = blockIdx.x * KT;
+    // Workgroup ids are handed to the 8 dies round-robin.  Die j takes a contiguous run of
+    // (slice, split) pairs, so that the slices whose pieces of a row of C lie side by side are
+    // written through the same L2.
+    const int n_slices = (a.K + KT - 1) / KT;
+    int pair;
+    {
+        const int nb = gridDim.x, per = nb / kXcds, rem = nb % kXcds;
+        const int die = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+        pair = die * per + (die < rem ? die : rem) + slot;
+    }
+    const int slice = pair % n_slices, split = pair / n_slices;
+    const int k0 = slice * KT;
     const int kw = a.K - k0 < KT ? a.K - k0 : KT;  // live columns of this slice
-    const int row_lo = static_cast<int>(static_cast<int64_t>(a.m) * blockIdx.y / a.row_splits);
-    const int row_hi = static_cast<int>(static_cast<int64_t>(a.m) * (blockIdx.y + 1) / a.row_splits);
     const bool full4 = a.vec_ok && 4 * q + 4 <= kw;  // this lane's float4 lies wholly inside the slice
 
     if (a.nnz == 0) {  // C <- beta*C; the main path below may then assume that A has entries
+        const int row_lo = static_cast<int>(static_cast<int64_t>(a.m) * split / a.row_splits);
+        const int row_hi = static_cast<int>(static_cast<int64_t>(a.m) * (split + 1) / a.row_splits);
         for (int r = row_lo + tid / 4; r < row_hi; r += kSpmmWG / 4) {
             float* dst = a.C + static_cast<size_t>(r) * a.ldc + k0 + 4 * q;
             for (int t = 0; t < 4; ++t)
@@ -85,15 +104,28 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
     }
     if (tid < KT) Bs[NB * KT + tid] = 0.f;  // the row that entries without a partner in this block point to
 
-    // Group number gi of a wavefront -> first row.  Every workgroup walks over all rows of A;
-    // starting each at a different place keeps them from asking for the same lines together.
-    const int n_groups = (row_hi - row_lo + RPW - 1) / RPW;
-    const int rot = static_cast<int>((static_cast<int64_t>(blockIdx.x) * n_groups) / gridDim.x);
-    auto base_of = [&](int gi) {
-        if (gi >= n_groups) return row_hi;
-        int g = gi + rot;
-        if (g >= n_groups) g -= n_groups;
-        return row_lo + g * RPW;
+    // Rows are dealt out in groups of 16 positions of the row order.  Workgroup (slice, split y of S)
+    // takes the groups y, y + S, y + 2S, ..: with the rows sorted by length every split gets its
+    // share of the long ones.  Its wavefronts take those in turn.  All slices walk through the
+    // rows in the same order, so a row of C is written, piece by piece, within a short time.
+    const int S = a.row_splits, y = split;
+    const int total_groups = (a.m + RPW - 1) / RPW;
+    const int n_groups = total_groups > y ? (total_groups - y + S - 1) / S : 0;
+    auto pos_of = [&](int j) {  // position of this lane's row in the wavefront's j-th group; m or more: none
+        if (j >= n_groups) return a.m;
+        return (y + S * j) * RPW + rsub;
+    };
+    // A lane without a row takes the last row again (and stores nothing): no select on loaded
+    // values anywhere, so nothing tempts the compiler into a branch with a wait behind it.
+    auto load_id = [&](int j) {
+        int p = pos_of(j);
+        p = p < a.m ? p : a.m - 1;
+        return SORTED ? a.rows[p] : p;
+    };
+    auto load_row = [&](int r, int& rs, int& len) {  // first entry and length of row r
+        const int32_t* rp = a.rowptr + r;
+        rs = rp[0];
+        len = rp[1] - rs;
     };
 
     for (int cb0 = 0; cb0 < (SINGLE ? 1 : a.n); cb0 += NB) {
@@ -113,35 +145,31 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
         }
         __syncthreads();
 
-        // (first entry, length) of this lane's row in group gi.  A lane past the last row takes the last
-        // row again (and stores nothing): two unconditional loads and no select, so nothing here
-        // tempts the compiler into a branch with a wait behind it.
-        auto load_row = [&](int gi, int& rs, int& len) {
-            int r = base_of(gi) + rsub;
-            r = r < row_hi ? r : row_hi - 1;
-            const int32_t* rp = a.rowptr + (r > 0 ? r : 0);
-            rs = rp[0];
-            len = rp[1] - rs;
-        };
-        // A chunk is entries c0 + q, c0 + q + 4, .. (U of them) of the lane's row.  issue() only
-        // requests them, so the loads stay in flight while something else is multiplied; a lane
-        // reads on past the end of its row (into the next rows) and finish() sorts that out.
-        // Where every lane's last read lies inside the arrays (all but the last rows of the matrix)
-        // the loads share one address and differ in their immediate offsets.
+        // A chunk is 32 consecutive entries of the lane's row from entry c0 on; lane q of the quad
+        // holds entries 4q .. 4q+3 (slots 0..3) and 16+4q .. 16+4q+3 (slots 4..7) of it, two 16-byte
+        // loads per array.  issue() only requests them, so the loads stay in flight while something
+        // else is multiplied; a lane reads on past the end of its row (into the next rows) and
+        // finish() sorts that out.  Only near the end of the arrays (the last rows of the matrix)
+        // are the reads clamped one by one.
         auto issue = [&](int rs, int c0, int (&col)[U], float (&val)[U]) {
-            const int kq = rs + c0 + q;
-            if (!__builtin_amdgcn_ballot_w64(kq + 4 * (U - 1) >= a.nnz)) {
-                const int32_t* cp = a.colidx + kq;
-                const float* vp = a.vals + kq;
+            const int kq = rs + c0 + 4 * q;
+            if (!__builtin_amdgcn_ballot_w64(kq + 20 > a.nnz)) {
+                const i32x4_a4 ca = *reinterpret_cast<const i32x4_a4*>(a.colidx + kq);
+                const i32x4_a4 cb = *reinterpret_cast<const i32x4_a4*>(a.colidx + kq + 16);
+                const f32x4_a4 va = *reinterpret_cast<const f32x4_a4*>(a.vals + kq);
+                const f32x4_a4 vb = *reinterpret_cast<const f32x4_a4*>(a.vals + kq + 16);
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    col[u] = cp[4 * u];
-                    val[u] = vp[4 * u];
+                for (int e = 0; e < 4; ++e) {
+                    col[e] = ca[e];
+                    col[4 + e] = cb[e];
+                    val[e] = va[e];
+                    val[4 + e] = vb[e];
                 }
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    const int k = kq + 4 * u < a.nnz ? kq + 4 * u : a.nnz - 1;
+                    const int t = kq + 16 * (u >> 2) + (u & 3);
+                    const int k = t < a.nnz ? t : a.nnz - 1;
                     col[u] = a.colidx[k];
                     val[u] = a.vals[k];
                 }
@@ -153,7 +181,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
         auto finish = [&](int len, int c0, int (&col)[U], float (&val)[U]) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const bool live = c0 + q + 4 * u < len;
+                const bool live = c0 + 16 * (u >> 2) + 4 * q + (u & 3) < len;
                 unsigned c = static_cast<unsigned>(col[u] - (SINGLE ? 0 : cb0));  // a column before the block wraps to a huge number
                 c = c < static_cast<unsigned>(NB) ? c : static_cast<unsigned>(NB);
                 c = live ? c : static_cast<unsigned>(NB);
@@ -162,42 +190,52 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
             }
         };
 
+        // Three stages in flight: row ids three groups ahead, row bounds two ahead, entries one ahead.
         int gi = wave;
+        int r = load_id(gi), r_n = load_id(gi + WAVES), r_nn = load_id(gi + 2 * WAVES);
         int rs, len, rs_n, len_n;
-        load_row(gi, rs, len);
-        load_row(gi + WAVES, rs_n, len_n);
+        load_row(r, rs, len);
+        load_row(r_n, rs_n, len_n);
         int col[U], coln[U];
         float val[U], valn[U];
         issue(rs, 0, col, val);
         finish(len, 0, col, val);
         while (gi < n_groups) {
-            // the next group's first chunk and the rows of the group after it: in flight during the multiply
             issue(rs_n, 0, coln, valn);
             int rs_nn, len_nn;
-            load_row(gi + 2 * WAVES, rs_nn, len_nn);
+            load_row(r_nn, rs_nn, len_nn);
+            int r_nnn = load_id(gi + 3 * WAVES);
 
             float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
             for (int c0 = 0;; c0 += 4 * U) {
-#pragma unroll
-                for (int u = 0; u < U; u += 2) {
-                    if (!__builtin_amdgcn_ballot_w64(c0 + 4 * u < len)) break;  // no row of the wavefront reaches this far
-                    // eight entries of the row: two from each lane of the quad
-                    f32x4 b[8];
-                    b[0] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<0>(col[u]));
-                    b[1] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<1>(col[u]));
-                    b[2] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<2>(col[u]));
-                    b[3] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<3>(col[u]));
-                    b[4] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<0>(col[u + 1]));
-                    b[5] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<1>(col[u + 1]));
-                    b[6] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<2>(col[u + 1]));
-                    b[7] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<3>(col[u + 1]));
-#define SPMM_FMA4(S, V, BV) \
-    fma_quad<S>(acc0, V, BV[0]); fma_quad<S>(acc1, V, BV[1]); fma_quad<S>(acc2, V, BV[2]); fma_quad<S>(acc3, V, BV[3]);
-                    SPMM_FMA4(0, val[u], b[0]) SPMM_FMA4(1, val[u], b[1]) SPMM_FMA4(2, val[u], b[2]) SPMM_FMA4(3, val[u], b[3])
-                    SPMM_FMA4(0, val[u + 1], b[4]) SPMM_FMA4(1, val[u + 1], b[5]) SPMM_FMA4(2, val[u + 1], b[6])
-                    SPMM_FMA4(3, val[u + 1], b[7])
-#undef SPMM_FMA4
-                }
+                // Step st takes entries c0 + 4 st .. c0 + 4 st + 3 of every row: slots 4 (st / 4) .. + 3
+                // of lane st % 4 of the quad.  Two steps per trip.
+#define SPMM_STEP_LOADS(B0, ST)                                                                                  \
+    B0[0] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<(ST) % 4>(col[4 * ((ST) / 4) + 0]));                \
+    B0[1] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<(ST) % 4>(col[4 * ((ST) / 4) + 1]));                \
+    B0[2] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<(ST) % 4>(col[4 * ((ST) / 4) + 2]));                \
+    B0[3] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<(ST) % 4>(col[4 * ((ST) / 4) + 3]));
+#define SPMM_STEP_FMAS(B0, ST)                                                 \
+    _Pragma("unroll") for (int e = 0; e < 4; ++e) {                            \
+        fma_quad<(ST) % 4>(acc0, val[4 * ((ST) / 4) + e], B0[e][0]);           \
+        fma_quad<(ST) % 4>(acc1, val[4 * ((ST) / 4) + e], B0[e][1]);           \
+        fma_quad<(ST) % 4>(acc2, val[4 * ((ST) / 4) + e], B0[e][2]);           \
+        fma_quad<(ST) % 4>(acc3, val[4 * ((ST) / 4) + e], B0[e][3]);           \
+    }
+#define SPMM_TWO_STEPS(ST)                                                                     \
+    if (__builtin_amdgcn_ballot_w64(c0 + 4 * (ST) < len)) {                                    \
+        f32x4 b0[4], b1[4];                                                                    \
+        SPMM_STEP_LOADS(b0, ST) SPMM_STEP_LOADS(b1, (ST) + 1)                                  \
+        SPMM_STEP_FMAS(b0, ST) SPMM_STEP_FMAS(b1, (ST) + 1)                                    \
+    } else {                                                                                   \
+        break;                                                                                 \
+    }
+                do {  // left by the first pair of steps that no row of the wavefront reaches
+                    SPMM_TWO_STEPS(0) SPMM_TWO_STEPS(2) SPMM_TWO_STEPS(4) SPMM_TWO_STEPS(6)
+                } while (false);
+#undef SPMM_TWO_STEPS
+#undef SPMM_STEP_FMAS
+#undef SPMM_STEP_LOADS
                 if (!__builtin_amdgcn_ballot_w64(c0 + 4 * U < len)) break;
                 issue(rs, c0 + 4 * U, col, val);  // rows longer than a chunk: fetched on demand
                 finish(len, c0 + 4 * U, col, val);
@@ -206,10 +244,9 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
             // What the next round needs is settled before C is touched: nothing that is loaded is
             // then still awaited when the loop comes round, and the store below stays in flight.
             finish(len_n, 0, coln, valn);
-            asm volatile("" : "+v"(rs_nn), "+v"(len_nn));
+            asm volatile("" : "+v"(rs_nn), "+v"(len_nn), "+v"(r_nnn));
 
-            const int r = base_of(gi) + rsub;
-            if (r < row_hi && 4 * q < kw) {
+            if (pos_of(gi) < a.m && 4 * q < kw) {
                 float* dst = a.C + static_cast<size_t>(r) * a.ldc + k0 + 4 * q;
                 const bool first = cb0 == 0;
                 const bool reads_c = !first || a.beta != 0.f;
@@ -225,6 +262,9 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                 }
             }
             gi += WAVES;
+            r = r_n;
+            r_n = r_nn;
+            r_nn = r_nnn;
             rs = rs_n;
             len = len_n;
             rs_n = rs_nn;
@@ -240,14 +280,15 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
 
 }  // namespace
 
-hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* C, int64_t ldc, int32_t K, Scalars s,
-                       hipStream_t st) {
+hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B, int64_t ldb, float* C, int64_t ldc,
+                       int32_t K, Scalars s, hipStream_t st) {
     if (A.m <= 0 || K <= 0) return hipSuccess;
     if (A.bf16) return hipErrorInvalidValue;
     SpmmArgs a{};
     a.rowptr = A.rowptr;
     a.colidx = A.colidx;
     a.vals = static_cast<const float*>(A.vals);
+    a.rows = rows;
     a.B = B;
     a.C = C;
     a.ldb = ldb;
@@ -271,17 +312,24 @@ hipError_t launch_spmm(const MatrixView& A, const float* B, int64_t ldb, float* 
     const size_t lds = sizeof(float) * (kSpmmNB + 1) * kSpmmKT;  // the B block and one zero row
     static thread_local bool allowed = false;
     if (!allowed) {
-        for (const void* k : {reinterpret_cast<const void*>(spmm_csr_kernel<true>),
-                              reinterpret_cast<const void*>(spmm_csr_kernel<false>)}) {
+        for (const void* k : {reinterpret_cast<const void*>(spmm_csr_kernel<true, true>),
+                              reinterpret_cast<const void*>(spmm_csr_kernel<true, false>),
+                              reinterpret_cast<const void*>(spmm_csr_kernel<false, true>),
+                              reinterpret_cast<const void*>(spmm_csr_kernel<false, false>)}) {
             hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
             if (e != hipSuccess) return e;
         }
         allowed = true;
     }
-    if (A.n <= kSpmmNB)
-        hipLaunchKernelGGL(spmm_csr_kernel<true>, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
-    else
-        hipLaunchKernelGGL(spmm_csr_kernel<false>, dim3(slices, splits), dim3(kSpmmWG), lds, st, a);
+    const dim3 grid(slices * splits), block(kSpmmWG);
+    const bool single = A.n <= kSpmmNB;
+    if (rows) {
+        if (single) hipLaunchKernelGGL((spmm_csr_kernel<true, true>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((spmm_csr_kernel<false, true>), grid, block, lds, st, a);
+    } else {
+        if (single) hipLaunchKernelGGL((spmm_csr_kernel<true, false>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((spmm_csr_kernel<false, false>), grid, block, lds, st, a);
+    }
     return hipGetLastError();
 }
 

@@ -34,7 +34,7 @@ EXPORTS = [
 class spmv_analyze_params_t(C.Structure):
     _fields_ = [("plan", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
                 ("items_per_chunk", C.c_int32), ("vector_lanes", C.c_int32), ("skip_validation", C.c_int32),
-                ("reserved", C.c_int32 * 2)]
+                ("prepare_spmm", C.c_int32), ("reserved", C.c_int32)]
 
 
 class spmv_analysis_info_t(C.Structure):
@@ -43,7 +43,7 @@ class spmv_analysis_info_t(C.Structure):
                 ("num_chunks", C.c_int64), ("num_x_vectors", C.c_int64), ("plan", C.c_int32),
                 ("vector_lanes", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
                 ("items_per_chunk", C.c_int32), ("max_x_vectors", C.c_int32), ("num_col_blocks", C.c_int32),
-                ("col_block_width", C.c_int32)]
+                ("col_block_width", C.c_int32), ("spmm_prepared", C.c_int32), ("reserved", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -53,7 +53,8 @@ class spmv_analysis_host_t(C.Structure):
     _fields_ = [("bin_count", C.c_void_p), ("bin_offset", C.c_void_p), ("bin_rows", C.c_void_p),
                 ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
                 ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p),
-                ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p)]
+                ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p),
+                ("spmm_rows", C.c_void_p)]
 
 
 class SpmvError(RuntimeError):
@@ -181,6 +182,8 @@ def _host_buffers(info):
     if info.plan == SPMV_PLAN_COLBLOCK:
         bufs.update(cb_ptr=np.zeros(info.num_col_blocks + 1, np.int32), cb_row=np.zeros(info.nnz, np.int32),
                     cb_col=np.zeros(info.nnz, np.int32), cb_src=np.zeros(info.nnz, np.int32))
+    if info.spmm_prepared:
+        bufs.update(spmm_rows=np.zeros(info.m, np.int32))
     out = spmv_analysis_host_t(**{k: v.ctypes.data for k, v in bufs.items()})
     return bufs, out
 

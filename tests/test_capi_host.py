@@ -96,6 +96,21 @@ def test_analyze_parameter_ranges():
         assert st(**bad) == s.SPMV_ERR_INVALID_ARG, bad
 
 
+def test_spmm_row_order_matches_the_oracle():
+    for lens in SHAPES + [list(np.random.default_rng(3).poisson(20.5, 13000)), [300, 252, 253, 0, 4, 5] * 7]:
+        rp = rowptr_of(lens)
+        m, nnz = rp.size - 1, int(rp[-1])
+        st, info, got = s.spmv_analyze_host(m, 7, nnz, rp, dict(prepare_spmm=1))
+        assert st == s.SPMV_OK and info.spmm_prepared == 1
+        assert np.array_equal(got["spmm_rows"], oracle.spmm_row_order(rp))
+        st, info, got = s.spmv_analyze_host(m, 7, nnz, rp)
+        assert st == s.SPMV_OK and info.spmm_prepared == 0 and "spmm_rows" not in got
+    rp = rowptr_of([1, 2, 3])
+    assert s.spmv_analyze_host(3, 4, 6, rp, dict(prepare_spmm=2))[0] == s.SPMV_ERR_INVALID_ARG
+    assert s.spmv_analyze_host(3, 4, 6, rp, dict(prepare_spmm=-1))[0] == s.SPMV_ERR_INVALID_ARG
+    assert s.spmv_analyze_host(3, 4, 6, rp, dict(reserved=1))[0] == s.SPMV_ERR_INVALID_ARG
+
+
 def test_analyze_rejects_malformed_rowptr():
     assert s.spmv_analyze_host(3, 4, 6, np.array([1, 2, 3, 6], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE
     assert s.spmv_analyze_host(3, 4, 6, np.array([0, 4, 3, 6], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE

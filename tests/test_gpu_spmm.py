@@ -45,13 +45,15 @@ def run_spmm(p, B, C0, alpha, beta, lead_pad=0, offset=0, matrix_params=None):
 
 
 def check(p, K, alpha=1.0, beta=0.0, seed=0, **kw):
+    """Both row orders: rows as they come, and the length-sorted order built at analysis time."""
     B, C0 = rand((p.n, K), seed), rand((p.m, K), seed + 1)
-    C = run_spmm(p, B, C0, alpha, beta, **kw)
     C_ref, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B, C0, alpha, beta)
     bound = TOL * (abs(alpha) * S + (np.abs(np.float64(np.float32(beta)) * C0) if beta != 0 else 0.0))
-    err = np.abs(C.astype(np.float64) - C_ref)
-    bad = np.argwhere(~(err <= bound))
-    assert bad.size == 0, (p.name, K, bad[:3].tolist(), err[tuple(bad[0])], bound[tuple(bad[0])])
+    for prepare in (0, 1):
+        C = run_spmm(p, B, C0, alpha, beta, matrix_params=dict(prepare_spmm=prepare), **kw)
+        err = np.abs(C.astype(np.float64) - C_ref)
+        bad = np.argwhere(~(err <= bound))
+        assert bad.size == 0, (p.name, K, prepare, bad[:3].tolist(), err[tuple(bad[0])], bound[tuple(bad[0])])
 
 
 @pytest.mark.parametrize("K", [1, 3, 4, 15, 16, 17, 40, 64, 100])
@@ -83,9 +85,10 @@ def test_exact_integer_bit_for_bit():
     rng = np.random.default_rng(8)
     B = rng.integers(-3, 4, (p.n, 20)).astype(np.float32)
     C0 = rng.integers(-5, 6, (p.m, 20)).astype(np.float32)
-    C = run_spmm(p, B, C0, p.alpha, p.beta)
     C_ref, _ = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, B, C0, p.alpha, p.beta)
-    assert np.array_equal(C.astype(np.float64), C_ref)
+    for prepare in (0, 1):
+        C = run_spmm(p, B, C0, p.alpha, p.beta, matrix_params=dict(prepare_spmm=prepare))
+        assert np.array_equal(C.astype(np.float64), C_ref)
 
 
 def test_beta_zero_ignores_nan_in_c_and_errors():
@@ -107,7 +110,19 @@ def test_beta_zero_ignores_nan_in_c_and_errors():
     d = DeviceProblem(q)
     A = d.matrix()
     assert s.spmm_csr_run(A.handle, Bt.data_ptr(), 16, Ct.data_ptr(), 16, 16, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_csr_analyze(A.handle, dict(prepare_spmm=1)) == s.SPMV_ERR_UNSUPPORTED
     A.close()
+
+
+def test_row_order_read_back_matches_the_oracle():
+    for p in (w.density_random(1 << 14, 2048, 0.01), w.powerlaw(5000), w.from_row_lengths([0, 300, 3, 0, 252, 253, 9], 400, seed=4)):
+        d = DeviceProblem(p)
+        A = d.matrix(dict(prepare_spmm=1))
+        assert A.info.spmm_prepared == 1
+        assert np.array_equal(A.analysis()["spmm_rows"], oracle.spmm_row_order(p.rowptr))
+        A.analyze()                                # re-planned without it: the order is dropped
+        assert A.info.spmm_prepared == 0 and "spmm_rows" not in A.analysis()
+        A.close()
 
 
 @pytest.mark.parametrize("rows_log2", [10, 12, 14])
@@ -124,7 +139,7 @@ def test_paper_shape_2_16_sampled_rows():
     K = 4096
     B = rand((p.n, K), 21)
     d = DeviceProblem(p)
-    A = d.matrix()
+    A = d.matrix(dict(prepare_spmm=1))             # as bench.py times it
     Bt = torch.from_numpy(B).cuda()
     Ct = torch.empty(p.m, K, dtype=torch.float32, device="cuda")
     A.spmm(Bt, Ct)

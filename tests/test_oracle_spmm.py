@@ -85,3 +85,35 @@ def test_linearity_in_B_and_rejects_bad_columns():
     bad[3] = p.n
     with pytest.raises(ValueError):
         oracle.spmm_csr(p.m, p.n, p.rowptr, bad, p.vals, B1)
+
+
+def rowptr_from(lens):
+    return np.concatenate(([0], np.cumsum(np.asarray(lens, dtype=np.int64)))).astype(np.int32)
+
+
+def test_row_order_handworked(golden_dir):
+    h = json.loads((golden_dir / "spmm_row_order_handworked.json").read_text())
+    assert np.array_equal(oracle.spmm_row_order(rowptr_from(h["lens"])), np.array(h["one_window"], np.int32))
+    assert np.array_equal(oracle.spmm_row_order(rowptr_from(h["lens"]), 11), np.array(h["one_window"], np.int32))
+    assert np.array_equal(oracle.spmm_row_order(rowptr_from(h["lens"]), 4), np.array(h["windows_of_4"], np.int32))
+    assert np.array_equal(oracle.spmm_row_order(rowptr_from(h["lens"]), 1), np.arange(11))
+    assert oracle.spmm_row_order(rowptr_from([])).size == 0
+    assert np.array_equal(oracle.spmm_row_order(rowptr_from([7])), [0])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_row_order_defining_properties(seed):
+    """A permutation of the rows; keys never increase along it; equal keys keep ascending row ids."""
+    rng = np.random.default_rng(seed)
+    m = int(rng.integers(1, 3000))
+    lens = np.where(rng.random(m) < 0.05, rng.integers(200, 400, m), rng.poisson(rng.choice([1.5, 6, 20]), m))
+    window = int(rng.choice([1, 7, 64, 4096]))
+    rows = oracle.spmm_row_order(rowptr_from(lens), window)
+    assert np.array_equal(np.sort(rows), np.arange(m))
+    key = np.minimum(-(-lens[rows] // 4), 64)
+    assert set(np.unique(key)) <= set(range(65)) and (key.max() == 64) == bool((lens > 252).any())
+    for w0 in range(0, m, window):                     # every window holds its own rows, sorted
+        part, kpart = rows[w0:w0 + window], key[w0:w0 + window]
+        assert np.array_equal(np.sort(part), np.arange(w0, min(w0 + window, m)))
+        assert np.all(np.diff(kpart) <= 0)
+        assert np.all(np.diff(part)[np.diff(kpart) == 0] > 0)
