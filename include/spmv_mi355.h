@@ -98,8 +98,9 @@ typedef struct {
     int32_t max_x_vectors;             /* most x vectors of any row block (0 when the windows were not counted) */
     int32_t num_col_blocks;            /* COLBLOCK plan: C, the number of column blocks; 0 otherwise */
     int32_t col_block_width;           /* COLBLOCK plan: columns per block (a power of two); 0 otherwise */
-    int32_t spmm_prepared;             /* 1 when spmm_rows was built (prepare_spmm), else 0 */
-    int32_t reserved;                  /* 0 */
+    int32_t spmm_prepared;             /* prepare_spmm: 0 not asked for, 1 spmm_rows built, 2 the packed copy as well */
+    int32_t spmm_col_bytes;            /* packed copy: bytes per column number (2 while n <= 32768, else 4); 0 without it */
+    int64_t spmm_num_blocks;           /* packed copy: blocks of 16 rows x 16 entries; 0 without it */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -125,6 +126,11 @@ typedef struct {
     /* With prepare_spmm only (skipped otherwise): */
     int32_t* spmm_rows;  /* [m]    inside each window of SPMV_SPMM_WINDOW consecutive rows:
                             row ids by decreasing min(ceil(len / 4), 64), ties ascending */
+    /* With the packed copy only (spmm_prepared == 2; G = ceil(m / 16) groups): */
+    int32_t* spmm_desc;  /* [2G+2] pairs (blocks of the groups before g, ceil(longest row of g / 4)),
+                            then (spmm_num_blocks, 0)                                  */
+    void* spmm_col;      /* [spmm_num_blocks * 256] uint16 or int32 (spmm_col_bytes)   */
+    float* spmm_val;     /* [spmm_num_blocks * 256]                                    */
 } spmv_analysis_host_t;
 
 /* Records the matrix (paper App. C task 12: values / col_indices / row_offsets).
@@ -178,6 +184,14 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     order.  spmm_csr_run() advances through a row four entries at a time, so rows of equal
  *     key keep a wavefront busy for the same number of steps; the windows keep the rows of C
  *     that are written at about the same time close together.
+ *     On top of it, a packed copy of A in that order: group g = the rows at positions 16g ..
+ *     16g+15 of spmm_rows (positions from m on: empty rows), stored as ceil(L_g / 16) blocks, L_g
+ *     the longest row of the group.  Slot ((first_g + b) * 64 + 4 i + q) * 4 + e of spmm_col /
+ *     spmm_val holds entry 16 b + 4 q + e of the group's i-th row (i = 0..15, q = 0..3,
+ *     e = 0..3), or padding past the row's end: value 0 and column 2048 when n <= 2048, else all
+ *     ones.  It is built when it has at most 2 * nnz slots and 2^22 blocks (spmm_prepared = 2);
+ *     otherwise only spmm_rows is (spmm_prepared = 1) and spmm_csr_run() reads CSR.  The copy
+ *     holds the values as they were at analyze time.
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
  * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */
 spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params);
@@ -195,8 +209,9 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
  *   h    a handle created with SPMV_F32 and analyzed (the analysis validates the structure; the
  *        product itself uses rowptr / colidx / vals as they are).  A wavefront works on 16 rows
  *        at a time, for as long as the longest of them lasts: analysed with prepare_spmm = 1
- *        it takes them from spmm_rows, where rows of like length are neighbours; otherwise in
- *        their natural order.  The result is the same either way.
+ *        it takes them from spmm_rows, where rows of like length are neighbours (and from the
+ *        packed copy where that was built: then vals as they were at analyze time);
+ *        otherwise in their natural order.  The result is the same to rounding either way.
  *   B    device float, n rows of K used columns, row-major, leading dimension ldb >= K.
  *   C    device float, m rows of K used columns, row-major, leading dimension ldc >= K; read only
  *        if beta != 0 (or when n exceeds 2048, where B is taken in several passes that accumulate

@@ -50,6 +50,12 @@ def _load():
         _lib.oracle_spmm_csr_f32.restype = C.c_int
         _lib.oracle_spmm_row_order.argtypes = [i64, vp, i64, vp]
         _lib.oracle_spmm_row_order.restype = None
+        _lib.oracle_spmm_packed_layout.argtypes = [i64, vp, vp, vp]
+        _lib.oracle_spmm_packed_layout.restype = i64
+        _lib.oracle_spmm_pack.argtypes = [i64, vp, vp, vp, vp, vp, vp, vp]
+        _lib.oracle_spmm_pack.restype = None
+        _lib.oracle_spmm_packed_choice.argtypes = [i64, i64]
+        _lib.oracle_spmm_packed_choice.restype = C.c_int
         _lib.oracle_spmv_coo.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
         _lib.oracle_spmv_csc.argtypes = [i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
         _lib.oracle_spmv_ell.argtypes = [i64, i64, i64, vp, vp, C.c_int, vp, vp, f32, f32, vp, vp]
@@ -288,6 +294,29 @@ def spmm_row_order(rowptr, window=4096):
     rows = np.empty(m, dtype=np.int32)
     _load().oracle_spmm_row_order(m, _p(rowptr), window, _p(rows))
     return rows
+
+
+def spmm_packed_layout(rowptr, rows):
+    """(desc int32[2G+2], number of blocks) of the packed copy for the row order `rows`."""
+    m = rowptr.size - 1
+    _chk(rowptr, np.int32, m + 1), _chk(rows, np.int32, m)
+    desc = np.zeros(2 * ((m + 15) // 16) + 2, dtype=np.int32)
+    blocks = _load().oracle_spmm_packed_layout(m, _p(rowptr), _p(rows), _p(desc))
+    return desc, int(blocks)
+
+
+def spmm_pack(rowptr, colidx, vals, rows, desc):
+    """(columns int32 with -1 as padding, values float32) of the packed copy, one slot each."""
+    m = rowptr.size - 1
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32), _chk(vals, np.float32), _chk(rows, np.int32, m)
+    slots = int(desc[-2]) * 256
+    pcol, pval = np.zeros(slots, dtype=np.int32), np.zeros(slots, dtype=np.float32)
+    _load().oracle_spmm_pack(m, _p(rowptr), _p(colidx), _p(vals), _p(rows), _p(desc), _p(pcol), _p(pval))
+    return pcol, pval
+
+
+def spmm_packed_choice(nnz, blocks):
+    return bool(_load().oracle_spmm_packed_choice(nnz, blocks))
 
 
 def column_block_choice(n, nnz, dtype, plan):

@@ -12,7 +12,9 @@
 //
 // Also the order in which the GPU kernel is handed the rows (its own scheduling aid, not part of
 // the paper's task): the definition written out as a stable sort.  Pins: a hand-worked fixture,
-// and the defining properties checked with numpy on random lengths.
+// and the defining properties checked with numpy on random lengths.  And the packed copy of A in
+// that order, slot by slot from its definition.  Pins: a hand-worked fixture; every entry found
+// exactly once, everything else padding.
 
 #include <algorithm>
 #include <cmath>
@@ -59,6 +61,53 @@ void oracle_spmm_row_order(int64_t m, const int32_t* rowptr, int64_t window, int
     std::iota(rows, rows + m, 0);
     for (int64_t w0 = 0; w0 < m; w0 += window)
         std::stable_sort(rows + w0, rows + std::min(w0 + window, m), [&](int32_t a, int32_t b) { return key(a) > key(b); });
+}
+
+// Packed copy, layout.  Group g = the rows at positions 16g .. 16g+15 of rows[] (positions from m
+// on count as empty rows); L_g = its longest row.  desc[2g] = sum over earlier groups of
+// ceil(L / 16), desc[2g+1] = ceil(L_g / 4); closing pair (total blocks, 0).  Returns the total.
+int64_t oracle_spmm_packed_layout(int64_t m, const int32_t* rowptr, const int32_t* rows, int32_t* desc) {
+    const int64_t groups = (m + 15) / 16;
+    int64_t blocks = 0;
+    for (int64_t g = 0; g < groups; ++g) {
+        int64_t L = 0;
+        for (int64_t i = 0; i < 16; ++i) {
+            const int64_t p = 16 * g + i;
+            if (p < m) L = std::max<int64_t>(L, static_cast<int64_t>(rowptr[rows[p] + 1]) - rowptr[rows[p]]);
+        }
+        desc[2 * g] = static_cast<int32_t>(blocks);
+        desc[2 * g + 1] = static_cast<int32_t>((L + 3) / 4);
+        blocks += (L + 15) / 16;
+    }
+    desc[2 * groups] = static_cast<int32_t>(blocks);
+    desc[2 * groups + 1] = 0;
+    return blocks;
+}
+
+// Packed copy, contents: slot ((desc[2g] + b) * 64 + 4 i + q) * 4 + e holds entry 16 b + 4 q + e
+// of the i-th row of group g, or padding (column -1, value 0) where the row has no such entry.
+void oracle_spmm_pack(int64_t m, const int32_t* rowptr, const int32_t* colidx, const float* vals, const int32_t* rows,
+                      const int32_t* desc, int32_t* pcol, float* pval) {
+    const int64_t groups = (m + 15) / 16;
+    for (int64_t g = 0; g < groups; ++g)
+        for (int64_t b = 0; b < desc[2 * g + 2] - desc[2 * g]; ++b)
+            for (int64_t i = 0; i < 16; ++i)
+                for (int64_t q = 0; q < 4; ++q)
+                    for (int64_t e = 0; e < 4; ++e) {
+                        const int64_t slot = ((desc[2 * g] + b) * 64 + 4 * i + q) * 4 + e;
+                        const int64_t p = 16 * g + i, t = 16 * b + 4 * q + e;
+                        pcol[slot] = -1;
+                        pval[slot] = 0.0f;
+                        if (p < m && t < rowptr[rows[p] + 1] - rowptr[rows[p]]) {
+                            pcol[slot] = colidx[rowptr[rows[p]] + t];
+                            pval[slot] = vals[rowptr[rows[p]] + t];
+                        }
+                    }
+}
+
+// The packed copy is built when it has at most 2 * nnz slots (256 per block) and 2^22 blocks.
+int oracle_spmm_packed_choice(int64_t nnz, int64_t blocks) {
+    return nnz > 0 && 256 * blocks <= 2 * nnz && blocks <= (int64_t{1} << 22);
 }
 
 }  // extern "C"

@@ -2,6 +2,7 @@
 #include "analysis.h"
 
 #include <algorithm>
+#include <climits>
 #include <new>
 
 namespace spmv {
@@ -217,6 +218,27 @@ void spmm_row_order(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows
         }
         for (int64_t i = w0; i < w1; ++i) (*rows)[static_cast<size_t>(cursor[key_of(i)]++)] = static_cast<int32_t>(i);
     }
+}
+
+bool spmm_packed_layout(int64_t m, int64_t nnz, const int32_t* rowptr, const int32_t* rows, std::vector<int32_t>* desc,
+                        int64_t* num_blocks) {
+    const int64_t groups = (m + 15) / 16;
+    desc->assign(static_cast<size_t>(2 * groups + 2), 0);
+    int64_t blocks = 0;
+    for (int64_t g = 0; g < groups; ++g) {
+        int64_t longest = 0;
+        for (int64_t p = 16 * g; p < 16 * g + 16 && p < m; ++p) {
+            const int64_t r = rows[p];
+            longest = std::max<int64_t>(longest, static_cast<int64_t>(rowptr[r + 1]) - rowptr[r]);
+        }
+        // (when the count leaves the int32 range the layout is not used: see the return value)
+        (*desc)[static_cast<size_t>(2 * g)] = static_cast<int32_t>(std::min<int64_t>(blocks, INT32_MAX));
+        (*desc)[static_cast<size_t>(2 * g + 1)] = static_cast<int32_t>((longest + 3) / 4);
+        blocks += (longest + 15) / 16;
+    }
+    (*desc)[static_cast<size_t>(2 * groups)] = static_cast<int32_t>(std::min<int64_t>(blocks, INT32_MAX));
+    *num_blocks = blocks;
+    return nnz > 0 && blocks * 256 <= 2 * nnz && blocks <= kSpmmMaxBlocks;
 }
 
 }  // namespace spmv

@@ -52,4 +52,14 @@ bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, i
 constexpr int kSpmmMaxKey = 64;
 void spmm_row_order(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows);
 
+// Packed layout of the sparse-times-dense kernel.  Group g holds the rows at positions 16g .. 16g+15
+// of `rows` and is stored as ceil(longest row / 16) blocks of 16 rows x 16 entries.
+// desc[2g] = blocks of the groups before g, desc[2g+1] = ceil(longest row of g / 4); one closing
+// pair (all blocks, 0).  Returns whether the packed copy is to be built: at most twice as many
+// slots (256 per block) as the matrix has entries, and at most kSpmmMaxBlocks blocks.  May throw
+// std::bad_alloc.
+constexpr int64_t kSpmmMaxBlocks = int64_t{1} << 22;
+bool spmm_packed_layout(int64_t m, int64_t nnz, const int32_t* rowptr, const int32_t* rows, std::vector<int32_t>* desc,
+                        int64_t* num_blocks);
+
 }  // namespace spmv

@@ -58,6 +58,9 @@ struct spmv_csr_s {
     int32_t* d_xv_pad = nullptr;
     uint16_t* d_lidx = nullptr;
     int32_t* d_spmm_rows = nullptr;  // row order of spmm_csr_run (prepare_spmm)
+    int32_t* d_spmm_desc = nullptr;  // packed copy of A in that order (spmm_prepared == 2)
+    void* d_spmm_col = nullptr;
+    float* d_spmm_val = nullptr;
 };
 
 namespace {
@@ -66,7 +69,8 @@ void free_metadata(spmv_csr_s* h) {
     void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
                     h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
                     h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc, h->d_cb_row, h->d_cb_col,
-                    h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows};
+                    h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
+                    h->d_spmm_val};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
@@ -76,7 +80,9 @@ void free_metadata(spmv_csr_s* h) {
     h->d_cb_vals = nullptr;
     h->cb_ptr.clear();
     h->d_lidx = nullptr;
-    h->d_spmm_rows = nullptr;
+    h->d_spmm_rows = h->d_spmm_desc = nullptr;
+    h->d_spmm_col = nullptr;
+    h->d_spmm_val = nullptr;
     h->analyzed = false;
 }
 
@@ -207,6 +213,36 @@ spmv_status_t build_column_blocks(spmv_csr_s* h, spmv::Analysis* a) {
     return SPMV_OK;
 }
 
+// Row order of the sparse-times-dense product and, where it pays, the packed copy of A in that order.
+spmv_status_t build_spmm_order(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a) try {
+    std::vector<int32_t> order, desc;
+    spmv::spmm_row_order(h->m, rowptr_host.data(), &order);
+    spmv_status_t st = upload(order, &h->d_spmm_rows);
+    if (st != SPMV_OK) return st;
+    a->info.spmm_prepared = 1;
+    int64_t blocks = 0;
+    if (!spmv::spmm_packed_layout(h->m, h->nnz, rowptr_host.data(), order.data(), &desc, &blocks)) return SPMV_OK;
+    const bool col16 = h->n <= spmv::kSpmmCol16MaxN;
+    const size_t slots = (static_cast<size_t>(blocks) + 1) * 256;  // one closing block that is only ever prefetched
+    const size_t col_bytes = col16 ? 2 : 4;
+    st = upload(desc, &h->d_spmm_desc);
+    if (st != SPMV_OK) return st;
+    if (hip_failed(hipMalloc(&h->d_spmm_col, col_bytes * slots)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_spmm_val), sizeof(float) * slots)))
+        return SPMV_ERR_ALLOC;
+    if (hip_failed(hipMemset(static_cast<char*>(h->d_spmm_col) + col_bytes * (slots - 256), 0, col_bytes * 256)) ||
+        hip_failed(hipMemset(h->d_spmm_val + (slots - 256), 0, sizeof(float) * 256)) ||
+        hip_failed(spmv::launch_spmm_pack(view_of(h), h->d_spmm_rows, h->d_spmm_desc, static_cast<int32_t>((h->m + 15) / 16),
+                                          col16, h->d_spmm_col, h->d_spmm_val, nullptr)))
+        return SPMV_ERR_HIP;
+    a->info.spmm_prepared = 2;
+    a->info.spmm_col_bytes = static_cast<int32_t>(col_bytes);
+    a->info.spmm_num_blocks = blocks;
+    return SPMV_OK;
+} catch (const std::bad_alloc&) {
+    return SPMV_ERR_ALLOC;
+}
+
 // Lanes per row the binned plan gives to length bin b (b >= 4: rows of 2^(b-2)+1 .. 2^(b-1) entries).
 inline int lanes_for_bin(int b) {
     const int g = 1 << (b - 3);
@@ -316,16 +352,7 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     }
     if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
     if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
-    if (st == SPMV_OK && p.prepare_spmm) {
-        try {
-            std::vector<int32_t> order;
-            spmv::spmm_row_order(h->m, rowptr_host.data(), &order);
-            st = upload(order, &h->d_spmm_rows);
-            a.info.spmm_prepared = 1;
-        } catch (const std::bad_alloc&) {
-            st = SPMV_ERR_ALLOC;
-        }
-    }
+    if (st == SPMV_OK && p.prepare_spmm) st = build_spmm_order(h, rowptr_host, &a);
     if (st == SPMV_OK) {
         const size_t P = static_cast<size_t>(a.info.num_chunks > 0 ? a.info.num_chunks : 1);
         if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_carry_row), sizeof(int32_t) * P)) ||
@@ -424,8 +451,16 @@ spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* 
     if (!C || ldc < K) return SPMV_ERR_INVALID_ARG;
     if (h->n > 0 && (!B || ldb < K)) return SPMV_ERR_INVALID_ARG;
     if (reinterpret_cast<uintptr_t>(B) % 4 || reinterpret_cast<uintptr_t>(C) % 4) return SPMV_ERR_UNSUPPORTED;
-    const hipError_t e = spmv::launch_spmm(view_of(h), h->d_spmm_rows, B, ldb, C, ldc, static_cast<int32_t>(K), spmv::Scalars{alpha, beta},
-                                           static_cast<hipStream_t>(stream));
+    hipError_t e;
+    if (h->info.spmm_prepared == 2) {
+        const spmv::PackedRows P{h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col, h->d_spmm_val,
+                                 static_cast<int32_t>((h->m + 15) / 16), h->info.spmm_col_bytes == 2};
+        e = spmv::launch_spmm_packed(view_of(h), P, B, ldb, C, ldc, static_cast<int32_t>(K), spmv::Scalars{alpha, beta},
+                                     static_cast<hipStream_t>(stream));
+    } else {
+        e = spmv::launch_spmm(view_of(h), h->d_spmm_rows, B, ldb, C, ldc, static_cast<int32_t>(K), spmv::Scalars{alpha, beta},
+                              static_cast<hipStream_t>(stream));
+    }
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
 
@@ -521,6 +556,18 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
     if (h->info.spmm_prepared && out->spmm_rows && h->info.m > 0 &&
         hip_failed(hipMemcpy(out->spmm_rows, h->d_spmm_rows, sizeof(int32_t) * static_cast<size_t>(h->info.m), hipMemcpyDeviceToHost)))
         return SPMV_ERR_HIP;
+    if (h->info.spmm_prepared == 2) {
+        const size_t groups = static_cast<size_t>((h->info.m + 15) / 16), slots = static_cast<size_t>(h->info.spmm_num_blocks) * 256;
+        if (out->spmm_desc &&
+            hip_failed(hipMemcpy(out->spmm_desc, h->d_spmm_desc, sizeof(int32_t) * (2 * groups + 2), hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+        if (out->spmm_col && slots > 0 &&
+            hip_failed(hipMemcpy(out->spmm_col, h->d_spmm_col, static_cast<size_t>(h->info.spmm_col_bytes) * slots, hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+        if (out->spmm_val && slots > 0 &&
+            hip_failed(hipMemcpy(out->spmm_val, h->d_spmm_val, sizeof(float) * slots, hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+    }
     if (h->info.plan == SPMV_PLAN_COLBLOCK) {
         if (out->cb_ptr) std::memcpy(out->cb_ptr, h->cb_ptr.data(), sizeof(int32_t) * h->cb_ptr.size());
         const Copy ccopies[] = {{out->cb_row, h->d_cb_row, h->info.nnz}, {out->cb_col, h->d_cb_col, h->info.nnz},
@@ -558,18 +605,25 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     spmv::Analysis a;
     st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
     if (st != SPMV_OK) return st;
-    std::vector<int32_t> order;
+    std::vector<int32_t> order, desc;
     if (p.prepare_spmm) {
         try {
             spmv::spmm_row_order(m, rowptr_host, &order);
+            a.info.spmm_prepared = 1;
+            int64_t blocks = 0;
+            if (spmv::spmm_packed_layout(m, nnz, rowptr_host, order.data(), &desc, &blocks)) {
+                a.info.spmm_prepared = 2;  // the layout only: packing needs colidx and vals, which live on the device
+                a.info.spmm_col_bytes = n <= spmv::kSpmmCol16MaxN ? 2 : 4;
+                a.info.spmm_num_blocks = blocks;
+            }
         } catch (const std::bad_alloc&) {
             return SPMV_ERR_ALLOC;
         }
-        a.info.spmm_prepared = 1;
     }
     *info = a.info;
     if (out) {
         if (out->spmm_rows && !order.empty()) std::memcpy(out->spmm_rows, order.data(), sizeof(int32_t) * order.size());
+        if (out->spmm_desc && a.info.spmm_prepared == 2) std::memcpy(out->spmm_desc, desc.data(), sizeof(int32_t) * desc.size());
         if (out->bin_count) std::memcpy(out->bin_count, a.bin_count, sizeof a.bin_count);
         if (out->bin_offset) std::memcpy(out->bin_offset, a.bin_offset, sizeof a.bin_offset);
         if (out->bin_rows && !a.bin_rows.empty())

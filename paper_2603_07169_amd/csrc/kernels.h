@@ -63,6 +63,22 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t 
 // of 0..m-1), or NULL for the natural order.
 hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B, int64_t ldb, float* C, int64_t ldc,
                        int32_t K, Scalars s, hipStream_t st);
+// The packed copy of A the sparse-times-dense product can run from (device pointers).
+constexpr int kSpmmCol16MaxN = 32768;  // up to this many columns the packed column numbers take 16 bits
+struct PackedRows {
+    const int32_t* rows;  // [m] row order
+    const int32_t* desc;  // [2 * (num_groups + 1)] pairs (first block, steps of 4 entries)
+    const void* pcol;     // [(blocks + 1) * 256] uint16 (col16) or int32
+    const float* pval;    // [(blocks + 1) * 256]
+    int32_t num_groups;
+    bool col16;
+};
+// Fills pcol / pval of all blocks of all groups from the CSR arrays (the extra closing block is not written).
+hipError_t launch_spmm_pack(const MatrixView& A, const int32_t* rows, const int32_t* desc, int32_t num_groups, bool col16,
+                            void* pcol, float* pval, hipStream_t st);
+hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const float* B, int64_t ldb, float* C, int64_t ldc,
+                              int32_t K, Scalars s, hipStream_t st);
+const char* spmm_packed_kernel_name();
 // flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st);
 

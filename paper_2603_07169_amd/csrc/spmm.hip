@@ -255,7 +255,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                 if (full4) {
                     f32x4 out = a.alpha * acc;
                     if (reads_c) out += scale_c * *reinterpret_cast<const f32x4*>(dst);
-                    *reinterpret_cast<f32x4*>(dst) = out;
+                    __builtin_nontemporal_store(out, reinterpret_cast<f32x4*>(dst));  // written once, not read again soon
                 } else {
                     for (int t = 0; t < 4; ++t)
                         if (4 * q + t < kw) dst[t] = a.alpha * acc[t] + (reads_c ? scale_c * dst[t] : 0.f);
@@ -274,6 +274,237 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                 col[u] = coln[u];
                 val[u] = valn[u];
             }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// The same product from a packed copy of A (built at analysis time on request).  The rows are
+// taken in the length-sorted order; group g (16 rows) is stored as ceil(longest row / 16) blocks,
+// a block being what one load of the wavefront fetches: lane (row rsub, quad lane q) owns the four
+// slots of entries 16b + 4q .. 16b + 4q + 3 of its row, columns and values in arrays of their
+// own.  Slots past a row's end hold the value 0 and a column that maps to the zero row.  Against
+// reading CSR directly: every load is aligned and fully coalesced, columns take 2 bytes while
+// n <= 32768, no row bounds are fetched, no entry needs a validity test, and the number of steps
+// of a group is a scalar from its descriptor.
+struct SpmmPackedArgs {
+    const int32_t* desc;  // pairs (first block, steps of 4 entries) per group, one closing pair
+    const void* pcol;     // [blocks + 1][64 lanes][4]: uint16 or int32; the last block is padding only
+    const float* pval;    // [blocks + 1][64][4]
+    const int32_t* rows;  // [m] the row order
+    const float* B;
+    float* C;
+    int64_t ldb, ldc;
+    int32_t m, n, K, num_groups;
+    int32_t row_splits, vec_ok;
+    float alpha, beta;
+};
+
+// Column number a padding slot holds: the zero row itself when all of B fits one block, else a
+// number no block of B contains.
+template <typename CT>
+__host__ __device__ inline CT packed_pad_column(int n) {
+    return n <= kSpmmNB ? static_cast<CT>(kSpmmNB) : static_cast<CT>(-1);
+}
+
+template <typename CT>
+__global__ __launch_bounds__(64) void spmm_pack_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
+                                                       const float* __restrict__ vals, const int32_t* __restrict__ rows,
+                                                       const int32_t* __restrict__ desc, int m, int n, CT* __restrict__ pcol,
+                                                       float* __restrict__ pval) {
+    const int g = blockIdx.x, lane = threadIdx.x, rsub = lane >> 2, q = lane & 3;
+    const int first = desc[2 * g], nblocks = desc[2 * g + 2] - first;
+    const int pos = 16 * g + rsub;
+    int rs = 0, len = 0;
+    if (pos < m) {
+        const int r = rows[pos];
+        rs = rowptr[r];
+        len = rowptr[r + 1] - rs;
+    }
+    const CT pad = packed_pad_column<CT>(n);
+    for (int b = 0; b < nblocks; ++b) {
+        const size_t slot0 = (static_cast<size_t>(first + b) * 64 + lane) * 4;
+        for (int e = 0; e < 4; ++e) {
+            const int t = 16 * b + 4 * q + e;
+            const bool live = t < len;
+            pcol[slot0 + e] = live ? static_cast<CT>(colidx[rs + t]) : pad;
+            pval[slot0 + e] = live ? vals[rs + t] : 0.f;
+        }
+    }
+}
+
+// One block of the packed copy as a lane holds it.
+template <typename CT>
+struct PackedBlock;
+template <>
+struct PackedBlock<uint16_t> {
+    unsigned c01, c23;  // four 16-bit columns
+    f32x4 v;
+    __device__ __forceinline__ void load(const void* pcol, const float* pval, size_t lane_slot) {
+        const uint2 c = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(pcol) + lane_slot);
+        c01 = c.x;
+        c23 = c.y;
+        v = *reinterpret_cast<const f32x4*>(pval + lane_slot);
+    }
+    __device__ __forceinline__ unsigned col(int e) const {
+        const unsigned w = e < 2 ? c01 : c23;
+        return (e & 1) ? w >> 16 : w & 0xFFFFu;
+    }
+    __device__ __forceinline__ void touch() { asm volatile("" : "+v"(c01), "+v"(c23), "+v"(v)); }
+};
+template <>
+struct PackedBlock<int32_t> {
+    i32x4 c;
+    f32x4 v;
+    __device__ __forceinline__ void load(const void* pcol, const float* pval, size_t lane_slot) {
+        c = *reinterpret_cast<const i32x4*>(static_cast<const int32_t*>(pcol) + lane_slot);
+        v = *reinterpret_cast<const f32x4*>(pval + lane_slot);
+    }
+    __device__ __forceinline__ unsigned col(int e) const { return static_cast<unsigned>(c[e]); }
+    __device__ __forceinline__ void touch() { asm volatile("" : "+v"(c), "+v"(v)); }
+};
+
+template <bool SINGLE, typename CT>
+__global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedArgs a) {
+    constexpr int KT = kSpmmKT, NB = kSpmmNB, RPW = 16, WAVES = kSpmmWG / 64;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    float* Bs = reinterpret_cast<float*>(smem_raw);  // [NB + 1][KT]; row NB stays zero
+    const unsigned char* const Bq = smem_raw + 16 * (threadIdx.x & 3);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q = lane & 3, rsub = lane >> 2;
+
+    // die-aware numbering of the (slice, split) pairs, as in spmm_csr_kernel
+    const int n_slices = (a.K + KT - 1) / KT;
+    int pair;
+    {
+        const int nb = gridDim.x, per = nb / kXcds, rem = nb % kXcds;
+        const int die = blockIdx.x % kXcds, slot = blockIdx.x / kXcds;
+        pair = die * per + (die < rem ? die : rem) + slot;
+    }
+    const int slice = pair % n_slices, split = pair / n_slices;
+    const int k0 = slice * KT;
+    const int kw = a.K - k0 < KT ? a.K - k0 : KT;
+    const bool full4 = a.vec_ok && 4 * q + 4 <= kw;
+    if (tid < KT) Bs[NB * KT + tid] = 0.f;
+
+    const int S = a.row_splits, y = split;
+    const int n_groups = a.num_groups > y ? (a.num_groups - y + S - 1) / S : 0;  // this workgroup's
+    // (first block, steps) of the wavefront's j-th group; past the end: the closing pair (all blocks, 0)
+    auto load_desc = [&](int j, int& first, int& nsteps) {
+        const int g = j < n_groups ? y + S * j : a.num_groups;
+        first = a.desc[2 * g];
+        nsteps = a.desc[2 * g + 1];
+    };
+
+    for (int cb0 = 0; cb0 < (SINGLE ? 1 : a.n); cb0 += NB) {
+        const int nbk = a.n - cb0 < NB ? a.n - cb0 : NB;
+        if (cb0 > 0) __syncthreads();
+        for (int idx = tid; idx < nbk * 4; idx += kSpmmWG) {
+            const int j = idx >> 2, qq = idx & 3;
+            const float* src = a.B + static_cast<size_t>(cb0 + j) * a.ldb + k0 + 4 * qq;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (a.vec_ok && 4 * qq + 4 <= kw) {
+                v = *reinterpret_cast<const f32x4*>(src);
+            } else {
+                for (int t = 0; t < 4; ++t)
+                    if (4 * qq + t < kw) v[t] = src[t];
+            }
+            *reinterpret_cast<f32x4*>(Bs + j * KT + 4 * qq) = v;
+        }
+        __syncthreads();
+
+        // column -> byte offset of the B row in the LDS block; padding and columns of other blocks -> zero row
+        auto offsets = [&](const PackedBlock<CT>& blk, int (&off)[4]) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                unsigned c = blk.col(e);
+                if constexpr (!SINGLE) {
+                    c -= static_cast<unsigned>(cb0);  // a column before the block wraps to a huge number
+                    c = c < static_cast<unsigned>(NB) ? c : static_cast<unsigned>(NB);
+                }
+                off[e] = static_cast<int>(c * (KT * 4));
+            }
+        };
+
+        int j = wave;
+        int first, nsteps, first_n, nsteps_n;
+        load_desc(j, first, nsteps);
+        load_desc(j + WAVES, first_n, nsteps_n);
+        PackedBlock<CT> cur;
+        cur.load(a.pcol, a.pval, (static_cast<size_t>(first) * 64 + lane) * 4);
+        while (j < n_groups) {
+            const int pos = (y + S * j) * RPW + rsub;
+            const int r = a.rows[pos < a.m ? pos : a.m - 1];
+            float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
+            const int nblocks = nsteps > 0 ? (nsteps + 3) / 4 : 1;  // a group of empty rows: one pass that multiplies nothing
+            for (int b = 0; b < nblocks; ++b) {
+                // the next block of the wavefront's stream: the group's next one, else the next group's first
+                const int next_block = b + 1 < nblocks ? first + b + 1 : first_n;
+                PackedBlock<CT> nxt;
+                nxt.load(a.pcol, a.pval, (static_cast<size_t>(next_block) * 64 + lane) * 4);
+                const int steps = nsteps - 4 * b;  // steps of this block still to do (4 or more: all four)
+                int off[4];
+                offsets(cur, off);
+#define SPMM_STEP_LOADS(B0, J)                                                   \
+    B0[0] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<J>(off[0]));         \
+    B0[1] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<J>(off[1]));         \
+    B0[2] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<J>(off[2]));         \
+    B0[3] = *reinterpret_cast<const f32x4*>(Bq + quad_bcast<J>(off[3]));
+#define SPMM_STEP_FMAS(B0, J)                          \
+    _Pragma("unroll") for (int e = 0; e < 4; ++e) {    \
+        fma_quad<J>(acc0, cur.v[e], B0[e][0]);         \
+        fma_quad<J>(acc1, cur.v[e], B0[e][1]);         \
+        fma_quad<J>(acc2, cur.v[e], B0[e][2]);         \
+        fma_quad<J>(acc3, cur.v[e], B0[e][3]);         \
+    }
+                // step J takes the four slots of lane J of every quad.  All LDS reads of the block go out
+                // first, so the multiply-adds of the early steps run while the later rows arrive.
+                {
+                    f32x4 b0[4], b1[4], b2[4], b3[4];
+                    switch (steps >= 4 ? 4 : steps) {
+                        case 4:
+                            SPMM_STEP_LOADS(b0, 0) SPMM_STEP_LOADS(b1, 1) SPMM_STEP_LOADS(b2, 2) SPMM_STEP_LOADS(b3, 3)
+                            SPMM_STEP_FMAS(b0, 0) SPMM_STEP_FMAS(b1, 1) SPMM_STEP_FMAS(b2, 2) SPMM_STEP_FMAS(b3, 3)
+                            break;
+                        case 3:
+                            SPMM_STEP_LOADS(b0, 0) SPMM_STEP_LOADS(b1, 1) SPMM_STEP_LOADS(b2, 2)
+                            SPMM_STEP_FMAS(b0, 0) SPMM_STEP_FMAS(b1, 1) SPMM_STEP_FMAS(b2, 2)
+                            break;
+                        case 2:
+                            SPMM_STEP_LOADS(b0, 0) SPMM_STEP_LOADS(b1, 1) SPMM_STEP_FMAS(b0, 0) SPMM_STEP_FMAS(b1, 1)
+                            break;
+                        case 1:
+                            SPMM_STEP_LOADS(b0, 0) SPMM_STEP_FMAS(b0, 0)
+                            break;
+                        default:
+                            break;
+                    }
+                }
+#undef SPMM_STEP_FMAS
+#undef SPMM_STEP_LOADS
+                nxt.touch();  // arrived before anything is stored: the loop never waits behind a store
+                cur = nxt;
+            }
+
+            if (pos < a.m && 4 * q < kw) {
+                float* dst = a.C + static_cast<size_t>(r) * a.ldc + k0 + 4 * q;
+                const bool first_pass = cb0 == 0;
+                const bool reads_c = !first_pass || a.beta != 0.f;
+                const float scale_c = first_pass ? a.beta : 1.f;
+                const f32x4 acc = {acc0, acc1, acc2, acc3};
+                if (full4) {
+                    f32x4 out = a.alpha * acc;
+                    if (reads_c) out += scale_c * *reinterpret_cast<const f32x4*>(dst);
+                    __builtin_nontemporal_store(out, reinterpret_cast<f32x4*>(dst));  // written once, not read again soon
+                } else {
+                    for (int t = 0; t < 4; ++t)
+                        if (4 * q + t < kw) dst[t] = a.alpha * acc[t] + (reads_c ? scale_c * dst[t] : 0.f);
+                }
+            }
+            j += WAVES;
+            first = first_n;
+            nsteps = nsteps_n;
+            load_desc(j + WAVES, first_n, nsteps_n);
         }
     }
 }
@@ -333,6 +564,67 @@ hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B,
     return hipGetLastError();
 }
 
+hipError_t launch_spmm_pack(const MatrixView& A, const int32_t* rows, const int32_t* desc, int32_t num_groups, bool col16,
+                            void* pcol, float* pval, hipStream_t st) {
+    if (num_groups <= 0) return hipSuccess;
+    if (A.bf16) return hipErrorInvalidValue;
+    if (col16)
+        hipLaunchKernelGGL((spmm_pack_kernel<uint16_t>), dim3(num_groups), dim3(64), 0, st, A.rowptr, A.colidx,
+                           static_cast<const float*>(A.vals), rows, desc, A.m, A.n, static_cast<uint16_t*>(pcol), pval);
+    else
+        hipLaunchKernelGGL((spmm_pack_kernel<int32_t>), dim3(num_groups), dim3(64), 0, st, A.rowptr, A.colidx,
+                           static_cast<const float*>(A.vals), rows, desc, A.m, A.n, static_cast<int32_t*>(pcol), pval);
+    return hipGetLastError();
+}
+
+hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const float* B, int64_t ldb, float* C, int64_t ldc,
+                              int32_t K, Scalars s, hipStream_t st) {
+    if (A.m <= 0 || K <= 0) return hipSuccess;
+    SpmmPackedArgs a{};
+    a.desc = P.desc;
+    a.pcol = P.pcol;
+    a.pval = P.pval;
+    a.rows = P.rows;
+    a.B = B;
+    a.C = C;
+    a.ldb = ldb;
+    a.ldc = ldc;
+    a.m = A.m;
+    a.n = A.n;
+    a.K = K;
+    a.num_groups = P.num_groups;
+    a.alpha = s.alpha;
+    a.beta = s.beta;
+    a.vec_ok = (reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldb % 4 == 0 &&
+                ldc % 4 == 0)
+                   ? 1
+                   : 0;
+    const int slices = ceil_div(K, kSpmmKT);
+    int splits = slices >= 256 ? 1 : ceil_div(256, slices);
+    if (splits > P.num_groups) splits = P.num_groups;
+    a.row_splits = splits;
+    const size_t lds = sizeof(float) * (kSpmmNB + 1) * kSpmmKT;
+    static thread_local bool allowed = false;
+    if (!allowed) {
+        for (const void* k : {reinterpret_cast<const void*>(spmm_packed_kernel<true, uint16_t>),
+                              reinterpret_cast<const void*>(spmm_packed_kernel<false, uint16_t>),
+                              reinterpret_cast<const void*>(spmm_packed_kernel<false, int32_t>)}) {
+            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return e;
+        }
+        allowed = true;
+    }
+    const dim3 grid(slices * splits), block(kSpmmWG);
+    if (P.col16) {
+        if (A.n <= kSpmmNB) hipLaunchKernelGGL((spmm_packed_kernel<true, uint16_t>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((spmm_packed_kernel<false, uint16_t>), grid, block, lds, st, a);
+    } else {
+        hipLaunchKernelGGL((spmm_packed_kernel<false, int32_t>), grid, block, lds, st, a);
+    }
+    return hipGetLastError();
+}
+
 const char* spmm_kernel_name() { return "spmm_csr_kernel"; }
+const char* spmm_packed_kernel_name() { return "spmm_packed_kernel"; }
 
 }  // namespace spmv

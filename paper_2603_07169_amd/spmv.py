@@ -43,7 +43,8 @@ class spmv_analysis_info_t(C.Structure):
                 ("num_chunks", C.c_int64), ("num_x_vectors", C.c_int64), ("plan", C.c_int32),
                 ("vector_lanes", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
                 ("items_per_chunk", C.c_int32), ("max_x_vectors", C.c_int32), ("num_col_blocks", C.c_int32),
-                ("col_block_width", C.c_int32), ("spmm_prepared", C.c_int32), ("reserved", C.c_int32)]
+                ("col_block_width", C.c_int32), ("spmm_prepared", C.c_int32), ("spmm_col_bytes", C.c_int32),
+                ("spmm_num_blocks", C.c_int64)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -54,7 +55,7 @@ class spmv_analysis_host_t(C.Structure):
                 ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
                 ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p),
                 ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p),
-                ("spmm_rows", C.c_void_p)]
+                ("spmm_rows", C.c_void_p), ("spmm_desc", C.c_void_p), ("spmm_col", C.c_void_p), ("spmm_val", C.c_void_p)]
 
 
 class SpmvError(RuntimeError):
@@ -184,6 +185,11 @@ def _host_buffers(info):
                     cb_col=np.zeros(info.nnz, np.int32), cb_src=np.zeros(info.nnz, np.int32))
     if info.spmm_prepared:
         bufs.update(spmm_rows=np.zeros(info.m, np.int32))
+    if info.spmm_prepared == 2:
+        slots = info.spmm_num_blocks * 256
+        bufs.update(spmm_desc=np.zeros(2 * ((info.m + 15) // 16) + 2, np.int32),
+                    spmm_col=np.zeros(slots, np.uint16 if info.spmm_col_bytes == 2 else np.int32),
+                    spmm_val=np.zeros(slots, np.float32))
     out = spmv_analysis_host_t(**{k: v.ctypes.data for k, v in bufs.items()})
     return bufs, out
 

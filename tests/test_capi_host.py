@@ -101,10 +101,20 @@ def test_spmm_row_order_matches_the_oracle():
         rp = rowptr_of(lens)
         m, nnz = rp.size - 1, int(rp[-1])
         st, info, got = s.spmv_analyze_host(m, 7, nnz, rp, dict(prepare_spmm=1))
-        assert st == s.SPMV_OK and info.spmm_prepared == 1
-        assert np.array_equal(got["spmm_rows"], oracle.spmm_row_order(rp))
+        assert st == s.SPMV_OK
+        rows = oracle.spmm_row_order(rp)
+        assert np.array_equal(got["spmm_rows"], rows)
+        desc, blocks = oracle.spmm_packed_layout(rp, rows)
+        packed = oracle.spmm_packed_choice(nnz, blocks)
+        assert info.spmm_prepared == (2 if packed else 1)
+        assert (info.spmm_num_blocks, info.spmm_col_bytes) == ((blocks, 2) if packed else (0, 0))
+        if packed:
+            assert np.array_equal(got["spmm_desc"], desc)
         st, info, got = s.spmv_analyze_host(m, 7, nnz, rp)
         assert st == s.SPMV_OK and info.spmm_prepared == 0 and "spmm_rows" not in got
+    rp = rowptr_of([20] * 100)                       # 32 slots a row for 20 entries: packed; column width by n
+    assert [s.spmv_analyze_host(100, n, 2000, rp, dict(prepare_spmm=1))[1].spmm_col_bytes for n in (32768, 32769)] == [2, 4]
+    assert s.spmv_analyze_host(400, 7, 2000, rowptr_of([5] * 400), dict(prepare_spmm=1))[1].spmm_prepared == 1
     rp = rowptr_of([1, 2, 3])
     assert s.spmv_analyze_host(3, 4, 6, rp, dict(prepare_spmm=2))[0] == s.SPMV_ERR_INVALID_ARG
     assert s.spmv_analyze_host(3, 4, 6, rp, dict(prepare_spmm=-1))[0] == s.SPMV_ERR_INVALID_ARG

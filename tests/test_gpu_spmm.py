@@ -114,12 +114,27 @@ def test_beta_zero_ignores_nan_in_c_and_errors():
     A.close()
 
 
-def test_row_order_read_back_matches_the_oracle():
-    for p in (w.density_random(1 << 14, 2048, 0.01), w.powerlaw(5000), w.from_row_lengths([0, 300, 3, 0, 252, 253, 9], 400, seed=4)):
+def test_row_order_and_packed_copy_read_back_match_the_oracle():
+    cases = [(w.density_random(1 << 14, 2048, 0.01), 2, 2), (w.powerlaw(5000), 1, 0),
+             (w.from_row_lengths([0, 300, 3, 0, 252, 253, 9], 400, seed=4), 1, 0),
+             (w.uniform_rows(3000, 5000, 24), 2, 2), (w.uniform_rows(700, 40000, 24), 2, 4),
+             (w.from_row_lengths(np.random.default_rng(1).poisson(30, 1000), 100, seed=2, allow_dup=True), 2, 2)]
+    for p, prepared, col_bytes in cases:
+        log("case spmm packed", p.name)
         d = DeviceProblem(p)
         A = d.matrix(dict(prepare_spmm=1))
-        assert A.info.spmm_prepared == 1
-        assert np.array_equal(A.analysis()["spmm_rows"], oracle.spmm_row_order(p.rowptr))
+        assert (A.info.spmm_prepared, A.info.spmm_col_bytes) == (prepared, col_bytes)
+        got = A.analysis()
+        rows = oracle.spmm_row_order(p.rowptr)
+        assert np.array_equal(got["spmm_rows"], rows)
+        if prepared == 2:
+            desc, blocks = oracle.spmm_packed_layout(p.rowptr, rows)
+            assert oracle.spmm_packed_choice(p.nnz, blocks) and A.info.spmm_num_blocks == blocks
+            assert np.array_equal(got["spmm_desc"], desc)
+            pcol, pval = oracle.spmm_pack(p.rowptr, p.colidx, p.vals, rows, desc)
+            pad = 2048 if p.n <= 2048 else (65535 if col_bytes == 2 else -1)   # what the library writes for "no entry"
+            lib_col = got["spmm_col"].astype(np.int64)
+            assert np.array_equal(np.where(lib_col == pad, -1, lib_col), pcol) and np.array_equal(got["spmm_val"], pval)
         A.analyze()                                # re-planned without it: the order is dropped
         assert A.info.spmm_prepared == 0 and "spmm_rows" not in A.analysis()
         A.close()

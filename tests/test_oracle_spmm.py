@@ -117,3 +117,48 @@ def test_row_order_defining_properties(seed):
         assert np.array_equal(np.sort(part), np.arange(w0, min(w0 + window, m)))
         assert np.all(np.diff(kpart) <= 0)
         assert np.all(np.diff(part)[np.diff(kpart) == 0] > 0)
+
+
+def test_packed_copy_handworked(golden_dir):
+    h = json.loads((golden_dir / "spmm_packed_handworked.json").read_text())
+    rp = rowptr_from(h["lens"])
+    nnz = int(rp[-1])
+    colidx = ((7 * np.arange(nnz)) % 50).astype(np.int32)
+    vals = (np.arange(nnz) + 1).astype(np.float32)
+    rows = oracle.spmm_row_order(rp)
+    assert rows.tolist() == h["rows"]
+    desc, blocks = oracle.spmm_packed_layout(rp, rows)
+    assert desc.tolist() == h["desc"] and blocks == h["blocks"]
+    pcol, pval = oracle.spmm_pack(rp, colidx, vals, rows, desc)
+    want_col, want_val = np.full(512, -1, np.int32), np.zeros(512, np.float32)
+    for slot, k in h["live"]:
+        want_col[slot], want_val[slot] = colidx[k], vals[k]
+    assert np.array_equal(pcol, want_col) and np.array_equal(pval, want_val)
+    assert not oracle.spmm_packed_choice(nnz, blocks)            # 512 slots for 23 entries
+    assert oracle.spmm_packed_choice(256, 2) and not oracle.spmm_packed_choice(255, 2)
+    assert not oracle.spmm_packed_choice(0, 0) and not oracle.spmm_packed_choice(2 ** 31, 2 ** 22 + 1)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_packed_copy_holds_every_entry_once(seed):
+    rng = np.random.default_rng(100 + seed)
+    m = int(rng.integers(1, 400))
+    lens = rng.poisson(rng.choice([2, 20.5, 70]), m)
+    lens[rng.integers(0, m, 3)] = 0
+    p = w.from_row_lengths(lens, 300, seed=seed, allow_dup=True)
+    rows = oracle.spmm_row_order(p.rowptr, int(rng.choice([16, 64, 4096])))
+    desc, blocks = oracle.spmm_packed_layout(p.rowptr, rows)
+    pcol, pval = oracle.spmm_pack(p.rowptr, p.colidx, p.vals, rows, desc)
+    assert pcol.size == blocks * 256 and desc[-2] == blocks and desc[-1] == 0
+    live = pcol >= 0
+    assert np.all(pval[~live] == 0) and np.all(pcol[~live] == -1) and live.sum() == p.nnz
+    slot = np.flatnonzero(live)
+    block, i = slot // 256, (slot % 256) // 16
+    group = np.searchsorted(desc[0::2], block, side="right") - 1          # the group a block belongs to
+    row = rows[16 * group + i]
+    got = sorted(zip(row.tolist(), pcol[live].tolist(), pval[live].tolist()))
+    want = sorted(zip(np.repeat(np.arange(m), lens).tolist(), p.colidx.tolist(), p.vals.tolist()))
+    assert got == want
+    # a group's steps: the quarter-rounded length of its longest row
+    longest = np.array([lens[rows[16 * g:16 * g + 16]].max() for g in range((m + 15) // 16)])
+    assert np.array_equal(desc[1:-2:2], -(-longest // 4)) and np.array_equal(np.diff(desc[0::2]), -(-longest // 16))
