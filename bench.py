@@ -61,7 +61,9 @@ def parse():
 def kernels_sha256():
     import hashlib
     h = hashlib.sha256()
-    for name in ("kernels.hip", "device_common.h", "capi.cpp", "analysis.cpp"):   # what the CSR product runs
+    # what the CSR matrix-vector product runs (the column-blocked plan multiplies with the coordinate kernel)
+    for name in ("kernels.hip", "device_common.h", "kernels.h", "capi.cpp", "analysis.cpp", "analysis.h", "formats.hip",
+                 "colblock.hip"):
         h.update((ROOT / "paper_2603_07169_amd" / "csrc" / name).read_bytes())
     return h.hexdigest()
 
