@@ -62,7 +62,7 @@ def kernels_sha256():
     import hashlib
     h = hashlib.sha256()
     # what the CSR matrix-vector product runs (the column-blocked plan multiplies with the coordinate kernel)
-    for name in ("kernels.hip", "device_common.h", "kernels.h", "capi.cpp", "analysis.cpp", "analysis.h", "formats.hip",
+    for name in ("kernels.hip", "device_common.h", "row_phase.h", "kernels.h", "capi.cpp", "analysis.cpp", "analysis.h", "formats.hip",
                  "colblock.hip"):
         h.update((ROOT / "paper_2603_07169_amd" / "csrc" / name).read_bytes())
     return h.hexdigest()

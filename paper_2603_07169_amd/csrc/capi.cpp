@@ -515,8 +515,11 @@ spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* c
     // m * width itself may exceed the limit: slots are addressed with 64-bit offsets
     const spmv_status_t st = check_stateless(m, n, m > 0 ? width : 0, dtype, col_ids, col_ids, vals, x, y);
     if (st != SPMV_OK) return st;
-    const hipError_t e = spmv::launch_ell(dtype == SPMV_BF16, static_cast<int32_t>(m), static_cast<int32_t>(width), col_ids,
-                                          vals, x, y, spmv::Scalars{alpha, beta}, static_cast<hipStream_t>(stream));
+    // without columns every slot is padding: y <- beta*y, and x (which may point at nothing) is never read
+    const hipError_t e =
+        n == 0 ? spmv::launch_scale_y(y, static_cast<int32_t>(m), beta, static_cast<hipStream_t>(stream))
+               : spmv::launch_ell(dtype == SPMV_BF16, static_cast<int32_t>(m), static_cast<int32_t>(width), col_ids, vals, x, y,
+                                  spmv::Scalars{alpha, beta}, static_cast<hipStream_t>(stream));
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
 

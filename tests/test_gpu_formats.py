@@ -133,3 +133,38 @@ def test_beta_zero_ignores_nan_and_argument_errors():
     assert s.spmv_ell_run(5, 3, 0, None, None, 0, d[3].data_ptr(), y.data_ptr(), 1.0, 0.5) == s.SPMV_OK
     torch.cuda.synchronize()
     assert np.array_equal(y.cpu().numpy(), np.arange(5, dtype=np.float32))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ell_widths_around_the_tile_limits_with_garbage_in_the_padding(dtype):
+    """Widths 1..513 (rows of up to 64 slots are staged through LDS, wider ones are not), row counts that are
+    no multiple of a tile, misaligned arrays, and NaN / Inf in the padding slots' values, which must be ignored."""
+    rng = np.random.default_rng(17)
+    for width, m, off in [(1, 1000, 0), (3, 777, 0), (7, 2049, 1), (8, 300, 0), (27, 5001, 0), (27, 5001, 3), (63, 900, 0), (64, 901, 1), (65, 902, 0), (100, 333, 0),
+                          (511, 70, 0), (512, 41, 0), (513, 40, 0), (16, 256, 0), (16, 257, 2)]:
+        lens = rng.integers(0, width + 1, m)
+        lens[rng.integers(0, m, 3)] = width
+        p = w.from_row_lengths(lens, max(width, 600), seed=width, dtype=dtype, beta=0.5, alpha=-2.0, allow_dup=True)
+        log("case ell width", width, m, off, dtype)
+        got_width, ci, vals = w.to_ell(p, width)
+        assert got_width == width
+        vals = vals.copy()
+        pad = ci < 0
+        junk = np.array([np.nan, np.inf, -np.inf, 3e38], np.float32)[rng.integers(0, 4, int(pad.sum()))]
+        vals[pad] = junk if dtype == "f32" else w.f32_to_bf16_bits(np.nan_to_num(junk, nan=3e38, posinf=3e38, neginf=-3e38)) | np.uint16(0x7F80)
+        y0 = y_init(p)
+        y_ref, S = oracle.spmv_ell(dtype, p.m, p.n, width, ci, vals, p.x, y0, p.alpha, p.beta)
+        assert np.all(np.isfinite(y_ref))
+        d = [to_dev(ci, off), to_dev(vals, off), to_dev(p.x)]
+        y = to_dev(y0.copy())
+        assert s.spmv_ell_run(p.m, p.n, width, d[0].data_ptr(), d[1].data_ptr(), DTYPE_CODE[dtype], d[2].data_ptr(),
+                              y.data_ptr(), p.alpha, p.beta) == s.SPMV_OK
+        torch.cuda.synchronize()
+        check(p, y.cpu().numpy(), y_ref, S, "ell widths")
+    # no columns at all: every slot is padding and x points at nothing
+    ci = np.full((50, 4), -1, np.int32).reshape(-1)
+    y = to_dev(np.ones(50, np.float32))
+    assert s.spmv_ell_run(50, 0, 4, to_dev(ci).data_ptr(), to_dev(np.zeros(200, np.float32)).data_ptr(), 0,
+                          to_dev(np.zeros(1, np.float32)).data_ptr(), y.data_ptr(), 1.0, 3.0) == s.SPMV_OK
+    torch.cuda.synchronize()
+    assert np.all(y.cpu().numpy() == 3.0)
