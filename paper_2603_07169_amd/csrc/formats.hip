@@ -21,35 +21,98 @@ __global__ __launch_bounds__(kWG) void scale_y_kernel(float* __restrict__ y, int
     for (int i = blockIdx.x * kWG + threadIdx.x; i < m; i += gridDim.x * kWG) y[i] = beta == 0.f ? 0.f : beta * y[i];
 }
 
-// One entry per lane and trip.  Runs of equal row numbers in consecutive lanes (the whole
-// wavefront when the entries are sorted by row) are summed first with a segmented scan, so a
-// run costs one atomic instead of one per entry.
+// Four consecutive entries per lane and trip.  A lane first sums the runs of equal row numbers
+// among its own four; runs that lie wholly inside go to y with one hardware float atomic each.
+// Its last run (its only one, if all four rows agree) may go on in the next lanes and its first may
+// continue the previous lane's: those are joined across the wavefront with a segmented scan over
+// the lanes' last-run sums, so a row held by consecutive entries (the whole row, for row-sorted
+// input) costs one atomic per wavefront it touches instead of one per entry.
+// shift: the arrays are read in aligned groups of four starting `shift` (0..3) entries before
+// `row`; vec: those groups may be fetched with one 16-byte (8-byte for bf16 values) load each.
 template <typename T>
 __global__ __launch_bounds__(kWG) void spmv_coo_kernel(const int32_t* __restrict__ row, const int32_t* __restrict__ col,
                                                        const typename T::elem* __restrict__ vals,
                                                        const typename T::elem* __restrict__ x, float* y, int nnz,
-                                                       float alpha) {
+                                                       int shift, int vec, float alpha) {
+    using E = typename T::elem;
     const int lane = threadIdx.x & 63;
-    const int wave = (blockIdx.x * kWG + threadIdx.x) >> 6;
-    const int n_waves = (gridDim.x * kWG) >> 6;
-    for (int base = wave * 64; base < nnz; base += n_waves * 64) {  // the same trip count for all lanes of a wavefront
-        const int e = base + lane;
-        const bool live = e < nnz;
-        const int r = live ? row[e] : -1;
-        float p = live ? alpha * (widen(vals[e]) * widen(x[col[e]])) : 0.f;
-        const int r_prev = __shfl_up(r, 1, 64);
-        bool head = lane == 0 || r_prev != r;
+    const int64_t wave = (static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x) >> 6;
+    const int64_t n_waves = (static_cast<int64_t>(gridDim.x) * kWG) >> 6;
+    const int64_t n_groups = (static_cast<int64_t>(nnz) + shift + 3) / 4;
+    for (int64_t gbase = wave * 64; gbase < n_groups; gbase += n_waves * 64) {  // the same trip count for all lanes of a wavefront
+        const int64_t e0_64 = 4 * (gbase + lane) - shift;  // first of this lane's four entries; < 0 or >= nnz: none
+        int r[4];
+        float p[4];
+        if (vec && e0_64 >= 0 && e0_64 + 3 < nnz) {
+            const int e0 = static_cast<int>(e0_64);
+            const i32x4 rv = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(row + e0));
+            const i32x4 cv = __builtin_nontemporal_load(reinterpret_cast<const i32x4*>(col + e0));
+            float v[4];
+            if constexpr (sizeof(E) == 4) {
+                const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(vals + e0));
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = vv[i];
+            } else {
+                typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                const u32x2 vv = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(vals + e0));
+                v[0] = __uint_as_float(vv[0] << 16);
+                v[1] = __uint_as_float(vv[0] & 0xFFFF0000u);
+                v[2] = __uint_as_float(vv[1] << 16);
+                v[3] = __uint_as_float(vv[1] & 0xFFFF0000u);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                r[i] = rv[i];
+                p[i] = alpha * (v[i] * widen(x[cv[i]]));
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int64_t e = e0_64 + i;
+                const bool live = e >= 0 && e < nnz;
+                r[i] = live ? row[e] : -1;
+                p[i] = live ? alpha * (widen(vals[e]) * widen(x[col[e]])) : 0.f;
+            }
+        }
+        // runs inside the lane: the first is kept as the head, the last as the tail, others go out at once
+        const int head_row = r[0];
+        float head_sum = 0.f;
+        bool single = true;  // no row change seen yet: the run in hand is still the first
+        int tail_row = r[0];
+        float tail_sum = p[0];
+#pragma unroll
+        for (int i = 1; i < 4; ++i) {
+            if (r[i] != tail_row) {
+                if (single) {
+                    head_sum = tail_sum;
+                    single = false;
+                } else if (tail_row >= 0) {
+                    unsafeAtomicAdd(y + tail_row, tail_sum);
+                }
+                tail_row = r[i];
+                tail_sum = p[i];
+            } else {
+                tail_sum += p[i];
+            }
+        }
+        // chains of last runs: a lane joins the chain of the lane before it when all its entries have that lane's last row
+        const int prev_tail_row = __shfl_up(tail_row, 1, 64);
+        const int next_head_row = __shfl_down(head_row, 1, 64);
+        const bool follows = lane > 0 && head_row == prev_tail_row;
+        float chain = tail_sum;
+        bool head = !(single && follows);
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
-            const float pp = __shfl_up(p, d, 64);
+            const float cc = __shfl_up(chain, d, 64);
             const int hh = __shfl_up(static_cast<int>(head), d, 64);
             if (lane >= d && !head) {
-                p += pp;
+                chain += cc;
                 head = hh != 0;
             }
         }
-        const int r_next = __shfl_down(r, 1, 64);
-        if (live && (lane == 63 || r_next != r)) unsafeAtomicAdd(y + r, p);
+        const float chain_before = __shfl_up(chain, 1, 64);
+        if (!single && head_row >= 0) unsafeAtomicAdd(y + head_row, follows ? head_sum + chain_before : head_sum);
+        if (tail_row >= 0 && (lane == 63 || next_head_row != tail_row)) unsafeAtomicAdd(y + tail_row, chain);
     }
 }
 
@@ -212,9 +275,12 @@ hipError_t launch_coo_t(int32_t m, int32_t nnz, const int32_t* row, const int32_
     int grid = ceil_div(m, kWG);
     hipLaunchKernelGGL(scale_y_kernel, dim3(grid > 2048 ? 2048 : grid), dim3(kWG), 0, st, y, m, s.beta);
     if (nnz > 0) {
-        grid = ceil_div(nnz, kWG);
+        // the caller's arrays start where they start: whole-vector loads only if all three are aligned as they are
+        const bool vec = reinterpret_cast<uintptr_t>(row) % 16 == 0 && reinterpret_cast<uintptr_t>(col) % 16 == 0 &&
+                         reinterpret_cast<uintptr_t>(vals) % (4 * sizeof(E)) == 0;
+        grid = ceil_div(nnz, 4 * kWG);
         hipLaunchKernelGGL((spmv_coo_kernel<T>), dim3(grid > 8192 ? 8192 : grid), dim3(kWG), 0, st, row, col,
-                           static_cast<const E*>(vals), static_cast<const E*>(x), y, nnz, s.alpha);
+                           static_cast<const E*>(vals), static_cast<const E*>(x), y, nnz, 0, vec ? 1 : 0, s.alpha);
     }
     return hipGetLastError();
 }
@@ -260,14 +326,22 @@ hipError_t launch_scale_y(float* y, int32_t m, float beta, hipStream_t st) {
 hipError_t launch_coo_accumulate(bool bf16, int32_t nnz, const int32_t* row, const int32_t* col, const void* vals,
                                  const void* x, float* y, float alpha, hipStream_t st) {
     if (nnz <= 0) return hipSuccess;
-    int grid = ceil_div(nnz, kWG);
+    // The arrays are stretches of the library's own allocations, all three starting the same number of
+    // entries into theirs: the (up to three) entries before `row` that complete its first aligned
+    // group of four may be read, and are ignored.
+    const int shift = static_cast<int>((reinterpret_cast<uintptr_t>(row) / 4) % 4);
+    const size_t esz = bf16 ? 2 : 4;
+    const bool vec = (reinterpret_cast<uintptr_t>(row) - 4 * shift) % 16 == 0 &&
+                     (reinterpret_cast<uintptr_t>(col) - 4 * shift) % 16 == 0 &&
+                     (reinterpret_cast<uintptr_t>(vals) - esz * shift) % (4 * esz) == 0;
+    int grid = ceil_div(static_cast<int64_t>(nnz) + shift, 4 * kWG);
     if (grid > 8192) grid = 8192;
     if (bf16)
         hipLaunchKernelGGL((spmv_coo_kernel<BF16>), dim3(grid), dim3(kWG), 0, st, row, col, static_cast<const uint16_t*>(vals),
-                           static_cast<const uint16_t*>(x), y, nnz, alpha);
+                           static_cast<const uint16_t*>(x), y, nnz, vec ? shift : 0, vec ? 1 : 0, alpha);
     else
         hipLaunchKernelGGL((spmv_coo_kernel<F32>), dim3(grid), dim3(kWG), 0, st, row, col, static_cast<const float*>(vals),
-                           static_cast<const float*>(x), y, nnz, alpha);
+                           static_cast<const float*>(x), y, nnz, vec ? shift : 0, vec ? 1 : 0, alpha);
     return hipGetLastError();
 }
 
