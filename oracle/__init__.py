@@ -14,7 +14,9 @@ from pathlib import Path
 import numpy as np
 
 _HERE = Path(__file__).resolve().parent
-LIB_PATH = _HERE / "liboracle.so"
+# SPMV_ORACLE_LIB: load that library instead (the mutation check of the pins builds deliberately
+# wrong copies of the sources below into libraries of their own and points the pin tests at them).
+LIB_PATH = Path(os.environ["SPMV_ORACLE_LIB"]) if os.environ.get("SPMV_ORACLE_LIB") else _HERE / "liboracle.so"
 SOURCES = [_HERE / "spmv_oracle.cpp", _HERE / "analysis_oracle.cpp", _HERE / "spmm_oracle.cpp", _HERE / "formats_oracle.cpp"]
 _lib = None
 

@@ -78,6 +78,11 @@ def test_row_stats():
     assert oracle.row_stats(rowptr_of([])) == {"min_len": 0, "max_len": 0, "n_empty": 0}
     assert oracle.row_stats(rowptr_of([4, 0, 9, 0, 2])) == {"min_len": 0, "max_len": 9, "n_empty": 2}
     assert oracle.row_stats(rowptr_of([3, 3])) == {"min_len": 3, "max_len": 3, "n_empty": 0}
+    assert oracle.row_stats(rowptr_of([1, 0, 1, 1, 7])) == {"min_len": 0, "max_len": 7, "n_empty": 1}   # a row of one entry is not empty
+    assert oracle.row_stats(rowptr_of([1, 1])) == {"min_len": 1, "max_len": 1, "n_empty": 0}
+    for lens in RAGGED[1:]:                                    # against numpy's own reductions
+        a = np.asarray(lens)
+        assert oracle.row_stats(rowptr_of(lens)) == {"min_len": int(a.min()), "max_len": int(a.max()), "n_empty": int((a == 0).sum())}
 
 
 # ------------------------------------------------------------------ row blocks

@@ -1,0 +1,102 @@
+"""Are the oracle's pins sharp?  One mistake at a time is planted in a COPY of the oracle's sources (a dropped
+term, a wrong sign, a wrong or transposed index, an off-by-one in a rule), the copy is built into a library of
+its own in a temporary directory, and the pin tests of the touched file are run against it in a child process:
+they must fail.  Nothing here touches the GPU path or the oracle that the other tests use."""
+import os
+import subprocess
+import sys
+from concurrent.futures import ThreadPoolExecutor
+from pathlib import Path
+
+import pytest
+
+import oracle
+
+ROOT = Path(__file__).resolve().parents[1]
+PINS = {"spmv_oracle.cpp": "tests/test_oracle_spmv.py", "analysis_oracle.cpp": "tests/test_oracle_analysis.py",
+        "spmm_oracle.cpp": "tests/test_oracle_spmm.py", "formats_oracle.cpp": "tests/test_oracle_formats.py"}
+
+# (file, text as it stands, text with the mistake, what the mistake is)
+MUTANTS = [
+    ("spmv_oracle.cpp", "acc += p;", "acc -= p;", "products subtracted"),
+    ("spmv_oracle.cpp", "if (beta != 0.0f) r += static_cast<double>(beta) * static_cast<double>(y0[i]);", ";", "beta*y0 dropped"),
+    ("spmv_oracle.cpp", "if (beta != 0.0f) r += static_cast<double>(beta)", "if (beta != 0.0f) r -= static_cast<double>(beta)", "beta*y0 subtracted"),
+    ("spmv_oracle.cpp", "static_cast<double>(x[j])", "static_cast<double>(x[i < n ? i : j])", "x taken at the row index (f32)"),
+    ("spmv_oracle.cpp", "bf16_bits_to_float(x[j])", "bf16_bits_to_float(x[i < n ? i : j])", "x taken at the row index (bf16)"),
+    ("spmv_oracle.cpp", "S += std::fabs(p);", "S += p;", "S without the absolute value"),
+    ("spmv_oracle.cpp", "for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k)", "for (int64_t k = rowptr[i] + 1; k < rowptr[i + 1]; ++k)", "first entry of every row dropped"),
+    ("spmv_oracle.cpp", "for (int64_t k = rowptr[i]; k < rowptr[i + 1]; ++k)", "for (int64_t k = rowptr[i]; k + 1 < rowptr[i + 1]; ++k)", "last entry of every row dropped"),
+    ("spmv_oracle.cpp", "static_cast<uint32_t>(b) << 16", "static_cast<uint32_t>(b) << 15", "bf16 widened by the wrong shift"),
+    ("spmv_oracle.cpp", "double r = static_cast<double>(alpha) * acc;", "double r = acc;", "alpha dropped"),
+    ("spmv_oracle.cpp", "const double p = static_cast<double>(vals[k]) * static_cast<double>(x[j]);", "const double p = vals[k] * x[j];", "product rounded to float"),
+    ("spmv_oracle.cpp", "const int32_t j = colidx[k];", "const int32_t j = colidx[k == rowptr[i] ? k : k - 1];", "column index taken one entry early"),
+    ("analysis_oracle.cpp", "while (cap < len) {", "while (cap <= len) {", "bins off by one at powers of two"),
+    ("analysis_oracle.cpp", "if (len == 0) ++empty;", "if (len <= 1) ++empty;", "rows of one entry counted as empty"),
+    ("analysis_oracle.cpp", "if (held + len > block_nnz) break;", "if (held + len >= block_nnz) break;", "row blocks close one entry early"),
+    ("analysis_oracle.cpp", "if (r - first >= rows_max) break;", "if (r - first > rows_max) break;", "row blocks take one row too many"),
+    ("analysis_oracle.cpp", "if (r == first) ++r;  // a single row that is longer than block_nnz", "if (r == first) r += 2;", "an over-long row swallows its successor"),
+    ("analysis_oracle.cpp", "rowptr[i + 1] > j)", "rowptr[i + 1] >= j)", "merge path moves down instead of right on a tie"),
+    ("analysis_oracle.cpp", "if (step == p * ipc || step == T) {", "if (step == p * ipc + 1 || step == T) {", "merge path diagonals shifted by one"),
+    ("analysis_oracle.cpp", "rank * vec_elems + colidx[k] % vec_elems", "rank + colidx[k] % vec_elems", "window position not scaled by the vector length"),
+    ("analysis_oracle.cpp", "xv_start[total + static_cast<int64_t>(j)] = keys[j] * vec_elems;", "xv_start[total + static_cast<int64_t>(j)] = keys[j];", "x vector start not scaled"),
+    ("analysis_oracle.cpp", "keys.erase(std::unique(keys.begin(), keys.end()), keys.end());", ";", "duplicate x vectors kept"),
+    ("analysis_oracle.cpp", "return 4 * nb * V <= nnz ? 1 : 0;", "return nb * V <= nnz ? 1 : 0;", "window rule without its factor 4"),
+    ("analysis_oracle.cpp", "if (V > max_vectors) return 0;", "if (V >= max_vectors) return 0;", "window rule refuses the largest allowed window"),
+    ("analysis_oracle.cpp", "cb_col[k] = static_cast<int32_t>(colidx[e] - b * width);", "cb_col[k] = static_cast<int32_t>(colidx[e]);", "column not made relative to its block"),
+    ("analysis_oracle.cpp", "cb_src[k] = static_cast<int32_t>(e);", "cb_src[k] = static_cast<int32_t>(e + 1);", "source position off by one"),
+    ("analysis_oracle.cpp", "if (colidx[e] / width == b) {", "if (colidx[e] / width == C - 1 - b) {", "column blocks in reverse order"),
+    ("analysis_oracle.cpp", "while (G < 64 && 16 * G < mean) G *= 2;", "while (G < 64 && 8 * G < mean) G *= 2;", "tile shape from the wrong lane rule"),
+    ("analysis_oracle.cpp", "if (max_len > block_nnz) return 5;", "if (max_len >= block_nnz) return 5;", "plan rule off by one"),
+    ("analysis_oracle.cpp", "while (G < 64 && 8 * static_cast<int64_t>(G) < mean_up) G *= 2;", "while (G < 64 && 8 * static_cast<int64_t>(G) <= mean_up) G *= 2;", "vector lanes off by one"),
+    ("analysis_oracle.cpp", "n > 2 * width && C <= 16", "n >= 2 * width && C <= 16", "column block rule off by one"),
+    ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * ldb + (K - 1 - k)]);", "columns of B reversed"),
+    ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * K + k]);", "leading dimension of B ignored"),
+    ("spmm_oracle.cpp", "if (beta != 0.0f) r += static_cast<double>(beta)", "if (beta != 0.0f) r -= static_cast<double>(beta)", "beta*C subtracted"),
+    ("spmm_oracle.cpp", "S += std::fabs(p);", "S += p;", "S without the absolute value"),
+    ("spmm_oracle.cpp", "return std::min<int64_t>((len + 3) / 4, 64);", "return std::min<int64_t>((len + 3) / 4, 63);", "row order: cap one too low"),
+    ("spmm_oracle.cpp", "return std::min<int64_t>((len + 3) / 4, 64);", "return std::min<int64_t>(len / 4, 64);", "row order: key rounded down"),
+    ("spmm_oracle.cpp", "return key(a) > key(b);", "return key(a) < key(b);", "row order ascending"),
+    ("spmm_oracle.cpp", "t = 16 * b + 4 * q + e;", "t = 16 * b + 4 * e + q;", "packed copy: slots of a lane interleaved"),
+    ("spmm_oracle.cpp", "desc[2 * g + 1] = static_cast<int32_t>((L + 3) / 4);", "desc[2 * g + 1] = static_cast<int32_t>((L + 4) / 4);", "packed copy: one step too many"),
+    ("spmm_oracle.cpp", "blocks += (L + 15) / 16;", "blocks += (L + 16) / 16;", "packed copy: one block too many for rows of 16"),
+    ("spmm_oracle.cpp", "256 * blocks <= 2 * nnz", "256 * blocks <= nnz", "packed copy: size rule without its factor 2"),
+    ("formats_oracle.cpp", "const double p = widen_at(vals, e, dtype) * widen_at(x, col[e], dtype);", "const double p = widen_at(vals, e, dtype) * widen_at(x, row[e] < n ? row[e] : col[e], dtype);", "COO: x taken at the row index"),
+    ("formats_oracle.cpp", "const double p = widen_at(vals, e, dtype) * widen_at(x, j, dtype);", "const double p = widen_at(vals, e, dtype) * widen_at(x, row[e] < n ? row[e] : j, dtype);", "CSC: x taken at the row index"),
+    ("formats_oracle.cpp", "if (j == -1) continue;", "if (j == -1) return 1;", "ELL: padding refused"),
+    ("formats_oracle.cpp", "const int32_t j = col_ids[i * width + s];", "const int32_t j = col_ids[s * m + i];", "ELL: read as column-major"),
+    ("formats_oracle.cpp", "double r = static_cast<double>(alpha) * acc[i];", "double r = acc[i];", "alpha dropped"),
+    ("formats_oracle.cpp", "y_ref[row[e]] += p;\n        S_ref[row[e]] += std::fabs(p);\n    }\n    finish", "y_ref[row[e]] = p;\n        S_ref[row[e]] += std::fabs(p);\n    }\n    finish", "COO: repeated coordinates overwrite"),
+]
+
+
+def build(tmp, tag, mutated_file=None, old=None, new=None):
+    srcs = []
+    for src in oracle.SOURCES:
+        text = src.read_text()
+        if src.name == mutated_file:
+            assert text.count(old) >= 1, (mutated_file, old)
+            text = text.replace(old, new)
+        dst = tmp / f"{tag}_{src.name}"
+        dst.write_text(text)
+        srcs.append(str(dst))
+    lib = tmp / f"lib_{tag}.so"
+    subprocess.run(["g++", "-O1", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off", "-o", str(lib)] + srcs, check=True)
+    return lib
+
+
+def pins_pass(lib, module):
+    env = dict(os.environ, SPMV_ORACLE_LIB=str(lib))
+    r = subprocess.run([sys.executable, "-m", "pytest", module, "-x", "-q", "-p", "no:cacheprovider"], cwd=ROOT, env=env,
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    return r.returncode == 0, r.stdout[-600:]
+
+
+def test_every_planted_mistake_is_caught(tmp_path):
+    with ThreadPoolExecutor(max_workers=6) as pool:
+        control = build(tmp_path, "control")
+        clean = list(pool.map(lambda mod: pins_pass(control, mod), PINS.values()))
+        assert all(ok for ok, _ in clean), [tail for ok, tail in clean if not ok]    # the same build, unchanged, passes
+        libs = list(pool.map(lambda kv: build(tmp_path, f"m{kv[0]}", kv[1][0], kv[1][1], kv[1][2]), enumerate(MUTANTS)))
+        results = list(pool.map(lambda kv: pins_pass(kv[0], PINS[kv[1][0]]), zip(libs, MUTANTS)))
+    survivors = [(m[0], m[3]) for m, (ok, _) in zip(MUTANTS, results) if ok]
+    assert not survivors, f"pins that let a planted mistake through: {survivors}"
