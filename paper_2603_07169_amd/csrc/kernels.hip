@@ -516,8 +516,8 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
 }
 
 // Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
-// keys = colidx >> shift of the block's entries, sorted in LDS (bitonic network over the next
-// power of two), duplicates dropped.  count pass (fill == 0): nv[b] = number of distinct keys.
+// keys = colidx >> shift of the block's entries (those that repeat their predecessor's are left out
+// at once), sorted in LDS (bitonic network over the next power of two), duplicates dropped.  count pass (fill == 0): nv[b] = number of distinct keys.
 // fill pass: xv_start[xv_ptr[b] + j] = xv_pad[b * x_cap + j] = j-th key << shift (the rest of the
 // block's xv_pad slice is -1), and for every entry
 // lidx[k] = rank of its key * 2^shift + colidx[k] mod 2^shift.  A block with more than tile_cap
@@ -532,6 +532,7 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
     __shared__ uint32_t keys[kMaxTileEntries];
     __shared__ uint32_t uniq[kMaxXVectors];
     __shared__ int counts[256];
+    __shared__ int chunk_base[kMaxTileEntries / 64 + 1];
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int k0 = block_nz[b], k1 = block_nz[b + 1];
@@ -544,9 +545,41 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
         }
         return;
     }
+    // Only an entry whose key differs from its predecessor's can bring a new key: those are
+    // compacted into keys[] (order kept), which for rows made of runs of consecutive columns leaves
+    // a fraction of the entries to sort.  Two sweeps over colidx: count per run of 64 entries, place.
+    const int lane = tid & 63, wv = tid >> 6;
+    const int nchunk = (cnt + 63) / 64;  // <= kMaxTileEntries / 64 = 128
+    auto first_of_run = [&](int i, uint32_t* key) {
+        if (i >= cnt) return false;
+        *key = static_cast<uint32_t>(colidx[k0 + i]) >> shift;
+        return i == 0 || (static_cast<uint32_t>(colidx[k0 + i - 1]) >> shift) != *key;
+    };
+    for (int c = wv; c < nchunk; c += 4) {
+        uint32_t key = 0;
+        const unsigned long long mask = __builtin_amdgcn_ballot_w64(first_of_run(c * 64 + lane, &key));
+        if (lane == 0) chunk_base[c] = __popcll(mask);
+    }
+    __syncthreads();
+    int mine = 0, before = 0;
+    if (tid < nchunk) {
+        mine = chunk_base[tid];
+        for (int q = 0; q < tid; ++q) before += chunk_base[q];
+    }
+    __syncthreads();
+    if (tid < nchunk) chunk_base[tid] = before;
+    if (tid == nchunk - 1) chunk_base[nchunk] = before + mine;
+    __syncthreads();
+    for (int c = wv; c < nchunk; c += 4) {
+        uint32_t key = 0;
+        const bool f = first_of_run(c * 64 + lane, &key);
+        const unsigned long long mask = __builtin_amdgcn_ballot_w64(f);
+        if (f) keys[chunk_base[c] + __popcll(mask & ((1ull << lane) - 1ull))] = key;
+    }
+    const int kept = chunk_base[nchunk];
     int P = 256;
-    while (P < cnt) P <<= 1;
-    for (int i = tid; i < P; i += 256) keys[i] = i < cnt ? static_cast<uint32_t>(colidx[k0 + i]) >> shift : 0xFFFFFFFFu;
+    while (P < kept) P <<= 1;
+    for (int i = kept + tid; i < P; i += 256) keys[i] = 0xFFFFFFFFu;
     __syncthreads();
     for (int k = 2; k <= P; k <<= 1)
         for (int j = k >> 1; j > 0; j >>= 1) {
