@@ -12,7 +12,7 @@ SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC /
 HEADERS = [CSRC / "kernels.h", CSRC / "device_common.h", CSRC / "row_phase.h", CSRC / "analysis.h", INCLUDE / "spmv_mi355.h"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-pthread",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",   # keep packed FP32 instructions out
     "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
 ]

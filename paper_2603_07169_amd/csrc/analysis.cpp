@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <climits>
+#include <thread>
 #include <new>
 
 namespace spmv {
@@ -31,6 +32,31 @@ inline int64_t split_rows_on_diagonal(int64_t d, int64_t m, int64_t nnz, const i
             lo = mid + 1;
     }
     return lo;
+}
+
+// Runs fn(t, begin, end) over [0, count) cut into contiguous, ascending pieces, one per thread.  Small
+// inputs run on the calling thread; the passes below are memory-bound, so a handful of threads is enough.
+constexpr int kMaxHostThreads = 8;
+constexpr int64_t kRowsPerThread = int64_t{1} << 17;
+
+inline int host_threads(int64_t count) {
+    const int64_t by_size = count / kRowsPerThread;
+    const int64_t hw = static_cast<int64_t>(std::thread::hardware_concurrency());
+    const int64_t t = std::min<int64_t>({by_size, hw > 0 ? hw : 1, kMaxHostThreads});
+    return static_cast<int>(t < 1 ? 1 : t);
+}
+
+template <typename F>
+void parallel_pieces(int64_t count, int threads, F fn) {
+    if (threads <= 1) {
+        fn(0, int64_t{0}, count);
+        return;
+    }
+    std::vector<std::thread> pool;
+    pool.reserve(static_cast<size_t>(threads));
+    for (int t = 0; t < threads; ++t)
+        pool.emplace_back([=]() { fn(t, count * t / threads, count * (t + 1) / threads); });
+    for (std::thread& th : pool) th.join();
 }
 
 }  // namespace
@@ -82,46 +108,78 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
         if (params.rows_max == 0) params.rows_max = rm;
     }
 
-    // ---- structure check + statistics + bin histogram, one sweep
+    // ---- structure check + statistics + bin histogram, one sweep (per thread: its own rows and counts)
     if (rowptr[0] != 0 || rowptr[m] != nnz) return SPMV_ERR_BAD_STRUCTURE;
+    const int threads = host_threads(m);
+    struct Part {
+        int64_t min_len = INT64_MAX, max_len = 0, n_empty = 0;
+        bool bad = false;
+        int32_t hist[SPMV_NUM_BINS] = {};
+    };
+    std::vector<Part> parts(static_cast<size_t>(threads));
+    parallel_pieces(m, threads, [&](int t, int64_t lo, int64_t hi) {
+        Part& q = parts[static_cast<size_t>(t)];
+        for (int64_t i = lo; i < hi; ++i) {
+            const int64_t len = static_cast<int64_t>(rowptr[i + 1]) - rowptr[i];
+            if (len < 0) {
+                q.bad = true;
+                return;
+            }
+            q.min_len = std::min(q.min_len, len);
+            q.max_len = std::max(q.max_len, len);
+            q.n_empty += (len == 0);
+            q.hist[length_bin(static_cast<uint32_t>(len))] += 1;
+        }
+    });
     int64_t min_len = m > 0 ? INT64_MAX : 0, max_len = 0, n_empty = 0;
-    for (int64_t i = 0; i < m; ++i) {
-        const int64_t len = static_cast<int64_t>(rowptr[i + 1]) - rowptr[i];
-        if (len < 0) return SPMV_ERR_BAD_STRUCTURE;
-        min_len = std::min(min_len, len);
-        max_len = std::max(max_len, len);
-        n_empty += (len == 0);
-        a.bin_count[length_bin(static_cast<uint32_t>(len))] += 1;
+    for (const Part& q : parts) {
+        if (q.bad) return SPMV_ERR_BAD_STRUCTURE;
+        min_len = std::min(min_len, q.min_len);
+        max_len = std::max(max_len, q.max_len);
+        n_empty += q.n_empty;
+        for (int b = 0; b < SPMV_NUM_BINS; ++b) a.bin_count[b] += q.hist[b];
     }
 
-    // ---- stable counting sort of the row ids by bin
+    // ---- stable counting sort of the row ids by bin: thread t writes behind the rows of the threads before it
     for (int b = 0; b < SPMV_NUM_BINS; ++b) a.bin_offset[b + 1] = a.bin_offset[b] + a.bin_count[b];
     a.bin_rows.resize(static_cast<size_t>(m));
     {
-        int32_t cursor[SPMV_NUM_BINS];
-        std::copy(a.bin_offset, a.bin_offset + SPMV_NUM_BINS, cursor);
-        for (int64_t i = 0; i < m; ++i) {
-            const uint32_t len = static_cast<uint32_t>(rowptr[i + 1] - rowptr[i]);
-            a.bin_rows[static_cast<size_t>(cursor[length_bin(len)]++)] = static_cast<int32_t>(i);
+        std::vector<int32_t> first(static_cast<size_t>(threads) * SPMV_NUM_BINS);
+        for (int b = 0; b < SPMV_NUM_BINS; ++b) {
+            int32_t at = a.bin_offset[b];
+            for (int t = 0; t < threads; ++t) {
+                first[static_cast<size_t>(t) * SPMV_NUM_BINS + b] = at;
+                at += parts[static_cast<size_t>(t)].hist[b];
+            }
         }
+        int32_t* bin_rows = a.bin_rows.data();
+        parallel_pieces(m, threads, [&, bin_rows](int t, int64_t lo, int64_t hi) {
+            int32_t cursor[SPMV_NUM_BINS];
+            std::copy(first.begin() + static_cast<size_t>(t) * SPMV_NUM_BINS,
+                      first.begin() + static_cast<size_t>(t + 1) * SPMV_NUM_BINS, cursor);
+            for (int64_t i = lo; i < hi; ++i) {
+                const uint32_t len = static_cast<uint32_t>(rowptr[i + 1] - rowptr[i]);
+                bin_rows[cursor[length_bin(len)]++] = static_cast<int32_t>(i);
+            }
+        });
     }
 
-    // ---- greedy row blocks: close the open block when the next row would overflow it
+    // ---- greedy row blocks.  The block opened at row s takes rows while it has fewer than rows_max of
+    // them and stays within block_nnz entries, i.e. it ends at the last r with r - s <= rows_max and
+    // rowptr[r] - rowptr[s] <= block_nnz (found by bisection: rowptr does not decrease), and a row that
+    // alone exceeds block_nnz stands alone.
     a.row_blocks.clear();
     a.row_blocks.push_back(0);
-    {
-        int64_t open_first = 0;  // first row of the open block
-        for (int64_t i = 0; i < m; ++i) {
-            const int64_t with_row = static_cast<int64_t>(rowptr[i + 1]) - rowptr[open_first];
-            const bool fits = (i - open_first) < params.rows_max && with_row <= params.block_nnz;
-            if (!fits && i > open_first) {
-                a.row_blocks.push_back(static_cast<int32_t>(i));
-                open_first = i;
-            }
-            // A row that alone exceeds block_nnz opens a block at i and is cut off by the next row:
-            // with_row for row i+1 is then > block_nnz as well, so the block closes at i+1.
-        }
-        if (m > 0) a.row_blocks.push_back(static_cast<int32_t>(m));
+    for (int64_t s = 0; s < m;) {
+        const int64_t limit = static_cast<int64_t>(rowptr[s]) + params.block_nnz;
+        const int64_t cap = std::min<int64_t>(m, s + params.rows_max);
+        // first index in (s, cap] whose offset exceeds the limit, or cap + 1
+        const int32_t* past = std::upper_bound(rowptr + s + 1, rowptr + cap + 1, limit,
+                                               [](int64_t v, int32_t off) { return v < static_cast<int64_t>(off); });
+        int64_t end = (past - rowptr) - 1;
+        if (end == s) end = s + 1;
+        a.row_blocks.push_back(static_cast<int32_t>(end));
+        s = end;
     }
 
     // ---- merge-path splits by bisection on each chunk's diagonal
@@ -130,11 +188,17 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
     const int64_t P = (T + ipc - 1) / ipc;
     a.mp_row.resize(static_cast<size_t>(P + 1));
     a.mp_nz.resize(static_cast<size_t>(P + 1));
-    for (int64_t p = 0; p <= P; ++p) {
-        const int64_t d = std::min(p * ipc, T);
-        const int64_t i = split_rows_on_diagonal(d, m, nnz, rowptr);
-        a.mp_row[static_cast<size_t>(p)] = static_cast<int32_t>(i);
-        a.mp_nz[static_cast<size_t>(p)] = static_cast<int32_t>(d - i);
+    {
+        int32_t* mp_row = a.mp_row.data();
+        int32_t* mp_nz = a.mp_nz.data();
+        parallel_pieces(P + 1, host_threads((P + 1) * 16), [=](int, int64_t lo, int64_t hi) {
+            for (int64_t p = lo; p < hi; ++p) {
+                const int64_t d = std::min(p * ipc, T);
+                const int64_t i = split_rows_on_diagonal(d, m, nnz, rowptr);
+                mp_row[p] = static_cast<int32_t>(i);
+                mp_nz[p] = static_cast<int32_t>(d - i);
+            }
+        });
     }
 
     // ---- plan

@@ -121,6 +121,18 @@ def test_spmm_row_order_matches_the_oracle():
     assert s.spmv_analyze_host(3, 4, 6, rp, dict(reserved=1))[0] == s.SPMV_ERR_INVALID_ARG
 
 
+def test_large_row_counts_take_the_threaded_passes_and_still_match_the_oracle():
+    """From 2^18 rows on the host analysis splits its passes over threads; results must not depend on that."""
+    rng = np.random.default_rng(77)
+    for m, params in ((300_000, {}), (1_100_000, dict(block_nnz=100, rows_max=7, items_per_chunk=64))):
+        lens = np.where(rng.random(m) < 0.3, 0, rng.integers(0, 60, m))
+        lens[rng.integers(0, m, 5)] = 9000
+        compare_with_oracle(rowptr_of(lens), 10_000, params)
+    bad = rowptr_of(np.full(400_000, 3))
+    bad[350_000] -= 10                              # a decreasing offset deep inside a later thread's rows
+    assert s.spmv_analyze_host(400_000, 10, int(bad[-1]), bad)[0] == s.SPMV_ERR_BAD_STRUCTURE
+
+
 def test_analyze_rejects_malformed_rowptr():
     assert s.spmv_analyze_host(3, 4, 6, np.array([1, 2, 3, 6], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE
     assert s.spmv_analyze_host(3, 4, 6, np.array([0, 4, 3, 6], np.int32))[0] == s.SPMV_ERR_BAD_STRUCTURE
