@@ -3,6 +3,7 @@
 
 #include <algorithm>
 #include <climits>
+#include <system_error>
 #include <thread>
 #include <new>
 
@@ -54,8 +55,14 @@ void parallel_pieces(int64_t count, int threads, F fn) {
     }
     std::vector<std::thread> pool;
     pool.reserve(static_cast<size_t>(threads));
-    for (int t = 0; t < threads; ++t)
-        pool.emplace_back([=]() { fn(t, count * t / threads, count * (t + 1) / threads); });
+    int started = 0;
+    try {
+        for (; started < threads; ++started)
+            pool.emplace_back([=]() { fn(started, count * started / threads, count * (started + 1) / threads); });
+    } catch (const std::system_error&) {
+        // no more threads to be had: the pieces not handed out yet are done here, in order
+    }
+    for (int t = started; t < threads; ++t) fn(t, count * t / threads, count * (t + 1) / threads);
     for (std::thread& th : pool) th.join();
 }
 
