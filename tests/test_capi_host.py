@@ -195,3 +195,33 @@ def test_host_analysis_equals_oracle_on_full_configs(k):
         assert info.num_row_blocks == 4096 and info.plan == s.SPMV_PLAN_ADAPTIVE
     if k == 4:
         assert info.plan == s.SPMV_PLAN_MERGE
+
+
+def test_struct_layouts_of_the_binding_match_the_header(tmp_path):
+    """The header compiled as plain C (it must be one) reports size and field offsets of every struct that crosses
+    the boundary; the ctypes mirrors must agree field by field."""
+    import subprocess
+    structs = {"spmv_analyze_params_t": s.spmv.spmv_analyze_params_t, "spmv_analysis_info_t": s.spmv.spmv_analysis_info_t,
+               "spmv_analysis_host_t": s.spmv.spmv_analysis_host_t}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "spmv_mi355.h"', 'int main(void) {']
+    for name, cls in structs.items():
+        lines.append(f'  printf("{name} size %zu\\n", sizeof({name}));')
+        for field, _ in cls._fields_:
+            lines.append(f'  printf("{name} {field} %zu\\n", offsetof({name}, {field}));')
+    lines += ['  printf("SPMV_MAX_SIZE %lld\\n", (long long)SPMV_MAX_SIZE);', '  printf("SPMV_SPMM_WINDOW %d\\n", SPMV_SPMM_WINDOW);',
+              '  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", f"-I{ROOT / 'include'}", str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, stdout=subprocess.PIPE, text=True).stdout.split("\n")
+    seen = {}
+    for line in filter(None, out):
+        parts = line.split()
+        seen[tuple(parts[:-1])] = int(parts[-1])
+    for name, cls in structs.items():
+        assert seen[(name, "size")] == C.sizeof(cls), name
+        for field, _ in cls._fields_:
+            assert seen[(name, field)] == getattr(cls, field).offset, (name, field)
+        assert len([k for k in seen if k[0] == name]) == len(cls._fields_) + 1
+    assert seen[("SPMV_MAX_SIZE",)] == s.SPMV_MAX_SIZE and seen[("SPMV_SPMM_WINDOW",)] == 4096
