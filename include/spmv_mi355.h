@@ -17,7 +17,8 @@
  *     exceed SPMV_MAX_SIZE = 2^31 - 2^22: index arithmetic in the kernels is 32-bit, and the
  *     margin keeps an index plus one grid stride inside int32.
  *   - Every array argument of create/run is a DEVICE pointer, BORROWED: the caller owns the
- *     memory and must keep rowptr/colidx/vals alive and unchanged until spmv_destroy().
+ *     memory and must keep rowptr/colidx/vals alive and unchanged until spmv_destroy()
+ *     (vals may be changed in place if spmv_csr_refresh_values() is called before the next run).
  *     The library owns only the metadata it allocates in spmv_csr_analyze().
  *   - Column indices inside a row may be in any order and may repeat (repeats add up).
  *   - Every function returns a status; nothing throws, aborts or prints.
@@ -245,6 +246,14 @@ spmv_status_t spmv_csc_run(int64_t m, int64_t n, int64_t nnz, const int32_t* col
                            void* stream);
 spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* col_ids, const void* vals,
                            spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta, void* stream);
+
+/* Brings the library's own copies of the matrix values up to date after the caller has changed vals
+ * in place (same structure, new numbers: the case of a nonlinear or time-stepping solver).  Only two
+ * things hold such copies: the COLBLOCK plan (values regrouped by column blocks) and the packed copy of
+ * the sparse-times-dense product; with neither, this does nothing.  Enqueues on `stream`: no
+ * allocation, no copy to the host, no synchronisation.  rowptr and colidx must be unchanged.
+ * Errors: INVALID_ARG (null handle), NOT_ANALYZED, HIP. */
+spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream);
 
 /* Frees the handle and the library-owned device metadata.  spmv_destroy(NULL) is OK. */
 spmv_status_t spmv_destroy(spmv_handle_t h);

@@ -523,6 +523,19 @@ spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* c
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
 
+spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream) {
+    if (!h) return SPMV_ERR_INVALID_ARG;
+    if (!h->analyzed) return SPMV_ERR_NOT_ANALYZED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const spmv::MatrixView A = view_of(h);
+    hipError_t e = hipSuccess;
+    if (h->info.plan == SPMV_PLAN_COLBLOCK) e = spmv::launch_column_block_values(A, h->d_cb_src, h->d_cb_vals, st);
+    if (e == hipSuccess && h->info.spmm_prepared == 2)
+        e = spmv::launch_spmm_pack(A, h->d_spmm_rows, h->d_spmm_desc, static_cast<int32_t>((h->m + 15) / 16),
+                                   h->info.spmm_col_bytes == 2, h->d_spmm_col, h->d_spmm_val, st);
+    return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
+}
+
 spmv_status_t spmv_destroy(spmv_handle_t h) {
     if (!h) return SPMV_OK;
     free_metadata(h);

@@ -74,6 +74,13 @@ __global__ __launch_bounds__(64) void cb_tile_kernel(const int32_t* __restrict__
     }
 }
 
+template <typename E>
+__global__ __launch_bounds__(kWG) void cb_values_kernel(const E* __restrict__ vals, const int32_t* __restrict__ cb_src,
+                                                        E* __restrict__ cb_vals, int nnz) {
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; k < nnz; k += static_cast<int64_t>(gridDim.x) * kWG)
+        cb_vals[k] = vals[cb_src[k]];
+}
+
 }  // namespace
 
 int32_t column_block_tiles(int32_t nnz) { return ceil_div(nnz, kCbTile); }
@@ -94,6 +101,19 @@ hipError_t launch_column_block_scatter(const MatrixView& A, int shift, int C, co
     if (C > kMaxColBlocks) return hipErrorInvalidValue;
     hipLaunchKernelGGL(cb_tile_kernel<true>, dim3(ntiles), dim3(64), 0, st, A.rowptr, A.colidx, A.vals, A.bf16 ? 2 : 4, A.m,
                        A.nnz, shift, C, ntiles, nullptr, tile_base, cb_row, cb_col, cb_src, cb_vals);
+    return hipGetLastError();
+}
+
+hipError_t launch_column_block_values(const MatrixView& A, const int32_t* cb_src, void* cb_vals, hipStream_t st) {
+    if (A.nnz <= 0) return hipSuccess;
+    int grid = ceil_div(A.nnz, kWG);
+    if (grid > 8192) grid = 8192;
+    if (A.bf16)
+        hipLaunchKernelGGL(cb_values_kernel<uint16_t>, dim3(grid), dim3(kWG), 0, st, static_cast<const uint16_t*>(A.vals), cb_src,
+                           static_cast<uint16_t*>(cb_vals), A.nnz);
+    else
+        hipLaunchKernelGGL(cb_values_kernel<float>, dim3(grid), dim3(kWG), 0, st, static_cast<const float*>(A.vals), cb_src,
+                           static_cast<float*>(cb_vals), A.nnz);
     return hipGetLastError();
 }
 

@@ -104,6 +104,8 @@ int32_t column_block_tiles(int32_t nnz);
 hipError_t launch_column_block_count(const MatrixView& A, int shift, int C, int32_t* tile_counts, hipStream_t st);
 hipError_t launch_column_block_scatter(const MatrixView& A, int shift, int C, const int32_t* tile_base, int32_t* cb_row,
                                        int32_t* cb_col, int32_t* cb_src, void* cb_vals, hipStream_t st);
+// cb_vals[k] = vals[cb_src[k]] for the nnz regrouped entries (the caller's values may have changed).
+hipError_t launch_column_block_values(const MatrixView& A, const int32_t* cb_src, void* cb_vals, hipStream_t st);
 
 // Cross-lane reduction self-check on one wavefront.  in: device float[64], lane l contributes in[l].
 // out: device float[14*64]; out[gi*64 + l] = sum over lane l's aligned group of G = 2^gi lanes,

@@ -25,7 +25,7 @@ SPMV_MAX_X_VECTORS = 1024
 SPMV_MAX_SIZE = 2 ** 31 - 2 ** 22
 
 EXPORTS = [
-    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmm_csr_run", "spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_csr_refresh_values", "spmm_csr_run", "spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_destroy", "spmv_csr_get_analysis_info",
     "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce", "spmv_csr_main_kernel_name",
     "spmv_status_string", "spmv_last_hip_error",
 ]
@@ -90,12 +90,13 @@ def _load():
     for name in ("spmv_coo_run", "spmv_csc_run", "spmv_ell_run"):
         getattr(lib, name).restype = C.c_int
     lib.spmv_destroy.argtypes = [vp]
+    lib.spmv_csr_refresh_values.argtypes = [vp, vp]
     lib.spmv_csr_get_analysis_info.argtypes = [vp, C.POINTER(spmv_analysis_info_t)]
     lib.spmv_csr_get_analysis.argtypes = [vp, C.POINTER(spmv_analysis_host_t)]
     lib.spmv_analyze_host.argtypes = [i64, i64, i64, vp, C.POINTER(spmv_analyze_params_t),
                                       C.POINTER(spmv_analysis_info_t), C.POINTER(spmv_analysis_host_t)]
     lib.spmv_selftest_reduce.argtypes = [vp, vp, vp]
-    for name in ("spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+    for name in ("spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_csr_refresh_values", "spmv_destroy", "spmv_csr_get_analysis_info",
                  "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce"):
         getattr(lib, name).restype = C.c_int
     lib.spmv_csr_main_kernel_name.argtypes = [vp]
@@ -158,6 +159,10 @@ def spmv_csc_run(m, n, nnz, col_offsets, row_indices, vals, dtype, x, y, alpha, 
 
 def spmv_ell_run(m, n, width, col_ids, vals, dtype, x, y, alpha, beta, stream=None):
     return _load().spmv_ell_run(m, n, width, col_ids, vals, dtype, x, y, alpha, beta, stream)
+
+
+def spmv_csr_refresh_values(handle, stream=None):
+    return _load().spmv_csr_refresh_values(handle, stream)
 
 
 def spmv_destroy(handle):
@@ -253,6 +258,9 @@ class CsrMatrix:
     def run(self, x_t, y_t, alpha=1.0, beta=0.0, stream=None):
         check(spmv_csr_run(self.handle, x_t.data_ptr() if x_t is not None else None, y_t.data_ptr(), alpha, beta,
                            stream), "spmv_csr_run")
+
+    def refresh_values(self, stream=None):
+        check(spmv_csr_refresh_values(self.handle, stream), "spmv_csr_refresh_values")
 
     def spmm(self, B_t, C_t, alpha=1.0, beta=0.0, stream=None):
         """C_t <- alpha*A*B_t + beta*C_t for 2-D row-major torch tensors (column slices allowed)."""

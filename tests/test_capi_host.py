@@ -59,6 +59,8 @@ def test_create_argument_errors():
     assert ok(4, 4, 8, A, A, A + 2, s.SPMV_BF16) == s.SPMV_OK
     st, h = s.spmv_csr_create(4, 4, 8, A, A, A, 0)
     assert s.spmv_csr_run(h, A, A, 1.0, 0.0) == s.SPMV_ERR_NOT_ANALYZED
+    assert s.spmv_csr_refresh_values(h) == s.SPMV_ERR_NOT_ANALYZED
+    assert s.spmv_csr_refresh_values(None) == s.SPMV_ERR_INVALID_ARG
     assert s.spmv_csr_get_analysis_info(h)[0] == s.SPMV_ERR_NOT_ANALYZED
     assert s.spmv_csr_main_kernel_name(h) == ""
     assert s.spmv_destroy(h) == s.SPMV_OK

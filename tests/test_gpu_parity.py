@@ -379,3 +379,26 @@ def test_seeded_random_shapes_and_parameters(seed):
         A = d.matrix(params)
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, what=str(params))
         A.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_values_changed_in_place_are_picked_up_after_refresh(dtype):
+    """Same structure, new numbers: every plan must give the new product once spmv_csr_refresh_values() has run
+    (the plans that read vals directly give it anyway; COLBLOCK holds a regrouped copy)."""
+    p = w.powerlaw(30000, dtype=dtype, beta=0.5)
+    d = DeviceProblem(p)
+    rng = np.random.default_rng(3)
+    new_vals = rng.permutation(p.vals)                                       # same bit patterns, shuffled
+    p2 = w.CsrProblem(p.name, p.dtype, p.m, p.n, p.rowptr, p.colidx, new_vals, p.x, p.y0, p.alpha, p.beta)
+    y_old, S_old = reference(p)
+    y_new, S_new = reference(p2)
+    for plan in ALL_PLANS:
+        log("case refresh", s.PLAN_NAMES[plan], dtype)
+        d.vals.copy_(to_dev(p.vals))
+        A = d.matrix(plan_params(plan))
+        assert_close(p, d.run(A), y_old, S_old, p.alpha, p.beta, what="before")
+        d.vals.copy_(to_dev(new_vals))
+        A.refresh_values()
+        assert_close(p2, d.run(A), y_new, S_new, p.alpha, p.beta, what="after " + s.PLAN_NAMES[plan])
+        A.close()
+

@@ -167,3 +167,25 @@ def test_paper_shape_2_16_sampled_rows():
     got = Ct[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - C_ref) <= TOL * S)
     A.close()
+
+
+def test_packed_copy_follows_values_after_refresh():
+    p = w.density_random(1 << 12, 2048, 0.01)
+    K = 32
+    B = rand((p.n, K), 5)
+    d = DeviceProblem(p)
+    A = d.matrix(dict(prepare_spmm=1))
+    assert A.info.spmm_prepared == 2
+    Bt = torch.from_numpy(B).cuda()
+    Ct = torch.empty(p.m, K, dtype=torch.float32, device="cuda")
+    new_vals = np.random.default_rng(4).permutation(p.vals)
+    for vals, refresh in ((p.vals, False), (new_vals, True)):
+        d.vals.copy_(to_dev(vals))
+        if refresh:
+            A.refresh_values()
+        A.spmm(Bt, Ct)
+        torch.cuda.synchronize()
+        C_ref, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, vals, B)
+        assert np.all(np.abs(Ct.cpu().numpy() - C_ref) <= TOL * S), refresh
+    A.close()
+
