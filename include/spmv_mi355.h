@@ -64,8 +64,11 @@ typedef enum {
     SPMV_PLAN_MERGE = 5,    /* equal-work merge-path chunks + carry fix-up                      */
     SPMV_PLAN_WINDOWED = 6, /* ADAPTIVE row blocks whose x values are served from a per-block
                                window in LDS, entries addressed by 16-bit window positions      */
-    SPMV_PLAN_COLBLOCK = 7  /* entries regrouped by blocks of columns (one 4 MiB stretch of x per
+    SPMV_PLAN_COLBLOCK = 7, /* entries regrouped by blocks of columns (one 4 MiB stretch of x per
                                block), each block multiplied in coordinate form with atomics    */
+    SPMV_PLAN_TWOPHASE = 8  /* two passes, neither gathering from memory: products by column block
+                               with the block of x in LDS, then row sums by merge-path chunk with
+                               the products dropped into LDS at their CSR positions             */
 } spmv_plan_t;
 
 #define SPMV_MAX_X_VECTORS 1024 /* most 16-byte x vectors in one row block's window */
@@ -102,6 +105,14 @@ typedef struct {
     int32_t spmm_prepared;             /* prepare_spmm: 0 not asked for, 1 spmm_rows built, 2 the packed copy as well */
     int32_t spmm_col_bytes;            /* packed copy: bytes per column number (2 while n <= 32768, else 4); 0 without it */
     int64_t spmm_num_blocks;           /* packed copy: blocks of 16 rows x 16 entries; 0 without it */
+    /* TWOPHASE plan (all 0 otherwise): */
+    int64_t tp_slots;                  /* S: padded entries (a multiple of 4)                        */
+    int32_t tp_col_shift;              /* column blocks of 2^tp_col_shift columns                    */
+    int32_t tp_items;                  /* merge-path steps per chunk of the reduce pass              */
+    int32_t tp_num_col_blocks;         /* C2                                                          */
+    int32_t tp_num_chunks;             /* P2: tp_row / tp_nz hold P2+1 entries                        */
+    int32_t tp_num_pieces;             /* Q: workgroups of the multiply pass                          */
+    int32_t tp_reserved;               /* 0                                                           */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -124,6 +135,16 @@ typedef struct {
     int32_t* cb_row;     /* [nnz]  row of every regrouped entry                      */
     int32_t* cb_col;     /* [nnz]  its column minus the block's first column         */
     int32_t* cb_src;     /* [nnz]  its position in the caller's colidx / vals        */
+    /* TWOPHASE plan only (skipped otherwise): */
+    int32_t* tp_row;     /* [P2+1] rows finished at each split of the reduce pass     */
+    int32_t* tp_nz;      /* [P2+1] entries taken at each split                        */
+    int32_t* tp_piece_c; /* [Q]    column block of each piece of the multiply pass    */
+    int32_t* tp_piece_g; /* [Q+1]  first group of four slots of each piece            */
+    int32_t* tp_chunk_g; /* [P2+1] first group of each chunk in the reduce order      */
+    uint16_t* tp_col;    /* [S]    multiply order: column within the block            */
+    int32_t* tp_src;     /* [S]    multiply order: position in colidx / vals, -1 pad  */
+    int32_t* tp_dst;     /* [S/4]  reduce-order group fed by each multiply-order group */
+    uint16_t* tp_pos;    /* [S]    reduce order: CSR position within the chunk        */
     /* With prepare_spmm only (skipped otherwise): */
     int32_t* spmm_rows;  /* [m]    inside each window of SPMV_SPMM_WINDOW consecutive rows:
                             row ids by decreasing min(ceil(len / 4), 64), ties ascending */
@@ -177,8 +198,27 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     are at most 16 blocks and nnz >= 2^22: x then no longer fits the L2s and the row-wise
  *     kernels would fetch a cache line per entry.  run() multiplies block after block with
  *     float atomics into y: results are reproducible to rounding, not bit for bit.  The copy is
- *     taken at analyze time: changing vals afterwards needs a new analyze.  A forced COLBLOCK
+ *     taken at analyze time (spmv_csr_refresh_values() renews it).  A forced COLBLOCK
  *     plan fails with UNSUPPORTED when there would be more than 16 blocks.
+ *   - the two-pass layout (plan TWOPHASE, or plan AUTO where the rule below holds; built on the
+ *     device).  Columns are cut into C2 blocks of 2^tp_col_shift (= 16384) columns; the CSR entry
+ *     list is cut by merge-path splits every tp_items (= 8192) steps into P2 chunks (tp_row /
+ *     tp_nz, defined like mp_row / mp_nz).  Tile (c, p) = the entries of column block c in chunk
+ *     p, in CSR order, padded to a multiple of four slots.  The multiply order lists the tiles by
+ *     (c, p), the reduce order by (p, c); S slots each.  Per slot of the multiply order: tp_col
+ *     (column - c * 2^tp_col_shift; padding: 2^tp_col_shift), tp_src (position k in colidx / vals;
+ *     padding: -1) and a copy of the value (padding: 0); per group of four slots tp_dst, the
+ *     group's number in the reduce order.  Per slot of the reduce order: tp_pos = k - tp_nz[p]
+ *     (padding: 0xFFFF).  Column block c's groups are cut into pieces of at most 8192 groups
+ *     (tp_piece_c, tp_piece_g; pieces are contiguous, tp_piece_g[Q] = S/4); tp_chunk_g[p] = first
+ *     group of chunk p in the reduce order.  run() multiplies piece by piece with the block of x
+ *     in LDS and writes the products to a scratch array of S floats owned by the handle (runs of
+ *     one handle with this plan must therefore not overlap), then sums chunk by chunk; sums are
+ *     taken in a fixed order, so results are reproducible bit for bit.  AUTO picks TWOPHASE ahead
+ *     of COLBLOCK when n > 2 W (W as above), nnz >= 2^22, C2 * P2 <= 2^22 and 8 * C2 * P2 <= nnz
+ *     (tiles of eight entries or more on average).  A forced TWOPHASE plan fails with UNSUPPORTED
+ *     when C2 > 65535, C2 * P2 > 2^22 or S > SPMV_MAX_SIZE; with m == 0 or nnz == 0 it runs as
+ *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
  *   - with prepare_spmm = 1 (SPMV_F32 handles; UNSUPPORTED on bf16 ones): spmm_rows.  The rows
  *     are cut into windows of SPMV_SPMM_WINDOW consecutive rows; inside a window the row ids are
  *     sorted by decreasing key(len) = min(ceil(len / 4), 64), rows of equal key in ascending

@@ -256,4 +256,109 @@ int32_t oracle_column_block_choice(int64_t n, int64_t nnz, int32_t elem_bytes, i
     return ((plan == 4 || plan == 5) && n > 2 * width && C <= 16 && nnz >= (int64_t{1} << 22)) ? 1 : 0;
 }
 
+// ---- the two-pass layout ---------------------------------------------------------------
+// Column blocks of 2^shift columns (C of them); chunks = the stretches of the CSR entry list
+// between consecutive merge-path splits taken every `items` steps (P of them).  Tile (c, p) =
+// the entries of column block c in chunk p, in CSR order, padded to a multiple of four slots.
+// Multiply order: tiles by (c, p); reduce order: tiles by (p, c).  Sizes first: S = padded slots,
+// Q = pieces (every column block's groups of four slots cut into runs of at most piece_groups).
+void oracle_two_phase_sizes(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int32_t shift, int32_t items,
+                            int32_t piece_groups, int64_t* S, int64_t* Q, int64_t* P_out, int64_t* C_out) {
+    const int64_t nnz = rowptr[m];
+    const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
+    const int64_t P = (m + nnz + items - 1) / items;
+    std::vector<int32_t> sr(static_cast<size_t>(P + 1)), sz(static_cast<size_t>(P + 1));
+    oracle_merge_path(m, nnz, rowptr, items, sr.data(), sz.data());
+    std::vector<int64_t> cnt(static_cast<size_t>(C * P), 0);
+    int64_t p = 0;
+    for (int64_t k = 0; k < nnz; ++k) {
+        while (sz[static_cast<size_t>(p + 1)] <= k) ++p;  // the chunk whose stretch holds entry k
+        ++cnt[static_cast<size_t>((colidx[k] >> shift) * P + p)];
+    }
+    int64_t slots = 0, pieces = 0;
+    for (int64_t c = 0; c < C; ++c) {
+        int64_t groups = 0;
+        for (int64_t q = 0; q < P; ++q) groups += (cnt[static_cast<size_t>(c * P + q)] + 3) / 4;
+        slots += 4 * groups;
+        pieces += (groups + piece_groups - 1) / piece_groups;
+    }
+    *S = slots;
+    *Q = pieces;
+    *P_out = P;
+    *C_out = C;
+}
+
+// Fills tp_row[P+1], tp_nz[P+1], piece_c[Q], piece_g[Q+1], chunk_g[P+1], col[S], src[S], dst[S/4], pos[S].
+void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int32_t shift, int32_t items,
+                             int32_t piece_groups, int32_t* tp_row, int32_t* tp_nz, int32_t* piece_c, int32_t* piece_g,
+                             int32_t* chunk_g, uint16_t* col, int32_t* src, int32_t* dst, uint16_t* pos) {
+    const int64_t nnz = rowptr[m];
+    const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
+    const int64_t P = oracle_merge_path(m, nnz, rowptr, items, tp_row, tp_nz);
+    std::vector<int64_t> cnt(static_cast<size_t>(C * P), 0), start1(static_cast<size_t>(C * P)), start2(static_cast<size_t>(C * P));
+    std::vector<int64_t> chunk_of(static_cast<size_t>(nnz));
+    int64_t p = 0;
+    for (int64_t k = 0; k < nnz; ++k) {
+        while (tp_nz[p + 1] <= k) ++p;
+        chunk_of[static_cast<size_t>(k)] = p;
+        ++cnt[static_cast<size_t>((colidx[k] >> shift) * P + p)];
+    }
+    // where every tile starts in the two orders, and the pieces
+    int64_t slot = 0, q = 0;
+    for (int64_t c = 0; c < C; ++c) {
+        const int64_t block_first_group = slot / 4;
+        for (int64_t pp = 0; pp < P; ++pp) {
+            start1[static_cast<size_t>(c * P + pp)] = slot;
+            slot += (cnt[static_cast<size_t>(c * P + pp)] + 3) / 4 * 4;
+        }
+        for (int64_t g = block_first_group; g < slot / 4; g += piece_groups) {
+            piece_c[q] = static_cast<int32_t>(c);
+            piece_g[q] = static_cast<int32_t>(g);
+            ++q;
+        }
+    }
+    const int64_t S = slot;
+    piece_g[q] = static_cast<int32_t>(S / 4);
+    slot = 0;
+    for (int64_t pp = 0; pp < P; ++pp) {
+        chunk_g[pp] = static_cast<int32_t>(slot / 4);
+        for (int64_t c = 0; c < C; ++c) {
+            start2[static_cast<size_t>(c * P + pp)] = slot;
+            slot += (cnt[static_cast<size_t>(c * P + pp)] + 3) / 4 * 4;
+        }
+    }
+    chunk_g[P] = static_cast<int32_t>(slot / 4);
+    // padding everywhere, then the entries in CSR order, each to the next free slot of its tile
+    for (int64_t s = 0; s < S; ++s) {
+        col[s] = static_cast<uint16_t>(1u << shift);
+        src[s] = -1;
+        pos[s] = 0xFFFF;
+    }
+    std::vector<int64_t> used(static_cast<size_t>(C * P), 0);
+    for (int64_t k = 0; k < nnz; ++k) {
+        const int64_t c = colidx[k] >> shift;
+        const int64_t pp = chunk_of[static_cast<size_t>(k)];
+        const size_t t = static_cast<size_t>(c * P + pp);
+        const int64_t o = used[t]++;
+        const int64_t s1 = start1[t] + o, s2 = start2[t] + o;
+        col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));
+        src[s1] = static_cast<int32_t>(k);
+        pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);
+        if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s2 / 4);
+    }
+}
+
+// AUTO takes the two-pass plan (ahead of the column-blocked one) when x is spread over more than two
+// column blocks of the column-blocked plan's width, there are at least 2^22 entries, at most 65535
+// column blocks and 2^22 tiles, and the tiles hold eight entries or more on average.
+int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan, int32_t shift, int32_t items) {
+    const int64_t width = oracle_column_block_width(elem_bytes);
+    const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
+    const int64_t P = (m + nnz + items - 1) / items;
+    return ((plan == 4 || plan == 5) && n > 2 * width && nnz >= (int64_t{1} << 22) && C <= 65535 && C * P <= (int64_t{1} << 22) &&
+            8 * C * P <= nnz)
+               ? 1
+               : 0;
+}
+
 }  // extern "C"

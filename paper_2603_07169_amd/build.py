@@ -8,7 +8,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB_PATH = PKG / "libspmv_mi355.so"
-SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "colblock.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
+SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "colblock.hip", CSRC / "twophase.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
 HEADERS = [CSRC / "kernels.h", CSRC / "device_common.h", CSRC / "row_phase.h", CSRC / "analysis.h", INCLUDE / "spmv_mi355.h"]
 
 HIPCC_FLAGS = [

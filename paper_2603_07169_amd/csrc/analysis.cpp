@@ -72,7 +72,7 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
     spmv_analyze_params_t p{};
     if (in) p = *in;
     if (p.reserved != 0 || (p.prepare_spmm != 0 && p.prepare_spmm != 1)) return SPMV_ERR_INVALID_ARG;
-    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_COLBLOCK) return SPMV_ERR_INVALID_ARG;
+    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_TWOPHASE) return SPMV_ERR_INVALID_ARG;
     if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
     if (p.block_nnz < 0 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
     if (p.rows_max < 0 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;
@@ -101,6 +101,24 @@ void default_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* row
     entries = std::max<int64_t>(2048, std::min<int64_t>(entries, kMaxBlockNnz));
     *block_nnz = static_cast<int32_t>(entries);
     *rows_max = rows;
+}
+
+void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ipc, std::vector<int32_t>* rows,
+                       std::vector<int32_t>* entries) {
+    const int64_t T = m + nnz;
+    const int64_t P = (T + ipc - 1) / ipc;
+    rows->resize(static_cast<size_t>(P + 1));
+    entries->resize(static_cast<size_t>(P + 1));
+    int32_t* mp_row = rows->data();
+    int32_t* mp_nz = entries->data();
+    parallel_pieces(P + 1, host_threads((P + 1) * 16), [=](int, int64_t lo, int64_t hi) {
+        for (int64_t p = lo; p < hi; ++p) {
+            const int64_t d = std::min(p * ipc, T);
+            const int64_t i = split_rows_on_diagonal(d, m, nnz, rowptr);
+            mp_row[p] = static_cast<int32_t>(i);
+            mp_nz[p] = static_cast<int32_t>(d - i);
+        }
+    });
 }
 
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
@@ -190,23 +208,8 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
     }
 
     // ---- merge-path splits by bisection on each chunk's diagonal
-    const int64_t T = m + nnz;
-    const int64_t ipc = params.items_per_chunk;
-    const int64_t P = (T + ipc - 1) / ipc;
-    a.mp_row.resize(static_cast<size_t>(P + 1));
-    a.mp_nz.resize(static_cast<size_t>(P + 1));
-    {
-        int32_t* mp_row = a.mp_row.data();
-        int32_t* mp_nz = a.mp_nz.data();
-        parallel_pieces(P + 1, host_threads((P + 1) * 16), [=](int, int64_t lo, int64_t hi) {
-            for (int64_t p = lo; p < hi; ++p) {
-                const int64_t d = std::min(p * ipc, T);
-                const int64_t i = split_rows_on_diagonal(d, m, nnz, rowptr);
-                mp_row[p] = static_cast<int32_t>(i);
-                mp_nz[p] = static_cast<int32_t>(d - i);
-            }
-        });
-    }
+    merge_path_splits(m, nnz, rowptr, params.items_per_chunk, &a.mp_row, &a.mp_nz);
+    const int64_t P = static_cast<int64_t>(a.mp_row.size()) - 1;
 
     // ---- plan
     int32_t plan = params.plan;
@@ -255,6 +258,62 @@ bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t pla
     const int64_t width = column_block_width(dtype);
     const int64_t blocks = (n + width - 1) / width;
     return (plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE) && n > 2 * width && blocks <= 16 && nnz >= (int64_t{1} << 22);
+}
+
+int two_phase_shift(int64_t n) {
+    (void)n;
+    return 14;
+}
+
+bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan) {
+    if (!(plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE)) return false;
+    const int64_t width = column_block_width(dtype);
+    if (n <= 2 * width || nnz < (int64_t{1} << 22)) return false;
+    const int64_t C = (n + (int64_t{1} << two_phase_shift(n)) - 1) >> two_phase_shift(n);
+    const int64_t P = (m + nnz + kTwoPhaseItems - 1) / kTwoPhaseItems;
+    // tiles of at least eight entries on average: the padding to whole groups of four then stays below a fifth
+    return C <= 65535 && C * P <= kTwoPhaseMaxTiles && 8 * C * P <= nnz;
+}
+
+bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int32_t>* first, std::vector<int32_t>* base1,
+                      std::vector<int32_t>* base2, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g,
+                      std::vector<int32_t>* chunk_g, int64_t* slots) {
+    const size_t T = static_cast<size_t>(C * P);
+    first->resize(T);
+    base1->resize(T);
+    base2->resize(T);
+    int64_t run = 0, padded = 0;
+    piece_c->clear();
+    piece_g->clear();
+    for (int64_t c = 0; c < C; ++c) {
+        const int64_t block_start = padded;
+        for (int64_t p = 0; p < P; ++p) {
+            const size_t t = static_cast<size_t>(c * P + p);
+            (*first)[t] = static_cast<int32_t>(run);
+            (*base1)[t] = static_cast<int32_t>(padded);
+            run += cnt[t];
+            padded += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
+            if (padded > SPMV_MAX_SIZE) return false;
+        }
+        for (int64_t g = block_start / 4; g < padded / 4; g += kTwoPhasePieceGroups) {
+            piece_c->push_back(static_cast<int32_t>(c));
+            piece_g->push_back(static_cast<int32_t>(g));
+        }
+    }
+    piece_g->push_back(static_cast<int32_t>(padded / 4));
+    *slots = padded;
+    chunk_g->resize(static_cast<size_t>(P) + 1);
+    padded = 0;
+    for (int64_t p = 0; p < P; ++p) {
+        (*chunk_g)[static_cast<size_t>(p)] = static_cast<int32_t>(padded / 4);
+        for (int64_t c = 0; c < C; ++c) {
+            const size_t t = static_cast<size_t>(c * P + p);
+            (*base2)[t] = static_cast<int32_t>(padded);
+            padded += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
+        }
+    }
+    (*chunk_g)[static_cast<size_t>(P)] = static_cast<int32_t>(padded / 4);
+    return true;
 }
 
 bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest) {

@@ -41,6 +41,23 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
 int64_t column_block_width(spmv_dtype_t dtype);
 bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan);
 
+// Merge-path splits every ipc steps: rows finished and entries taken at each split (P+1 of each).
+void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ipc, std::vector<int32_t>* rows,
+                       std::vector<int32_t>* entries);
+
+// The two-pass plan.
+constexpr int kTwoPhaseItems = 8192;               // merge-path steps per chunk of the reduce pass
+constexpr int kTwoPhasePieceGroups = 8192;         // most groups of four slots a workgroup of the multiply pass takes
+constexpr int64_t kTwoPhaseMaxTiles = 1 << 22;     // most (column block, chunk) pairs
+int two_phase_shift(int64_t n);                    // log2 of the columns per block
+bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan);
+// From the tiles' entry counts cnt[c*P + p]: per tile, the entries before it (first) and the padded slots
+// before it in (c, p) order (base1) and in (p, c) order (base2); the pieces of the multiply pass; the
+// chunks' first groups in the reduce order; the padded total.  false: more than SPMV_MAX_SIZE slots.
+bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int32_t>* first, std::vector<int32_t>* base1,
+                      std::vector<int32_t>* base2, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g,
+                      std::vector<int32_t>* chunk_g, int64_t* slots);
+
 // Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x
 // from the windows: every block within SPMV_MAX_X_VECTORS, and the fixed-stride address lists
 // (one slot per block and possible vector) no longer than a quarter of the entries.

@@ -57,6 +57,21 @@ struct spmv_csr_s {
     int32_t* d_xv_start = nullptr;
     int32_t* d_xv_pad = nullptr;
     uint16_t* d_lidx = nullptr;
+    // the two-pass plan (TWOPHASE)
+    int32_t* d_tp_desc = nullptr;     // pairs (tp_row[p], tp_nz[p])
+    int32_t* d_tp_piece_c = nullptr;
+    int32_t* d_tp_piece_g = nullptr;
+    int32_t* d_tp_chunk_g = nullptr;
+    uint16_t* d_tp_col = nullptr;
+    void* d_tp_val = nullptr;
+    int32_t* d_tp_src = nullptr;
+    int32_t* d_tp_dst = nullptr;
+    uint16_t* d_tp_pos = nullptr;
+    float* d_tp_prod = nullptr;
+    int32_t* d_tp_carry_row = nullptr;
+    float* d_tp_carry_val = nullptr;
+    size_t tp_reduce_lds = 0;
+    std::vector<int32_t> tp_row, tp_nz;  // host copies for the read-back
     int32_t* d_spmm_rows = nullptr;  // row order of spmm_csr_run (prepare_spmm)
     int32_t* d_spmm_desc = nullptr;  // packed copy of A in that order (spmm_prepared == 2)
     void* d_spmm_col = nullptr;
@@ -70,9 +85,18 @@ void free_metadata(spmv_csr_s* h) {
                     h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
                     h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc, h->d_cb_row, h->d_cb_col,
                     h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
-                    h->d_spmm_val};
+                    h->d_spmm_val,  h->d_tp_desc,   h->d_tp_piece_c, h->d_tp_piece_g, h->d_tp_chunk_g,
+                    h->d_tp_col,    h->d_tp_val,    h->d_tp_src,    h->d_tp_dst,    h->d_tp_pos,
+                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
+    h->d_tp_desc = h->d_tp_piece_c = h->d_tp_piece_g = h->d_tp_chunk_g = h->d_tp_src = h->d_tp_dst = nullptr;
+    h->d_tp_carry_row = nullptr;
+    h->d_tp_col = h->d_tp_pos = nullptr;
+    h->d_tp_val = nullptr;
+    h->d_tp_prod = h->d_tp_carry_val = nullptr;
+    h->tp_row.clear();
+    h->tp_nz.clear();
     h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
     h->d_carry_val = nullptr;
     h->d_xv_ptr = h->d_xv_start = h->d_xv_pad = h->d_block_desc = h->d_chunk_desc = nullptr;
@@ -213,6 +237,129 @@ spmv_status_t build_column_blocks(spmv_csr_s* h, spmv::Analysis* a) {
     return SPMV_OK;
 }
 
+// Regroups the entries for the two-pass plan on the device (a stable sort by column block, a count
+// per tile, prefix sums on the host, a placement pass) and switches the plan to TWOPHASE.
+spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a) try {
+    if (h->m == 0 || h->nnz == 0) {
+        a->info.plan = SPMV_PLAN_SCALAR;
+        return SPMV_OK;
+    }
+    const int shift = spmv::two_phase_shift(h->n);
+    const int64_t C = (h->n + (int64_t{1} << shift) - 1) >> shift;
+    spmv::merge_path_splits(h->m, h->nnz, rowptr_host.data(), spmv::kTwoPhaseItems, &h->tp_row, &h->tp_nz);
+    const int64_t P = static_cast<int64_t>(h->tp_row.size()) - 1;
+    if (C > 65535 || C * P > spmv::kTwoPhaseMaxTiles) return SPMV_ERR_UNSUPPORTED;
+    int bits = 1;
+    while ((int64_t{1} << bits) < C) ++bits;
+    const spmv::MatrixView A = view_of(h);
+    const size_t nnz = static_cast<size_t>(h->nnz);
+    const size_t T = static_cast<size_t>(C * P);
+
+    std::vector<int32_t> desc(2 * h->tp_row.size());
+    size_t lds = 0;
+    for (size_t q = 0; q < h->tp_row.size(); ++q) {
+        desc[2 * q] = h->tp_row[q];
+        desc[2 * q + 1] = h->tp_nz[q];
+        if (q > 0) lds = std::max(lds, spmv::two_phase_reduce_lds(h->tp_nz[q] - h->tp_nz[q - 1], h->tp_row[q] - h->tp_row[q - 1]));
+    }
+    h->tp_reduce_lds = lds;
+    spmv_status_t st = upload(desc, &h->d_tp_desc);
+    if (st != SPMV_OK) return st;
+
+    // temporaries of the regrouping
+    void* d_temp = nullptr;
+    uint16_t *d_key_in = nullptr, *d_key = nullptr;
+    uint32_t *d_idx_in = nullptr, *d_idx = nullptr;
+    int32_t *d_chunk_of = nullptr, *d_cnt = nullptr, *d_first = nullptr, *d_base1 = nullptr, *d_base2 = nullptr;
+    auto release = [&] {
+        for (void* p : {d_temp, static_cast<void*>(d_key_in), static_cast<void*>(d_key), static_cast<void*>(d_idx_in),
+                        static_cast<void*>(d_idx), static_cast<void*>(d_chunk_of), static_cast<void*>(d_cnt),
+                        static_cast<void*>(d_first), static_cast<void*>(d_base1), static_cast<void*>(d_base2)})
+            if (p) (void)hipFree(p);
+    };
+    const size_t temp_bytes = spmv::two_phase_sort_bytes(A.nnz, bits);
+    if (temp_bytes == 0) return SPMV_ERR_HIP;
+    if (hip_failed(hipMalloc(&d_temp, temp_bytes)) || hip_failed(hipMalloc(reinterpret_cast<void**>(&d_key_in), 2 * nnz)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_key), 2 * nnz)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_idx_in), 4 * nnz)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_idx), 4 * nnz)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_chunk_of), 4 * nnz)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_cnt), 4 * T))) {
+        release();
+        return SPMV_ERR_ALLOC;
+    }
+    std::vector<int32_t> cnt(T), first, base1, base2, piece_c, piece_g, chunk_g;
+    int64_t slots = 0;
+    if (hip_failed(hipMemset(d_cnt, 0, 4 * T)) ||
+        hip_failed(spmv::launch_two_phase_sort(A, shift, static_cast<int>(C), bits, d_temp, temp_bytes, d_key_in, d_key, d_idx_in,
+                                               d_idx, nullptr)) ||
+        hip_failed(spmv::launch_two_phase_count(d_key, d_idx, A.nnz, h->d_tp_desc, static_cast<int32_t>(P), d_chunk_of, d_cnt,
+                                                nullptr)) ||
+        hip_failed(hipMemcpy(cnt.data(), d_cnt, 4 * T, hipMemcpyDeviceToHost))) {
+        release();
+        return SPMV_ERR_HIP;
+    }
+    if (!spmv::two_phase_tables(C, P, cnt.data(), &first, &base1, &base2, &piece_c, &piece_g, &chunk_g, &slots)) {
+        release();
+        return SPMV_ERR_UNSUPPORTED;
+    }
+    const size_t S = static_cast<size_t>(slots);
+    st = upload(first, &d_first);
+    if (st == SPMV_OK) st = upload(base1, &d_base1);
+    if (st == SPMV_OK) st = upload(base2, &d_base2);
+    if (st == SPMV_OK) st = upload(piece_c, &h->d_tp_piece_c);
+    if (st == SPMV_OK) st = upload(piece_g, &h->d_tp_piece_g);
+    if (st == SPMV_OK) st = upload(chunk_g, &h->d_tp_chunk_g);
+    if (st == SPMV_OK &&
+        (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_col), 2 * S)) ||
+         hip_failed(hipMalloc(&h->d_tp_val, (h->dtype == SPMV_F32 ? 4 : 2) * S)) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_src), 4 * S)) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_dst), S)) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_pos), 2 * S)) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_prod), 4 * S)) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_carry_row), 4 * static_cast<size_t>(P))) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_carry_val), 4 * static_cast<size_t>(P)))))
+        st = SPMV_ERR_ALLOC;
+    if (st == SPMV_OK &&
+        (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(P), d_key, d_idx, d_chunk_of, d_first, d_base1,
+                                                 d_base2, h->d_tp_desc, slots, h->d_tp_col, h->d_tp_val, h->d_tp_src,
+                                                 h->d_tp_dst, h->d_tp_pos, nullptr)) ||
+         hip_failed(hipDeviceSynchronize())))
+        st = SPMV_ERR_HIP;
+    release();
+    if (st != SPMV_OK) return st;
+    a->info.plan = SPMV_PLAN_TWOPHASE;
+    a->info.tp_slots = slots;
+    a->info.tp_col_shift = shift;
+    a->info.tp_items = spmv::kTwoPhaseItems;
+    a->info.tp_num_col_blocks = static_cast<int32_t>(C);
+    a->info.tp_num_chunks = static_cast<int32_t>(P);
+    a->info.tp_num_pieces = static_cast<int32_t>(piece_c.size());
+    return SPMV_OK;
+} catch (const std::bad_alloc&) {
+    return SPMV_ERR_ALLOC;
+}
+
+spmv::TwoPhase two_phase_of(const spmv_csr_s* h) {
+    spmv::TwoPhase t{};
+    t.shift = h->info.tp_col_shift;
+    t.num_pieces = h->info.tp_num_pieces;
+    t.num_chunks = h->info.tp_num_chunks;
+    t.reduce_lds = h->tp_reduce_lds;
+    t.piece_c = h->d_tp_piece_c;
+    t.piece_g = h->d_tp_piece_g;
+    t.tp_col = h->d_tp_col;
+    t.tp_val = h->d_tp_val;
+    t.tp_dst = h->d_tp_dst;
+    t.tp_pos = h->d_tp_pos;
+    t.chunk_desc = h->d_tp_desc;
+    t.chunk_g = h->d_tp_chunk_g;
+    t.prod = h->d_tp_prod;
+    t.carry_row = h->d_tp_carry_row;
+    t.carry_val = h->d_tp_carry_val;
+    return t;
+}
+
 // Row order of the sparse-times-dense product and, where it pays, the packed copy of A in that order.
 spmv_status_t build_spmm_order(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a) try {
     std::vector<int32_t> order, desc;
@@ -347,6 +494,11 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         if (forced || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE)) st = build_x_windows(h, forced, &a);
     }
     if (st == SPMV_OK) {
+        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan);
+        if (p.plan == SPMV_PLAN_TWOPHASE || automatic) st = build_two_phase(h, rowptr_host, &a);
+        if (automatic && st == SPMV_ERR_UNSUPPORTED) st = SPMV_OK;  // too many padded slots: the plan stays what it was
+    }
+    if (st == SPMV_OK) {
         const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::column_block_choice(h->n, h->nnz, h->dtype, a.info.plan);
         if (p.plan == SPMV_PLAN_COLBLOCK || automatic) st = build_column_blocks(h, &a);
     }
@@ -431,6 +583,9 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
             }
             break;
         }
+        case SPMV_PLAN_TWOPHASE:
+            e = spmv::launch_two_phase(two_phase_of(h), A, x, y, s, st);
+            break;
         case SPMV_PLAN_MERGE:
             e = spmv::launch_merge(A, h->d_chunk_desc, static_cast<int32_t>(h->info.num_chunks),
                                    h->info.items_per_chunk, h->d_carry_row, h->d_carry_val, x, y, s, st);
@@ -530,6 +685,7 @@ spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream) {
     const spmv::MatrixView A = view_of(h);
     hipError_t e = hipSuccess;
     if (h->info.plan == SPMV_PLAN_COLBLOCK) e = spmv::launch_column_block_values(A, h->d_cb_src, h->d_cb_vals, st);
+    if (h->info.plan == SPMV_PLAN_TWOPHASE) e = spmv::launch_two_phase_values(A, h->d_tp_src, h->d_tp_val, h->info.tp_slots, st);
     if (e == hipSuccess && h->info.spmm_prepared == 2)
         e = spmv::launch_spmm_pack(A, h->d_spmm_rows, h->d_spmm_desc, static_cast<int32_t>((h->m + 15) / 16),
                                    h->info.spmm_col_bytes == 2, h->d_spmm_col, h->d_spmm_val, st);
@@ -593,6 +749,24 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
                 hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
                 return SPMV_ERR_HIP;
     }
+    if (h->info.plan == SPMV_PLAN_TWOPHASE) {
+        const size_t P1 = static_cast<size_t>(h->info.tp_num_chunks) + 1, S = static_cast<size_t>(h->info.tp_slots);
+        if (out->tp_row) std::memcpy(out->tp_row, h->tp_row.data(), sizeof(int32_t) * P1);
+        if (out->tp_nz) std::memcpy(out->tp_nz, h->tp_nz.data(), sizeof(int32_t) * P1);
+        const Copy tcopies[] = {{out->tp_piece_c, h->d_tp_piece_c, h->info.tp_num_pieces},
+                                {out->tp_piece_g, h->d_tp_piece_g, h->info.tp_num_pieces + 1},
+                                {out->tp_chunk_g, h->d_tp_chunk_g, h->info.tp_num_chunks + 1},
+                                {out->tp_src, h->d_tp_src, h->info.tp_slots},
+                                {out->tp_dst, h->d_tp_dst, h->info.tp_slots / 4}};
+        for (const Copy& c : tcopies)
+            if (c.dst && c.count > 0 &&
+                hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
+                return SPMV_ERR_HIP;
+        if (out->tp_col && S > 0 && hip_failed(hipMemcpy(out->tp_col, h->d_tp_col, sizeof(uint16_t) * S, hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+        if (out->tp_pos && S > 0 && hip_failed(hipMemcpy(out->tp_pos, h->d_tp_pos, sizeof(uint16_t) * S, hipMemcpyDeviceToHost)))
+            return SPMV_ERR_HIP;
+    }
     if (h->info.plan == SPMV_PLAN_WINDOWED) {
         const Copy wcopies[] = {{out->xv_ptr, h->d_xv_ptr, h->info.num_row_blocks + 1},
                                 {out->xv_start, h->d_xv_start, h->info.num_x_vectors},
@@ -617,7 +791,8 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     spmv_analyze_params_t p{};
     spmv_status_t st = spmv::resolve_params(params, &p);
     if (st != SPMV_OK) return st;
-    if (p.plan == SPMV_PLAN_WINDOWED || p.plan == SPMV_PLAN_COLBLOCK) return SPMV_ERR_INVALID_ARG;  // they need colidx: device only
+    if (p.plan == SPMV_PLAN_WINDOWED || p.plan == SPMV_PLAN_COLBLOCK || p.plan == SPMV_PLAN_TWOPHASE)
+        return SPMV_ERR_INVALID_ARG;  // they need colidx: device only
     spmv::Analysis a;
     st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
     if (st != SPMV_OK) return st;
@@ -667,6 +842,7 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_MERGE: return spmv::tile_kernel_name();
         case SPMV_PLAN_WINDOWED: return spmv::window_kernel_name();
         case SPMV_PLAN_COLBLOCK: return "spmv_coo_kernel";
+        case SPMV_PLAN_TWOPHASE: return "tp_multiply_kernel";
         default: return "";
     }
 }

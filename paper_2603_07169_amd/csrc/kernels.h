@@ -107,6 +107,46 @@ hipError_t launch_column_block_scatter(const MatrixView& A, int shift, int C, co
 // cb_vals[k] = vals[cb_src[k]] for the nnz regrouped entries (the caller's values may have changed).
 hipError_t launch_column_block_values(const MatrixView& A, const int32_t* cb_src, void* cb_vals, hipStream_t st);
 
+// The carry fix-up of the merge-path kernels: y[carry_row[p]] += alpha * carry_val[p], runs of equal rows summed in chunk order.
+hipError_t launch_merge_fixup(const int32_t* carry_row, const float* carry_val, int32_t P, float* y, float alpha,
+                              hipStream_t st);
+
+// The two-pass plan (device arrays owned by the handle).
+struct TwoPhase {
+    int32_t shift;              // column blocks of 2^shift columns
+    int32_t num_pieces;         // multiply pass: workgroups
+    int32_t num_chunks;         // reduce pass: merge-path chunks
+    size_t reduce_lds;          // two_phase_reduce_lds() of the largest chunk
+    const int32_t* piece_c;     // [num_pieces]   column block of each piece
+    const int32_t* piece_g;     // [num_pieces+1] first group of each piece (pieces are contiguous)
+    const uint16_t* tp_col;     // [slots] column within the block; padding: 2^shift
+    const void* tp_val;         // [slots] values in the handle's dtype; padding: 0
+    const int32_t* tp_dst;      // [slots/4] group of the reduce order that each group of the multiply order feeds
+    const uint16_t* tp_pos;     // [slots] reduce order: CSR position within the chunk; padding: 0xFFFF
+    const int32_t* chunk_desc;  // [2*(num_chunks+1)] pairs (rows finished, entries taken)
+    const int32_t* chunk_g;     // [num_chunks+1] first group of each chunk in the reduce order
+    float* prod;                // [slots] scratch: the products between the two passes
+    int32_t* carry_row;         // [num_chunks] scratch
+    float* carry_val;           // [num_chunks] scratch
+};
+constexpr int kTpMaxShift = 15;  // column blocks of at most 32768 columns (16-bit columns, one more value for padding)
+size_t two_phase_reduce_lds(int32_t entries, int32_t rows);
+hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* x, float* y, Scalars s, hipStream_t st);
+// Analysis time.  sort: key_out/idx_out = column block and CSR position of every entry, by column block, CSR order kept.
+size_t two_phase_sort_bytes(int32_t nnz, int bits);
+hipError_t launch_two_phase_sort(const MatrixView& A, int shift, int C, int bits, void* temp, size_t temp_bytes,
+                                 uint16_t* key_in, uint16_t* key_out, uint32_t* idx_in, uint32_t* idx_out, hipStream_t st);
+// chunk_of[q] = chunk of the q-th sorted entry; cnt[c*P + p] += 1 (cnt zeroed by the caller).
+hipError_t launch_two_phase_count(const uint16_t* key, const uint32_t* idx, int32_t nnz, const int32_t* chunk_desc, int32_t P,
+                                  int32_t* chunk_of, int32_t* cnt, hipStream_t st);
+// Fills the padding and places every entry (first/base1/base2: per tile, see twophase.hip).
+hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, const uint16_t* key, const uint32_t* idx,
+                                  const int32_t* chunk_of, const int32_t* first, const int32_t* base1, const int32_t* base2,
+                                  const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val, int32_t* tp_src,
+                                  int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st);
+// tp_val[s] = vals[tp_src[s]] wherever tp_src[s] >= 0.
+hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, hipStream_t st);
+
 // Cross-lane reduction self-check on one wavefront.  in: device float[64], lane l contributes in[l].
 // out: device float[14*64]; out[gi*64 + l] = sum over lane l's aligned group of G = 2^gi lanes,
 // gi = 0..6 from the compile-time variant, then the same seven again from the run-time variant.

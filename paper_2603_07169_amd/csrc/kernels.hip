@@ -877,6 +877,13 @@ hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t 
     return hipGetLastError();
 }
 
+hipError_t launch_merge_fixup(const int32_t* carry_row, const float* carry_val, int32_t P, float* y, float alpha,
+                              hipStream_t st) {
+    if (P <= 0) return hipSuccess;
+    hipLaunchKernelGGL(merge_fixup_kernel, dim3(ceil_div(P, kWG)), dim3(kWG), 0, st, carry_row, carry_val, P, y, alpha);
+    return hipGetLastError();
+}
+
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st) {
     if (A.nnz <= 0) return hipSuccess;
     int grid = ceil_div(A.nnz, kWG);

@@ -8,6 +8,10 @@ namespace {
 
 constexpr int kMaxDeferred = 136;  // segments far longer than the tile's mean that can be set aside per tile
 
+// Column type of a tile whose staged values are finished products: nothing is gathered, the row
+// phase only adds.  cols and x are then null pointers that are never read.
+struct NoGather {};
+
 // B entries of one segment for one lane of a team of G lanes: staged slots j, j+G, .., j+(B-1)G.
 // Three bursts of independent accesses, each issued back to back: column indices out of LDS,
 // x out of memory, matrix values out of LDS.  G and B are compile-time so that every LDS
@@ -27,6 +31,17 @@ __device__ __forceinline__ float gather_batch(const I* cols, const E* vals, cons
     float acc = 0.f;
 #pragma unroll
     for (int u = 0; u < B; ++u) acc += widen(av[u]) * widen(xv[u]);
+    return acc;
+}
+
+template <int B, int G>
+__device__ __forceinline__ float gather_batch(const NoGather*, const float* vals, const float*, int j) {
+    float p[B];
+#pragma unroll
+    for (int u = 0; u < B; ++u) p[u] = vals[j + u * G];
+    float acc = 0.f;
+#pragma unroll
+    for (int u = 0; u < B; ++u) acc += p[u];
     return acc;
 }
 

@@ -18,8 +18,9 @@ SPMV_OK = 0
 (SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_STRUCTURE, SPMV_ERR_UNSUPPORTED, SPMV_ERR_NOT_ANALYZED, SPMV_ERR_ALLOC,
  SPMV_ERR_HIP) = range(1, 7)
 (SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE,
- SPMV_PLAN_WINDOWED, SPMV_PLAN_COLBLOCK) = range(8)
-PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock"}
+ SPMV_PLAN_WINDOWED, SPMV_PLAN_COLBLOCK, SPMV_PLAN_TWOPHASE) = range(9)
+PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock",
+              8: "twophase"}
 SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 SPMV_MAX_SIZE = 2 ** 31 - 2 ** 22
@@ -44,7 +45,9 @@ class spmv_analysis_info_t(C.Structure):
                 ("vector_lanes", C.c_int32), ("block_nnz", C.c_int32), ("rows_max", C.c_int32),
                 ("items_per_chunk", C.c_int32), ("max_x_vectors", C.c_int32), ("num_col_blocks", C.c_int32),
                 ("col_block_width", C.c_int32), ("spmm_prepared", C.c_int32), ("spmm_col_bytes", C.c_int32),
-                ("spmm_num_blocks", C.c_int64)]
+                ("spmm_num_blocks", C.c_int64), ("tp_slots", C.c_int64), ("tp_col_shift", C.c_int32),
+                ("tp_items", C.c_int32), ("tp_num_col_blocks", C.c_int32), ("tp_num_chunks", C.c_int32),
+                ("tp_num_pieces", C.c_int32), ("tp_reserved", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -55,6 +58,9 @@ class spmv_analysis_host_t(C.Structure):
                 ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
                 ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p),
                 ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p),
+                ("tp_row", C.c_void_p), ("tp_nz", C.c_void_p), ("tp_piece_c", C.c_void_p), ("tp_piece_g", C.c_void_p),
+                ("tp_chunk_g", C.c_void_p), ("tp_col", C.c_void_p), ("tp_src", C.c_void_p), ("tp_dst", C.c_void_p),
+                ("tp_pos", C.c_void_p),
                 ("spmm_rows", C.c_void_p), ("spmm_desc", C.c_void_p), ("spmm_col", C.c_void_p), ("spmm_val", C.c_void_p)]
 
 
@@ -188,6 +194,12 @@ def _host_buffers(info):
     if info.plan == SPMV_PLAN_COLBLOCK:
         bufs.update(cb_ptr=np.zeros(info.num_col_blocks + 1, np.int32), cb_row=np.zeros(info.nnz, np.int32),
                     cb_col=np.zeros(info.nnz, np.int32), cb_src=np.zeros(info.nnz, np.int32))
+    if info.plan == SPMV_PLAN_TWOPHASE:
+        bufs.update(tp_row=np.zeros(info.tp_num_chunks + 1, np.int32), tp_nz=np.zeros(info.tp_num_chunks + 1, np.int32),
+                    tp_piece_c=np.zeros(info.tp_num_pieces, np.int32), tp_piece_g=np.zeros(info.tp_num_pieces + 1, np.int32),
+                    tp_chunk_g=np.zeros(info.tp_num_chunks + 1, np.int32), tp_col=np.zeros(info.tp_slots, np.uint16),
+                    tp_src=np.zeros(info.tp_slots, np.int32), tp_dst=np.zeros(info.tp_slots // 4, np.int32),
+                    tp_pos=np.zeros(info.tp_slots, np.uint16))
     if info.spmm_prepared:
         bufs.update(spmm_rows=np.zeros(info.m, np.int32))
     if info.spmm_prepared == 2:

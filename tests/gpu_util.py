@@ -11,7 +11,7 @@ import paper_2603_07169_amd as s
 TOL = {"f32": 1e-5, "bf16": 8e-3}
 DTYPE_CODE = {"f32": s.SPMV_F32, "bf16": s.SPMV_BF16}
 ALL_PLANS = [s.SPMV_PLAN_SCALAR, s.SPMV_PLAN_VECTOR, s.SPMV_PLAN_BINNED, s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE,
-             s.SPMV_PLAN_WINDOWED, s.SPMV_PLAN_COLBLOCK]
+             s.SPMV_PLAN_WINDOWED, s.SPMV_PLAN_COLBLOCK, s.SPMV_PLAN_TWOPHASE]
 
 
 def plan_params(plan):
@@ -31,6 +31,8 @@ def expected_auto_plan(p, info):
         nv, _, _, _ = oracle.x_windows(p.rowptr, p.colidx, rb, info.block_nnz, 8 if p.dtype == "bf16" else 4)
         if oracle.window_choice(nv, p.nnz):
             plan = s.SPMV_PLAN_WINDOWED
+    if oracle.two_phase_choice(p.m, p.n, p.nnz, p.dtype, plan):
+        plan = s.SPMV_PLAN_TWOPHASE
     if oracle.column_block_choice(p.n, p.nnz, p.dtype, plan):
         plan = s.SPMV_PLAN_COLBLOCK
     return plan

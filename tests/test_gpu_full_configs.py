@@ -15,7 +15,7 @@ EXPECT = {   # nnz, algorithmic bytes, plan chosen by analyze
     1: (65536, 573444, "adaptive"),
     2: (5238784, 58687492, "windowed"),
     3: (55742968, 355429332, "windowed"),
-    4: (None, None, "colblock"),
+    4: (None, None, "twophase"),
     5: (128000000, 778000004, "windowed"),
 }
 
@@ -35,10 +35,8 @@ def test_full_config_matches_oracle(k):
     # the stated bound, as written: |y - y_ref| <= tol * sum_j |a_ij x_j| for every row
     worst = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict=True, what="full")
     print(f"  {p.name}: plan {plan}, max |err| / sum|a x| = {worst:.3e}", flush=True)
-    # second run on the same handle gives the same bits (no atomics on the path), except for the
-    # column-blocked plan, whose float atomics land in varying order
-    if plan != "colblock":
-        assert np.array_equal(d.run(A), y)
+    # second run on the same handle gives the same bits (no atomics on the path)
+    assert np.array_equal(d.run(A), y)
     # analysis outputs read back from the device, bit for bit
     got = A.analysis()
     assert np.array_equal(got["row_blocks"], oracle.row_blocks(p.rowptr, A.info.block_nnz, A.info.rows_max))
@@ -46,8 +44,19 @@ def test_full_config_matches_oracle(k):
     assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
     cnt, off, rows = oracle.row_bins(p.rowptr)
     assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_rows"], rows)
-    if plan == "colblock":
-        # the regrouping, bit for bit (the oracle's literal definition takes a few seconds at this size)
+    if plan == "twophase":
+        # the two-pass regrouping, bit for bit
+        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+        assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
+        for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos"):
+            assert np.array_equal(got[name], L[name]), name
+        del L
+        A.close()
+        # the column-blocked plan, which AUTO no longer picks here: its regrouping, bit for bit (the oracle's
+        # literal definition takes a few seconds at this size), and its product (float atomics)
+        A = d.matrix(dict(plan=s.SPMV_PLAN_COLBLOCK))
+        got = A.analysis()
+        assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full colblock")
         ptr, row, col, src = oracle.column_blocks(p.m, p.n, p.rowptr, p.colidx, A.info.col_block_width)
         assert np.array_equal(got["cb_ptr"], ptr) and np.array_equal(got["cb_src"], src)
         assert np.array_equal(got["cb_row"], row) and np.array_equal(got["cb_col"], col)

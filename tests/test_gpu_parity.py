@@ -276,6 +276,44 @@ def test_column_blocks_equal_oracle_and_multiply(dtype, n):
     A.close()
 
 
+TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos")
+
+
+@pytest.mark.parametrize("dtype,n", [("f32", 100_000), ("bf16", 70_001), ("f32", 4000)])
+def test_two_phase_layout_equals_oracle_and_multiplies(dtype, n):
+    """Forced TWOPHASE plan on matrices with several column blocks and chunks (and one with a single block):
+    the regrouping read back bit for bit, the product within tolerance and the same bits on every run."""
+    rng = np.random.default_rng(78)
+    lens = np.minimum(np.concatenate([rng.integers(0, 40, 20000), [30000, 0, 0, 1], rng.integers(0, 5, 5000), [9000, 9000]]), n)
+    p = w.from_row_lengths(lens, n, seed=6, dtype=dtype, alpha=1.5, beta=-0.5, sort_cols=(dtype == "f32"),
+                           allow_dup=(dtype == "bf16"))
+    d = DeviceProblem(p, offset_elems=1 if dtype == "f32" else 0)
+    log("case two-phase layout", dtype, n, p.nnz)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
+    info = A.info
+    assert info.plan == s.SPMV_PLAN_TWOPHASE and info.tp_col_shift == oracle.TP_SHIFT and info.tp_items == oracle.TP_ITEMS
+    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+    assert (info.tp_num_col_blocks, info.tp_num_chunks, info.tp_slots, info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
+    got = A.analysis()
+    for k in TP_ARRAYS:
+        assert np.array_equal(got[k], L[k]), k
+    y_ref, S_ref = reference(p)
+    y = d.run(A)
+    assert_close(p, y, y_ref, S_ref, p.alpha, p.beta)
+    assert np.array_equal(d.run(A), y)
+    A.close()
+
+
+def test_forced_two_phase_rejects_too_many_column_blocks():
+    n = 65536 * (1 << oracle.TP_SHIFT) + 1                              # 65537 column blocks
+    rowptr, colidx, vals = to_dev(np.array([0, 2], np.int32)), to_dev(np.array([0, n - 1], np.int32)), to_dev(np.ones(2, np.float32))
+    st, h = s.spmv_csr_create(1, n, 2, rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr(), 0)
+    assert st == s.SPMV_OK
+    assert s.spmv_csr_analyze(h, dict(plan=s.SPMV_PLAN_TWOPHASE)) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_csr_analyze(h, dict(plan=s.SPMV_PLAN_SCALAR)) == s.SPMV_OK
+    s.spmv_destroy(h)
+
+
 def test_forced_column_blocks_reject_too_many_blocks():
     p = w.from_row_lengths([3, 0, 5], 17 * (1 << 20) + 1, seed=1)      # 18 blocks of binary32 columns
     d = DeviceProblem(p)

@@ -294,3 +294,100 @@ def test_column_block_choice_rule():
     assert not oracle.column_block_choice((2 << 20) + 1, big - 1, "f32", 5)         # too few entries to pay for the passes
     assert not oracle.column_block_choice(4_000_000, 31_000_000, "bf16", 5)         # 8 MB of bf16 x: two blocks
     assert not oracle.column_block_choice(17 << 20, 1 << 30, "f32", 5)              # more than 16 blocks
+
+
+# ------------------------------------------------------------------ the two-pass layout
+TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos")
+
+
+def test_two_phase_layout_handworked(golden_dir):
+    g = json.loads((golden_dir / "two_phase_handworked.json").read_text())
+    L = oracle.two_phase_layout(g["m"], g["n"], np.array(g["rowptr"], np.int32), np.array(g["colidx"], np.int32),
+                                g["shift"], g["items"], g["piece_groups"])
+    for k in ("C", "P", "S", "Q"):
+        assert L[k] == g[k], k
+    for k in TP_ARRAYS:
+        assert L[k].tolist() == g[k], k
+
+
+@pytest.mark.parametrize("shift,items,piece_groups", [(3, 16, 4), (6, 256, 32), (14, 8192, 8192), (1, 5, 1)])
+def test_two_phase_layout_properties(shift, items, piece_groups):
+    """What the layout promises, checked from the arrays alone, and the product taken through it."""
+    rng = np.random.default_rng(shift)
+    for p in (w.powerlaw(2500, n=700), w.uniform_rows(300, 5000, 9), w.from_row_lengths([0, 0, 900, 1, 0, 77, 3000, 0], 3001, seed=5),
+              w.from_row_lengths([0, 0, 0], 10)):
+        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, shift, items, piece_groups)
+        C, P, S = L["C"], L["P"], L["S"]
+        mp_row, mp_nz = oracle.merge_path(p.rowptr, items)
+        assert np.array_equal(L["tp_row"], mp_row) and np.array_equal(L["tp_nz"], mp_nz)
+        assert C == -(-p.n // (1 << shift)) and S % 4 == 0 and S >= p.nnz
+        src, col, pos, dst = L["tp_src"], L["tp_col"], L["tp_pos"], L["tp_dst"]
+        real = src >= 0
+        assert np.array_equal(np.sort(src[real]), np.arange(p.nnz))                       # every entry exactly once
+        assert np.all(col[~real] == (1 << shift)) and np.all(col[real] < (1 << shift))
+        # multiply order: pieces name the column block; with it the column comes back
+        g_of_slot = np.arange(S) // 4
+        piece_of_group = np.searchsorted(L["tp_piece_g"], np.arange(S // 4), side="right") - 1
+        assert L["tp_piece_g"][0] == 0 and L["tp_piece_g"][-1] == S // 4 and np.all(np.diff(L["tp_piece_g"]) > 0)
+        assert np.all(np.diff(L["tp_piece_g"]) <= piece_groups) and np.all(np.diff(L["tp_piece_c"]) >= 0)
+        cblk = L["tp_piece_c"][piece_of_group][g_of_slot] if S else np.zeros(0, np.int64)
+        assert np.array_equal(cblk[real].astype(np.int64) * (1 << shift) + col[real], p.colidx[src[real]])
+        # tiles: the chunk of an entry, from its CSR position
+        chunk = np.searchsorted(mp_nz, src[real], side="right") - 1
+        key = cblk[real].astype(np.int64) * P + chunk
+        assert np.all(np.diff(key) >= 0)                                                   # tiles in (c, p) order
+        assert np.all((np.diff(src[real]) > 0) | (np.diff(key) > 0))                       # CSR order inside a tile
+        # a group of four never straddles two tiles, and padding only closes a tile
+        r4 = real.reshape(-1, 4)
+        assert np.all(r4[:, 0]) and np.all(r4[:, :-1] >= r4[:, 1:])
+        k4 = np.full(S, -1, np.int64)
+        k4[real] = key
+        k4 = k4.reshape(-1, 4)
+        assert np.all((k4 == k4[:, :1]) | (k4 == -1))
+        full = r4.all(axis=1)
+        assert np.all(full[:-1] | (k4[:-1, 0] != k4[1:, 0]))                               # a padded group is its tile's last
+        # reduce order: group for group the same entries, at their position within the chunk
+        assert np.array_equal(np.sort(dst), np.arange(S // 4))
+        pos4, src4 = pos.reshape(-1, 4), src.reshape(-1, 4)
+        moved = np.full((S // 4, 4), -1, np.int64)
+        moved[dst] = src4                                                                  # CSR position of every reduce-order slot
+        chunk_of_group = np.searchsorted(L["tp_chunk_g"], np.arange(S // 4), side="right") - 1
+        assert L["tp_chunk_g"][0] == 0 and L["tp_chunk_g"][-1] == S // 4
+        want_pos = np.where(moved >= 0, moved - mp_nz[chunk_of_group][:, None], 0xFFFF)
+        assert np.array_equal(pos4, want_pos)
+        moved_c = np.full(S // 4, -1, np.int64)
+        moved_c[dst] = cblk.reshape(-1, 4)[:, 0] if S else 0
+        same_chunk = np.diff(chunk_of_group) == 0
+        assert np.all(np.diff(moved_c)[same_chunk] >= 0)                                   # inside a chunk: by column block
+        # the product taken through the layout is the product
+        x = rng.uniform(-1, 1, p.n)
+        a = rng.uniform(-1, 1, p.nnz)
+        xs = np.concatenate((x, np.zeros(2 << shift)))
+        prod1 = np.where(real, np.where(real, a[np.maximum(src, 0)], 0.0) * xs[np.where(real, cblk.astype(np.int64) * (1 << shift) + col, p.n)], 0.0)
+        prod2 = np.zeros((S // 4, 4))
+        prod2[dst] = prod1.reshape(-1, 4)
+        lds = np.zeros(p.nnz + 1)
+        sel = pos4 != 0xFFFF
+        lds[(mp_nz[chunk_of_group][:, None] + pos4)[sel]] = prod2[sel]
+        y = np.add.reduceat(np.concatenate((lds[:p.nnz], [0.0])), np.minimum(p.rowptr[:-1], p.nnz))[: p.m] if p.m else np.zeros(0)
+        y = np.where(np.diff(p.rowptr) > 0, y, 0.0)
+        rows = np.repeat(np.arange(p.m), np.diff(p.rowptr))
+        want = np.bincount(rows, weights=a * x[p.colidx], minlength=p.m)
+        assert np.allclose(y, want, rtol=0, atol=1e-12)
+
+
+def test_two_phase_choice_rule():
+    f = oracle.two_phase_choice
+    M = 4_000_000
+    assert f(M, M, 31_913_584, "f32", 5)                       # 245 column blocks x 4384 chunks, 30 entries a tile
+    assert f(M, M, 31_913_584, "f32", 4)
+    assert not f(M, M, 31_913_584, "f32", 6)                   # only from the adaptive or the merge plan
+    assert not f(M, 2 << 20, 31_913_584, "f32", 5)             # x within two column blocks of 2^20 floats
+    assert f(M, (2 << 20) + 1, 31_913_584, "f32", 5)
+    assert not f(M, (4 << 20), 31_913_584, "bf16", 5) and f(M, (4 << 20) + 1, 31_913_584, "bf16", 5)
+    assert not f(M, M, (1 << 22) - 1, "f32", 5) and f(1 << 20, M, 1 << 22, "f32", 5)
+    # tiles of fewer than eight entries on average: C = 245, P = ceil((m + nnz) / 8192)
+    nnz = 8 * 245 * 3000
+    assert f(8192 * 3000 - nnz, M, nnz, "f32", 5) and not f(8192 * 3000 - nnz + 1, M, nnz, "f32", 5)
+    # more than 2^22 tiles
+    assert not f(1 << 27, 1 << 27, 1 << 30, "f32", 5)

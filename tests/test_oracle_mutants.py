@@ -49,6 +49,14 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (max_len > block_nnz) return 5;", "if (max_len >= block_nnz) return 5;", "plan rule off by one"),
     ("analysis_oracle.cpp", "while (G < 64 && 8 * static_cast<int64_t>(G) < mean_up) G *= 2;", "while (G < 64 && 8 * static_cast<int64_t>(G) <= mean_up) G *= 2;", "vector lanes off by one"),
     ("analysis_oracle.cpp", "n > 2 * width && C <= 16", "n >= 2 * width && C <= 16", "column block rule off by one"),
+    ("analysis_oracle.cpp", "col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));", "col[s1] = static_cast<uint16_t>(colidx[k]);", "two-pass: column not made relative to its block"),
+    ("analysis_oracle.cpp", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp] + 1);", "two-pass: position in the chunk off by one"),
+    ("analysis_oracle.cpp", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s2 / 4);", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s1 / 4);", "two-pass: products left in the multiply order"),
+    ("analysis_oracle.cpp", "start2[static_cast<size_t>(c * P + pp)] = slot;\n            slot += (cnt[static_cast<size_t>(c * P + pp)] + 3) / 4 * 4;", "start2[static_cast<size_t>(c * P + pp)] = slot;\n            slot += cnt[static_cast<size_t>(c * P + pp)];", "two-pass: reduce order not padded"),
+    ("analysis_oracle.cpp", "while (tp_nz[p + 1] <= k) ++p;", "while (tp_nz[p + 1] < k) ++p;", "two-pass: an entry on a split goes to the chunk before"),
+    ("analysis_oracle.cpp", "for (int64_t g = block_first_group; g < slot / 4; g += piece_groups) {", "for (int64_t g = block_first_group; g < slot / 4; g += piece_groups + 1) {", "two-pass: pieces one group too long"),
+    ("analysis_oracle.cpp", "8 * C * P <= nnz)", "8 * C * P < nnz)", "two-pass rule off by one"),
+    ("analysis_oracle.cpp", "nnz >= (int64_t{1} << 22) && C <= 65535", "nnz > (int64_t{1} << 22) && C <= 65535", "two-pass rule: entry threshold off by one"),
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * ldb + (K - 1 - k)]);", "columns of B reversed"),
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * K + k]);", "leading dimension of B ignored"),
     ("spmm_oracle.cpp", "if (beta != 0.0f) r += static_cast<double>(beta)", "if (beta != 0.0f) r -= static_cast<double>(beta)", "beta*C subtracted"),
