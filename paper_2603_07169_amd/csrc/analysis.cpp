@@ -302,16 +302,24 @@ bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int3
     }
     piece_g->push_back(static_cast<int32_t>(padded / 4));
     *slots = padded;
-    chunk_g->resize(static_cast<size_t>(P) + 1);
+    // the (p, c) order, walked in memory order all the same: first every chunk's total, then per tile the
+    // chunk's start plus what the column blocks before it put into that chunk
+    chunk_g->assign(static_cast<size_t>(P) + 1, 0);
+    std::vector<int64_t> in_chunk(static_cast<size_t>(P), 0);
+    for (int64_t c = 0; c < C; ++c)
+        for (int64_t p = 0; p < P; ++p) in_chunk[static_cast<size_t>(p)] += (static_cast<int64_t>(cnt[static_cast<size_t>(c * P + p)]) + 3) / 4;
     padded = 0;
     for (int64_t p = 0; p < P; ++p) {
         (*chunk_g)[static_cast<size_t>(p)] = static_cast<int32_t>(padded / 4);
-        for (int64_t c = 0; c < C; ++c) {
-            const size_t t = static_cast<size_t>(c * P + p);
-            (*base2)[t] = static_cast<int32_t>(padded);
-            padded += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
-        }
+        padded += 4 * in_chunk[static_cast<size_t>(p)];
+        in_chunk[static_cast<size_t>(p)] = 0;
     }
+    for (int64_t c = 0; c < C; ++c)
+        for (int64_t p = 0; p < P; ++p) {
+            const size_t t = static_cast<size_t>(c * P + p);
+            (*base2)[t] = 4 * (*chunk_g)[static_cast<size_t>(p)] + static_cast<int32_t>(in_chunk[static_cast<size_t>(p)]);
+            in_chunk[static_cast<size_t>(p)] += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
+        }
     (*chunk_g)[static_cast<size_t>(P)] = static_cast<int32_t>(padded / 4);
     return true;
 }

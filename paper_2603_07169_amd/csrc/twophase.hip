@@ -31,8 +31,10 @@ namespace {
 typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kTpMulWG = 1024;  // the x block takes 64 KB of LDS: two workgroups per compute unit
-constexpr int kTpRedWG = 256;
+constexpr int kTpMulWG = 1024;  // the x block takes 64 KB of LDS: two workgroups per compute unit, if a lane stays within 64 registers
+constexpr int kTpMulGroups = 2;  // groups a lane of the multiply pass has in flight (4 and 8 need more registers: one workgroup per unit)
+constexpr int kTpRedWG = 512;
+constexpr int kTpRedGroups = 4;
 
 __device__ __forceinline__ void load_vals4(const float* vals, int g, float (&v)[4]) {
     const f32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(vals) + g);
@@ -63,13 +65,11 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
     const int width = 1 << shift;
     const int64_t first = static_cast<int64_t>(c) << shift;
     const int have = n - first < width ? static_cast<int>(n - first) : width;  // columns of this block that exist
-    for (int i = tid; i < width; i += kTpMulWG) xs[i] = i < have ? widen(x[first + i]) : 0.f;
-    if (tid < 4) xs[width + tid] = 0.f;
-    __syncthreads();
-    for (int gb = g0 + tid; gb < g1; gb += U * kTpMulWG) {
-        u16x4 cc[U];
-        float v[U][4];
-        int d[U];
+    // the piece's first U groups per lane are asked for before the block of x, so that the two overlap
+    u16x4 cc[U];
+    float v[U][4];
+    int d[U];
+    auto fetch = [&](int gb) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {  // past the end: the piece's last group again, not stored
             const int g = gb + u * kTpMulWG < g1 ? gb + u * kTpMulWG : g1 - 1;
@@ -77,6 +77,13 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
             load_vals4(tp_val, g, v[u]);
             d[u] = __builtin_nontemporal_load(tp_dst + g);
         }
+    };
+    if (g0 < g1) fetch(g0 + tid);
+    for (int i = tid; i < width; i += kTpMulWG) xs[i] = i < have ? widen(x[first + i]) : 0.f;
+    if (tid < 4) xs[width + tid] = 0.f;
+    __syncthreads();
+    for (int gb = g0 + tid; gb < g1; gb += U * kTpMulWG) {
+        if (gb != g0 + tid) fetch(gb);
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             f32x4 p;
@@ -259,14 +266,14 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
     hipError_t e;
     if (t.num_pieces > 0) {
         if (A.bf16) {
-            auto k = tp_multiply_kernel<BF16, 4>;
+            auto k = tp_multiply_kernel<BF16, kTpMulGroups>;
             static thread_local size_t allowed = 0;
             if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
             hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
                                static_cast<const uint16_t*>(t.tp_val), t.tp_dst, static_cast<const uint16_t*>(x), A.n, t.shift,
                                t.prod);
         } else {
-            auto k = tp_multiply_kernel<F32, 4>;
+            auto k = tp_multiply_kernel<F32, kTpMulGroups>;
             static thread_local size_t allowed = 0;
             if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
             hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
@@ -276,7 +283,7 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
     }
     const TpReduceArgs a{t.chunk_desc, t.chunk_g, t.tp_pos, t.prod, A.rowptr, y, t.carry_row, t.carry_val, t.num_chunks,
                          s.alpha,      s.beta};
-    auto k = tp_reduce_kernel<kTpRedWG, 4>;
+    auto k = tp_reduce_kernel<kTpRedWG, kTpRedGroups>;
     static thread_local size_t allowed = 0;
     if ((e = allow_lds(k, t.reduce_lds, &allowed)) != hipSuccess) return e;
     hipLaunchKernelGGL(k, dim3(t.num_chunks), dim3(kTpRedWG), t.reduce_lds, st, a);
