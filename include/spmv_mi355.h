@@ -209,7 +209,8 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     (column - c * 2^tp_col_shift; padding: 2^tp_col_shift), tp_src (position k in colidx / vals;
  *     padding: -1) and a copy of the value (padding: 0); per group of four slots tp_dst, the
  *     group's number in the reduce order.  Per slot of the reduce order: tp_pos = k - tp_nz[p]
- *     (padding: 0xFFFF).  Column block c's groups are cut into pieces of at most 8192 groups
+ *     (padding: 0xFFFF).  Column block c's groups are cut evenly into the fewest pieces of at most
+ *     8192 groups: q = ceil(groups / 8192) pieces of ceil(groups / q), the last one shorter
  *     (tp_piece_c, tp_piece_g; pieces are contiguous, tp_piece_g[Q] = S/4); tp_chunk_g[p] = first
  *     group of chunk p in the reduce order.  run() multiplies piece by piece with the block of x
  *     in LDS and writes the products to a scratch array of S floats owned by the handle (runs of

@@ -261,7 +261,7 @@ int32_t oracle_column_block_choice(int64_t n, int64_t nnz, int32_t elem_bytes, i
 // between consecutive merge-path splits taken every `items` steps (P of them).  Tile (c, p) =
 // the entries of column block c in chunk p, in CSR order, padded to a multiple of four slots.
 // Multiply order: tiles by (c, p); reduce order: tiles by (p, c).  Sizes first: S = padded slots,
-// Q = pieces (every column block's groups of four slots cut into runs of at most piece_groups).
+// Q = pieces (every column block's groups of four slots cut evenly into the fewest runs of at most piece_groups).
 void oracle_two_phase_sizes(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int32_t shift, int32_t items,
                             int32_t piece_groups, int64_t* S, int64_t* Q, int64_t* P_out, int64_t* C_out) {
     const int64_t nnz = rowptr[m];
@@ -311,9 +311,13 @@ void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const 
             start1[static_cast<size_t>(c * P + pp)] = slot;
             slot += (cnt[static_cast<size_t>(c * P + pp)] + 3) / 4 * 4;
         }
-        for (int64_t g = block_first_group; g < slot / 4; g += piece_groups) {
+        // the block's groups go into the fewest pieces that hold at most piece_groups each, cut evenly:
+        // piece i starts i * ceil(groups / pieces) groups into the block
+        const int64_t groups = slot / 4 - block_first_group;
+        const int64_t pieces = (groups + piece_groups - 1) / piece_groups;
+        for (int64_t i = 0; i < pieces; ++i) {
             piece_c[q] = static_cast<int32_t>(c);
-            piece_g[q] = static_cast<int32_t>(g);
+            piece_g[q] = static_cast<int32_t>(block_first_group + i * ((groups + pieces - 1) / pieces));
             ++q;
         }
     }

@@ -295,7 +295,11 @@ bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int3
             padded += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
             if (padded > SPMV_MAX_SIZE) return false;
         }
-        for (int64_t g = block_start / 4; g < padded / 4; g += kTwoPhasePieceGroups) {
+        // the block's groups in the fewest pieces the cap allows, all of one size (the last may be shorter)
+        const int64_t first_group = block_start / 4, groups = padded / 4 - first_group;
+        const int64_t pieces = (groups + kTwoPhasePieceGroups - 1) / kTwoPhasePieceGroups;
+        const int64_t size = pieces > 0 ? (groups + pieces - 1) / pieces : 1;
+        for (int64_t g = first_group; g < first_group + groups; g += size) {
             piece_c->push_back(static_cast<int32_t>(c));
             piece_g->push_back(static_cast<int32_t>(g));
         }

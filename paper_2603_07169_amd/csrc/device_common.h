@@ -76,6 +76,14 @@ __device__ __forceinline__ float epilogue(float acc, float alpha, float beta, co
     return beta == 0.f ? alpha * acc : alpha * acc + beta * y[r];
 }
 
+// Workgroup ids are handed to the 8 dies round-robin (id % 8).  Each die has its own L2, so
+// give die j one contiguous run of logical tiles: its x window then lives in one L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nb) {
+    const int q = nb / kXcds, r = nb % kXcds;
+    const int die = bid % kXcds, slot = bid / kXcds;
+    return die * q + (die < r ? die : r) + slot;
+}
+
 inline int ceil_div(int64_t a, int64_t b) { return static_cast<int>((a + b - 1) / b); }
 
 }  // namespace

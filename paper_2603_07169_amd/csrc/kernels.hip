@@ -25,15 +25,6 @@ namespace spmv {
 namespace {
 
 // ------------------------------------------------------------------------------------------
-// Workgroup ids are handed to the 8 dies round-robin (id % 8).  Each die has its own L2, so
-// give die j one contiguous run of logical tiles: its x window then lives in one L2.
-__device__ __forceinline__ int xcd_remap(int bid, int nb) {
-    const int q = nb / kXcds, r = nb % kXcds;
-    const int die = bid % kXcds, slot = bid / kXcds;
-    return die * q + (die < r ? die : r) + slot;
-}
-
-// ------------------------------------------------------------------------------------------
 // 128-bit streaming loads.  vals/colidx are read once: mark them non-temporal so they do not
 // push x out of the caches.
 __device__ __forceinline__ i32x4 load_idx4(const int32_t* p) {

@@ -60,8 +60,10 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
                                                                float* __restrict__ prod) {
     extern __shared__ __align__(16) float xs[];  // 2^shift x values, then four zeros
     const int tid = threadIdx.x;
-    const int c = piece_c[blockIdx.x];
-    const int g0 = piece_g[blockIdx.x], g1 = piece_g[blockIdx.x + 1];
+    // a column block's pieces on one die: its block of x then crosses the fabric once, not once per die
+    const int piece = xcd_remap(blockIdx.x, gridDim.x);
+    const int c = piece_c[piece];
+    const int g0 = piece_g[piece], g1 = piece_g[piece + 1];
     const int width = 1 << shift;
     const int64_t first = static_cast<int64_t>(c) << shift;
     const int have = n - first < width ? static_cast<int>(n - first) : width;  // columns of this block that exist
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(WG) void tp_reduce_kernel(const TpReduceArgs a) {
         for (int u = 0; u < U; ++u) {
             const int g = gb + u * WG < g1 ? gb + u * WG : g1 - 1;
             pos[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x4*>(a.tp_pos) + g);
-            pp[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(a.prod) + g);
+            pp[u] = reinterpret_cast<const f32x4*>(a.prod)[g];  // written a moment ago: a plain load finds much of it still cached
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)

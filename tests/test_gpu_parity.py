@@ -304,6 +304,19 @@ def test_two_phase_layout_equals_oracle_and_multiplies(dtype, n):
     A.close()
 
 
+def test_auto_takes_two_passes_for_a_wide_bf16_matrix():
+    """x of 4.3 M bf16 values is more than two 4 MiB stretches and 5 M entries give tiles of 30: AUTO = TWOPHASE."""
+    rng = np.random.default_rng(5)
+    p = w.from_row_lengths(rng.integers(2, 9, 1_000_000), 4_300_000, seed=9, dtype="bf16", alpha=-2.0, beta=1.0)
+    log("case wide bf16", p.nnz)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    assert A.info.plan == s.SPMV_PLAN_TWOPHASE == expected_auto_plan(p, A.info)
+    y_ref, S_ref = reference(p)
+    assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta)
+    A.close()
+
+
 def test_forced_two_phase_rejects_too_many_column_blocks():
     n = 65536 * (1 << oracle.TP_SHIFT) + 1                              # 65537 column blocks
     rowptr, colidx, vals = to_dev(np.array([0, 2], np.int32)), to_dev(np.array([0, n - 1], np.int32)), to_dev(np.ones(2, np.float32))
@@ -361,7 +374,7 @@ def test_degenerate_shapes():
 
 
 # ------------------------------------------------------------------ HIP graph capture
-@pytest.mark.parametrize("k,plan", [(2, 0), (4, 0), (1, 0), (5, 3)])
+@pytest.mark.parametrize("k,plan", [(2, 0), (4, 0), (1, 0), (5, 3), (4, 8)])
 def test_run_can_be_captured_in_a_graph_and_replayed(k, plan):
     """spmv_csr_run only enqueues kernels (no allocation, copy, memset or synchronisation), so a stream
     capture records it as it is.  Every replay is checked against the eager result, with eager work and

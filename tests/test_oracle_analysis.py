@@ -301,13 +301,14 @@ TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_co
 
 
 def test_two_phase_layout_handworked(golden_dir):
-    g = json.loads((golden_dir / "two_phase_handworked.json").read_text())
-    L = oracle.two_phase_layout(g["m"], g["n"], np.array(g["rowptr"], np.int32), np.array(g["colidx"], np.int32),
-                                g["shift"], g["items"], g["piece_groups"])
-    for k in ("C", "P", "S", "Q"):
-        assert L[k] == g[k], k
-    for k in TP_ARRAYS:
-        assert L[k].tolist() == g[k], k
+    both = json.loads((golden_dir / "two_phase_handworked.json").read_text())
+    for g in (both, both["second"]):
+        L = oracle.two_phase_layout(g["m"], g["n"], np.array(g["rowptr"], np.int32), np.array(g["colidx"], np.int32),
+                                    g["shift"], g["items"], g["piece_groups"])
+        for k in ("C", "P", "S", "Q"):
+            assert L[k] == g[k], k
+        for k in TP_ARRAYS:
+            assert L[k].tolist() == g[k], k
 
 
 @pytest.mark.parametrize("shift,items,piece_groups", [(3, 16, 4), (6, 256, 32), (14, 8192, 8192), (1, 5, 1)])
@@ -330,6 +331,13 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
         piece_of_group = np.searchsorted(L["tp_piece_g"], np.arange(S // 4), side="right") - 1
         assert L["tp_piece_g"][0] == 0 and L["tp_piece_g"][-1] == S // 4 and np.all(np.diff(L["tp_piece_g"]) > 0)
         assert np.all(np.diff(L["tp_piece_g"]) <= piece_groups) and np.all(np.diff(L["tp_piece_c"]) >= 0)
+        for c in range(C):                                                                 # a block's pieces: fewest, cut evenly
+            mine = np.flatnonzero(L["tp_piece_c"] == c)
+            if mine.size:
+                sizes = np.diff(L["tp_piece_g"])[mine]
+                groups = int(sizes.sum())
+                assert mine.size == -(-groups // piece_groups)
+                assert np.all(sizes[:-1] == -(-groups // mine.size)) and 0 < sizes[-1] <= -(-groups // mine.size)
         cblk = L["tp_piece_c"][piece_of_group][g_of_slot] if S else np.zeros(0, np.int64)
         assert np.array_equal(cblk[real].astype(np.int64) * (1 << shift) + col[real], p.colidx[src[real]])
         # tiles: the chunk of an entry, from its CSR position

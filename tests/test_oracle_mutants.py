@@ -54,7 +54,8 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s2 / 4);", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s1 / 4);", "two-pass: products left in the multiply order"),
     ("analysis_oracle.cpp", "start2[static_cast<size_t>(c * P + pp)] = slot;\n            slot += (cnt[static_cast<size_t>(c * P + pp)] + 3) / 4 * 4;", "start2[static_cast<size_t>(c * P + pp)] = slot;\n            slot += cnt[static_cast<size_t>(c * P + pp)];", "two-pass: reduce order not padded"),
     ("analysis_oracle.cpp", "while (tp_nz[p + 1] <= k) ++p;", "while (tp_nz[p + 1] < k) ++p;", "two-pass: an entry on a split goes to the chunk before"),
-    ("analysis_oracle.cpp", "for (int64_t g = block_first_group; g < slot / 4; g += piece_groups) {", "for (int64_t g = block_first_group; g < slot / 4; g += piece_groups + 1) {", "two-pass: pieces one group too long"),
+    ("analysis_oracle.cpp", "block_first_group + i * ((groups + pieces - 1) / pieces)", "block_first_group + i * piece_groups", "two-pass: pieces filled to the cap instead of cut evenly"),
+    ("analysis_oracle.cpp", "const int64_t pieces = (groups + piece_groups - 1) / piece_groups;\n        for (int64_t i = 0; i < pieces; ++i) {", "const int64_t pieces = groups / piece_groups + 1;\n        for (int64_t i = 0; i < pieces; ++i) {", "two-pass: one piece too many when the cap divides the block"),
     ("analysis_oracle.cpp", "8 * C * P <= nnz)", "8 * C * P < nnz)", "two-pass rule off by one"),
     ("analysis_oracle.cpp", "nnz >= (int64_t{1} << 22) && C <= 65535", "nnz > (int64_t{1} << 22) && C <= 65535", "two-pass rule: entry threshold off by one"),
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * ldb + (K - 1 - k)]);", "columns of B reversed"),
