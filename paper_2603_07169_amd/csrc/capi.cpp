@@ -266,35 +266,32 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     spmv_status_t st = upload(desc, &h->d_tp_desc);
     if (st != SPMV_OK) return st;
 
-    // temporaries of the regrouping
-    void* d_temp = nullptr;
-    uint16_t *d_key_in = nullptr, *d_key = nullptr;
-    uint32_t *d_idx_in = nullptr, *d_idx = nullptr;
-    int32_t *d_chunk_of = nullptr, *d_cnt = nullptr, *d_first = nullptr, *d_base1 = nullptr, *d_base2 = nullptr;
-    auto release = [&] {
-        for (void* p : {d_temp, static_cast<void*>(d_key_in), static_cast<void*>(d_key), static_cast<void*>(d_idx_in),
-                        static_cast<void*>(d_idx), static_cast<void*>(d_chunk_of), static_cast<void*>(d_cnt),
-                        static_cast<void*>(d_first), static_cast<void*>(d_base1), static_cast<void*>(d_base2)})
-            if (p) (void)hipFree(p);
-    };
+    // temporaries of the regrouping: one allocation, cut into 256-byte aligned stretches
     const size_t temp_bytes = spmv::two_phase_sort_bytes(A.nnz, bits);
     if (temp_bytes == 0) return SPMV_ERR_HIP;
-    if (hip_failed(hipMalloc(&d_temp, temp_bytes)) || hip_failed(hipMalloc(reinterpret_cast<void**>(&d_key_in), 2 * nnz)) ||
-        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_key), 2 * nnz)) ||
-        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_idx_in), 4 * nnz)) ||
-        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_idx), 4 * nnz)) ||
-        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_chunk_of), 4 * nnz)) ||
-        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_cnt), 4 * T))) {
-        release();
-        return SPMV_ERR_ALLOC;
-    }
+    const size_t stretch[] = {temp_bytes, 2 * nnz, 2 * nnz, 4 * nnz, 4 * nnz, 4 * nnz, 4 * T, 4 * T, 4 * T, 4 * T};
+    size_t offset[11] = {0};
+    for (int i = 0; i < 10; ++i) offset[i + 1] = offset[i] + (stretch[i] + 255) / 256 * 256;
+    char* pool = nullptr;
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&pool), offset[10]))) return SPMV_ERR_ALLOC;
+    void* d_temp = pool + offset[0];
+    uint16_t* d_key_in = reinterpret_cast<uint16_t*>(pool + offset[1]);
+    uint16_t* d_key = reinterpret_cast<uint16_t*>(pool + offset[2]);
+    uint32_t* d_idx_in = reinterpret_cast<uint32_t*>(pool + offset[3]);  // after the sort: the chunk of every CSR position
+    uint32_t* d_idx = reinterpret_cast<uint32_t*>(pool + offset[4]);
+    int32_t* d_chunk_of = reinterpret_cast<int32_t*>(pool + offset[5]);
+    int32_t* d_cnt = reinterpret_cast<int32_t*>(pool + offset[6]);
+    int32_t* d_first = reinterpret_cast<int32_t*>(pool + offset[7]);
+    int32_t* d_base1 = reinterpret_cast<int32_t*>(pool + offset[8]);
+    int32_t* d_base2 = reinterpret_cast<int32_t*>(pool + offset[9]);
+    auto release = [&] { (void)hipFree(pool); };
     std::vector<int32_t> cnt(T), first, base1, base2, piece_c, piece_g, chunk_g;
     int64_t slots = 0;
     if (hip_failed(hipMemset(d_cnt, 0, 4 * T)) ||
         hip_failed(spmv::launch_two_phase_sort(A, shift, static_cast<int>(C), bits, d_temp, temp_bytes, d_key_in, d_key, d_idx_in,
                                                d_idx, nullptr)) ||
-        hip_failed(spmv::launch_two_phase_count(d_key, d_idx, A.nnz, h->d_tp_desc, static_cast<int32_t>(P), d_chunk_of, d_cnt,
-                                                nullptr)) ||
+        hip_failed(spmv::launch_two_phase_count(d_key, d_idx, A.nnz, h->d_tp_desc, static_cast<int32_t>(P),
+                                                reinterpret_cast<int32_t*>(d_idx_in), d_chunk_of, d_cnt, nullptr)) ||
         hip_failed(hipMemcpy(cnt.data(), d_cnt, 4 * T, hipMemcpyDeviceToHost))) {
         release();
         return SPMV_ERR_HIP;
@@ -304,9 +301,10 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
         return SPMV_ERR_UNSUPPORTED;
     }
     const size_t S = static_cast<size_t>(slots);
-    st = upload(first, &d_first);
-    if (st == SPMV_OK) st = upload(base1, &d_base1);
-    if (st == SPMV_OK) st = upload(base2, &d_base2);
+    if (hip_failed(hipMemcpy(d_first, first.data(), 4 * T, hipMemcpyHostToDevice)) ||
+        hip_failed(hipMemcpy(d_base1, base1.data(), 4 * T, hipMemcpyHostToDevice)) ||
+        hip_failed(hipMemcpy(d_base2, base2.data(), 4 * T, hipMemcpyHostToDevice)))
+        st = SPMV_ERR_HIP;
     if (st == SPMV_OK) st = upload(piece_c, &h->d_tp_piece_c);
     if (st == SPMV_OK) st = upload(piece_g, &h->d_tp_piece_g);
     if (st == SPMV_OK) st = upload(chunk_g, &h->d_tp_chunk_g);

@@ -136,9 +136,10 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
 size_t two_phase_sort_bytes(int32_t nnz, int bits);
 hipError_t launch_two_phase_sort(const MatrixView& A, int shift, int C, int bits, void* temp, size_t temp_bytes,
                                  uint16_t* key_in, uint16_t* key_out, uint32_t* idx_in, uint32_t* idx_out, hipStream_t st);
-// chunk_of[q] = chunk of the q-th sorted entry; cnt[c*P + p] += 1 (cnt zeroed by the caller).
+// chunk_of[q] = chunk of the q-th sorted entry; cnt[c*P + p] += 1 (cnt zeroed by the caller).  chunk_at: nnz ints of scratch
+// (the chunk of every CSR position, filled here).
 hipError_t launch_two_phase_count(const uint16_t* key, const uint32_t* idx, int32_t nnz, const int32_t* chunk_desc, int32_t P,
-                                  int32_t* chunk_of, int32_t* cnt, hipStream_t st);
+                                  int32_t* chunk_at, int32_t* chunk_of, int32_t* cnt, hipStream_t st);
 // Fills the padding and places every entry (first/base1/base2: per tile, see twophase.hip).
 hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, const uint16_t* key, const uint32_t* idx,
                                   const int32_t* chunk_of, const int32_t* first, const int32_t* base1, const int32_t* base2,

@@ -176,20 +176,21 @@ __global__ __launch_bounds__(kWG) void tp_keys_kernel(const int32_t* __restrict_
     }
 }
 
+// chunk_at[k] = the chunk whose stretch of the entry list holds position k.  One workgroup per chunk.
+__global__ __launch_bounds__(kWG) void tp_chunk_fill_kernel(const int32_t* __restrict__ chunk_desc, int32_t* __restrict__ chunk_at) {
+    const int p = blockIdx.x;
+    const int k1 = chunk_desc[2 * p + 3];
+    for (int k = chunk_desc[2 * p + 1] + threadIdx.x; k < k1; k += kWG) chunk_at[k] = p;
+}
+
 // q-th entry in (column block, CSR position) order: its chunk, and one more in its tile's count.
 __global__ __launch_bounds__(kWG) void tp_count_kernel(const uint16_t* __restrict__ key, const uint32_t* __restrict__ idx,
-                                                       int nnz, const int32_t* __restrict__ chunk_desc, int P,
+                                                       int nnz, const int32_t* __restrict__ chunk_at, int P,
                                                        int32_t* __restrict__ chunk_of, int32_t* __restrict__ cnt) {
     for (int64_t q = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; q < nnz; q += static_cast<int64_t>(gridDim.x) * kWG) {
-        const int k = static_cast<int>(idx[q]);
-        int lo = 0, hi = P - 1;  // the last chunk p whose first entry is <= k (empty chunks before it end at k too)
-        while (lo < hi) {
-            const int mid = lo + ((hi - lo + 1) >> 1);
-            if (chunk_desc[2 * mid + 1] <= k) lo = mid;
-            else hi = mid - 1;
-        }
-        chunk_of[q] = lo;
-        atomicAdd(cnt + static_cast<int64_t>(key[q]) * P + lo, 1);
+        const int p = chunk_at[idx[q]];
+        chunk_of[q] = p;
+        atomicAdd(cnt + static_cast<int64_t>(key[q]) * P + p, 1);
     }
 }
 
@@ -314,8 +315,9 @@ hipError_t launch_two_phase_sort(const MatrixView& A, int shift, int C, int bits
 }
 
 hipError_t launch_two_phase_count(const uint16_t* key, const uint32_t* idx, int32_t nnz, const int32_t* chunk_desc, int32_t P,
-                                  int32_t* chunk_of, int32_t* cnt, hipStream_t st) {
-    hipLaunchKernelGGL(tp_count_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, key, idx, nnz, chunk_desc, P, chunk_of, cnt);
+                                  int32_t* chunk_at, int32_t* chunk_of, int32_t* cnt, hipStream_t st) {
+    hipLaunchKernelGGL(tp_chunk_fill_kernel, dim3(P), dim3(kWG), 0, st, chunk_desc, chunk_at);
+    hipLaunchKernelGGL(tp_count_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, key, idx, nnz, chunk_at, P, chunk_of, cnt);
     return hipGetLastError();
 }
 
