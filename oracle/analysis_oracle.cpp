@@ -352,14 +352,14 @@ void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const 
     }
 }
 
-// AUTO takes the two-pass plan (ahead of the column-blocked one) when x is spread over more than two
-// column blocks of the column-blocked plan's width, there are at least 2^22 entries, at most 65535
+// AUTO takes the two-pass plan (ahead of the column-blocked one) when x holds at least half a column
+// block of the column-blocked plan's width (2 MiB), there are at least 3 * 2^21 entries, at most 65535
 // column blocks and 2^22 tiles, and the tiles hold eight entries or more on average.
 int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan, int32_t shift, int32_t items) {
     const int64_t width = oracle_column_block_width(elem_bytes);
     const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
     const int64_t P = (m + nnz + items - 1) / items;
-    return ((plan == 4 || plan == 5) && n > 2 * width && nnz >= (int64_t{1} << 22) && C <= 65535 && C * P <= (int64_t{1} << 22) &&
+    return ((plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 22) &&
             8 * C * P <= nnz)
                ? 1
                : 0;

@@ -267,8 +267,9 @@ int two_phase_shift(int64_t n) {
 
 bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan) {
     if (!(plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE)) return false;
-    const int64_t width = column_block_width(dtype);
-    if (n <= 2 * width || nnz < (int64_t{1} << 22)) return false;
+    // x of 2 MiB or more and 1.5 * 2^22 entries: below either, the row-wise kernels' gathers (one address-unit slot
+    // each, x out of the L2s) cost less than writing the products out and reading them back
+    if (2 * n < column_block_width(dtype) || nnz < 3 * (int64_t{1} << 21)) return false;
     const int64_t C = (n + (int64_t{1} << two_phase_shift(n)) - 1) >> two_phase_shift(n);
     const int64_t P = (m + nnz + kTwoPhaseItems - 1) / kTwoPhaseItems;
     // tiles of at least eight entries on average: the padding to whole groups of four then stays below a fifth

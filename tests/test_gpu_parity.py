@@ -304,14 +304,23 @@ def test_two_phase_layout_equals_oracle_and_multiplies(dtype, n):
     A.close()
 
 
-def test_auto_takes_two_passes_for_a_wide_bf16_matrix():
-    """x of 4.3 M bf16 values is more than two 4 MiB stretches and 5 M entries give tiles of 30: AUTO = TWOPHASE."""
+@pytest.mark.parametrize("which", ["wide_bf16", "powerlaw_1M_f32", "too_few_entries", "x_too_small"])
+def test_auto_and_the_two_pass_plan(which):
+    """AUTO = TWOPHASE from x of 2 MiB and 1.5 * 2^22 entries on (tiles of eight entries or more), not below."""
     rng = np.random.default_rng(5)
-    p = w.from_row_lengths(rng.integers(2, 9, 1_000_000), 4_300_000, seed=9, dtype="bf16", alpha=-2.0, beta=1.0)
-    log("case wide bf16", p.nnz)
+    if which == "wide_bf16":            # 4.3 M bf16 columns, 5 M... entries: not enough; 7 M are
+        p = w.from_row_lengths(rng.integers(4, 11, 1_000_000), 4_300_000, seed=9, dtype="bf16", alpha=-2.0, beta=1.0)
+    elif which == "powerlaw_1M_f32":    # x of 4 MB, 8.2 M entries
+        p = w.powerlaw(1_000_000)
+    elif which == "too_few_entries":    # 6.0 M entries
+        p = w.from_row_lengths(np.full(1_000_000, 6), 1_048_576, seed=3)
+    else:                               # one column short of 2 MiB
+        p = w.from_row_lengths(np.full(1_000_000, 7), 524_287, seed=4)
+    log("case auto two-pass", which, p.nnz)
     d = DeviceProblem(p)
     A = d.matrix()
-    assert A.info.plan == s.SPMV_PLAN_TWOPHASE == expected_auto_plan(p, A.info)
+    want = s.SPMV_PLAN_TWOPHASE if which in ("wide_bf16", "powerlaw_1M_f32") else s.SPMV_PLAN_ADAPTIVE
+    assert A.info.plan == want == expected_auto_plan(p, A.info)
     y_ref, S_ref = reference(p)
     assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta)
     A.close()
