@@ -81,7 +81,28 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
         }
     };
     if (g0 < g1) fetch(g0 + tid);
-    for (int i = tid; i < width; i += kTpMulWG) xs[i] = i < have ? widen(x[first + i]) : 0.f;
+    if (have == width && reinterpret_cast<uintptr_t>(x) % 16 == 0) {  // a whole block from an aligned x: 16 bytes per lane and trip
+        if constexpr (sizeof(typename T::elem) == 4) {
+            for (int i = 4 * tid; i < width; i += 4 * kTpMulWG)
+                *reinterpret_cast<f32x4*>(xs + i) = *reinterpret_cast<const f32x4*>(x + first + i);
+        } else {
+            for (int i = 8 * tid; i < width; i += 8 * kTpMulWG) {
+                const u32x4 b = *reinterpret_cast<const u32x4*>(x + first + i);
+                f32x4 lo, hi;
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    lo[2 * j] = __uint_as_float(b[j] << 16);
+                    lo[2 * j + 1] = __uint_as_float(b[j] & 0xFFFF0000u);
+                    hi[2 * j] = __uint_as_float(b[2 + j] << 16);
+                    hi[2 * j + 1] = __uint_as_float(b[2 + j] & 0xFFFF0000u);
+                }
+                *reinterpret_cast<f32x4*>(xs + i) = lo;
+                *reinterpret_cast<f32x4*>(xs + i + 4) = hi;
+            }
+        }
+    } else {
+        for (int i = tid; i < width; i += kTpMulWG) xs[i] = i < have ? widen(x[first + i]) : 0.f;
+    }
     if (tid < 4) xs[width + tid] = 0.f;
     __syncthreads();
     for (int gb = g0 + tid; gb < g1; gb += U * kTpMulWG) {
