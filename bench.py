@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--spmm", type=int, default=0, metavar="LOG2ROWS",
                     help="run only the SpMM CSR product of the paper's shape with 2^LOG2ROWS rows and print its line")
+    ap.add_argument("--two-pass-sweep", action="store_true",
+                    help="run only the matrices that place the two-pass plan's thresholds (row-wise plan against plan 8) and print their lines")
     ap.add_argument("--formats", action="store_true", help="run only the COO / CSC / ELL products and print their lines")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the launch floor, the large uniform matrix and the paper-shaped sweep")
@@ -181,6 +183,29 @@ def measure_problem(p, args, params):
     }
     res.close()
     return p, out
+
+
+def two_pass_sweep(args):
+    """Matrices with scattered columns around the sizes where the two-pass plan starts to pay: the row-wise plan AUTO
+    arrives at without it (merge for the power-law rows, adaptive for the uniform ones) against the two-pass plan."""
+    import workloads as w
+    import paper_2603_07169_amd as s
+    out = []
+    makers = [lambda: w.powerlaw(250_000), lambda: w.powerlaw(500_000), lambda: w.powerlaw(1_000_000), lambda: w.powerlaw(2_000_000),
+              lambda: w.uniform_rows(1 << 18, 1 << 18, 16), lambda: w.uniform_rows(1 << 20, 1 << 20, 16),
+              lambda: w.uniform_rows(1 << 21, 1 << 21, 16), lambda: w.uniform_rows(1 << 20, 1 << 20, 16, dtype="bf16"),
+              lambda: w.uniform_rows(1 << 20, 1 << 18, 32), lambda: w.uniform_rows(1 << 16, 1 << 20, 64)]
+    for make in makers:
+        p = make()
+        row_wise = s.SPMV_PLAN_MERGE if int(np.diff(p.rowptr).max()) > 8192 else s.SPMV_PLAN_ADAPTIVE
+        entry = {"workload": p.name, "dtype": p.dtype, "m": p.m, "n": p.n, "nnz": p.nnz}
+        for plan in (row_wise, s.SPMV_PLAN_TWOPHASE):
+            _, r = measure_problem(p, args, dict(plan=plan))
+            entry[r["plan"] + "_us"] = r["ms_per_step"] * 1e3
+        _, r = measure_problem(p, args, dict(plan=0))
+        entry["auto_plan"] = r["plan"]
+        out.append(entry)
+    return out
 
 
 def launch_floor_us(n=200):
@@ -392,6 +417,9 @@ def main():
     torch.cuda.set_device(0)
     if args.formats:
         print(json.dumps({"formats": formats_sweep(args)}))
+        return
+    if args.two_pass_sweep:
+        print(json.dumps({"two_pass_sweep": two_pass_sweep(args)}))
         return
     if args.spmm:
         print(json.dumps({"spmm_csr": spmm_sweep(args, rows_log2=(args.spmm,))}))
