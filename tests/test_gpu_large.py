@@ -3,6 +3,7 @@ the oracle row by row, every row.  The kernels index entries with 32-bit integer
 case that shows an index, or a byte offset formed from one, leaving the 31-bit range."""
 import numpy as np
 import pytest
+import torch
 
 import oracle
 import paper_2603_07169_amd as s
@@ -61,3 +62,32 @@ def test_more_than_2_to_30_entries_every_plan():
         worst = assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what=s.PLAN_NAMES[plan])
         print(f"    max |err| / sum|a x| = {worst:.3e}", flush=True)
         A.close()
+
+
+def test_two_pass_plan_on_67_million_scattered_entries():
+    """The largest matrix the benchmark line reports for the two-pass plan (4 M x 4 M, 16 entries a row at random
+    columns: 256 column blocks x 8704 chunks): the regrouping bit for bit, every row against the oracle, same
+    bits on a second run, and values changed in place picked up after a refresh."""
+    p = w.uniform_rows(1 << 22, 1 << 22, 16, alpha=1.25, beta=-0.5)
+    print("case", p.name, p.nnz, flush=True)
+    d = DeviceProblem(p)
+    A = d.matrix()
+    assert A.info.plan == s.SPMV_PLAN_TWOPHASE
+    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+    assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
+    got = A.analysis()
+    for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos"):
+        assert np.array_equal(got[name], L[name]), name
+    del got, L
+    y_ref, S_ref = reference(p)
+    y = d.run(A)
+    worst = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict=False, what="two-pass")
+    print(f"  two-pass: max |err| / sum|a x| = {worst:.3e}", flush=True)
+    assert np.array_equal(d.run(A), y)
+    new_vals = np.roll(p.vals, 12345)
+    d.vals.copy_(torch.from_numpy(new_vals).cuda())
+    A.refresh_values()
+    q = w.CsrProblem(p.name, p.dtype, p.m, p.n, p.rowptr, p.colidx, new_vals, p.x, p.y0, p.alpha, p.beta)
+    y_ref, S_ref = reference(q)
+    assert_close(q, d.run(A), y_ref, S_ref, q.alpha, q.beta, what="two-pass after refresh")
+    A.close()
