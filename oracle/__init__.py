@@ -92,7 +92,9 @@ def _load():
         _lib.oracle_two_phase_sizes.restype = None
         _lib.oracle_two_phase_layout.argtypes = [i64, i64, vp, vp, i32, i32, i32] + [vp] * 9
         _lib.oracle_two_phase_layout.restype = None
-        _lib.oracle_two_phase_choice.argtypes = [i64, i64, i64, i32, i32, i32, i32]
+        _lib.oracle_two_phase_choice.argtypes = [i64, i64, i64, i32, i32, i32, i32, i64, i64]
+        _lib.oracle_scatter_counts.argtypes = [i64, vp, vp, i32, vp, vp, vp]
+        _lib.oracle_scatter_counts.restype = None
         _lib.oracle_two_phase_choice.restype = i32
     return _lib
 
@@ -348,5 +350,15 @@ def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece
     return out
 
 
-def two_phase_choice(m, n, nnz, dtype, plan, shift=TP_SHIFT, items=TP_ITEMS):
-    return bool(_load().oracle_two_phase_choice(m, n, nnz, 4 if dtype == "f32" else 2, plan, shift, items))
+def scatter_counts(rowptr, row_blocks, block_nnz, nv):
+    """(distinct x vectors of the row blocks summed, entries of the blocks that were counted)."""
+    nv = np.ascontiguousarray(nv, dtype=np.int32)
+    vectors, entries = C.c_int64(), C.c_int64()
+    _load().oracle_scatter_counts(row_blocks.size - 1, _p(_chk(row_blocks, np.int32)), _p(_chk(rowptr, np.int32)), block_nnz, _p(nv),
+                                  C.byref(vectors), C.byref(entries))
+    return int(vectors.value), int(entries.value)
+
+
+def two_phase_choice(m, n, nnz, dtype, plan, vectors, entries, shift=TP_SHIFT, items=TP_ITEMS):
+    """vectors, entries: scatter_counts() of the row blocks' x windows (vectors < 0: not counted)."""
+    return bool(_load().oracle_two_phase_choice(m, n, nnz, 4 if dtype == "f32" else 2, plan, shift, items, vectors, entries))

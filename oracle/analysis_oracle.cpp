@@ -352,13 +352,29 @@ void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const 
     }
 }
 
+// How scattered the columns are: the distinct x vectors of the row blocks (nv from oracle_x_windows), summed,
+// against the entries of the blocks that were counted (every block but a single row longer than block_nnz).
+void oracle_scatter_counts(int64_t nb, const int32_t* row_blocks, const int32_t* rowptr, int32_t block_nnz, const int32_t* nv,
+                           int64_t* vectors, int64_t* entries) {
+    *vectors = 0;
+    *entries = 0;
+    for (int64_t b = 0; b < nb; ++b) {
+        const int64_t in_block = static_cast<int64_t>(rowptr[row_blocks[b + 1]]) - rowptr[row_blocks[b]];
+        *vectors += nv[b];
+        if (in_block <= block_nnz) *entries += in_block;
+    }
+}
+
 // AUTO takes the two-pass plan (ahead of the column-blocked one) when x holds at least half a column
 // block of the column-blocked plan's width (2 MiB), there are at least 3 * 2^21 entries, at most 65535
-// column blocks and 2^22 tiles, and the tiles hold eight entries or more on average.
-int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan, int32_t shift, int32_t items) {
+// column blocks and 2^22 tiles, the tiles hold eight entries or more on average, and the columns are
+// scattered: at least three distinct x vectors per four counted entries (vectors < 0: not counted, no).
+int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan, int32_t shift, int32_t items,
+                                int64_t vectors, int64_t entries) {
     const int64_t width = oracle_column_block_width(elem_bytes);
     const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
     const int64_t P = (m + nnz + items - 1) / items;
+    if (vectors < 0 || 4 * vectors < 3 * entries) return 0;
     return ((plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 22) &&
             8 * C * P <= nnz)
                ? 1

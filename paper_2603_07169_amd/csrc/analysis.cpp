@@ -265,8 +265,7 @@ int two_phase_shift(int64_t n) {
     return 14;
 }
 
-bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan) {
-    if (!(plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE)) return false;
+bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype) {
     // x of 2 MiB or more and 1.5 * 2^22 entries: below either, the row-wise kernels' gathers (one address-unit slot
     // each, x out of the L2s) cost less than writing the products out and reading them back
     if (2 * n < column_block_width(dtype) || nnz < 3 * (int64_t{1} << 21)) return false;
@@ -274,6 +273,15 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
     const int64_t P = (m + nnz + kTwoPhaseItems - 1) / kTwoPhaseItems;
     // tiles of at least eight entries on average: the padding to whole groups of four then stays below a fifth
     return C <= 65535 && C * P <= kTwoPhaseMaxTiles && 8 * C * P <= nnz;
+}
+
+bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, int64_t x_vectors_counted,
+                      int64_t entries_counted) {
+    if (!(plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE)) return false;
+    // columns that cluster (a band, a stencil too wide for the x windows) keep the row-wise gathers cheap:
+    // neighbouring lanes share cache lines.  Only scattered columns go through the two passes.
+    if (x_vectors_counted < 0 || 4 * x_vectors_counted < 3 * entries_counted) return false;
+    return two_phase_sizes_ok(m, n, nnz, dtype);
 }
 
 bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int32_t>* first, std::vector<int32_t>* base1,

@@ -21,6 +21,11 @@ struct Analysis {
     std::vector<int32_t> row_blocks;  // [nb+1]
     std::vector<int32_t> mp_row;      // [P+1]
     std::vector<int32_t> mp_nz;       // [P+1]
+    // How scattered the columns are, from the count pass of the x windows (-1: not counted): the distinct
+    // 16-byte x vectors of the row blocks, summed, and the entries of the blocks that were counted
+    // (all but single rows longer than block_nnz).
+    int64_t x_vectors_counted = -1;
+    int64_t entries_counted = 0;
 };
 
 // Range-checks the parameters and fills in the defaults that do not depend on the matrix
@@ -50,7 +55,12 @@ constexpr int kTwoPhaseItems = 8192;               // merge-path steps per chunk
 constexpr int kTwoPhasePieceGroups = 8192;         // most groups of four slots a workgroup of the multiply pass takes
 constexpr int64_t kTwoPhaseMaxTiles = 1 << 22;     // most (column block, chunk) pairs
 int two_phase_shift(int64_t n);                    // log2 of the columns per block
-bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan);
+// Sizes alone: x of 2 MiB or more, 3 * 2^21 entries or more, tiles few and dense enough.
+bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype);
+// The whole rule: the sizes, a row-wise plan to replace, and scattered columns (at least three distinct x vectors
+// per four counted entries; x_vectors_counted < 0, nothing counted, says no).
+bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, int64_t x_vectors_counted,
+                      int64_t entries_counted);
 // From the tiles' entry counts cnt[c*P + p]: per tile, the entries before it (first) and the padded slots
 // before it in (c, p) order (base1) and in (p, c) order (base2); the pieces of the multiply pass; the
 // chunks' first groups in the reduce order; the padded total.  false: more than SPMV_MAX_SIZE slots.

@@ -134,7 +134,9 @@ spmv::MatrixView view_of(const spmv_csr_s* h) {
 
 // Counts the x vectors of every row block on the device, settles the plan (AUTO: ADAPTIVE or
 // WINDOWED) and, for WINDOWED, builds xv_ptr / xv_start / lidx.  Needs d_block_nz.
-spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, spmv::Analysis* a) {
+// count_only: stop after the count (it also says how scattered the columns are).
+spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, bool count_only, const std::vector<int32_t>& rowptr_host,
+                              spmv::Analysis* a) {
     const int64_t nb = a->info.num_row_blocks;
     const spmv::MatrixView A = view_of(h);
     std::vector<int32_t> nv, xv_ptr;
@@ -157,6 +159,14 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, spmv::Analysis* a) {
     int32_t largest = 0;
     const bool pays = spmv::window_choice(nv.data(), nb, h->nnz, &total, &largest);
     a->info.max_x_vectors = largest;
+    a->x_vectors_counted = total;
+    a->entries_counted = 0;
+    for (int64_t b = 0; b < nb; ++b) {
+        const int64_t entries = static_cast<int64_t>(rowptr_host[static_cast<size_t>(a->row_blocks[static_cast<size_t>(b) + 1])]) -
+                                rowptr_host[static_cast<size_t>(a->row_blocks[static_cast<size_t>(b)])];
+        if (entries <= a->info.block_nnz) a->entries_counted += entries;
+    }
+    if (count_only) return SPMV_OK;
     if (forced && largest > SPMV_MAX_X_VECTORS) return SPMV_ERR_UNSUPPORTED;
     if (!forced && !pays) return SPMV_OK;  // stays ADAPTIVE
     const int32_t x_cap = largest > 0 ? largest : 1;
@@ -489,10 +499,15 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     }
     if (st == SPMV_OK) {
         const bool forced = p.plan == SPMV_PLAN_WINDOWED;
-        if (forced || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE)) st = build_x_windows(h, forced, &a);
+        // a matrix headed for the merge plan is counted too where the two-pass plan could take it: is it scattered?
+        const bool count_only = p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_MERGE &&
+                                spmv::two_phase_sizes_ok(h->m, h->n, h->nnz, h->dtype);
+        if (forced || count_only || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE))
+            st = build_x_windows(h, forced, count_only, rowptr_host, &a);
     }
     if (st == SPMV_OK) {
-        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan);
+        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan,
+                                                                                  a.x_vectors_counted, a.entries_counted);
         if (p.plan == SPMV_PLAN_TWOPHASE || automatic) st = build_two_phase(h, rowptr_host, &a);
         if (automatic && st == SPMV_ERR_UNSUPPORTED) st = SPMV_OK;  // too many padded slots: the plan stays what it was
     }

@@ -385,7 +385,8 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
 
 
 def test_two_phase_choice_rule():
-    f = oracle.two_phase_choice
+    def f(m, n, nnz, dtype, plan, vectors=None, entries=None):       # scattered unless said otherwise: a vector per entry
+        return oracle.two_phase_choice(m, n, nnz, dtype, plan, nnz if vectors is None else vectors, nnz if entries is None else entries)
     M = 4_000_000
     assert f(M, M, 31_913_584, "f32", 5)                       # 245 column blocks x 4384 chunks, 30 entries a tile
     assert f(M, M, 31_913_584, "f32", 4)
@@ -399,3 +400,18 @@ def test_two_phase_choice_rule():
     assert f(8192 * 4000 - nnz, M, nnz, "f32", 5) and not f(8192 * 4000 - nnz + 1, M, nnz, "f32", 5)
     # more than 2^22 tiles
     assert not f(1 << 27, 1 << 27, 1 << 30, "f32", 5)
+    # scattered columns only: three distinct x vectors per four counted entries, or more
+    assert f(M, M, 31_913_584, "f32", 5, vectors=3_000_000, entries=4_000_000)
+    assert not f(M, M, 31_913_584, "f32", 5, vectors=2_999_999, entries=4_000_000)
+    assert f(M, M, 31_913_584, "f32", 5, vectors=0, entries=0)            # nothing but over-long rows: no evidence of clustering
+    assert not f(M, M, 31_913_584, "f32", 5, vectors=-1, entries=0)       # not counted: no,
+    assert not f(M, M, 31_913_584, "f32", 5, vectors=-1, entries=-2)      # whatever the second figure says
+
+
+def test_scatter_counts_handworked():
+    """Three row blocks of a 6-row matrix, block_nnz 4: entries 3, 7 (one over-long row: not counted), 2."""
+    rowptr = np.array([0, 1, 3, 10, 10, 11, 12], np.int32)
+    row_blocks = np.array([0, 2, 3, 6], np.int32)
+    assert oracle.scatter_counts(rowptr, row_blocks, 4, [2, 0, 1]) == (3, 5)
+    assert oracle.scatter_counts(rowptr, row_blocks, 7, [2, 5, 1]) == (8, 12)
+    assert oracle.scatter_counts(rowptr, np.array([0, 6], np.int32), 4, [0]) == (0, 0)

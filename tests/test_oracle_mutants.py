@@ -57,6 +57,10 @@ MUTANTS = [
     ("analysis_oracle.cpp", "block_first_group + i * ((groups + pieces - 1) / pieces)", "block_first_group + i * piece_groups", "two-pass: pieces filled to the cap instead of cut evenly"),
     ("analysis_oracle.cpp", "const int64_t pieces = (groups + piece_groups - 1) / piece_groups;\n        for (int64_t i = 0; i < pieces; ++i) {", "const int64_t pieces = groups / piece_groups + 1;\n        for (int64_t i = 0; i < pieces; ++i) {", "two-pass: one piece too many when the cap divides the block"),
     ("analysis_oracle.cpp", "8 * C * P <= nnz)", "8 * C * P < nnz)", "two-pass rule off by one"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;", "two-pass rule: scatter threshold off by one"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;", "if (4 * vectors < 3 * entries) return 0;", "two-pass rule: uncounted windows taken for scattered"),
+    ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "*entries += in_block;", "scatter counts: over-long rows counted"),
+    ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "if (in_block < block_nnz) *entries += in_block;", "scatter counts: full blocks left out"),
     ("analysis_oracle.cpp", "nnz >= 3 * (int64_t{1} << 21) && C <= 65535", "nnz > 3 * (int64_t{1} << 21) && C <= 65535", "two-pass rule: entry threshold off by one"),
     ("analysis_oracle.cpp", "(plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3", "(plan == 4 || plan == 5) && 2 * n > width && nnz >= 3", "two-pass rule: width threshold off by one"),
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * ldb + (K - 1 - k)]);", "columns of B reversed"),

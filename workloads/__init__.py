@@ -298,6 +298,25 @@ def clustered_arithmetic(m=2 ** 23, runs=17, width=8, n=2 ** 22, seed=SEED_BASE 
                       float(alpha), float(beta), {"runs": runs, "width": width})
 
 
+def banded_random(m, half_width, per_row, seed=SEED_BASE + 41, dtype="f32", alpha=1.0, beta=0.0) -> CsrProblem:
+    """Square matrix with `per_row` entries a row at distinct random columns within `half_width` of the diagonal
+    (clipped at the edges, where columns may then repeat): clustered columns that need not fit an x window."""
+    rng = _rng(seed)
+    cols = np.empty((m, per_row), dtype=np.int64)
+    step = 1 << 15
+    for a in range(0, m, step):
+        b = min(m, a + step)
+        keys = rng.random((b - a, 2 * half_width + 1), dtype=np.float32)
+        off = np.argpartition(keys, per_row, axis=1)[:, :per_row] - half_width
+        cols[a:b] = np.sort(np.clip(np.arange(a, b)[:, None] + off, 0, m - 1), axis=1)
+    rowptr = np.arange(m + 1, dtype=np.int64) * per_row
+    colidx = cols.reshape(-1)
+    vals = _uniform_pm1(rng, colidx.size)
+    x = _uniform_pm1(rng, m)
+    y0 = _uniform_pm1(rng, m) if beta != 0.0 else None
+    return _finish(f"banded{half_width}_{per_row}_{m}", dtype, m, m, rowptr, colidx, vals, x, y0, alpha, beta)
+
+
 def from_row_lengths(lens, n, seed=1, dtype="f32", alpha=1.0, beta=0.0, sort_cols=True, allow_dup=False,
                      normal=False, name="custom") -> CsrProblem:
     """Arbitrary row-length profile; columns uniform (distinct + ascending unless asked otherwise)."""
