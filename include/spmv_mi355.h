@@ -195,8 +195,9 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     regrouped block after block, keeping their row-major order inside a block, each with its
  *     row (cb_row), its column within the block (cb_col) and its source position (cb_src); the
  *     library keeps a copy of the values in that order.  AUTO picks COLBLOCK when n > 2 W, there
- *     are at most 16 blocks and nnz >= 2^22 (and the two-pass layout below was not taken): x then
- *     no longer fits the L2s and the row-wise kernels would fetch a cache line per entry.  run() multiplies block after block with
+ *     are at most 16 blocks, nnz >= 2^22, the columns are scattered (the condition on nv_b given
+ *     with the two-pass layout below) and that layout was not taken: x then no longer fits the
+ *     L2s and the row-wise kernels would fetch a cache line per entry.  run() multiplies block after block with
  *     float atomics into y: results are reproducible to rounding, not bit for bit.  The copy is
  *     taken at analyze time (spmv_csr_refresh_values() renews it).  A forced COLBLOCK
  *     plan fails with UNSUPPORTED when there would be more than 16 blocks.

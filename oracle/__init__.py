@@ -86,7 +86,7 @@ def _load():
         _lib.oracle_column_blocks.restype = i64
         _lib.oracle_column_block_width.argtypes = [i32]
         _lib.oracle_column_block_width.restype = i64
-        _lib.oracle_column_block_choice.argtypes = [i64, i64, i32, i32]
+        _lib.oracle_column_block_choice.argtypes = [i64, i64, i32, i32, i64, i64]
         _lib.oracle_column_block_choice.restype = i32
         _lib.oracle_two_phase_sizes.argtypes = [i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, vp]
         _lib.oracle_two_phase_sizes.restype = None
@@ -330,8 +330,9 @@ def spmm_packed_choice(nnz, blocks):
     return bool(_load().oracle_spmm_packed_choice(nnz, blocks))
 
 
-def column_block_choice(n, nnz, dtype, plan):
-    return bool(_load().oracle_column_block_choice(n, nnz, 4 if dtype == "f32" else 2, plan))
+def column_block_choice(n, nnz, dtype, plan, vectors, entries):
+    """vectors, entries: scatter_counts() of the row blocks' x windows (vectors < 0: not counted)."""
+    return bool(_load().oracle_column_block_choice(n, nnz, 4 if dtype == "f32" else 2, plan, vectors, entries))
 
 
 def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece_groups=TP_PIECE_GROUPS):

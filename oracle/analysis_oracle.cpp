@@ -247,12 +247,14 @@ int64_t oracle_column_blocks(int64_t m, int64_t n, const int32_t* rowptr, const 
 // Block width and the automatic choice.  A block of x is 4 MiB (2^20 binary32 or 2^21 bf16
 // columns: what one die's L2 holds).  The column-blocked plan is taken when the matrix would
 // otherwise run on row blocks or merge-path chunks with x gathered from memory (plan 4 or 5),
-// x is larger than two blocks, there are at most 16 blocks and at least 2^22 entries.
+// x is larger than two blocks, there are at most 16 blocks and at least 2^22 entries, and the columns
+// are scattered (oracle_scatter_counts: three distinct x vectors per four counted entries, or more).
 int64_t oracle_column_block_width(int32_t elem_bytes) { return (int64_t{4} << 20) / elem_bytes; }
 
-int32_t oracle_column_block_choice(int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan) {
+int32_t oracle_column_block_choice(int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan, int64_t vectors, int64_t entries) {
     const int64_t width = oracle_column_block_width(elem_bytes);
     const int64_t C = (n + width - 1) / width;
+    if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered columns (or none counted): the row-wise plan stays
     return ((plan == 4 || plan == 5) && n > 2 * width && C <= 16 && nnz >= (int64_t{1} << 22)) ? 1 : 0;
 }
 

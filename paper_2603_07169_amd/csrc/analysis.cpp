@@ -254,10 +254,20 @@ namespace spmv {
 
 int64_t column_block_width(spmv_dtype_t dtype) { return (int64_t{4} << 20) / (dtype == SPMV_F32 ? 4 : 2); }
 
-bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan) {
+bool columns_scattered(int64_t x_vectors_counted, int64_t entries_counted) {
+    return x_vectors_counted >= 0 && 4 * x_vectors_counted >= 3 * entries_counted;
+}
+
+bool column_block_sizes_ok(int64_t n, int64_t nnz, spmv_dtype_t dtype) {
     const int64_t width = column_block_width(dtype);
     const int64_t blocks = (n + width - 1) / width;
-    return (plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE) && n > 2 * width && blocks <= 16 && nnz >= (int64_t{1} << 22);
+    return n > 2 * width && blocks <= 16 && nnz >= (int64_t{1} << 22);
+}
+
+bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, int64_t x_vectors_counted, int64_t entries_counted) {
+    // clustered columns keep the row-wise gathers cheap, whatever the size of x: only scattered ones are regrouped
+    return (plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE) && column_block_sizes_ok(n, nnz, dtype) &&
+           columns_scattered(x_vectors_counted, entries_counted);
 }
 
 int two_phase_shift(int64_t n) {
@@ -280,8 +290,7 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
     if (!(plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE)) return false;
     // columns that cluster (a band, a stencil too wide for the x windows) keep the row-wise gathers cheap:
     // neighbouring lanes share cache lines.  Only scattered columns go through the two passes.
-    if (x_vectors_counted < 0 || 4 * x_vectors_counted < 3 * entries_counted) return false;
-    return two_phase_sizes_ok(m, n, nnz, dtype);
+    return columns_scattered(x_vectors_counted, entries_counted) && two_phase_sizes_ok(m, n, nnz, dtype);
 }
 
 bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int32_t>* first, std::vector<int32_t>* base1,

@@ -44,7 +44,10 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
 // takes it: only in place of ADAPTIVE / MERGE, with x beyond two blocks, at most 16 blocks and
 // at least 2^22 entries.
 int64_t column_block_width(spmv_dtype_t dtype);
-bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan);
+// scattered: at least three distinct x vectors per four counted entries (x_vectors_counted < 0, nothing counted: no).
+bool columns_scattered(int64_t x_vectors_counted, int64_t entries_counted);
+bool column_block_sizes_ok(int64_t n, int64_t nnz, spmv_dtype_t dtype);
+bool column_block_choice(int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, int64_t x_vectors_counted, int64_t entries_counted);
 
 // Merge-path splits every ipc steps: rows finished and entries taken at each split (P+1 of each).
 void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ipc, std::vector<int32_t>* rows,

@@ -499,9 +499,10 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     }
     if (st == SPMV_OK) {
         const bool forced = p.plan == SPMV_PLAN_WINDOWED;
-        // a matrix headed for the merge plan is counted too where the two-pass plan could take it: is it scattered?
+        // a matrix headed for the merge plan is counted too where a regrouping plan could take it: is it scattered?
         const bool count_only = p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_MERGE &&
-                                spmv::two_phase_sizes_ok(h->m, h->n, h->nnz, h->dtype);
+                                (spmv::two_phase_sizes_ok(h->m, h->n, h->nnz, h->dtype) ||
+                                 spmv::column_block_sizes_ok(h->n, h->nnz, h->dtype));
         if (forced || count_only || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE))
             st = build_x_windows(h, forced, count_only, rowptr_host, &a);
     }
@@ -512,7 +513,8 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         if (automatic && st == SPMV_ERR_UNSUPPORTED) st = SPMV_OK;  // too many padded slots: the plan stays what it was
     }
     if (st == SPMV_OK) {
-        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::column_block_choice(h->n, h->nnz, h->dtype, a.info.plan);
+        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::column_block_choice(h->n, h->nnz, h->dtype, a.info.plan,
+                                                                                     a.x_vectors_counted, a.entries_counted);
         if (p.plan == SPMV_PLAN_COLBLOCK || automatic) st = build_column_blocks(h, &a);
     }
     if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);

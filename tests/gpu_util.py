@@ -31,14 +31,14 @@ def expected_auto_plan(p, info):
         nv, _, _, _ = oracle.x_windows(p.rowptr, p.colidx, rb, info.block_nnz, 8 if p.dtype == "bf16" else 4)
         if oracle.window_choice(nv, p.nnz):
             plan = s.SPMV_PLAN_WINDOWED
-    if plan in (s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE) and p.nnz >= 3 << 21:     # below that many entries the rule says no anyway
+    if plan in (s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE) and p.nnz >= 1 << 22:     # below that many entries both rules say no anyway
         rb = oracle.row_blocks(p.rowptr, info.block_nnz, info.rows_max)
         nv, _, _, _ = oracle.x_windows(p.rowptr, p.colidx, rb, info.block_nnz, 8 if p.dtype == "bf16" else 4)
         vectors, entries = oracle.scatter_counts(p.rowptr, rb, info.block_nnz, nv)
         if oracle.two_phase_choice(p.m, p.n, p.nnz, p.dtype, plan, vectors, entries):
             plan = s.SPMV_PLAN_TWOPHASE
-    if oracle.column_block_choice(p.n, p.nnz, p.dtype, plan):
-        plan = s.SPMV_PLAN_COLBLOCK
+        elif oracle.column_block_choice(p.n, p.nnz, p.dtype, plan, vectors, entries):
+            plan = s.SPMV_PLAN_COLBLOCK
     return plan
 
 

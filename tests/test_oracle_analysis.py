@@ -286,14 +286,20 @@ def test_column_blocks_properties(width):
 def test_column_block_choice_rule():
     assert oracle.column_block_width("f32") == 1 << 20 and oracle.column_block_width("bf16") == 1 << 21
     big = 1 << 22
-    assert oracle.column_block_choice(4_000_000, 31_000_000, "f32", 5)
-    assert oracle.column_block_choice(4_000_000, 31_000_000, "f32", 4)
-    assert not oracle.column_block_choice(4_000_000, 31_000_000, "f32", 6)          # windows already keep x on chip
-    assert not oracle.column_block_choice(2 << 20, 31_000_000, "f32", 5)            # x is exactly two blocks
-    assert oracle.column_block_choice((2 << 20) + 1, big, "f32", 5)
-    assert not oracle.column_block_choice((2 << 20) + 1, big - 1, "f32", 5)         # too few entries to pay for the passes
-    assert not oracle.column_block_choice(4_000_000, 31_000_000, "bf16", 5)         # 8 MB of bf16 x: two blocks
-    assert not oracle.column_block_choice(17 << 20, 1 << 30, "f32", 5)              # more than 16 blocks
+
+    def f(n, nnz, dtype, plan, vectors=None, entries=None):      # scattered unless said otherwise: a vector per entry
+        return oracle.column_block_choice(n, nnz, dtype, plan, nnz if vectors is None else vectors, nnz if entries is None else entries)
+    assert f(4_000_000, 31_000_000, "f32", 5)
+    assert f(4_000_000, 31_000_000, "f32", 4)
+    assert not f(4_000_000, 31_000_000, "f32", 6)          # windows already keep x on chip
+    assert not f(2 << 20, 31_000_000, "f32", 5)            # x is exactly two blocks
+    assert f((2 << 20) + 1, big, "f32", 5)
+    assert not f((2 << 20) + 1, big - 1, "f32", 5)         # too few entries to pay for the passes
+    assert not f(4_000_000, 31_000_000, "bf16", 5)         # 8 MB of bf16 x: two blocks
+    assert not f(17 << 20, 1 << 30, "f32", 5)              # more than 16 blocks
+    assert f(4_000_000, 31_000_000, "f32", 5, vectors=3000, entries=4000)        # scattered columns only
+    assert not f(4_000_000, 31_000_000, "f32", 5, vectors=2999, entries=4000)
+    assert not f(4_000_000, 31_000_000, "f32", 5, vectors=-1, entries=-2)        # not counted: no
 
 
 # ------------------------------------------------------------------ the two-pass layout

@@ -49,6 +49,8 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (max_len > block_nnz) return 5;", "if (max_len >= block_nnz) return 5;", "plan rule off by one"),
     ("analysis_oracle.cpp", "while (G < 64 && 8 * static_cast<int64_t>(G) < mean_up) G *= 2;", "while (G < 64 && 8 * static_cast<int64_t>(G) <= mean_up) G *= 2;", "vector lanes off by one"),
     ("analysis_oracle.cpp", "n > 2 * width && C <= 16", "n >= 2 * width && C <= 16", "column block rule off by one"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;  // clustered", "column block rule: scatter threshold off by one"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (4 * vectors < 3 * entries) return 0;  // clustered", "column block rule: uncounted windows taken for scattered"),
     ("analysis_oracle.cpp", "col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));", "col[s1] = static_cast<uint16_t>(colidx[k]);", "two-pass: column not made relative to its block"),
     ("analysis_oracle.cpp", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp] + 1);", "two-pass: position in the chunk off by one"),
     ("analysis_oracle.cpp", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s2 / 4);", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s1 / 4);", "two-pass: products left in the multiply order"),
@@ -57,8 +59,8 @@ MUTANTS = [
     ("analysis_oracle.cpp", "block_first_group + i * ((groups + pieces - 1) / pieces)", "block_first_group + i * piece_groups", "two-pass: pieces filled to the cap instead of cut evenly"),
     ("analysis_oracle.cpp", "const int64_t pieces = (groups + piece_groups - 1) / piece_groups;\n        for (int64_t i = 0; i < pieces; ++i) {", "const int64_t pieces = groups / piece_groups + 1;\n        for (int64_t i = 0; i < pieces; ++i) {", "two-pass: one piece too many when the cap divides the block"),
     ("analysis_oracle.cpp", "8 * C * P <= nnz)", "8 * C * P < nnz)", "two-pass rule off by one"),
-    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;", "two-pass rule: scatter threshold off by one"),
-    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;", "if (4 * vectors < 3 * entries) return 0;", "two-pass rule: uncounted windows taken for scattered"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "two-pass rule: scatter threshold off by one"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "if (4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "two-pass rule: uncounted windows taken for scattered"),
     ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "*entries += in_block;", "scatter counts: over-long rows counted"),
     ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "if (in_block < block_nnz) *entries += in_block;", "scatter counts: full blocks left out"),
     ("analysis_oracle.cpp", "nnz >= 3 * (int64_t{1} << 21) && C <= 65535", "nnz > 3 * (int64_t{1} << 21) && C <= 65535", "two-pass rule: entry threshold off by one"),
