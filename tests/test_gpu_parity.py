@@ -304,7 +304,7 @@ def test_two_phase_layout_equals_oracle_and_multiplies(dtype, n):
     A.close()
 
 
-@pytest.mark.parametrize("which", ["wide_bf16", "powerlaw_1M_f32", "too_few_entries", "x_too_small", "banded"])
+@pytest.mark.parametrize("which", ["wide_bf16", "powerlaw_1M_f32", "too_few_entries", "x_too_small", "banded", "banded_wide"])
 def test_auto_and_the_two_pass_plan(which):
     """AUTO = TWOPHASE from x of 2 MiB and 1.5 * 2^22 entries on (tiles of eight entries or more), not below."""
     rng = np.random.default_rng(5)
@@ -314,6 +314,8 @@ def test_auto_and_the_two_pass_plan(which):
         p = w.powerlaw(1_000_000)
     elif which == "too_few_entries":    # 6.0 M entries
         p = w.from_row_lengths(np.full(1_000_000, 6), 1_048_576, seed=3)
+    elif which == "banded_wide":        # x beyond two 4 MiB stretches as well: neither regrouping plan takes clustered columns
+        p = w.banded_random(2_200_000, 2048, 16)
     elif which == "banded":             # big enough, but the columns cluster (a band too wide for the x windows): row-wise gathers stay cheap
         p = w.banded_random(1 << 20, 2048, 16)
     else:                               # one column short of 2 MiB

@@ -299,16 +299,14 @@ def clustered_arithmetic(m=2 ** 23, runs=17, width=8, n=2 ** 22, seed=SEED_BASE 
 
 
 def banded_random(m, half_width, per_row, seed=SEED_BASE + 41, dtype="f32", alpha=1.0, beta=0.0) -> CsrProblem:
-    """Square matrix with `per_row` entries a row at distinct random columns within `half_width` of the diagonal
-    (clipped at the edges, where columns may then repeat): clustered columns that need not fit an x window."""
+    """Square matrix with `per_row` entries a row at random columns within `half_width` of the diagonal: the band is cut
+    into `per_row` equal strata and every row draws one column from each (so they are distinct and ascending; clipped at the
+    matrix edges, where columns may then repeat).  Clustered columns that need not fit an x window."""
     rng = _rng(seed)
-    cols = np.empty((m, per_row), dtype=np.int64)
-    step = 1 << 15
-    for a in range(0, m, step):
-        b = min(m, a + step)
-        keys = rng.random((b - a, 2 * half_width + 1), dtype=np.float32)
-        off = np.argpartition(keys, per_row, axis=1)[:, :per_row] - half_width
-        cols[a:b] = np.sort(np.clip(np.arange(a, b)[:, None] + off, 0, m - 1), axis=1)
+    stratum = (2 * half_width + 1) // per_row
+    assert stratum >= 1
+    off = np.arange(per_row, dtype=np.int64)[None, :] * stratum + rng.integers(0, stratum, (m, per_row)) - half_width
+    cols = np.clip(np.arange(m, dtype=np.int64)[:, None] + off, 0, m - 1)
     rowptr = np.arange(m + 1, dtype=np.int64) * per_row
     colidx = cols.reshape(-1)
     vals = _uniform_pm1(rng, colidx.size)
