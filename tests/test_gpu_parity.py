@@ -330,6 +330,40 @@ def test_auto_and_the_two_pass_plan(which):
     A.close()
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_two_phase_seeded_random_shapes(seed):
+    """Several column blocks and chunks, row-length mixes with empty and very long rows, both storage types, x and the
+    matrix arrays at odd offsets: layout bit for bit, product within tolerance."""
+    rng = np.random.default_rng(2000 + seed)
+    dtype = "f32" if seed % 2 == 0 else "bf16"
+    m = int(rng.integers(1, 120_000))
+    n = int(rng.integers(1, 200_000))
+    kind = seed % 4
+    if kind == 0:
+        lens = rng.integers(0, min(n, 30) + 1, m)
+    elif kind == 1:
+        lens = np.minimum(w.powerlaw_lengths(rng, m, cap=60_000), n)
+    elif kind == 2:
+        lens = np.where(rng.random(m) < 0.8, 0, rng.integers(0, min(n, 300) + 1, m))
+    else:
+        lens = np.concatenate([[min(n, 40_000)], np.zeros(min(m, 20_000), np.int64), rng.integers(0, min(n, 12) + 1, max(m - 1, 0))])[:max(m, 1)]
+    p = w.from_row_lengths(lens, n, seed=seed, dtype=dtype, alpha=float(rng.uniform(-2, 2)), beta=float(rng.choice([0.0, 1.0, -0.75])),
+                           sort_cols=bool(seed & 4), allow_dup=(kind == 2))
+    log("case two-phase seeded", seed, dtype, p.m, p.n, p.nnz)
+    d = DeviceProblem(p, offset_elems=seed % 3)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
+    if p.nnz == 0:
+        assert A.info.plan == s.SPMV_PLAN_SCALAR
+    else:
+        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+        got = A.analysis()
+        for k in TP_ARRAYS:
+            assert np.array_equal(got[k], L[k]), k
+    y_ref, S_ref = reference(p)
+    assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta)
+    A.close()
+
+
 def test_forced_two_phase_rejects_too_many_column_blocks():
     n = 65536 * (1 << oracle.TP_SHIFT) + 1                              # 65537 column blocks
     rowptr, colidx, vals = to_dev(np.array([0, 2], np.int32)), to_dev(np.array([0, n - 1], np.int32)), to_dev(np.ones(2, np.float32))
