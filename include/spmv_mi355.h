@@ -217,14 +217,14 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     in LDS and writes the products to a scratch array of S floats owned by the handle (runs of
  *     one handle with this plan must therefore not overlap), then sums chunk by chunk; sums are
  *     taken in a fixed order, so results are reproducible bit for bit.  AUTO picks TWOPHASE ahead
- *     of COLBLOCK when 2 n >= W (W as above: x of 2 MiB or more), nnz >= 3 * 2^21, C2 * P2 <= 2^22,
+ *     of COLBLOCK when 2 n >= W (W as above: x of 2 MiB or more), nnz >= 3 * 2^21, C2 * P2 <= 2^24,
  *     8 * C2 * P2 <= nnz (tiles of eight entries or more on average) and the columns are scattered:
  *     4 * sum_b nv_b >= 3 * E, with nv_b the distinct x vectors of row block b (the count pass of
  *     the x windows, which AUTO then also runs on a matrix headed for MERGE) and E the entries of
  *     the blocks counted (all but single rows longer than block_nnz).  Clustered columns - a band,
  *     a stencil too wide for the x windows - stay with the row-wise plans, whose gathers then
  *     share cache lines.  A forced TWOPHASE plan fails with UNSUPPORTED
- *     when C2 > 65535, C2 * P2 > 2^22 or S > SPMV_MAX_SIZE; with m == 0 or nnz == 0 it runs as
+ *     when C2 > 65535, C2 * P2 > 2^24 or S > SPMV_MAX_SIZE; with m == 0 or nnz == 0 it runs as
  *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
  *   - with prepare_spmm = 1 (SPMV_F32 handles; UNSUPPORTED on bf16 ones): spmm_rows.  The rows
  *     are cut into windows of SPMV_SPMM_WINDOW consecutive rows; inside a window the row ids are

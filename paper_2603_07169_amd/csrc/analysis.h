@@ -56,7 +56,7 @@ void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ip
 // The two-pass plan.
 constexpr int kTwoPhaseItems = 8192;               // merge-path steps per chunk of the reduce pass
 constexpr int kTwoPhasePieceGroups = 8192;         // most groups of four slots a workgroup of the multiply pass takes
-constexpr int64_t kTwoPhaseMaxTiles = 1 << 22;     // most (column block, chunk) pairs
+constexpr int64_t kTwoPhaseMaxTiles = 1 << 24;     // most (column block, chunk) pairs
 int two_phase_shift(int64_t n);                    // log2 of the columns per block
 // Sizes alone: x of 2 MiB or more, 3 * 2^21 entries or more, tiles few and dense enough.
 bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype);

@@ -64,11 +64,13 @@ def test_more_than_2_to_30_entries_every_plan():
         A.close()
 
 
-def test_two_pass_plan_on_67_million_scattered_entries():
-    """The largest matrix the benchmark line reports for the two-pass plan (4 M x 4 M, 16 entries a row at random
-    columns: 256 column blocks x 8704 chunks): the regrouping bit for bit, every row against the oracle, same
-    bits on a second run, and values changed in place picked up after a refresh."""
-    p = w.uniform_rows(1 << 22, 1 << 22, 16, alpha=1.25, beta=-0.5)
+@pytest.mark.parametrize("log2_rows", [22, 23])
+def test_two_pass_plan_on_many_scattered_entries(log2_rows):
+    """16 entries a row at random columns, 4 M x 4 M (67 M entries: the largest matrix the benchmark line reports for the
+    two-pass plan, 256 column blocks x 8704 chunks) and 8 M x 8 M (134 M entries, 8.9 M tiles of 15 entries): the regrouping
+    bit for bit, every row against the oracle, same bits on a second run, and values changed in place picked up after a
+    refresh."""
+    p = w.uniform_rows(1 << log2_rows, 1 << log2_rows, 16, alpha=1.25, beta=-0.5)
     print("case", p.name, p.nnz, flush=True)
     d = DeviceProblem(p)
     A = d.matrix()

@@ -404,7 +404,9 @@ def test_two_phase_choice_rule():
     # tiles of fewer than eight entries on average: C = 245, P = ceil((m + nnz) / 8192)
     nnz = 8 * 245 * 4000
     assert f(8192 * 4000 - nnz, M, nnz, "f32", 5) and not f(8192 * 4000 - nnz + 1, M, nnz, "f32", 5)
-    # more than 2^22 tiles
+    # more than 2^24 tiles: 512 column blocks x 2^15 chunks is the most
+    assert f((1 << 27) - (1 << 20), 1 << 23, (1 << 27) + (1 << 20), "f32", 5)
+    assert not f((1 << 27) - (1 << 20) + 1, 1 << 23, (1 << 27) + (1 << 20), "f32", 5)
     assert not f(1 << 27, 1 << 27, 1 << 30, "f32", 5)
     # scattered columns only: three distinct x vectors per four counted entries, or more
     assert f(M, M, 31_913_584, "f32", 5, vectors=3_000_000, entries=4_000_000)

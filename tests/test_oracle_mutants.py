@@ -59,6 +59,7 @@ MUTANTS = [
     ("analysis_oracle.cpp", "block_first_group + i * ((groups + pieces - 1) / pieces)", "block_first_group + i * piece_groups", "two-pass: pieces filled to the cap instead of cut evenly"),
     ("analysis_oracle.cpp", "const int64_t pieces = (groups + piece_groups - 1) / piece_groups;\n        for (int64_t i = 0; i < pieces; ++i) {", "const int64_t pieces = groups / piece_groups + 1;\n        for (int64_t i = 0; i < pieces; ++i) {", "two-pass: one piece too many when the cap divides the block"),
     ("analysis_oracle.cpp", "8 * C * P <= nnz)", "8 * C * P < nnz)", "two-pass rule off by one"),
+    ("analysis_oracle.cpp", "C * P <= (int64_t{1} << 24) &&", "C * P < (int64_t{1} << 24) &&", "two-pass rule: tile limit off by one"),
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "two-pass rule: scatter threshold off by one"),
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "if (4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "two-pass rule: uncounted windows taken for scattered"),
     ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "*entries += in_block;", "scatter counts: over-long rows counted"),
