@@ -194,14 +194,19 @@ def two_pass_sweep(args):
     makers = [lambda: w.powerlaw(250_000), lambda: w.powerlaw(500_000), lambda: w.powerlaw(1_000_000), lambda: w.powerlaw(2_000_000),
               lambda: w.uniform_rows(1 << 18, 1 << 18, 16), lambda: w.uniform_rows(1 << 20, 1 << 20, 16),
               lambda: w.uniform_rows(1 << 21, 1 << 21, 16), lambda: w.uniform_rows(1 << 20, 1 << 20, 16, dtype="bf16"),
-              lambda: w.uniform_rows(1 << 20, 1 << 18, 32), lambda: w.uniform_rows(1 << 16, 1 << 20, 64)]
+              lambda: w.uniform_rows(1 << 20, 1 << 18, 32), lambda: w.uniform_rows(1 << 16, 1 << 20, 64),
+              lambda: w.powerlaw(8_000_000), lambda: w.uniform_rows(1 << 23, 1 << 23, 16)]
     for make in makers:
         p = make()
         row_wise = s.SPMV_PLAN_MERGE if int(np.diff(p.rowptr).max()) > 8192 else s.SPMV_PLAN_ADAPTIVE
         entry = {"workload": p.name, "dtype": p.dtype, "m": p.m, "n": p.n, "nnz": p.nnz}
-        for plan in (row_wise, s.SPMV_PLAN_TWOPHASE):
+        plans = [row_wise, s.SPMV_PLAN_TWOPHASE]
+        if p.n > 2 * ((4 << 20) // (4 if p.dtype == "f32" else 2)):      # x beyond two 4 MiB stretches: the column-blocked plan as well
+            plans.append(s.SPMV_PLAN_COLBLOCK)
+        for plan in plans:
             _, r = measure_problem(p, args, dict(plan=plan))
             entry[r["plan"] + "_us"] = r["ms_per_step"] * 1e3
+            entry[r["plan"] + "_analysis_ms"] = r["analysis_ms"]
         _, r = measure_problem(p, args, dict(plan=0))
         entry["auto_plan"] = r["plan"]
         out.append(entry)
