@@ -224,7 +224,7 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     the blocks counted (all but single rows longer than block_nnz).  Clustered columns - a band,
  *     a stencil too wide for the x windows - stay with the row-wise plans, whose gathers then
  *     share cache lines.  A forced TWOPHASE plan fails with UNSUPPORTED
- *     when C2 > 65535, C2 * P2 > 2^24 or S > SPMV_MAX_SIZE; with m == 0 or nnz == 0 it runs as
+ *     when C2 > 65535, C2 * P2 > 2^24 or nnz + 3 * C2 * P2 > SPMV_MAX_SIZE (a bound on S); with m == 0 or nnz == 0 it runs as
  *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
  *   - with prepare_spmm = 1 (SPMV_F32 handles; UNSUPPORTED on bf16 ones): spmm_rows.  The rows
  *     are cut into windows of SPMV_SPMM_WINDOW consecutive rows; inside a window the row ids are

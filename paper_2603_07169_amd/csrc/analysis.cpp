@@ -293,28 +293,12 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
     return columns_scattered(x_vectors_counted, entries_counted) && two_phase_sizes_ok(m, n, nnz, dtype);
 }
 
-bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int32_t>* first, std::vector<int32_t>* base1,
-                      std::vector<int32_t>* base2, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g,
-                      std::vector<int32_t>* chunk_g, int64_t* slots) {
-    const size_t T = static_cast<size_t>(C * P);
-    first->resize(T);
-    base1->resize(T);
-    base2->resize(T);
-    int64_t run = 0, padded = 0;
+void two_phase_pieces(int64_t C, const int32_t* block_first, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g) {
     piece_c->clear();
     piece_g->clear();
     for (int64_t c = 0; c < C; ++c) {
-        const int64_t block_start = padded;
-        for (int64_t p = 0; p < P; ++p) {
-            const size_t t = static_cast<size_t>(c * P + p);
-            (*first)[t] = static_cast<int32_t>(run);
-            (*base1)[t] = static_cast<int32_t>(padded);
-            run += cnt[t];
-            padded += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
-            if (padded > SPMV_MAX_SIZE) return false;
-        }
         // the block's groups in the fewest pieces the cap allows, all of one size (the last may be shorter)
-        const int64_t first_group = block_start / 4, groups = padded / 4 - first_group;
+        const int64_t first_group = block_first[c] / 4, groups = block_first[c + 1] / 4 - first_group;
         const int64_t pieces = (groups + kTwoPhasePieceGroups - 1) / kTwoPhasePieceGroups;
         const int64_t size = pieces > 0 ? (groups + pieces - 1) / pieces : 1;
         for (int64_t g = first_group; g < first_group + groups; g += size) {
@@ -322,28 +306,7 @@ bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int3
             piece_g->push_back(static_cast<int32_t>(g));
         }
     }
-    piece_g->push_back(static_cast<int32_t>(padded / 4));
-    *slots = padded;
-    // the (p, c) order, walked in memory order all the same: first every chunk's total, then per tile the
-    // chunk's start plus what the column blocks before it put into that chunk
-    chunk_g->assign(static_cast<size_t>(P) + 1, 0);
-    std::vector<int64_t> in_chunk(static_cast<size_t>(P), 0);
-    for (int64_t c = 0; c < C; ++c)
-        for (int64_t p = 0; p < P; ++p) in_chunk[static_cast<size_t>(p)] += (static_cast<int64_t>(cnt[static_cast<size_t>(c * P + p)]) + 3) / 4;
-    padded = 0;
-    for (int64_t p = 0; p < P; ++p) {
-        (*chunk_g)[static_cast<size_t>(p)] = static_cast<int32_t>(padded / 4);
-        padded += 4 * in_chunk[static_cast<size_t>(p)];
-        in_chunk[static_cast<size_t>(p)] = 0;
-    }
-    for (int64_t c = 0; c < C; ++c)
-        for (int64_t p = 0; p < P; ++p) {
-            const size_t t = static_cast<size_t>(c * P + p);
-            (*base2)[t] = 4 * (*chunk_g)[static_cast<size_t>(p)] + static_cast<int32_t>(in_chunk[static_cast<size_t>(p)]);
-            in_chunk[static_cast<size_t>(p)] += (static_cast<int64_t>(cnt[t]) + 3) / 4 * 4;
-        }
-    (*chunk_g)[static_cast<size_t>(P)] = static_cast<int32_t>(padded / 4);
-    return true;
+    piece_g->push_back(block_first[C] / 4);
 }
 
 bool window_choice(const int32_t* nv, int64_t nb, int64_t nnz, int64_t* total, int32_t* largest) {

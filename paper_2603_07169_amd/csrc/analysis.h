@@ -64,12 +64,9 @@ bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype);
 // per four counted entries; x_vectors_counted < 0, nothing counted, says no).
 bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, int64_t x_vectors_counted,
                       int64_t entries_counted);
-// From the tiles' entry counts cnt[c*P + p]: per tile, the entries before it (first) and the padded slots
-// before it in (c, p) order (base1) and in (p, c) order (base2); the pieces of the multiply pass; the
-// chunks' first groups in the reduce order; the padded total.  false: more than SPMV_MAX_SIZE slots.
-bool two_phase_tables(int64_t C, int64_t P, const int32_t* cnt, std::vector<int32_t>* first, std::vector<int32_t>* base1,
-                      std::vector<int32_t>* base2, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g,
-                      std::vector<int32_t>* chunk_g, int64_t* slots);
+// The pieces of the multiply pass from where the column blocks start in the multiply order (block_first[C+1], in slots,
+// the last entry = all slots): every block's groups cut evenly into the fewest pieces of at most kTwoPhasePieceGroups.
+void two_phase_pieces(int64_t C, const int32_t* block_first, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g);
 
 // Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x
 // from the windows: every block within SPMV_MAX_X_VECTORS, and the fixed-stride address lists

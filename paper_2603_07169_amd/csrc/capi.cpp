@@ -276,48 +276,60 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     spmv_status_t st = upload(desc, &h->d_tp_desc);
     if (st != SPMV_OK) return st;
 
+    // 32-bit prefix sums on the device: every tile adds at most three slots of padding
+    if (h->nnz + 3 * C * P > kMaxCount) return SPMV_ERR_UNSUPPORTED;
     // temporaries of the regrouping: one allocation, cut into 256-byte aligned stretches
-    const size_t temp_bytes = spmv::two_phase_sort_bytes(A.nnz, bits);
+    // (the scans run over the T tiles, then over P + 1 <= T + 1 chunk totals)
+    const size_t temp_bytes =
+        std::max(spmv::two_phase_sort_bytes(A.nnz, bits), spmv::two_phase_scan_bytes(static_cast<int64_t>(T) + 1));
     if (temp_bytes == 0) return SPMV_ERR_HIP;
-    const size_t stretch[] = {temp_bytes, 2 * nnz, 2 * nnz, 4 * nnz, 4 * nnz, 4 * nnz, 4 * T, 4 * T, 4 * T, 4 * T};
-    size_t offset[11] = {0};
-    for (int i = 0; i < 10; ++i) offset[i + 1] = offset[i] + (stretch[i] + 255) / 256 * 256;
+    const size_t P1 = static_cast<size_t>(P) + 1, C1 = static_cast<size_t>(C) + 1;
+    const size_t stretch[] = {temp_bytes, 2 * nnz, 2 * nnz, 4 * nnz, 4 * nnz, 4 * nnz, 4 * T, 4 * T,
+                              4 * T,      4 * T,   4 * T,   4 * P1,  4 * P1,  4 * C1};
+    constexpr int kStretches = sizeof(stretch) / sizeof(stretch[0]);
+    size_t offset[kStretches + 1] = {0};
+    for (int i = 0; i < kStretches; ++i) offset[i + 1] = offset[i] + (stretch[i] + 255) / 256 * 256;
     char* pool = nullptr;
-    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&pool), offset[10]))) return SPMV_ERR_ALLOC;
-    void* d_temp = pool + offset[0];
-    uint16_t* d_key_in = reinterpret_cast<uint16_t*>(pool + offset[1]);
-    uint16_t* d_key = reinterpret_cast<uint16_t*>(pool + offset[2]);
-    uint32_t* d_idx_in = reinterpret_cast<uint32_t*>(pool + offset[3]);  // after the sort: the chunk of every CSR position
-    uint32_t* d_idx = reinterpret_cast<uint32_t*>(pool + offset[4]);
-    int32_t* d_chunk_of = reinterpret_cast<int32_t*>(pool + offset[5]);
-    int32_t* d_cnt = reinterpret_cast<int32_t*>(pool + offset[6]);
-    int32_t* d_first = reinterpret_cast<int32_t*>(pool + offset[7]);
-    int32_t* d_base1 = reinterpret_cast<int32_t*>(pool + offset[8]);
-    int32_t* d_base2 = reinterpret_cast<int32_t*>(pool + offset[9]);
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&pool), offset[kStretches]))) return SPMV_ERR_ALLOC;
+    auto at = [&](int i) { return pool + offset[i]; };
+    void* d_temp = at(0);
+    uint16_t* d_key_in = reinterpret_cast<uint16_t*>(at(1));
+    uint16_t* d_key = reinterpret_cast<uint16_t*>(at(2));
+    uint32_t* d_idx_in = reinterpret_cast<uint32_t*>(at(3));  // after the sort: the chunk of every CSR position
+    uint32_t* d_idx = reinterpret_cast<uint32_t*>(at(4));
+    spmv::TwoPhaseTables w{};
+    w.chunk_at = reinterpret_cast<int32_t*>(d_idx_in);
+    w.chunk_of = reinterpret_cast<int32_t*>(at(5));
+    w.first = reinterpret_cast<int32_t*>(at(6));
+    w.last = reinterpret_cast<int32_t*>(at(7));
+    w.padded = reinterpret_cast<int32_t*>(at(8));
+    w.base1 = reinterpret_cast<int32_t*>(at(9));
+    w.within = reinterpret_cast<int32_t*>(at(10));
+    w.in_chunk = reinterpret_cast<int32_t*>(at(11));
+    w.chunk_first = reinterpret_cast<int32_t*>(at(12));
+    w.block_first = reinterpret_cast<int32_t*>(at(13));
     auto release = [&] { (void)hipFree(pool); };
-    std::vector<int32_t> cnt(T), first, base1, base2, piece_c, piece_g, chunk_g;
-    int64_t slots = 0;
-    if (hip_failed(hipMemset(d_cnt, 0, 4 * T)) ||
-        hip_failed(spmv::launch_two_phase_sort(A, shift, static_cast<int>(C), bits, d_temp, temp_bytes, d_key_in, d_key, d_idx_in,
+
+    // sorted entries -> tiles -> prefix sums in both orders, all on the device; the host only needs where the column
+    // blocks start (to cut them into pieces) and the total
+    std::vector<int32_t> block_first(C1), piece_c, piece_g;
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_chunk_g), 4 * P1))) {
+        release();
+        return SPMV_ERR_ALLOC;
+    }
+    if (hip_failed(spmv::launch_two_phase_sort(A, shift, static_cast<int>(C), bits, d_temp, temp_bytes, d_key_in, d_key, d_idx_in,
                                                d_idx, nullptr)) ||
-        hip_failed(spmv::launch_two_phase_count(d_key, d_idx, A.nnz, h->d_tp_desc, static_cast<int32_t>(P),
-                                                reinterpret_cast<int32_t*>(d_idx_in), d_chunk_of, d_cnt, nullptr)) ||
-        hip_failed(hipMemcpy(cnt.data(), d_cnt, 4 * T, hipMemcpyDeviceToHost))) {
+        hip_failed(spmv::launch_two_phase_tables(w, d_key, d_idx, A.nnz, h->d_tp_desc, static_cast<int32_t>(C),
+                                                 static_cast<int32_t>(P), d_temp, temp_bytes, h->d_tp_chunk_g, nullptr)) ||
+        hip_failed(hipMemcpy(block_first.data(), w.block_first, 4 * C1, hipMemcpyDeviceToHost))) {
         release();
         return SPMV_ERR_HIP;
     }
-    if (!spmv::two_phase_tables(C, P, cnt.data(), &first, &base1, &base2, &piece_c, &piece_g, &chunk_g, &slots)) {
-        release();
-        return SPMV_ERR_UNSUPPORTED;
-    }
+    const int64_t slots = block_first[static_cast<size_t>(C)];
+    spmv::two_phase_pieces(C, block_first.data(), &piece_c, &piece_g);
     const size_t S = static_cast<size_t>(slots);
-    if (hip_failed(hipMemcpy(d_first, first.data(), 4 * T, hipMemcpyHostToDevice)) ||
-        hip_failed(hipMemcpy(d_base1, base1.data(), 4 * T, hipMemcpyHostToDevice)) ||
-        hip_failed(hipMemcpy(d_base2, base2.data(), 4 * T, hipMemcpyHostToDevice)))
-        st = SPMV_ERR_HIP;
-    if (st == SPMV_OK) st = upload(piece_c, &h->d_tp_piece_c);
+    st = upload(piece_c, &h->d_tp_piece_c);
     if (st == SPMV_OK) st = upload(piece_g, &h->d_tp_piece_g);
-    if (st == SPMV_OK) st = upload(chunk_g, &h->d_tp_chunk_g);
     if (st == SPMV_OK &&
         (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_col), 2 * S)) ||
          hip_failed(hipMalloc(&h->d_tp_val, (h->dtype == SPMV_F32 ? 4 : 2) * S)) ||
@@ -329,9 +341,8 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_carry_val), 4 * static_cast<size_t>(P)))))
         st = SPMV_ERR_ALLOC;
     if (st == SPMV_OK &&
-        (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(P), d_key, d_idx, d_chunk_of, d_first, d_base1,
-                                                 d_base2, h->d_tp_desc, slots, h->d_tp_col, h->d_tp_val, h->d_tp_src,
-                                                 h->d_tp_dst, h->d_tp_pos, nullptr)) ||
+        (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(P), d_key, d_idx, w, h->d_tp_desc, slots,
+                                                 h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_dst, h->d_tp_pos, nullptr)) ||
          hip_failed(hipDeviceSynchronize())))
         st = SPMV_ERR_HIP;
     release();

@@ -20,6 +20,7 @@
 
 #include <hip/hip_runtime.h>
 #include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_scan.hpp>
 
 #include "device_common.h"
 #include "kernels.h"
@@ -204,24 +205,67 @@ __global__ __launch_bounds__(kWG) void tp_chunk_fill_kernel(const int32_t* __res
     for (int k = chunk_desc[2 * p + 1] + threadIdx.x; k < k1; k += kWG) chunk_at[k] = p;
 }
 
-// q-th entry in (column block, CSR position) order: its chunk, and one more in its tile's count.
-__global__ __launch_bounds__(kWG) void tp_count_kernel(const uint16_t* __restrict__ key, const uint32_t* __restrict__ idx,
-                                                       int nnz, const int32_t* __restrict__ chunk_at, int P,
-                                                       int32_t* __restrict__ chunk_of, int32_t* __restrict__ cnt) {
+// chunk_of[q] = chunk of the q-th entry in (column block, CSR position) order.
+__global__ __launch_bounds__(kWG) void tp_chunk_of_kernel(const uint32_t* __restrict__ idx, int nnz, const int32_t* __restrict__ chunk_at,
+                                                          int32_t* __restrict__ chunk_of) {
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; q < nnz; q += static_cast<int64_t>(gridDim.x) * kWG)
+        chunk_of[q] = chunk_at[idx[q]];
+}
+
+// In that order the tile number c*P + p never decreases, so a tile is a run: first[t] = where it starts,
+// last[t] = where it ends (both stay 0 for a tile without entries).  No counters, no atomics.
+__global__ __launch_bounds__(kWG) void tp_runs_kernel(const uint16_t* __restrict__ key, const int32_t* __restrict__ chunk_of, int nnz,
+                                                      int P, int32_t* __restrict__ first, int32_t* __restrict__ last) {
     for (int64_t q = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; q < nnz; q += static_cast<int64_t>(gridDim.x) * kWG) {
-        const int p = chunk_at[idx[q]];
-        chunk_of[q] = p;
-        atomicAdd(cnt + static_cast<int64_t>(key[q]) * P + p, 1);
+        const int t = key[q] * P + chunk_of[q];
+        const int before = q > 0 ? key[q - 1] * P + chunk_of[q - 1] : -1;
+        const int after = q + 1 < nnz ? key[q + 1] * P + chunk_of[q + 1] : -1;
+        if (t != before) first[t] = static_cast<int32_t>(q);
+        if (t != after) last[t] = static_cast<int32_t>(q + 1);
     }
+}
+
+// padded[t] = the tile's entries rounded up to whole groups of four slots.
+__global__ __launch_bounds__(kWG) void tp_pad_kernel(const int32_t* __restrict__ first, const int32_t* __restrict__ last, int T,
+                                                     int32_t* __restrict__ padded) {
+    for (int t = blockIdx.x * kWG + threadIdx.x; t < T; t += gridDim.x * kWG) padded[t] = (last[t] - first[t] + 3) & ~3;
+}
+
+// One lane per chunk p walks down its column of the (c, p) table: within[c*P + p] = slots of chunk p in the column
+// blocks before c, in_chunk[p] = the chunk's slots (in_chunk[P] = 0 closes the list for the scan that follows).
+__global__ __launch_bounds__(kWG) void tp_chunk_columns_kernel(const int32_t* __restrict__ padded, int C, int P,
+                                                               int32_t* __restrict__ within, int32_t* __restrict__ in_chunk) {
+    const int p = blockIdx.x * kWG + threadIdx.x;
+    if (p > P) return;
+    int run = 0;
+    if (p < P)
+        for (int c = 0; c < C; ++c) {
+            const int64_t t = static_cast<int64_t>(c) * P + p;
+            within[t] = run;
+            run += padded[t];
+        }
+    in_chunk[p] = run;
+}
+
+// block_first[c] = first slot of column block c in the multiply order (block_first[C] = all slots);
+// chunk_g[p] = first group of chunk p in the reduce order (chunk_g[P] = all groups).
+__global__ __launch_bounds__(kWG) void tp_starts_kernel(const int32_t* __restrict__ base1, const int32_t* __restrict__ padded, int C,
+                                                        int P, const int32_t* __restrict__ chunk_first,
+                                                        int32_t* __restrict__ block_first, int32_t* __restrict__ chunk_g) {
+    const int i = blockIdx.x * kWG + threadIdx.x;
+    const int64_t T = static_cast<int64_t>(C) * P;
+    if (i <= C) block_first[i] = i < C ? base1[static_cast<int64_t>(i) * P] : base1[T - 1] + padded[T - 1];
+    if (i <= P) chunk_g[i] = chunk_first[i] >> 2;
 }
 
 struct TpPlaceArgs {
     const uint16_t* key;
     const uint32_t* idx;
     const int32_t* chunk_of;
-    const int32_t* first;  // [C*P] entries in the tiles before tile t (t = c*P + p)
-    const int32_t* base1;  // [C*P] slots before tile t in (c, p) order
-    const int32_t* base2;  // [C*P] slots before tile t in (p, c) order
+    const int32_t* first;        // [C*P] where tile t starts in the sorted order (t = c*P + p)
+    const int32_t* base1;        // [C*P] slots before tile t in (c, p) order
+    const int32_t* within;       // [C*P] slots of t's chunk in the column blocks before t's
+    const int32_t* chunk_first;  // [P+1] slots before each chunk in (p, c) order
     const int32_t* chunk_desc;
     const int32_t* colidx;
     const void* vals;
@@ -241,7 +285,7 @@ __global__ __launch_bounds__(kWG) void tp_place_kernel(const TpPlaceArgs a) {
         const int64_t t = static_cast<int64_t>(c) * a.P + p;
         const int o = static_cast<int>(q) - a.first[t];
         const int s1 = a.base1[t] + o;
-        const int s2 = a.base2[t] + o;
+        const int s2 = a.chunk_first[p] + a.within[t] + o;
         a.tp_col[s1] = static_cast<uint16_t>(static_cast<unsigned>(a.colidx[k]) & ((1u << a.shift) - 1u));
         if (a.elem_bytes == 4) static_cast<float*>(a.tp_val)[s1] = static_cast<const float*>(a.vals)[k];
         else static_cast<uint16_t*>(a.tp_val)[s1] = static_cast<const uint16_t*>(a.vals)[k];
@@ -335,17 +379,43 @@ hipError_t launch_two_phase_sort(const MatrixView& A, int shift, int C, int bits
                                      st);
 }
 
-hipError_t launch_two_phase_count(const uint16_t* key, const uint32_t* idx, int32_t nnz, const int32_t* chunk_desc, int32_t P,
-                                  int32_t* chunk_at, int32_t* chunk_of, int32_t* cnt, hipStream_t st) {
-    hipLaunchKernelGGL(tp_chunk_fill_kernel, dim3(P), dim3(kWG), 0, st, chunk_desc, chunk_at);
-    hipLaunchKernelGGL(tp_count_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, key, idx, nnz, chunk_at, P, chunk_of, cnt);
+size_t two_phase_scan_bytes(int64_t tiles) {
+    size_t bytes = 0;
+    if (rocprim::exclusive_scan(nullptr, bytes, static_cast<const int32_t*>(nullptr), static_cast<int32_t*>(nullptr), int32_t{0},
+                                static_cast<size_t>(tiles), rocprim::plus<int32_t>(), nullptr) != hipSuccess)
+        return 0;
+    return bytes < 16 ? 16 : bytes;
+}
+
+hipError_t launch_two_phase_tables(const TwoPhaseTables& w, const uint16_t* key, const uint32_t* idx, int32_t nnz,
+                                   const int32_t* chunk_desc, int32_t C, int32_t P, void* temp, size_t temp_bytes,
+                                   int32_t* chunk_g, hipStream_t st) {
+    const int64_t T = static_cast<int64_t>(C) * P;
+    hipError_t e;
+    if ((e = hipMemsetAsync(w.first, 0, sizeof(int32_t) * T, st)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(w.last, 0, sizeof(int32_t) * T, st)) != hipSuccess) return e;
+    hipLaunchKernelGGL(tp_chunk_fill_kernel, dim3(P), dim3(kWG), 0, st, chunk_desc, w.chunk_at);
+    hipLaunchKernelGGL(tp_chunk_of_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, idx, nnz, w.chunk_at, w.chunk_of);
+    hipLaunchKernelGGL(tp_runs_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, key, w.chunk_of, nnz, P, w.first, w.last);
+    hipLaunchKernelGGL(tp_pad_kernel, dim3(capped_grid(T)), dim3(kWG), 0, st, w.first, w.last, static_cast<int>(T), w.padded);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    size_t bytes = temp_bytes;
+    if ((e = rocprim::exclusive_scan(temp, bytes, w.padded, w.base1, int32_t{0}, static_cast<size_t>(T), rocprim::plus<int32_t>(),
+                                     st)) != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(tp_chunk_columns_kernel, dim3(ceil_div(P + 1, kWG)), dim3(kWG), 0, st, w.padded, C, P, w.within, w.in_chunk);
+    bytes = temp_bytes;
+    if ((e = rocprim::exclusive_scan(temp, bytes, w.in_chunk, w.chunk_first, int32_t{0}, static_cast<size_t>(P) + 1,
+                                     rocprim::plus<int32_t>(), st)) != hipSuccess)
+        return e;
+    hipLaunchKernelGGL(tp_starts_kernel, dim3(ceil_div((C > P ? C : P) + 1, kWG)), dim3(kWG), 0, st, w.base1, w.padded, C, P,
+                       w.chunk_first, w.block_first, chunk_g);
     return hipGetLastError();
 }
 
 hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, const uint16_t* key, const uint32_t* idx,
-                                  const int32_t* chunk_of, const int32_t* first, const int32_t* base1, const int32_t* base2,
-                                  const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val, int32_t* tp_src,
-                                  int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
+                                  const TwoPhaseTables& w, const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val,
+                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
     // padding first: column = the zero slot after the x block, value 0, no source, position "dropped"
     hipLaunchKernelGGL(tp_fill16_kernel, dim3(capped_grid(slots)), dim3(kWG), 0, st, tp_col, slots,
                        static_cast<uint16_t>(1u << shift));
@@ -354,7 +424,7 @@ hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, con
     if (e != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_src, 0xFF, static_cast<size_t>(slots) * 4, st)) != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_dst, 0, static_cast<size_t>(slots), st)) != hipSuccess) return e;
-    const TpPlaceArgs a{key, idx, chunk_of, first, base1, base2, chunk_desc, A.colidx, A.vals, A.nnz,
+    const TpPlaceArgs a{key, idx, w.chunk_of, w.first, w.base1, w.within, w.chunk_first, chunk_desc, A.colidx, A.vals, A.nnz,
                         P,   shift, A.bf16 ? 2 : 4, tp_col, tp_val, tp_src, tp_dst, tp_pos};
     hipLaunchKernelGGL(tp_place_kernel, dim3(capped_grid(A.nnz)), dim3(kWG), 0, st, a);
     return hipGetLastError();
