@@ -112,7 +112,7 @@ typedef struct {
     int32_t tp_num_col_blocks;         /* C2                                                          */
     int32_t tp_num_chunks;             /* P2: tp_row / tp_nz hold P2+1 entries                        */
     int32_t tp_num_pieces;             /* Q: workgroups of the multiply pass                          */
-    int32_t tp_reserved;               /* 0                                                           */
+    int32_t lidx_grouped;              /* WINDOWED plan: 1 when the window positions are grouped (see analyze)  */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -189,7 +189,11 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     block, AUTO picks WINDOWED when V <= SPMV_MAX_X_VECTORS and 4 * nb * V <= nnz (the kernel
  *     reads the lists at a fixed stride of V per block); a forced WINDOWED plan fails with
  *     UNSUPPORTED when V is larger.  The library then holds 2 bytes per
- *     stored entry of its own (lidx) and run() no longer reads colidx.
+ *     stored entry of its own (lidx) and run() no longer reads colidx.  The positions are
+ *     grouped (lidx_grouped = 1) when every row block starts at a multiple of eight entries and
+ *     every aligned group of eight entries 8g .. 8g+7 (8g+8 <= nnz) has lidx[8g+i] = lidx[8g] + i:
+ *     rows made of aligned runs of columns.  run() then reads one position per group (a copy of
+ *     lidx[8g], 2 bytes per eight entries) and counts the other seven up from it.
  *   - column blocks (plan AUTO that arrived at ADAPTIVE or MERGE, or plan COLBLOCK; built on the
  *     device).  Columns are cut into blocks of W = 4 MiB / element size columns; the entries are
  *     regrouped block after block, keeping their row-major order inside a block, each with its

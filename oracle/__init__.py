@@ -82,6 +82,8 @@ def _load():
         _lib.oracle_x_windows.restype = i64
         _lib.oracle_window_choice.argtypes = [i64, vp, i64, i32]
         _lib.oracle_window_choice.restype = i32
+        _lib.oracle_lidx_grouped.argtypes = [i64, vp, i64, vp, vp]
+        _lib.oracle_lidx_grouped.restype = i32
         _lib.oracle_column_blocks.argtypes = [i64, i64, vp, vp, i64, vp, vp, vp, vp]
         _lib.oracle_column_blocks.restype = i64
         _lib.oracle_column_block_width.argtypes = [i32]
@@ -279,6 +281,13 @@ def x_windows(rowptr, colidx, row_blocks, block_nnz, vec_elems):
 def window_choice(nv, nnz, max_vectors=MAX_X_VECTORS):
     nv = np.ascontiguousarray(nv, dtype=np.int32)
     return bool(_load().oracle_window_choice(nv.size, _p(nv), nnz, max_vectors))
+
+
+def lidx_grouped(rowptr, row_blocks, lidx):
+    """Whether the window positions come in aligned groups of eight consecutive numbers."""
+    lidx = np.ascontiguousarray(lidx, dtype=np.uint16)
+    return bool(_load().oracle_lidx_grouped(int(rowptr[-1]), _p(lidx), row_blocks.size - 1, _p(_chk(row_blocks, np.int32)),
+                                            _p(_chk(rowptr, np.int32))))
 
 
 def column_blocks(m, n, rowptr, colidx, width):

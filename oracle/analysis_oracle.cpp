@@ -258,6 +258,19 @@ int32_t oracle_column_block_choice(int64_t n, int64_t nnz, int32_t elem_bytes, i
     return ((plan == 4 || plan == 5) && n > 2 * width && C <= 16 && nnz >= (int64_t{1} << 22)) ? 1 : 0;
 }
 
+// The window positions are grouped when every row block starts at a multiple of eight entries and every
+// whole aligned group of eight entries 8g .. 8g+7 sits at eight consecutive positions (rows made of aligned
+// runs of columns).  Entries past the last whole group do not matter.
+int32_t oracle_lidx_grouped(int64_t nnz, const uint16_t* lidx, int64_t nb, const int32_t* row_blocks, const int32_t* rowptr) {
+    if (nnz < 8) return 0;
+    for (int64_t b = 0; b < nb; ++b)
+        if (rowptr[row_blocks[b]] % 8 != 0) return 0;
+    for (int64_t g = 0; g < nnz / 8; ++g)
+        for (int64_t i = 1; i < 8; ++i)
+            if (lidx[8 * g + i] != lidx[8 * g] + i) return 0;
+    return 1;
+}
+
 // ---- the two-pass layout ---------------------------------------------------------------
 // Column blocks of 2^shift columns (C of them); chunks = the stretches of the CSR entry list
 // between consecutive merge-path splits taken every `items` steps (P of them).  Tile (c, p) =

@@ -57,6 +57,7 @@ struct spmv_csr_s {
     int32_t* d_xv_start = nullptr;
     int32_t* d_xv_pad = nullptr;
     uint16_t* d_lidx = nullptr;
+    uint16_t* d_lidx8 = nullptr;  // lidx[8g], kept when the window positions are grouped (info.lidx_grouped)
     // the two-pass plan (TWOPHASE)
     int32_t* d_tp_desc = nullptr;     // pairs (tp_row[p], tp_nz[p])
     int32_t* d_tp_piece_c = nullptr;
@@ -87,7 +88,7 @@ void free_metadata(spmv_csr_s* h) {
                     h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
                     h->d_spmm_val,  h->d_tp_desc,   h->d_tp_piece_c, h->d_tp_piece_g, h->d_tp_chunk_g,
                     h->d_tp_col,    h->d_tp_val,    h->d_tp_src,    h->d_tp_dst,    h->d_tp_pos,
-                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val};
+                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val, h->d_lidx8};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_tp_desc = h->d_tp_piece_c = h->d_tp_piece_g = h->d_tp_chunk_g = h->d_tp_src = h->d_tp_dst = nullptr;
@@ -103,7 +104,7 @@ void free_metadata(spmv_csr_s* h) {
     h->d_cb_row = h->d_cb_col = h->d_cb_src = nullptr;
     h->d_cb_vals = nullptr;
     h->cb_ptr.clear();
-    h->d_lidx = nullptr;
+    h->d_lidx = h->d_lidx8 = nullptr;
     h->d_spmm_rows = h->d_spmm_desc = nullptr;
     h->d_spmm_col = nullptr;
     h->d_spmm_val = nullptr;
@@ -185,6 +186,31 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, bool count_only, const
     if (hip_failed(spmv::launch_window_build(A, h->d_block_nz, static_cast<int32_t>(nb), a->info.block_nnz, true, nullptr,
                                              h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, x_cap, h->d_lidx, nullptr)))
         return SPMV_ERR_HIP;
+    // Grouped positions: every aligned group of eight entries inside one row block (all blocks start at a multiple
+    // of eight) and at eight consecutive window positions.  The kernel then reads one position per group.
+    bool aligned_blocks = h->nnz >= 8;
+    for (int64_t b = 0; b < nb && aligned_blocks; ++b)
+        aligned_blocks = rowptr_host[static_cast<size_t>(a->row_blocks[static_cast<size_t>(b)])] % 8 == 0;
+    if (aligned_blocks) {
+        const int32_t groups = static_cast<int32_t>(h->nnz / 8);
+        int32_t* d_flag = nullptr;
+        int32_t flag = 0;
+        if (hip_failed(hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t))) ||
+            hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_lidx8), sizeof(uint16_t) * static_cast<size_t>(groups)))) {
+            (void)hipFree(d_flag);
+            return SPMV_ERR_ALLOC;
+        }
+        bool failed = hip_failed(hipMemcpy(d_flag, &flag, sizeof flag, hipMemcpyHostToDevice));
+        failed = failed || hip_failed(spmv::launch_lidx_groups(h->d_lidx, groups, h->d_lidx8, d_flag, nullptr));
+        failed = failed || hip_failed(hipMemcpy(&flag, d_flag, sizeof flag, hipMemcpyDeviceToHost));
+        (void)hipFree(d_flag);
+        if (failed) return SPMV_ERR_HIP;
+        if (flag != 0) {
+            (void)hipFree(h->d_lidx8);
+            h->d_lidx8 = nullptr;
+        }
+        a->info.lidx_grouped = flag == 0 ? 1 : 0;
+    }
     a->info.plan = SPMV_PLAN_WINDOWED;
     a->info.num_x_vectors = total;
     return SPMV_OK;
@@ -591,7 +617,7 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
                                       h->info.block_nnz, h->info.rows_max, x, y, s, st);
             break;
         case SPMV_PLAN_WINDOWED: {
-            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx, h->info.max_x_vectors};
+            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx8, h->d_lidx, h->info.max_x_vectors};
             e = spmv::launch_windowed(A, h->d_block_desc, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->max_block_entries, h->info.rows_max, w, x, y, s, st);
             break;

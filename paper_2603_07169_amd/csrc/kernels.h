@@ -25,6 +25,7 @@ struct XWindows {
     const int32_t* xv_ptr;    // [nb+1]
     const int32_t* xv_start;  // [xv_ptr[nb]]
     const int32_t* xv_pad;    // [nb * max_vectors] xv_start at a fixed stride per block, -1 padded: what the kernel reads
+    const uint16_t* lidx8;    // [nnz / 8] lidx[8g] where the positions are grouped (see launch_lidx_groups), else null
     const uint16_t* lidx;     // [nnz rounded up to a multiple of 8]
     int32_t max_vectors;      // largest xv_ptr[b+1] - xv_ptr[b]
 };
@@ -79,6 +80,9 @@ hipError_t launch_spmm_pack(const MatrixView& A, const int32_t* rows, const int3
 hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const float* B, int64_t ldb, float* C, int64_t ldc,
                               int32_t K, Scalars s, hipStream_t st);
 const char* spmm_packed_kernel_name();
+// Whole aligned groups of eight entries (groups = nnz / 8): lidx8[g] = lidx[8g]; *flag (device int32, 0 on entry) is set to 1
+// if some group's eight positions are not consecutive numbers.
+hipError_t launch_lidx_groups(const uint16_t* lidx, int32_t groups, uint16_t* lidx8, int32_t* flag, hipStream_t st);
 // flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st);
 

@@ -166,6 +166,7 @@ struct TileArgs {
     // what a workgroup needs before its first vector load comes first, in one stretch
     int32_t nparts, x_cap, tile_cap, nnz;
     const int32_t* xv_pad;     // window kernel: [nparts * x_cap] first element of each 16-byte x vector of a block, -1 padded
+    const uint16_t* lidx8;     // window kernel, grouped positions: [nnz/8] lidx[8g], the first of every aligned group of eight
     const uint16_t* lidx;      // window kernel: [nnz, padded to a multiple of 8] position of each entry's x value in the block's window
     const int32_t* part_desc;  // [2*(nparts+1)] pairs (row, entry): first row and first entry of each row block, or rows
                                // finished and entries taken at each merge-path split
@@ -355,7 +356,10 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
 // phase issues no global load at all.  A block that is one over-long row takes the global path.
 // XPL: x vectors a lane fetches (x_cap <= XPL*WG); NG: 8-entry groups a lane stages in the
 // first, branch-free round (blocks of up to NG*WG*8 - 7 entries need no second round).
-template <typename T, int WG, int XPL, int NG>
+// GROUPED: the analysis found every aligned group of eight entries at eight consecutive window
+// positions (rows made of aligned runs of columns): one 16-bit position per group is read instead
+// of eight, and the other seven are counted up from it.
+template <typename T, int WG, int XPL, int NG, bool GROUPED>
 __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window_kernel(const TileArgs a) {
     using E = typename T::elem;
     constexpr int XE = 16 / sizeof(E);  // elements per x vector
@@ -437,7 +441,12 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
         const uint16_t* lp = g.vec ? a.lidx + k : dummy;
         g.v0 = load_val8(vp);
         if constexpr (sizeof(E) == 4) g.v1 = load_val8(g.vec ? vp + 8 : dummy);
-        g.l = load_val8(lp);
+        if constexpr (GROUPED) {
+            const unsigned both = static_cast<unsigned>(*(g.vec ? a.lidx8 + (k >> 3) : dummy)) * 0x10001u;  // the position in both halves
+            g.l = u32x4{both + 0x00010000u, both + 0x00030002u, both + 0x00050004u, both + 0x00070006u};
+        } else {
+            g.l = load_val8(lp);
+        }
     };
     auto store_group = [&](int off, const Group& g) {
         if (g.vec) {
@@ -645,6 +654,21 @@ __global__ __launch_bounds__(kWG) void merge_fixup_kernel(const int32_t* __restr
     y[r] += alpha * s;
 }
 
+// lidx8[g] = lidx[8g] for every whole aligned group of eight entries; *flag = 1 if some group's positions are not
+// eight consecutive numbers (then lidx8 is of no use).
+__global__ __launch_bounds__(kWG) void lidx_groups_kernel(const uint16_t* __restrict__ lidx, int groups, uint16_t* __restrict__ lidx8,
+                                                          int32_t* flag) {
+    bool bad = false;
+    for (int g = blockIdx.x * kWG + threadIdx.x; g < groups; g += gridDim.x * kWG) {
+        const u32x4 l = *reinterpret_cast<const u32x4*>(lidx + 8 * static_cast<int64_t>(g));
+        const unsigned both = (l[0] & 0xFFFFu) * 0x10001u;
+        bad = bad || l[0] != both + 0x00010000u || l[1] != both + 0x00030002u || l[2] != both + 0x00050004u ||
+              l[3] != both + 0x00070006u;
+        lidx8[g] = static_cast<uint16_t>(l[0] & 0xFFFFu);
+    }
+    if (bad) *flag = 1;
+}
+
 __global__ __launch_bounds__(kWG) void validate_columns_kernel(const int32_t* __restrict__ colidx, int nnz, int n,
                                                                int32_t* flag) {
     bool bad = false;
@@ -774,9 +798,9 @@ hipError_t launch_tiles(const TileArgs& a, size_t lds, hipStream_t st) {
     return launch_tiles_wg<T, MERGE, 256>(a, lds, st);
 }
 
-template <typename T, int XPL, int NG>
-hipError_t launch_window_k(const TileArgs& a, size_t lds, hipStream_t st) {
-    auto kernel = spmv_window_kernel<T, 256, XPL, NG>;
+template <typename T, int XPL, int NG, bool GROUPED>
+hipError_t launch_window_g(const TileArgs& a, size_t lds, hipStream_t st) {
+    auto kernel = spmv_window_kernel<T, 256, XPL, NG, GROUPED>;
     if (lds > 64 * 1024) {
         static thread_local size_t allowed = 0;
         if (lds > allowed) {
@@ -791,6 +815,11 @@ hipError_t launch_window_k(const TileArgs& a, size_t lds, hipStream_t st) {
 }
 
 // Picks the instantiation whose fixed first round of loads just covers the blocks.
+template <typename T, int XPL, int NG>
+hipError_t launch_window_k(const TileArgs& a, size_t lds, hipStream_t st) {
+    return a.lidx8 ? launch_window_g<T, XPL, NG, true>(a, lds, st) : launch_window_g<T, XPL, NG, false>(a, lds, st);
+}
+
 template <typename T>
 hipError_t launch_window_t(const TileArgs& a, int staged_max, size_t lds, hipStream_t st) {
     const bool one_group = staged_max + 7 <= 256 * 8;  // a block's span starts up to 7 entries early
@@ -827,6 +856,7 @@ hipError_t launch_windowed(const MatrixView& A, const int32_t* block_desc, int32
     a.tile_cap = block_nnz;
     a.xv_pad = w.xv_pad;
     a.lidx = w.lidx;
+    a.lidx8 = w.lidx8;
     a.x_cap = w.max_vectors > 0 ? w.max_vectors : 1;
     a.x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 ? 1 : 0;
     const size_t esz = A.bf16 ? 2 : 4;
@@ -872,6 +902,13 @@ hipError_t launch_merge_fixup(const int32_t* carry_row, const float* carry_val, 
                               hipStream_t st) {
     if (P <= 0) return hipSuccess;
     hipLaunchKernelGGL(merge_fixup_kernel, dim3(ceil_div(P, kWG)), dim3(kWG), 0, st, carry_row, carry_val, P, y, alpha);
+    return hipGetLastError();
+}
+
+hipError_t launch_lidx_groups(const uint16_t* lidx, int32_t groups, uint16_t* lidx8, int32_t* flag, hipStream_t st) {
+    if (groups <= 0) return hipSuccess;
+    const int grid = ceil_div(groups, kWG);
+    hipLaunchKernelGGL(lidx_groups_kernel, dim3(grid > 8192 ? 8192 : grid), dim3(kWG), 0, st, lidx, groups, lidx8, flag);
     return hipGetLastError();
 }
 

@@ -47,7 +47,7 @@ class spmv_analysis_info_t(C.Structure):
                 ("col_block_width", C.c_int32), ("spmm_prepared", C.c_int32), ("spmm_col_bytes", C.c_int32),
                 ("spmm_num_blocks", C.c_int64), ("tp_slots", C.c_int64), ("tp_col_shift", C.c_int32),
                 ("tp_items", C.c_int32), ("tp_num_col_blocks", C.c_int32), ("tp_num_chunks", C.c_int32),
-                ("tp_num_pieces", C.c_int32), ("tp_reserved", C.c_int32)]
+                ("tp_num_pieces", C.c_int32), ("lidx_grouped", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}

@@ -64,6 +64,7 @@ def test_full_config_matches_oracle(k):
         A = d.matrix(dict(plan=s.SPMV_PLAN_MERGE))      # the merge plan, which AUTO no longer picks here
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full merge")
     if plan == "windowed":
+        assert A.info.lidx_grouped == (1 if k == 5 else 0)      # config 5's rows are aligned runs of eight columns
         # x windows: 300 sampled row blocks (first, last, random), each against the oracle run on that block alone
         rb, xv_ptr = got["row_blocks"], got["xv_ptr"]
         nb = rb.size - 1

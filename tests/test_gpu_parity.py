@@ -183,12 +183,41 @@ def check_windows_equal_oracle(p, A):
     assert np.array_equal(got["xv_ptr"], xv_ptr)
     assert np.array_equal(got["xv_start"], xv_start)
     assert np.array_equal(got["lidx"], lidx)
+    assert A.info.lidx_grouped == int(oracle.lidx_grouped(p.rowptr, got["row_blocks"], lidx))
     # the fixed-stride copy: block b's vectors at b*V, then -1
     V = max(1, int(A.info.max_x_vectors))
     pad = np.full((nv.size, V), -1, np.int32)
     for b in range(nv.size):
         pad[b, :nv[b]] = xv_start[xv_ptr[b]:xv_ptr[b + 1]]
     assert np.array_equal(got["xv_pad"].reshape(nv.size, V), pad)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ["whole", "tail", "one_off", "shifted"])
+def test_grouped_window_positions(dtype, shape):
+    """Rows made of aligned runs of eight columns: one window position per group of eight entries is read.  With a
+    tail of fewer than eight entries it still is (the tail goes element by element); with one run broken by a
+    skipped column, or every block start moved off the multiples of eight, it is not.  Product against the oracle each time."""
+    p = w.block_clustered(m=5000, n=40_000, blocks_per_row=12, width=8, dtype=dtype, alpha=1.5, beta=0.25)
+    rowptr, colidx, vals = p.rowptr.copy(), p.colidx.copy(), p.vals.copy()
+    if shape == "tail":                       # the last row loses three entries
+        rowptr[-1] -= 3
+        colidx, vals = colidx[:-3], vals[:-3]
+    elif shape == "one_off":                  # one run of eight skips a column: its last entry sits one further
+        colidx[96 * 2500 + 8 + 7] += 1
+    elif shape == "shifted":                  # the first row loses its first entry: every later row starts off the multiples of eight
+        rowptr[1:] -= 1
+        colidx, vals = colidx[1:], vals[1:]
+    q = w.CsrProblem(p.name + "_" + shape, p.dtype, p.m, p.n, rowptr, colidx, vals, p.x, p.y0, p.alpha, p.beta)
+    log("case grouped positions", dtype, shape, q.nnz)
+    d = DeviceProblem(q)
+    A = d.matrix(plan_params(s.SPMV_PLAN_WINDOWED))
+    assert A.info.plan == s.SPMV_PLAN_WINDOWED
+    assert A.info.lidx_grouped == (1 if shape in ("whole", "tail") else 0)
+    check_windows_equal_oracle(q, A)
+    y_ref, S_ref = reference(q)
+    assert_close(q, d.run(A), y_ref, S_ref, q.alpha, q.beta)
+    A.close()
 
 
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 5])

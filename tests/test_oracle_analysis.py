@@ -302,6 +302,22 @@ def test_column_block_choice_rule():
     assert not f(4_000_000, 31_000_000, "f32", 5, vectors=-1, entries=-2)        # not counted: no
 
 
+def test_lidx_grouped_handworked():
+    rowptr = np.array([0, 8, 16, 20], np.int32)                       # 20 entries: two whole groups and a tail of four
+    blocks = np.array([0, 1, 3], np.int32)                            # blocks start at entries 0 and 8
+    run = np.arange(8)
+    good = np.concatenate([run + 3, run + 40, [9, 9, 0, 1]])          # consecutive, from any start; the tail does not matter
+    assert oracle.lidx_grouped(rowptr, blocks, good)
+    for k in (1, 7, 9, 15):
+        bad = good.copy()
+        bad[k] += 1
+        assert not oracle.lidx_grouped(rowptr, blocks, bad), k
+    assert not oracle.lidx_grouped(np.array([0, 4, 16, 20], np.int32), blocks, good)         # a block starting at entry 4
+    assert oracle.lidx_grouped(np.array([0, 4, 16, 20], np.int32), np.array([0, 2, 3], np.int32), good)   # ... unless no block starts there
+    assert not oracle.lidx_grouped(np.array([0, 7], np.int32), np.array([0, 1], np.int32), np.arange(7))  # no whole group
+    assert oracle.lidx_grouped(np.array([0, 8], np.int32), np.array([0, 1], np.int32), np.arange(8))
+
+
 # ------------------------------------------------------------------ the two-pass layout
 TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos")
 

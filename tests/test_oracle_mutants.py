@@ -49,6 +49,10 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (max_len > block_nnz) return 5;", "if (max_len >= block_nnz) return 5;", "plan rule off by one"),
     ("analysis_oracle.cpp", "while (G < 64 && 8 * static_cast<int64_t>(G) < mean_up) G *= 2;", "while (G < 64 && 8 * static_cast<int64_t>(G) <= mean_up) G *= 2;", "vector lanes off by one"),
     ("analysis_oracle.cpp", "n > 2 * width && C <= 16", "n >= 2 * width && C <= 16", "column block rule off by one"),
+    ("analysis_oracle.cpp", "if (rowptr[row_blocks[b]] % 8 != 0) return 0;", ";", "grouped positions: block starts not checked"),
+    ("analysis_oracle.cpp", "for (int64_t i = 1; i < 8; ++i)\n            if (lidx[8 * g + i] != lidx[8 * g] + i) return 0;", "for (int64_t i = 1; i < 7; ++i)\n            if (lidx[8 * g + i] != lidx[8 * g] + i) return 0;", "grouped positions: last of a group not checked"),
+    ("analysis_oracle.cpp", "for (int64_t g = 0; g < nnz / 8; ++g)\n        for (int64_t i = 1; i < 8; ++i)", "for (int64_t g = 0; g < (nnz + 7) / 8; ++g)\n        for (int64_t i = 1; i < 8; ++i)", "grouped positions: the tail taken for a group"),
+    ("analysis_oracle.cpp", "if (nnz < 8) return 0;\n    for (int64_t b = 0; b < nb; ++b)\n        if (rowptr[row_blocks[b]] % 8", "if (nnz < 0) return 0;\n    for (int64_t b = 0; b < nb; ++b)\n        if (rowptr[row_blocks[b]] % 8", "grouped positions: fewer than eight entries accepted"),
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;  // clustered", "column block rule: scatter threshold off by one"),
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (4 * vectors < 3 * entries) return 0;  // clustered", "column block rule: uncounted windows taken for scattered"),
     ("analysis_oracle.cpp", "col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));", "col[s1] = static_cast<uint16_t>(colidx[k]);", "two-pass: column not made relative to its block"),
