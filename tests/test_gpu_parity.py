@@ -193,7 +193,7 @@ def check_windows_equal_oracle(p, A):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("shape", ["whole", "tail", "one_off", "shifted"])
+@pytest.mark.parametrize("shape", ["whole", "unaligned", "tail", "one_off", "shifted"])
 def test_grouped_window_positions(dtype, shape):
     """Rows made of aligned runs of eight columns: one window position per group of eight entries is read.  With a
     tail of fewer than eight entries it still is (the tail goes element by element); with one run broken by a
@@ -210,10 +210,10 @@ def test_grouped_window_positions(dtype, shape):
         colidx, vals = colidx[1:], vals[1:]
     q = w.CsrProblem(p.name + "_" + shape, p.dtype, p.m, p.n, rowptr, colidx, vals, p.x, p.y0, p.alpha, p.beta)
     log("case grouped positions", dtype, shape, q.nnz)
-    d = DeviceProblem(q)
+    d = DeviceProblem(q, offset_elems=1 if shape == "unaligned" else 0)   # vals, colidx and x one element off their allocations
     A = d.matrix(plan_params(s.SPMV_PLAN_WINDOWED))
     assert A.info.plan == s.SPMV_PLAN_WINDOWED
-    assert A.info.lidx_grouped == (1 if shape in ("whole", "tail") else 0)
+    assert A.info.lidx_grouped == (1 if shape in ("whole", "unaligned", "tail") else 0)
     check_windows_equal_oracle(q, A)
     y_ref, S_ref = reference(q)
     assert_close(q, d.run(A), y_ref, S_ref, q.alpha, q.beta)
