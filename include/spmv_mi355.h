@@ -306,6 +306,25 @@ spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* c
  * Errors: INVALID_ARG (null handle), NOT_ANALYZED, HIP. */
 spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  The product y <- alpha*A*x + beta*y of spmv_csr_run() under the MERGE plan (items_per_chunk 2048),
+ * without a handle and without an analysis step: the merge-path splits are found by a small kernel, then the same
+ * kernels run, so the result equals that of spmv_csr_run() on a handle analyzed with plan MERGE bit for bit.  Calls
+ * no hipMalloc / hipFree and nothing else that allocates: the splits and the carries of cut rows (16 bytes per chunk of
+ * 2048 steps) go to a fixed 2 MiB array in device memory that every GPU the library runs on holds until the process
+ * ends, which limits the size to  m + nnz <= SPMV_STATIC_MAX_ITEMS  (larger: UNSUPPORTED, nothing is enqueued).
+ * All calls on one GPU share that array: calls that overlap on one GPU (two streams, two threads) race; calls on one
+ * stream, or ordered by events, are safe.  Nothing in the array has to be cleared between calls.
+ *   rowptr / colidx / vals / x / y  DEVICE pointers as for spmv_csr_create() and spmv_csr_run(), borrowed until the
+ *   enqueued work has finished.  The structure is NOT checked: rowptr must be non-decreasing from 0 to nnz and every
+ *   column must lie in [0, n).  m == 0 is a no-op; nnz == 0 gives y <- beta*y.  Enqueues on `stream`, no synchronisation.
+ * Errors: INVALID_ARG (null pointer with a non-empty array, negative size, unknown dtype), UNSUPPORTED (too large,
+ * misaligned pointer), HIP. */
+#define SPMV_STATIC_MAX_ITEMS (((int64_t)1 << 28) - 2048)
+spmv_status_t spmv_csr_run_static(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr, const int32_t* colidx,
+                                  const void* vals, spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta,
+                                  void* stream);
+
 /* Frees the handle and the library-owned device metadata.  spmv_destroy(NULL) is OK. */
 spmv_status_t spmv_destroy(spmv_handle_t h);
 

@@ -2,13 +2,15 @@
 from __future__ import annotations
 
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB_PATH = PKG / "libspmv_mi355.so"
-SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "colblock.hip", CSRC / "twophase.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
+OBJ = PKG / "_build"   # objects only; never committed
+SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "colblock.hip", CSRC / "twophase.hip", CSRC / "static_scratch.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
 HEADERS = [CSRC / "kernels.h", CSRC / "device_common.h", CSRC / "row_phase.h", CSRC / "analysis.h", INCLUDE / "spmv_mi355.h"]
 
 HIPCC_FLAGS = [
@@ -25,9 +27,7 @@ def is_stale() -> bool:
     return any(p.stat().st_mtime > t for p in SOURCES + HEADERS)
 
 
-def build(verbose: bool = False) -> Path:
-    cmd = ["hipcc", *HIPCC_FLAGS, f"-I{INCLUDE}", f"-I{CSRC}", "-x", "hip",
-           *[str(s) for s in SOURCES], "-o", str(LIB_PATH)]
+def _run(cmd, verbose):
     r = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass does not know the gfx feature name and says so once per file: harmless
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
@@ -36,8 +36,28 @@ def build(verbose: bool = False) -> Path:
         print(r.stdout + err)
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + err)
+
+
+def build(verbose: bool = False, incremental: bool = False) -> Path:
+    """Compiles every source to an object of its own (in parallel) and links them.  incremental: sources older than
+    their object and than every header are not compiled again (for work on one file; the default compiles all)."""
+    OBJ.mkdir(exist_ok=True)
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    newest_header = max(p.stat().st_mtime for p in HEADERS)
+    jobs = []
+    for src in SOURCES:
+        obj = OBJ / (src.name + ".o")
+        if incremental and obj.exists() and obj.stat().st_mtime > max(src.stat().st_mtime, newest_header):
+            continue
+        jobs.append(["hipcc", *compile_flags, f"-I{INCLUDE}", f"-I{CSRC}", "-x", "hip", "-c", str(src), "-o", str(obj)])
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as pool:
+        for f in [pool.submit(_run, cmd, verbose) for cmd in jobs]:
+            f.result()
+    _run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-pthread",
+          *[str(OBJ / (s.name + ".o")) for s in SOURCES], "-o", str(LIB_PATH)], verbose)
     return LIB_PATH
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build(verbose="-v" in sys.argv, incremental="-i" in sys.argv))

@@ -25,6 +25,10 @@ constexpr int64_t kMaxCount = SPMV_MAX_SIZE;  // an index plus a grid stride (at
 
 }  // namespace
 
+namespace spmv {
+bool note_hip_error(hipError_t e) { return hip_failed(e); }
+}  // namespace spmv
+
 struct spmv_csr_s {
     int64_t m = 0, n = 0, nnz = 0;
     const int32_t* rowptr = nullptr;

@@ -34,6 +34,9 @@ struct Scalars {
     float alpha, beta;
 };
 
+// Records a failing HIP call for spmv_last_hip_error() and clears the runtime's sticky error; true when e is an error.
+bool note_hip_error(hipError_t e);
+
 // rows == nullptr: rows 0..count-1; otherwise the `count` row ids listed in rows[].
 hipError_t launch_scalar(const MatrixView& A, const int32_t* rows, int32_t count, const void* x, float* y, Scalars s,
                          hipStream_t st);

@@ -24,9 +24,10 @@ PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5
 SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 SPMV_MAX_SIZE = 2 ** 31 - 2 ** 22
+SPMV_STATIC_MAX_ITEMS = 2 ** 28 - 2048
 
 EXPORTS = [
-    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_csr_refresh_values", "spmm_csr_run", "spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_destroy", "spmv_csr_get_analysis_info",
+    "spmv_csr_create", "spmv_csr_analyze", "spmv_csr_run", "spmv_csr_refresh_values", "spmm_csr_run", "spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_csr_run_static", "spmv_destroy", "spmv_csr_get_analysis_info",
     "spmv_csr_get_analysis", "spmv_analyze_host", "spmv_selftest_reduce", "spmv_csr_main_kernel_name",
     "spmv_status_string", "spmv_last_hip_error",
 ]
@@ -93,7 +94,8 @@ def _load():
     lib.spmv_coo_run.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp]
     lib.spmv_csc_run.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp]
     lib.spmv_ell_run.argtypes = [i64, i64, i64, vp, vp, C.c_int, vp, vp, f32, f32, vp]
-    for name in ("spmv_coo_run", "spmv_csc_run", "spmv_ell_run"):
+    lib.spmv_csr_run_static.argtypes = [i64, i64, i64, vp, vp, vp, C.c_int, vp, vp, f32, f32, vp]
+    for name in ("spmv_coo_run", "spmv_csc_run", "spmv_ell_run", "spmv_csr_run_static"):
         getattr(lib, name).restype = C.c_int
     lib.spmv_destroy.argtypes = [vp]
     lib.spmv_csr_refresh_values.argtypes = [vp, vp]
@@ -165,6 +167,10 @@ def spmv_csc_run(m, n, nnz, col_offsets, row_indices, vals, dtype, x, y, alpha, 
 
 def spmv_ell_run(m, n, width, col_ids, vals, dtype, x, y, alpha, beta, stream=None):
     return _load().spmv_ell_run(m, n, width, col_ids, vals, dtype, x, y, alpha, beta, stream)
+
+
+def spmv_csr_run_static(m, n, nnz, rowptr, colidx, vals, dtype, x, y, alpha, beta, stream=None):
+    return _load().spmv_csr_run_static(m, n, nnz, rowptr, colidx, vals, dtype, x, y, alpha, beta, stream)
 
 
 def spmv_csr_refresh_values(handle, stream=None):

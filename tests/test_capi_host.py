@@ -84,6 +84,16 @@ def test_size_limit_matches_the_header_and_binds_every_entry_point():
     assert s.spmv_csc_run(4, big + 1, 8, A, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
     assert s.spmv_ell_run(4, 4, big + 1, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
     assert s.spmv_ell_run(4, 4, -1, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    # the entry point with the fixed scratch array: its own, smaller limit on rows + entries, checked on the host first
+    mm = re.search(r"#define SPMV_STATIC_MAX_ITEMS \(\(\(int64_t\)1 << (\d+)\) - (\d+)\)", header)
+    lim = (1 << int(mm.group(1))) - int(mm.group(2))
+    assert lim == s.SPMV_STATIC_MAX_ITEMS and lim % DEFAULT_ITEMS_PER_CHUNK == 0
+    assert 16 * (lim // DEFAULT_ITEMS_PER_CHUNK) + 8 <= 2 << 20          # splits + carries of every chunk fit the 2 MiB array
+    assert s.spmv_csr_run_static(lim // 2, 4, lim - lim // 2 + 1, A, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED
+    assert s.spmv_csr_run_static(-1, 4, 8, A, A, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    assert s.spmv_csr_run_static(4, 4, 8, A, A, A, 2, A, A, 1.0, 0.0) == s.SPMV_ERR_INVALID_ARG
+    assert s.spmv_csr_run_static(0, 4, 0, None, None, None, 0, None, None, 1.0, 0.0) == s.SPMV_OK
+    assert s.spmv_csr_run_static(4, 4, 8, A, A + 2, A, 0, A, A, 1.0, 0.0) == s.SPMV_ERR_UNSUPPORTED    # misaligned colidx
 
 
 def test_analyze_parameter_ranges():
