@@ -24,6 +24,7 @@ NUM_BINS = 33
 PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock", 8: "twophase"}
 TP_SHIFT, TP_ITEMS, TP_PIECE_GROUPS = 14, 8192, 8192
 MAX_X_VECTORS = 1024
+MAX_PATTERN_RUNS, MAX_PATTERN_LEN = 4, 64
 
 
 def build(force: bool = True) -> Path:
@@ -84,6 +85,10 @@ def _load():
         _lib.oracle_window_choice.restype = i32
         _lib.oracle_lidx_grouped.argtypes = [i64, vp, i64, vp, vp]
         _lib.oracle_lidx_grouped.restype = i32
+        _lib.oracle_row_patterns.argtypes = [i64, vp, vp, vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
+        _lib.oracle_row_patterns.restype = i64
+        _lib.oracle_pattern_choice.argtypes = [i64, i64]
+        _lib.oracle_pattern_choice.restype = i32
         _lib.oracle_column_blocks.argtypes = [i64, i64, vp, vp, i64, vp, vp, vp, vp]
         _lib.oracle_column_blocks.restype = i64
         _lib.oracle_column_block_width.argtypes = [i32]
@@ -288,6 +293,32 @@ def lidx_grouped(rowptr, row_blocks, lidx):
     lidx = np.ascontiguousarray(lidx, dtype=np.uint16)
     return bool(_load().oracle_lidx_grouped(int(rowptr[-1]), _p(lidx), row_blocks.size - 1, _p(_chk(row_blocks, np.int32)),
                                             _p(_chk(rowptr, np.int32))))
+
+
+def row_patterns(rowptr, row_blocks, lidx, block_nnz, max_runs=MAX_PATTERN_RUNS, max_len=MAX_PATTERN_LEN):
+    """Runs of rows whose window positions repeat with a constant step.  Returns a dict: n_runs[nb]; run_rows, run_len,
+    run_base, run_stride, each [nb, max_runs]; pat_ptr[nb+1], pat[pat_ptr[nb]]; covered (entries of patterned blocks)."""
+    lib = _load()
+    _chk(rowptr, np.int32), _chk(row_blocks, np.int32)
+    lidx = np.ascontiguousarray(lidx, dtype=np.uint16)
+    nb = row_blocks.size - 1
+    out = dict(n_runs=np.zeros(max(nb, 1), np.int32))
+    for name in ("run_rows", "run_len", "run_base", "run_stride"):
+        out[name] = np.zeros((max(nb, 1), max_runs), np.int32)
+    pat_ptr = np.zeros(nb + 1, np.int32)
+    args = (nb, _p(row_blocks), _p(rowptr), _p(lidx), block_nnz, max_runs, max_len, _p(out["n_runs"]), _p(out["run_rows"]),
+            _p(out["run_len"]), _p(out["run_base"]), _p(out["run_stride"]), _p(pat_ptr))
+    covered = lib.oracle_row_patterns(*args, None)
+    pat = np.zeros(max(int(pat_ptr[-1]), 1), np.uint16)
+    assert lib.oracle_row_patterns(*args, _p(pat)) == covered
+    for name in ("n_runs", "run_rows", "run_len", "run_base", "run_stride"):
+        out[name] = out[name][:nb]
+    out.update(pat_ptr=pat_ptr, pat=pat[: int(pat_ptr[-1])], covered=int(covered))
+    return out
+
+
+def pattern_choice(nnz, covered):
+    return bool(_load().oracle_pattern_choice(nnz, covered))
 
 
 def column_blocks(m, n, rowptr, colidx, width):

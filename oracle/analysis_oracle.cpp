@@ -271,6 +271,88 @@ int32_t oracle_lidx_grouped(int64_t nnz, const uint16_t* lidx, int64_t nb, const
     return 1;
 }
 
+// ---- row patterns of the window positions -----------------------------------------------
+// Inside a row block of a stencil the window positions of one row are those of the row before, moved on by a
+// constant.  Row i of a block (entries k_i .. k_i + len_i - 1) has
+//   base_i = lidx[k_i]  (0 for an empty row),   rel_i[j] = lidx[k_i + j] - base_i   (j = 0 .. len_i - 1).
+// A run is a stretch of consecutive rows of the block, found greedily from the block's first row on: the run that
+// holds row i - 1 also takes row i when len_i = len_{i-1}, rel_i = rel_{i-1} and, if the run already has two rows
+// or more, base_i - base_{i-1} equals the step between those (the run's stride; a run of one row has stride 0).
+// The block is patterned when it is staged (at most block_nnz entries), no row is longer than max_len, no rel is
+// negative (a row's first entry sits lowest in the window) and it has at most max_runs runs.  Then, for its runs
+// r = 0 .. n_runs[b] - 1, slot q = b * max_runs + r holds run_rows[q] (rows in the run), run_len[q] (entries per row),
+// run_base[q] (base of its first row) and run_stride[q]; the block's pattern list is rel of the first row of run 0,
+// then of run 1, ..., pat_ptr[b] .. pat_ptr[b+1] - 1 in pat (which may be null: sizes only).  A block that is not
+// patterned has n_runs 0, zeros in its slots and no pattern entries.  Returns the entries held by patterned blocks.
+int64_t oracle_row_patterns(int64_t nb, const int32_t* row_blocks, const int32_t* rowptr, const uint16_t* lidx, int32_t block_nnz,
+                            int32_t max_runs, int32_t max_len, int32_t* n_runs, int32_t* run_rows, int32_t* run_len,
+                            int32_t* run_base, int32_t* run_stride, int32_t* pat_ptr, uint16_t* pat) {
+    int64_t covered = 0;
+    pat_ptr[0] = 0;
+    for (int64_t b = 0; b < nb; ++b) {
+        const int64_t first = row_blocks[b], last = row_blocks[b + 1];
+        for (int r = 0; r < max_runs; ++r) run_rows[b * max_runs + r] = run_len[b * max_runs + r] = run_base[b * max_runs + r] = run_stride[b * max_runs + r] = 0;
+        n_runs[b] = 0;
+        pat_ptr[b + 1] = pat_ptr[b];
+        const int64_t entries = static_cast<int64_t>(rowptr[last]) - rowptr[first];
+        bool ok = entries <= block_nnz;
+        // the rows one by one: base and rel of each
+        std::vector<int64_t> base;
+        std::vector<std::vector<int64_t>> rel;
+        for (int64_t i = first; i < last && ok; ++i) {
+            const int64_t k = rowptr[i], len = static_cast<int64_t>(rowptr[i + 1]) - k;
+            if (len > max_len) ok = false;
+            base.push_back(len > 0 ? lidx[k] : 0);
+            rel.emplace_back();
+            for (int64_t j = 0; j < len && ok; ++j) {
+                const int64_t d = static_cast<int64_t>(lidx[k + j]) - base.back();
+                if (d < 0) ok = false;
+                rel.back().push_back(d);
+            }
+        }
+        if (!ok) continue;
+        // greedy runs
+        std::vector<int64_t> start;  // first row (within the block) of every run
+        std::vector<int64_t> stride;
+        for (int64_t i = 0; i < last - first; ++i) {
+            bool joins = false;
+            if (!start.empty() && rel[i] == rel[i - 1]) {
+                const int64_t rows_so_far = i - start.back();
+                const int64_t step = base[i] - base[i - 1];
+                if (rows_so_far == 1) {
+                    joins = true;
+                    stride.back() = step;
+                } else if (step == stride.back()) {
+                    joins = true;
+                }
+            }
+            if (!joins) {
+                start.push_back(i);
+                stride.push_back(0);
+            }
+        }
+        if (static_cast<int64_t>(start.size()) > max_runs) continue;
+        n_runs[b] = static_cast<int32_t>(start.size());
+        for (size_t r = 0; r < start.size(); ++r) {
+            const int64_t end = r + 1 < start.size() ? start[r + 1] : last - first;
+            const int64_t q = b * max_runs + static_cast<int64_t>(r);
+            run_rows[q] = static_cast<int32_t>(end - start[r]);
+            run_len[q] = static_cast<int32_t>(rel[start[r]].size());
+            run_base[q] = static_cast<int32_t>(base[start[r]]);
+            run_stride[q] = static_cast<int32_t>(stride[r]);
+            for (int64_t d : rel[start[r]]) {
+                if (pat) pat[pat_ptr[b + 1]] = static_cast<uint16_t>(d);
+                pat_ptr[b + 1] += 1;
+            }
+        }
+        covered += entries;
+    }
+    return covered;
+}
+
+// The kernel that works from the patterns is taken when the patterned blocks hold at least half of the entries.
+int32_t oracle_pattern_choice(int64_t nnz, int64_t covered) { return (nnz > 0 && 2 * covered >= nnz) ? 1 : 0; }
+
 // ---- the two-pass layout ---------------------------------------------------------------
 // Column blocks of 2^shift columns (C of them); chunks = the stretches of the CSR entry list
 // between consecutive merge-path splits taken every `items` steps (P of them).  Tile (c, p) =

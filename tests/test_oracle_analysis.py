@@ -322,6 +322,117 @@ def test_lidx_grouped_handworked():
 TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos")
 
 
+# ---- row patterns of the window positions --------------------------------------------------
+def test_row_patterns_handworked(golden_dir):
+    h = json.loads((golden_dir / "row_patterns_handworked.json").read_text())
+    rp, li, rb = np.array(h["rowptr"], np.int32), np.array(h["lidx"], np.uint16), np.array(h["row_blocks"], np.int32)
+    for c in h["cases"]:
+        got = oracle.row_patterns(rp, rb, li, c["block_nnz"], c["max_runs"], c["max_len"])
+        for name in ("n_runs", "run_rows", "run_len", "run_base", "run_stride", "pat_ptr", "pat"):
+            assert got[name].tolist() == c[name], (name, c["why"])
+        assert got["covered"] == c["covered"]
+
+
+def check_row_patterns(rowptr, rb, lidx, block_nnz, max_runs, max_len):
+    """Pins the run tables without restating how they are found: expanding them gives back lidx exactly; neighbouring
+    runs cannot be merged; a block left out really breaks one of the four conditions (counted by brute force)."""
+    got = oracle.row_patterns(rowptr, rb, lidx, block_nnz, max_runs, max_len)
+    covered = 0
+    for b in range(rb.size - 1):
+        rows = np.arange(rb[b], rb[b + 1])
+        lens = (rowptr[rows + 1] - rowptr[rows]).astype(np.int64)
+        entries = int(lens.sum())
+        R = int(got["n_runs"][b])
+        table = got["pat"][got["pat_ptr"][b]:got["pat_ptr"][b + 1]].astype(np.int64)
+        if R:
+            covered += entries
+            assert entries <= block_nnz and (lens <= max_len).all()
+            assert got["run_rows"][b, :R].sum() == rows.size and (got["run_rows"][b, :R] > 0).all()
+            assert not got["run_rows"][b, R:].any() and table.size == got["run_len"][b, :R].sum()
+            i, t = 0, 0
+            firsts = []
+            for r in range(R):
+                n, L, B, S = (int(got[name][b, r]) for name in ("run_rows", "run_len", "run_base", "run_stride"))
+                firsts.append(i)
+                for q in range(n):
+                    k = rowptr[rows[i + q]]
+                    assert lens[i + q] == L
+                    assert np.array_equal(lidx[k:k + L].astype(np.int64), B + q * S + table[t:t + L]), (b, r, q)
+                if n == 1:
+                    assert S == 0
+                i += n
+                t += L
+            # maximal: the first row of run r + 1 could not have stayed in run r
+            for r in range(R - 1):
+                n, L, S = (int(got[name][b, r]) for name in ("run_rows", "run_len", "run_stride"))
+                L2 = int(got["run_len"][b, r + 1])
+                same_rel = L2 == L and np.array_equal(table[sum(got["run_len"][b, :r]):][:L], table[sum(got["run_len"][b, :r + 1]):][:L])
+                if same_rel:
+                    step = (int(got["run_base"][b, r + 1]) - (int(got["run_base"][b, r]) + (n - 1) * S)) if L else 0
+                    assert n >= 2 and step != S, (b, r)
+        else:
+            assert not any(got[name][b].any() for name in ("run_rows", "run_len", "run_base", "run_stride")) and table.size == 0
+            # brute force: count the maximal runs straight from lidx
+            bases = [int(lidx[rowptr[i]]) if rowptr[i + 1] > rowptr[i] else 0 for i in rows]
+            rels = [tuple(int(v) - bases[j] for v in lidx[rowptr[i]:rowptr[i + 1]]) for j, i in enumerate(rows)]
+            runs, in_run, stride = 0, 0, 0
+            for j in range(rows.size):
+                if in_run and rels[j] == rels[j - 1] and (in_run == 1 or bases[j] - bases[j - 1] == stride):
+                    stride = bases[j] - bases[j - 1]
+                    in_run += 1
+                else:
+                    runs, in_run, stride = runs + 1, 1, 0
+            negative = any(v < 0 for rel in rels for v in rel)
+            assert entries > block_nnz or (lens > max_len).any() or negative or runs > max_runs, b
+    assert covered == got["covered"]
+    return got
+
+
+def test_row_patterns_properties():
+    cases = [(w.laplace2d(40), 256, 64), (w.stencil27(9), 512, 32), (w.stencil27(6, dtype="f32"), 162, 6),
+             (w.block_clustered(300, blocks_per_row=4, width=8), 1024, 8), (w.uniform_rows(300, 300, 16), 128, 16),
+             (w.banded_random(400, 30, 5), 256, 64)]
+    cases += [(p, 64, 8) for p in w.tiny_adversarial()] + [(p, 8192, 1024) for p in w.tiny_adversarial()]
+    some = 0
+    for p, bn, rm in cases:
+        rb = oracle.row_blocks(p.rowptr, bn, rm)
+        _, _, _, lidx = oracle.x_windows(p.rowptr, p.colidx, rb, bn, 8 if p.dtype == "bf16" else 4)
+        for max_runs, max_len in ((4, 64), (2, 5), (1, 27)):
+            some += check_row_patterns(p.rowptr, rb, lidx, bn, max_runs, max_len)["n_runs"].astype(bool).sum()
+    assert some > 100
+
+
+def test_row_patterns_closed_form_on_the_stencils():
+    """Blocks that are whole grid lines (or aligned halves of one): every row of a line's interior has the positions of
+    its left neighbour plus one, the rows at the two ends of a line have patterns of their own."""
+    g = 32
+    p = w.laplace2d(g)
+    rb = np.arange(0, g * g + 1, g // 2, dtype=np.int32)           # half a grid line per block
+    _, _, _, lidx = oracle.x_windows(p.rowptr, p.colidx, rb, 1 << 20, 4)
+    got = oracle.row_patterns(p.rowptr, rb, lidx, 1 << 20)
+    assert got["n_runs"].tolist() == [2] * (2 * g) and got["covered"] == p.nnz
+    left, right = got["run_rows"][0::2], got["run_rows"][1::2]
+    assert (left[:, :2] == [1, g // 2 - 1]).all() and (right[:, :2] == [g // 2 - 1, 1]).all()
+    assert (got["run_stride"][0::2, 1] == 1).all() and (got["run_stride"][1::2, 0] == 1).all()
+    assert got["run_len"][2, :2].tolist() == [4, 5] and got["run_len"][0, :2].tolist() == [3, 4]   # interior line, top line
+    g = 8
+    p = w.stencil27(g)
+    rb = np.arange(0, g ** 3 + 1, g, dtype=np.int32)               # one grid line per block
+    _, _, _, lidx = oracle.x_windows(p.rowptr, p.colidx, rb, 1 << 20, 8)
+    got = oracle.row_patterns(p.rowptr, rb, lidx, 1 << 20)
+    assert (got["n_runs"] == 3).all() and (got["run_rows"][:, :3] == [1, g - 2, 1]).all() and (got["run_stride"][:, 1] == 1).all()
+    # block g + 1 is the line iy = 1, iz = 1: in the interior of the grid
+    assert got["run_len"][g + 1, :3].tolist() == [18, 27, 18] and got["run_len"][0, :3].tolist() == [8, 12, 8]
+    # nine neighbouring lines of g columns each sit back to back in the window: an entry (line q, dx) is at q*g + dx + 1 past the base
+    assert got["pat"][got["pat_ptr"][g + 1] + 18:][:27].tolist() == [q * g + d for q in range(9) for d in range(3)]
+
+
+def test_pattern_choice_rule():
+    assert oracle.pattern_choice(10, 5) and not oracle.pattern_choice(11, 5)
+    assert oracle.pattern_choice(10, 10) and not oracle.pattern_choice(0, 0) and not oracle.pattern_choice(10, 0)
+
+
+
 def test_two_phase_layout_handworked(golden_dir):
     both = json.loads((golden_dir / "two_phase_handworked.json").read_text())
     for g in (both, both["second"]):

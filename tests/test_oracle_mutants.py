@@ -70,6 +70,16 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "if (in_block < block_nnz) *entries += in_block;", "scatter counts: full blocks left out"),
     ("analysis_oracle.cpp", "nnz >= 3 * (int64_t{1} << 21) && C <= 65535", "nnz > 3 * (int64_t{1} << 21) && C <= 65535", "two-pass rule: entry threshold off by one"),
     ("analysis_oracle.cpp", "(plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3", "(plan == 4 || plan == 5) && 2 * n > width && nnz >= 3", "two-pass rule: width threshold off by one"),
+    ("analysis_oracle.cpp", "if (rows_so_far == 1) {\n                    joins = true;", "if (rows_so_far >= 1) {\n                    joins = true;", "row patterns: every step accepted as the run's stride"),
+    ("analysis_oracle.cpp", "} else if (step == stride.back()) {", "} else if (step >= stride.back()) {", "row patterns: a larger step joins the run"),
+    ("analysis_oracle.cpp", "if (!start.empty() && rel[i] == rel[i - 1]) {", "if (!start.empty() && rel[i].size() == rel[i - 1].size()) {", "row patterns: only the lengths compared"),
+    ("analysis_oracle.cpp", "if (d < 0) ok = false;", ";", "row patterns: negative offsets accepted"),
+    ("analysis_oracle.cpp", "if (len > max_len) ok = false;", "if (len >= max_len) ok = false;", "row patterns: the longest allowed row refused"),
+    ("analysis_oracle.cpp", "if (static_cast<int64_t>(start.size()) > max_runs) continue;", "if (static_cast<int64_t>(start.size()) >= max_runs) continue;", "row patterns: the most allowed runs refused"),
+    ("analysis_oracle.cpp", "bool ok = entries <= block_nnz;", "bool ok = entries < block_nnz;", "row patterns: a full block left out"),
+    ("analysis_oracle.cpp", "run_base[q] = static_cast<int32_t>(base[start[r]]);", "run_base[q] = static_cast<int32_t>(base[end - 1]);", "row patterns: base of the run's last row"),
+    ("analysis_oracle.cpp", "base.push_back(len > 0 ? lidx[k] : 0);", "base.push_back(len > 0 ? lidx[k + len - 1] : 0);", "row patterns: base from the row's last entry"),
+    ("analysis_oracle.cpp", "return (nnz > 0 && 2 * covered >= nnz) ? 1 : 0;", "return (nnz > 0 && 2 * covered > nnz) ? 1 : 0;", "pattern rule off by one"),
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * ldb + (K - 1 - k)]);", "columns of B reversed"),
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * K + k]);", "leading dimension of B ignored"),
     ("spmm_oracle.cpp", "if (beta != 0.0f) r += static_cast<double>(beta)", "if (beta != 0.0f) r -= static_cast<double>(beta)", "beta*C subtracted"),
