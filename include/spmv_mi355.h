@@ -113,6 +113,9 @@ typedef struct {
     int32_t tp_num_chunks;             /* P2: tp_row / tp_nz hold P2+1 entries                        */
     int32_t tp_num_pieces;             /* Q: workgroups of the multiply pass                          */
     int32_t lidx_grouped;              /* WINDOWED plan: 1 when the window positions are grouped (see analyze)  */
+    int32_t lidx_patterned;            /* WINDOWED plan: 1 when run() works from row patterns (see analyze)      */
+    int32_t pat_cap;                   /* ... then: entries per block in pat_pad (a multiple of 8); 0 otherwise  */
+    int64_t pat_entries;               /* ... then: stored entries held by the patterned blocks; 0 otherwise     */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -130,6 +133,9 @@ typedef struct {
                             xv_pad[b*max_x_vectors ...], then -1 up to the next block:
                             the fixed-stride copy the kernel reads                    */
     uint16_t* lidx;      /* [nnz]  window position of every entry's x value          */
+    /* ... with lidx_patterned only (skipped otherwise): */
+    int32_t* run_desc;   /* [8 nb] the runs of every block, packed (see analyze)      */
+    uint16_t* pat_pad;   /* [nb * pat_cap] the blocks' pattern lists, zero padded     */
     /* COLBLOCK plan only (skipped otherwise): */
     int32_t* cb_ptr;     /* [C+1]  entries in the blocks before block b              */
     int32_t* cb_row;     /* [nnz]  row of every regrouped entry                      */
@@ -194,6 +200,19 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     every aligned group of eight entries 8g .. 8g+7 (8g+8 <= nnz) has lidx[8g+i] = lidx[8g] + i:
  *     rows made of aligned runs of columns.  run() then reads one position per group (a copy of
  *     lidx[8g], 2 bytes per eight entries) and counts the other seven up from it.
+ *     Row patterns (looked for when the positions are not grouped).  Row i of a block has base_i = lidx of its first
+ *     entry (0 for an empty row) and rel_i[j] = lidx of its j-th entry minus base_i.  The rows of a block are cut
+ *     greedily into runs: the run of row i-1 also takes row i when rel_i = rel_{i-1} (same length, same numbers) and,
+ *     if the run already has two rows or more, base_i - base_{i-1} equals the step between those (the run's stride; a
+ *     run of one row has stride 0).  A block is patterned when it is staged (at most block_nnz entries), no row is longer
+ *     than 64 entries, no rel is negative and it has at most 4 runs.  When the patterned blocks hold at least half of
+ *     the stored entries (lidx_patterned = 1) the library keeps, per block b, run_desc[8b .. 8b+7] - words 0-1: rows of
+ *     runs 0..3, words 3-4: base of each run's first row, words 5-6: stride (two's complement), 16 bits each, low half
+ *     first; word 2: entries per row of runs 0..3, 8 bits each, low byte first; word 7: number of runs, 0 for a block
+ *     without a pattern (then all eight words are 0) - and pat_pad[b * pat_cap ..]: rel of the first row of run 0, of
+ *     run 1, .., then zeros (pat_cap = the longest such list rounded up to a multiple of 8).  run() then reads neither the
+ *     positions nor the row offsets of a patterned block: the position of entry j of the q-th row of a run is
+ *     base + q * stride + rel[j].  Blocks without a pattern are served from lidx as before.
  *   - column blocks (plan AUTO that arrived at ADAPTIVE or MERGE, or plan COLBLOCK; built on the
  *     device).  Columns are cut into blocks of W = 4 MiB / element size columns; the entries are
  *     regrouped block after block, keeping their row-major order inside a block, each with its

@@ -62,6 +62,8 @@ struct spmv_csr_s {
     int32_t* d_xv_pad = nullptr;
     uint16_t* d_lidx = nullptr;
     uint16_t* d_lidx8 = nullptr;  // lidx[8g], kept when the window positions are grouped (info.lidx_grouped)
+    int32_t* d_run_desc = nullptr;  // row patterns of the window positions, kept when info.lidx_patterned
+    uint16_t* d_pat_pad = nullptr;
     // the two-pass plan (TWOPHASE)
     int32_t* d_tp_desc = nullptr;     // pairs (tp_row[p], tp_nz[p])
     int32_t* d_tp_piece_c = nullptr;
@@ -92,7 +94,7 @@ void free_metadata(spmv_csr_s* h) {
                     h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
                     h->d_spmm_val,  h->d_tp_desc,   h->d_tp_piece_c, h->d_tp_piece_g, h->d_tp_chunk_g,
                     h->d_tp_col,    h->d_tp_val,    h->d_tp_src,    h->d_tp_dst,    h->d_tp_pos,
-                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val, h->d_lidx8};
+                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val, h->d_lidx8, h->d_run_desc, h->d_pat_pad};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_tp_desc = h->d_tp_piece_c = h->d_tp_piece_g = h->d_tp_chunk_g = h->d_tp_src = h->d_tp_dst = nullptr;
@@ -108,7 +110,8 @@ void free_metadata(spmv_csr_s* h) {
     h->d_cb_row = h->d_cb_col = h->d_cb_src = nullptr;
     h->d_cb_vals = nullptr;
     h->cb_ptr.clear();
-    h->d_lidx = h->d_lidx8 = nullptr;
+    h->d_lidx = h->d_lidx8 = h->d_pat_pad = nullptr;
+    h->d_run_desc = nullptr;
     h->d_spmm_rows = h->d_spmm_desc = nullptr;
     h->d_spmm_col = nullptr;
     h->d_spmm_val = nullptr;
@@ -214,6 +217,42 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, bool count_only, const
             h->d_lidx8 = nullptr;
         }
         a->info.lidx_grouped = flag == 0 ? 1 : 0;
+    }
+    // Row patterns (stencils): where the positions are not grouped, look for runs of rows whose positions repeat with a
+    // constant step; when the patterned blocks hold half of the entries or more, run() works from the patterns.
+    if (!a->info.lidx_grouped && nb > 0) {
+        struct Counts {
+            unsigned long long covered;
+            int32_t max_table, pad;
+        } counts{0, 0, 0};
+        Counts* d_counts = nullptr;
+        if (hip_failed(hipMalloc(reinterpret_cast<void**>(&d_counts), sizeof(Counts))) ||
+            hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_run_desc), 32 * static_cast<size_t>(nb)))) {
+            (void)hipFree(d_counts);
+            return SPMV_ERR_ALLOC;
+        }
+        bool failed = hip_failed(hipMemcpy(d_counts, &counts, sizeof counts, hipMemcpyHostToDevice));
+        failed = failed || hip_failed(spmv::launch_pattern_build(h->d_block_desc, static_cast<int32_t>(nb), h->rowptr, h->d_lidx,
+                                                                 a->info.block_nnz, false, h->d_run_desc, &d_counts->max_table,
+                                                                 &d_counts->covered, nullptr, 0, nullptr));
+        failed = failed || hip_failed(hipMemcpy(&counts, d_counts, sizeof counts, hipMemcpyDeviceToHost));
+        (void)hipFree(d_counts);
+        if (failed) return SPMV_ERR_HIP;
+        const int64_t covered = static_cast<int64_t>(counts.covered);
+        const int32_t pt_cap = counts.max_table > 0 ? (counts.max_table + 7) / 8 * 8 : 8;
+        if (h->nnz > 0 && 2 * covered >= h->nnz && nb * static_cast<int64_t>(pt_cap) <= kMaxCount) {
+            if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_pat_pad), 2 * static_cast<size_t>(nb) * static_cast<size_t>(pt_cap))))
+                return SPMV_ERR_ALLOC;
+            if (hip_failed(spmv::launch_pattern_build(h->d_block_desc, static_cast<int32_t>(nb), h->rowptr, h->d_lidx, a->info.block_nnz,
+                                                      true, h->d_run_desc, nullptr, nullptr, h->d_pat_pad, pt_cap, nullptr)))
+                return SPMV_ERR_HIP;
+            a->info.lidx_patterned = 1;
+            a->info.pat_cap = pt_cap;
+            a->info.pat_entries = covered;
+        } else {
+            (void)hipFree(h->d_run_desc);
+            h->d_run_desc = nullptr;
+        }
     }
     a->info.plan = SPMV_PLAN_WINDOWED;
     a->info.num_x_vectors = total;
@@ -621,7 +660,8 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
                                       h->info.block_nnz, h->info.rows_max, x, y, s, st);
             break;
         case SPMV_PLAN_WINDOWED: {
-            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx8, h->d_lidx, h->info.max_x_vectors};
+            const spmv::XWindows w{h->d_xv_ptr, h->d_xv_start, h->d_xv_pad, h->d_lidx8, h->d_lidx, h->info.max_x_vectors,
+                                   h->d_run_desc, h->d_pat_pad, h->info.pat_cap};
             e = spmv::launch_windowed(A, h->d_block_desc, static_cast<int32_t>(h->info.num_row_blocks),
                                       h->info.block_nnz, h->max_block_entries, h->info.rows_max, w, x, y, s, st);
             break;
@@ -835,6 +875,13 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
         if (out->lidx && h->nnz > 0 &&
             hip_failed(hipMemcpy(out->lidx, h->d_lidx, sizeof(uint16_t) * static_cast<size_t>(h->nnz), hipMemcpyDeviceToHost)))
             return SPMV_ERR_HIP;
+        if (h->info.lidx_patterned) {
+            const size_t nb = static_cast<size_t>(h->info.num_row_blocks);
+            if (out->run_desc && hip_failed(hipMemcpy(out->run_desc, h->d_run_desc, 32 * nb, hipMemcpyDeviceToHost))) return SPMV_ERR_HIP;
+            if (out->pat_pad &&
+                hip_failed(hipMemcpy(out->pat_pad, h->d_pat_pad, 2 * nb * static_cast<size_t>(h->info.pat_cap), hipMemcpyDeviceToHost)))
+                return SPMV_ERR_HIP;
+        }
     }
     return SPMV_OK;
 }
@@ -896,7 +943,7 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_BINNED: return spmv::vector_kernel_name();
         case SPMV_PLAN_ADAPTIVE:
         case SPMV_PLAN_MERGE: return spmv::tile_kernel_name();
-        case SPMV_PLAN_WINDOWED: return spmv::window_kernel_name();
+        case SPMV_PLAN_WINDOWED: return h->info.lidx_patterned ? spmv::pattern_kernel_name() : spmv::window_kernel_name();
         case SPMV_PLAN_COLBLOCK: return "spmv_coo_kernel";
         case SPMV_PLAN_TWOPHASE: return "tp_multiply_kernel";
         default: return "";

@@ -19,6 +19,9 @@ constexpr int kMaxColBlocks = 16;  // most column blocks of the column-blocked p
 constexpr int kCbTile = 2048;      // entries a wavefront regroups at a time
 constexpr int kMaxXVectors = 1024;     // most 16-byte x vectors a row block may keep in LDS
 constexpr int kMaxTileEntries = 8192;  // most entries of a row block
+constexpr int kMaxRowsPerBlock = 1024; // most rows of a row block
+constexpr int kMaxPatternRuns = 4;     // most runs of rows in a patterned block
+constexpr int kMaxPatternLen = 64;     // longest row of a patterned block
 
 // x windows of the row blocks (device arrays owned by the handle).
 struct XWindows {
@@ -28,6 +31,9 @@ struct XWindows {
     const uint16_t* lidx8;    // [nnz / 8] lidx[8g] where the positions are grouped (see launch_lidx_groups), else null
     const uint16_t* lidx;     // [nnz rounded up to a multiple of 8]
     int32_t max_vectors;      // largest xv_ptr[b+1] - xv_ptr[b]
+    const int32_t* run_desc;  // [8 * nb] packed runs of the row patterns (see launch_pattern_build), or null: no patterns
+    const uint16_t* pat_pad;  // [nb * pt_cap] the blocks' pattern lists
+    int32_t pt_cap;           // a multiple of 8, at most kMaxPatternRuns * kMaxPatternLen
 };
 
 struct Scalars {
@@ -86,6 +92,14 @@ const char* spmm_packed_kernel_name();
 // Whole aligned groups of eight entries (groups = nnz / 8): lidx8[g] = lidx[8g]; *flag (device int32, 0 on entry) is set to 1
 // if some group's eight positions are not consecutive numbers.
 hipError_t launch_lidx_groups(const uint16_t* lidx, int32_t groups, uint16_t* lidx8, int32_t* flag, hipStream_t st);
+// Row patterns of the window positions (analysis).  block_desc as for launch_adaptive.  fill == false: run_desc[8b..8b+7] =
+// the runs of block b, packed: words 0-1 rows per run, 3-4 base of the run's first row, 5-6 stride (two's complement), 16 bits
+// each in run order; word 2 entries per row, 8 bits each; word 7 the number of runs (0: the block has no pattern, all words 0);
+// *max_table (device int32, 0 on entry) = longest pattern list of any block; *covered (device uint64, 0 on entry) = entries
+// of the patterned blocks.  fill == true: pat_pad[b * pt_cap ..] = block b's list (rel of the first row of every run), then zeros.
+hipError_t launch_pattern_build(const int32_t* block_desc, int32_t nb, const int32_t* rowptr, const uint16_t* lidx, int32_t block_nnz,
+                                bool fill, int32_t* run_desc, int32_t* max_table, unsigned long long* covered, uint16_t* pat_pad,
+                                int32_t pt_cap, hipStream_t st);
 // flag: device int32, must be 0 on entry; set to 1 if any colidx is outside [0, n).
 hipError_t launch_validate_columns(const MatrixView& A, int32_t* flag, hipStream_t st);
 
@@ -178,6 +192,7 @@ const char* scalar_kernel_name();
 const char* vector_kernel_name();
 const char* tile_kernel_name();  // kernel of the adaptive and merge plans
 const char* window_kernel_name();
+const char* pattern_kernel_name();
 const char* spmm_kernel_name();
 
 }  // namespace spmv

@@ -16,6 +16,7 @@
 
 #include <cstdio>
 #include <cstdlib>
+#include <type_traits>
 
 #include "device_common.h"
 #include "kernels.h"
@@ -168,6 +169,9 @@ struct TileArgs {
     const int32_t* xv_pad;     // window kernel: [nparts * x_cap] first element of each 16-byte x vector of a block, -1 padded
     const uint16_t* lidx8;     // window kernel, grouped positions: [nnz/8] lidx[8g], the first of every aligned group of eight
     const uint16_t* lidx;      // window kernel: [nnz, padded to a multiple of 8] position of each entry's x value in the block's window
+    const int32_t* run_desc;   // pattern kernel: [8 * nparts] the runs of every row block (packed; word 7 = number of runs, 0: no pattern)
+    const uint16_t* pat_pad;   // pattern kernel: [nparts * pt_cap] the blocks' pattern lists at a fixed stride
+    int32_t pt_cap;            // pattern kernel: entries per block in pat_pad (a multiple of 8)
     const int32_t* part_desc;  // [2*(nparts+1)] pairs (row, entry): first row and first entry of each row block, or rows
                                // finished and entries taken at each merge-path split
     const int32_t* rowptr;
@@ -345,6 +349,19 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
     tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
 }
 
+// First elements of the x vectors a lane fetches for block `part` (-1: none).  after: 0, possibly obtained from a value
+// the loads are to follow.  A lane with nothing to fetch reads the start of lidx instead.
+template <int WG, int XPL>
+__device__ __forceinline__ void load_x_addresses(const TileArgs& a, int part, int tid, int after, int (&xs)[XPL]) {
+#pragma unroll
+    for (int u = 0; u < XPL; ++u) {
+        const int i = tid + u * WG;
+        const int32_t* src = i < a.x_cap ? a.xv_pad + part * a.x_cap + i + after : reinterpret_cast<const int32_t*>(a.lidx);
+        xs[u] = *src;
+        xs[u] = i < a.x_cap ? xs[u] : -1;
+    }
+}
+
 // Row blocks with x served from LDS.  The analysis has listed, for every row block, the
 // distinct aligned 16-byte vectors of x that its entries touch (xv_pad: one fixed-size slice per
 // block, so a lane knows where its vector's address is before any descriptor has arrived) and
@@ -359,8 +376,12 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
 // GROUPED: the analysis found every aligned group of eight entries at eight consecutive window
 // positions (rows made of aligned runs of columns): one 16-bit position per group is read instead
 // of eight, and the other seven are counted up from it.
+// One row block of the window kernel.  xs: with XPL == 1 the x vector addresses, already requested by the caller
+// (they need only the block number, so they go out before the block's descriptor has arrived); with larger windows
+// the x gathers that follow them keep the address units busy for long, and measured best when they start after the
+// entry stream has been requested, so there the addresses are fetched here, with the stream.
 template <typename T, int WG, int XPL, int NG, bool GROUPED>
-__global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window_kernel(const TileArgs a) {
+__device__ __forceinline__ void window_block(const TileArgs& a, int part, int (&xs)[XPL]) {
     using E = typename T::elem;
     constexpr int XE = 16 / sizeof(E);  // elements per x vector
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -369,27 +390,9 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     __shared__ float wave_part[WG / 64];
 
     const int tid = threadIdx.x;
-    const int part = xcd_remap(blockIdx.x, a.nparts);
     const E* vals = static_cast<const E*>(a.vals);
     const E* x = static_cast<const E*>(a.x);
-
-    // x vector addresses need only the block number.  With small windows (one vector per lane)
-    // they go out before the block's descriptor has arrived; with large windows the x gathers
-    // that follow them keep the address units busy for long, and measured best when they start
-    // after the entry stream has been requested, so there the addresses are fetched with the stream.
     const uint16_t* const dummy = a.lidx;
-    int xs[XPL];
-    auto load_x_addresses = [&](int after) {  // after: 0, possibly obtained from a value the loads are to follow
-#pragma unroll
-        for (int u = 0; u < XPL; ++u) {
-            const int i = tid + u * WG;
-            const int32_t* src =
-                i < a.x_cap ? a.xv_pad + part * a.x_cap + i + after : reinterpret_cast<const int32_t*>(dummy);
-            xs[u] = *src;
-            xs[u] = i < a.x_cap ? xs[u] : -1;
-        }
-    };
-    if constexpr (XPL == 1) load_x_addresses(0);
 
     const int r0 = a.part_desc[2 * part];  // one 16-byte scalar load: (r0, k0, r1, k1)
     const int k0 = a.part_desc[2 * part + 1];
@@ -419,7 +422,7 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
         // then really wait for it instead of being scheduled back to the top
         int zero;
         asm volatile("s_mov_b32 %0, 0" : "=s"(zero) : "s"(k1));
-        load_x_addresses(zero);
+        load_x_addresses<WG, XPL>(a, part, tid, zero, xs);
     }
     const int rp0 = a.rowptr[r0 + (tid < nr ? tid : nr)];  // bound nr is k1: no load needed for it
     const float* const y_src = (a.beta != 0.f && tid < nr) ? a.y + r0 + tid : reinterpret_cast<const float*>(dummy);
@@ -513,6 +516,238 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window
     }
     const RowOut o{a.y, y0_l, a.carry_row, a.carry_val, a.alpha, a.beta};
     tile_rows<false, WG>(lidx_l, vals_l, xbuf, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
+}
+
+template <typename T, int WG, int XPL, int NG, bool GROUPED>
+__global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_window_kernel(const TileArgs a) {
+    const int part = xcd_remap(blockIdx.x, a.nparts);
+    int xs[XPL];
+    if constexpr (XPL == 1) load_x_addresses<WG, XPL>(a, part, threadIdx.x, 0, xs);
+    window_block<T, WG, XPL, NG, GROUPED>(a, part, xs);
+}
+
+// The window kernel for matrices whose window positions follow row patterns (stencils).  The analysis has cut the
+// rows of a block into at most four runs; inside a run every row has the same number of entries, and the window
+// position of its j-th entry is  base + (row's place in the run) * stride + pat[j]  (run_desc: eight words per block,
+// one scalar load; pat_pad: the blocks' pattern lists, a few dozen 16-bit numbers each, at a fixed stride).  Such a block
+// is served without its position stream and without its row offsets: what is read per entry is the value alone.
+// A block without a pattern (word 7 of its descriptor is 0) is taken by window_block as it is.
+// Packing of run_desc: words 0-1 the runs' row counts, words 3-4 their bases, words 5-6 their strides (signed), 16 bits
+// each; word 2 their row lengths, 8 bits each.
+template <int G, typename E>
+__device__ __forceinline__ float pattern_dot(const E* vals, const E* xbuf, const uint16_t* pat, int slot, int pos0, int len,
+                                             int tl) {
+    // the lane's entries j = tl, tl + G, ..: four at a time, then two, then one
+    float acc = 0.f;
+    int cnt = (len - tl + G - 1) / G;
+    vals += slot + tl;
+    pat += tl;
+    auto batch = [&](auto B_) {
+        constexpr int B = decltype(B_)::value;
+        unsigned c[B];
+        E xv[B], av[B];
+#pragma unroll
+        for (int u = 0; u < B; ++u) c[u] = static_cast<unsigned>(pos0) + pat[u * G];
+#pragma unroll
+        for (int u = 0; u < B; ++u) xv[u] = xbuf[c[u]];
+#pragma unroll
+        for (int u = 0; u < B; ++u) av[u] = vals[u * G];
+#pragma unroll
+        for (int u = 0; u < B; ++u) acc += widen(av[u]) * widen(xv[u]);
+        vals += B * G;
+        pat += B * G;
+        cnt -= B;
+    };
+    while (cnt >= 4) batch(std::integral_constant<int, 4>{});
+    if (cnt >= 2) batch(std::integral_constant<int, 2>{});
+    if (cnt >= 1) batch(std::integral_constant<int, 1>{});
+    return acc;
+}
+
+struct RunTable {
+    int n;          // runs in the block, 1..4
+    int cut[3];     // rows before run 1, 2, 3 (INT_MAX for a run that does not exist)
+    int len[4];     // entries per row
+    int slot[4];    // staged slot of entry 0 of row `row` of the block = slot[r] + row * len[r]
+    int pos[4];     // window position of that entry = pos[r] + row * stride[r]
+    int stride[4];
+    int tab[4];     // where the run's pattern starts in the block's list
+};
+
+template <int WG, int G, typename E>
+__device__ __forceinline__ void pattern_rows_g(const E* vals_l, const E* xbuf, const uint16_t* pat_l, const float* y0_l,
+                                               const RunTable& rt, int nr, int r0, float* y, float alpha, float beta, int tid) {
+    constexpr int teams = WG / G;
+    const int team = tid / G, tl = tid % G;
+    for (int first = 0; first < nr; first += teams) {
+        const int row = first + team;
+        int len = rt.len[0], slot = rt.slot[0], pos = rt.pos[0], stride = rt.stride[0], tab = rt.tab[0];
+        if (rt.n > 1) {  // uniform over the workgroup
+#pragma unroll
+            for (int r = 1; r < 4; ++r) {
+                const bool in = row >= rt.cut[r - 1];
+                len = in ? rt.len[r] : len;
+                slot = in ? rt.slot[r] : slot;
+                pos = in ? rt.pos[r] : pos;
+                stride = in ? rt.stride[r] : stride;
+                tab = in ? rt.tab[r] : tab;
+            }
+        }
+        const bool live = row < nr;
+        len = live ? len : 0;
+        float acc = pattern_dot<G>(vals_l, xbuf, pat_l + tab, slot + row * len, pos + row * stride, len, tl);
+        acc = group_sum<G>(acc);  // every lane takes part
+        if (live && tl == 0) y[r0 + row] = epilogue(acc, alpha, beta, y0_l, row);
+    }
+}
+
+template <typename T, int WG, int XPL, int NG>
+__device__ __forceinline__ void pattern_block(const TileArgs& a, int part, int (&xs)[XPL], const int32_t* rd) {
+    using E = typename T::elem;
+    constexpr int XE = 16 / sizeof(E);
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    const int tid = threadIdx.x;
+    const E* vals = static_cast<const E*>(a.vals);
+    const E* x = static_cast<const E*>(a.x);
+    const uint16_t* const dummy = a.lidx;
+
+    // the block's pattern list needs only the block number
+    const int pt_vecs = a.pt_cap >> 3;
+    const uint16_t* const pt_src = tid < pt_vecs ? a.pat_pad + static_cast<int64_t>(part) * a.pt_cap + 8 * tid : dummy;
+    const u32x4 ptab = *reinterpret_cast<const u32x4*>(pt_src);
+
+    const int r0 = a.part_desc[2 * part];
+    const int k0 = a.part_desc[2 * part + 1];
+    const int nr = a.part_desc[2 * part + 2] - r0;
+    const int k1 = a.part_desc[2 * part + 3];
+    if constexpr (XPL > 1) {
+        int zero;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(zero) : "s"(k1));
+        load_x_addresses<WG, XPL>(a, part, tid, zero, xs);
+    }
+    const float* const y_src = (a.beta != 0.f && tid < nr) ? a.y + r0 + tid : reinterpret_cast<const float*>(dummy);
+    const float y0v = *y_src;
+
+    const int k0a = k0 & ~7;
+    const int span = k1 - k0a;
+    const int slots = (span + 7) & ~7;
+    E* xbuf = reinterpret_cast<E*>(smem_raw);
+    E* vals_l = reinterpret_cast<E*>(smem_raw + 16 * a.x_cap);
+    uint16_t* pat_l = reinterpret_cast<uint16_t*>(smem_raw + 16 * a.x_cap + sizeof(E) * slots);
+    float* y0_l = reinterpret_cast<float*>(smem_raw + 16 * a.x_cap + sizeof(E) * slots + 2 * a.pt_cap);
+
+    // the entry stream is the values alone: groups of eight, all loads unconditional (see window_block)
+    struct Group {
+        u32x4 v0, v1;
+        bool live, vec;
+    };
+    const int nnz_vec = a.vec_ok ? a.nnz & ~7 : 0;
+    auto load_group = [&](int off, Group& g) {
+        const int k = k0a + off;
+        g.live = off < span;
+        g.vec = g.live && k < nnz_vec;
+        const uint16_t* vp = g.vec ? reinterpret_cast<const uint16_t*>(vals + k) : dummy;
+        g.v0 = load_val8(vp);
+        if constexpr (sizeof(E) == 4) g.v1 = load_val8(g.vec ? vp + 8 : dummy);
+    };
+    auto store_group = [&](int off, const Group& g) {
+        if (g.vec) {
+            *reinterpret_cast<u32x4*>(vals_l + off) = g.v0;
+            if constexpr (sizeof(E) == 4) *reinterpret_cast<u32x4*>(vals_l + off + 4) = g.v1;
+        } else if (g.live) {
+            const int k = k0a + off;
+            for (int i = 0; i < 8; ++i)
+                if (k + i >= k0 && k + i < k1) vals_l[off + i] = vals[k + i];
+        }
+    };
+    Group g[NG];
+#pragma unroll
+    for (int u = 0; u < NG; ++u) load_group((tid + u * WG) * 8, g[u]);
+
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 xv[XPL];
+    bool xvec[XPL];
+#pragma unroll
+    for (int u = 0; u < XPL; ++u) {
+        xvec[u] = xs[u] >= 0 && a.x_vec_ok && xs[u] + XE <= a.n;
+        const E* src = xvec[u] ? x + xs[u] : reinterpret_cast<const E*>(dummy);
+        xv[u] = *reinterpret_cast<const u32x4*>(src);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // the runs, unpacked with scalar arithmetic while the loads are in flight
+    RunTable rt;
+    rt.n = rd[7];
+    const int rows[4] = {rd[0] & 0xFFFF, static_cast<int>(static_cast<unsigned>(rd[0]) >> 16), rd[1] & 0xFFFF,
+                         static_cast<int>(static_cast<unsigned>(rd[1]) >> 16)};
+    const int base[4] = {rd[3] & 0xFFFF, static_cast<int>(static_cast<unsigned>(rd[3]) >> 16), rd[4] & 0xFFFF,
+                         static_cast<int>(static_cast<unsigned>(rd[4]) >> 16)};
+    const int stride[4] = {static_cast<int16_t>(rd[5] & 0xFFFF), rd[5] >> 16, static_cast<int16_t>(rd[6] & 0xFFFF), rd[6] >> 16};
+    int row_first = 0, entry_first = k0 - k0a, tab = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int len = (rd[2] >> (8 * r)) & 0xFF;
+        rt.len[r] = len;
+        rt.slot[r] = entry_first - row_first * len;
+        rt.pos[r] = base[r] - row_first * stride[r];
+        rt.stride[r] = stride[r];
+        rt.tab[r] = tab;
+        row_first += rows[r];
+        entry_first += rows[r] * len;
+        tab += len;
+        if (r < 3) rt.cut[r] = r + 1 < rt.n ? row_first : 0x7FFFFFFF;
+    }
+
+    if (tid < pt_vecs) *reinterpret_cast<u32x4*>(pat_l + 8 * tid) = ptab;
+    if (tid < nr) y0_l[tid] = y0v;
+#pragma unroll
+    for (int u = 0; u < NG; ++u) store_group((tid + u * WG) * 8, g[u]);
+#pragma unroll
+    for (int u = 0; u < XPL; ++u) {
+        const int i = tid + u * WG;
+        if (xvec[u]) {
+            *reinterpret_cast<u32x4*>(xbuf + i * XE) = xv[u];
+        } else if (xs[u] >= 0) {
+            for (int e = 0; e < XE; ++e) xbuf[i * XE + e] = xs[u] + e < a.n ? x[xs[u] + e] : E(0);
+        }
+    }
+    // what the fixed-size first round did not cover (blocks of more than WG rows or NG*WG*8 entries)
+    if (a.beta != 0.f)
+        for (int i = tid + WG; i < nr; i += WG) y0_l[i] = a.y[r0 + i];
+    for (int off = (tid + NG * WG) * 8; off < span; off += WG * 8) {
+        Group h;
+        load_group(off, h);
+        store_group(off, h);
+    }
+    __syncthreads();
+
+    // lanes per row as in tile_rows
+    const int tile_nnz = k1 - k0;
+    int G = 1;
+    while (G < 64 && (16 * G + 1) * nr <= tile_nnz) G <<= 1;
+    if (tile_nnz >= 64 * nr) {
+        G = 64;
+        while (4 * G * nr > tile_nnz) G >>= 1;
+    }
+    switch (G) {
+        case 1: pattern_rows_g<WG, 1>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
+        case 2: pattern_rows_g<WG, 2>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
+        case 4: pattern_rows_g<WG, 4>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
+        case 8: pattern_rows_g<WG, 8>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
+        default: pattern_rows_g<WG, 16>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
+    }
+}
+
+template <typename T, int WG, int XPL, int NG>
+__global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_pattern_kernel(const TileArgs a) {
+    const int part = xcd_remap(blockIdx.x, a.nparts);
+    int xs[XPL];
+    if constexpr (XPL == 1) load_x_addresses<WG, XPL>(a, part, threadIdx.x, 0, xs);
+    const int32_t* rd = a.run_desc + 8 * static_cast<int64_t>(part);
+    if (rd[7] == 0)
+        window_block<T, WG, XPL, NG, false>(a, part, xs);
+    else
+        pattern_block<T, WG, XPL, NG>(a, part, xs, rd);
 }
 
 // Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
@@ -637,6 +872,116 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
         }
         lidx[k0 + i] = static_cast<uint16_t>((static_cast<uint32_t>(lo) << shift) + (c & low));
     }
+}
+
+// Finds the row patterns of the window positions (one workgroup of 256 lanes per row block; analysis time).
+// Row i of the block has base_i = lidx of its first entry (0 when empty) and rel_i = its positions minus base_i.
+// A run takes the next row when rel repeats and, from its third row on, the bases keep the step of its first two rows.
+// The block is patterned when it is staged, no row exceeds kMaxPatternLen entries, no rel is negative and there are at
+// most kMaxPatternRuns runs.  fill == 0: packs the runs into run_desc[8b .. 8b+7] (word 7 = runs, 0 when not
+// patterned), raises *max_table to the length of the block's pattern list and adds the block's entries to *covered.
+// fill == 1 (same inputs, pat_pad allocated with stride pt_cap): writes the list, zero padded.
+__global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __restrict__ block_desc, const int32_t* __restrict__ rowptr,
+                                                            const uint16_t* __restrict__ lidx, int tile_cap, int fill,
+                                                            int32_t* __restrict__ run_desc, int32_t* max_table,
+                                                            unsigned long long* covered, uint16_t* __restrict__ pat_pad, int pt_cap) {
+    __shared__ int base_s[kMaxRowsPerBlock];
+    __shared__ unsigned char len_s[kMaxRowsPerBlock], same_s[kMaxRowsPerBlock];
+    __shared__ int bad;
+    __shared__ int run_first[kMaxPatternRuns + 1], run_stride[kMaxPatternRuns], n_runs;
+    const int tid = threadIdx.x, b = blockIdx.x;
+    const int r0 = block_desc[2 * b], k0 = block_desc[2 * b + 1], r1 = block_desc[2 * b + 2], k1 = block_desc[2 * b + 3];
+    const int nr = r1 - r0;
+    if (tid == 0) bad = (k1 - k0 > tile_cap || nr > kMaxRowsPerBlock) ? 1 : 0;
+    __syncthreads();
+    if (!bad) {
+        for (int i = tid; i < nr; i += 256) {
+            const int ka = rowptr[r0 + i], len = rowptr[r0 + i + 1] - ka;
+            if (len > kMaxPatternLen) {
+                bad = 1;
+                continue;
+            }
+            const int base = len > 0 ? lidx[ka] : 0;
+            bool same = false;
+            if (i > 0) {
+                const int pa = rowptr[r0 + i - 1];
+                if (ka - pa == len) {
+                    same = true;
+                    const int pbase = len > 0 ? lidx[pa] : 0;
+                    for (int j = 1; j < len; ++j) same = same && (lidx[ka + j] - base == lidx[pa + j] - pbase);
+                }
+            }
+            bool negative = false;
+            for (int j = 1; j < len; ++j) negative = negative || lidx[ka + j] < base;
+            if (negative) bad = 1;
+            base_s[i] = base;
+            len_s[i] = static_cast<unsigned char>(len);
+            same_s[i] = same ? 1 : 0;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int runs = 0;
+        if (!bad) {
+            for (int i = 0; i < nr; ++i) {
+                bool joins = false;
+                if (runs > 0 && same_s[i]) {
+                    const int so_far = i - run_first[runs - 1], step = base_s[i] - base_s[i - 1];
+                    if (so_far == 1) {
+                        joins = true;
+                        run_stride[runs - 1] = step;
+                    } else if (step == run_stride[runs - 1]) {
+                        joins = true;
+                    }
+                }
+                if (!joins) {
+                    if (runs == kMaxPatternRuns) {
+                        runs = 0;
+                        break;
+                    }
+                    run_first[runs] = i;
+                    run_stride[runs] = 0;
+                    ++runs;
+                }
+            }
+            run_first[runs] = nr;
+        }
+        n_runs = runs;
+        if (!fill) {
+            int rows[4] = {0, 0, 0, 0}, len[4] = {0, 0, 0, 0}, base[4] = {0, 0, 0, 0}, stride[4] = {0, 0, 0, 0}, table = 0;
+            for (int r = 0; r < runs; ++r) {
+                rows[r] = run_first[r + 1] - run_first[r];
+                len[r] = len_s[run_first[r]];
+                base[r] = base_s[run_first[r]];
+                stride[r] = run_stride[r] & 0xFFFF;
+                table += len[r];
+            }
+            int32_t* d = run_desc + 8 * static_cast<int64_t>(b);
+            d[0] = rows[0] | rows[1] << 16;
+            d[1] = rows[2] | rows[3] << 16;
+            d[2] = len[0] | len[1] << 8 | len[2] << 16 | len[3] << 24;
+            d[3] = base[0] | base[1] << 16;
+            d[4] = base[2] | base[3] << 16;
+            d[5] = stride[0] | stride[1] << 16;
+            d[6] = stride[2] | stride[3] << 16;
+            d[7] = runs;
+            if (runs > 0) {
+                atomicMax(max_table, table);
+                atomicAdd(covered, static_cast<unsigned long long>(k1 - k0));
+            }
+        }
+    }
+    __syncthreads();
+    if (!fill) return;
+    uint16_t* out = pat_pad + static_cast<int64_t>(b) * pt_cap;
+    int at = 0;
+    for (int r = 0; r < n_runs; ++r) {
+        const int row = run_first[r], len = len_s[row];
+        const int ka = rowptr[r0 + row];
+        for (int j = tid; j < len; j += 256) out[at + j] = static_cast<uint16_t>(lidx[ka + j] - base_s[row]);
+        at += len;
+    }
+    for (int j = at + tid; j < pt_cap; j += 256) out[j] = 0;
 }
 
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
@@ -814,9 +1159,26 @@ hipError_t launch_window_g(const TileArgs& a, size_t lds, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <typename T, int XPL, int NG>
+hipError_t launch_pattern_g(const TileArgs& a, size_t lds, hipStream_t st) {
+    auto kernel = spmv_pattern_kernel<T, 256, XPL, NG>;
+    if (lds > 64 * 1024) {
+        static thread_local size_t allowed = 0;
+        if (lds > allowed) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+            if (e != hipSuccess) return e;
+            allowed = lds;
+        }
+    }
+    hipLaunchKernelGGL(kernel, dim3(a.nparts), dim3(256), lds, st, a);
+    return hipGetLastError();
+}
+
 // Picks the instantiation whose fixed first round of loads just covers the blocks.
 template <typename T, int XPL, int NG>
 hipError_t launch_window_k(const TileArgs& a, size_t lds, hipStream_t st) {
+    if (a.run_desc) return launch_pattern_g<T, XPL, NG>(a, lds, st);
     return a.lidx8 ? launch_window_g<T, XPL, NG, true>(a, lds, st) : launch_window_g<T, XPL, NG, false>(a, lds, st);
 }
 
@@ -856,12 +1218,17 @@ hipError_t launch_windowed(const MatrixView& A, const int32_t* block_desc, int32
     a.tile_cap = block_nnz;
     a.xv_pad = w.xv_pad;
     a.lidx = w.lidx;
-    a.lidx8 = w.lidx8;
+    a.lidx8 = w.run_desc ? nullptr : w.lidx8;
+    a.run_desc = w.run_desc;
+    a.pat_pad = w.pat_pad;
+    a.pt_cap = w.run_desc ? w.pt_cap : 0;
+    if (w.run_desc && (w.pt_cap < 8 || w.pt_cap % 8 != 0 || w.pt_cap > kMaxPatternRuns * kMaxPatternLen || !w.pat_pad))
+        return hipErrorInvalidValue;
     a.x_cap = w.max_vectors > 0 ? w.max_vectors : 1;
     a.x_vec_ok = reinterpret_cast<uintptr_t>(x) % 16 == 0 ? 1 : 0;
     const size_t esz = A.bf16 ? 2 : 4;
     const size_t lds = 16 * static_cast<size_t>(a.x_cap) + (esz + 2) * static_cast<size_t>(staged_max + 16) +
-                       (sizeof(int) + sizeof(float)) * static_cast<size_t>(rows_max + 2);
+                       (sizeof(int) + sizeof(float)) * static_cast<size_t>(rows_max + 2) + 2 * static_cast<size_t>(a.pt_cap);
     if (A.bf16) return launch_window_t<BF16>(a, staged_max, lds, st);
     return launch_window_t<F32>(a, staged_max, lds, st);
 }
@@ -873,6 +1240,15 @@ hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int
     const int shift = A.bf16 ? 3 : 2;
     hipLaunchKernelGGL(window_build_kernel, dim3(nb), dim3(256), 0, st, block_nz, A.colidx, block_nnz, shift,
                        fill ? 1 : 0, nv, xv_ptr, xv_start, xv_pad, x_cap, lidx);
+    return hipGetLastError();
+}
+
+hipError_t launch_pattern_build(const int32_t* block_desc, int32_t nb, const int32_t* rowptr, const uint16_t* lidx, int32_t block_nnz,
+                                bool fill, int32_t* run_desc, int32_t* max_table, unsigned long long* covered, uint16_t* pat_pad,
+                                int32_t pt_cap, hipStream_t st) {
+    if (nb <= 0) return hipSuccess;
+    hipLaunchKernelGGL(pattern_build_kernel, dim3(nb), dim3(256), 0, st, block_desc, rowptr, lidx, block_nnz, fill ? 1 : 0, run_desc,
+                       max_table, covered, pat_pad, pt_cap);
     return hipGetLastError();
 }
 
@@ -929,5 +1305,6 @@ const char* scalar_kernel_name() { return "spmv_scalar_kernel"; }
 const char* vector_kernel_name() { return "spmv_vector_kernel"; }
 const char* tile_kernel_name() { return "spmv_tile_kernel"; }
 const char* window_kernel_name() { return "spmv_window_kernel"; }
+const char* pattern_kernel_name() { return "spmv_pattern_kernel"; }
 
 }  // namespace spmv

@@ -48,7 +48,8 @@ class spmv_analysis_info_t(C.Structure):
                 ("col_block_width", C.c_int32), ("spmm_prepared", C.c_int32), ("spmm_col_bytes", C.c_int32),
                 ("spmm_num_blocks", C.c_int64), ("tp_slots", C.c_int64), ("tp_col_shift", C.c_int32),
                 ("tp_items", C.c_int32), ("tp_num_col_blocks", C.c_int32), ("tp_num_chunks", C.c_int32),
-                ("tp_num_pieces", C.c_int32), ("lidx_grouped", C.c_int32)]
+                ("tp_num_pieces", C.c_int32), ("lidx_grouped", C.c_int32), ("lidx_patterned", C.c_int32),
+                ("pat_cap", C.c_int32), ("pat_entries", C.c_int64)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -58,6 +59,7 @@ class spmv_analysis_host_t(C.Structure):
     _fields_ = [("bin_count", C.c_void_p), ("bin_offset", C.c_void_p), ("bin_rows", C.c_void_p),
                 ("row_blocks", C.c_void_p), ("mp_row", C.c_void_p), ("mp_nz", C.c_void_p),
                 ("xv_ptr", C.c_void_p), ("xv_start", C.c_void_p), ("xv_pad", C.c_void_p), ("lidx", C.c_void_p),
+                ("run_desc", C.c_void_p), ("pat_pad", C.c_void_p),
                 ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p),
                 ("tp_row", C.c_void_p), ("tp_nz", C.c_void_p), ("tp_piece_c", C.c_void_p), ("tp_piece_g", C.c_void_p),
                 ("tp_chunk_g", C.c_void_p), ("tp_col", C.c_void_p), ("tp_src", C.c_void_p), ("tp_dst", C.c_void_p),
@@ -197,6 +199,9 @@ def _host_buffers(info):
         bufs.update(xv_ptr=np.zeros(info.num_row_blocks + 1, np.int32), xv_start=np.zeros(info.num_x_vectors, np.int32),
                     xv_pad=np.zeros(info.num_row_blocks * max(1, info.max_x_vectors), np.int32),
                     lidx=np.zeros(info.nnz, np.uint16))
+        if info.lidx_patterned:
+            bufs.update(run_desc=np.zeros(8 * info.num_row_blocks, np.int32),
+                        pat_pad=np.zeros(info.num_row_blocks * info.pat_cap, np.uint16))
     if info.plan == SPMV_PLAN_COLBLOCK:
         bufs.update(cb_ptr=np.zeros(info.num_col_blocks + 1, np.int32), cb_row=np.zeros(info.nnz, np.int32),
                     cb_col=np.zeros(info.nnz, np.int32), cb_src=np.zeros(info.nnz, np.int32))

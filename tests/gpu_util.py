@@ -115,3 +115,37 @@ def check_problem(p, params=None, strict=False, offset_elems=0, what=""):
     r = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict, what)
     A.close()
     return r
+
+
+def unpack_run_desc(words):
+    """The packed runs of the row patterns (eight words per block, see include/spmv_mi355.h) as the oracle's arrays:
+    n_runs[nb] and run_rows / run_len / run_base / run_stride [nb, 4]."""
+    w8 = words.reshape(-1, 8).astype(np.int64) & 0xFFFFFFFF
+    halves = lambda lo, hi: np.stack([w8[:, lo] & 0xFFFF, w8[:, lo] >> 16, w8[:, hi] & 0xFFFF, w8[:, hi] >> 16], axis=1)
+    stride = halves(5, 6)
+    stride = np.where(stride >= 1 << 15, stride - (1 << 16), stride)
+    length = np.stack([(w8[:, 2] >> (8 * r)) & 0xFF for r in range(4)], axis=1)
+    return dict(n_runs=w8[:, 7], run_rows=halves(0, 1), run_len=length, run_base=halves(3, 4), run_stride=stride)
+
+
+def check_patterns_equal_oracle(p, A, got, lidx, grouped):
+    """The row patterns the library kept (or its decision to keep none) against the oracle's, bit for bit."""
+    rb = got["row_blocks"]
+    nb = rb.size - 1
+    want = oracle.row_patterns(p.rowptr, rb, lidx, A.info.block_nnz)
+    patterned = (not grouped) and oracle.pattern_choice(p.nnz, want["covered"])
+    assert A.info.lidx_patterned == int(patterned), (A.info.lidx_patterned, want["covered"], p.nnz)
+    if not patterned:
+        assert A.info.pat_cap == 0 and A.info.pat_entries == 0
+        return want
+    sizes = np.diff(want["pat_ptr"])
+    cap = max(8, -(-int(sizes.max()) // 8) * 8)
+    assert (A.info.pat_cap, A.info.pat_entries) == (cap, want["covered"])
+    have = unpack_run_desc(got["run_desc"])
+    for name in ("n_runs", "run_rows", "run_len", "run_base", "run_stride"):
+        assert np.array_equal(have[name], want[name]), name
+    pad = np.zeros((nb, cap), np.uint16)
+    for b in range(nb):
+        pad[b, :sizes[b]] = want["pat"][want["pat_ptr"][b]:want["pat_ptr"][b + 1]]
+    assert np.array_equal(got["pat_pad"].reshape(nb, cap), pad)
+    return want

@@ -7,7 +7,7 @@ import pytest
 import oracle
 import paper_2603_07169_amd as s
 import workloads as w
-from gpu_util import DeviceProblem, assert_close, reference
+from gpu_util import DeviceProblem, assert_close, reference, unpack_run_desc
 
 pytestmark = pytest.mark.gpu
 
@@ -65,6 +65,11 @@ def test_full_config_matches_oracle(k):
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full merge")
     if plan == "windowed":
         assert A.info.lidx_grouped == (1 if k == 5 else 0)      # config 5's rows are aligned runs of eight columns
+        assert A.info.lidx_patterned == (1 if k in (2, 3) else 0)  # the stencils: runs of rows instead of positions
+        if A.info.lidx_patterned:
+            runs = unpack_run_desc(got["run_desc"])
+            assert (runs["n_runs"] > 0).all() and A.info.pat_entries == p.nnz and A.info.pat_cap == {2: 16, 3: 64}[k]
+            assert s.spmv_csr_main_kernel_name(A.handle) == "spmv_pattern_kernel"
         # x windows: 300 sampled row blocks (first, last, random), each against the oracle run on that block alone
         rb, xv_ptr = got["row_blocks"], got["xv_ptr"]
         nb = rb.size - 1
@@ -78,6 +83,13 @@ def test_full_config_matches_oracle(k):
             assert np.array_equal(got["lidx"][k0:k1], li[k0:k1]), b
             V = int(A.info.max_x_vectors)
             assert np.array_equal(got["xv_pad"][b * V:b * V + nv[0]], xs) and np.all(got["xv_pad"][b * V + nv[0]:(b + 1) * V] == -1), b
+            if A.info.lidx_patterned:
+                want = oracle.row_patterns(p.rowptr, rb[b:b + 2].copy(), li, A.info.block_nnz)
+                for name in ("n_runs", "run_rows", "run_len", "run_base", "run_stride"):
+                    assert np.array_equal(runs[name][b], want[name][0]), (name, b)
+                cap = int(A.info.pat_cap)
+                assert np.array_equal(got["pat_pad"][b * cap:b * cap + want["pat"].size], want["pat"]), b
+                assert not got["pat_pad"][b * cap + want["pat"].size:(b + 1) * cap].any(), b
         A.close()
         # the tile kernel (global x gathers) on the same matrix, which AUTO no longer picks here
         A = d.matrix(dict(plan=s.SPMV_PLAN_ADAPTIVE))

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2603_07169_amd as s
 import workloads as w
-from gpu_util import (ALL_PLANS, DeviceProblem, assert_close, check_problem, expected_auto_plan, plan_params, reference,
+from gpu_util import (check_patterns_equal_oracle, ALL_PLANS, DeviceProblem, assert_close, check_problem, expected_auto_plan, plan_params, reference,
                       to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -183,13 +183,70 @@ def check_windows_equal_oracle(p, A):
     assert np.array_equal(got["xv_ptr"], xv_ptr)
     assert np.array_equal(got["xv_start"], xv_start)
     assert np.array_equal(got["lidx"], lidx)
-    assert A.info.lidx_grouped == int(oracle.lidx_grouped(p.rowptr, got["row_blocks"], lidx))
+    grouped = oracle.lidx_grouped(p.rowptr, got["row_blocks"], lidx)
+    assert A.info.lidx_grouped == int(grouped)
+    check_patterns_equal_oracle(p, A, got, lidx, grouped)
     # the fixed-stride copy: block b's vectors at b*V, then -1
     V = max(1, int(A.info.max_x_vectors))
     pad = np.full((nv.size, V), -1, np.int32)
     for b in range(nv.size):
         pad[b, :nv[b]] = xv_start[xv_ptr[b]:xv_ptr[b + 1]]
     assert np.array_equal(got["xv_pad"].reshape(nv.size, V), pad)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", ["laplace", "stencil27", "broken", "unaligned", "wide_blocks", "reversed"])
+def test_row_patterns_of_window_positions(dtype, shape):
+    """Stencils: the window positions of a row are those of the row before plus a constant, so the kernel works from a
+    few runs per block instead of the position stream and the row offsets.  Rows that break the pattern in the middle
+    of a block (more than four runs: that block falls back to its positions; up to four: it stays patterned), arrays
+    off their allocations, blocks of more rows than a workgroup has lanes, columns stored in descending order (a row's
+    first entry no longer sits lowest: no pattern).  The runs and pattern lists bit for bit, and the product, each time."""
+    params = None
+    if shape == "stencil27":
+        p = w.stencil27(24, dtype=dtype, alpha=0.75, beta=-0.5)
+        p.y0 = np.linspace(-1, 1, p.m, dtype=np.float32)
+        params = dict(rows_max=24, block_nnz=24 * 27)          # one grid line per block: three runs
+    elif shape == "wide_blocks":
+        p = w.laplace2d(640, dtype=dtype, alpha=-1.25, beta=0.5)
+        params = dict(rows_max=640, block_nnz=3200)            # one grid line per block: 640 rows for 256 lanes
+    else:
+        p = w.laplace2d(160, dtype=dtype, alpha=-1.25, beta=0.5)
+    colidx, vals = p.colidx.copy(), p.vals
+    if shape == "broken":
+        # default blocks hold 64 rows here; blocks 10 and 20 start a grid line.  Block 10: three rows apart lose their
+        # pattern (eight runs: positions again).  Block 20: one row does (four runs: still patterned).  The right
+        # neighbour's column moves two further.
+        for r in (10 * 64 + 9, 10 * 64 + 30, 10 * 64 + 50, 20 * 64 + 33):
+            k = p.rowptr[r] + int(np.flatnonzero(colidx[p.rowptr[r]:p.rowptr[r + 1]] == r + 1)[0])
+            colidx[k] = r + 3
+    if shape == "reversed":
+        for r in range(p.m):
+            colidx[p.rowptr[r]:p.rowptr[r + 1]] = colidx[p.rowptr[r]:p.rowptr[r + 1]][::-1]
+        vals = p.vals.copy()
+        for r in range(p.m):
+            vals[p.rowptr[r]:p.rowptr[r + 1]] = vals[p.rowptr[r]:p.rowptr[r + 1]][::-1]
+    q = w.CsrProblem(p.name + "_" + shape, p.dtype, p.m, p.n, p.rowptr, colidx, vals, p.x, p.y0, p.alpha, p.beta)
+    log("case row patterns", dtype, shape, q.nnz)
+    d = DeviceProblem(q, offset_elems=1 if shape == "unaligned" else 0)
+    A = d.matrix(params)
+    assert A.info.plan == s.SPMV_PLAN_WINDOWED
+    assert A.info.lidx_patterned == (0 if shape == "reversed" else 1)
+    assert s.spmv_csr_main_kernel_name(A.handle) == ("spmv_window_kernel" if shape == "reversed" else "spmv_pattern_kernel")
+    got = A.analysis()
+    ve = 8 if dtype == "bf16" else 4
+    _, _, _, lidx = oracle.x_windows(q.rowptr, q.colidx, got["row_blocks"], A.info.block_nnz, ve)
+    want = check_patterns_equal_oracle(q, A, got, lidx, False)
+    if shape == "broken":
+        assert want["n_runs"][10] == 0 and want["n_runs"][20] == 4 and (np.delete(want["n_runs"], 10) > 0).all()
+    elif shape != "reversed":
+        assert (want["n_runs"] > 0).all()
+    check_windows_equal_oracle(q, A)
+    y_ref, S_ref = reference(q)
+    assert_close(q, d.run(A), y_ref, S_ref, q.alpha, q.beta)
+    y1 = d.run(A)
+    assert np.array_equal(y1, d.run(A))       # no atomics on the path: the same bits again
+    A.close()
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
