@@ -349,16 +349,15 @@ __global__ __launch_bounds__(WG, 8) void spmv_tile_kernel(const TileArgs a) {
     tile_rows<MERGE, WG>(cols_l, vals_l, x, seg, nr, r0, part, k1 - k0, o, deferred, &n_deferred, tid);
 }
 
-// First elements of the x vectors a lane fetches for block `part` (-1: none).  after: 0, possibly obtained from a value
-// the loads are to follow.  A lane with nothing to fetch reads the start of lidx instead.
+// First elements of the x vectors a lane fetches for block `part` (-1: none; lanes from x_cap on read the start of lidx
+// instead and must not use what they get).  after: 0, possibly obtained from a value the loads are to follow.
 template <int WG, int XPL>
 __device__ __forceinline__ void load_x_addresses(const TileArgs& a, int part, int tid, int after, int (&xs)[XPL]) {
 #pragma unroll
     for (int u = 0; u < XPL; ++u) {
         const int i = tid + u * WG;
         const int32_t* src = i < a.x_cap ? a.xv_pad + part * a.x_cap + i + after : reinterpret_cast<const int32_t*>(a.lidx);
-        xs[u] = *src;
-        xs[u] = i < a.x_cap ? xs[u] : -1;
+        xs[u] = *src;  // a lane beyond x_cap holds something else than an address: the users test i < x_cap first
     }
 }
 
@@ -477,6 +476,7 @@ __device__ __forceinline__ void window_block(const TileArgs& a, int part, int (&
     bool xvec[XPL];
 #pragma unroll
     for (int u = 0; u < XPL; ++u) {
+        xs[u] = tid + u * WG < a.x_cap ? xs[u] : -1;
         xvec[u] = xs[u] >= 0 && a.x_vec_ok && xs[u] + XE <= a.n;
         const E* src = xvec[u] ? x + xs[u] : reinterpret_cast<const E*>(dummy);
         xv[u] = *reinterpret_cast<const u32x4*>(src);
@@ -602,7 +602,8 @@ __device__ __forceinline__ void pattern_rows_g(const E* vals_l, const E* xbuf, c
 }
 
 template <typename T, int WG, int XPL, int NG>
-__device__ __forceinline__ void pattern_block(const TileArgs& a, int part, int (&xs)[XPL], const int32_t* rd) {
+__device__ __forceinline__ void pattern_block(const TileArgs& a, int part, int (&xs)[XPL], const int32_t* rd, int r0, int k0,
+                                              int r1, int k1) {
     using E = typename T::elem;
     constexpr int XE = 16 / sizeof(E);
     extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -616,10 +617,7 @@ __device__ __forceinline__ void pattern_block(const TileArgs& a, int part, int (
     const uint16_t* const pt_src = tid < pt_vecs ? a.pat_pad + static_cast<int64_t>(part) * a.pt_cap + 8 * tid : dummy;
     const u32x4 ptab = *reinterpret_cast<const u32x4*>(pt_src);
 
-    const int r0 = a.part_desc[2 * part];
-    const int k0 = a.part_desc[2 * part + 1];
-    const int nr = a.part_desc[2 * part + 2] - r0;
-    const int k1 = a.part_desc[2 * part + 3];
+    const int nr = r1 - r0;
     if constexpr (XPL > 1) {
         int zero;
         asm volatile("s_mov_b32 %0, 0" : "=s"(zero) : "s"(k1));
@@ -669,6 +667,7 @@ __device__ __forceinline__ void pattern_block(const TileArgs& a, int part, int (
     bool xvec[XPL];
 #pragma unroll
     for (int u = 0; u < XPL; ++u) {
+        xs[u] = tid + u * WG < a.x_cap ? xs[u] : -1;
         xvec[u] = xs[u] >= 0 && a.x_vec_ok && xs[u] + XE <= a.n;
         const E* src = xvec[u] ? x + xs[u] : reinterpret_cast<const E*>(dummy);
         xv[u] = *reinterpret_cast<const u32x4*>(src);
@@ -721,14 +720,12 @@ __device__ __forceinline__ void pattern_block(const TileArgs& a, int part, int (
     }
     __syncthreads();
 
-    // lanes per row as in tile_rows
+    // Lanes per row: as many as fill the workgroup in one sweep over the block's rows (what is in LDS is then taken by
+    // the most lanes at once: measured 35 us on the 27-point stencil with two lanes for each of its 128 rows, 58 us
+    // with one, 38 us with four), but at least four entries for every lane.
     const int tile_nnz = k1 - k0;
     int G = 1;
-    while (G < 64 && (16 * G + 1) * nr <= tile_nnz) G <<= 1;
-    if (tile_nnz >= 64 * nr) {
-        G = 64;
-        while (4 * G * nr > tile_nnz) G >>= 1;
-    }
+    while (G < 16 && 2 * G * nr <= WG && 8 * G * nr <= tile_nnz) G <<= 1;
     switch (G) {
         case 1: pattern_rows_g<WG, 1>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
         case 2: pattern_rows_g<WG, 2>(vals_l, xbuf, pat_l, y0_l, rt, nr, r0, a.y, a.alpha, a.beta, tid); break;
@@ -744,10 +741,13 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_patter
     int xs[XPL];
     if constexpr (XPL == 1) load_x_addresses<WG, XPL>(a, part, threadIdx.x, 0, xs);
     const int32_t* rd = a.run_desc + 8 * static_cast<int64_t>(part);
-    if (rd[7] == 0)
+    const int runs = rd[7];
+    const int r0 = a.part_desc[2 * part], k0 = a.part_desc[2 * part + 1];  // with the runs: one wait for both scalar loads
+    const int r1 = a.part_desc[2 * part + 2], k1 = a.part_desc[2 * part + 3];
+    if (runs == 0)
         window_block<T, WG, XPL, NG, false>(a, part, xs);
     else
-        pattern_block<T, WG, XPL, NG>(a, part, xs, rd);
+        pattern_block<T, WG, XPL, NG>(a, part, xs, rd, r0, k0, r1, k1);
 }
 
 // Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
