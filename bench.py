@@ -71,8 +71,9 @@ def kernels_sha256():
 
 
 def recorded_traffic(workload):
-    """HBM bytes per launch from the committed counter summary, or None when there is none or the
-    kernel sources have changed since it was taken."""
+    """HBM bytes one product really moves (FETCH_SIZE + WRITE_SIZE of every kernel of the plan, scaled by the copy
+    calibration) from the committed counter summary, or None when there is none or the kernel sources have changed
+    since it was taken."""
     f = ROOT / "profiles" / f"traffic_{workload}.txt"
     if not f.exists():
         return None
@@ -87,6 +88,19 @@ def recorded_traffic(workload):
         return float(kv["hbm_bytes_per_launch"])
     except (KeyError, ValueError):
         return None
+
+
+def roofline_block(r):
+    """The HBM roofline of one measured workload.  frac_effective = algorithmic CSR bytes / time / peak is the metric's
+    ratio; a plan that moves fewer bytes than CSR's own arrays (16-bit window positions, row patterns) can push it past
+    1, so it is no statement about the memory.  frac_real = bytes the counters saw / time / peak is that statement."""
+    traffic = recorded_traffic(r["workload"])
+    ms = r["ms_per_step"]
+    return {"bound": "hbm", "peak": HBM_PEAK_GBPS, "unit": "GB/s", "kernel": r["kernel"],
+            "algorithmic_bytes": r["algorithmic_bytes"], "achieved": r["GBps"], "frac_effective": r["GBps"] / HBM_PEAK_GBPS,
+            "traffic": traffic, "real_GBps": None if traffic is None else traffic / ms / 1e6,
+            "frac_real": None if traffic is None else traffic / ms / 1e6 / HBM_PEAK_GBPS,
+            "traffic_over_algorithmic": None if traffic is None else traffic / r["algorithmic_bytes"]}
 
 
 def dev(a):
@@ -178,9 +192,10 @@ def measure_problem(p, args, params):
         "workload": p.name, "dtype": p.dtype, "m": p.m, "n": p.n, "nnz": p.nnz, "alpha": p.alpha, "beta": p.beta,
         "algorithmic_bytes": bytes_alg, "plan": s.PLAN_NAMES[res.info.plan], "kernel": res.kernel,
         "copies_rotated": copies, "ms_per_step": ms, "ms_median": med, "ms_min": mn, "ms_per_step_wall": wall_ms,
-        "GBps": bytes_alg / ms / 1e6, "GFLOPs": p.flops() / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS,
+        "GBps": bytes_alg / ms / 1e6, "GFLOPs": p.flops() / ms / 1e6,
         "warm_ms_per_step": ms_warm, "warm_GBps": bytes_alg / ms_warm / 1e6, "analysis_ms": res.analysis_ms,
     }
+    out["roofline"] = roofline_block(out)
     res.close()
     return p, out
 
@@ -390,23 +405,23 @@ def graph_replay(args, configs=(1, 2)):
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / args.steps
         out.append({"workload": p.name, "steps_in_graph": args.steps, "copies_rotated": copies, "ms_per_step": ms,
-                    "GBps": bytes_alg / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS})
+                    "GBps": bytes_alg / ms / 1e6, "frac_effective": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS})
         res.close()
     return out
 
 
-def cpu_baseline(p):
-    """The oracle as it stands, one thread, on the whole workload: 1 warm-up + best of 5."""
+def cpu_baseline(p, runs=3):
+    """The oracle as it stands, one thread, on the whole workload: 1 warm-up + best of `runs`."""
     import oracle
     best = float("inf")
-    for i in range(6):
+    for i in range(runs + 1):
         t0 = time.perf_counter()
         oracle.spmv_problem(p)
         dt = time.perf_counter() - t0
         if i > 0:
             best = min(best, dt)
     return {"value": p.algorithmic_bytes() / best / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": f"whole workload {p.name} ({p.nnz} nnz), single thread, best of 5 after 1 warm-up",
+            "sample": f"whole workload {p.name} ({p.nnz} nnz), single thread, best of {runs} after 1 warm-up",
             "ms": best * 1e3, "GFLOPs": p.flops() / best / 1e9, "host_cores_available": os.cpu_count()}
 
 
@@ -431,19 +446,32 @@ def main():
         return
     params = dict(plan=args.plan, block_nnz=args.block_nnz, rows_max=args.rows_max,
                   items_per_chunk=args.items_per_chunk, vector_lanes=args.vector_lanes, skip_validation=0)
-    p, head = measure(args.config, args, params)
+    # every configuration in turn, each with the oracle timed on this host beside it; the headline is one of them
+    per = {}
+    for k in ([args.config] if args.only else range(1, 6)):
+        p, r = measure(k, args, params)
+        if not args.no_cpu_baseline:
+            r["cpu_baseline"] = cpu_baseline(p)
+        per[k] = r
+        if k == args.config:
+            head, shape = r, (p.m, p.n, p.nnz, p.alpha, p.beta, p.dtype)
+        del p
+    m, n, nnz, alpha, beta, storage = shape
+    roof = dict(head["roofline"])
+    roof["frac"] = roof["frac_effective"]   # algorithmic bytes / time / peak, as the metric defines it (see frac_real beside it)
+    roof["algorithmic_bytes_per_launch"] = head["algorithmic_bytes"]
+    roof["avg_launch_ms"] = head["ms_per_step"]
     line = {
         "metric": "CSR SpMV effective HBM bandwidth (algorithmic bytes / time)",
         "value": head["GBps"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": head["workload"], "m": p.m, "n": p.n, "nnz": p.nnz, "alpha": p.alpha, "beta": p.beta,
-                   "storage": p.dtype, "plan": head["plan"], "cache_state": f"cold: rotating over {head['copies_rotated']} disjoint copies"},
+        "dtype": storage, "data": "synthetic",
+        "config": {"workload": head["workload"], "m": m, "n": n, "nnz": nnz, "alpha": alpha, "beta": beta,
+                   "storage": storage, "plan": head["plan"], "cache_state": f"cold: rotating over {head['copies_rotated']} disjoint copies",
+                   "why_this_one": "the second of the five configurations (the 2-D Laplacian), the one the 70 % target names that is large "
+                                   "enough to stream; all five are measured in per_config, each with its own roofline block"},
         "gflops": head["GFLOPs"], "warm_GBps": head["warm_GBps"],
-        "roofline": {"bound": "hbm", "achieved": head["GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": head["hbm_frac"], "traffic": recorded_traffic(head["workload"]), "kernel": head["kernel"],
-                     "algorithmic_bytes_per_launch": head["algorithmic_bytes"],
-                     "avg_launch_ms": head["ms_per_step"]},
+        "roofline": roof,
     }
     if args.calibration_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
@@ -452,15 +480,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(p)
-    del p
+        line["cpu_baseline"] = head["cpu_baseline"]
     if not args.only:
-        per = [head]
-        for k in range(1, 6):
-            if k != args.config:
-                _, r = measure(k, args, params)
-                per.append(r)
-        line["per_config"] = sorted(per, key=lambda r: r["workload"])
+        line["per_config"] = sorted(per.values(), key=lambda r: r["workload"])
     if not args.only and not args.no_extras:
         import workloads as w
         line["launch_floor_us"] = launch_floor_us()

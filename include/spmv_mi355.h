@@ -23,8 +23,12 @@
  *   - Column indices inside a row may be in any order and may repeat (repeats add up).
  *   - Every function returns a status; nothing throws, aborts or prints.
  *   - spmv_csr_run() only enqueues kernels on the given stream: no synchronisation, no
- *     allocation, no host<->device copy.  At most one run per handle may be in flight
- *     (the merge plan keeps its carry-out buffers in the handle).
+ *     allocation, no host<->device copy.  Runs of one handle on one stream follow each other; runs
+ *     on several streams may overlap under every plan except MERGE and TWOPHASE, whose kernels pass
+ *     carries / products through scratch kept in the handle: there a run on another stream while
+ *     the last one is still in flight is refused with SPMV_ERR_BUSY and enqueues nothing (order the
+ *     streams with an event, or give each stream a handle of its own; the check is an event query
+ *     and is left out on a stream that is being captured into a graph).
  *   - Read-back functions copy to caller-owned HOST buffers and synchronise the device.
  */
 #ifndef SPMV_MI355_H
@@ -51,7 +55,8 @@ typedef enum {
     SPMV_ERR_UNSUPPORTED = 3,   /* a size > SPMV_MAX_SIZE, or pointers not aligned to the element size */
     SPMV_ERR_NOT_ANALYZED = 4,  /* run or read-back before a successful analyze */
     SPMV_ERR_ALLOC = 5,         /* host or device allocation failed */
-    SPMV_ERR_HIP = 6            /* a HIP runtime call failed; see spmv_last_hip_error() */
+    SPMV_ERR_HIP = 6,           /* a HIP runtime call failed; see spmv_last_hip_error() */
+    SPMV_ERR_BUSY = 7           /* spmv_csr_run: the plan's scratch is still in use by a run on another stream */
 } spmv_status_t;
 
 /* Execution plans.  AUTO lets analyze choose (rule documented at spmv_csr_analyze). */
@@ -272,7 +277,7 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
  *   x  device, n elements of the handle's dtype;   y  device float[m], read only if beta != 0.
  *   x and y must not overlap.  beta == 0 never reads y (NaN/Inf there do not propagate).
  * m == 0 is a no-op; nnz == 0 gives y <- beta*y.
- * Errors: INVALID_ARG (null x or y with m, n > 0), NOT_ANALYZED, HIP (launch failure). */
+ * Errors: INVALID_ARG (null x or y with m, n > 0), NOT_ANALYZED, BUSY (see the conventions), HIP (launch failure). */
 spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha, float beta, void* stream);
 
 /* Sparse times dense (paper App. C task 13: C = A B, A in CSR, B of shape cols x K), in the BLAS

@@ -79,6 +79,11 @@ struct spmv_csr_s {
     float* d_tp_carry_val = nullptr;
     size_t tp_reduce_lds = 0;
     std::vector<int32_t> tp_row, tp_nz;  // host copies for the read-back
+    // The MERGE and TWOPHASE plans keep scratch in the handle (carries, products): a run on another stream while one is
+    // still in flight would share it.  An event recorded behind every such run tells.
+    hipEvent_t scratch_free = nullptr;
+    hipStream_t scratch_stream = nullptr;
+    bool scratch_used = false;
     int32_t* d_spmm_rows = nullptr;  // row order of spmm_csr_run (prepare_spmm)
     int32_t* d_spmm_desc = nullptr;  // packed copy of A in that order (spmm_prepared == 2)
     void* d_spmm_col = nullptr;
@@ -115,7 +120,32 @@ void free_metadata(spmv_csr_s* h) {
     h->d_spmm_rows = h->d_spmm_desc = nullptr;
     h->d_spmm_col = nullptr;
     h->d_spmm_val = nullptr;
+    if (h->scratch_free) (void)hipEventDestroy(h->scratch_free);
+    h->scratch_free = nullptr;
+    h->scratch_used = false;
     h->analyzed = false;
+}
+
+// Plans whose kernels write scratch owned by the handle.
+inline bool plan_has_scratch(int32_t plan) { return plan == SPMV_PLAN_MERGE || plan == SPMV_PLAN_TWOPHASE; }
+
+// Before a run that uses the handle's scratch: SPMV_ERR_BUSY when an earlier run on another stream has not finished.
+// Nothing is asked of a stream under capture (the queries are not allowed there): *tracked says whether to record.
+spmv_status_t scratch_acquire(spmv_csr_s* h, hipStream_t st, bool* tracked) {
+    *tracked = false;
+    if (!h->scratch_free) return SPMV_OK;
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (st != nullptr && (hip_failed(hipStreamIsCapturing(st, &cs)) || cs != hipStreamCaptureStatusNone)) return SPMV_OK;
+    *tracked = true;
+    if (h->scratch_used && st != h->scratch_stream) {
+        const hipError_t e = hipEventQuery(h->scratch_free);
+        if (e == hipErrorNotReady) {
+            (void)hipGetLastError();
+            return SPMV_ERR_BUSY;
+        }
+        if (hip_failed(e)) return SPMV_ERR_HIP;
+    }
+    return SPMV_OK;
 }
 
 template <typename T>
@@ -303,6 +333,8 @@ spmv_status_t build_column_blocks(spmv_csr_s* h, spmv::Analysis* a) {
                  hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_cb_src), sizeof(int32_t) * slots)) ||
                  hip_failed(hipMalloc(&h->d_cb_vals, (h->dtype == SPMV_F32 ? 4 : 2) * slots)))
             st = SPMV_ERR_ALLOC;
+        else if (hip_failed(hipMemset(h->d_cb_src, 0xFF, sizeof(int32_t) * slots)))  // -1: a slot no entry was placed in
+            st = SPMV_ERR_HIP;
         else if (hip_failed(spmv::launch_column_block_scatter(A, shift, C, d_counts, h->d_cb_row, h->d_cb_col, h->d_cb_src,
                                                               h->d_cb_vals, nullptr)) ||
                  hip_failed(hipDeviceSynchronize()))
@@ -606,6 +638,9 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
             hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_carry_val), sizeof(float) * P)))
             st = SPMV_ERR_ALLOC;
     }
+    if (st == SPMV_OK && plan_has_scratch(a.info.plan) &&
+        hip_failed(hipEventCreateWithFlags(&h->scratch_free, hipEventDisableTiming)))
+        st = SPMV_ERR_HIP;
     if (st == SPMV_OK && hip_failed(hipDeviceSynchronize())) st = SPMV_ERR_HIP;
     if (st != SPMV_OK) {
         free_metadata(h);
@@ -632,6 +667,11 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
     const spmv::Scalars s{alpha, beta};
     const int32_t m = A.m;
     hipError_t e = hipSuccess;
+    bool tracked = false;
+    if (plan_has_scratch(h->info.plan)) {
+        const spmv_status_t busy = scratch_acquire(h, st, &tracked);
+        if (busy != SPMV_OK) return busy;
+    }
     switch (h->info.plan) {
         case SPMV_PLAN_SCALAR:
             e = spmv::launch_scalar(A, nullptr, m, x, y, s, st);
@@ -688,6 +728,11 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
             break;
         default:
             return SPMV_ERR_INVALID_ARG;
+    }
+    if (tracked && e == hipSuccess) {
+        e = hipEventRecord(h->scratch_free, st);
+        h->scratch_stream = st;
+        h->scratch_used = true;
     }
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
@@ -764,7 +809,8 @@ spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* c
     if (width < 0) return SPMV_ERR_INVALID_ARG;
     if (width > kMaxCount) return SPMV_ERR_UNSUPPORTED;
     // m * width itself may exceed the limit: slots are addressed with 64-bit offsets
-    const spmv_status_t st = check_stateless(m, n, m > 0 ? width : 0, dtype, col_ids, col_ids, vals, x, y);
+    // without columns x may point at nothing: only the slot arrays are then checked for alignment
+    const spmv_status_t st = check_stateless(m, n, m > 0 && n > 0 ? width : 0, dtype, col_ids, col_ids, vals, n > 0 ? x : nullptr, y);
     if (st != SPMV_OK) return st;
     // without columns every slot is padding: y <- beta*y, and x (which may point at nothing) is never read
     const hipError_t e =
@@ -959,6 +1005,7 @@ const char* spmv_status_string(spmv_status_t s) {
         case SPMV_ERR_NOT_ANALYZED: return "handle not analyzed";
         case SPMV_ERR_ALLOC: return "allocation failed";
         case SPMV_ERR_HIP: return "HIP runtime error";
+        case SPMV_ERR_BUSY: return "the handle's scratch is in use by a run on another stream";
         default: return "unknown status";
     }
 }

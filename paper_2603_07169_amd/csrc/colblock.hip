@@ -77,8 +77,12 @@ __global__ __launch_bounds__(64) void cb_tile_kernel(const int32_t* __restrict__
 template <typename E>
 __global__ __launch_bounds__(kWG) void cb_values_kernel(const E* __restrict__ vals, const int32_t* __restrict__ cb_src,
                                                         E* __restrict__ cb_vals, int nnz) {
-    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; k < nnz; k += static_cast<int64_t>(gridDim.x) * kWG)
-        cb_vals[k] = vals[cb_src[k]];
+    // a slot the regrouping left unfilled (an entry dropped for a column outside the matrix, which only a caller who
+    // skipped the validation can have) keeps the -1 it was cleared to
+    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; k < nnz; k += static_cast<int64_t>(gridDim.x) * kWG) {
+        const int src = cb_src[k];
+        if (src >= 0 && src < nnz) cb_vals[k] = vals[src];
+    }
 }
 
 }  // namespace

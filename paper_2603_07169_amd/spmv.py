@@ -16,7 +16,7 @@ from . import build as _build
 SPMV_F32, SPMV_BF16 = 0, 1
 SPMV_OK = 0
 (SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_STRUCTURE, SPMV_ERR_UNSUPPORTED, SPMV_ERR_NOT_ANALYZED, SPMV_ERR_ALLOC,
- SPMV_ERR_HIP) = range(1, 7)
+ SPMV_ERR_HIP, SPMV_ERR_BUSY) = range(1, 8)
 (SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE,
  SPMV_PLAN_WINDOWED, SPMV_PLAN_COLBLOCK, SPMV_PLAN_TWOPHASE) = range(9)
 PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock",

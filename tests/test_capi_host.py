@@ -32,7 +32,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_status_strings():
     assert s.spmv_status_string(0) == "ok"
-    assert len({s.spmv_status_string(k) for k in range(7)}) == 7
+    assert len({s.spmv_status_string(k) for k in range(8)}) == 8 and s.spmv_status_string(8) == "unknown status"
 
 
 def test_create_argument_errors():

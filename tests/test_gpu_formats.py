@@ -133,6 +133,11 @@ def test_beta_zero_ignores_nan_and_argument_errors():
     assert s.spmv_ell_run(5, 3, 0, None, None, 0, d[3].data_ptr(), y.data_ptr(), 1.0, 0.5) == s.SPMV_OK
     torch.cuda.synchronize()
     assert np.array_equal(y.cpu().numpy(), np.arange(5, dtype=np.float32))
+    # no columns at all: every slot is padding, x may point at nothing
+    ci = to_dev(np.full(5 * 4, -1, np.int32))
+    assert s.spmv_ell_run(5, 0, 4, ci.data_ptr(), d[2].data_ptr(), 0, None, y.data_ptr(), 1.0, 3.0) == s.SPMV_OK
+    torch.cuda.synchronize()
+    assert np.array_equal(y.cpu().numpy(), 3 * np.arange(5, dtype=np.float32))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])

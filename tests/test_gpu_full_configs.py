@@ -119,7 +119,7 @@ def test_power_law_literal_reading_and_capped_row():
         A.close()
 
 
-@pytest.mark.parametrize("rows", [2 ** 10, 2 ** 12, 2 ** 15])
+@pytest.mark.parametrize("rows", [2 ** 10, 2 ** 11, 2 ** 12, 2 ** 13, 2 ** 14, 2 ** 15])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_paper_shapes_absolute_tolerance(rows, dtype):
     """The benchmark's own sizes for this task (App. C task 12: cols 2048, density 0.01) with its

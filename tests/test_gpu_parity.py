@@ -586,3 +586,64 @@ def test_values_changed_in_place_are_picked_up_after_refresh(dtype):
         assert_close(p2, d.run(A), y_new, S_new, p.alpha, p.beta, what="after " + s.PLAN_NAMES[plan])
         A.close()
 
+
+
+def test_two_handles_on_two_streams_and_one_handle_refusing_a_second_stream():
+    """Two handles, each on a stream of its own, overlap freely and both give the oracle's result.  One handle whose plan
+    keeps scratch (MERGE, TWOPHASE) refuses a run on a second stream while its last run is still in flight, enqueues
+    nothing, and takes the run once the first has finished; a plan without scratch takes both at once."""
+    p = w.powerlaw(1_000_000, beta=0.5)
+    p.y0 = np.linspace(-1, 1, p.m, dtype=np.float32)
+    y_ref, S_ref = reference(p)
+    d1, d2 = DeviceProblem(p), DeviceProblem(p)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for plan in (s.SPMV_PLAN_MERGE, s.SPMV_PLAN_TWOPHASE, s.SPMV_PLAN_ADAPTIVE):
+        log("case two streams", s.PLAN_NAMES[plan])
+        A1, A2 = d1.matrix(dict(plan=plan)), d2.matrix(dict(plan=plan))
+        ya, yb = d1.y0.clone(), d2.y0.clone()
+        torch.cuda.synchronize()
+        for _ in range(3):            # re-runs on a handle's own stream are always in order
+            ya.copy_(d1.y0), yb.copy_(d2.y0)
+            torch.cuda.synchronize()
+            assert s.spmv_csr_run(A1.handle, d1.x.data_ptr(), ya.data_ptr(), p.alpha, p.beta, s1.cuda_stream) == s.SPMV_OK
+            assert s.spmv_csr_run(A2.handle, d2.x.data_ptr(), yb.data_ptr(), p.alpha, p.beta, s2.cuda_stream) == s.SPMV_OK
+            torch.cuda.synchronize()
+            assert_close(p, ya.cpu().numpy(), y_ref, S_ref, p.alpha, p.beta, what="stream 1")
+            assert_close(p, yb.cpu().numpy(), y_ref, S_ref, p.alpha, p.beta, what="stream 2")
+        # one handle, two streams, no ordering between them
+        ya.copy_(d1.y0), yb.copy_(d1.y0)
+        torch.cuda.synchronize()
+        first = [s.spmv_csr_run(A1.handle, d1.x.data_ptr(), ya.data_ptr(), p.alpha, p.beta, s1.cuda_stream) for _ in range(4)]
+        second = s.spmv_csr_run(A1.handle, d1.x.data_ptr(), yb.data_ptr(), p.alpha, p.beta, s2.cuda_stream)
+        assert first[0] == s.SPMV_OK
+        if plan == s.SPMV_PLAN_ADAPTIVE:
+            assert second == s.SPMV_OK
+        else:
+            assert second == s.SPMV_ERR_BUSY            # four products of 8 M entries cannot have finished yet
+            torch.cuda.synchronize()
+            assert np.array_equal(yb.cpu().numpy(), d1.y0.cpu().numpy())     # nothing was enqueued
+            assert s.spmv_csr_run(A1.handle, d1.x.data_ptr(), yb.data_ptr(), p.alpha, p.beta, s2.cuda_stream) == s.SPMV_OK
+        torch.cuda.synchronize()
+        assert_close(p, yb.cpu().numpy(), y_ref, S_ref, p.alpha, p.beta, what="second stream")
+        A1.close(), A2.close()
+
+
+def test_column_block_refresh_with_columns_the_caller_did_not_check():
+    """skip_validation with a column outside the matrix: the regrouping drops that entry, and refreshing the value copy
+    must not read through the slot it left unfilled."""
+    p = w.uniform_rows(3000, 5000, 9)
+    colidx = p.colidx.copy()
+    colidx[123] = 1 << 30                                   # far outside every column block
+    d = DeviceProblem(p)
+    d.colidx.copy_(to_dev(colidx))
+    A = d.matrix(dict(plan=s.SPMV_PLAN_COLBLOCK, skip_validation=1))
+    A.refresh_values()
+    torch.cuda.synchronize()
+    got = A.analysis()
+    assert got["cb_ptr"][-1] == p.nnz - 1 and got["cb_src"][-1] == -1
+    vals = p.vals.copy()
+    vals[123] = 0.0                                         # the product without the dropped entry
+    q = w.CsrProblem(p.name, p.dtype, p.m, p.n, p.rowptr, p.colidx, vals, p.x, p.y0, p.alpha, p.beta)
+    y_ref, S_ref = reference(q)
+    assert_close(q, d.run(A), y_ref, S_ref, q.alpha, q.beta, what="dropped entry")
+    A.close()
