@@ -52,6 +52,8 @@ def _load():
         _lib.oracle_spmv_csr_bf16.restype = C.c_int
         _lib.oracle_spmm_csr_f32.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, f32, f32, vp, vp]
         _lib.oracle_spmm_csr_f32.restype = C.c_int
+        _lib.oracle_spmm_csr_bf16.argtypes = [i64, i64, i64, vp, vp, vp, vp, i64, vp, i64, f32, f32, vp, vp]
+        _lib.oracle_spmm_csr_bf16.restype = C.c_int
         _lib.oracle_spmm_row_order.argtypes = [i64, vp, i64, vp]
         _lib.oracle_spmm_row_order.restype = None
         _lib.oracle_spmm_packed_layout.argtypes = [i64, vp, vp, vp]
@@ -149,13 +151,16 @@ def spmv_problem(p):
 
 
 def spmm_csr(m, n, rowptr, colidx, vals, B, C0=None, alpha=1.0, beta=0.0):
-    """C <- alpha*A*B + beta*C0 for FP32 CSR A (m x n) and dense row-major B (n x K), possibly a
-    column slice of a wider array.  Returns (C_ref float64[m, K], S_ref float64[m, K])."""
+    """C <- alpha*A*B + beta*C0 for CSR A (m x n) and dense row-major B (n x K), possibly a column slice of a wider
+    array; vals and B both float32, or both uint16 (bf16 bit patterns).  C0 is float32.
+    Returns (C_ref float64[m, K], S_ref float64[m, K])."""
     lib = _load()
-    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32), _chk(vals, np.float32)
-    assert B.dtype == np.float32 and B.ndim == 2 and B.shape[0] == n and B.strides[1] == 4
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
+    assert vals.dtype == B.dtype and vals.dtype in (np.float32, np.uint16) and vals.flags.c_contiguous
+    esz = B.dtype.itemsize
+    assert B.ndim == 2 and B.shape[0] == n and B.strides[1] == esz
     K = B.shape[1]
-    ldb = B.strides[0] // 4
+    ldb = B.strides[0] // esz
     ldc = 0
     if beta != 0.0:
         assert C0.dtype == np.float32 and C0.shape == (m, K) and C0.strides[1] == 4
@@ -164,8 +169,9 @@ def spmm_csr(m, n, rowptr, colidx, vals, B, C0=None, alpha=1.0, beta=0.0):
         C0 = None
     Cr = np.empty((m, K), dtype=np.float64)
     S = np.empty((m, K), dtype=np.float64)
-    rc = lib.oracle_spmm_csr_f32(m, n, K, _p(rowptr), _p(colidx), _p(vals), B.ctypes.data_as(C.c_void_p), ldb,
-                                 None if C0 is None else C0.ctypes.data_as(C.c_void_p), ldc, alpha, beta, _p(Cr), _p(S))
+    fn = lib.oracle_spmm_csr_f32 if esz == 4 else lib.oracle_spmm_csr_bf16
+    rc = fn(m, n, K, _p(rowptr), _p(colidx), _p(vals), B.ctypes.data_as(C.c_void_p), ldb,
+            None if C0 is None else C0.ctypes.data_as(C.c_void_p), ldc, alpha, beta, _p(Cr), _p(S))
     if rc != 0:
         raise ValueError("malformed CSR input")
     return Cr, S

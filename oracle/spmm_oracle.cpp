@@ -49,6 +49,40 @@ int oracle_spmm_csr_f32(int64_t m, int64_t n, int64_t K, const int32_t* rowptr, 
     return 0;
 }
 
+// The same product with A's values and B stored as bf16 (the upper half of an IEEE binary32, here as uint16 bit
+// patterns; App. C task 13 in the benchmark's BF16 variant, section 3.1).  Every stored number is widened exactly
+// (bits << 16 read as a binary32); products and sums in double as above; C0, alpha, beta stay binary32.
+static double bf16_to_double(uint16_t b) {
+    const uint32_t u = static_cast<uint32_t>(b) << 16;
+    float f;
+    static_assert(sizeof f == sizeof u, "binary32");
+    __builtin_memcpy(&f, &u, sizeof f);
+    return static_cast<double>(f);
+}
+
+int oracle_spmm_csr_bf16(int64_t m, int64_t n, int64_t K, const int32_t* rowptr, const int32_t* colidx,
+                         const uint16_t* vals, const uint16_t* B, int64_t ldb, const float* C0, int64_t ldc, float alpha,
+                         float beta, double* C_ref, double* S_ref) {
+    for (int64_t i = 0; i < m; ++i) {
+        if (rowptr[i + 1] < rowptr[i]) return 1;
+        for (int64_t k = 0; k < K; ++k) {
+            double acc = 0.0, S = 0.0;
+            for (int64_t e = rowptr[i]; e < rowptr[i + 1]; ++e) {
+                const int32_t j = colidx[e];
+                if (j < 0 || j >= n) return 1;
+                const double p = bf16_to_double(vals[e]) * bf16_to_double(B[j * ldb + k]);
+                acc += p;
+                S += std::fabs(p);
+            }
+            double r = static_cast<double>(alpha) * acc;
+            if (beta != 0.0f) r += static_cast<double>(beta) * static_cast<double>(C0[i * ldc + k]);
+            C_ref[i * K + k] = r;
+            S_ref[i * K + k] = S;
+        }
+    }
+    return 0;
+}
+
 // The rows are cut into windows of `window` consecutive rows (the last one may be shorter).
 // rows[0..m) lists, window after window, the window's row ids sorted by decreasing
 // key(i) = min(ceil(len_i / 4), 64), len_i = rowptr[i+1] - rowptr[i]; rows of equal key keep

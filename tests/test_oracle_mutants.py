@@ -84,6 +84,9 @@ MUTANTS = [
     ("spmm_oracle.cpp", "static_cast<double>(B[j * ldb + k]);", "static_cast<double>(B[j * K + k]);", "leading dimension of B ignored"),
     ("spmm_oracle.cpp", "if (beta != 0.0f) r += static_cast<double>(beta)", "if (beta != 0.0f) r -= static_cast<double>(beta)", "beta*C subtracted"),
     ("spmm_oracle.cpp", "S += std::fabs(p);", "S += p;", "S without the absolute value"),
+    ("spmm_oracle.cpp", "const uint32_t u = static_cast<uint32_t>(b) << 16;\n    float f;\n    static_assert", "const uint32_t u = static_cast<uint32_t>(b) << 15;\n    float f;\n    static_assert", "bf16 widened by the wrong shift (SpMM)"),
+    ("spmm_oracle.cpp", "const double p = bf16_to_double(vals[e]) * bf16_to_double(B[j * ldb + k]);", "const double p = bf16_to_double(vals[e]) * bf16_to_double(B[j * K + k]);", "leading dimension of a bf16 B ignored"),
+    ("spmm_oracle.cpp", "const double p = bf16_to_double(vals[e]) * bf16_to_double(B[j * ldb + k]);", "const double p = static_cast<double>(static_cast<float>(bf16_to_double(vals[e]) * bf16_to_double(B[j * ldb + k])) * 1.0000001f);", "bf16 products rounded and scaled"),
     ("spmm_oracle.cpp", "return std::min<int64_t>((len + 3) / 4, 64);", "return std::min<int64_t>((len + 3) / 4, 63);", "row order: cap one too low"),
     ("spmm_oracle.cpp", "return std::min<int64_t>((len + 3) / 4, 64);", "return std::min<int64_t>(len / 4, 64);", "row order: key rounded down"),
     ("spmm_oracle.cpp", "return key(a) > key(b);", "return key(a) < key(b);", "row order ascending"),

@@ -162,3 +162,32 @@ def test_packed_copy_holds_every_entry_once(seed):
     # a group's steps: the quarter-rounded length of its longest row
     longest = np.array([lens[rows[16 * g:16 * g + 16]].max() for g in range((m + 15) // 16)])
     assert np.array_equal(desc[1:-2:2], -(-longest // 4)) and np.array_equal(np.diff(desc[0::2]), -(-longest // 16))
+
+
+# ---- bf16 storage --------------------------------------------------------------------------------
+def test_bf16_handworked_and_against_the_pinned_oracles():
+    """Values that bf16 holds exactly, worked by hand: A = [[1.5, 0, -2], [0, 0.25, 0]], B = [[2, -1], [4, 8], [0.5, 3]]
+    gives A B = [[3 - 1, -1.5 - 6], [1, 2]] and S = [[3 + 1, 1.5 + 6], [1, 2]].  Then: one column against the pinned
+    bf16 SpMV oracle, and any K against the pinned FP32 product on the widened numbers (widening is exact, so the two
+    must agree bit for bit)."""
+    bits = lambda a: w.f32_to_bf16_bits(np.asarray(a, np.float32))
+    rp, ci = np.array([0, 2, 3], np.int32), np.array([0, 2, 1], np.int32)
+    va, B = bits([1.5, -2.0, 0.25]), bits([[2, -1], [4, 8], [0.5, 3]])
+    C, S = oracle.spmm_csr(2, 3, rp, ci, va, B)
+    assert C.tolist() == [[2.0, -7.5], [1.0, 2.0]] and S.tolist() == [[4.0, 7.5], [1.0, 2.0]]
+    C0 = np.array([[1, 2], [3, 4]], np.float32)
+    C, _ = oracle.spmm_csr(2, 3, rp, ci, va, B, C0, 2.0, -0.5)
+    assert C.tolist() == [[3.5, -16.0], [0.5, 2.0]]
+    assert va.dtype == np.uint16 and va.tolist() == [0x3FC0, 0xC000, 0x3E80]      # 1.5, -2, 0.25 as bf16 bit patterns
+    p = w.powerlaw(300, dtype="bf16")
+    y0 = np.linspace(-1, 1, p.m, dtype=np.float32)
+    C, S = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, p.x.reshape(-1, 1).copy(), y0.reshape(-1, 1).copy(), 0.75, 2.0)
+    y, Sy = oracle.spmv_csr("bf16", p.m, p.n, p.rowptr, p.colidx, p.vals, p.x, y0, 0.75, 2.0)
+    assert np.array_equal(C[:, 0], y) and np.array_equal(S[:, 0], Sy)
+    Bb = bits(rand_B(p.n, 7, seed=3))
+    wide = np.zeros((p.n, 20), np.uint16)
+    wide[:, 5:12] = Bb                                                              # a column slice: ldb = 20
+    C0 = rand_B(p.m, 7, seed=4)
+    C16, S16 = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, wide[:, 5:12], C0, -1.25, 0.5)
+    C32, S32 = oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, w.bf16_bits_to_f32(p.vals), w.bf16_bits_to_f32(Bb), C0, -1.25, 0.5)
+    assert np.array_equal(C16, C32) and np.array_equal(S16, S32)
