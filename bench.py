@@ -270,21 +270,24 @@ def paper_sweep(args):
     return out
 
 
-def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
-    """The paper's SpMM CSR workload (App. C task 13: cols 2048, K 4096, density 0.01): time of
+def spmm_sweep(args, cases=((10, "f32"), (12, "f32"), (14, "f32"), (16, "f32"), (18, "f32"), (16, "bf16"))):
+    """The paper's SpMM CSR workload (App. C task 13: rows 2^10..2^18, cols 2048, K 4096, density 0.01): time of
     C <- A*B per size, GFLOP/s = 2*nnz*K / time, effective GB/s over the algorithmic bytes
-    (A's three arrays + B once + C written once)."""
+    (A's three arrays + B once + C written once).  bf16: A's values and B stored as bf16, C as float."""
     import torch
     import paper_2603_07169_amd as s
     import workloads as w
     out = []
     K = 4096
     stream = torch.cuda.current_stream()
-    for e in rows_log2:
-        p = w.density_random(1 << e, 2048, 0.01)
+    for e, dtype in cases:
+        p = w.density_random(1 << e, 2048, 0.01, dtype=dtype)
+        esz = 4 if dtype == "f32" else 2
         rowptr, colidx, vals = dev(p.rowptr), dev(p.colidx), dev(p.vals)
-        A = s.CsrMatrix(p.m, p.n, rowptr, colidx, vals, s.SPMV_F32, dict(prepare_spmm=1))
+        A = s.CsrMatrix(p.m, p.n, rowptr, colidx, vals, s.SPMV_F32 if dtype == "f32" else s.SPMV_BF16, dict(prepare_spmm=1))
         B = torch.rand(p.n, K, dtype=torch.float32, device="cuda")
+        if dtype == "bf16":
+            B = B.to(torch.bfloat16).view(torch.int16)
         C = torch.empty(p.m, K, dtype=torch.float32, device="cuda")
         steps = max(5, min(args.steps, int(2e9 // (p.m * K * 4)) or 5))
         for _ in range(2):
@@ -297,8 +300,8 @@ def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
         e1.record(stream)
         torch.cuda.synchronize()
         ms = e0.elapsed_time(e1) / steps
-        bytes_alg = 8 * p.nnz + 4 * (p.m + 1) + 4 * p.n * K + 4 * p.m * K
-        out.append({"rows": p.m, "cols": p.n, "K": K, "nnz": p.nnz, "steps": steps, "ms": ms,
+        bytes_alg = (4 + esz) * p.nnz + 4 * (p.m + 1) + esz * p.n * K + 4 * p.m * K
+        out.append({"rows": p.m, "cols": p.n, "K": K, "nnz": p.nnz, "storage": dtype, "steps": steps, "ms": ms,
                     "GFLOPs": 2.0 * p.nnz * K / ms / 1e6, "algorithmic_bytes": bytes_alg,
                     "GBps": bytes_alg / ms / 1e6, "hbm_frac": bytes_alg / ms / 1e6 / HBM_PEAK_GBPS,
                     # bound by vector FMA issue: 256 CUs x 64 lanes x 2 flops x 2.4 GHz = 78.6 TFLOP/s without
@@ -308,6 +311,7 @@ def spmm_sweep(args, rows_log2=(10, 12, 14, 16)):
             # the oracle beside it (one host thread), on the sizes it finishes in seconds
             import oracle
             Bh = B.cpu().numpy()
+            Bh = Bh.view(np.uint16) if dtype == "bf16" else Bh
             t0 = time.perf_counter()
             oracle.spmm_csr(p.m, p.n, p.rowptr, p.colidx, p.vals, Bh)
             dt = time.perf_counter() - t0
@@ -442,7 +446,7 @@ def main():
         print(json.dumps({"two_pass_sweep": two_pass_sweep(args)}))
         return
     if args.spmm:
-        print(json.dumps({"spmm_csr": spmm_sweep(args, rows_log2=(args.spmm,))}))
+        print(json.dumps({"spmm_csr": spmm_sweep(args, cases=((args.spmm, "f32"), (args.spmm, "bf16")))}))
         return
     params = dict(plan=args.plan, block_nnz=args.block_nnz, rows_max=args.rows_max,
                   items_per_chunk=args.items_per_chunk, vector_lanes=args.vector_lanes, skip_validation=0)

@@ -91,7 +91,7 @@ typedef struct {
     int32_t vector_lanes;     /* VECTOR plan: lanes per row, power of two 2..64; default: chosen from nnz/m */
     int32_t skip_validation;  /* nonzero: do not scan colidx for out-of-range columns in analyze */
     int32_t prepare_spmm;     /* 1: also build spmm_rows, the row order spmm_csr_run() then works in
-                                 (SPMV_F32 handles only); 0: spmm_csr_run() takes the rows as they come */
+                                 (and, where it pays, a packed copy of A); 0: spmm_csr_run() takes the rows as they come */
     int32_t reserved;         /* must be zero */
 } spmv_analyze_params_t;
 
@@ -254,7 +254,7 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     share cache lines.  A forced TWOPHASE plan fails with UNSUPPORTED
  *     when C2 > 65535, C2 * P2 > 2^24 or nnz + 3 * C2 * P2 > SPMV_MAX_SIZE (a bound on S); with m == 0 or nnz == 0 it runs as
  *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
- *   - with prepare_spmm = 1 (SPMV_F32 handles; UNSUPPORTED on bf16 ones): spmm_rows.  The rows
+ *   - with prepare_spmm = 1: spmm_rows.  The rows
  *     are cut into windows of SPMV_SPMM_WINDOW consecutive rows; inside a window the row ids are
  *     sorted by decreasing key(len) = min(ceil(len / 4), 64), rows of equal key in ascending
  *     order.  spmm_csr_run() advances through a row four entries at a time, so rows of equal
@@ -267,7 +267,7 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     e = 0..3), or padding past the row's end: value 0 and column 2048 when n <= 2048, else all
  *     ones.  It is built when it has at most 2 * nnz slots and 2^22 blocks (spmm_prepared = 2);
  *     otherwise only spmm_rows is (spmm_prepared = 1) and spmm_csr_run() reads CSR.  The copy
- *     holds the values as they were at analyze time.
+ *     holds the values as they were at analyze time, as binary32 (bf16 values widened).
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).
  * Synchronises the device.  Errors: INVALID_ARG, BAD_STRUCTURE, ALLOC, HIP. */
 spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* params);
@@ -282,21 +282,24 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
 
 /* Sparse times dense (paper App. C task 13: C = A B, A in CSR, B of shape cols x K), in the BLAS
  * form  C <- alpha * A * B + beta * C,  enqueued on `stream`.
- *   h    a handle created with SPMV_F32 and analyzed (the analysis validates the structure; the
- *        product itself uses rowptr / colidx / vals as they are).  A wavefront works on 16 rows
+ *   h    an analyzed handle of either storage type (the benchmark gives every task an FP32 and a BF16
+ *        variant, paper section 3.1): with SPMV_BF16 the values of A and B are bf16, products and
+ *        sums binary32, C binary32.  The analysis validates the structure; the
+ *        product itself uses rowptr / colidx / vals as they are.  A wavefront works on 16 rows
  *        at a time, for as long as the longest of them lasts: analysed with prepare_spmm = 1
  *        it takes them from spmm_rows, where rows of like length are neighbours (and from the
  *        packed copy where that was built: then vals as they were at analyze time);
  *        otherwise in their natural order.  The result is the same to rounding either way.
- *   B    device float, n rows of K used columns, row-major, leading dimension ldb >= K.
+ *   B    device, elements of the handle's storage type (float, or uint16 bf16 bit patterns), n rows
+ *        of K used columns, row-major, leading dimension ldb >= K (in elements).
  *   C    device float, m rows of K used columns, row-major, leading dimension ldc >= K; read only
  *        if beta != 0 (or when n exceeds 2048, where B is taken in several passes that accumulate
  *        into C).  B and C must not overlap.
- * 128-bit accesses are used when B and C are 16-byte aligned and ldb, ldc are multiples of 4;
- * any other layout works element by element.  m == 0 or K == 0 is a no-op.
- * Errors: INVALID_ARG (null B or C, K < 0, ldb or ldc < K), UNSUPPORTED (bf16 handle, K > SPMV_MAX_SIZE,
- * pointers not 4-byte aligned), NOT_ANALYZED, HIP. */
-spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
+ * Wide accesses are used when C is 16-byte aligned, B 16-byte (float) or 8-byte (bf16) aligned and
+ * ldb, ldc are multiples of 4; any other layout works element by element.  m == 0 or K == 0 is a no-op.
+ * Errors: INVALID_ARG (null B or C, K < 0, ldb or ldc < K), UNSUPPORTED (K > SPMV_MAX_SIZE,
+ * pointers not aligned to their element size), NOT_ANALYZED, HIP. */
+spmv_status_t spmm_csr_run(spmv_handle_t h, const void* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
                            float beta, void* stream);
 
 /* The same product y <- alpha*A*x + beta*y with A in the benchmark's other storage layouts

@@ -553,7 +553,6 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     spmv_analyze_params_t p{};
     spmv_status_t st = spmv::resolve_params(params, &p);
     if (st != SPMV_OK) return st;
-    if (p.prepare_spmm && h->dtype != SPMV_F32) return SPMV_ERR_UNSUPPORTED;
     free_metadata(h);
 
     std::vector<int32_t> rowptr_host;
@@ -737,16 +736,16 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
     return hip_failed(e) ? SPMV_ERR_HIP : SPMV_OK;
 }
 
-spmv_status_t spmm_csr_run(spmv_handle_t h, const float* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
+spmv_status_t spmm_csr_run(spmv_handle_t h, const void* B, int64_t ldb, float* C, int64_t ldc, int64_t K, float alpha,
                            float beta, void* stream) {
     if (!h) return SPMV_ERR_INVALID_ARG;
     if (!h->analyzed) return SPMV_ERR_NOT_ANALYZED;
     if (K < 0) return SPMV_ERR_INVALID_ARG;
-    if (h->dtype != SPMV_F32 || K > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    if (K > kMaxCount) return SPMV_ERR_UNSUPPORTED;
     if (h->m == 0 || K == 0) return SPMV_OK;
     if (!C || ldc < K) return SPMV_ERR_INVALID_ARG;
     if (h->n > 0 && (!B || ldb < K)) return SPMV_ERR_INVALID_ARG;
-    if (reinterpret_cast<uintptr_t>(B) % 4 || reinterpret_cast<uintptr_t>(C) % 4) return SPMV_ERR_UNSUPPORTED;
+    if (reinterpret_cast<uintptr_t>(B) % (h->dtype == SPMV_F32 ? 4 : 2) || reinterpret_cast<uintptr_t>(C) % 4) return SPMV_ERR_UNSUPPORTED;
     hipError_t e;
     if (h->info.spmm_prepared == 2) {
         const spmv::PackedRows P{h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col, h->d_spmm_val,

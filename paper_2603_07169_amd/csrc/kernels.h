@@ -68,10 +68,10 @@ hipError_t launch_window_build(const MatrixView& A, const int32_t* block_nz, int
 hipError_t launch_merge(const MatrixView& A, const int32_t* chunk_desc, int32_t P,
                         int32_t items_per_chunk, int32_t* carry_row, float* carry_val, const void* x, float* y,
                         Scalars s, hipStream_t st);
-// C <- alpha*A*B + beta*C; A FP32 CSR, B device float[n x ldb], C device float[m x ldc], row-major, K columns used.
+// C <- alpha*A*B + beta*C; A CSR, B device [n x ldb] in A's storage type, C device float[m x ldc], row-major, K columns used.
 // rows: device int32[m], the order in which the rows are handed to the wavefronts (a permutation
 // of 0..m-1), or NULL for the natural order.
-hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B, int64_t ldb, float* C, int64_t ldc,
+hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const void* B, int64_t ldb, float* C, int64_t ldc,
                        int32_t K, Scalars s, hipStream_t st);
 // The packed copy of A the sparse-times-dense product can run from (device pointers).
 constexpr int kSpmmCol16MaxN = 32768;  // up to this many columns the packed column numbers take 16 bits
@@ -86,7 +86,7 @@ struct PackedRows {
 // Fills pcol / pval of all blocks of all groups from the CSR arrays (the extra closing block is not written).
 hipError_t launch_spmm_pack(const MatrixView& A, const int32_t* rows, const int32_t* desc, int32_t num_groups, bool col16,
                             void* pcol, float* pval, hipStream_t st);
-hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const float* B, int64_t ldb, float* C, int64_t ldc,
+hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const void* B, int64_t ldb, float* C, int64_t ldc,
                               int32_t K, Scalars s, hipStream_t st);
 const char* spmm_packed_kernel_name();
 // Whole aligned groups of eight entries (groups = nnz / 8): lidx8[g] = lidx[8g]; *flag (device int32, 0 on entry) is set to 1

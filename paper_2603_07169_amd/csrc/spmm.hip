@@ -28,9 +28,9 @@ constexpr int kSpmmNB = 2048;  // rows of B held in LDS at a time (2048 x 16 flo
 struct SpmmArgs {
     const int32_t* rowptr;
     const int32_t* colidx;
-    const float* vals;
+    const void* vals;     // float or bf16 bit patterns (the kernel's storage type)
     const int32_t* rows;  // row order (SORTED kernels), else unused
-    const float* B;
+    const void* B;        // same storage type as vals
     float* C;
     int64_t ldb, ldc;
     int32_t m, n, K, nnz;
@@ -61,12 +61,45 @@ __device__ __forceinline__ void fma_quad(float& acc, float val, float b) {
 // 4-byte aligned vectors of four: a row's entries start anywhere in colidx / vals.
 typedef int32_t i32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef float f32x4_a4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x2_a2 __attribute__((ext_vector_type(2), aligned(2)));
+
+__device__ __forceinline__ f32x4 widen4(u32x2_t b) {  // four bf16 values, little-endian pairs
+    return f32x4{__uint_as_float(b[0] << 16), __uint_as_float(b[0] & 0xFFFF0000u), __uint_as_float(b[1] << 16),
+                 __uint_as_float(b[1] & 0xFFFF0000u)};
+}
+// Four consecutive stored values from element k on (any alignment the element type allows), as floats.
+__device__ __forceinline__ f32x4 load4_any(const float* p, int64_t k) { return *reinterpret_cast<const f32x4_a4*>(p + k); }
+__device__ __forceinline__ f32x4 load4_any(const uint16_t* p, int64_t k) { return widen4(*reinterpret_cast<const u32x2_a2*>(p + k)); }
+// Four consecutive values from a 16-byte (float) or 8-byte (bf16) aligned address.
+__device__ __forceinline__ f32x4 load4_aligned(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+__device__ __forceinline__ f32x4 load4_aligned(const uint16_t* p) { return widen4(*reinterpret_cast<const u32x2_t*>(p)); }
+
+// Copies rows cb0 .. cb0+nbk-1 of the slice of B (columns k0 .. k0+kw-1) to the LDS block Bs[row][16] as floats.
+template <typename E>
+__device__ __forceinline__ void stage_b_block(const E* B, int64_t ldb, int cb0, int nbk, int k0, int kw, bool vec_ok, float* Bs,
+                                              int tid) {
+    for (int idx = tid; idx < nbk * 4; idx += kSpmmWG) {
+        const int j = idx >> 2, qq = idx & 3;
+        const E* src = B + static_cast<size_t>(cb0 + j) * ldb + k0 + 4 * qq;
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (vec_ok && 4 * qq + 4 <= kw) {
+            v = load4_aligned(src);
+        } else {
+            for (int t = 0; t < 4; ++t)
+                if (4 * qq + t < kw) v[t] = widen(src[t]);
+        }
+        *reinterpret_cast<f32x4*>(Bs + j * kSpmmKT + 4 * qq) = v;
+    }
+}
 
 // SINGLE: B has at most kSpmmNB rows, so one block holds all of it and cb0 is 0 throughout.
 // SORTED: the wavefronts take their rows from a.rows (rows of like length side by side) instead
 // of in natural order.
-template <bool SINGLE, bool SORTED>
+template <typename T, bool SINGLE, bool SORTED>
 __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
+    using E = typename T::elem;
+    const E* const a_vals = static_cast<const E*>(a.vals);
     constexpr int KT = kSpmmKT, NB = kSpmmNB, RPW = 16, WAVES = kSpmmWG / 64;
     constexpr int U = 8;  // entries per lane and chunk: a chunk covers 32 entries of a row
     static_assert(KT == 16, "four lanes per row, one float4 each");
@@ -131,18 +164,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
     for (int cb0 = 0; cb0 < (SINGLE ? 1 : a.n); cb0 += NB) {
         const int nbk = a.n - cb0 < NB ? a.n - cb0 : NB;  // rows of B in this block
         if (cb0 > 0) __syncthreads();                     // the previous block is no longer read
-        for (int idx = tid; idx < nbk * 4; idx += kSpmmWG) {
-            const int j = idx >> 2, qq = idx & 3;
-            const float* src = a.B + static_cast<size_t>(cb0 + j) * a.ldb + k0 + 4 * qq;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (a.vec_ok && 4 * qq + 4 <= kw) {
-                v = *reinterpret_cast<const f32x4*>(src);
-            } else {
-                for (int t = 0; t < 4; ++t)
-                    if (4 * qq + t < kw) v[t] = src[t];
-            }
-            *reinterpret_cast<f32x4*>(Bs + j * KT + 4 * qq) = v;
-        }
+        stage_b_block(static_cast<const E*>(a.B), a.ldb, cb0, nbk, k0, kw, a.vec_ok != 0, Bs, tid);
         __syncthreads();
 
         // A chunk is 32 consecutive entries of the lane's row from entry c0 on; lane q of the quad
@@ -156,8 +178,8 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
             if (!__builtin_amdgcn_ballot_w64(kq + 20 > a.nnz)) {
                 const i32x4_a4 ca = *reinterpret_cast<const i32x4_a4*>(a.colidx + kq);
                 const i32x4_a4 cb = *reinterpret_cast<const i32x4_a4*>(a.colidx + kq + 16);
-                const f32x4_a4 va = *reinterpret_cast<const f32x4_a4*>(a.vals + kq);
-                const f32x4_a4 vb = *reinterpret_cast<const f32x4_a4*>(a.vals + kq + 16);
+                const f32x4 va = load4_any(a_vals, kq);
+                const f32x4 vb = load4_any(a_vals, kq + 16);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     col[e] = ca[e];
@@ -171,7 +193,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
                     const int t = kq + 16 * (u >> 2) + (u & 3);
                     const int k = t < a.nnz ? t : a.nnz - 1;
                     col[u] = a.colidx[k];
-                    val[u] = a.vals[k];
+                    val[u] = widen(a_vals[k]);
                 }
             }
         };
@@ -292,7 +314,7 @@ struct SpmmPackedArgs {
     const void* pcol;     // [blocks + 1][64 lanes][4]: uint16 or int32; the last block is padding only
     const float* pval;    // [blocks + 1][64][4]
     const int32_t* rows;  // [m] the row order
-    const float* B;
+    const void* B;        // float or bf16 bit patterns
     float* C;
     int64_t ldb, ldc;
     int32_t m, n, K, num_groups;
@@ -307,9 +329,9 @@ __host__ __device__ inline CT packed_pad_column(int n) {
     return n <= kSpmmNB ? static_cast<CT>(kSpmmNB) : static_cast<CT>(-1);
 }
 
-template <typename CT>
+template <typename CT, typename E>
 __global__ __launch_bounds__(64) void spmm_pack_kernel(const int32_t* __restrict__ rowptr, const int32_t* __restrict__ colidx,
-                                                       const float* __restrict__ vals, const int32_t* __restrict__ rows,
+                                                       const E* __restrict__ vals, const int32_t* __restrict__ rows,
                                                        const int32_t* __restrict__ desc, int m, int n, CT* __restrict__ pcol,
                                                        float* __restrict__ pval) {
     const int g = blockIdx.x, lane = threadIdx.x, rsub = lane >> 2, q = lane & 3;
@@ -328,7 +350,7 @@ __global__ __launch_bounds__(64) void spmm_pack_kernel(const int32_t* __restrict
             const int t = 16 * b + 4 * q + e;
             const bool live = t < len;
             pcol[slot0 + e] = live ? static_cast<CT>(colidx[rs + t]) : pad;
-            pval[slot0 + e] = live ? vals[rs + t] : 0.f;
+            pval[slot0 + e] = live ? widen(vals[rs + t]) : 0.f;
         }
     }
 }
@@ -364,8 +386,9 @@ struct PackedBlock<int32_t> {
     __device__ __forceinline__ void touch() { asm volatile("" : "+v"(c), "+v"(v)); }
 };
 
-template <bool SINGLE, typename CT>
+template <typename T, bool SINGLE, typename CT>
 __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedArgs a) {
+    using E = typename T::elem;
     constexpr int KT = kSpmmKT, NB = kSpmmNB, RPW = 16, WAVES = kSpmmWG / 64;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float* Bs = reinterpret_cast<float*>(smem_raw);  // [NB + 1][KT]; row NB stays zero
@@ -399,18 +422,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
     for (int cb0 = 0; cb0 < (SINGLE ? 1 : a.n); cb0 += NB) {
         const int nbk = a.n - cb0 < NB ? a.n - cb0 : NB;
         if (cb0 > 0) __syncthreads();
-        for (int idx = tid; idx < nbk * 4; idx += kSpmmWG) {
-            const int j = idx >> 2, qq = idx & 3;
-            const float* src = a.B + static_cast<size_t>(cb0 + j) * a.ldb + k0 + 4 * qq;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (a.vec_ok && 4 * qq + 4 <= kw) {
-                v = *reinterpret_cast<const f32x4*>(src);
-            } else {
-                for (int t = 0; t < 4; ++t)
-                    if (4 * qq + t < kw) v[t] = src[t];
-            }
-            *reinterpret_cast<f32x4*>(Bs + j * KT + 4 * qq) = v;
-        }
+        stage_b_block(static_cast<const E*>(a.B), a.ldb, cb0, nbk, k0, kw, a.vec_ok != 0, Bs, tid);
         __syncthreads();
 
         // column -> byte offset of the B row in the LDS block; padding and columns of other blocks -> zero row
@@ -511,14 +523,82 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
 
 }  // namespace
 
-hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B, int64_t ldb, float* C, int64_t ldc,
+namespace {
+
+// 128-bit (float) or 64-bit (bf16) accesses to B, 128-bit ones to C: base addresses and leading dimensions must allow them.
+bool spmm_vec_ok(bool bf16, const void* B, int64_t ldb, const float* C, int64_t ldc) {
+    return reinterpret_cast<uintptr_t>(B) % (bf16 ? 8 : 16) == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldb % 4 == 0 &&
+           ldc % 4 == 0;
+}
+
+template <typename K>
+hipError_t allow_lds(K kernel, size_t lds) {
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
+}
+
+template <typename T>
+hipError_t launch_spmm_t(const SpmmArgs& a, bool single, bool sorted, dim3 grid, size_t lds, hipStream_t st) {
+    static thread_local bool allowed = false;
+    if (!allowed) {
+        hipError_t e = allow_lds(spmm_csr_kernel<T, true, true>, lds);
+        if (e == hipSuccess) e = allow_lds(spmm_csr_kernel<T, true, false>, lds);
+        if (e == hipSuccess) e = allow_lds(spmm_csr_kernel<T, false, true>, lds);
+        if (e == hipSuccess) e = allow_lds(spmm_csr_kernel<T, false, false>, lds);
+        if (e != hipSuccess) return e;
+        allowed = true;
+    }
+    const dim3 block(kSpmmWG);
+    if (sorted) {
+        if (single) hipLaunchKernelGGL((spmm_csr_kernel<T, true, true>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((spmm_csr_kernel<T, false, true>), grid, block, lds, st, a);
+    } else {
+        if (single) hipLaunchKernelGGL((spmm_csr_kernel<T, true, false>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((spmm_csr_kernel<T, false, false>), grid, block, lds, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t launch_spmm_packed_t(const SpmmPackedArgs& a, bool col16, bool single, dim3 grid, size_t lds, hipStream_t st) {
+    static thread_local bool allowed = false;
+    if (!allowed) {
+        hipError_t e = allow_lds(spmm_packed_kernel<T, true, uint16_t>, lds);
+        if (e == hipSuccess) e = allow_lds(spmm_packed_kernel<T, false, uint16_t>, lds);
+        if (e == hipSuccess) e = allow_lds(spmm_packed_kernel<T, false, int32_t>, lds);
+        if (e != hipSuccess) return e;
+        allowed = true;
+    }
+    const dim3 block(kSpmmWG);
+    if (col16) {
+        if (single) hipLaunchKernelGGL((spmm_packed_kernel<T, true, uint16_t>), grid, block, lds, st, a);
+        else hipLaunchKernelGGL((spmm_packed_kernel<T, false, uint16_t>), grid, block, lds, st, a);
+    } else {
+        hipLaunchKernelGGL((spmm_packed_kernel<T, false, int32_t>), grid, block, lds, st, a);
+    }
+    return hipGetLastError();
+}
+
+template <typename CT>
+hipError_t launch_spmm_pack_t(const MatrixView& A, const int32_t* rows, const int32_t* desc, int32_t num_groups, CT* pcol, float* pval,
+                              hipStream_t st) {
+    if (A.bf16)
+        hipLaunchKernelGGL((spmm_pack_kernel<CT, uint16_t>), dim3(num_groups), dim3(64), 0, st, A.rowptr, A.colidx,
+                           static_cast<const uint16_t*>(A.vals), rows, desc, A.m, A.n, pcol, pval);
+    else
+        hipLaunchKernelGGL((spmm_pack_kernel<CT, float>), dim3(num_groups), dim3(64), 0, st, A.rowptr, A.colidx,
+                           static_cast<const float*>(A.vals), rows, desc, A.m, A.n, pcol, pval);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const void* B, int64_t ldb, float* C, int64_t ldc,
                        int32_t K, Scalars s, hipStream_t st) {
     if (A.m <= 0 || K <= 0) return hipSuccess;
-    if (A.bf16) return hipErrorInvalidValue;
     SpmmArgs a{};
     a.rowptr = A.rowptr;
     a.colidx = A.colidx;
-    a.vals = static_cast<const float*>(A.vals);
+    a.vals = A.vals;
     a.rows = rows;
     a.B = B;
     a.C = C;
@@ -530,10 +610,7 @@ hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B,
     a.nnz = A.nnz;
     a.alpha = s.alpha;
     a.beta = s.beta;
-    a.vec_ok = (reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldb % 4 == 0 &&
-                ldc % 4 == 0)
-                   ? 1
-                   : 0;
+    a.vec_ok = spmm_vec_ok(A.bf16, B, ldb, C, ldc) ? 1 : 0;
     const int slices = ceil_div(K, kSpmmKT);
     // one workgroup fits a CU (its B slice takes most of the LDS): aim at one per CU or more
     int splits = slices >= 256 ? 1 : ceil_div(256, slices);
@@ -541,43 +618,20 @@ hipError_t launch_spmm(const MatrixView& A, const int32_t* rows, const float* B,
     if (splits > max_splits) splits = max_splits;
     a.row_splits = splits;
     const size_t lds = sizeof(float) * (kSpmmNB + 1) * kSpmmKT;  // the B block and one zero row
-    static thread_local bool allowed = false;
-    if (!allowed) {
-        for (const void* k : {reinterpret_cast<const void*>(spmm_csr_kernel<true, true>),
-                              reinterpret_cast<const void*>(spmm_csr_kernel<true, false>),
-                              reinterpret_cast<const void*>(spmm_csr_kernel<false, true>),
-                              reinterpret_cast<const void*>(spmm_csr_kernel<false, false>)}) {
-            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-            if (e != hipSuccess) return e;
-        }
-        allowed = true;
-    }
-    const dim3 grid(slices * splits), block(kSpmmWG);
+    const dim3 grid(slices * splits);
     const bool single = A.n <= kSpmmNB;
-    if (rows) {
-        if (single) hipLaunchKernelGGL((spmm_csr_kernel<true, true>), grid, block, lds, st, a);
-        else hipLaunchKernelGGL((spmm_csr_kernel<false, true>), grid, block, lds, st, a);
-    } else {
-        if (single) hipLaunchKernelGGL((spmm_csr_kernel<true, false>), grid, block, lds, st, a);
-        else hipLaunchKernelGGL((spmm_csr_kernel<false, false>), grid, block, lds, st, a);
-    }
-    return hipGetLastError();
+    return A.bf16 ? launch_spmm_t<BF16>(a, single, rows != nullptr, grid, lds, st)
+                  : launch_spmm_t<F32>(a, single, rows != nullptr, grid, lds, st);
 }
 
 hipError_t launch_spmm_pack(const MatrixView& A, const int32_t* rows, const int32_t* desc, int32_t num_groups, bool col16,
                             void* pcol, float* pval, hipStream_t st) {
     if (num_groups <= 0) return hipSuccess;
-    if (A.bf16) return hipErrorInvalidValue;
-    if (col16)
-        hipLaunchKernelGGL((spmm_pack_kernel<uint16_t>), dim3(num_groups), dim3(64), 0, st, A.rowptr, A.colidx,
-                           static_cast<const float*>(A.vals), rows, desc, A.m, A.n, static_cast<uint16_t*>(pcol), pval);
-    else
-        hipLaunchKernelGGL((spmm_pack_kernel<int32_t>), dim3(num_groups), dim3(64), 0, st, A.rowptr, A.colidx,
-                           static_cast<const float*>(A.vals), rows, desc, A.m, A.n, static_cast<int32_t*>(pcol), pval);
-    return hipGetLastError();
+    return col16 ? launch_spmm_pack_t(A, rows, desc, num_groups, static_cast<uint16_t*>(pcol), pval, st)
+                 : launch_spmm_pack_t(A, rows, desc, num_groups, static_cast<int32_t*>(pcol), pval, st);
 }
 
-hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const float* B, int64_t ldb, float* C, int64_t ldc,
+hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const void* B, int64_t ldb, float* C, int64_t ldc,
                               int32_t K, Scalars s, hipStream_t st) {
     if (A.m <= 0 || K <= 0) return hipSuccess;
     SpmmPackedArgs a{};
@@ -595,33 +649,15 @@ hipError_t launch_spmm_packed(const MatrixView& A, const PackedRows& P, const fl
     a.num_groups = P.num_groups;
     a.alpha = s.alpha;
     a.beta = s.beta;
-    a.vec_ok = (reinterpret_cast<uintptr_t>(B) % 16 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && ldb % 4 == 0 &&
-                ldc % 4 == 0)
-                   ? 1
-                   : 0;
+    a.vec_ok = spmm_vec_ok(A.bf16, B, ldb, C, ldc) ? 1 : 0;
     const int slices = ceil_div(K, kSpmmKT);
     int splits = slices >= 256 ? 1 : ceil_div(256, slices);
     if (splits > P.num_groups) splits = P.num_groups;
     a.row_splits = splits;
     const size_t lds = sizeof(float) * (kSpmmNB + 1) * kSpmmKT;
-    static thread_local bool allowed = false;
-    if (!allowed) {
-        for (const void* k : {reinterpret_cast<const void*>(spmm_packed_kernel<true, uint16_t>),
-                              reinterpret_cast<const void*>(spmm_packed_kernel<false, uint16_t>),
-                              reinterpret_cast<const void*>(spmm_packed_kernel<false, int32_t>)}) {
-            hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(lds));
-            if (e != hipSuccess) return e;
-        }
-        allowed = true;
-    }
-    const dim3 grid(slices * splits), block(kSpmmWG);
-    if (P.col16) {
-        if (A.n <= kSpmmNB) hipLaunchKernelGGL((spmm_packed_kernel<true, uint16_t>), grid, block, lds, st, a);
-        else hipLaunchKernelGGL((spmm_packed_kernel<false, uint16_t>), grid, block, lds, st, a);
-    } else {
-        hipLaunchKernelGGL((spmm_packed_kernel<false, int32_t>), grid, block, lds, st, a);
-    }
-    return hipGetLastError();
+    const dim3 grid(slices * splits);
+    return A.bf16 ? launch_spmm_packed_t<BF16>(a, P.col16, A.n <= kSpmmNB, grid, lds, st)
+                  : launch_spmm_packed_t<F32>(a, P.col16, A.n <= kSpmmNB, grid, lds, st);
 }
 
 const char* spmm_kernel_name() { return "spmm_csr_kernel"; }
