@@ -134,24 +134,26 @@ __global__ __launch_bounds__(kWG) void spmv_csc_kernel(const int32_t* __restrict
 // The same for matrices with few rows, where the atomics of thousands of columns would queue up
 // on the same few addresses of y: a workgroup adds its columns into a private copy of y in LDS
 // and sends every row's total to memory once.  Few workgroups, so few atomics per address.
+constexpr int kCscLdsWG = 512;      // lanes of a workgroup of spmv_csc_lds_kernel
+constexpr int kCscLdsBlocks = 128;  // most workgroups it is launched with
 template <typename T, int G>
-__global__ __launch_bounds__(kWG) void spmv_csc_lds_kernel(const int32_t* __restrict__ col_offsets,
+__global__ __launch_bounds__(kCscLdsWG) void spmv_csc_lds_kernel(const int32_t* __restrict__ col_offsets,
                                                            const int32_t* __restrict__ row,
                                                            const typename T::elem* __restrict__ vals,
                                                            const typename T::elem* __restrict__ x, float* y, int m, int n,
                                                            float alpha) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float* ly = reinterpret_cast<float*>(smem_raw);  // [m]
-    for (int i = threadIdx.x; i < m; i += kWG) ly[i] = 0.f;
+    for (int i = threadIdx.x; i < m; i += kCscLdsWG) ly[i] = 0.f;
     __syncthreads();
     const int tl = threadIdx.x % G;
-    for (int j = (blockIdx.x * kWG + threadIdx.x) / G; j < n; j += gridDim.x * (kWG / G)) {
+    for (int j = (blockIdx.x * kCscLdsWG + threadIdx.x) / G; j < n; j += gridDim.x * (kCscLdsWG / G)) {
         const float xj = alpha * widen(x[j]);
         const int e1 = col_offsets[j + 1];
         for (int e = col_offsets[j] + tl; e < e1; e += G) atomicAdd(ly + row[e], widen(vals[e]) * xj);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < m; i += kWG) {
+    for (int i = threadIdx.x; i < m; i += kCscLdsWG) {
         const float v = ly[i];
         if (v != 0.f) unsafeAtomicAdd(y + i, v);
     }
@@ -294,9 +296,12 @@ hipError_t launch_csc_tg(int32_t m, int32_t n, const int32_t* col_offsets, const
     if (n <= 0) return hipGetLastError();
     const int blocks = ceil_div(static_cast<int64_t>(n) * G, kWG);
     if (m <= kCscLdsRows) {
-        // a private y per workgroup: 64 workgroups keep the chip busy enough for these small problems
-        // and leave at most 64 atomics per row
-        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(blocks > 64 ? 64 : blocks), dim3(kWG), sizeof(float) * m, st,
+        // A private y per workgroup.  The LDS float atomics of a compute unit retire about one lane every three cycles
+        // whatever the workgroup's size, so the time to add the entries falls with the number of workgroups, while each
+        // workgroup sends m global atomics at the end: measured 57 / 31 / 18 / 13 / 15 us with 16 / 32 / 64 / 128 / 256
+        // workgroups on the benchmark's 2048 x 32768 shape (256, 512 or 1024 lanes each: the same).
+        const int lds_blocks = ceil_div(static_cast<int64_t>(n) * G, kCscLdsWG);
+        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(lds_blocks > kCscLdsBlocks ? kCscLdsBlocks : lds_blocks), dim3(kCscLdsWG), sizeof(float) * m, st,
                            col_offsets, row, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, n, s.alpha);
     } else {
         hipLaunchKernelGGL((spmv_csc_kernel<T, G>), dim3(blocks), dim3(kWG), 0, st, col_offsets, row,
