@@ -180,7 +180,8 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  * (rowptr[0] == 0, non-decreasing, rowptr[m] == nnz), optionally checks 0 <= colidx < n on the
  * device, then derives and uploads:
  *   - row statistics; bin(len) = 0 for len 0, else the smallest b >= 1 with 2^(b-1) >= len;
- *     bin_rows = stable grouping of row ids by bin;
+ *     bin_rows = stable grouping of row ids by bin (kept on the device for the BINNED plan, whose kernels read it;
+ *     under any other plan it is built when spmv_csr_get_analysis() is asked for it, from rowptr as it then is);
  *   - row blocks: greedy left-to-right, a block takes the next row while it has < rows_max
  *     rows and the row keeps it at <= block_nnz entries; a longer row stands alone.
  *     Defaults (a field left 0): with mean = ceil(nnz/m) and G the largest power of two <= 64
@@ -358,7 +359,10 @@ spmv_status_t spmv_destroy(spmv_handle_t h);
 /* Sizes and scalars of the analysis, so the caller can size read-back buffers. */
 spmv_status_t spmv_csr_get_analysis_info(spmv_handle_t h, spmv_analysis_info_t* out);
 
-/* Copies the integer analysis outputs from the device to the host buffers in `out`. */
+/* Copies the integer analysis outputs to the host buffers in `out`: from the device what the kernels read (x windows, row
+ * patterns, column blocks, the two-pass layout, the sparse-times-dense order and packed copy), from the handle's own host
+ * memory what was derived from rowptr on the host and is read by the kernels only through the interleaved descriptors
+ * (bin_rows unless the plan is BINNED, row_blocks, mp_row, mp_nz). */
 spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t* out);
 
 /* The analysis of spmv_csr_analyze() on a HOST copy of rowptr, with HOST outputs and no device

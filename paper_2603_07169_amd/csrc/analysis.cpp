@@ -112,17 +112,45 @@ void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ip
     int32_t* mp_row = rows->data();
     int32_t* mp_nz = entries->data();
     parallel_pieces(P + 1, host_threads((P + 1) * 16), [=](int, int64_t lo, int64_t hi) {
+        // The split on diagonal d + ipc lies at most ipc rows past the one on diagonal d (every row passed costs a step),
+        // so after a piece's first split each bisection runs over a window of ipc rows: a few steps in memory just touched.
+        int64_t prev = -1;
         for (int64_t p = lo; p < hi; ++p) {
             const int64_t d = std::min(p * ipc, T);
-            const int64_t i = split_rows_on_diagonal(d, m, nnz, rowptr);
+            int64_t i;
+            if (prev < 0) {
+                i = split_rows_on_diagonal(d, m, nnz, rowptr);
+            } else {
+                int64_t a = std::max<int64_t>(prev, d - nnz), b = std::min<int64_t>({d, m, prev + ipc});
+                while (a < b) {
+                    const int64_t mid = a + (b - a) / 2;
+                    if (static_cast<int64_t>(rowptr[mid + 1]) + mid > d - 1)
+                        b = mid;
+                    else
+                        a = mid + 1;
+                }
+                i = a;
+            }
+            prev = i;
             mp_row[p] = static_cast<int32_t>(i);
             mp_nz[p] = static_cast<int32_t>(d - i);
         }
     });
 }
 
+void bin_rows_of(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows) {
+    // a stable counting sort, in one thread: the lengths are counted per bin, then every row goes behind the rows
+    // before it in its bin
+    int64_t cursor[SPMV_NUM_BINS + 1] = {};
+    for (int64_t i = 0; i < m; ++i) cursor[length_bin(static_cast<uint32_t>(rowptr[i + 1] - rowptr[i])) + 1] += 1;
+    for (int b = 0; b < SPMV_NUM_BINS; ++b) cursor[b + 1] += cursor[b];
+    rows->resize(static_cast<size_t>(m));
+    for (int64_t i = 0; i < m; ++i)
+        (*rows)[static_cast<size_t>(cursor[length_bin(static_cast<uint32_t>(rowptr[i + 1] - rowptr[i]))]++)] = static_cast<int32_t>(i);
+}
+
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
-                             const spmv_analyze_params_t& params_in, Analysis* out) try {
+                             const spmv_analyze_params_t& params_in, Analysis* out, bool want_bin_rows) try {
     Analysis& a = *out;
     a = Analysis{};
     spmv_analyze_params_t params = params_in;
@@ -165,10 +193,12 @@ spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* r
         for (int b = 0; b < SPMV_NUM_BINS; ++b) a.bin_count[b] += q.hist[b];
     }
 
-    // ---- stable counting sort of the row ids by bin: thread t writes behind the rows of the threads before it
+    // ---- stable counting sort of the row ids by bin: thread t writes behind the rows of the threads before it.
+    // Only the BINNED plan's kernels read the list, so it is built when that plan is asked for (want_bin_rows); for any
+    // other plan bin_rows_of() builds it when the caller reads the analysis back.
     for (int b = 0; b < SPMV_NUM_BINS; ++b) a.bin_offset[b + 1] = a.bin_offset[b] + a.bin_count[b];
-    a.bin_rows.resize(static_cast<size_t>(m));
-    {
+    if (want_bin_rows) {
+        a.bin_rows.resize(static_cast<size_t>(m));
         std::vector<int32_t> first(static_cast<size_t>(threads) * SPMV_NUM_BINS);
         for (int b = 0; b < SPMV_NUM_BINS; ++b) {
             int32_t at = a.bin_offset[b];

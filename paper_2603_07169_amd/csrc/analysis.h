@@ -37,8 +37,12 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
 void default_tile_shape(int64_t m, int64_t nnz, int32_t* block_nnz, int32_t* rows_max);
 
 // rowptr is a HOST array of m+1 entries.  Returns SPMV_OK, SPMV_ERR_BAD_STRUCTURE or SPMV_ERR_ALLOC.
+// want_bin_rows: also build out->bin_rows (the one output only the BINNED plan's kernels read: 4 bytes a row that
+// every other plan can do without until somebody reads the analysis back; bin_count / bin_offset are always filled).
 spmv_status_t analyze_rowptr(int64_t m, int64_t n, int64_t nnz, const int32_t* rowptr,
-                             const spmv_analyze_params_t& params, Analysis* out);
+                             const spmv_analyze_params_t& params, Analysis* out, bool want_bin_rows);
+// The same list on its own (rowptr: HOST array of m+1 checked entries).  May throw std::bad_alloc.
+void bin_rows_of(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows);
 
 // Columns per block of the column-blocked plan (4 MiB of x), and whether the automatic plan
 // takes it: only in place of ADAPTIVE / MERGE, with x beyond two blocks, at most 16 blocks and

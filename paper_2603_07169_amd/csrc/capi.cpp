@@ -42,8 +42,9 @@ struct spmv_csr_s {
     int32_t bin_count[SPMV_NUM_BINS]{};
     int32_t bin_offset[SPMV_NUM_BINS + 1]{};
     // device metadata, owned
-    int32_t* d_bin_rows = nullptr;
-    int32_t* d_row_blocks = nullptr;
+    int32_t* d_bin_rows = nullptr;  // uploaded for the BINNED plan only (the one plan whose kernels read it)
+    // analysis outputs that no kernel reads in this form stay on the host, for the read-back
+    std::vector<int32_t> bin_rows, row_blocks, mp_row, mp_nz;
     int32_t* d_block_nz = nullptr;  // rowptr[row_blocks[b]]: spares the kernels a dependent load
     int32_t* d_block_desc = nullptr;  // pairs (row_blocks[b], block_nz[b]): one scalar load per workgroup
     int32_t* d_chunk_desc = nullptr;  // pairs (mp_row[p], mp_nz[p])
@@ -53,8 +54,6 @@ struct spmv_csr_s {
     void* d_cb_vals = nullptr;
     std::vector<int32_t> cb_ptr;   // host: [C+1]
     int32_t max_block_entries = 0;  // most entries of any row block that is not a single over-long row
-    int32_t* d_mp_row = nullptr;
-    int32_t* d_mp_nz = nullptr;
     int32_t* d_carry_row = nullptr;
     float* d_carry_val = nullptr;
     int32_t* d_xv_ptr = nullptr;  // x windows (WINDOWED plan)
@@ -93,7 +92,7 @@ struct spmv_csr_s {
 namespace {
 
 void free_metadata(spmv_csr_s* h) {
-    void* ptrs[] = {h->d_bin_rows, h->d_row_blocks, h->d_block_nz, h->d_mp_row,   h->d_mp_nz,
+    void* ptrs[] = {h->d_bin_rows, h->d_block_nz,
                     h->d_carry_row, h->d_carry_val, h->d_xv_ptr,   h->d_xv_start, h->d_lidx,
                     h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc, h->d_cb_row, h->d_cb_col,
                     h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
@@ -109,7 +108,11 @@ void free_metadata(spmv_csr_s* h) {
     h->d_tp_prod = h->d_tp_carry_val = nullptr;
     h->tp_row.clear();
     h->tp_nz.clear();
-    h->d_bin_rows = h->d_row_blocks = h->d_block_nz = h->d_mp_row = h->d_mp_nz = h->d_carry_row = nullptr;
+    h->d_bin_rows = h->d_block_nz = h->d_carry_row = nullptr;
+    h->bin_rows.clear();
+    h->row_blocks.clear();
+    h->mp_row.clear();
+    h->mp_nz.clear();
     h->d_carry_val = nullptr;
     h->d_xv_ptr = h->d_xv_start = h->d_xv_pad = h->d_block_desc = h->d_chunk_desc = nullptr;
     h->d_cb_row = h->d_cb_col = h->d_cb_src = nullptr;
@@ -565,7 +568,7 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         return SPMV_ERR_HIP;
 
     spmv::Analysis a;
-    st = spmv::analyze_rowptr(h->m, h->n, h->nnz, rowptr_host.data(), p, &a);
+    st = spmv::analyze_rowptr(h->m, h->n, h->nnz, rowptr_host.data(), p, &a, p.plan == SPMV_PLAN_BINNED);
     if (st != SPMV_OK) return st;
 
     if (!p.skip_validation && h->nnz > 0) {
@@ -580,8 +583,7 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         if (flag != 0) return SPMV_ERR_BAD_STRUCTURE;
     }
 
-    st = upload(a.bin_rows, &h->d_bin_rows);
-    if (st == SPMV_OK) st = upload(a.row_blocks, &h->d_row_blocks);
+    if (p.plan == SPMV_PLAN_BINNED) st = upload(a.bin_rows, &h->d_bin_rows);
     if (st == SPMV_OK) {
         try {
             std::vector<int32_t> block_nz(a.row_blocks.size());
@@ -628,8 +630,6 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
                                                                                      a.x_vectors_counted, a.entries_counted);
         if (p.plan == SPMV_PLAN_COLBLOCK || automatic) st = build_column_blocks(h, &a);
     }
-    if (st == SPMV_OK) st = upload(a.mp_row, &h->d_mp_row);
-    if (st == SPMV_OK) st = upload(a.mp_nz, &h->d_mp_nz);
     if (st == SPMV_OK && p.prepare_spmm) st = build_spmm_order(h, rowptr_host, &a);
     if (st == SPMV_OK) {
         const size_t P = static_cast<size_t>(a.info.num_chunks > 0 ? a.info.num_chunks : 1);
@@ -646,6 +646,10 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         return st;
     }
     h->info = a.info;
+    h->bin_rows = std::move(a.bin_rows);
+    h->row_blocks = std::move(a.row_blocks);
+    h->mp_row = std::move(a.mp_row);
+    h->mp_nz = std::move(a.mp_nz);
     std::memcpy(h->bin_count, a.bin_count, sizeof h->bin_count);
     std::memcpy(h->bin_offset, a.bin_offset, sizeof h->bin_offset);
     h->analyzed = true;
@@ -856,16 +860,25 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
         int32_t* dst;
         const int32_t* src;
         int64_t count;
-    } copies[] = {
-        {out->bin_rows, h->d_bin_rows, h->info.m},
-        {out->row_blocks, h->d_row_blocks, h->info.num_row_blocks + 1},
-        {out->mp_row, h->d_mp_row, h->info.num_chunks + 1},
-        {out->mp_nz, h->d_mp_nz, h->info.num_chunks + 1},
     };
-    for (const Copy& c : copies)
-        if (c.dst && c.count > 0 &&
-            hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
-            return SPMV_ERR_HIP;
+    // derived on the host from rowptr and kept there (kernels read the interleaved descriptors instead)
+    const struct {
+        int32_t* dst;
+        const std::vector<int32_t>* src;
+    } host_copies[] = {{out->bin_rows, &h->bin_rows}, {out->row_blocks, &h->row_blocks}, {out->mp_row, &h->mp_row}, {out->mp_nz, &h->mp_nz}};
+    if (out->bin_rows && h->bin_rows.empty() && h->m > 0) {
+        // not built at analyze time (no kernel of this plan reads it): built now, from the caller's rowptr
+        try {
+            std::vector<int32_t> rowptr_host(static_cast<size_t>(h->m) + 1);
+            if (hip_failed(hipMemcpy(rowptr_host.data(), h->rowptr, sizeof(int32_t) * rowptr_host.size(), hipMemcpyDeviceToHost)))
+                return SPMV_ERR_HIP;
+            spmv::bin_rows_of(h->m, rowptr_host.data(), &h->bin_rows);
+        } catch (const std::bad_alloc&) {
+            return SPMV_ERR_ALLOC;
+        }
+    }
+    for (const auto& c : host_copies)
+        if (c.dst && !c.src->empty()) std::memcpy(c.dst, c.src->data(), sizeof(int32_t) * c.src->size());
     if (h->info.spmm_prepared && out->spmm_rows && h->info.m > 0 &&
         hip_failed(hipMemcpy(out->spmm_rows, h->d_spmm_rows, sizeof(int32_t) * static_cast<size_t>(h->info.m), hipMemcpyDeviceToHost)))
         return SPMV_ERR_HIP;
@@ -942,7 +955,7 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     if (p.plan == SPMV_PLAN_WINDOWED || p.plan == SPMV_PLAN_COLBLOCK || p.plan == SPMV_PLAN_TWOPHASE)
         return SPMV_ERR_INVALID_ARG;  // they need colidx: device only
     spmv::Analysis a;
-    st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a);
+    st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a, out && out->bin_rows);
     if (st != SPMV_OK) return st;
     std::vector<int32_t> order, desc;
     if (p.prepare_spmm) {

@@ -751,8 +751,9 @@ __global__ __launch_bounds__(WG, (XPL == 4 && NG == 2) ? 4 : 8) void spmv_patter
 }
 
 // Builds the x windows of row blocks (one workgroup of 256 lanes per block; analysis time).
-// keys = colidx >> shift of the block's entries (those that repeat their predecessor's are left out
-// at once), sorted in LDS (bitonic network over the next power of two), duplicates dropped.  count pass (fill == 0): nv[b] = number of distinct keys.
+// keys = colidx >> shift of the block's entries.  Where they span few enough values, a bitmap in LDS gives the
+// distinct keys and every key's rank without sorting; otherwise the keys (those that repeat their predecessor's are left out
+// at once) are sorted in LDS (bitonic network over the next power of two) and duplicates dropped.  count pass (fill == 0): nv[b] = number of distinct keys.
 // fill pass: xv_start[xv_ptr[b] + j] = xv_pad[b * x_cap + j] = j-th key << shift (the rest of the
 // block's xv_pad slice is -1), and for every entry
 // lidx[k] = rank of its key * 2^shift + colidx[k] mod 2^shift.  A block with more than tile_cap
@@ -764,10 +765,12 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
                                                            const int32_t* __restrict__ xv_ptr,
                                                            int32_t* __restrict__ xv_start, int32_t* __restrict__ xv_pad,
                                                            int x_cap, uint16_t* __restrict__ lidx) {
-    __shared__ uint32_t keys[kMaxTileEntries];
+    __shared__ uint32_t keys[kMaxTileEntries];  // the keys to sort, or one bit per possible key
     __shared__ uint32_t uniq[kMaxXVectors];
     __shared__ int counts[256];
     __shared__ int chunk_base[kMaxTileEntries / 64 + 1];
+    __shared__ uint16_t word_rank[kMaxTileEntries];  // bitmap path: distinct keys below each word
+    __shared__ uint32_t key_lo, key_hi;
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int k0 = block_nz[b], k1 = block_nz[b + 1];
@@ -777,6 +780,100 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
         if (fill) {
             for (int i = tid; i < cnt; i += 256) lidx[k0 + i] = 0;
             for (int i = tid; i < x_cap; i += 256) xv_pad[b * x_cap + i] = -1;
+        }
+        return;
+    }
+    // Keys that span at most 32 * kMaxTileEntries values (a stencil's neighbouring grid lines, a band, a matrix of
+    // moderate width) need no sort: one bit per possible key in LDS, ranks from the population counts below a bit.
+    {
+        uint32_t lo = 0xFFFFFFFFu, hi = 0;
+        for (int i = tid; i < cnt; i += 256) {
+            const uint32_t key = static_cast<uint32_t>(colidx[k0 + i]) >> shift;
+            lo = key < lo ? key : lo;
+            hi = key > hi ? key : hi;
+        }
+        if (tid == 0) {
+            key_lo = 0xFFFFFFFFu;
+            key_hi = 0;
+        }
+        __syncthreads();
+        atomicMin(&key_lo, lo);
+        atomicMax(&key_hi, hi);
+        __syncthreads();
+    }
+    const uint32_t kmin = key_lo;
+    const uint32_t range = key_hi - kmin + 1;
+    constexpr uint32_t kBitmapKeys = 32u * kMaxTileEntries;
+    if (!fill && range > kBitmapKeys && range <= 16u * kBitmapKeys) {
+        // counting alone over a wider span of keys: the bitmap slides over it, a window of keys at a time
+        int mine = 0;
+        for (uint32_t first = kmin; first - kmin < range; first += kBitmapKeys) {
+            for (int w = tid; w < kMaxTileEntries; w += 256) keys[w] = 0;
+            __syncthreads();
+            for (int i = tid; i < cnt; i += 256) {
+                const uint32_t rel = (static_cast<uint32_t>(colidx[k0 + i]) >> shift) - first;  // a key below the window wraps to a huge number
+                if (rel < kBitmapKeys) atomicOr(&keys[rel >> 5], 1u << (rel & 31));
+            }
+            __syncthreads();
+            for (int w = tid; w < kMaxTileEntries; w += 256) mine += __popc(keys[w]);
+            __syncthreads();
+        }
+        counts[tid] = mine;
+        __syncthreads();
+        if (tid == 0) {
+            int total = 0;
+            for (int t = 0; t < 256; ++t) total += counts[t];
+            nv[b] = total;
+        }
+        return;
+    }
+    if (range <= kBitmapKeys) {
+        const int nwords = static_cast<int>((range + 31) >> 5);
+        for (int w = tid; w < nwords; w += 256) keys[w] = 0;
+        __syncthreads();
+        for (int i = tid; i < cnt; i += 256) {
+            const uint32_t rel = (static_cast<uint32_t>(colidx[k0 + i]) >> shift) - kmin;
+            atomicOr(&keys[rel >> 5], 1u << (rel & 31));
+        }
+        __syncthreads();
+        const int per = (nwords + 255) / 256;  // each lane owns `per` consecutive words
+        const int w0 = tid * per < nwords ? tid * per : nwords, w1 = w0 + per < nwords ? w0 + per : nwords;
+        int mine = 0;
+        for (int w = w0; w < w1; ++w) mine += __popc(keys[w]);
+        counts[tid] = mine;
+        __syncthreads();
+        int pre = 0, total = 0;
+        for (int t = 0; t < 256; ++t) {
+            const int c = counts[t];
+            pre += t < tid ? c : 0;
+            total += c;
+        }
+        if (!fill) {
+            if (tid == 0) nv[b] = total;
+            return;
+        }
+        if (total > kMaxXVectors) return;  // not reached: the host launches the fill pass only when all fit
+        const int v0 = xv_ptr[b];
+        for (int w = w0; w < w1; ++w) {
+            word_rank[w] = static_cast<uint16_t>(pre);
+            uint32_t bits = keys[w];
+            while (bits) {
+                const int bit = __ffs(bits) - 1;
+                bits &= bits - 1;
+                const int32_t first = static_cast<int32_t>((kmin + 32u * w + bit) << shift);
+                xv_start[v0 + pre] = first;
+                xv_pad[b * x_cap + pre] = first;
+                ++pre;
+            }
+        }
+        for (int i = total + tid; i < x_cap; i += 256) xv_pad[b * x_cap + i] = -1;
+        __syncthreads();
+        const uint32_t low = (1u << shift) - 1u;
+        for (int i = tid; i < cnt; i += 256) {
+            const uint32_t c = static_cast<uint32_t>(colidx[k0 + i]);
+            const uint32_t rel = (c >> shift) - kmin;
+            const uint32_t rank = word_rank[rel >> 5] + __popc(keys[rel >> 5] & ((1u << (rel & 31)) - 1u));
+            lidx[k0 + i] = static_cast<uint16_t>((rank << shift) + (c & low));
         }
         return;
     }
@@ -888,12 +985,29 @@ __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __res
     __shared__ int base_s[kMaxRowsPerBlock];
     __shared__ unsigned char len_s[kMaxRowsPerBlock], same_s[kMaxRowsPerBlock];
     __shared__ int bad;
-    __shared__ int run_first[kMaxPatternRuns + 1], run_stride[kMaxPatternRuns], n_runs;
+    __shared__ int run_first[kMaxPatternRuns + 1], run_stride[kMaxPatternRuns];
     const int tid = threadIdx.x, b = blockIdx.x;
     const int r0 = block_desc[2 * b], k0 = block_desc[2 * b + 1], r1 = block_desc[2 * b + 2], k1 = block_desc[2 * b + 3];
     const int nr = r1 - r0;
     if (tid == 0) bad = (k1 - k0 > tile_cap || nr > kMaxRowsPerBlock) ? 1 : 0;
     __syncthreads();
+    if (fill) {  // the runs were found and packed by the first pass: the lists are written from them
+        const int32_t* d = run_desc + 8 * static_cast<int64_t>(b);
+        uint16_t* out = pat_pad + static_cast<int64_t>(b) * pt_cap;
+        const int runs = d[7];
+        int row = 0, at = 0;
+        for (int r = 0; r < runs; ++r) {
+            const int rows = (static_cast<uint32_t>(d[r >> 1]) >> (16 * (r & 1))) & 0xFFFF;
+            const int len = (static_cast<uint32_t>(d[2]) >> (8 * r)) & 0xFF;
+            const int base = (static_cast<uint32_t>(d[3 + (r >> 1)]) >> (16 * (r & 1))) & 0xFFFF;
+            const int ka = rowptr[r0 + row];
+            for (int j = tid; j < len; j += 256) out[at + j] = static_cast<uint16_t>(lidx[ka + j] - base);
+            row += rows;
+            at += len;
+        }
+        for (int j = at + tid; j < pt_cap; j += 256) out[j] = 0;
+        return;
+    }
     if (!bad) {
         for (int i = tid; i < nr; i += 256) {
             const int ka = rowptr[r0 + i], len = rowptr[r0 + i + 1] - ka;
@@ -946,8 +1060,7 @@ __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __res
             }
             run_first[runs] = nr;
         }
-        n_runs = runs;
-        if (!fill) {
+        {
             int rows[4] = {0, 0, 0, 0}, len[4] = {0, 0, 0, 0}, base[4] = {0, 0, 0, 0}, stride[4] = {0, 0, 0, 0}, table = 0;
             for (int r = 0; r < runs; ++r) {
                 rows[r] = run_first[r + 1] - run_first[r];
@@ -971,17 +1084,6 @@ __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __res
             }
         }
     }
-    __syncthreads();
-    if (!fill) return;
-    uint16_t* out = pat_pad + static_cast<int64_t>(b) * pt_cap;
-    int at = 0;
-    for (int r = 0; r < n_runs; ++r) {
-        const int row = run_first[r], len = len_s[row];
-        const int ka = rowptr[r0 + row];
-        for (int j = tid; j < len; j += 256) out[at + j] = static_cast<uint16_t>(lidx[ka + j] - base_s[row]);
-        at += len;
-    }
-    for (int j = at + tid; j < pt_cap; j += 256) out[j] = 0;
 }
 
 // Adds the carries of rows that were cut by chunk boundaries.  Chunks that cut the same row
