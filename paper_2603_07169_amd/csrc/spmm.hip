@@ -393,7 +393,8 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
     extern __shared__ __align__(16) unsigned char smem_raw[];
     float* Bs = reinterpret_cast<float*>(smem_raw);  // [NB + 1][KT]; row NB stays zero
     const unsigned char* const Bq = smem_raw + 16 * (threadIdx.x & 3);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // the same in every lane: what depends on it alone stays in scalar registers
     const int q = lane & 3, rsub = lane >> 2;
 
     // die-aware numbering of the (slice, split) pairs, as in spmm_csr_kernel
@@ -439,19 +440,24 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
         };
 
         int j = wave;
-        int first, nsteps, first_n, nsteps_n;
+        int first, nsteps, first_n, nsteps_n;  // first_n, nsteps_n: as loaded (vector registers), one group ahead
         load_desc(j, first, nsteps);
         load_desc(j + WAVES, first_n, nsteps_n);
+        first = __builtin_amdgcn_readfirstlane(first);
+        nsteps = __builtin_amdgcn_readfirstlane(nsteps);
         PackedBlock<CT> cur;
         cur.load(a.pcol, a.pval, (static_cast<size_t>(first) * 64 + lane) * 4);
         while (j < n_groups) {
+            // the next group's pair arrived a group ago; as scalars, block numbers and step counts cost no vector work
+            const int first_nu = __builtin_amdgcn_readfirstlane(first_n);
+            const int nsteps_nu = __builtin_amdgcn_readfirstlane(nsteps_n);
             const int pos = (y + S * j) * RPW + rsub;
             const int r = a.rows[pos < a.m ? pos : a.m - 1];
             float acc0 = 0.f, acc1 = 0.f, acc2 = 0.f, acc3 = 0.f;
             const int nblocks = nsteps > 0 ? (nsteps + 3) / 4 : 1;  // a group of empty rows: one pass that multiplies nothing
             for (int b = 0; b < nblocks; ++b) {
                 // the next block of the wavefront's stream: the group's next one, else the next group's first
-                const int next_block = b + 1 < nblocks ? first + b + 1 : first_n;
+                const int next_block = b + 1 < nblocks ? first + b + 1 : first_nu;
                 PackedBlock<CT> nxt;
                 nxt.load(a.pcol, a.pval, (static_cast<size_t>(next_block) * 64 + lane) * 4);
                 const int steps = nsteps - 4 * b;  // steps of this block still to do (4 or more: all four)
@@ -514,8 +520,8 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
                 }
             }
             j += WAVES;
-            first = first_n;
-            nsteps = nsteps_n;
+            first = first_nu;
+            nsteps = nsteps_nu;
             load_desc(j + WAVES, first_n, nsteps_n);
         }
     }
