@@ -351,8 +351,8 @@ spmv_status_t build_column_blocks(spmv_csr_s* h, spmv::Analysis* a) {
     return SPMV_OK;
 }
 
-// Regroups the entries for the two-pass plan on the device (a stable sort by column block, a count
-// per tile, prefix sums on the host, a placement pass) and switches the plan to TWOPHASE.
+// Regroups the entries for the two-pass plan on the device (a count per chunk and column block, prefix
+// sums in both orders, a placement pass that keeps the CSR order inside a tile) and switches the plan to TWOPHASE.
 spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a) try {
     if (h->m == 0 || h->nnz == 0) {
         a->info.plan = SPMV_PLAN_SCALAR;
@@ -363,10 +363,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     spmv::merge_path_splits(h->m, h->nnz, rowptr_host.data(), spmv::kTwoPhaseItems, &h->tp_row, &h->tp_nz);
     const int64_t P = static_cast<int64_t>(h->tp_row.size()) - 1;
     if (C > 65535 || C * P > spmv::kTwoPhaseMaxTiles) return SPMV_ERR_UNSUPPORTED;
-    int bits = 1;
-    while ((int64_t{1} << bits) < C) ++bits;
     const spmv::MatrixView A = view_of(h);
-    const size_t nnz = static_cast<size_t>(h->nnz);
     const size_t T = static_cast<size_t>(C * P);
 
     std::vector<int32_t> desc(2 * h->tp_row.size());
@@ -383,48 +380,34 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     // 32-bit prefix sums on the device: every tile adds at most three slots of padding
     if (h->nnz + 3 * C * P > kMaxCount) return SPMV_ERR_UNSUPPORTED;
     // temporaries of the regrouping: one allocation, cut into 256-byte aligned stretches
-    // (the scans run over the T tiles, then over P + 1 <= T + 1 chunk totals)
-    const size_t temp_bytes =
-        std::max(spmv::two_phase_sort_bytes(A.nnz, bits), spmv::two_phase_scan_bytes(static_cast<int64_t>(T) + 1));
-    if (temp_bytes == 0) return SPMV_ERR_HIP;
     const size_t P1 = static_cast<size_t>(P) + 1, C1 = static_cast<size_t>(C) + 1;
-    const size_t stretch[] = {temp_bytes, 2 * nnz, 2 * nnz, 4 * nnz, 4 * nnz, 4 * nnz, 4 * T, 4 * T,
-                              4 * T,      4 * T,   4 * T,   4 * P1,  4 * P1,  4 * C1};
+    const size_t stretch[] = {4 * T, 4 * T, 4 * T, 4 * P1, 4 * P1, 4 * C1,
+                              4 * static_cast<size_t>(spmv::two_phase_scan_blocks(static_cast<int64_t>(T) + 1))};
     constexpr int kStretches = sizeof(stretch) / sizeof(stretch[0]);
     size_t offset[kStretches + 1] = {0};
     for (int i = 0; i < kStretches; ++i) offset[i + 1] = offset[i] + (stretch[i] + 255) / 256 * 256;
     char* pool = nullptr;
     if (hip_failed(hipMalloc(reinterpret_cast<void**>(&pool), offset[kStretches]))) return SPMV_ERR_ALLOC;
-    auto at = [&](int i) { return pool + offset[i]; };
-    void* d_temp = at(0);
-    uint16_t* d_key_in = reinterpret_cast<uint16_t*>(at(1));
-    uint16_t* d_key = reinterpret_cast<uint16_t*>(at(2));
-    uint32_t* d_idx_in = reinterpret_cast<uint32_t*>(at(3));  // after the sort: the chunk of every CSR position
-    uint32_t* d_idx = reinterpret_cast<uint32_t*>(at(4));
+    auto at = [&](int i) { return reinterpret_cast<int32_t*>(pool + offset[i]); };
     spmv::TwoPhaseTables w{};
-    w.chunk_at = reinterpret_cast<int32_t*>(d_idx_in);
-    w.chunk_of = reinterpret_cast<int32_t*>(at(5));
-    w.first = reinterpret_cast<int32_t*>(at(6));
-    w.last = reinterpret_cast<int32_t*>(at(7));
-    w.padded = reinterpret_cast<int32_t*>(at(8));
-    w.base1 = reinterpret_cast<int32_t*>(at(9));
-    w.within = reinterpret_cast<int32_t*>(at(10));
-    w.in_chunk = reinterpret_cast<int32_t*>(at(11));
-    w.chunk_first = reinterpret_cast<int32_t*>(at(12));
-    w.block_first = reinterpret_cast<int32_t*>(at(13));
+    w.padded = at(0);
+    w.base1 = at(1);
+    w.within = at(2);
+    w.in_chunk = at(3);
+    w.chunk_first = at(4);
+    w.block_first = at(5);
+    w.scan_sums = at(6);
     auto release = [&] { (void)hipFree(pool); };
 
-    // sorted entries -> tiles -> prefix sums in both orders, all on the device; the host only needs where the column
-    // blocks start (to cut them into pieces) and the total
+    // counts per (column block, chunk) -> prefix sums in both orders, all on the device; the host only needs where the
+    // column blocks start (to cut them into pieces) and the total
     std::vector<int32_t> block_first(C1), piece_c, piece_g;
     if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_chunk_g), 4 * P1))) {
         release();
         return SPMV_ERR_ALLOC;
     }
-    if (hip_failed(spmv::launch_two_phase_sort(A, shift, static_cast<int>(C), bits, d_temp, temp_bytes, d_key_in, d_key, d_idx_in,
-                                               d_idx, nullptr)) ||
-        hip_failed(spmv::launch_two_phase_tables(w, d_key, d_idx, A.nnz, h->d_tp_desc, static_cast<int32_t>(C),
-                                                 static_cast<int32_t>(P), d_temp, temp_bytes, h->d_tp_chunk_g, nullptr)) ||
+    if (hip_failed(spmv::launch_two_phase_tables(A, shift, static_cast<int32_t>(C), static_cast<int32_t>(P), h->d_tp_desc, w,
+                                                 h->d_tp_chunk_g, nullptr)) ||
         hip_failed(hipMemcpy(block_first.data(), w.block_first, 4 * C1, hipMemcpyDeviceToHost))) {
         release();
         return SPMV_ERR_HIP;
@@ -445,8 +428,8 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_carry_val), 4 * static_cast<size_t>(P)))))
         st = SPMV_ERR_ALLOC;
     if (st == SPMV_OK &&
-        (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(P), d_key, d_idx, w, h->d_tp_desc, slots,
-                                                 h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_dst, h->d_tp_pos, nullptr)) ||
+        (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(C), static_cast<int32_t>(P), w, h->d_tp_desc,
+                                                 slots, h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_dst, h->d_tp_pos, nullptr)) ||
          hip_failed(hipDeviceSynchronize())))
         st = SPMV_ERR_HIP;
     release();

@@ -153,33 +153,25 @@ struct TwoPhase {
 constexpr int kTpMaxShift = 15;  // column blocks of at most 32768 columns (16-bit columns, one more value for padding)
 size_t two_phase_reduce_lds(int32_t entries, int32_t rows);
 hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* x, float* y, Scalars s, hipStream_t st);
-// Analysis time.  sort: key_out/idx_out = column block and CSR position of every entry, by column block, CSR order kept.
-size_t two_phase_sort_bytes(int32_t nnz, int bits);
-hipError_t launch_two_phase_sort(const MatrixView& A, int shift, int C, int bits, void* temp, size_t temp_bytes,
-                                 uint16_t* key_in, uint16_t* key_out, uint32_t* idx_in, uint32_t* idx_out, hipStream_t st);
-// Scratch of the regrouping (device, T = C*P tiles): all of it is temporary.
+// Analysis time.  Scratch of the regrouping (device, T = C*P tiles): all of it is temporary.
 struct TwoPhaseTables {
-    int32_t* chunk_at;     // [nnz]  chunk of every CSR position
-    int32_t* chunk_of;     // [nnz]  chunk of every sorted entry
-    int32_t* first;        // [T]    where tile t starts in the sorted order
-    int32_t* last;         // [T]    where it ends
-    int32_t* padded;       // [T]    its slots
+    int32_t* padded;       // [T]    slots of tile t = c*P + p (entries rounded up to whole groups of four)
     int32_t* base1;        // [T]    slots before it in the multiply order
     int32_t* within;       // [T]    slots of its chunk in the column blocks before its own
     int32_t* in_chunk;     // [P+1]  slots of every chunk, then 0
     int32_t* chunk_first;  // [P+1]  slots before every chunk in the reduce order, then all slots
     int32_t* block_first;  // [C+1]  slots before every column block in the multiply order, then all slots
+    int32_t* scan_sums;    // [two_phase_scan_blocks(T)] scratch of the prefix sums
 };
-size_t two_phase_scan_bytes(int64_t tiles);
-// From the sorted entries: every table above, and chunk_g[P+1] (first group of every chunk in the reduce order).
-// No atomics: in the sorted order a tile is a run.  temp: max(two_phase_sort_bytes, two_phase_scan_bytes(T)) bytes.
-hipError_t launch_two_phase_tables(const TwoPhaseTables& w, const uint16_t* key, const uint32_t* idx, int32_t nnz,
-                                   const int32_t* chunk_desc, int32_t C, int32_t P, void* temp, size_t temp_bytes,
-                                   int32_t* chunk_g, hipStream_t st);
-// Fills the padding and places every entry.
-hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, const uint16_t* key, const uint32_t* idx,
-                                  const TwoPhaseTables& w, const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val,
-                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st);
+int64_t two_phase_scan_blocks(int64_t count);
+// Counts every chunk's entries per column block and derives every table above, and chunk_g[P+1] (first group of
+// every chunk in the reduce order).  Integer arithmetic only: the result does not depend on scheduling.
+hipError_t launch_two_phase_tables(const MatrixView& A, int shift, int32_t C, int32_t P, const int32_t* chunk_desc,
+                                   const TwoPhaseTables& w, int32_t* chunk_g, hipStream_t st);
+// Fills the padding and places every entry (CSR order kept inside a tile).
+hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int32_t P, const TwoPhaseTables& w,
+                                  const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val, int32_t* tp_src,
+                                  int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st);
 // tp_val[s] = vals[tp_src[s]] wherever tp_src[s] >= 0.
 hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, hipStream_t st);
 

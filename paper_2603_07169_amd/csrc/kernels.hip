@@ -831,21 +831,31 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
         const int nwords = static_cast<int>((range + 31) >> 5);
         for (int w = tid; w < nwords; w += 256) keys[w] = 0;
         __syncthreads();
-        for (int i = tid; i < cnt; i += 256) {
-            const uint32_t rel = (static_cast<uint32_t>(colidx[k0 + i]) >> shift) - kmin;
-            atomicOr(&keys[rel >> 5], 1u << (rel & 31));
+        for (int i0 = 0; i0 < cnt; i0 += 256) {
+            const int i = i0 + tid;
+            const uint32_t rel = i < cnt ? (static_cast<uint32_t>(colidx[k0 + i]) >> shift) - kmin : 0xFFFFFFFFu;
+            const uint32_t before = __shfl_up(rel, 1);  // the entry before: the same key again needs no second atomic
+            if (i < cnt && ((tid & 63) == 0 || before != rel)) atomicOr(&keys[rel >> 5], 1u << (rel & 31));
         }
         __syncthreads();
         const int per = (nwords + 255) / 256;  // each lane owns `per` consecutive words
         const int w0 = tid * per < nwords ? tid * per : nwords, w1 = w0 + per < nwords ? w0 + per : nwords;
         int mine = 0;
         for (int w = w0; w < w1; ++w) mine += __popc(keys[w]);
-        counts[tid] = mine;
+        // distinct keys in the words of the lanes before this one, and in all
+        int incl = mine;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int up = __shfl_up(incl, d);
+            if ((tid & 63) >= d) incl += up;
+        }
+        if ((tid & 63) == 63) counts[tid >> 6] = incl;
         __syncthreads();
-        int pre = 0, total = 0;
-        for (int t = 0; t < 256; ++t) {
-            const int c = counts[t];
-            pre += t < tid ? c : 0;
+        int pre = incl - mine, total = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int c = counts[w];
+            pre += w < (tid >> 6) ? c : 0;
             total += c;
         }
         if (!fill) {
@@ -975,15 +985,13 @@ __global__ __launch_bounds__(256) void window_build_kernel(const int32_t* __rest
 // Row i of the block has base_i = lidx of its first entry (0 when empty) and rel_i = its positions minus base_i.
 // A run takes the next row when rel repeats and, from its third row on, the bases keep the step of its first two rows.
 // The block is patterned when it is staged, no row exceeds kMaxPatternLen entries, no rel is negative and there are at
-// most kMaxPatternRuns runs.  fill == 0: packs the runs into run_desc[8b .. 8b+7] (word 7 = runs, 0 when not
-// patterned), raises *max_table to the length of the block's pattern list and adds the block's entries to *covered.
+// most kMaxPatternRuns runs.  fill == 0: packs the runs into run_desc[8b .. 8b+7] (word 7 = runs, 0 when not patterned).
 // fill == 1 (same inputs, pat_pad allocated with stride pt_cap): writes the list, zero padded.
 __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __restrict__ block_desc, const int32_t* __restrict__ rowptr,
                                                             const uint16_t* __restrict__ lidx, int tile_cap, int fill,
-                                                            int32_t* __restrict__ run_desc, int32_t* max_table,
-                                                            unsigned long long* covered, uint16_t* __restrict__ pat_pad, int pt_cap) {
+                                                            int32_t* __restrict__ run_desc, uint16_t* __restrict__ pat_pad, int pt_cap) {
     __shared__ int base_s[kMaxRowsPerBlock];
-    __shared__ unsigned char len_s[kMaxRowsPerBlock], same_s[kMaxRowsPerBlock];
+    __shared__ unsigned char len_s[kMaxRowsPerBlock], same_s[kMaxRowsPerBlock], flag_s[kMaxRowsPerBlock];
     __shared__ int bad;
     __shared__ int run_first[kMaxPatternRuns + 1], run_stride[kMaxPatternRuns];
     const int tid = threadIdx.x, b = blockIdx.x;
@@ -1022,11 +1030,11 @@ __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __res
                 if (ka - pa == len) {
                     same = true;
                     const int pbase = len > 0 ? lidx[pa] : 0;
-                    for (int j = 1; j < len; ++j) same = same && (lidx[ka + j] - base == lidx[pa + j] - pbase);
+                    for (int j = 1; j < len; ++j) same &= lidx[ka + j] - base == lidx[pa + j] - pbase;
                 }
             }
             bool negative = false;
-            for (int j = 1; j < len; ++j) negative = negative || lidx[ka + j] < base;
+            for (int j = 1; j < len; ++j) negative |= lidx[ka + j] < base;
             if (negative) bad = 1;
             base_s[i] = base;
             len_s[i] = static_cast<unsigned char>(len);
@@ -1034,40 +1042,44 @@ __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __res
         }
     }
     __syncthreads();
+    // What row i does to the runs, as far as it can be said without knowing them: 1 = starts a run (its positions
+    // differ from the row before), 2 = repeats them but with another step than the row before (joins only as a run's
+    // second row), 0 = repeats positions and step.
+    if (!bad)
+        for (int i = tid; i < nr; i += 256) {
+            int f = same_s[i] ? 0 : 1;
+            if (f == 0 && i >= 2 && base_s[i] - base_s[i - 1] != base_s[i - 1] - base_s[i - 2]) f = 2;
+            flag_s[i] = static_cast<unsigned char>(f);
+        }
+    __syncthreads();
     if (tid == 0) {
         int runs = 0;
         if (!bad) {
+            bool prev_started = false;
             for (int i = 0; i < nr; ++i) {
-                bool joins = false;
-                if (runs > 0 && same_s[i]) {
-                    const int so_far = i - run_first[runs - 1], step = base_s[i] - base_s[i - 1];
-                    if (so_far == 1) {
-                        joins = true;
-                        run_stride[runs - 1] = step;
-                    } else if (step == run_stride[runs - 1]) {
-                        joins = true;
-                    }
-                }
-                if (!joins) {
+                const int f = flag_s[i];
+                const bool starts = f == 1 || (f == 2 && !prev_started);
+                if (starts) {
                     if (runs == kMaxPatternRuns) {
                         runs = 0;
                         break;
                     }
                     run_first[runs] = i;
-                    run_stride[runs] = 0;
                     ++runs;
                 }
+                prev_started = starts;
             }
             run_first[runs] = nr;
+            for (int r = 0; r < runs; ++r)  // the step of a run is that of its first two rows
+                run_stride[r] = run_first[r + 1] - run_first[r] >= 2 ? base_s[run_first[r] + 1] - base_s[run_first[r]] : 0;
         }
         {
-            int rows[4] = {0, 0, 0, 0}, len[4] = {0, 0, 0, 0}, base[4] = {0, 0, 0, 0}, stride[4] = {0, 0, 0, 0}, table = 0;
+            int rows[4] = {0, 0, 0, 0}, len[4] = {0, 0, 0, 0}, base[4] = {0, 0, 0, 0}, stride[4] = {0, 0, 0, 0};
             for (int r = 0; r < runs; ++r) {
                 rows[r] = run_first[r + 1] - run_first[r];
                 len[r] = len_s[run_first[r]];
                 base[r] = base_s[run_first[r]];
                 stride[r] = run_stride[r] & 0xFFFF;
-                table += len[r];
             }
             int32_t* d = run_desc + 8 * static_cast<int64_t>(b);
             d[0] = rows[0] | rows[1] << 16;
@@ -1078,11 +1090,35 @@ __global__ __launch_bounds__(256) void pattern_build_kernel(const int32_t* __res
             d[5] = stride[0] | stride[1] << 16;
             d[6] = stride[2] | stride[3] << 16;
             d[7] = runs;
-            if (runs > 0) {
-                atomicMax(max_table, table);
-                atomicAdd(covered, static_cast<unsigned long long>(k1 - k0));
-            }
         }
+    }
+}
+
+// *max_table = the longest pattern list of a patterned block, *covered = the entries of the patterned blocks (both
+// cleared by the caller).  A pass of its own over the packed runs: one atomic per wavefront instead of two per block
+// on the same two addresses.
+__global__ __launch_bounds__(256) void pattern_totals_kernel(const int32_t* __restrict__ block_desc, const int32_t* __restrict__ run_desc,
+                                                             int nb, int32_t* max_table, unsigned long long* covered) {
+    int table = 0;
+    unsigned long long entries = 0;
+    for (int b = blockIdx.x * 256 + threadIdx.x; b < nb; b += gridDim.x * 256) {
+        const int32_t* d = run_desc + 8 * static_cast<int64_t>(b);
+        if (d[7] > 0) {
+            const uint32_t lens = static_cast<uint32_t>(d[2]);
+            const int t = static_cast<int>((lens & 0xFF) + ((lens >> 8) & 0xFF) + ((lens >> 16) & 0xFF) + (lens >> 24));
+            table = t > table ? t : table;
+            entries += static_cast<unsigned long long>(block_desc[2 * b + 3] - block_desc[2 * b + 1]);
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int t = __shfl_xor(table, d);
+        table = t > table ? t : table;
+        entries += __shfl_xor(entries, d);
+    }
+    if ((threadIdx.x & 63) == 0 && entries > 0) {
+        atomicMax(max_table, table);
+        atomicAdd(covered, entries);
     }
 }
 
@@ -1350,7 +1386,12 @@ hipError_t launch_pattern_build(const int32_t* block_desc, int32_t nb, const int
                                 int32_t pt_cap, hipStream_t st) {
     if (nb <= 0) return hipSuccess;
     hipLaunchKernelGGL(pattern_build_kernel, dim3(nb), dim3(256), 0, st, block_desc, rowptr, lidx, block_nnz, fill ? 1 : 0, run_desc,
-                       max_table, covered, pat_pad, pt_cap);
+                       pat_pad, pt_cap);
+    if (!fill) {
+        const int grid = nb < 256 * 64 ? (nb + 255) / 256 : 64;
+        hipLaunchKernelGGL(pattern_totals_kernel, dim3(grid), dim3(256), 0, st, block_desc, static_cast<const int32_t*>(run_desc), nb,
+                           max_table, covered);
+    }
     return hipGetLastError();
 }
 

@@ -19,9 +19,8 @@
 #include <cstring>
 
 #include <hip/hip_runtime.h>
-#include <rocprim/device/device_radix_sort.hpp>
-#include <rocprim/device/device_scan.hpp>
 
+#include "analysis.h"
 #include "device_common.h"
 #include "kernels.h"
 #include "row_phase.h"
@@ -187,48 +186,113 @@ __global__ __launch_bounds__(WG) void tp_reduce_kernel(const TpReduceArgs a) {
 }
 
 // ---------------------------------------------------------------------------- analysis time
-// key[k] = column block of entry k, idx[k] = k.
-__global__ __launch_bounds__(kWG) void tp_keys_kernel(const int32_t* __restrict__ colidx, int nnz, int shift, int C,
-                                                      uint16_t* __restrict__ key, uint32_t* __restrict__ idx) {
-    for (int64_t k = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; k < nnz; k += static_cast<int64_t>(gridDim.x) * kWG) {
-        unsigned c = static_cast<unsigned>(colidx[k]) >> shift;
-        if (c >= static_cast<unsigned>(C)) c = C - 1;  // only possible when the caller skipped validation
-        key[k] = static_cast<uint16_t>(c);
-        idx[k] = static_cast<uint32_t>(k);
+// A tile is the set of entries that share a column block c and a chunk p.  A chunk is a contiguous stretch of the
+// CSR entry list, so everything is derived chunk by chunk from colidx as it lies: one workgroup counts its chunk's
+// entries per column block, prefix sums over the (c, p) table give every tile its slots in both orders, and one
+// workgroup per chunk then ranks its entries (CSR order kept inside a tile) and writes them out.  No sort over the
+// whole matrix and no gather.
+
+constexpr int kTpBinSpan = 2048;  // column blocks a workgroup handles per pass over its chunk (more: several passes)
+constexpr int kTpScanBlock = 4096;  // elements per workgroup of the prefix sums
+
+__device__ __forceinline__ unsigned column_block_of(int col, int shift, int C) {
+    const unsigned c = static_cast<unsigned>(col) >> shift;
+    return c < static_cast<unsigned>(C) ? c : static_cast<unsigned>(C - 1);  // beyond n only when the caller skipped validation
+}
+
+// padded[c*P + p] = slots of tile (c, p): its entries rounded up to whole groups of four.  One workgroup per chunk.
+__global__ __launch_bounds__(kWG) void tp_count_kernel(const int32_t* __restrict__ colidx, const int32_t* __restrict__ chunk_desc,
+                                                       int shift, int C, int P, int32_t* __restrict__ padded) {
+    __shared__ int cnt[kTpBinSpan];
+    const int p = blockIdx.x, tid = threadIdx.x;
+    const int k0 = chunk_desc[2 * p + 1], k1 = chunk_desc[2 * p + 3];
+    for (int lo = 0; lo < C; lo += kTpBinSpan) {
+        const int span = C - lo < kTpBinSpan ? C - lo : kTpBinSpan;
+        for (int i = tid; i < span; i += kWG) cnt[i] = 0;
+        __syncthreads();
+        for (int k = k0 + tid; k < k1; k += kWG) {
+            const unsigned b = column_block_of(colidx[k], shift, C) - static_cast<unsigned>(lo);
+            if (b < static_cast<unsigned>(span)) atomicAdd(&cnt[b], 1);
+        }
+        __syncthreads();
+        for (int i = tid; i < span; i += kWG) padded[static_cast<int64_t>(lo + i) * P + p] = (cnt[i] + 3) & ~3;
+        __syncthreads();
     }
 }
 
-// chunk_at[k] = the chunk whose stretch of the entry list holds position k.  One workgroup per chunk.
-__global__ __launch_bounds__(kWG) void tp_chunk_fill_kernel(const int32_t* __restrict__ chunk_desc, int32_t* __restrict__ chunk_at) {
-    const int p = blockIdx.x;
-    const int k1 = chunk_desc[2 * p + 3];
-    for (int k = chunk_desc[2 * p + 1] + threadIdx.x; k < k1; k += kWG) chunk_at[k] = p;
+// Exclusive prefix sums of 32-bit counts, three launches: sums of blocks of kTpScanBlock elements, their prefix sums
+// (one workgroup), the elements themselves.  count may be anything up to 2^31 - 1.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(v, d);
+        if (lane >= d) v += up;
+    }
+    return v;
+}
+// Exclusive prefix of v over the workgroup's kWG lanes (in lane order) and the workgroup's total; wave_sums: kWG/64 ints of LDS.
+__device__ __forceinline__ int block_exclusive_scan(int v, int* wave_sums, int* total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int incl = wave_inclusive_scan(v, lane);
+    __syncthreads();  // wave_sums may still be read from the call before
+    if (lane == 63) wave_sums[wave] = incl;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < kWG / 64; ++w) {
+        const int sw = wave_sums[w];
+        before += w < wave ? sw : 0;
+        all += sw;
+    }
+    *total = all;
+    return before + incl - v;
 }
 
-// chunk_of[q] = chunk of the q-th entry in (column block, CSR position) order.
-__global__ __launch_bounds__(kWG) void tp_chunk_of_kernel(const uint32_t* __restrict__ idx, int nnz, const int32_t* __restrict__ chunk_at,
-                                                          int32_t* __restrict__ chunk_of) {
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; q < nnz; q += static_cast<int64_t>(gridDim.x) * kWG)
-        chunk_of[q] = chunk_at[idx[q]];
+__global__ __launch_bounds__(kWG) void tp_scan_sums_kernel(const int32_t* __restrict__ in, int64_t count, int32_t* __restrict__ sums) {
+    __shared__ int wave_sums[kWG / 64];
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kTpScanBlock;
+    int v = 0;
+    for (int i = threadIdx.x; i < kTpScanBlock; i += kWG)
+        if (base + i < count) v += in[base + i];
+    int total;
+    block_exclusive_scan(v, wave_sums, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
 }
 
-// In that order the tile number c*P + p never decreases, so a tile is a run: first[t] = where it starts,
-// last[t] = where it ends (both stay 0 for a tile without entries).  No counters, no atomics.
-__global__ __launch_bounds__(kWG) void tp_runs_kernel(const uint16_t* __restrict__ key, const int32_t* __restrict__ chunk_of, int nnz,
-                                                      int P, int32_t* __restrict__ first, int32_t* __restrict__ last) {
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; q < nnz; q += static_cast<int64_t>(gridDim.x) * kWG) {
-        const int t = key[q] * P + chunk_of[q];
-        const int before = q > 0 ? key[q - 1] * P + chunk_of[q - 1] : -1;
-        const int after = q + 1 < nnz ? key[q + 1] * P + chunk_of[q + 1] : -1;
-        if (t != before) first[t] = static_cast<int32_t>(q);
-        if (t != after) last[t] = static_cast<int32_t>(q + 1);
+__global__ __launch_bounds__(kWG) void tp_scan_top_kernel(int32_t* __restrict__ sums, int nblocks) {
+    __shared__ int wave_sums[kWG / 64];
+    const int per = (nblocks + kWG - 1) / kWG;  // consecutive block sums per lane
+    const int first = threadIdx.x * per;
+    int v = 0;
+    for (int i = first; i < first + per && i < nblocks; ++i) v += sums[i];
+    int total;
+    int run = block_exclusive_scan(v, wave_sums, &total);
+    for (int i = first; i < first + per && i < nblocks; ++i) {
+        const int x = sums[i];
+        sums[i] = run;
+        run += x;
     }
 }
 
-// padded[t] = the tile's entries rounded up to whole groups of four slots.
-__global__ __launch_bounds__(kWG) void tp_pad_kernel(const int32_t* __restrict__ first, const int32_t* __restrict__ last, int T,
-                                                     int32_t* __restrict__ padded) {
-    for (int t = blockIdx.x * kWG + threadIdx.x; t < T; t += gridDim.x * kWG) padded[t] = (last[t] - first[t] + 3) & ~3;
+__global__ __launch_bounds__(kWG) void tp_scan_apply_kernel(const int32_t* __restrict__ in, int64_t count, const int32_t* __restrict__ sums,
+                                                            int32_t* __restrict__ out) {
+    __shared__ int wave_sums[kWG / 64];
+    constexpr int PER = kTpScanBlock / kWG;  // consecutive elements per lane
+    const int64_t base = static_cast<int64_t>(blockIdx.x) * kTpScanBlock + static_cast<int64_t>(threadIdx.x) * PER;
+    int x[PER];
+    int v = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        x[j] = base + j < count ? in[base + j] : 0;
+        v += x[j];
+    }
+    int total;
+    int run = sums[blockIdx.x] + block_exclusive_scan(v, wave_sums, &total);
+#pragma unroll
+    for (int j = 0; j < PER; ++j) {
+        if (base + j < count) out[base + j] = run;
+        run += x[j];
+    }
 }
 
 // One lane per chunk p walks down its column of the (c, p) table: within[c*P + p] = slots of chunk p in the column
@@ -259,17 +323,14 @@ __global__ __launch_bounds__(kWG) void tp_starts_kernel(const int32_t* __restric
 }
 
 struct TpPlaceArgs {
-    const uint16_t* key;
-    const uint32_t* idx;
-    const int32_t* chunk_of;
-    const int32_t* first;        // [C*P] where tile t starts in the sorted order (t = c*P + p)
-    const int32_t* base1;        // [C*P] slots before tile t in (c, p) order
+    const int32_t* base1;        // [C*P] slots before tile t in the multiply order (t = c*P + p)
     const int32_t* within;       // [C*P] slots of t's chunk in the column blocks before t's
-    const int32_t* chunk_first;  // [P+1] slots before each chunk in (p, c) order
+    const int32_t* chunk_first;  // [P+1] slots before each chunk in the reduce order
     const int32_t* chunk_desc;
     const int32_t* colidx;
     const void* vals;
-    int32_t nnz, P, shift, elem_bytes;
+    int32_t C, P, shift, elem_bytes;
+    int32_t span_cap;  // min(C, kTpBinSpan): the LDS tables' size
     uint16_t* tp_col;
     void* tp_val;
     int32_t* tp_src;
@@ -277,21 +338,146 @@ struct TpPlaceArgs {
     uint16_t* tp_pos;
 };
 
+// One workgroup per chunk.  Per pass over a range of column blocks: every wavefront counts its quarter of the chunk's
+// entries per block; prefix sums over (block, wavefront) give each wavefront its first place in each block's run;
+// the wavefronts then walk through their quarters 64 entries at a time, in CSR order, ranking the lanes that share a
+// block with ballots, and drop every entry at its place in an LDS copy sorted by (block, CSR position); the copy is
+// written out run by run, so the stores of a tile are coalesced.
 __global__ __launch_bounds__(kWG) void tp_place_kernel(const TpPlaceArgs a) {
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; q < a.nnz; q += static_cast<int64_t>(gridDim.x) * kWG) {
-        const int k = static_cast<int>(a.idx[q]);
-        const int c = a.key[q];
-        const int p = a.chunk_of[q];
-        const int64_t t = static_cast<int64_t>(c) * a.P + p;
-        const int o = static_cast<int>(q) - a.first[t];
-        const int s1 = a.base1[t] + o;
-        const int s2 = a.chunk_first[p] + a.within[t] + o;
-        a.tp_col[s1] = static_cast<uint16_t>(static_cast<unsigned>(a.colidx[k]) & ((1u << a.shift) - 1u));
-        if (a.elem_bytes == 4) static_cast<float*>(a.tp_val)[s1] = static_cast<const float*>(a.vals)[k];
-        else static_cast<uint16_t*>(a.tp_val)[s1] = static_cast<const uint16_t*>(a.vals)[k];
-        a.tp_src[s1] = k;
-        a.tp_pos[s2] = static_cast<uint16_t>(k - a.chunk_desc[2 * p + 1]);
-        if ((o & 3) == 0) a.tp_dst[s1 >> 2] = s2 >> 2;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    __shared__ int wave_sums[kWG / 64];
+    __shared__ int n_staged;
+    constexpr int WAVES = kWG / 64;
+    int* cntw = reinterpret_cast<int*>(smem_raw);                           // [WAVES][span_cap]
+    int* lstart = cntw + WAVES * a.span_cap;                                 // [span_cap + 1], padded to a multiple of four
+    int* tile1 = lstart + ((a.span_cap + 4) & ~3);                           // [span_cap] the tile's first slot in the multiply order, less lstart
+    int* tile2 = tile1 + a.span_cap;                                         // [span_cap] the same in the reduce order
+    uint32_t* sval = reinterpret_cast<uint32_t*>(tile2 + a.span_cap);        // [kTwoPhaseItems] value bits
+    uint16_t* spos = reinterpret_cast<uint16_t*>(sval + kTwoPhaseItems);     // CSR position within the chunk
+    uint16_t* scol = spos + kTwoPhaseItems;                                  // column within the block
+    uint16_t* sblk = scol + kTwoPhaseItems;                                  // block within the pass's range
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int p = blockIdx.x;
+    const int k0 = a.chunk_desc[2 * p + 1], k1 = a.chunk_desc[2 * p + 3];
+    const int quarter = (((k1 - k0 + WAVES - 1) / WAVES) + 63) & ~63;
+    const int q0 = k0 + wave * quarter < k1 ? k0 + wave * quarter : k1;
+    const int q1 = q0 + quarter < k1 ? q0 + quarter : k1;
+    const unsigned col_mask = (1u << a.shift) - 1u;
+    const int slot2 = a.chunk_first[p];
+
+    // the wavefront's quarter, 64 entries per round, fetched once and in one go (a lane past the quarter's end reads
+    // the chunk's last entry again and never uses it): the passes below then run out of registers
+    constexpr int ROUNDS = kTwoPhaseItems / kWG;
+    int cols[ROUNDS];
+    uint32_t vbits[ROUNDS];
+#pragma unroll
+    for (int r = 0; r < ROUNDS; ++r) {
+        cols[r] = 0;
+        vbits[r] = 0;
+    }
+    if (k0 < k1) {
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            int k = q0 + r * 64 + lane;
+            k = k < k1 ? k : k1 - 1;
+            cols[r] = a.colidx[k];
+            if (a.elem_bytes == 4) vbits[r] = static_cast<const uint32_t*>(a.vals)[k];
+            else vbits[r] = static_cast<const uint16_t*>(a.vals)[k];
+        }
+    }
+
+    for (int lo = 0; lo < a.C; lo += kTpBinSpan) {
+        const int span = a.C - lo < kTpBinSpan ? a.C - lo : kTpBinSpan;
+        int nbits = 0;
+        while ((1 << nbits) < span) ++nbits;
+        for (int i = tid; i < WAVES * a.span_cap; i += kWG) cntw[i] = 0;
+        __syncthreads();
+        int* mine_cnt = cntw + wave * a.span_cap;
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            const unsigned b = column_block_of(cols[r], a.shift, a.C) - static_cast<unsigned>(lo);
+            if (q0 + r * 64 + lane < q1 && b < static_cast<unsigned>(span)) atomicAdd(&mine_cnt[b], 1);
+        }
+        __syncthreads();
+        // per block: the wavefronts' counts become their first places inside the block's run; lstart = the runs' starts
+        constexpr int PER = kTpBinSpan / kWG;  // consecutive blocks per lane
+        int tot[PER];
+        int v = 0;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int b = tid * PER + j;
+            int run = 0;
+            if (b < span) {
+#pragma unroll
+                for (int w = 0; w < WAVES; ++w) {
+                    const int c = cntw[w * a.span_cap + b];
+                    cntw[w * a.span_cap + b] = run;
+                    run += c;
+                }
+            }
+            tot[j] = run;
+            v += run;
+        }
+        int total;
+        int run = block_exclusive_scan(v, wave_sums, &total);
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            const int b = tid * PER + j;
+            if (b < span) lstart[b] = run;
+            run += tot[j];
+        }
+        if (tid == 0) {
+            lstart[span] = total;
+            n_staged = total;
+        }
+        __syncthreads();
+        // where each block's run goes (one gather per block instead of two per entry)
+        for (int b = tid; b < span; b += kWG) {
+            const int64_t t = static_cast<int64_t>(lo + b) * a.P + p;
+            tile1[b] = a.base1[t] - lstart[b];
+            tile2[b] = slot2 + a.within[t] - lstart[b];
+        }
+        // rank and stage, wavefront by wavefront over its own quarter, 64 entries at a time in CSR order
+#pragma unroll
+        for (int r = 0; r < ROUNDS; ++r) {
+            if (q0 + r * 64 >= q1) break;
+            const int k = q0 + r * 64 + lane;
+            const unsigned b = column_block_of(cols[r], a.shift, a.C) - static_cast<unsigned>(lo);
+            const bool mine = k < q1 && b < static_cast<unsigned>(span);
+            unsigned long long same = __builtin_amdgcn_ballot_w64(mine);  // lanes of this round in the same block as this one
+            for (int bit = 0; bit < nbits; ++bit) {
+                const bool one = (b >> bit) & 1u;
+                const unsigned long long with_one = __builtin_amdgcn_ballot_w64(one);
+                same &= one ? with_one : ~with_one;
+            }
+            if (mine) {
+                const int i = lstart[b] + mine_cnt[b] + __popcll(same & below);
+                sval[i] = vbits[r];
+                spos[i] = static_cast<uint16_t>(k - k0);
+                scol[i] = static_cast<uint16_t>(static_cast<unsigned>(cols[r]) & col_mask);
+                sblk[i] = static_cast<uint16_t>(b);
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (mine && (same & below) == 0) mine_cnt[b] += __popcll(same);  // the first lane of each block moves its wavefront's place on
+            __builtin_amdgcn_wave_barrier();
+        }
+        __syncthreads();
+        const int n = n_staged;
+        for (int i = tid; i < n; i += kWG) {
+            const int b = sblk[i];
+            const int o = i - lstart[b];
+            const int s1 = tile1[b] + i;
+            const int s2 = tile2[b] + i;
+            a.tp_col[s1] = scol[i];
+            if (a.elem_bytes == 4) static_cast<uint32_t*>(a.tp_val)[s1] = sval[i];
+            else static_cast<uint16_t*>(a.tp_val)[s1] = static_cast<uint16_t>(sval[i]);
+            a.tp_src[s1] = k0 + spos[i];
+            a.tp_pos[s2] = spos[i];
+            if ((o & 3) == 0) a.tp_dst[s1 >> 2] = s2 >> 2;
+        }
+        __syncthreads();
     }
 }
 
@@ -359,63 +545,37 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
     return launch_merge_fixup(t.carry_row, t.carry_val, t.num_chunks, y, s.alpha, st);
 }
 
-size_t two_phase_sort_bytes(int32_t nnz, int bits) {
-    size_t bytes = 0;
-    if (rocprim::radix_sort_pairs(nullptr, bytes, static_cast<const uint16_t*>(nullptr), static_cast<uint16_t*>(nullptr),
-                                  static_cast<const uint32_t*>(nullptr), static_cast<uint32_t*>(nullptr),
-                                  static_cast<size_t>(nnz), 0, bits, nullptr) != hipSuccess)
-        return 0;
-    return bytes < 16 ? 16 : bytes;
-}
+int64_t two_phase_scan_blocks(int64_t count) { return (count + kTpScanBlock - 1) / kTpScanBlock; }
 
-hipError_t launch_two_phase_sort(const MatrixView& A, int shift, int C, int bits, void* temp, size_t temp_bytes,
-                                 uint16_t* key_in, uint16_t* key_out, uint32_t* idx_in, uint32_t* idx_out, hipStream_t st) {
-    hipLaunchKernelGGL(tp_keys_kernel, dim3(capped_grid(A.nnz)), dim3(kWG), 0, st, A.colidx, A.nnz, shift, C, key_in, idx_in);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    // a stable sort by column block alone: the CSR positions stay ascending inside a block, and
-    // with them the chunks
-    return rocprim::radix_sort_pairs(temp, temp_bytes, key_in, key_out, idx_in, idx_out, static_cast<size_t>(A.nnz), 0, bits,
-                                     st);
+namespace {
+// out[i] = in[0] + .. + in[i-1] for i < count; sums: two_phase_scan_blocks(count) ints of scratch.
+hipError_t exclusive_scan(const int32_t* in, int64_t count, int32_t* sums, int32_t* out, hipStream_t st) {
+    if (count <= 0) return hipSuccess;
+    const int nblocks = static_cast<int>(two_phase_scan_blocks(count));
+    hipLaunchKernelGGL(tp_scan_sums_kernel, dim3(nblocks), dim3(kWG), 0, st, in, count, sums);
+    hipLaunchKernelGGL(tp_scan_top_kernel, dim3(1), dim3(kWG), 0, st, sums, nblocks);
+    hipLaunchKernelGGL(tp_scan_apply_kernel, dim3(nblocks), dim3(kWG), 0, st, in, count, static_cast<const int32_t*>(sums), out);
+    return hipGetLastError();
 }
+}  // namespace
 
-size_t two_phase_scan_bytes(int64_t tiles) {
-    size_t bytes = 0;
-    if (rocprim::exclusive_scan(nullptr, bytes, static_cast<const int32_t*>(nullptr), static_cast<int32_t*>(nullptr), int32_t{0},
-                                static_cast<size_t>(tiles), rocprim::plus<int32_t>(), nullptr) != hipSuccess)
-        return 0;
-    return bytes < 16 ? 16 : bytes;
-}
-
-hipError_t launch_two_phase_tables(const TwoPhaseTables& w, const uint16_t* key, const uint32_t* idx, int32_t nnz,
-                                   const int32_t* chunk_desc, int32_t C, int32_t P, void* temp, size_t temp_bytes,
-                                   int32_t* chunk_g, hipStream_t st) {
+hipError_t launch_two_phase_tables(const MatrixView& A, int shift, int32_t C, int32_t P, const int32_t* chunk_desc,
+                                   const TwoPhaseTables& w, int32_t* chunk_g, hipStream_t st) {
     const int64_t T = static_cast<int64_t>(C) * P;
     hipError_t e;
-    if ((e = hipMemsetAsync(w.first, 0, sizeof(int32_t) * T, st)) != hipSuccess) return e;
-    if ((e = hipMemsetAsync(w.last, 0, sizeof(int32_t) * T, st)) != hipSuccess) return e;
-    hipLaunchKernelGGL(tp_chunk_fill_kernel, dim3(P), dim3(kWG), 0, st, chunk_desc, w.chunk_at);
-    hipLaunchKernelGGL(tp_chunk_of_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, idx, nnz, w.chunk_at, w.chunk_of);
-    hipLaunchKernelGGL(tp_runs_kernel, dim3(capped_grid(nnz)), dim3(kWG), 0, st, key, w.chunk_of, nnz, P, w.first, w.last);
-    hipLaunchKernelGGL(tp_pad_kernel, dim3(capped_grid(T)), dim3(kWG), 0, st, w.first, w.last, static_cast<int>(T), w.padded);
+    hipLaunchKernelGGL(tp_count_kernel, dim3(P), dim3(kWG), 0, st, A.colidx, chunk_desc, shift, C, P, w.padded);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    size_t bytes = temp_bytes;
-    if ((e = rocprim::exclusive_scan(temp, bytes, w.padded, w.base1, int32_t{0}, static_cast<size_t>(T), rocprim::plus<int32_t>(),
-                                     st)) != hipSuccess)
-        return e;
+    if ((e = exclusive_scan(w.padded, T, w.scan_sums, w.base1, st)) != hipSuccess) return e;
     hipLaunchKernelGGL(tp_chunk_columns_kernel, dim3(ceil_div(P + 1, kWG)), dim3(kWG), 0, st, w.padded, C, P, w.within, w.in_chunk);
-    bytes = temp_bytes;
-    if ((e = rocprim::exclusive_scan(temp, bytes, w.in_chunk, w.chunk_first, int32_t{0}, static_cast<size_t>(P) + 1,
-                                     rocprim::plus<int32_t>(), st)) != hipSuccess)
-        return e;
+    if ((e = exclusive_scan(w.in_chunk, static_cast<int64_t>(P) + 1, w.scan_sums, w.chunk_first, st)) != hipSuccess) return e;
     hipLaunchKernelGGL(tp_starts_kernel, dim3(ceil_div((C > P ? C : P) + 1, kWG)), dim3(kWG), 0, st, w.base1, w.padded, C, P,
                        w.chunk_first, w.block_first, chunk_g);
     return hipGetLastError();
 }
 
-hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, const uint16_t* key, const uint32_t* idx,
-                                  const TwoPhaseTables& w, const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val,
-                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
+hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int32_t P, const TwoPhaseTables& w,
+                                  const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val, int32_t* tp_src,
+                                  int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
     // padding first: column = the zero slot after the x block, value 0, no source, position "dropped"
     hipLaunchKernelGGL(tp_fill16_kernel, dim3(capped_grid(slots)), dim3(kWG), 0, st, tp_col, slots,
                        static_cast<uint16_t>(1u << shift));
@@ -424,9 +584,14 @@ hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t P, con
     if (e != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_src, 0xFF, static_cast<size_t>(slots) * 4, st)) != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_dst, 0, static_cast<size_t>(slots), st)) != hipSuccess) return e;
-    const TpPlaceArgs a{key, idx, w.chunk_of, w.first, w.base1, w.within, w.chunk_first, chunk_desc, A.colidx, A.vals, A.nnz,
-                        P,   shift, A.bf16 ? 2 : 4, tp_col, tp_val, tp_src, tp_dst, tp_pos};
-    hipLaunchKernelGGL(tp_place_kernel, dim3(capped_grid(A.nnz)), dim3(kWG), 0, st, a);
+    const int span_cap = C < kTpBinSpan ? C : kTpBinSpan;
+    const TpPlaceArgs a{w.base1, w.within, w.chunk_first, chunk_desc, A.colidx, A.vals, C,      P,     shift,
+                        A.bf16 ? 2 : 4, span_cap, tp_col,    tp_val,     tp_src,   tp_dst, tp_pos};
+    const size_t lds = sizeof(int) * (static_cast<size_t>(kWG / 64 + 2) * span_cap + ((span_cap + 4) & ~3)) +
+                       static_cast<size_t>(kTwoPhaseItems) * (sizeof(uint32_t) + 3 * sizeof(uint16_t));
+    static thread_local size_t allowed = 0;
+    if ((e = allow_lds(tp_place_kernel, lds, &allowed)) != hipSuccess) return e;
+    hipLaunchKernelGGL(tp_place_kernel, dim3(P), dim3(kWG), lds, st, a);
     return hipGetLastError();
 }
 

@@ -450,6 +450,26 @@ def test_two_phase_seeded_random_shapes(seed):
     A.close()
 
 
+def test_two_phase_more_column_blocks_than_one_ranking_pass():
+    """40 M columns = 2442 column blocks: the placement ranks 2048 blocks per pass over a chunk, so this takes two;
+    rows of every length class, columns over the whole width.  Layout bit for bit, product within tolerance."""
+    rng = np.random.default_rng(77)
+    n = 40_000_000
+    lens = np.concatenate([rng.integers(0, 9, 30_000), [25_000, 0, 3], rng.integers(0, 3, 4_000)])
+    p = w.from_row_lengths(lens, n, seed=12, dtype="f32", alpha=0.5, beta=1.0)
+    log("case two-phase wide", p.m, p.n, p.nnz)
+    d = DeviceProblem(p)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
+    assert A.info.plan == s.SPMV_PLAN_TWOPHASE and A.info.tp_num_col_blocks == (n + (1 << oracle.TP_SHIFT) - 1) >> oracle.TP_SHIFT > 2048
+    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+    got = A.analysis()
+    for k in TP_ARRAYS:
+        assert np.array_equal(got[k], L[k]), k
+    y_ref, S_ref = reference(p)
+    assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta)
+    A.close()
+
+
 def test_forced_two_phase_rejects_too_many_column_blocks():
     n = 65536 * (1 << oracle.TP_SHIFT) + 1                              # 65537 column blocks
     rowptr, colidx, vals = to_dev(np.array([0, 2], np.int32)), to_dev(np.array([0, n - 1], np.int32)), to_dev(np.ones(2, np.float32))
