@@ -25,6 +25,7 @@ PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 
 TP_SHIFT, TP_ITEMS, TP_PIECE_GROUPS = 14, 8192, 8192
 MAX_X_VECTORS = 1024
 MAX_PATTERN_RUNS, MAX_PATTERN_LEN = 4, 64
+SELL_HEIGHT = 64
 
 
 def build(force: bool = True) -> Path:
@@ -105,6 +106,10 @@ def _load():
         _lib.oracle_scatter_counts.argtypes = [i64, vp, vp, i32, vp, vp, vp]
         _lib.oracle_scatter_counts.restype = None
         _lib.oracle_two_phase_choice.restype = i32
+        _lib.oracle_sell_slices.argtypes = [i64, vp, i64, vp]
+        _lib.oracle_sell_slices.restype = i64
+        _lib.oracle_sell_fill.argtypes = [i64, vp, vp, i64, vp, vp, vp]
+        _lib.oracle_sell_fill.restype = None
     return _lib
 
 
@@ -395,6 +400,20 @@ def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece
     lib.oracle_two_phase_layout(m, n, _p(rowptr), _p(colidx), shift, items, piece_groups, *[_p(v) for v in out.values()])
     out.update(C=Cn, P=P, S=S, Q=Q)
     return out
+
+
+def sell_layout(m, rowptr, colidx, height=SELL_HEIGHT):
+    """The sliced ELL re-layout: dict with ns (slices), S (slots) and the arrays sell_ptr (int32, ns + 1),
+    sell_col, sell_src (int32, S; -1 where a slot holds no entry)."""
+    lib = _load()
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
+    ns = (m + height - 1) // height
+    ptr = np.zeros(ns + 1, np.int64)
+    S = int(lib.oracle_sell_slices(m, _p(rowptr), height, _p(ptr)))
+    col, src = np.zeros(S, np.int32), np.zeros(S, np.int32)
+    lib.oracle_sell_fill(m, _p(rowptr), _p(colidx), height, _p(ptr), _p(col), _p(src))
+    assert S < 2 ** 31
+    return dict(ns=ns, S=S, sell_ptr=ptr.astype(np.int32), sell_col=col, sell_src=src)
 
 
 def scatter_counts(rowptr, row_blocks, block_nnz, nv):

@@ -478,4 +478,46 @@ int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_
                : 0;
 }
 
+// Sliced ELL re-layout (the ELL storage of App. C task 14 - fixed width, col_id -1 marks padding - applied to slices
+// of `height` consecutive rows, each slice with a width of its own): slice s holds rows s*height .. s*height+height-1
+// (rows from m on count as empty), its width is its longest row, and it takes width * height slots stored column by
+// column: slot slice_ptr[s] + j * height + i belongs to entry j of the slice's i-th row.
+// slice_ptr[s] = slots of the slices before s (ns + 1 numbers, ns = ceil(m / height)); returns the total.
+int64_t oracle_sell_slices(int64_t m, const int32_t* rowptr, int64_t height, int64_t* slice_ptr) {
+    const int64_t ns = (m + height - 1) / height;
+    int64_t slots = 0;
+    for (int64_t s = 0; s < ns; ++s) {
+        int64_t width = 0;
+        for (int64_t i = 0; i < height; ++i) {
+            const int64_t r = s * height + i;
+            if (r < m) width = std::max<int64_t>(width, rowptr[r + 1] - rowptr[r]);
+        }
+        slice_ptr[s] = slots;
+        slots += width * height;
+    }
+    slice_ptr[ns] = slots;
+    return slots;
+}
+
+// sell_col[slot] = the entry's column, sell_src[slot] = its position in colidx / vals; a slot without an entry
+// (a row shorter than its slice is wide, a row from m on) holds -1 in both.
+void oracle_sell_fill(int64_t m, const int32_t* rowptr, const int32_t* colidx, int64_t height, const int64_t* slice_ptr,
+                      int32_t* sell_col, int32_t* sell_src) {
+    const int64_t ns = (m + height - 1) / height;
+    for (int64_t s = 0; s < ns; ++s) {
+        const int64_t width = (slice_ptr[s + 1] - slice_ptr[s]) / height;
+        for (int64_t j = 0; j < width; ++j)
+            for (int64_t i = 0; i < height; ++i) {
+                const int64_t slot = slice_ptr[s] + j * height + i;
+                const int64_t r = s * height + i;
+                sell_col[slot] = -1;
+                sell_src[slot] = -1;
+                if (r < m && j < rowptr[r + 1] - rowptr[r]) {
+                    sell_col[slot] = colidx[rowptr[r] + j];
+                    sell_src[slot] = static_cast<int32_t>(rowptr[r] + j);
+                }
+            }
+    }
+}
+
 }  // extern "C"

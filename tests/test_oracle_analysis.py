@@ -550,3 +550,77 @@ def test_scatter_counts_handworked():
     assert oracle.scatter_counts(rowptr, row_blocks, 4, [2, 0, 1]) == (3, 5)
     assert oracle.scatter_counts(rowptr, row_blocks, 7, [2, 5, 1]) == (8, 12)
     assert oracle.scatter_counts(rowptr, np.array([0, 6], np.int32), 4, [0]) == (0, 0)
+
+
+# ---- sliced ELL re-layout -------------------------------------------------------------------
+def test_sell_handworked(golden_dir):
+    h = json.loads((golden_dir / "sell_handworked.json").read_text())
+    rp, ci = np.array(h["rowptr"], np.int32), np.array(h["colidx"], np.int32)
+    for c in h["cases"]:
+        got = oracle.sell_layout(h["m"], rp, ci, c["height"])
+        for name in ("sell_ptr", "sell_col", "sell_src"):
+            assert got[name].tolist() == c[name], (name, c["why"])
+        assert got["S"] == c["sell_ptr"][-1] and got["ns"] == len(c["sell_ptr"]) - 1
+
+
+def check_sell(p, height):
+    """Pins the layout without restating the loops: every stored entry sits in exactly one slot, at the place the
+    definition gives its (row, entry number); everything else is padding; the slices are as wide as their longest row
+    and no wider; and the product taken slot by slot through the layout is the pinned CSR oracle's, bit for bit."""
+    L = oracle.sell_layout(p.m, p.rowptr, p.colidx, height)
+    ptr, col, src = L["sell_ptr"].astype(np.int64), L["sell_col"], L["sell_src"]
+    lens = np.diff(p.rowptr).astype(np.int64)
+    assert L["ns"] == -(-p.m // height) and ptr[0] == 0 and ptr[-1] == L["S"] == col.size == src.size
+    live = src >= 0
+    assert np.array_equal(np.sort(src[live]), np.arange(p.nnz))           # every entry once
+    assert np.array_equal(col[live], p.colidx[src[live]]) and (col[~live] == -1).all()
+    slot = np.flatnonzero(live)
+    s = np.searchsorted(ptr, slot, side="right") - 1                        # the slot's slice
+    off = slot - ptr[s]
+    row, j = s * height + off % height, off // height
+    assert (row < p.m).all() and np.array_equal(src[live], p.rowptr[row] + j) and (j < lens[row]).all()
+    widths = np.diff(ptr) // height
+    assert (np.diff(ptr) % height == 0).all()
+    padded = np.concatenate([lens, np.zeros(L["ns"] * height - p.m, np.int64)]).reshape(L["ns"], height)
+    assert np.array_equal(widths, padded.max(axis=1) if p.m else widths)
+    # the product through the layout, entries of a row in their slot order (= storage order), in double
+    y_ref, _ = oracle.spmv_problem(p)
+    wide = (lambda a: a.astype(np.float64)) if p.dtype == "f32" else (lambda a: w.bf16_bits_to_f32(a).astype(np.float64))
+    vals, x = wide(p.vals), wide(p.x)
+    y = np.zeros(p.m)
+    for k in range(int(widths.max()) if widths.size else 0):               # entry number k of every row, slice by slice
+        for sl in np.flatnonzero(widths > k):
+            base = ptr[sl] + k * height
+            e = src[base:base + height]
+            rows = sl * height + np.flatnonzero(e >= 0)
+            y[rows] += vals[e[e >= 0]] * x[col[base:base + height][e >= 0]]
+    y0 = p.y0.astype(np.float64) if p.y0 is not None else 0.0
+    assert np.array_equal(np.float64(np.float32(p.alpha)) * y + (np.float64(np.float32(p.beta)) * y0 if p.beta != 0 else 0.0), y_ref)
+
+
+@pytest.mark.parametrize("height", [1, 4, 64])
+def test_sell_properties_on_random_and_degenerate_matrices(height):
+    rng = np.random.default_rng(height)
+    for lens, n in ((rng.integers(0, 9, 300), 50), (np.zeros(70, np.int64), 5), ([0, 0, 40, 0, 1], 64), ([3], 3), ([], 7),
+                    (np.minimum(w.powerlaw_lengths(rng, 500, cap=300), 200), 200)):
+        p = w.from_row_lengths(np.asarray(lens, np.int64), n, seed=3, dtype="f32", alpha=-1.5, beta=0.5)
+        check_sell(p, height)
+    check_sell(w.from_row_lengths(rng.integers(0, 20, 129), 100, seed=4, dtype="bf16"), height)
+
+
+def test_sell_closed_forms():
+    # rows of one length L: every slice is L wide, nothing is padded but the rows past m
+    p = w.uniform_rows(1000, 1000, 7)
+    L = oracle.sell_layout(p.m, p.rowptr, p.colidx, 64)
+    assert L["ns"] == 16 and L["S"] == 16 * 64 * 7 and np.array_equal(L["sell_ptr"], np.arange(17) * 64 * 7)
+    assert (L["sell_src"] >= 0).sum() == 7000 and (L["sell_src"][-64 * 7:].reshape(7, 64)[:, 40:] == -1).all()
+    # height 1: the slices are the rows and the layout is CSR itself
+    q = w.from_row_lengths(np.array([3, 0, 5, 1]), 9, seed=1)
+    L1 = oracle.sell_layout(q.m, q.rowptr, q.colidx, 1)
+    assert np.array_equal(L1["sell_ptr"], q.rowptr) and np.array_equal(L1["sell_col"], q.colidx)
+    assert np.array_equal(L1["sell_src"], np.arange(q.nnz))
+    # one slice as tall as the matrix: the ELL layout of App. C task 14, transposed (ELL is stored row by row)
+    width = int(np.diff(q.rowptr).max())
+    ell = w.to_ell(q)[1].reshape(q.m, width)
+    Lm = oracle.sell_layout(q.m, q.rowptr, q.colidx, q.m)
+    assert np.array_equal(Lm["sell_col"].reshape(width, q.m), ell.T)

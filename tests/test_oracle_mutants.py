@@ -100,6 +100,12 @@ MUTANTS = [
     ("formats_oracle.cpp", "const int32_t j = col_ids[i * width + s];", "const int32_t j = col_ids[s * m + i];", "ELL: read as column-major"),
     ("formats_oracle.cpp", "double r = static_cast<double>(alpha) * acc[i];", "double r = acc[i];", "alpha dropped"),
     ("formats_oracle.cpp", "y_ref[row[e]] += p;\n        S_ref[row[e]] += std::fabs(p);\n    }\n    finish", "y_ref[row[e]] = p;\n        S_ref[row[e]] += std::fabs(p);\n    }\n    finish", "COO: repeated coordinates overwrite"),
+    ("analysis_oracle.cpp", "if (r < m) width = std::max<int64_t>(width, rowptr[r + 1] - rowptr[r]);", "if (r < m) width = std::max<int64_t>(width, rowptr[r + 1] - rowptr[r] - 1);", "sliced ELL: slices one entry too narrow"),
+    ("analysis_oracle.cpp", "const int64_t slot = slice_ptr[s] + j * height + i;", "const int64_t slot = slice_ptr[s] + i * ((slice_ptr[s + 1] - slice_ptr[s]) / height) + j;", "sliced ELL: slices stored row by row"),
+    ("analysis_oracle.cpp", "sell_col[slot] = -1;\n                sell_src[slot] = -1;", "sell_col[slot] = 0;\n                sell_src[slot] = -1;", "sliced ELL: padding marked with column 0"),
+    ("analysis_oracle.cpp", "for (int64_t i = 0; i < height; ++i) {\n            const int64_t r = s * height + i;\n            if (r < m) width", "for (int64_t i = 0; i + 1 < height || i == 0; ++i) {\n            const int64_t r = s * height + i;\n            if (r < m) width", "sliced ELL: a slice's last row not measured"),
+    ("analysis_oracle.cpp", "sell_src[slot] = static_cast<int32_t>(rowptr[r] + j);", "sell_src[slot] = static_cast<int32_t>(rowptr[r] + j + 1);", "sliced ELL: source position off by one"),
+    ("analysis_oracle.cpp", "sell_col[slot] = colidx[rowptr[r] + j];", "sell_col[slot] = colidx[rowptr[r]];", "sliced ELL: every slot of a row holds its first column"),
 ]
 
 
