@@ -39,7 +39,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="headline workload: one of the five configurations, 1..5")
-    ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 scalar, 2 vector, 3 binned, 4 adaptive, 5 merge, 6 windowed, 7 colblock, 8 twophase")
+    ap.add_argument("--plan", type=int, default=0, help="0 auto, 1 scalar, 2 vector, 3 binned, 4 adaptive, 5 merge, 6 windowed, 7 colblock, 8 twophase, 9 sell")
     ap.add_argument("--block-nnz", type=int, default=0)
     ap.add_argument("--rows-max", type=int, default=0)
     ap.add_argument("--items-per-chunk", type=int, default=0)
@@ -65,7 +65,7 @@ def kernels_sha256():
     h = hashlib.sha256()
     # what the CSR matrix-vector product runs (the column-blocked plan multiplies with the coordinate kernel)
     for name in ("kernels.hip", "device_common.h", "row_phase.h", "kernels.h", "capi.cpp", "analysis.cpp", "analysis.h", "formats.hip",
-                 "colblock.hip", "twophase.hip"):
+                 "colblock.hip", "twophase.hip", "sell.hip"):
         h.update((ROOT / "paper_2603_07169_amd" / "csrc" / name).read_bytes())
     return h.hexdigest()
 

@@ -71,10 +71,15 @@ typedef enum {
                                window in LDS, entries addressed by 16-bit window positions      */
     SPMV_PLAN_COLBLOCK = 7, /* entries regrouped by blocks of columns (one 4 MiB stretch of x per
                                block), each block multiplied in coordinate form with atomics    */
-    SPMV_PLAN_TWOPHASE = 8  /* two passes, neither gathering from memory: products by column block
+    SPMV_PLAN_TWOPHASE = 8, /* two passes, neither gathering from memory: products by column block
                                with the block of x in LDS, then row sums by merge-path chunk with
                                the products dropped into LDS at their CSR positions             */
+    SPMV_PLAN_SELL = 9      /* a sliced ELL copy built at analysis time (the ELL storage of paper
+                               App. C task 14, col_id -1 = padding, slice by slice): one wavefront
+                               per slice of 64 rows, one lane per row, no row offsets read       */
 } spmv_plan_t;
+
+#define SPMV_SELL_HEIGHT 64 /* rows per slice of the SELL plan */
 
 #define SPMV_MAX_X_VECTORS 1024 /* most 16-byte x vectors in one row block's window */
 
@@ -121,6 +126,10 @@ typedef struct {
     int32_t lidx_patterned;            /* WINDOWED plan: 1 when run() works from row patterns (see analyze)      */
     int32_t pat_cap;                   /* ... then: entries per block in pat_pad (a multiple of 8); 0 otherwise  */
     int64_t pat_entries;               /* ... then: stored entries held by the patterned blocks; 0 otherwise     */
+    /* SELL plan (all 0 otherwise): */
+    int64_t sell_slots;                /* slots of the sliced copy, padding included (a multiple of 64)          */
+    int32_t sell_num_slices;           /* ns = ceil(m / 64): sell_ptr holds ns+1 entries                          */
+    int32_t sell_reserved;             /* 0                                                                       */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -164,6 +173,10 @@ typedef struct {
                             then (spmm_num_blocks, 0)                                  */
     void* spmm_col;      /* [spmm_num_blocks * 256] uint16 or int32 (spmm_col_bytes)   */
     float* spmm_val;     /* [spmm_num_blocks * 256]                                    */
+    /* SELL plan only (skipped otherwise): */
+    int32_t* sell_ptr;   /* [ns+1] slots of the slices before slice s                  */
+    int32_t* sell_col;   /* [sell_slots] column of every slot, -1 = padding            */
+    int32_t* sell_src;   /* [sell_slots] its position in colidx / vals, -1 = padding   */
 } spmv_analysis_host_t;
 
 /* Records the matrix (paper App. C task 12: values / col_indices / row_offsets).
@@ -255,6 +268,16 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     share cache lines.  A forced TWOPHASE plan fails with UNSUPPORTED
  *     when C2 > 65535, C2 * P2 > 2^24 or nnz + 3 * C2 * P2 > SPMV_MAX_SIZE (a bound on S); with m == 0 or nnz == 0 it runs as
  *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
+ *   - the sliced ELL copy (plan SELL only; AUTO never picks it: on every matrix it measured the windowed or the
+ *     tile kernel did better).  The ELL storage of paper App. C task 14 - rows of one width, col_id -1 marking
+ *     padding - applied to slices of SPMV_SELL_HEIGHT = 64 consecutive rows (rows from m on count as
+ *     empty): slice s is as wide as its longest row and takes width_s * 64 slots stored column by
+ *     column, slot sell_ptr[s] + j * 64 + i belonging to entry j of the slice's i-th row; sell_col /
+ *     sell_src hold the entry's column / its position in colidx and vals, -1 in both where the row
+ *     has no such entry, and the library keeps a copy of the values in the same order (padding 0).
+ *     run() gives a wavefront to every slice and a lane to every row: aligned contiguous loads,
+ *     no row offsets, no cross-lane sums, x gathered from memory.  Fails with UNSUPPORTED when the copy would
+ *     exceed SPMV_MAX_SIZE slots; with m == 0 or nnz == 0 it runs as SCALAR.  8 + (4 or 2) bytes per slot.
  *   - with prepare_spmm = 1: spmm_rows.  The rows
  *     are cut into windows of SPMV_SPMM_WINDOW consecutive rows; inside a window the row ids are
  *     sorted by decreasing key(len) = min(ceil(len / 4), 64), rows of equal key in ascending

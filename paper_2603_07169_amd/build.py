@@ -10,7 +10,7 @@ CSRC = PKG / "csrc"
 INCLUDE = PKG.parent / "include"
 LIB_PATH = PKG / "libspmv_mi355.so"
 OBJ = PKG / "_build"   # objects only; never committed
-SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "colblock.hip", CSRC / "twophase.hip", CSRC / "static_scratch.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
+SOURCES = [CSRC / "kernels.hip", CSRC / "spmm.hip", CSRC / "formats.hip", CSRC / "colblock.hip", CSRC / "twophase.hip", CSRC / "sell.hip", CSRC / "static_scratch.hip", CSRC / "capi.cpp", CSRC / "analysis.cpp"]
 HEADERS = [CSRC / "kernels.h", CSRC / "device_common.h", CSRC / "row_phase.h", CSRC / "analysis.h", INCLUDE / "spmv_mi355.h"]
 
 HIPCC_FLAGS = [

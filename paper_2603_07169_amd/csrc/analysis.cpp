@@ -72,7 +72,7 @@ spmv_status_t resolve_params(const spmv_analyze_params_t* in, spmv_analyze_param
     spmv_analyze_params_t p{};
     if (in) p = *in;
     if (p.reserved != 0 || (p.prepare_spmm != 0 && p.prepare_spmm != 1)) return SPMV_ERR_INVALID_ARG;
-    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_TWOPHASE) return SPMV_ERR_INVALID_ARG;
+    if (p.plan < SPMV_PLAN_AUTO || p.plan > SPMV_PLAN_SELL) return SPMV_ERR_INVALID_ARG;
     if (p.items_per_chunk == 0) p.items_per_chunk = kDefaultItemsPerChunk;
     if (p.block_nnz < 0 || p.block_nnz > kMaxBlockNnz) return SPMV_ERR_INVALID_ARG;
     if (p.rows_max < 0 || p.rows_max > kMaxRowsMax) return SPMV_ERR_INVALID_ARG;

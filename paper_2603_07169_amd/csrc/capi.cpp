@@ -83,6 +83,11 @@ struct spmv_csr_s {
     hipEvent_t scratch_free = nullptr;
     hipStream_t scratch_stream = nullptr;
     bool scratch_used = false;
+    int32_t* d_sell_ptr = nullptr;  // the sliced ELL copy (SELL plan)
+    int32_t* d_sell_col = nullptr;
+    int32_t* d_sell_src = nullptr;
+    void* d_sell_val = nullptr;
+    std::vector<int32_t> sell_ptr;  // host copy for the read-back
     int32_t* d_spmm_rows = nullptr;  // row order of spmm_csr_run (prepare_spmm)
     int32_t* d_spmm_desc = nullptr;  // packed copy of A in that order (spmm_prepared == 2)
     void* d_spmm_col = nullptr;
@@ -98,7 +103,8 @@ void free_metadata(spmv_csr_s* h) {
                     h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
                     h->d_spmm_val,  h->d_tp_desc,   h->d_tp_piece_c, h->d_tp_piece_g, h->d_tp_chunk_g,
                     h->d_tp_col,    h->d_tp_val,    h->d_tp_src,    h->d_tp_dst,    h->d_tp_pos,
-                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val, h->d_lidx8, h->d_run_desc, h->d_pat_pad};
+                    h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val, h->d_lidx8, h->d_run_desc, h->d_pat_pad,
+                    h->d_sell_ptr,  h->d_sell_col,  h->d_sell_src,  h->d_sell_val};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
     h->d_tp_desc = h->d_tp_piece_c = h->d_tp_piece_g = h->d_tp_chunk_g = h->d_tp_src = h->d_tp_dst = nullptr;
@@ -120,6 +126,9 @@ void free_metadata(spmv_csr_s* h) {
     h->cb_ptr.clear();
     h->d_lidx = h->d_lidx8 = h->d_pat_pad = nullptr;
     h->d_run_desc = nullptr;
+    h->d_sell_ptr = h->d_sell_col = h->d_sell_src = nullptr;
+    h->d_sell_val = nullptr;
+    h->sell_ptr.clear();
     h->d_spmm_rows = h->d_spmm_desc = nullptr;
     h->d_spmm_col = nullptr;
     h->d_spmm_val = nullptr;
@@ -446,6 +455,45 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     return SPMV_ERR_ALLOC;
 }
 
+// Builds the sliced ELL copy (slice widths on the host from rowptr, the slots on the device) and switches the plan to SELL.
+spmv_status_t build_sell(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a) try {
+    if (h->m == 0 || h->nnz == 0) {
+        a->info.plan = SPMV_PLAN_SCALAR;
+        return SPMV_OK;
+    }
+    constexpr int64_t H = spmv::kSellHeight;
+    const int64_t ns = (h->m + H - 1) / H;
+    h->sell_ptr.assign(static_cast<size_t>(ns) + 1, 0);
+    int64_t slots = 0;
+    for (int64_t s = 0; s < ns; ++s) {
+        int64_t width = 0;
+        const int64_t r1 = std::min<int64_t>(h->m, (s + 1) * H);
+        for (int64_t r = s * H; r < r1; ++r)
+            width = std::max<int64_t>(width, static_cast<int64_t>(rowptr_host[static_cast<size_t>(r) + 1]) - rowptr_host[static_cast<size_t>(r)]);
+        h->sell_ptr[static_cast<size_t>(s)] = static_cast<int32_t>(slots);
+        slots += width * H;
+        if (slots > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    }
+    h->sell_ptr[static_cast<size_t>(ns)] = static_cast<int32_t>(slots);
+    spmv_status_t st = upload(h->sell_ptr, &h->d_sell_ptr);
+    if (st != SPMV_OK) return st;
+    const size_t S = static_cast<size_t>(slots > 0 ? slots : 1);
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_sell_col), 4 * S)) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_sell_src), 4 * S)) ||
+        hip_failed(hipMalloc(&h->d_sell_val, (h->dtype == SPMV_F32 ? 4 : 2) * S)))
+        return SPMV_ERR_ALLOC;
+    if (hip_failed(spmv::launch_sell_fill(view_of(h), h->d_sell_ptr, static_cast<int32_t>(ns), h->d_sell_col, h->d_sell_src,
+                                          h->d_sell_val, nullptr)) ||
+        hip_failed(hipDeviceSynchronize()))
+        return SPMV_ERR_HIP;
+    a->info.plan = SPMV_PLAN_SELL;
+    a->info.sell_slots = slots;
+    a->info.sell_num_slices = static_cast<int32_t>(ns);
+    return SPMV_OK;
+} catch (const std::bad_alloc&) {
+    return SPMV_ERR_ALLOC;
+}
+
 spmv::TwoPhase two_phase_of(const spmv_csr_s* h) {
     spmv::TwoPhase t{};
     t.shift = h->info.tp_col_shift;
@@ -613,6 +661,7 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
                                                                                      a.x_vectors_counted, a.entries_counted);
         if (p.plan == SPMV_PLAN_COLBLOCK || automatic) st = build_column_blocks(h, &a);
     }
+    if (st == SPMV_OK && p.plan == SPMV_PLAN_SELL) st = build_sell(h, rowptr_host, &a);
     if (st == SPMV_OK && p.prepare_spmm) st = build_spmm_order(h, rowptr_host, &a);
     if (st == SPMV_OK) {
         const size_t P = static_cast<size_t>(a.info.num_chunks > 0 ? a.info.num_chunks : 1);
@@ -707,6 +756,9 @@ spmv_status_t spmv_csr_run(spmv_handle_t h, const void* x, float* y, float alpha
         }
         case SPMV_PLAN_TWOPHASE:
             e = spmv::launch_two_phase(two_phase_of(h), A, x, y, s, st);
+            break;
+        case SPMV_PLAN_SELL:
+            e = spmv::launch_sell(A, h->d_sell_ptr, h->info.sell_num_slices, h->d_sell_col, h->d_sell_val, x, y, s, st);
             break;
         case SPMV_PLAN_MERGE:
             e = spmv::launch_merge(A, h->d_chunk_desc, static_cast<int32_t>(h->info.num_chunks),
@@ -814,6 +866,7 @@ spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream) {
     hipError_t e = hipSuccess;
     if (h->info.plan == SPMV_PLAN_COLBLOCK) e = spmv::launch_column_block_values(A, h->d_cb_src, h->d_cb_vals, st);
     if (h->info.plan == SPMV_PLAN_TWOPHASE) e = spmv::launch_two_phase_values(A, h->d_tp_src, h->d_tp_val, h->info.tp_slots, st);
+    if (h->info.plan == SPMV_PLAN_SELL) e = spmv::launch_sell_values(A, h->d_sell_src, h->d_sell_val, h->info.sell_slots, st);
     if (e == hipSuccess && h->info.spmm_prepared == 2)
         e = spmv::launch_spmm_pack(A, h->d_spmm_rows, h->d_spmm_desc, static_cast<int32_t>((h->m + 15) / 16),
                                    h->info.spmm_col_bytes == 2, h->d_spmm_col, h->d_spmm_val, st);
@@ -904,6 +957,14 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
         if (out->tp_pos && S > 0 && hip_failed(hipMemcpy(out->tp_pos, h->d_tp_pos, sizeof(uint16_t) * S, hipMemcpyDeviceToHost)))
             return SPMV_ERR_HIP;
     }
+    if (h->info.plan == SPMV_PLAN_SELL) {
+        if (out->sell_ptr) std::memcpy(out->sell_ptr, h->sell_ptr.data(), sizeof(int32_t) * h->sell_ptr.size());
+        const Copy scopies[] = {{out->sell_col, h->d_sell_col, h->info.sell_slots}, {out->sell_src, h->d_sell_src, h->info.sell_slots}};
+        for (const Copy& c : scopies)
+            if (c.dst && c.count > 0 &&
+                hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))
+                return SPMV_ERR_HIP;
+    }
     if (h->info.plan == SPMV_PLAN_WINDOWED) {
         const Copy wcopies[] = {{out->xv_ptr, h->d_xv_ptr, h->info.num_row_blocks + 1},
                                 {out->xv_start, h->d_xv_start, h->info.num_x_vectors},
@@ -935,7 +996,7 @@ spmv_status_t spmv_analyze_host(int64_t m, int64_t n, int64_t nnz, const int32_t
     spmv_analyze_params_t p{};
     spmv_status_t st = spmv::resolve_params(params, &p);
     if (st != SPMV_OK) return st;
-    if (p.plan == SPMV_PLAN_WINDOWED || p.plan == SPMV_PLAN_COLBLOCK || p.plan == SPMV_PLAN_TWOPHASE)
+    if (p.plan == SPMV_PLAN_WINDOWED || p.plan == SPMV_PLAN_COLBLOCK || p.plan == SPMV_PLAN_TWOPHASE || p.plan == SPMV_PLAN_SELL)
         return SPMV_ERR_INVALID_ARG;  // they need colidx: device only
     spmv::Analysis a;
     st = spmv::analyze_rowptr(m, n, nnz, rowptr_host, p, &a, out && out->bin_rows);
@@ -987,6 +1048,7 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_WINDOWED: return h->info.lidx_patterned ? spmv::pattern_kernel_name() : spmv::window_kernel_name();
         case SPMV_PLAN_COLBLOCK: return "spmv_coo_kernel";
         case SPMV_PLAN_TWOPHASE: return "tp_multiply_kernel";
+        case SPMV_PLAN_SELL: return spmv::sell_kernel_name();
         default: return "";
     }
 }

@@ -175,6 +175,16 @@ hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int
 // tp_val[s] = vals[tp_src[s]] wherever tp_src[s] >= 0.
 hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, hipStream_t st);
 
+// The sliced ELL plan.  slice_ptr[ns+1]: slots before each slice of kSellHeight rows (a slice takes width * kSellHeight
+// slots, stored column by column).  fill: column, source position and value of every slot (-1, -1, 0 for padding).
+constexpr int kSellHeight = 64;
+hipError_t launch_sell_fill(const MatrixView& A, const int32_t* slice_ptr, int32_t ns, int32_t* sell_col, int32_t* sell_src,
+                            void* sell_val, hipStream_t st);
+// sell_val[s] = vals[sell_src[s]] wherever sell_src[s] >= 0.
+hipError_t launch_sell_values(const MatrixView& A, const int32_t* sell_src, void* sell_val, int64_t slots, hipStream_t st);
+hipError_t launch_sell(const MatrixView& A, const int32_t* slice_ptr, int32_t ns, const int32_t* sell_col, const void* sell_val,
+                       const void* x, float* y, Scalars s, hipStream_t st);
+
 // Cross-lane reduction self-check on one wavefront.  in: device float[64], lane l contributes in[l].
 // out: device float[14*64]; out[gi*64 + l] = sum over lane l's aligned group of G = 2^gi lanes,
 // gi = 0..6 from the compile-time variant, then the same seven again from the run-time variant.
@@ -186,5 +196,6 @@ const char* tile_kernel_name();  // kernel of the adaptive and merge plans
 const char* window_kernel_name();
 const char* pattern_kernel_name();
 const char* spmm_kernel_name();
+const char* sell_kernel_name();
 
 }  // namespace spmv

@@ -18,9 +18,10 @@ SPMV_OK = 0
 (SPMV_ERR_INVALID_ARG, SPMV_ERR_BAD_STRUCTURE, SPMV_ERR_UNSUPPORTED, SPMV_ERR_NOT_ANALYZED, SPMV_ERR_ALLOC,
  SPMV_ERR_HIP, SPMV_ERR_BUSY) = range(1, 8)
 (SPMV_PLAN_AUTO, SPMV_PLAN_SCALAR, SPMV_PLAN_VECTOR, SPMV_PLAN_BINNED, SPMV_PLAN_ADAPTIVE, SPMV_PLAN_MERGE,
- SPMV_PLAN_WINDOWED, SPMV_PLAN_COLBLOCK, SPMV_PLAN_TWOPHASE) = range(9)
+ SPMV_PLAN_WINDOWED, SPMV_PLAN_COLBLOCK, SPMV_PLAN_TWOPHASE, SPMV_PLAN_SELL) = range(10)
 PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock",
-              8: "twophase"}
+              8: "twophase", 9: "sell"}
+SPMV_SELL_HEIGHT = 64
 SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 SPMV_MAX_SIZE = 2 ** 31 - 2 ** 22
@@ -49,7 +50,8 @@ class spmv_analysis_info_t(C.Structure):
                 ("spmm_num_blocks", C.c_int64), ("tp_slots", C.c_int64), ("tp_col_shift", C.c_int32),
                 ("tp_items", C.c_int32), ("tp_num_col_blocks", C.c_int32), ("tp_num_chunks", C.c_int32),
                 ("tp_num_pieces", C.c_int32), ("lidx_grouped", C.c_int32), ("lidx_patterned", C.c_int32),
-                ("pat_cap", C.c_int32), ("pat_entries", C.c_int64)]
+                ("pat_cap", C.c_int32), ("pat_entries", C.c_int64), ("sell_slots", C.c_int64), ("sell_num_slices", C.c_int32),
+                ("sell_reserved", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
@@ -64,7 +66,8 @@ class spmv_analysis_host_t(C.Structure):
                 ("tp_row", C.c_void_p), ("tp_nz", C.c_void_p), ("tp_piece_c", C.c_void_p), ("tp_piece_g", C.c_void_p),
                 ("tp_chunk_g", C.c_void_p), ("tp_col", C.c_void_p), ("tp_src", C.c_void_p), ("tp_dst", C.c_void_p),
                 ("tp_pos", C.c_void_p),
-                ("spmm_rows", C.c_void_p), ("spmm_desc", C.c_void_p), ("spmm_col", C.c_void_p), ("spmm_val", C.c_void_p)]
+                ("spmm_rows", C.c_void_p), ("spmm_desc", C.c_void_p), ("spmm_col", C.c_void_p), ("spmm_val", C.c_void_p),
+                ("sell_ptr", C.c_void_p), ("sell_col", C.c_void_p), ("sell_src", C.c_void_p)]
 
 
 class SpmvError(RuntimeError):
@@ -211,6 +214,9 @@ def _host_buffers(info):
                     tp_chunk_g=np.zeros(info.tp_num_chunks + 1, np.int32), tp_col=np.zeros(info.tp_slots, np.uint16),
                     tp_src=np.zeros(info.tp_slots, np.int32), tp_dst=np.zeros(info.tp_slots // 4, np.int32),
                     tp_pos=np.zeros(info.tp_slots, np.uint16))
+    if info.plan == SPMV_PLAN_SELL:
+        bufs.update(sell_ptr=np.zeros(info.sell_num_slices + 1, np.int32), sell_col=np.zeros(info.sell_slots, np.int32),
+                    sell_src=np.zeros(info.sell_slots, np.int32))
     if info.spmm_prepared:
         bufs.update(spmm_rows=np.zeros(info.m, np.int32))
     if info.spmm_prepared == 2:

@@ -11,7 +11,7 @@ import paper_2603_07169_amd as s
 TOL = {"f32": 1e-5, "bf16": 8e-3}
 DTYPE_CODE = {"f32": s.SPMV_F32, "bf16": s.SPMV_BF16}
 ALL_PLANS = [s.SPMV_PLAN_SCALAR, s.SPMV_PLAN_VECTOR, s.SPMV_PLAN_BINNED, s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE,
-             s.SPMV_PLAN_WINDOWED, s.SPMV_PLAN_COLBLOCK, s.SPMV_PLAN_TWOPHASE]
+             s.SPMV_PLAN_WINDOWED, s.SPMV_PLAN_COLBLOCK, s.SPMV_PLAN_TWOPHASE, s.SPMV_PLAN_SELL]
 
 
 def plan_params(plan):

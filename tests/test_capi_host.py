@@ -104,7 +104,7 @@ def test_analyze_parameter_ranges():
     assert st(block_nnz=8192, rows_max=1024, items_per_chunk=8192, vector_lanes=64, plan=5) == s.SPMV_OK
     for bad in (dict(block_nnz=8193), dict(block_nnz=-1), dict(rows_max=1025), dict(rows_max=-3),
                 dict(items_per_chunk=8193), dict(items_per_chunk=-1), dict(vector_lanes=3), dict(vector_lanes=1),
-                dict(vector_lanes=128), dict(plan=6), dict(plan=7), dict(plan=8), dict(plan=9), dict(plan=-1)):  # 6, 7, 8 need colidx: device only
+                dict(vector_lanes=128), dict(plan=6), dict(plan=7), dict(plan=8), dict(plan=9), dict(plan=10), dict(plan=-1)):  # 6 .. 9 need colidx: device only
         assert st(**bad) == s.SPMV_ERR_INVALID_ARG, bad
 
 

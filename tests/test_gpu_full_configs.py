@@ -95,6 +95,16 @@ def test_full_config_matches_oracle(k):
         A = d.matrix(dict(plan=s.SPMV_PLAN_ADAPTIVE))
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full adaptive")
     A.close()
+    if k != 4:
+        # the sliced ELL plan (forced; AUTO never picks it) on the near-uniform configs: product, and on the Laplacian the copy itself
+        A = d.matrix(dict(plan=s.SPMV_PLAN_SELL))
+        assert A.info.plan == s.SPMV_PLAN_SELL
+        assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full sell")
+        if k == 2:
+            L = oracle.sell_layout(p.m, p.rowptr, p.colidx)
+            got = A.analysis()
+            assert A.info.sell_slots == L["S"] and all(np.array_equal(got[n], L[n]) for n in ("sell_ptr", "sell_col", "sell_src"))
+        A.close()
 
 
 def test_power_law_literal_reading_and_capped_row():

@@ -470,6 +470,55 @@ def test_two_phase_more_column_blocks_than_one_ranking_pass():
     A.close()
 
 
+# ------------------------------------------------------------------ the sliced ELL plan
+@pytest.mark.parametrize("which", ["mixed_f32", "mixed_bf16", "uniform", "one_row", "long_row", "stencil", "short_last_slice"])
+def test_sell_layout_equals_oracle_and_multiplies(which):
+    """Forced SELL plan: the sliced copy read back bit for bit (slice bounds, columns, source positions, -1 padding),
+    the product within tolerance and the same bits on every run; the kernel name says which kernel ran."""
+    rng = np.random.default_rng(91)
+    if which.startswith("mixed"):
+        lens = np.concatenate([rng.integers(0, 40, 3000), [0] * 130, [300, 0, 1], rng.integers(0, 5, 1000)])
+        p = w.from_row_lengths(lens, 5000, seed=8, dtype=which[6:], alpha=1.5, beta=-0.5, allow_dup=True)
+    elif which == "uniform":
+        p = w.uniform_rows(4096, 4096, 16)
+    elif which == "one_row":
+        p = w.from_row_lengths(np.array([37]), 64, seed=2, beta=1.0)
+    elif which == "long_row":
+        p = w.from_row_lengths(np.concatenate([rng.integers(0, 6, 200), [50_000], rng.integers(0, 6, 200)]), 60_000, seed=3, dtype="bf16")
+    elif which == "stencil":
+        p = w.stencil27(20, dtype="bf16")
+    else:
+        p = w.from_row_lengths(rng.integers(1, 9, 64 * 5 + 1), 700, seed=5)
+    log("case sell", which, p.m, p.nnz)
+    d = DeviceProblem(p, offset_elems=1 if which == "mixed_f32" else 0)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_SELL))
+    L = oracle.sell_layout(p.m, p.rowptr, p.colidx)
+    assert A.info.plan == s.SPMV_PLAN_SELL and (A.info.sell_num_slices, A.info.sell_slots) == (L["ns"], L["S"])
+    assert s.spmv_csr_main_kernel_name(A.handle) == "spmv_sell_kernel"
+    got = A.analysis()
+    for k in ("sell_ptr", "sell_col", "sell_src"):
+        assert np.array_equal(got[k], L[k]), k
+    y_ref, S_ref = reference(p)
+    y = d.run(A)
+    assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict=(p.beta == 0.0))
+    assert np.array_equal(d.run(A), y)
+    A.close()
+
+
+def test_sell_does_not_carry_nan_from_x0_into_padded_rows():
+    """Padding slots point at no column: whatever x[0] holds (here NaN), a row shorter than its slice is not touched by it."""
+    p = w.from_row_lengths(np.array([5, 1, 0, 3] * 40), 49, seed=11)
+    x = np.concatenate([[np.float32("nan")], p.x]).astype(np.float32)      # column 0 is read by no entry
+    q = w.CsrProblem("no_col0", "f32", p.m, 50, p.rowptr, (p.colidx + 1).astype(np.int32), p.vals, x, None, 1.0, 0.0)
+    d = DeviceProblem(q)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_SELL))
+    y = d.run(A)
+    y_ref, S_ref = reference(q)
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(y_ref))
+    assert_close(q, y, y_ref, S_ref, 1.0, 0.0, strict=True)
+    A.close()
+
+
 def test_forced_two_phase_rejects_too_many_column_blocks():
     n = 65536 * (1 << oracle.TP_SHIFT) + 1                              # 65537 column blocks
     rowptr, colidx, vals = to_dev(np.array([0, 2], np.int32)), to_dev(np.array([0, n - 1], np.int32)), to_dev(np.ones(2, np.float32))
