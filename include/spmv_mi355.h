@@ -350,9 +350,9 @@ spmv_status_t spmv_ell_run(int64_t m, int64_t n, int64_t width, const int32_t* c
                            spmv_dtype_t dtype, const void* x, float* y, float alpha, float beta, void* stream);
 
 /* Brings the library's own copies of the matrix values up to date after the caller has changed vals
- * in place (same structure, new numbers: the case of a nonlinear or time-stepping solver).  Three
- * things hold such copies: the COLBLOCK and TWOPHASE plans (values regrouped by column blocks / by
- * tiles) and the packed copy of the sparse-times-dense product; with none of them, this does nothing.  Enqueues on `stream`: no
+ * in place (same structure, new numbers: the case of a nonlinear or time-stepping solver).  Four
+ * things hold such copies: the COLBLOCK, TWOPHASE and SELL plans (values regrouped by column blocks / by
+ * tiles / by slices) and the packed copy of the sparse-times-dense product; with none of them, this does nothing.  Enqueues on `stream`: no
  * allocation, no copy to the host, no synchronisation.  rowptr and colidx must be unchanged.
  * Errors: INVALID_ARG (null handle), NOT_ANALYZED, HIP. */
 spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream);
