@@ -14,12 +14,14 @@
 // the paper's task): the definition written out as a stable sort.  Pins: a hand-worked fixture,
 // and the defining properties checked with numpy on random lengths.  And the packed copy of A in
 // that order, slot by slot from its definition.  Pins: a hand-worked fixture; every entry found
-// exactly once, everything else padding.
+// exactly once, everything else padding; rows with equally many columns of every residue (a closed form).
 
 #include <algorithm>
 #include <cmath>
 #include <cstdint>
 #include <numeric>
+#include <utility>
+#include <vector>
 
 extern "C" {
 
@@ -118,25 +120,47 @@ int64_t oracle_spmm_packed_layout(int64_t m, const int32_t* rowptr, const int32_
     return blocks;
 }
 
-// Packed copy, contents: slot ((desc[2g] + b) * 64 + 4 i + q) * 4 + e holds entry 16 b + 4 q + e
-// of the i-th row of group g, or padding (column -1, value 0) where the row has no such entry.
+// Packed copy, the order of a row's entries.  The row at position p of rows[] takes its entries by increasing
+// key(e) = 4 * (earlier entries of the row whose column is congruent to e's modulo 4) + (column of e - p) mod 4
+// (the keys of a row are distinct).  The kernel keeps B's rows 64 bytes apart in LDS, four to a cycle of the banks, and
+// reads entry number t of 16 rows at once: this way neighbouring rows ask for different quarters of the banks as long
+// as each has entries of every residue left.
+static std::vector<int64_t> packed_entry_order(const int32_t* colidx, int64_t first, int64_t len, int64_t p) {
+    std::vector<std::pair<int64_t, int64_t>> keyed(static_cast<size_t>(len));
+    int64_t seen[4] = {0, 0, 0, 0};
+    for (int64_t t = 0; t < len; ++t) {
+        const int64_t c = colidx[first + t];
+        keyed[static_cast<size_t>(t)] = {4 * seen[c % 4]++ + ((c - p) % 4 + 4) % 4, t};
+    }
+    std::sort(keyed.begin(), keyed.end());
+    std::vector<int64_t> order(static_cast<size_t>(len));
+    for (int64_t t = 0; t < len; ++t) order[static_cast<size_t>(t)] = keyed[static_cast<size_t>(t)].second;
+    return order;
+}
+
+// Packed copy, contents: slot ((desc[2g] + b) * 64 + 4 i + q) * 4 + e holds the entry of rank 16 b + 4 q + e (in the
+// order above) of the i-th row of group g, or padding (column -1, value 0) where the row has no such entry.
 void oracle_spmm_pack(int64_t m, const int32_t* rowptr, const int32_t* colidx, const float* vals, const int32_t* rows,
                       const int32_t* desc, int32_t* pcol, float* pval) {
     const int64_t groups = (m + 15) / 16;
     for (int64_t g = 0; g < groups; ++g)
-        for (int64_t b = 0; b < desc[2 * g + 2] - desc[2 * g]; ++b)
-            for (int64_t i = 0; i < 16; ++i)
+        for (int64_t i = 0; i < 16; ++i) {
+            const int64_t p = 16 * g + i;
+            const int64_t first = p < m ? rowptr[rows[p]] : 0, len = p < m ? rowptr[rows[p] + 1] - first : 0;
+            const std::vector<int64_t> order = packed_entry_order(colidx, first, len, p);
+            for (int64_t b = 0; b < desc[2 * g + 2] - desc[2 * g]; ++b)
                 for (int64_t q = 0; q < 4; ++q)
                     for (int64_t e = 0; e < 4; ++e) {
                         const int64_t slot = ((desc[2 * g] + b) * 64 + 4 * i + q) * 4 + e;
-                        const int64_t p = 16 * g + i, t = 16 * b + 4 * q + e;
+                        const int64_t t = 16 * b + 4 * q + e;
                         pcol[slot] = -1;
                         pval[slot] = 0.0f;
-                        if (p < m && t < rowptr[rows[p] + 1] - rowptr[rows[p]]) {
-                            pcol[slot] = colidx[rowptr[rows[p]] + t];
-                            pval[slot] = vals[rowptr[rows[p]] + t];
+                        if (t < len) {
+                            pcol[slot] = colidx[first + order[static_cast<size_t>(t)]];
+                            pval[slot] = vals[first + order[static_cast<size_t>(t)]];
                         }
                     }
+        }
 }
 
 // The packed copy is built when it has at most 2 * nnz slots (256 per block) and 2^22 blocks.

@@ -106,6 +106,9 @@ MUTANTS = [
     ("analysis_oracle.cpp", "for (int64_t i = 0; i < height; ++i) {\n            const int64_t r = s * height + i;\n            if (r < m) width", "for (int64_t i = 0; i + 1 < height || i == 0; ++i) {\n            const int64_t r = s * height + i;\n            if (r < m) width", "sliced ELL: a slice's last row not measured"),
     ("analysis_oracle.cpp", "sell_src[slot] = static_cast<int32_t>(rowptr[r] + j);", "sell_src[slot] = static_cast<int32_t>(rowptr[r] + j + 1);", "sliced ELL: source position off by one"),
     ("analysis_oracle.cpp", "sell_col[slot] = colidx[rowptr[r] + j];", "sell_col[slot] = colidx[rowptr[r]];", "sliced ELL: every slot of a row holds its first column"),
+    ("spmm_oracle.cpp", "keyed[static_cast<size_t>(t)] = {4 * seen[c % 4]++ + ((c - p) % 4 + 4) % 4, t};", "keyed[static_cast<size_t>(t)] = {4 * seen[c % 4]++ + c % 4, t};", "packed copy: entry order not turned by the row's position"),
+    ("spmm_oracle.cpp", "keyed[static_cast<size_t>(t)] = {4 * seen[c % 4]++ + ((c - p) % 4 + 4) % 4, t};", "keyed[static_cast<size_t>(t)] = {seen[c % 4]++ + 4 * (((c - p) % 4 + 4) % 4), t};", "packed copy: entries grouped by residue instead of dealt out in turn"),
+    ("spmm_oracle.cpp", "pcol[slot] = colidx[first + order[static_cast<size_t>(t)]];", "pcol[slot] = colidx[first + t];", "packed copy: columns left in storage order"),
 ]
 
 

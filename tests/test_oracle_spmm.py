@@ -164,6 +164,30 @@ def test_packed_copy_holds_every_entry_once(seed):
     assert np.array_equal(desc[1:-2:2], -(-longest // 4)) and np.array_equal(np.diff(desc[0::2]), -(-longest // 16))
 
 
+def test_packed_copy_entry_order_on_rows_with_every_residue_equally_often():
+    """Rows that hold equally many columns of each residue modulo 4 (here: c consecutive quadruples of columns, in a
+    shuffled storage order): the row at position p of the order then shows, at rank t, a column with
+    (column - p) mod 4 == t mod 4 - so the 16 rows of a group ask for the four quarters of the banks in turn at every
+    rank - and columns of one residue keep their storage order."""
+    rng = np.random.default_rng(5)
+    m, c = 40, 3
+    rowptr = (np.arange(m + 1) * 4 * c).astype(np.int32)
+    colidx = np.concatenate([rng.permutation(4 * c) + 4 * int(rng.integers(0, 10)) for _ in range(m)]).astype(np.int32)
+    vals = np.arange(colidx.size, dtype=np.float32)                     # the value names the storage position
+    rows = oracle.spmm_row_order(rowptr)
+    assert rows.tolist() == list(range(m))                              # equal lengths: the order is the natural one
+    desc, blocks = oracle.spmm_packed_layout(rowptr, rows)
+    pcol, pval = oracle.spmm_pack(rowptr, colidx, vals, rows, desc)
+    for p in range(m):
+        g, i = divmod(p, 16)
+        t = np.arange(4 * c)
+        slot = ((desc[2 * g] + t // 16) * 64 + 4 * i + (t % 16) // 4) * 4 + t % 4
+        assert np.array_equal((pcol[slot] - p) % 4, t % 4), p
+        for r in range(4):                                              # one residue: storage order kept
+            pos = pval[slot][pcol[slot] % 4 == r]
+            assert np.all(np.diff(pos) > 0), (p, r)
+
+
 # ---- bf16 storage --------------------------------------------------------------------------------
 def test_bf16_handworked_and_against_the_pinned_oracles():
     """Values that bf16 holds exactly, worked by hand: A = [[1.5, 0, -2], [0, 0.25, 0]], B = [[2, -1], [4, 8], [0.5, 3]]
