@@ -287,9 +287,12 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     On top of it, a packed copy of A in that order: group g = the rows at positions 16g ..
  *     16g+15 of spmm_rows (positions from m on: empty rows), stored as ceil(L_g / 16) blocks, L_g
  *     the longest row of the group.  Slot ((first_g + b) * 64 + 4 i + q) * 4 + e of spmm_col /
- *     spmm_val holds entry 16 b + 4 q + e of the group's i-th row (i = 0..15, q = 0..3,
+ *     spmm_val holds the entry of rank 16 b + 4 q + e of the group's i-th row (i = 0..15, q = 0..3,
  *     e = 0..3), or padding past the row's end: value 0 and column 2048 when n <= 2048, else all
- *     ones.  It is built when it has at most 2 * nnz slots and 2^22 blocks (spmm_prepared = 2);
+ *     ones.  The ranks inside the row at position p of spmm_rows go by increasing
+ *     4 * (earlier entries of the row whose column is congruent to the entry's modulo 4) +
+ *     (column - p) mod 4: the entries are dealt out by column residue, turned by the row's position, so that the 16 rows
+ *     a wavefront reads at once ask for different quarters of the LDS banks.  It is built when it has at most 2 * nnz slots and 2^22 blocks (spmm_prepared = 2);
  *     otherwise only spmm_rows is (spmm_prepared = 1) and spmm_csr_run() reads CSR.  The copy
  *     holds the values as they were at analyze time, as binary32 (bf16 values widened).
  * params == NULL means all defaults.  May be called again to re-plan (old metadata is freed).

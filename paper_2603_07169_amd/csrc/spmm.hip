@@ -304,8 +304,11 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_csr_kernel(const SpmmArgs a) {
 // The same product from a packed copy of A (built at analysis time on request).  The rows are
 // taken in the length-sorted order; group g (16 rows) is stored as ceil(longest row / 16) blocks,
 // a block being what one load of the wavefront fetches: lane (row rsub, quad lane q) owns the four
-// slots of entries 16b + 4q .. 16b + 4q + 3 of its row, columns and values in arrays of their
-// own.  Slots past a row's end hold the value 0 and a column that maps to the zero row.  Against
+// slots of the entries ranked 16b + 4q .. 16b + 4q + 3 in its row's order (below), columns and values in arrays of their
+// own.  The order inside a row deals the entries out by column residue modulo 4, turned by the row's position: B's rows
+// lie 64 bytes apart in LDS, four to a cycle of the banks, and the 16 rows a wavefront reads at once then fall on the
+// four quarters in turn (bank-conflict cycles -44 % against storage order).  Slots past a row's end hold the value 0
+// and a column that maps to the zero row.  Against
 // reading CSR directly: every load is aligned and fully coalesced, columns take 2 bytes while
 // n <= 32768, no row bounds are fetched, no entry needs a validity test, and the number of steps
 // of a group is a scalar from its descriptor.
@@ -344,13 +347,36 @@ __global__ __launch_bounds__(64) void spmm_pack_kernel(const int32_t* __restrict
         len = rowptr[r + 1] - rs;
     }
     const CT pad = packed_pad_column<CT>(n);
+    // padding first: the slots past the row's end
     for (int b = 0; b < nblocks; ++b) {
         const size_t slot0 = (static_cast<size_t>(first + b) * 64 + lane) * 4;
         for (int e = 0; e < 4; ++e) {
-            const int t = 16 * b + 4 * q + e;
-            const bool live = t < len;
-            pcol[slot0 + e] = live ? static_cast<CT>(colidx[rs + t]) : pad;
-            pval[slot0 + e] = live ? widen(vals[rs + t]) : 0.f;
+            if (16 * b + 4 * q + e >= len) {
+                pcol[slot0 + e] = pad;
+                pval[slot0 + e] = 0.f;
+            }
+        }
+    }
+    // The row's entries, one lane per row.  Entry e, the j-th of the row's entries with its column residue, has the key
+    // 4 j + d with d = (column - pos) mod 4; its rank is the number of entries with a smaller key: of the entries with
+    // difference dd, those numbered below j (and number j itself when dd < d), as far as there are any.
+    if (q == 0 && len > 0) {
+        int cnt[4] = {0, 0, 0, 0};
+        for (int k = 0; k < len; ++k) ++cnt[(colidx[rs + k] - pos) & 3];
+        int seen[4] = {0, 0, 0, 0};
+        for (int k = 0; k < len; ++k) {
+            const int c = colidx[rs + k];
+            const int d = (c - pos) & 3;
+            const int j = seen[d]++;
+            int t = 0;
+#pragma unroll
+            for (int dd = 0; dd < 4; ++dd) {
+                const int below = j + (dd < d ? 1 : 0);
+                t += cnt[dd] < below ? cnt[dd] : below;
+            }
+            const size_t slot = ((static_cast<size_t>(first + (t >> 4)) * 64 + 4 * rsub + ((t >> 2) & 3)) * 4) + (t & 3);
+            pcol[slot] = static_cast<CT>(c);
+            pval[slot] = widen(vals[rs + k]);
         }
     }
 }
