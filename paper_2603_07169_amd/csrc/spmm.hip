@@ -388,11 +388,14 @@ template <>
 struct PackedBlock<uint16_t> {
     unsigned c01, c23;  // four 16-bit columns
     f32x4 v;
-    __device__ __forceinline__ void load(const void* pcol, const float* pval, size_t lane_slot) {
-        const uint2 c = *reinterpret_cast<const uint2*>(static_cast<const uint16_t*>(pcol) + lane_slot);
+    // block: the same in every lane (a scalar base address), lane: the only per-lane part of the address
+    __device__ __forceinline__ void load(const void* pcol, const float* pval, int block, int lane) {
+        const uint16_t* cb = static_cast<const uint16_t*>(pcol) + static_cast<size_t>(block) * 256;
+        const float* vb = pval + static_cast<size_t>(block) * 256;
+        const uint2 c = *reinterpret_cast<const uint2*>(cb + static_cast<unsigned>(4 * lane));
         c01 = c.x;
         c23 = c.y;
-        v = *reinterpret_cast<const f32x4*>(pval + lane_slot);
+        v = *reinterpret_cast<const f32x4*>(vb + static_cast<unsigned>(4 * lane));
     }
     __device__ __forceinline__ unsigned col(int e) const {
         const unsigned w = e < 2 ? c01 : c23;
@@ -404,9 +407,9 @@ template <>
 struct PackedBlock<int32_t> {
     i32x4 c;
     f32x4 v;
-    __device__ __forceinline__ void load(const void* pcol, const float* pval, size_t lane_slot) {
-        c = *reinterpret_cast<const i32x4*>(static_cast<const int32_t*>(pcol) + lane_slot);
-        v = *reinterpret_cast<const f32x4*>(pval + lane_slot);
+    __device__ __forceinline__ void load(const void* pcol, const float* pval, int block, int lane) {
+        c = *reinterpret_cast<const i32x4*>(static_cast<const int32_t*>(pcol) + static_cast<size_t>(block) * 256 + static_cast<unsigned>(4 * lane));
+        v = *reinterpret_cast<const f32x4*>(pval + static_cast<size_t>(block) * 256 + static_cast<unsigned>(4 * lane));
     }
     __device__ __forceinline__ unsigned col(int e) const { return static_cast<unsigned>(c[e]); }
     __device__ __forceinline__ void touch() { asm volatile("" : "+v"(c), "+v"(v)); }
@@ -472,7 +475,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
         first = __builtin_amdgcn_readfirstlane(first);
         nsteps = __builtin_amdgcn_readfirstlane(nsteps);
         PackedBlock<CT> cur;
-        cur.load(a.pcol, a.pval, (static_cast<size_t>(first) * 64 + lane) * 4);
+        cur.load(a.pcol, a.pval, first, lane);
         while (j < n_groups) {
             // the next group's pair arrived a group ago; as scalars, block numbers and step counts cost no vector work
             const int first_nu = __builtin_amdgcn_readfirstlane(first_n);
@@ -485,7 +488,7 @@ __global__ __launch_bounds__(kSpmmWG) void spmm_packed_kernel(const SpmmPackedAr
                 // the next block of the wavefront's stream: the group's next one, else the next group's first
                 const int next_block = b + 1 < nblocks ? first + b + 1 : first_nu;
                 PackedBlock<CT> nxt;
-                nxt.load(a.pcol, a.pval, (static_cast<size_t>(next_block) * 64 + lane) * 4);
+                nxt.load(a.pcol, a.pval, next_block, lane);
                 const int steps = nsteps - 4 * b;  // steps of this block still to do (4 or more: all four)
                 int off[4];
                 offsets(cur, off);
