@@ -26,6 +26,8 @@ TP_SHIFT, TP_ITEMS, TP_PIECE_GROUPS = 14, 8192, 8192
 MAX_X_VECTORS = 1024
 MAX_PATTERN_RUNS, MAX_PATTERN_LEN = 4, 64
 SELL_HEIGHT = 64
+TP_GROUP = 8                       # entries per group of the two-pass plan on groups
+TP_GROUP_SHIFT = {"bf16": 12, "f32": 11}   # log2 of the groups' columns per block: 64 KB of x either way
 
 
 def build(force: bool = True) -> Path:
@@ -106,6 +108,12 @@ def _load():
         _lib.oracle_scatter_counts.argtypes = [i64, vp, vp, i32, vp, vp, vp]
         _lib.oracle_scatter_counts.restype = None
         _lib.oracle_two_phase_choice.restype = i32
+        _lib.oracle_csr_groups.argtypes = [i64, i64, vp, vp, i32]
+        _lib.oracle_csr_groups.restype = i32
+        _lib.oracle_group_matrix.argtypes = [i64, i64, vp, vp, i32, vp, vp]
+        _lib.oracle_group_matrix.restype = None
+        _lib.oracle_grouped_two_phase_choice.argtypes = [i64, i64, i64, i32, i32, i32, i32, i32, i32, i64, i64]
+        _lib.oracle_grouped_two_phase_choice.restype = i32
         _lib.oracle_sell_slices.argtypes = [i64, vp, i64, vp]
         _lib.oracle_sell_slices.restype = i64
         _lib.oracle_sell_fill.argtypes = [i64, vp, vp, i64, vp, vp, vp]
@@ -400,6 +408,26 @@ def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece
     lib.oracle_two_phase_layout(m, n, _p(rowptr), _p(colidx), shift, items, piece_groups, *[_p(v) for v in out.values()])
     out.update(C=Cn, P=P, S=S, Q=Q)
     return out
+
+
+def csr_groups(m, rowptr, colidx, width=TP_GROUP):
+    """1 when the matrix is group-aligned (whole groups of `width` consecutive, aligned columns), else 0."""
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
+    return int(_load().oracle_csr_groups(m, colidx.size, _p(rowptr), _p(colidx), width))
+
+
+def group_matrix(m, rowptr, colidx, width=TP_GROUP):
+    """(rowptr_g, col_g) of the matrix of groups."""
+    _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
+    rp, cg = np.zeros(m + 1, np.int32), np.zeros(colidx.size // width, np.int32)
+    _load().oracle_group_matrix(m, colidx.size, _p(rowptr), _p(colidx), width, _p(rp), _p(cg))
+    return rp, cg
+
+
+def grouped_two_phase_choice(m, n, nnz, dtype, windowed_grouped, group_aligned, vectors, entries, items=TP_ITEMS):
+    eb, ve = (4, 4) if dtype == "f32" else (2, 8)
+    return int(_load().oracle_grouped_two_phase_choice(m, n, nnz, eb, ve, int(windowed_grouped), int(group_aligned),
+                                                       TP_GROUP_SHIFT[dtype], items, vectors, entries))
 
 
 def sell_layout(m, rowptr, colidx, height=SELL_HEIGHT):

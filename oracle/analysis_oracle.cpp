@@ -520,4 +520,49 @@ void oracle_sell_fill(int64_t m, const int32_t* rowptr, const int32_t* colidx, i
     }
 }
 
+// Group-aligned CSR: every row starts at a multiple of `width` entries (so it holds whole groups of `width`), and
+// every group k = width*g .. width*g + width - 1 has the columns c, c+1, .., c+width-1 with c a multiple of width: the
+// x values a group multiplies are one aligned run.  On such a matrix the two-pass plan works on groups instead of
+// entries.  Returns 1 or 0 (0 also when there is no entry).
+int32_t oracle_csr_groups(int64_t m, int64_t nnz, const int32_t* rowptr, const int32_t* colidx, int32_t width) {
+    if (nnz == 0) return 0;
+    for (int64_t i = 0; i <= m; ++i)
+        if (rowptr[i] % width != 0) return 0;
+    for (int64_t g = 0; g < nnz / width; ++g) {
+        const int64_t c = colidx[width * g];
+        if (c % width != 0) return 0;
+        for (int64_t i = 1; i < width; ++i)
+            if (colidx[width * g + i] != c + i) return 0;
+    }
+    return 1;
+}
+
+// The matrix of groups of a group-aligned matrix: m rows, ceil(n / width) columns, nnz / width entries;
+// rowptr_g[i] = rowptr[i] / width, col_g[g] = colidx[width * g] / width.
+void oracle_group_matrix(int64_t m, int64_t nnz, const int32_t* rowptr, const int32_t* colidx, int32_t width, int32_t* rowptr_g,
+                         int32_t* col_g) {
+    for (int64_t i = 0; i <= m; ++i) rowptr_g[i] = rowptr[i] / width;
+    for (int64_t g = 0; g < nnz / width; ++g) col_g[g] = colidx[width * g] / width;
+}
+
+// When AUTO takes the two-pass plan on groups of eight.  Candidates are matrices that arrived at the windowed plan with
+// grouped window positions (windowed_grouped) and are group-aligned.  Taken when x holds at least 1 MiB, the matrix of
+// groups meets the two-pass plan's own size conditions (3 * 2^21 entries, at most 65535 column blocks of 2^shift
+// columns and 2^24 tiles, eight entries or more per tile on average) and the groups are scattered: the counted row
+// blocks touch at least three distinct x vectors per four vectors their entries would fill (vec_elems entries each;
+// vectors < 0: not counted, no).
+int32_t oracle_grouped_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t vec_elems,
+                                        int32_t windowed_grouped, int32_t group_aligned, int32_t shift, int32_t items,
+                                        int64_t vectors, int64_t entries) {
+    if (!windowed_grouped || !group_aligned) return 0;
+    if (vectors < 0 || 4 * vec_elems * vectors < 3 * entries) return 0;
+    const int64_t ng = nnz / 8, ncol = (n + 7) / 8;
+    const int64_t C = (ncol + (int64_t{1} << shift) - 1) >> shift;
+    const int64_t P = (m + ng + items - 1) / items;
+    return (n * elem_bytes >= (int64_t{1} << 20) && ng >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 24) &&
+            8 * C * P <= ng)
+               ? 1
+               : 0;
+}
+
 }  // extern "C"
