@@ -129,7 +129,7 @@ typedef struct {
     /* SELL plan (all 0 otherwise): */
     int64_t sell_slots;                /* slots of the sliced copy, padding included (a multiple of 64)          */
     int32_t sell_num_slices;           /* ns = ceil(m / 64): sell_ptr holds ns+1 entries                          */
-    int32_t sell_reserved;             /* 0                                                                       */
+    int32_t tp_group;                  /* TWOPHASE plan: entries a slot stands for, 1 or 8 (see analyze); 0 otherwise */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -268,6 +268,13 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     share cache lines.  A forced TWOPHASE plan fails with UNSUPPORTED
  *     when C2 > 65535, C2 * P2 > 2^24 or nnz + 3 * C2 * P2 > SPMV_MAX_SIZE (a bound on S); with m == 0 or nnz == 0 it runs as
  *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
+ *     On groups (tp_group = 8).  A matrix is group-aligned when every row starts at a multiple of eight entries and every
+ *     group of entries 8g .. 8g+7 has the columns c, c+1, .., c+7 with c a multiple of eight.  The two-pass plan is then
+ *     laid out over the matrix of groups - m rows, ceil(n / 8) columns, nnz / 8 entries with rowptr / 8 and
+ *     colidx[8g] / 8 - by the rules above, with column blocks of 2^12 (bf16) or 2^11 (binary32) groups' columns
+ *     (64 KB of x either way): tp_src holds group numbers, tp_pos group positions within the chunk, a slot's value copy
+ *     the group's eight values, and the product written for a slot is the dot product of those eight with their run of
+ *     x.  An eighth of the slots; every size limit above then applies to the matrix of groups.
  *   - the sliced ELL copy (plan SELL only; AUTO never picks it: on every matrix it measured the windowed or the
  *     tile kernel did better).  The ELL storage of paper App. C task 14 - rows of one width, col_id -1 marking
  *     padding - applied to slices of SPMV_SELL_HEIGHT = 64 consecutive rows (rows from m on count as

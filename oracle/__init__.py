@@ -112,8 +112,6 @@ def _load():
         _lib.oracle_csr_groups.restype = i32
         _lib.oracle_group_matrix.argtypes = [i64, i64, vp, vp, i32, vp, vp]
         _lib.oracle_group_matrix.restype = None
-        _lib.oracle_grouped_two_phase_choice.argtypes = [i64, i64, i64, i32, i32, i32, i32, i32, i32, i64, i64]
-        _lib.oracle_grouped_two_phase_choice.restype = i32
         _lib.oracle_sell_slices.argtypes = [i64, vp, i64, vp]
         _lib.oracle_sell_slices.restype = i64
         _lib.oracle_sell_fill.argtypes = [i64, vp, vp, i64, vp, vp, vp]
@@ -422,12 +420,6 @@ def group_matrix(m, rowptr, colidx, width=TP_GROUP):
     rp, cg = np.zeros(m + 1, np.int32), np.zeros(colidx.size // width, np.int32)
     _load().oracle_group_matrix(m, colidx.size, _p(rowptr), _p(colidx), width, _p(rp), _p(cg))
     return rp, cg
-
-
-def grouped_two_phase_choice(m, n, nnz, dtype, windowed_grouped, group_aligned, vectors, entries, items=TP_ITEMS):
-    eb, ve = (4, 4) if dtype == "f32" else (2, 8)
-    return int(_load().oracle_grouped_two_phase_choice(m, n, nnz, eb, ve, int(windowed_grouped), int(group_aligned),
-                                                       TP_GROUP_SHIFT[dtype], items, vectors, entries))
 
 
 def sell_layout(m, rowptr, colidx, height=SELL_HEIGHT):

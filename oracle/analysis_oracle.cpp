@@ -545,24 +545,4 @@ void oracle_group_matrix(int64_t m, int64_t nnz, const int32_t* rowptr, const in
     for (int64_t g = 0; g < nnz / width; ++g) col_g[g] = colidx[width * g] / width;
 }
 
-// When AUTO takes the two-pass plan on groups of eight.  Candidates are matrices that arrived at the windowed plan with
-// grouped window positions (windowed_grouped) and are group-aligned.  Taken when x holds at least 1 MiB, the matrix of
-// groups meets the two-pass plan's own size conditions (3 * 2^21 entries, at most 65535 column blocks of 2^shift
-// columns and 2^24 tiles, eight entries or more per tile on average) and the groups are scattered: the counted row
-// blocks touch at least three distinct x vectors per four vectors their entries would fill (vec_elems entries each;
-// vectors < 0: not counted, no).
-int32_t oracle_grouped_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t vec_elems,
-                                        int32_t windowed_grouped, int32_t group_aligned, int32_t shift, int32_t items,
-                                        int64_t vectors, int64_t entries) {
-    if (!windowed_grouped || !group_aligned) return 0;
-    if (vectors < 0 || 4 * vec_elems * vectors < 3 * entries) return 0;
-    const int64_t ng = nnz / 8, ncol = (n + 7) / 8;
-    const int64_t C = (ncol + (int64_t{1} << shift) - 1) >> shift;
-    const int64_t P = (m + ng + items - 1) / items;
-    return (n * elem_bytes >= (int64_t{1} << 20) && ng >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 24) &&
-            8 * C * P <= ng)
-               ? 1
-               : 0;
-}
-
 }  // extern "C"

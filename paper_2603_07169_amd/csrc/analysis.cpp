@@ -323,6 +323,8 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
     return columns_scattered(x_vectors_counted, entries_counted) && two_phase_sizes_ok(m, n, nnz, dtype);
 }
 
+int two_phase_group_shift(spmv_dtype_t dtype) { return dtype == SPMV_BF16 ? 12 : 11; }
+
 void two_phase_pieces(int64_t C, const int32_t* block_first, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g) {
     piece_c->clear();
     piece_g->clear();

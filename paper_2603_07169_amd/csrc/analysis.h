@@ -70,6 +70,11 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
                       int64_t entries_counted);
 // The pieces of the multiply pass from where the column blocks start in the multiply order (block_first[C+1], in slots,
 // the last entry = all slots): every block's groups cut evenly into the fewest pieces of at most kTwoPhasePieceGroups.
+// The two-pass plan on groups of eight entries (a group-aligned matrix: every row starts at a multiple of eight entries and
+// every group of eight is an aligned run of eight consecutive columns).  The matrix of groups has m rows, ceil(n / 8)
+// columns and nnz / 8 entries; its column blocks hold 2^two_phase_group_shift columns (64 KB of x either way).
+constexpr int kTpGroup = 8;
+int two_phase_group_shift(spmv_dtype_t dtype);
 void two_phase_pieces(int64_t C, const int32_t* block_first, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g);
 
 // Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x

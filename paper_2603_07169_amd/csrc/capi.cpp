@@ -360,19 +360,66 @@ spmv_status_t build_column_blocks(spmv_csr_s* h, spmv::Analysis* a) {
     return SPMV_OK;
 }
 
+// Is the matrix group-aligned (every row a whole number of groups of eight entries, every group an aligned run of eight
+// consecutive columns)?  The rows are checked on the host; the columns on the device, which also leaves the groups'
+// columns in *d_gcol (allocated here, the caller frees it) when the answer is yes.
+spmv_status_t check_groups(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, bool* aligned, int32_t** d_gcol) {
+    *aligned = false;
+    *d_gcol = nullptr;
+    if (h->nnz == 0 || h->nnz % spmv::kTpGroup != 0) return SPMV_OK;
+    for (int32_t r : rowptr_host)
+        if (r % spmv::kTpGroup != 0) return SPMV_OK;
+    const int32_t ngroups = static_cast<int32_t>(h->nnz / spmv::kTpGroup);
+    int32_t* d_flag = nullptr;
+    int32_t flag = 0;
+    if (hip_failed(hipMalloc(reinterpret_cast<void**>(d_gcol), sizeof(int32_t) * static_cast<size_t>(ngroups))) ||
+        hip_failed(hipMalloc(reinterpret_cast<void**>(&d_flag), sizeof(int32_t)))) {
+        (void)hipFree(*d_gcol);
+        *d_gcol = nullptr;
+        return SPMV_ERR_ALLOC;
+    }
+    bool failed = hip_failed(hipMemcpy(d_flag, &flag, sizeof flag, hipMemcpyHostToDevice));
+    failed = failed || hip_failed(spmv::launch_two_phase_groups(h->colidx, ngroups, *d_gcol, d_flag, nullptr));
+    failed = failed || hip_failed(hipMemcpy(&flag, d_flag, sizeof flag, hipMemcpyDeviceToHost));
+    (void)hipFree(d_flag);
+    if (failed || flag != 0) {
+        (void)hipFree(*d_gcol);
+        *d_gcol = nullptr;
+        return failed ? SPMV_ERR_HIP : SPMV_OK;
+    }
+    *aligned = true;
+    return SPMV_OK;
+}
+
 // Regroups the entries for the two-pass plan on the device (a count per chunk and column block, prefix
 // sums in both orders, a placement pass that keeps the CSR order inside a tile) and switches the plan to TWOPHASE.
-spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a) try {
+// d_gcol != nullptr: the matrix is group-aligned and the plan is laid out over its matrix of groups (m rows,
+// ceil(n / 8) columns, nnz / 8 entries whose columns are d_gcol): a slot then stands for eight entries.
+spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, spmv::Analysis* a, const int32_t* d_gcol) try {
     if (h->m == 0 || h->nnz == 0) {
         a->info.plan = SPMV_PLAN_SCALAR;
         return SPMV_OK;
     }
-    const int shift = spmv::two_phase_shift(h->n);
-    const int64_t C = (h->n + (int64_t{1} << shift) - 1) >> shift;
-    spmv::merge_path_splits(h->m, h->nnz, rowptr_host.data(), spmv::kTwoPhaseItems, &h->tp_row, &h->tp_nz);
+    const int group = d_gcol ? spmv::kTpGroup : 1;
+    const int shift = d_gcol ? spmv::two_phase_group_shift(h->dtype) : spmv::two_phase_shift(h->n);
+    const int64_t ncols = d_gcol ? (h->n + group - 1) / group : h->n, nent = h->nnz / group;
+    const int64_t C = (ncols + (int64_t{1} << shift) - 1) >> shift;
+    std::vector<int32_t> rowptr_groups;
+    if (d_gcol) {
+        rowptr_groups.resize(rowptr_host.size());
+        for (size_t i = 0; i < rowptr_host.size(); ++i) rowptr_groups[i] = rowptr_host[i] / group;
+    }
+    const std::vector<int32_t>& rowptr_used = d_gcol ? rowptr_groups : rowptr_host;
+    spmv::merge_path_splits(h->m, nent, rowptr_used.data(), spmv::kTwoPhaseItems, &h->tp_row, &h->tp_nz);
     const int64_t P = static_cast<int64_t>(h->tp_row.size()) - 1;
     if (C > 65535 || C * P > spmv::kTwoPhaseMaxTiles) return SPMV_ERR_UNSUPPORTED;
-    const spmv::MatrixView A = view_of(h);
+    spmv::MatrixView A = view_of(h);
+    if (d_gcol) {  // the matrix of groups, as far as the regrouping kernels look at it
+        A.n = static_cast<int32_t>(ncols);
+        A.nnz = static_cast<int32_t>(nent);
+        A.colidx = d_gcol;
+        A.vals = nullptr;
+    }
     const size_t T = static_cast<size_t>(C * P);
 
     std::vector<int32_t> desc(2 * h->tp_row.size());
@@ -387,7 +434,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     if (st != SPMV_OK) return st;
 
     // 32-bit prefix sums on the device: every tile adds at most three slots of padding
-    if (h->nnz + 3 * C * P > kMaxCount) return SPMV_ERR_UNSUPPORTED;
+    if (nent + 3 * C * P > kMaxCount) return SPMV_ERR_UNSUPPORTED;
     // temporaries of the regrouping: one allocation, cut into 256-byte aligned stretches
     const size_t P1 = static_cast<size_t>(P) + 1, C1 = static_cast<size_t>(C) + 1;
     const size_t stretch[] = {4 * T, 4 * T, 4 * T, 4 * P1, 4 * P1, 4 * C1,
@@ -428,7 +475,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     if (st == SPMV_OK) st = upload(piece_g, &h->d_tp_piece_g);
     if (st == SPMV_OK &&
         (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_col), 2 * S)) ||
-         hip_failed(hipMalloc(&h->d_tp_val, (h->dtype == SPMV_F32 ? 4 : 2) * S)) ||
+         hip_failed(hipMalloc(&h->d_tp_val, static_cast<size_t>(group) * (h->dtype == SPMV_F32 ? 4 : 2) * S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_src), 4 * S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_dst), S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_pos), 2 * S)) ||
@@ -438,7 +485,9 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
         st = SPMV_ERR_ALLOC;
     if (st == SPMV_OK &&
         (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(C), static_cast<int32_t>(P), w, h->d_tp_desc,
-                                                 slots, h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_dst, h->d_tp_pos, nullptr)) ||
+                                                 slots, group, h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_dst, h->d_tp_pos,
+                                                 nullptr)) ||
+         (group > 1 && hip_failed(spmv::launch_two_phase_values(view_of(h), h->d_tp_src, h->d_tp_val, slots, group, nullptr))) ||
          hip_failed(hipDeviceSynchronize())))
         st = SPMV_ERR_HIP;
     release();
@@ -450,6 +499,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     a->info.tp_num_col_blocks = static_cast<int32_t>(C);
     a->info.tp_num_chunks = static_cast<int32_t>(P);
     a->info.tp_num_pieces = static_cast<int32_t>(piece_c.size());
+    a->info.tp_group = group;
     return SPMV_OK;
 } catch (const std::bad_alloc&) {
     return SPMV_ERR_ALLOC;
@@ -497,6 +547,7 @@ spmv_status_t build_sell(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host,
 spmv::TwoPhase two_phase_of(const spmv_csr_s* h) {
     spmv::TwoPhase t{};
     t.shift = h->info.tp_col_shift;
+    t.group = h->info.tp_group > 1 ? h->info.tp_group : 1;
     t.num_pieces = h->info.tp_num_pieces;
     t.num_chunks = h->info.tp_num_chunks;
     t.reduce_lds = h->tp_reduce_lds;
@@ -653,8 +704,15 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
     if (st == SPMV_OK) {
         const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan,
                                                                                   a.x_vectors_counted, a.entries_counted);
-        if (p.plan == SPMV_PLAN_TWOPHASE || automatic) st = build_two_phase(h, rowptr_host, &a);
-        if (automatic && st == SPMV_ERR_UNSUPPORTED) st = SPMV_OK;  // too many padded slots: the plan stays what it was
+        if (p.plan == SPMV_PLAN_TWOPHASE || automatic) {
+            // a group-aligned matrix is laid out over its groups of eight entries: an eighth of the slots
+            bool aligned = false;
+            int32_t* d_gcol = nullptr;
+            st = check_groups(h, rowptr_host, &aligned, &d_gcol);
+            if (st == SPMV_OK) st = build_two_phase(h, rowptr_host, &a, d_gcol);
+            if (d_gcol) (void)hipFree(d_gcol);
+            if (automatic && st == SPMV_ERR_UNSUPPORTED) st = SPMV_OK;  // too many padded slots: the plan stays what it was
+        }
     }
     if (st == SPMV_OK) {
         const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::column_block_choice(h->n, h->nnz, h->dtype, a.info.plan,
@@ -865,7 +923,8 @@ spmv_status_t spmv_csr_refresh_values(spmv_handle_t h, void* stream) {
     const spmv::MatrixView A = view_of(h);
     hipError_t e = hipSuccess;
     if (h->info.plan == SPMV_PLAN_COLBLOCK) e = spmv::launch_column_block_values(A, h->d_cb_src, h->d_cb_vals, st);
-    if (h->info.plan == SPMV_PLAN_TWOPHASE) e = spmv::launch_two_phase_values(A, h->d_tp_src, h->d_tp_val, h->info.tp_slots, st);
+    if (h->info.plan == SPMV_PLAN_TWOPHASE)
+        e = spmv::launch_two_phase_values(A, h->d_tp_src, h->d_tp_val, h->info.tp_slots, h->info.tp_group > 1 ? h->info.tp_group : 1, st);
     if (h->info.plan == SPMV_PLAN_SELL) e = spmv::launch_sell_values(A, h->d_sell_src, h->d_sell_val, h->info.sell_slots, st);
     if (e == hipSuccess && h->info.spmm_prepared == 2)
         e = spmv::launch_spmm_pack(A, h->d_spmm_rows, h->d_spmm_desc, static_cast<int32_t>((h->m + 15) / 16),
@@ -1047,7 +1106,7 @@ const char* spmv_csr_main_kernel_name(spmv_handle_t h) {
         case SPMV_PLAN_MERGE: return spmv::tile_kernel_name();
         case SPMV_PLAN_WINDOWED: return h->info.lidx_patterned ? spmv::pattern_kernel_name() : spmv::window_kernel_name();
         case SPMV_PLAN_COLBLOCK: return "spmv_coo_kernel";
-        case SPMV_PLAN_TWOPHASE: return "tp_multiply_kernel";
+        case SPMV_PLAN_TWOPHASE: return h->info.tp_group > 1 ? "tp_multiply_group_kernel" : "tp_multiply_kernel";
         case SPMV_PLAN_SELL: return spmv::sell_kernel_name();
         default: return "";
     }

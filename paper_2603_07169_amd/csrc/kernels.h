@@ -134,7 +134,8 @@ hipError_t launch_merge_fixup(const int32_t* carry_row, const float* carry_val, 
 
 // The two-pass plan (device arrays owned by the handle).
 struct TwoPhase {
-    int32_t shift;              // column blocks of 2^shift columns
+    int32_t shift;              // column blocks of 2^shift columns (of 2^shift groups' columns when group == 8)
+    int32_t group;              // 1, or 8: a slot stands for a group of eight entries (group-aligned matrix)
     int32_t num_pieces;         // multiply pass: workgroups
     int32_t num_chunks;         // reduce pass: merge-path chunks
     size_t reduce_lds;          // two_phase_reduce_lds() of the largest chunk
@@ -169,11 +170,17 @@ int64_t two_phase_scan_blocks(int64_t count);
 hipError_t launch_two_phase_tables(const MatrixView& A, int shift, int32_t C, int32_t P, const int32_t* chunk_desc,
                                    const TwoPhaseTables& w, int32_t* chunk_g, hipStream_t st);
 // Fills the padding and places every entry (CSR order kept inside a tile).
+// group == 8: A is the matrix of groups (its colidx the groups' columns) and no value is placed.
 hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int32_t P, const TwoPhaseTables& w,
-                                  const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val, int32_t* tp_src,
-                                  int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st);
-// tp_val[s] = vals[tp_src[s]] wherever tp_src[s] >= 0.
-hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, hipStream_t st);
+                                  const int32_t* chunk_desc, int64_t slots, int group, uint16_t* tp_col, void* tp_val,
+                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st);
+// tp_val[s] = vals[tp_src[s]] wherever tp_src[s] >= 0; group == 8: A is the caller's matrix, a slot holds the eight values of
+// group tp_src[s].
+hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, int group,
+                                   hipStream_t st);
+// gcol[g] = colidx[8g] / 8; *flag (cleared by the caller) is set when some group of eight entries is not an aligned run
+// of eight consecutive columns.
+hipError_t launch_two_phase_groups(const int32_t* colidx, int32_t ngroups, int32_t* gcol, int32_t* flag, hipStream_t st);
 
 // The sliced ELL plan.  slice_ptr[ns+1]: slots before each slice of kSellHeight rows (a slice takes width * kSellHeight
 // slots, stored column by column).  fill: column, source position and value of every slot (-1, -1, 0 for padding).

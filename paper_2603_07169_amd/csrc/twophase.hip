@@ -117,6 +117,92 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
     }
 }
 
+// The multiply pass on a group-aligned matrix: a slot stands for a group of eight entries, its "column" is the number of
+// the aligned run of eight x values within the block, its value eight stored numbers; the product written is the dot
+// product of the two.  The block of x in LDS: 2^shift runs of eight (64 KB: bf16 runs as they are stored, binary32 runs as
+// two vectors of four), then one run of zeros for the padding slots.
+__device__ __forceinline__ float dot8(const u32x4 v, const u32x4 xv) {  // eight bf16 pairs
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        acc += __uint_as_float(v[j] << 16) * __uint_as_float(xv[j] << 16);
+        acc += __uint_as_float(v[j] & 0xFFFF0000u) * __uint_as_float(xv[j] & 0xFFFF0000u);
+    }
+    return acc;
+}
+__device__ __forceinline__ float dot8(const f32x4 v0, const f32x4 v1, const f32x4 x0, const f32x4 x1) {
+    float acc = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc += v0[j] * x0[j];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc += v1[j] * x1[j];
+    return acc;
+}
+
+template <typename T>
+__global__ __launch_bounds__(kTpMulWG) void tp_multiply_group_kernel(const int32_t* __restrict__ piece_c,
+                                                                     const int32_t* __restrict__ piece_g,
+                                                                     const uint16_t* __restrict__ tp_col,
+                                                                     const typename T::elem* __restrict__ tp_val,
+                                                                     const int32_t* __restrict__ tp_dst,
+                                                                     const typename T::elem* __restrict__ x, int n, int shift,
+                                                                     float* __restrict__ prod) {
+    using E = typename T::elem;
+    constexpr int VPR = sizeof(E) == 2 ? 1 : 2;  // 16-byte vectors per run of eight
+    extern __shared__ __align__(16) u32x4 xs_raw[];  // (2^shift + 1) * VPR vectors
+    const int tid = threadIdx.x;
+    const int piece = xcd_remap(blockIdx.x, gridDim.x);
+    const int c = piece_c[piece];
+    const int g0 = piece_g[piece], g1 = piece_g[piece + 1];
+    const int runs = 1 << shift;
+    const int64_t first = (static_cast<int64_t>(c) << shift) * 8;  // first column of the block
+    // the block of x: whole aligned runs where x allows 16-byte loads and the run lies inside the matrix
+    const bool x_vec = reinterpret_cast<uintptr_t>(x) % 16 == 0;
+    for (int r = tid; r <= runs; r += kTpMulWG) {
+        const int64_t col = first + 8 * static_cast<int64_t>(r);
+        if (r < runs && x_vec && col + 8 <= n) {
+#pragma unroll
+            for (int v = 0; v < VPR; ++v) xs_raw[r * VPR + v] = *reinterpret_cast<const u32x4*>(x + col + (8 / VPR) * v);
+        } else {
+            E tmp[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) tmp[e] = (r < runs && col + e < n) ? x[col + e] : E(0);
+#pragma unroll
+            for (int v = 0; v < VPR; ++v) xs_raw[r * VPR + v] = *reinterpret_cast<const u32x4*>(tmp + (8 / VPR) * v);
+        }
+    }
+    __syncthreads();
+    // One slot per lane and trip, U trips in flight: neighbouring lanes read neighbouring 16-byte (32-byte) value runs, and
+    // the four products of a group of slots leave from four neighbouring lanes.
+    constexpr int U = 2;
+    const u32x4* vals = reinterpret_cast<const u32x4*>(tp_val);
+    const int s0 = 4 * g0, s1 = 4 * g1;
+    for (int sb = s0 + tid; sb < s1; sb += U * kTpMulWG) {
+        u32x4 v[U][VPR];
+        int cc[U], d[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {  // past the end: the piece's last slot again, not stored
+            const int sl = sb + u * kTpMulWG < s1 ? sb + u * kTpMulWG : s1 - 1;
+#pragma unroll
+            for (int i = 0; i < VPR; ++i) v[u][i] = __builtin_nontemporal_load(vals + static_cast<int64_t>(sl) * VPR + i);
+            cc[u] = __builtin_nontemporal_load(tp_col + sl);
+            d[u] = __builtin_nontemporal_load(tp_dst + (sl >> 2));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int sl = sb + u * kTpMulWG;
+            float p;
+            if constexpr (VPR == 1) {
+                p = dot8(v[u][0], xs_raw[cc[u]]);
+            } else {
+                p = dot8(__builtin_bit_cast(f32x4, v[u][0]), __builtin_bit_cast(f32x4, v[u][1]),
+                         __builtin_bit_cast(f32x4, xs_raw[2 * cc[u]]), __builtin_bit_cast(f32x4, xs_raw[2 * cc[u] + 1]));
+            }
+            if (sl < s1) prod[4 * static_cast<int64_t>(d[u]) + (sl & 3)] = p;
+        }
+    }
+}
+
 struct TpReduceArgs {
     const int32_t* chunk_desc;  // [2*(P+1)] pairs (rows finished, entries taken) at each split
     const int32_t* chunk_g;     // [P+1] first group of each chunk's stretch of tp_pos / prod
@@ -127,6 +213,7 @@ struct TpReduceArgs {
     int32_t* carry_row;
     float* carry_val;
     int32_t nparts;
+    int32_t row_shift;  // 0, or 3 when a slot stands for a group of eight entries: rowptr is then counted in groups
     float alpha, beta;
 };
 
@@ -155,7 +242,7 @@ __global__ __launch_bounds__(WG) void tp_reduce_kernel(const TpReduceArgs a) {
         v = v > k1 ? k1 : v;
         return v - k0;
     };
-    for (int i = tid; i <= nr; i += WG) seg[i] = bound(a.rowptr[r0 + i]);
+    for (int i = tid; i <= nr; i += WG) seg[i] = bound(a.rowptr[r0 + i] >> a.row_shift);
     if (tid == 0) {
         seg[nseg] = ent;
         n_deferred = 0;
@@ -329,7 +416,7 @@ struct TpPlaceArgs {
     const int32_t* chunk_desc;
     const int32_t* colidx;
     const void* vals;
-    int32_t C, P, shift, elem_bytes;
+    int32_t C, P, shift, elem_bytes;  // elem_bytes 0: a slot stands for a group of entries, no value is placed here
     int32_t span_cap;  // min(C, kTpBinSpan): the LDS tables' size
     uint16_t* tp_col;
     void* tp_val;
@@ -384,7 +471,7 @@ __global__ __launch_bounds__(kWG) void tp_place_kernel(const TpPlaceArgs a) {
             k = k < k1 ? k : k1 - 1;
             cols[r] = a.colidx[k];
             if (a.elem_bytes == 4) vbits[r] = static_cast<const uint32_t*>(a.vals)[k];
-            else vbits[r] = static_cast<const uint16_t*>(a.vals)[k];
+            else if (a.elem_bytes == 2) vbits[r] = static_cast<const uint16_t*>(a.vals)[k];  // 0: the values are placed by a pass of their own
         }
     }
 
@@ -472,12 +559,38 @@ __global__ __launch_bounds__(kWG) void tp_place_kernel(const TpPlaceArgs a) {
             const int s2 = tile2[b] + i;
             a.tp_col[s1] = scol[i];
             if (a.elem_bytes == 4) static_cast<uint32_t*>(a.tp_val)[s1] = sval[i];
-            else static_cast<uint16_t*>(a.tp_val)[s1] = static_cast<uint16_t>(sval[i]);
+            else if (a.elem_bytes == 2) static_cast<uint16_t*>(a.tp_val)[s1] = static_cast<uint16_t>(sval[i]);
             a.tp_src[s1] = k0 + spos[i];
             a.tp_pos[s2] = spos[i];
             if ((o & 3) == 0) a.tp_dst[s1 >> 2] = s2 >> 2;
         }
         __syncthreads();
+    }
+}
+
+// Group-aligned?  gcol[g] = colidx[8g] / 8 for every group of eight entries; *flag is set when a group does not start
+// at a multiple of eight columns or its columns are not eight consecutive numbers.
+__global__ __launch_bounds__(kWG) void tp_groups_kernel(const int32_t* __restrict__ colidx, int ngroups, int32_t* __restrict__ gcol,
+                                                        int32_t* flag) {
+    bool bad = false;
+    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; g < ngroups; g += static_cast<int64_t>(gridDim.x) * kWG) {
+        const int32_t* c = colidx + 8 * g;
+        const int c0 = c[0];
+        bad = bad || (c0 & 7) != 0;
+#pragma unroll
+        for (int i = 1; i < 8; ++i) bad = bad || c[i] != c0 + i;
+        gcol[g] = c0 >> 3;
+    }
+    if (__builtin_amdgcn_ballot_w64(bad) != 0 && (threadIdx.x & 63) == 0) *flag = 1;  // plain store: every writer writes 1
+}
+
+// tp_val[8s + e] = vals[8 tp_src[s] + e] for the slots that hold a group (tp_src[s] >= 0).
+template <typename E>
+__global__ __launch_bounds__(kWG) void tp_group_values_kernel(const E* __restrict__ vals, const int32_t* __restrict__ tp_src,
+                                                              E* __restrict__ tp_val, int64_t slots, int ngroups) {
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kWG + threadIdx.x; i < 8 * slots; i += static_cast<int64_t>(gridDim.x) * kWG) {
+        const int g = tp_src[i >> 3];
+        if (g >= 0 && g < ngroups) tp_val[i] = vals[8 * static_cast<int64_t>(g) + (i & 7)];
     }
 }
 
@@ -516,9 +629,27 @@ size_t two_phase_reduce_lds(int32_t entries, int32_t rows) {
 }
 
 hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* x, float* y, Scalars s, hipStream_t st) {
-    const size_t lds1 = sizeof(float) * ((size_t{1} << t.shift) + 4);
     hipError_t e;
-    if (t.num_pieces > 0) {
+    if (t.num_pieces > 0 && t.group == 8) {
+        // a slot is a group of eight entries: the block of x as 2^shift aligned runs of eight, and one run of zeros
+        const size_t lds1 = (A.bf16 ? 16 : 32) * ((size_t{1} << t.shift) + 1);
+        if (A.bf16) {
+            auto k = tp_multiply_group_kernel<BF16>;
+            static thread_local size_t allowed = 0;
+            if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
+            hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
+                               static_cast<const uint16_t*>(t.tp_val), t.tp_dst, static_cast<const uint16_t*>(x), A.n, t.shift,
+                               t.prod);
+        } else {
+            auto k = tp_multiply_group_kernel<F32>;
+            static thread_local size_t allowed = 0;
+            if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
+            hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
+                               static_cast<const float*>(t.tp_val), t.tp_dst, static_cast<const float*>(x), A.n, t.shift, t.prod);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else if (t.num_pieces > 0) {
+        const size_t lds1 = sizeof(float) * ((size_t{1} << t.shift) + 4);
         if (A.bf16) {
             auto k = tp_multiply_kernel<BF16, kTpMulGroups>;
             static thread_local size_t allowed = 0;
@@ -536,13 +667,19 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const TpReduceArgs a{t.chunk_desc, t.chunk_g, t.tp_pos, t.prod, A.rowptr, y, t.carry_row, t.carry_val, t.num_chunks,
-                         s.alpha,      s.beta};
+                         t.group == 8 ? 3 : 0, s.alpha, s.beta};
     auto k = tp_reduce_kernel<kTpRedWG, kTpRedGroups>;
     static thread_local size_t allowed = 0;
     if ((e = allow_lds(k, t.reduce_lds, &allowed)) != hipSuccess) return e;
     hipLaunchKernelGGL(k, dim3(t.num_chunks), dim3(kTpRedWG), t.reduce_lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     return launch_merge_fixup(t.carry_row, t.carry_val, t.num_chunks, y, s.alpha, st);
+}
+
+hipError_t launch_two_phase_groups(const int32_t* colidx, int32_t ngroups, int32_t* gcol, int32_t* flag, hipStream_t st) {
+    if (ngroups <= 0) return hipSuccess;
+    hipLaunchKernelGGL(tp_groups_kernel, dim3(capped_grid(ngroups)), dim3(kWG), 0, st, colidx, ngroups, gcol, flag);
+    return hipGetLastError();
 }
 
 int64_t two_phase_scan_blocks(int64_t count) { return (count + kTpScanBlock - 1) / kTpScanBlock; }
@@ -574,19 +711,20 @@ hipError_t launch_two_phase_tables(const MatrixView& A, int shift, int32_t C, in
 }
 
 hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int32_t P, const TwoPhaseTables& w,
-                                  const int32_t* chunk_desc, int64_t slots, uint16_t* tp_col, void* tp_val, int32_t* tp_src,
-                                  int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
+                                  const int32_t* chunk_desc, int64_t slots, int group, uint16_t* tp_col, void* tp_val,
+                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
     // padding first: column = the zero slot after the x block, value 0, no source, position "dropped"
     hipLaunchKernelGGL(tp_fill16_kernel, dim3(capped_grid(slots)), dim3(kWG), 0, st, tp_col, slots,
                        static_cast<uint16_t>(1u << shift));
     hipLaunchKernelGGL(tp_fill16_kernel, dim3(capped_grid(slots)), dim3(kWG), 0, st, tp_pos, slots, static_cast<uint16_t>(0xFFFF));
-    hipError_t e = hipMemsetAsync(tp_val, 0, static_cast<size_t>(slots) * (A.bf16 ? 2 : 4), st);
+    hipError_t e = hipMemsetAsync(tp_val, 0, static_cast<size_t>(slots) * group * (A.bf16 ? 2 : 4), st);
     if (e != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_src, 0xFF, static_cast<size_t>(slots) * 4, st)) != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_dst, 0, static_cast<size_t>(slots), st)) != hipSuccess) return e;
     const int span_cap = C < kTpBinSpan ? C : kTpBinSpan;
+    // group > 1: A is the matrix of groups (colidx = the groups' columns); the values follow in a pass of their own
     const TpPlaceArgs a{w.base1, w.within, w.chunk_first, chunk_desc, A.colidx, A.vals, C,      P,     shift,
-                        A.bf16 ? 2 : 4, span_cap, tp_col,    tp_val,     tp_src,   tp_dst, tp_pos};
+                        group > 1 ? 0 : (A.bf16 ? 2 : 4), span_cap, tp_col, tp_val, tp_src, tp_dst, tp_pos};
     const size_t lds = sizeof(int) * (static_cast<size_t>(kWG / 64 + 2) * span_cap + ((span_cap + 4) & ~3)) +
                        static_cast<size_t>(kTwoPhaseItems) * (sizeof(uint32_t) + 3 * sizeof(uint16_t));
     static thread_local size_t allowed = 0;
@@ -595,8 +733,19 @@ hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int
     return hipGetLastError();
 }
 
-hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, hipStream_t st) {
+hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, int group,
+                                   hipStream_t st) {
     if (slots <= 0) return hipSuccess;
+    if (group == 8) {
+        const int ngroups = A.nnz / 8;
+        if (A.bf16)
+            hipLaunchKernelGGL(tp_group_values_kernel<uint16_t>, dim3(capped_grid(8 * slots)), dim3(kWG), 0, st,
+                               static_cast<const uint16_t*>(A.vals), tp_src, static_cast<uint16_t*>(tp_val), slots, ngroups);
+        else
+            hipLaunchKernelGGL(tp_group_values_kernel<float>, dim3(capped_grid(8 * slots)), dim3(kWG), 0, st,
+                               static_cast<const float*>(A.vals), tp_src, static_cast<float*>(tp_val), slots, ngroups);
+        return hipGetLastError();
+    }
     if (A.bf16)
         hipLaunchKernelGGL(tp_values_kernel<uint16_t>, dim3(capped_grid(slots)), dim3(kWG), 0, st,
                            static_cast<const uint16_t*>(A.vals), tp_src, static_cast<uint16_t*>(tp_val), static_cast<int>(slots));

@@ -45,6 +45,7 @@ def test_full_config_matches_oracle(k):
     cnt, off, rows = oracle.row_bins(p.rowptr)
     assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_rows"], rows)
     if plan == "twophase":
+        assert A.info.tp_group == 1
         # the two-pass regrouping, bit for bit
         L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
         assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
@@ -94,6 +95,21 @@ def test_full_config_matches_oracle(k):
         # the tile kernel (global x gathers) on the same matrix, which AUTO no longer picks here
         A = d.matrix(dict(plan=s.SPMV_PLAN_ADAPTIVE))
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full adaptive")
+        if k == 5:
+            # group-aligned: a forced two-pass plan works on the 16 M groups of eight entries; the regrouping of the matrix of
+            # groups bit for bit, and the product
+            A.close()
+            A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
+            assert A.info.plan == s.SPMV_PLAN_TWOPHASE and A.info.tp_group == 8 and oracle.csr_groups(p.m, p.rowptr, p.colidx) == 1
+            assert s.spmv_csr_main_kernel_name(A.handle) == "tp_multiply_group_kernel"
+            rg, cg = oracle.group_matrix(p.m, p.rowptr, p.colidx)
+            L = oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype])
+            assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
+            got = A.analysis()
+            for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos"):
+                assert np.array_equal(got[name], L[name]), name
+            del L, rg, cg
+            assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full two-pass on groups")
     A.close()
     if k != 4:
         # the sliced ELL plan (forced; AUTO never picks it) on the near-uniform configs: product, and on the Laplacian the copy itself

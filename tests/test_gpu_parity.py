@@ -519,6 +519,69 @@ def test_sell_does_not_carry_nan_from_x0_into_padded_rows():
     A.close()
 
 
+def group_layout(p):
+    """The two-pass layout of the matrix of groups (what a group-aligned matrix is laid out as)."""
+    rg, cg = oracle.group_matrix(p.m, p.rowptr, p.colidx)
+    return oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype])
+
+
+@pytest.mark.parametrize("dtype,m,n,offset", [("bf16", 20_000, 300_000, 0), ("f32", 9_000, 70_000, 0), ("bf16", 3_000, 40_004, 1),
+                                                ("f32", 700, 16_390, 1), ("bf16", 1, 64, 0)])
+def test_two_phase_on_groups_layout_equals_oracle_and_multiplies(dtype, m, n, offset):
+    """A forced TWOPHASE plan on a group-aligned matrix works on groups of eight entries: the layout read back is the
+    oracle's two-pass layout of the matrix of groups, bit for bit; the product is within tolerance and the same on every
+    run; x may start off a 16-byte boundary and n need not be a multiple of eight; values refreshed in place are picked up."""
+    p = w.block_clustered(m=m, n=n, blocks_per_row=min(16, n // 8), dtype=dtype, alpha=-1.25, beta=0.5)
+    p.y0 = np.random.default_rng(3).standard_normal(p.m).astype(np.float32)
+    assert oracle.csr_groups(p.m, p.rowptr, p.colidx) == 1
+    log("case two-phase on groups", dtype, m, n, p.nnz)
+    d = DeviceProblem(p, offset_elems=offset)
+    A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
+    info = A.info
+    assert info.plan == s.SPMV_PLAN_TWOPHASE and info.tp_group == 8 and info.tp_col_shift == oracle.TP_GROUP_SHIFT[dtype]
+    assert s.spmv_csr_main_kernel_name(A.handle) == "tp_multiply_group_kernel"
+    L = group_layout(p)
+    assert (info.tp_num_col_blocks, info.tp_num_chunks, info.tp_slots, info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
+    got = A.analysis()
+    for k in TP_ARRAYS:
+        assert np.array_equal(got[k], L[k]), k
+    y_ref, S_ref = reference(p)
+    y = d.run(A)
+    assert_close(p, y, y_ref, S_ref, p.alpha, p.beta)
+    assert np.array_equal(d.run(A), y)
+    new_vals = np.random.default_rng(9).permutation(p.vals)
+    d.vals.copy_(to_dev(new_vals))
+    A.refresh_values()
+    q = w.CsrProblem(p.name, p.dtype, p.m, p.n, p.rowptr, p.colidx, new_vals, p.x, p.y0, p.alpha, p.beta)
+    y2_ref, S2_ref = reference(q)
+    assert_close(q, d.run(A), y2_ref, S2_ref, p.alpha, p.beta, what="after refresh")
+    A.close()
+
+
+def test_two_phase_stays_on_entries_when_a_group_is_broken():
+    """One column moved inside one group, or a row that starts inside a group: the matrix is no longer group-aligned and a
+    forced TWOPHASE plan lays out entries as before."""
+    p = w.block_clustered(m=2_000, n=100_000, dtype="bf16")
+    for which in ("column", "row"):
+        colidx, rowptr = p.colidx.copy(), p.rowptr.copy()
+        if which == "column":
+            colidx[8 * 777 + 3] += 8                                          # still ascending inside the row, no longer consecutive
+        else:
+            rowptr[5] += 4
+        assert oracle.csr_groups(p.m, rowptr, colidx) == 0
+        q = w.CsrProblem("broken_" + which, p.dtype, p.m, p.n, rowptr, colidx, p.vals, p.x, None, 1.0, 0.0)
+        d = DeviceProblem(q)
+        A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
+        assert A.info.plan == s.SPMV_PLAN_TWOPHASE and A.info.tp_group == 1
+        L = oracle.two_phase_layout(q.m, q.n, q.rowptr, q.colidx)
+        got = A.analysis()
+        for k in TP_ARRAYS:
+            assert np.array_equal(got[k], L[k]), k
+        y_ref, S_ref = reference(q)
+        assert_close(q, d.run(A), y_ref, S_ref, 1.0, 0.0, strict=True)
+        A.close()
+
+
 def test_forced_two_phase_rejects_too_many_column_blocks():
     n = 65536 * (1 << oracle.TP_SHIFT) + 1                              # 65537 column blocks
     rowptr, colidx, vals = to_dev(np.array([0, 2], np.int32)), to_dev(np.array([0, n - 1], np.int32)), to_dev(np.ones(2, np.float32))

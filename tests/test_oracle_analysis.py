@@ -655,27 +655,3 @@ def test_csr_groups_on_the_generators():
     assert np.array_equal(rg, p.rowptr // 8) and np.array_equal(np.repeat(cg, 8) * 8 + np.tile(np.arange(8), cg.size), p.colidx)
     for q in (w.uniform_rows(64, 64, 8), w.laplace2d(16), w.from_row_lengths(np.full(10, 8), 100, seed=1)):
         assert oracle.csr_groups(q.m, q.rowptr, q.colidx) == 0
-
-
-def test_grouped_two_phase_choice_boundaries():
-    """Config 5 (1 M rows and columns, 16 M groups, bf16: x of 2.0 MB, 31 column blocks of 4096 groups, 2076 chunks) is
-    taken; each condition is then moved across its threshold, the figures worked by hand."""
-    m = n = 1_000_000
-    nnz = 128_000_000
-    E = nnz                                                               # all entries counted
-    yes = lambda **k: oracle.grouped_two_phase_choice(**{**dict(m=m, n=n, nnz=nnz, dtype="bf16", windowed_grouped=1, group_aligned=1,
-                                                              vectors=15_970_000, entries=E), **k})
-    assert yes() == 1
-    assert yes(windowed_grouped=0) == 0 and yes(group_aligned=0) == 0
-    assert yes(vectors=-1) == 0
-    assert yes(vectors=12_000_000) == 1 and yes(vectors=11_999_999) == 0   # 4 * 8 * v >= 3 * E  <=>  v >= 12 000 000
-    assert yes(dtype="f32", vectors=24_000_000) == 1 and yes(dtype="f32", vectors=23_999_999) == 0   # vectors of four
-    assert yes(n=524_288) == 1 and yes(n=524_287) == 0                    # x of exactly 1 MiB in bf16
-    assert yes(dtype="f32", n=262_144, vectors=24_000_000) == 1 and yes(dtype="f32", n=262_143, vectors=24_000_000) == 0
-    ng = 3 * 2 ** 21                                                       # 6 291 456 groups
-    assert yes(nnz=8 * ng, entries=8 * ng, vectors=ng) == 1 and yes(nnz=8 * ng - 8, entries=8 * ng - 8, vectors=ng) == 0
-    # tiles of eight groups: C = ceil(ceil(n / 8) / 4096), P = ceil((m + ng) / 8192); n = 64 M columns -> C = 1954,
-    # m = 1 M, ng = 16 M -> P = 2076: C * P = 4 056 504 tiles, 8 * that = 32 452 032 > 16 M groups
-    assert yes(n=64_000_000) == 0
-    # n = 32 M -> C = 977: 8 * 977 * 2076 = 16 226 016 > 16 000 000; n = 31 M -> C = 947: 8 * 947 * 2076 = 15 727 776 <= 16 M
-    assert yes(n=32_000_000) == 0 and yes(n=31_000_000) == 1

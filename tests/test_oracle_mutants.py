@@ -112,9 +112,6 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (c % width != 0) return 0;", ";", "group-aligned: a group may start anywhere"),
     ("analysis_oracle.cpp", "for (int64_t i = 1; i < width; ++i)\n            if (colidx[width * g + i] != c + i) return 0;", "for (int64_t i = 1; i + 1 < width; ++i)\n            if (colidx[width * g + i] != c + i) return 0;", "group-aligned: last column of a group not checked"),
     ("analysis_oracle.cpp", "if (rowptr[i] % width != 0) return 0;", ";", "group-aligned: rows may start inside a group"),
-    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vec_elems * vectors < 3 * entries) return 0;", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;", "two-pass on groups: scatter measured per entry"),
-    ("analysis_oracle.cpp", "n * elem_bytes >= (int64_t{1} << 20) && ng >= 3", "n * elem_bytes > (int64_t{1} << 20) && ng >= 3", "two-pass on groups: x threshold off by one"),
-    ("analysis_oracle.cpp", "C * P <= (int64_t{1} << 24) &&\n            8 * C * P <= ng)", "C * P <= (int64_t{1} << 24) &&\n            8 * C * P <= nnz)", "two-pass on groups: tiles measured in entries"),
 ]
 
 
