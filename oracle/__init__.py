@@ -394,7 +394,7 @@ def column_block_choice(n, nnz, dtype, plan, vectors, entries):
 
 def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece_groups=TP_PIECE_GROUPS):
     """The two-pass plan's regrouping: dict with C, P, S, Q and the arrays tp_row, tp_nz, tp_piece_c, tp_piece_g,
-    tp_chunk_g, tp_col, tp_src, tp_dst, tp_pos."""
+    tp_chunk_g, tp_col, tp_src, tp_from, tp_pos."""
     lib = _load()
     _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
     sizes = [C.c_int64() for _ in range(4)]
@@ -402,7 +402,7 @@ def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece
     S, Q, P, Cn = (int(v.value) for v in sizes)
     out = dict(tp_row=np.zeros(P + 1, np.int32), tp_nz=np.zeros(P + 1, np.int32), tp_piece_c=np.zeros(Q, np.int32),
                tp_piece_g=np.zeros(Q + 1, np.int32), tp_chunk_g=np.zeros(P + 1, np.int32), tp_col=np.zeros(S, np.uint16),
-               tp_src=np.zeros(S, np.int32), tp_dst=np.zeros(S // 4, np.int32), tp_pos=np.zeros(S, np.uint16))
+               tp_src=np.zeros(S, np.int32), tp_from=np.zeros(S // 4, np.int32), tp_pos=np.zeros(S, np.uint16))
     lib.oracle_two_phase_layout(m, n, _p(rowptr), _p(colidx), shift, items, piece_groups, *[_p(v) for v in out.values()])
     out.update(C=Cn, P=P, S=S, Q=Q)
     return out

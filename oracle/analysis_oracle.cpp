@@ -385,10 +385,12 @@ void oracle_two_phase_sizes(int64_t m, int64_t n, const int32_t* rowptr, const i
     *C_out = C;
 }
 
-// Fills tp_row[P+1], tp_nz[P+1], piece_c[Q], piece_g[Q+1], chunk_g[P+1], col[S], src[S], dst[S/4], pos[S].
+// Fills tp_row[P+1], tp_nz[P+1], piece_c[Q], piece_g[Q+1], chunk_g[P+1], col[S], src[S], from[S/4], pos[S].
+// from[g] = the group of the multiply order whose four slots are group g of the reduce order (the products stay where
+// the multiply pass made them; the reduce pass fetches them).
 void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int32_t shift, int32_t items,
                              int32_t piece_groups, int32_t* tp_row, int32_t* tp_nz, int32_t* piece_c, int32_t* piece_g,
-                             int32_t* chunk_g, uint16_t* col, int32_t* src, int32_t* dst, uint16_t* pos) {
+                             int32_t* chunk_g, uint16_t* col, int32_t* src, int32_t* from, uint16_t* pos) {
     const int64_t nnz = rowptr[m];
     const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
     const int64_t P = oracle_merge_path(m, nnz, rowptr, items, tp_row, tp_nz);
@@ -445,7 +447,7 @@ void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const 
         col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));
         src[s1] = static_cast<int32_t>(k);
         pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);
-        if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s2 / 4);
+        if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s1 / 4);
     }
 }
 

@@ -49,7 +49,7 @@ def test_full_config_matches_oracle(k):
         # the two-pass regrouping, bit for bit
         L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
         assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
-        for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos"):
+        for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):
             assert np.array_equal(got[name], L[name]), name
         del L
         A.close()
@@ -106,7 +106,7 @@ def test_full_config_matches_oracle(k):
             L = oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype])
             assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
             got = A.analysis()
-            for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos"):
+            for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):
                 assert np.array_equal(got[name], L[name]), name
             del L, rg, cg
             assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full two-pass on groups")

@@ -78,7 +78,7 @@ def test_two_pass_plan_on_many_scattered_entries(log2_rows):
     L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
     assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
     got = A.analysis()
-    for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos"):
+    for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):
         assert np.array_equal(got[name], L[name]), name
     del got, L
     y_ref, S_ref = reference(p)

@@ -362,7 +362,7 @@ def test_column_blocks_equal_oracle_and_multiply(dtype, n):
     A.close()
 
 
-TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos")
+TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos")
 
 
 @pytest.mark.parametrize("dtype,n", [("f32", 100_000), ("bf16", 70_001), ("f32", 4000)])

@@ -319,7 +319,7 @@ def test_lidx_grouped_handworked():
 
 
 # ------------------------------------------------------------------ the two-pass layout
-TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_dst", "tp_pos")
+TP_ARRAYS = ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos")
 
 
 # ---- row patterns of the window positions --------------------------------------------------
@@ -455,7 +455,7 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
         mp_row, mp_nz = oracle.merge_path(p.rowptr, items)
         assert np.array_equal(L["tp_row"], mp_row) and np.array_equal(L["tp_nz"], mp_nz)
         assert C == -(-p.n // (1 << shift)) and S % 4 == 0 and S >= p.nnz
-        src, col, pos, dst = L["tp_src"], L["tp_col"], L["tp_pos"], L["tp_dst"]
+        src, col, pos, frm = L["tp_src"], L["tp_col"], L["tp_pos"], L["tp_from"]
         real = src >= 0
         assert np.array_equal(np.sort(src[real]), np.arange(p.nnz))                       # every entry exactly once
         assert np.all(col[~real] == (1 << shift)) and np.all(col[real] < (1 << shift))
@@ -488,16 +488,14 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
         full = r4.all(axis=1)
         assert np.all(full[:-1] | (k4[:-1, 0] != k4[1:, 0]))                               # a padded group is its tile's last
         # reduce order: group for group the same entries, at their position within the chunk
-        assert np.array_equal(np.sort(dst), np.arange(S // 4))
+        assert np.array_equal(np.sort(frm), np.arange(S // 4))                             # every group fetched exactly once
         pos4, src4 = pos.reshape(-1, 4), src.reshape(-1, 4)
-        moved = np.full((S // 4, 4), -1, np.int64)
-        moved[dst] = src4                                                                  # CSR position of every reduce-order slot
+        moved = src4[frm].astype(np.int64)                                                 # CSR position of every reduce-order slot
         chunk_of_group = np.searchsorted(L["tp_chunk_g"], np.arange(S // 4), side="right") - 1
         assert L["tp_chunk_g"][0] == 0 and L["tp_chunk_g"][-1] == S // 4
         want_pos = np.where(moved >= 0, moved - mp_nz[chunk_of_group][:, None], 0xFFFF)
         assert np.array_equal(pos4, want_pos)
-        moved_c = np.full(S // 4, -1, np.int64)
-        moved_c[dst] = cblk.reshape(-1, 4)[:, 0] if S else 0
+        moved_c = cblk.reshape(-1, 4)[:, 0][frm].astype(np.int64) if S else np.zeros(0, np.int64)
         same_chunk = np.diff(chunk_of_group) == 0
         assert np.all(np.diff(moved_c)[same_chunk] >= 0)                                   # inside a chunk: by column block
         # the product taken through the layout is the product
@@ -505,8 +503,7 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
         a = rng.uniform(-1, 1, p.nnz)
         xs = np.concatenate((x, np.zeros(2 << shift)))
         prod1 = np.where(real, np.where(real, a[np.maximum(src, 0)], 0.0) * xs[np.where(real, cblk.astype(np.int64) * (1 << shift) + col, p.n)], 0.0)
-        prod2 = np.zeros((S // 4, 4))
-        prod2[dst] = prod1.reshape(-1, 4)
+        prod2 = prod1.reshape(-1, 4)[frm]                                                  # the reduce pass fetches group by group
         lds = np.zeros(p.nnz + 1)
         sel = pos4 != 0xFFFF
         lds[(mp_nz[chunk_of_group][:, None] + pos4)[sel]] = prod2[sel]

@@ -57,7 +57,8 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (4 * vectors < 3 * entries) return 0;  // clustered", "column block rule: uncounted windows taken for scattered"),
     ("analysis_oracle.cpp", "col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));", "col[s1] = static_cast<uint16_t>(colidx[k]);", "two-pass: column not made relative to its block"),
     ("analysis_oracle.cpp", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp] + 1);", "two-pass: position in the chunk off by one"),
-    ("analysis_oracle.cpp", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s2 / 4);", "if (o % 4 == 0) dst[s1 / 4] = static_cast<int32_t>(s1 / 4);", "two-pass: products left in the multiply order"),
+    ("analysis_oracle.cpp", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s1 / 4);", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s2 / 4);", "two-pass: products fetched as if they lay in the reduce order"),
+    ("analysis_oracle.cpp", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s1 / 4);", "if (o % 4 == 0) from[s1 / 4] = static_cast<int32_t>(s2 / 4);", "two-pass: the map of groups taken the other way round"),
     ("analysis_oracle.cpp", "start2[static_cast<size_t>(c * P + pp)] = slot;\n            slot += (cnt[static_cast<size_t>(c * P + pp)] + 3) / 4 * 4;", "start2[static_cast<size_t>(c * P + pp)] = slot;\n            slot += cnt[static_cast<size_t>(c * P + pp)];", "two-pass: reduce order not padded"),
     ("analysis_oracle.cpp", "while (tp_nz[p + 1] <= k) ++p;", "while (tp_nz[p + 1] < k) ++p;", "two-pass: an entry on a split goes to the chunk before"),
     ("analysis_oracle.cpp", "block_first_group + i * ((groups + pieces - 1) / pieces)", "block_first_group + i * piece_groups", "two-pass: pieces filled to the cap instead of cut evenly"),
