@@ -163,7 +163,7 @@ typedef struct {
     int32_t* tp_chunk_g; /* [P2+1] first group of each chunk in the reduce order      */
     uint16_t* tp_col;    /* [S]    multiply order: column within the block            */
     int32_t* tp_src;     /* [S]    multiply order: position in colidx / vals, -1 pad  */
-    int32_t* tp_dst;     /* [S/4]  reduce-order group fed by each multiply-order group */
+    int32_t* tp_from;    /* [S/4]  reduce order: the multiply-order group that is this group */
     uint16_t* tp_pos;    /* [S]    reduce order: CSR position within the chunk        */
     /* With prepare_spmm only (skipped otherwise): */
     int32_t* spmm_rows;  /* [m]    inside each window of SPMV_SPMM_WINDOW consecutive rows:
@@ -250,14 +250,15 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     p, in CSR order, padded to a multiple of four slots.  The multiply order lists the tiles by
  *     (c, p), the reduce order by (p, c); S slots each.  Per slot of the multiply order: tp_col
  *     (column - c * 2^tp_col_shift; padding: 2^tp_col_shift), tp_src (position k in colidx / vals;
- *     padding: -1) and a copy of the value (padding: 0); per group of four slots tp_dst, the
- *     group's number in the reduce order.  Per slot of the reduce order: tp_pos = k - tp_nz[p]
- *     (padding: 0xFFFF).  Column block c's groups are cut evenly into the fewest pieces of at most
+ *     padding: -1) and a copy of the value (padding: 0).  Per slot of the reduce order: tp_pos =
+ *     k - tp_nz[p] (padding: 0xFFFF); per group of four slots of the reduce order tp_from, the
+ *     number of the same group in the multiply order.  Column block c's groups are cut evenly into the fewest pieces of at most
  *     8192 groups: q = ceil(groups / 8192) pieces of ceil(groups / q), the last one shorter
  *     (tp_piece_c, tp_piece_g; pieces are contiguous, tp_piece_g[Q] = S/4); tp_chunk_g[p] = first
  *     group of chunk p in the reduce order.  run() multiplies piece by piece with the block of x
- *     in LDS and writes the products to a scratch array of S floats owned by the handle (runs of
- *     one handle with this plan must therefore not overlap), then sums chunk by chunk; sums are
+ *     in LDS and writes the products, in the multiply order, to a scratch array of S floats owned
+ *     by the handle (runs of one handle with this plan must therefore not overlap), then sums
+ *     chunk by chunk, fetching every group of the chunk through tp_from; sums are
  *     taken in a fixed order, so results are reproducible bit for bit.  AUTO picks TWOPHASE ahead
  *     of COLBLOCK when 2 n >= W (W as above: x of 2 MiB or more), nnz >= 3 * 2^21, C2 * P2 <= 2^24,
  *     8 * C2 * P2 <= nnz (tiles of eight entries or more on average) and the columns are scattered:

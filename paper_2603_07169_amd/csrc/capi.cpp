@@ -71,7 +71,7 @@ struct spmv_csr_s {
     uint16_t* d_tp_col = nullptr;
     void* d_tp_val = nullptr;
     int32_t* d_tp_src = nullptr;
-    int32_t* d_tp_dst = nullptr;
+    int32_t* d_tp_from = nullptr;
     uint16_t* d_tp_pos = nullptr;
     float* d_tp_prod = nullptr;
     int32_t* d_tp_carry_row = nullptr;
@@ -102,12 +102,12 @@ void free_metadata(spmv_csr_s* h) {
                     h->d_xv_pad,    h->d_block_desc, h->d_chunk_desc, h->d_cb_row, h->d_cb_col,
                     h->d_cb_src,    h->d_cb_vals,   h->d_spmm_rows, h->d_spmm_desc, h->d_spmm_col,
                     h->d_spmm_val,  h->d_tp_desc,   h->d_tp_piece_c, h->d_tp_piece_g, h->d_tp_chunk_g,
-                    h->d_tp_col,    h->d_tp_val,    h->d_tp_src,    h->d_tp_dst,    h->d_tp_pos,
+                    h->d_tp_col,    h->d_tp_val,    h->d_tp_src,    h->d_tp_from,    h->d_tp_pos,
                     h->d_tp_prod,   h->d_tp_carry_row, h->d_tp_carry_val, h->d_lidx8, h->d_run_desc, h->d_pat_pad,
                     h->d_sell_ptr,  h->d_sell_col,  h->d_sell_src,  h->d_sell_val};
     for (void* p : ptrs)
         if (p) (void)hipFree(p);
-    h->d_tp_desc = h->d_tp_piece_c = h->d_tp_piece_g = h->d_tp_chunk_g = h->d_tp_src = h->d_tp_dst = nullptr;
+    h->d_tp_desc = h->d_tp_piece_c = h->d_tp_piece_g = h->d_tp_chunk_g = h->d_tp_src = h->d_tp_from = nullptr;
     h->d_tp_carry_row = nullptr;
     h->d_tp_col = h->d_tp_pos = nullptr;
     h->d_tp_val = nullptr;
@@ -477,7 +477,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
         (hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_col), 2 * S)) ||
          hip_failed(hipMalloc(&h->d_tp_val, static_cast<size_t>(group) * (h->dtype == SPMV_F32 ? 4 : 2) * S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_src), 4 * S)) ||
-         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_dst), S)) ||
+         hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_from), S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_pos), 2 * S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_prod), 4 * S)) ||
          hip_failed(hipMalloc(reinterpret_cast<void**>(&h->d_tp_carry_row), 4 * static_cast<size_t>(P))) ||
@@ -485,7 +485,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
         st = SPMV_ERR_ALLOC;
     if (st == SPMV_OK &&
         (hip_failed(spmv::launch_two_phase_place(A, shift, static_cast<int32_t>(C), static_cast<int32_t>(P), w, h->d_tp_desc,
-                                                 slots, group, h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_dst, h->d_tp_pos,
+                                                 slots, group, h->d_tp_col, h->d_tp_val, h->d_tp_src, h->d_tp_from, h->d_tp_pos,
                                                  nullptr)) ||
          (group > 1 && hip_failed(spmv::launch_two_phase_values(view_of(h), h->d_tp_src, h->d_tp_val, slots, group, nullptr))) ||
          hip_failed(hipDeviceSynchronize())))
@@ -555,7 +555,7 @@ spmv::TwoPhase two_phase_of(const spmv_csr_s* h) {
     t.piece_g = h->d_tp_piece_g;
     t.tp_col = h->d_tp_col;
     t.tp_val = h->d_tp_val;
-    t.tp_dst = h->d_tp_dst;
+    t.tp_from = h->d_tp_from;
     t.tp_pos = h->d_tp_pos;
     t.chunk_desc = h->d_tp_desc;
     t.chunk_g = h->d_tp_chunk_g;
@@ -1006,7 +1006,7 @@ spmv_status_t spmv_csr_get_analysis(spmv_handle_t h, const spmv_analysis_host_t*
                                 {out->tp_piece_g, h->d_tp_piece_g, h->info.tp_num_pieces + 1},
                                 {out->tp_chunk_g, h->d_tp_chunk_g, h->info.tp_num_chunks + 1},
                                 {out->tp_src, h->d_tp_src, h->info.tp_slots},
-                                {out->tp_dst, h->d_tp_dst, h->info.tp_slots / 4}};
+                                {out->tp_from, h->d_tp_from, h->info.tp_slots / 4}};
         for (const Copy& c : tcopies)
             if (c.dst && c.count > 0 &&
                 hip_failed(hipMemcpy(c.dst, c.src, sizeof(int32_t) * static_cast<size_t>(c.count), hipMemcpyDeviceToHost)))

@@ -143,11 +143,11 @@ struct TwoPhase {
     const int32_t* piece_g;     // [num_pieces+1] first group of each piece (pieces are contiguous)
     const uint16_t* tp_col;     // [slots] column within the block; padding: 2^shift
     const void* tp_val;         // [slots] values in the handle's dtype; padding: 0
-    const int32_t* tp_dst;      // [slots/4] group of the reduce order that each group of the multiply order feeds
+    const int32_t* tp_from;     // [slots/4] group of the multiply order that each group of the reduce order is fed by
     const uint16_t* tp_pos;     // [slots] reduce order: CSR position within the chunk; padding: 0xFFFF
     const int32_t* chunk_desc;  // [2*(num_chunks+1)] pairs (rows finished, entries taken)
     const int32_t* chunk_g;     // [num_chunks+1] first group of each chunk in the reduce order
-    float* prod;                // [slots] scratch: the products between the two passes
+    float* prod;                // [slots] scratch: the products between the two passes, in the multiply order
     int32_t* carry_row;         // [num_chunks] scratch
     float* carry_val;           // [num_chunks] scratch
 };
@@ -173,7 +173,7 @@ hipError_t launch_two_phase_tables(const MatrixView& A, int shift, int32_t C, in
 // group == 8: A is the matrix of groups (its colidx the groups' columns) and no value is placed.
 hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int32_t P, const TwoPhaseTables& w,
                                   const int32_t* chunk_desc, int64_t slots, int group, uint16_t* tp_col, void* tp_val,
-                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st);
+                                  int32_t* tp_src, int32_t* tp_from, uint16_t* tp_pos, hipStream_t st);
 // tp_val[s] = vals[tp_src[s]] wherever tp_src[s] >= 0; group == 8: A is the caller's matrix, a slot holds the eight values of
 // group tp_src[s].
 hipError_t launch_two_phase_values(const MatrixView& A, const int32_t* tp_src, void* tp_val, int64_t slots, int group,

@@ -3,18 +3,21 @@
 //
 //   multiply  The entries are kept regrouped by blocks of 2^s columns.  A workgroup copies one
 //             block of x to LDS, streams a piece of that block's entries (16-bit column within the
-//             block, value), takes x out of LDS and writes the products, four at a time, to where
-//             the second pass wants them.
-//   reduce    The products are kept grouped by merge-path chunk (a contiguous stretch of the CSR
-//             entry list plus the rows that end in it).  A workgroup streams its chunk's products,
-//             drops each into LDS at its CSR position within the chunk (16-bit), and then runs the
+//             block, value), takes x out of LDS and writes the products where the entries lie:
+//             every store of the pass is one contiguous run.
+//   reduce    One workgroup per merge-path chunk (a contiguous stretch of the CSR entry list plus
+//             the rows that end in it).  It fetches its chunk's products, four at a time, from
+//             where the first pass left them (a tile's products lie together, and the tiles of
+//             neighbouring chunks are neighbours, so the chunks a die works on at one time share
+//             their cache lines), drops each into LDS at its CSR position within the chunk
+//             (16-bit), and then runs the
 //             row phase of the tile kernels over them: teams of lanes add up one row each, the
 //             piece of a row that the chunk cuts off leaves as a carry.
 //
 // A tile is the set of entries that share a column block and a chunk.  Its entries keep their CSR
 // order, and every tile is padded to a multiple of four entries (value 0, column = the zero slot
 // after the x block, position 0xFFFF = dropped), so that a group of four consecutive slots never
-// straddles two tiles: one 32-bit number per group says where its four products go.
+// straddles two tiles: one 32-bit number per group of the reduce order says which four products it is.
 // The regrouping is done once, at analysis time, on the device (the kernels in the second half).
 #include <cstring>
 
@@ -55,7 +58,6 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
                                                                const int32_t* __restrict__ piece_g,
                                                                const uint16_t* __restrict__ tp_col,
                                                                const typename T::elem* __restrict__ tp_val,
-                                                               const int32_t* __restrict__ tp_dst,
                                                                const typename T::elem* __restrict__ x, int n, int shift,
                                                                float* __restrict__ prod) {
     extern __shared__ __align__(16) float xs[];  // 2^shift x values, then four zeros
@@ -70,14 +72,12 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
     // the piece's first U groups per lane are asked for before the block of x, so that the two overlap
     u16x4 cc[U];
     float v[U][4];
-    int d[U];
     auto fetch = [&](int gb) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {  // past the end: the piece's last group again, not stored
             const int g = gb + u * kTpMulWG < g1 ? gb + u * kTpMulWG : g1 - 1;
             cc[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x4*>(tp_col) + g);
             load_vals4(tp_val, g, v[u]);
-            d[u] = __builtin_nontemporal_load(tp_dst + g);
         }
     };
     if (g0 < g1) fetch(g0 + tid);
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_kernel(const int32_t* __
             f32x4 p;
 #pragma unroll
             for (int i = 0; i < 4; ++i) p[i] = v[u][i] * xs[cc[u][i]];
-            if (gb + u * kTpMulWG < g1) reinterpret_cast<f32x4*>(prod)[d[u]] = p;
+            if (gb + u * kTpMulWG < g1) reinterpret_cast<f32x4*>(prod)[gb + u * kTpMulWG] = p;
         }
     }
 }
@@ -144,7 +144,6 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_group_kernel(const int32
                                                                      const int32_t* __restrict__ piece_g,
                                                                      const uint16_t* __restrict__ tp_col,
                                                                      const typename T::elem* __restrict__ tp_val,
-                                                                     const int32_t* __restrict__ tp_dst,
                                                                      const typename T::elem* __restrict__ x, int n, int shift,
                                                                      float* __restrict__ prod) {
     using E = typename T::elem;
@@ -172,21 +171,20 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_group_kernel(const int32
         }
     }
     __syncthreads();
-    // One slot per lane and trip, U trips in flight: neighbouring lanes read neighbouring 16-byte (32-byte) value runs, and
-    // the four products of a group of slots leave from four neighbouring lanes.
+    // One slot per lane and trip, U trips in flight: neighbouring lanes read neighbouring 16-byte (32-byte) value runs and
+    // write neighbouring products.
     constexpr int U = 2;
     const u32x4* vals = reinterpret_cast<const u32x4*>(tp_val);
     const int s0 = 4 * g0, s1 = 4 * g1;
     for (int sb = s0 + tid; sb < s1; sb += U * kTpMulWG) {
         u32x4 v[U][VPR];
-        int cc[U], d[U];
+        int cc[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {  // past the end: the piece's last slot again, not stored
             const int sl = sb + u * kTpMulWG < s1 ? sb + u * kTpMulWG : s1 - 1;
 #pragma unroll
             for (int i = 0; i < VPR; ++i) v[u][i] = __builtin_nontemporal_load(vals + static_cast<int64_t>(sl) * VPR + i);
             cc[u] = __builtin_nontemporal_load(tp_col + sl);
-            d[u] = __builtin_nontemporal_load(tp_dst + (sl >> 2));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -198,7 +196,7 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_group_kernel(const int32
                 p = dot8(__builtin_bit_cast(f32x4, v[u][0]), __builtin_bit_cast(f32x4, v[u][1]),
                          __builtin_bit_cast(f32x4, xs_raw[2 * cc[u]]), __builtin_bit_cast(f32x4, xs_raw[2 * cc[u] + 1]));
             }
-            if (sl < s1) prod[4 * static_cast<int64_t>(d[u]) + (sl & 3)] = p;
+            if (sl < s1) prod[sl] = p;
         }
     }
 }
@@ -206,6 +204,7 @@ __global__ __launch_bounds__(kTpMulWG) void tp_multiply_group_kernel(const int32
 struct TpReduceArgs {
     const int32_t* chunk_desc;  // [2*(P+1)] pairs (rows finished, entries taken) at each split
     const int32_t* chunk_g;     // [P+1] first group of each chunk's stretch of tp_pos / prod
+    const int32_t* tp_from;     // [groups] the group of prod that each group of the reduce order is
     const uint16_t* tp_pos;
     const float* prod;
     const int32_t* rowptr;
@@ -225,7 +224,8 @@ __global__ __launch_bounds__(WG) void tp_reduce_kernel(const TpReduceArgs a) {
     __shared__ int deferred[kMaxDeferred];
     __shared__ int n_deferred;
     const int tid = threadIdx.x;
-    const int part = blockIdx.x;
+    // a die works through a contiguous stretch of chunks: the lines their tiles share are fetched into one L2
+    const int part = xcd_remap(blockIdx.x, gridDim.x);
     const int r0 = a.chunk_desc[2 * part];
     const int k0 = a.chunk_desc[2 * part + 1];
     const int nr = a.chunk_desc[2 * part + 2] - r0;
@@ -256,7 +256,8 @@ __global__ __launch_bounds__(WG) void tp_reduce_kernel(const TpReduceArgs a) {
         for (int u = 0; u < U; ++u) {
             const int g = gb + u * WG < g1 ? gb + u * WG : g1 - 1;
             pos[u] = __builtin_nontemporal_load(reinterpret_cast<const u16x4*>(a.tp_pos) + g);
-            pp[u] = reinterpret_cast<const f32x4*>(a.prod)[g];  // written a moment ago: a plain load finds much of it still cached
+            // written a moment ago: a plain load finds much of it still cached
+            pp[u] = reinterpret_cast<const f32x4*>(a.prod)[__builtin_nontemporal_load(a.tp_from + g)];
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -421,7 +422,7 @@ struct TpPlaceArgs {
     uint16_t* tp_col;
     void* tp_val;
     int32_t* tp_src;
-    int32_t* tp_dst;
+    int32_t* tp_from;
     uint16_t* tp_pos;
 };
 
@@ -562,7 +563,7 @@ __global__ __launch_bounds__(kWG) void tp_place_kernel(const TpPlaceArgs a) {
             else if (a.elem_bytes == 2) static_cast<uint16_t*>(a.tp_val)[s1] = static_cast<uint16_t>(sval[i]);
             a.tp_src[s1] = k0 + spos[i];
             a.tp_pos[s2] = spos[i];
-            if ((o & 3) == 0) a.tp_dst[s1 >> 2] = s2 >> 2;
+            if ((o & 3) == 0) a.tp_from[s2 >> 2] = s1 >> 2;
         }
         __syncthreads();
     }
@@ -638,14 +639,14 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
             static thread_local size_t allowed = 0;
             if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
             hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
-                               static_cast<const uint16_t*>(t.tp_val), t.tp_dst, static_cast<const uint16_t*>(x), A.n, t.shift,
+                               static_cast<const uint16_t*>(t.tp_val), static_cast<const uint16_t*>(x), A.n, t.shift,
                                t.prod);
         } else {
             auto k = tp_multiply_group_kernel<F32>;
             static thread_local size_t allowed = 0;
             if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
             hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
-                               static_cast<const float*>(t.tp_val), t.tp_dst, static_cast<const float*>(x), A.n, t.shift, t.prod);
+                               static_cast<const float*>(t.tp_val), static_cast<const float*>(x), A.n, t.shift, t.prod);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else if (t.num_pieces > 0) {
@@ -655,18 +656,18 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
             static thread_local size_t allowed = 0;
             if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
             hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
-                               static_cast<const uint16_t*>(t.tp_val), t.tp_dst, static_cast<const uint16_t*>(x), A.n, t.shift,
+                               static_cast<const uint16_t*>(t.tp_val), static_cast<const uint16_t*>(x), A.n, t.shift,
                                t.prod);
         } else {
             auto k = tp_multiply_kernel<F32, kTpMulGroups>;
             static thread_local size_t allowed = 0;
             if ((e = allow_lds(k, lds1, &allowed)) != hipSuccess) return e;
             hipLaunchKernelGGL(k, dim3(t.num_pieces), dim3(kTpMulWG), lds1, st, t.piece_c, t.piece_g, t.tp_col,
-                               static_cast<const float*>(t.tp_val), t.tp_dst, static_cast<const float*>(x), A.n, t.shift, t.prod);
+                               static_cast<const float*>(t.tp_val), static_cast<const float*>(x), A.n, t.shift, t.prod);
         }
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
-    const TpReduceArgs a{t.chunk_desc, t.chunk_g, t.tp_pos, t.prod, A.rowptr, y, t.carry_row, t.carry_val, t.num_chunks,
+    const TpReduceArgs a{t.chunk_desc, t.chunk_g, t.tp_from, t.tp_pos, t.prod, A.rowptr, y, t.carry_row, t.carry_val, t.num_chunks,
                          t.group == 8 ? 3 : 0, s.alpha, s.beta};
     auto k = tp_reduce_kernel<kTpRedWG, kTpRedGroups>;
     static thread_local size_t allowed = 0;
@@ -712,7 +713,7 @@ hipError_t launch_two_phase_tables(const MatrixView& A, int shift, int32_t C, in
 
 hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int32_t P, const TwoPhaseTables& w,
                                   const int32_t* chunk_desc, int64_t slots, int group, uint16_t* tp_col, void* tp_val,
-                                  int32_t* tp_src, int32_t* tp_dst, uint16_t* tp_pos, hipStream_t st) {
+                                  int32_t* tp_src, int32_t* tp_from, uint16_t* tp_pos, hipStream_t st) {
     // padding first: column = the zero slot after the x block, value 0, no source, position "dropped"
     hipLaunchKernelGGL(tp_fill16_kernel, dim3(capped_grid(slots)), dim3(kWG), 0, st, tp_col, slots,
                        static_cast<uint16_t>(1u << shift));
@@ -720,11 +721,11 @@ hipError_t launch_two_phase_place(const MatrixView& A, int shift, int32_t C, int
     hipError_t e = hipMemsetAsync(tp_val, 0, static_cast<size_t>(slots) * group * (A.bf16 ? 2 : 4), st);
     if (e != hipSuccess) return e;
     if ((e = hipMemsetAsync(tp_src, 0xFF, static_cast<size_t>(slots) * 4, st)) != hipSuccess) return e;
-    if ((e = hipMemsetAsync(tp_dst, 0, static_cast<size_t>(slots), st)) != hipSuccess) return e;
+    if ((e = hipMemsetAsync(tp_from, 0, static_cast<size_t>(slots), st)) != hipSuccess) return e;
     const int span_cap = C < kTpBinSpan ? C : kTpBinSpan;
     // group > 1: A is the matrix of groups (colidx = the groups' columns); the values follow in a pass of their own
     const TpPlaceArgs a{w.base1, w.within, w.chunk_first, chunk_desc, A.colidx, A.vals, C,      P,     shift,
-                        group > 1 ? 0 : (A.bf16 ? 2 : 4), span_cap, tp_col, tp_val, tp_src, tp_dst, tp_pos};
+                        group > 1 ? 0 : (A.bf16 ? 2 : 4), span_cap, tp_col, tp_val, tp_src, tp_from, tp_pos};
     const size_t lds = sizeof(int) * (static_cast<size_t>(kWG / 64 + 2) * span_cap + ((span_cap + 4) & ~3)) +
                        static_cast<size_t>(kTwoPhaseItems) * (sizeof(uint32_t) + 3 * sizeof(uint16_t));
     static thread_local size_t allowed = 0;

@@ -64,7 +64,7 @@ class spmv_analysis_host_t(C.Structure):
                 ("run_desc", C.c_void_p), ("pat_pad", C.c_void_p),
                 ("cb_ptr", C.c_void_p), ("cb_row", C.c_void_p), ("cb_col", C.c_void_p), ("cb_src", C.c_void_p),
                 ("tp_row", C.c_void_p), ("tp_nz", C.c_void_p), ("tp_piece_c", C.c_void_p), ("tp_piece_g", C.c_void_p),
-                ("tp_chunk_g", C.c_void_p), ("tp_col", C.c_void_p), ("tp_src", C.c_void_p), ("tp_dst", C.c_void_p),
+                ("tp_chunk_g", C.c_void_p), ("tp_col", C.c_void_p), ("tp_src", C.c_void_p), ("tp_from", C.c_void_p),
                 ("tp_pos", C.c_void_p),
                 ("spmm_rows", C.c_void_p), ("spmm_desc", C.c_void_p), ("spmm_col", C.c_void_p), ("spmm_val", C.c_void_p),
                 ("sell_ptr", C.c_void_p), ("sell_col", C.c_void_p), ("sell_src", C.c_void_p)]
@@ -212,7 +212,7 @@ def _host_buffers(info):
         bufs.update(tp_row=np.zeros(info.tp_num_chunks + 1, np.int32), tp_nz=np.zeros(info.tp_num_chunks + 1, np.int32),
                     tp_piece_c=np.zeros(info.tp_num_pieces, np.int32), tp_piece_g=np.zeros(info.tp_num_pieces + 1, np.int32),
                     tp_chunk_g=np.zeros(info.tp_num_chunks + 1, np.int32), tp_col=np.zeros(info.tp_slots, np.uint16),
-                    tp_src=np.zeros(info.tp_slots, np.int32), tp_dst=np.zeros(info.tp_slots // 4, np.int32),
+                    tp_src=np.zeros(info.tp_slots, np.int32), tp_from=np.zeros(info.tp_slots // 4, np.int32),
                     tp_pos=np.zeros(info.tp_slots, np.uint16))
     if info.plan == SPMV_PLAN_SELL:
         bufs.update(sell_ptr=np.zeros(info.sell_num_slices + 1, np.int32), sell_col=np.zeros(info.sell_slots, np.int32),
