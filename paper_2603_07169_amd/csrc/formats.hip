@@ -134,6 +134,7 @@ __global__ __launch_bounds__(kWG) void spmv_csc_kernel(const int32_t* __restrict
 // The same for matrices with few rows, where the atomics of thousands of columns would queue up
 // on the same few addresses of y: a workgroup adds its columns into a private copy of y in LDS
 // and sends every row's total to memory once.  Few workgroups, so few atomics per address.
+// gridDim.y workgroups share a stretch of columns, each with its own stretch of the rows.
 constexpr int kCscLdsWG = 512;      // lanes of a workgroup of spmv_csc_lds_kernel
 constexpr int kCscLdsBlocks = 128;  // most workgroups it is launched with
 template <typename T, int G>
@@ -143,19 +144,25 @@ __global__ __launch_bounds__(kCscLdsWG) void spmv_csc_lds_kernel(const int32_t* 
                                                            const typename T::elem* __restrict__ x, float* y, int m, int n,
                                                            float alpha) {
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    float* ly = reinterpret_cast<float*>(smem_raw);  // [m]
-    for (int i = threadIdx.x; i < m; i += kCscLdsWG) ly[i] = 0.f;
+    float* ly = reinterpret_cast<float*>(smem_raw);  // [hi - lo]
+    // blockIdx.y: the stretch of rows this workgroup adds up; entries of other rows are read and passed over
+    const int lo = static_cast<int>(static_cast<int64_t>(m) * blockIdx.y / gridDim.y);
+    const int hi = static_cast<int>(static_cast<int64_t>(m) * (blockIdx.y + 1) / gridDim.y);
+    for (int i = threadIdx.x; i < hi - lo; i += kCscLdsWG) ly[i] = 0.f;
     __syncthreads();
     const int tl = threadIdx.x % G;
     for (int j = (blockIdx.x * kCscLdsWG + threadIdx.x) / G; j < n; j += gridDim.x * (kCscLdsWG / G)) {
         const float xj = alpha * widen(x[j]);
         const int e1 = col_offsets[j + 1];
-        for (int e = col_offsets[j] + tl; e < e1; e += G) atomicAdd(ly + row[e], widen(vals[e]) * xj);
+        for (int e = col_offsets[j] + tl; e < e1; e += G) {
+            const int r = row[e];
+            if (r >= lo && r < hi) atomicAdd(ly + (r - lo), widen(vals[e]) * xj);
+        }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < m; i += kCscLdsWG) {
+    for (int i = threadIdx.x; i < hi - lo; i += kCscLdsWG) {
         const float v = ly[i];
-        if (v != 0.f) unsafeAtomicAdd(y + i, v);
+        if (v != 0.f) unsafeAtomicAdd(y + lo + i, v);
     }
 }
 
@@ -288,7 +295,7 @@ hipError_t launch_coo_t(int32_t m, int32_t nnz, const int32_t* row, const int32_
 }
 
 template <typename T, int G>
-hipError_t launch_csc_tg(int32_t m, int32_t n, const int32_t* col_offsets, const int32_t* row, const void* vals,
+hipError_t launch_csc_tg(int32_t m, int32_t n, int32_t nnz, const int32_t* col_offsets, const int32_t* row, const void* vals,
                          const void* x, float* y, Scalars s, hipStream_t st) {
     using E = typename T::elem;
     const int grid = ceil_div(m, kWG);
@@ -296,12 +303,18 @@ hipError_t launch_csc_tg(int32_t m, int32_t n, const int32_t* col_offsets, const
     if (n <= 0) return hipGetLastError();
     const int blocks = ceil_div(static_cast<int64_t>(n) * G, kWG);
     if (m <= kCscLdsRows) {
-        // A private y per workgroup.  The LDS float atomics of a compute unit retire about one lane every three cycles
-        // whatever the workgroup's size, so the time to add the entries falls with the number of workgroups, while each
-        // workgroup sends m global atomics at the end: measured 57 / 31 / 18 / 13 / 15 us with 16 / 32 / 64 / 128 / 256
-        // workgroups on the benchmark's 2048 x 32768 shape (256, 512 or 1024 lanes each: the same).
+        // A private y per workgroup.  A compute unit retires one LDS float atomic every 1.3 ns whatever the workgroup's
+        // size (integer ones every 0.5 ns), so the time to add the entries falls with the number of workgroups, while each
+        // workgroup sends one global atomic per row at the end: measured 57 / 31 / 18 / 13 / 15 us with 16 / 32 / 64 / 128 /
+        // 256 workgroups on the benchmark's 2048 x 32768 shape (256, 512 or 1024 lanes each: the same).  Up to 2^20 entries
+        // entries in columns of eight or more, a second workgroup per stretch of columns takes the other half of the rows:
+        // both read every entry of the stretch, each adds half of them, and no row gets more atomics than before
+        // (13 -> 10.5 us; with 1.3 entries per column the walk over the columns is what takes the time, and doubling it
+        // costs 13.5 -> 15.4 us).
         const int lds_blocks = ceil_div(static_cast<int64_t>(n) * G, kCscLdsWG);
-        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(lds_blocks > kCscLdsBlocks ? kCscLdsBlocks : lds_blocks), dim3(kCscLdsWG), sizeof(float) * m, st,
+        const int col_blocks = lds_blocks > kCscLdsBlocks ? kCscLdsBlocks : lds_blocks;
+        const int parts = (nnz <= (1 << 20) && nnz >= 8 * static_cast<int64_t>(n) && m >= 2) ? 2 : 1;
+        hipLaunchKernelGGL((spmv_csc_lds_kernel<T, G>), dim3(col_blocks, parts), dim3(kCscLdsWG), sizeof(float) * (m / parts + 1), st,
                            col_offsets, row, static_cast<const E*>(vals), static_cast<const E*>(x), y, m, n, s.alpha);
     } else {
         hipLaunchKernelGGL((spmv_csc_kernel<T, G>), dim3(blocks), dim3(kWG), 0, st, col_offsets, row,
@@ -361,8 +374,8 @@ hipError_t launch_csc(bool bf16, int32_t m, int32_t n, int32_t nnz, const int32_
                       const void* vals, const void* x, float* y, Scalars s, hipStream_t st) {
     if (m <= 0) return hipSuccess;
 #define SPMV_CSC_CASE(G) \
-    case G: return bf16 ? launch_csc_tg<BF16, G>(m, n, col_offsets, row, vals, x, y, s, st) \
-                        : launch_csc_tg<F32, G>(m, n, col_offsets, row, vals, x, y, s, st);
+    case G: return bf16 ? launch_csc_tg<BF16, G>(m, n, nnz, col_offsets, row, vals, x, y, s, st) \
+                        : launch_csc_tg<F32, G>(m, n, nnz, col_offsets, row, vals, x, y, s, st);
     switch (lanes_for_length(n > 0 ? (nnz + n - 1) / n : 0)) {
         SPMV_CSC_CASE(2) SPMV_CSC_CASE(4) SPMV_CSC_CASE(8) SPMV_CSC_CASE(16) SPMV_CSC_CASE(32) SPMV_CSC_CASE(64)
     }

@@ -54,7 +54,11 @@ def test_coo(dtype):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_csc(dtype):
-    for p in problems(dtype):
+    # the last three: few rows and long columns, which two workgroups per stretch of columns share by halves of the rows
+    few_rows = [w.from_row_lengths([50, 0, 60, 33, 1, 0, 47], 20, seed=3, dtype=dtype, beta=-0.5, allow_dup=True),
+                w.from_row_lengths([400, 300], 37, seed=4, dtype=dtype, allow_dup=True),
+                w.density_random(2048, 1 << 13, 0.01, dtype=dtype)]
+    for p in problems(dtype) + few_rows:
         log("case csc", p.name, dtype)
         y0 = y_init(p)
         co, row, vals = w.to_csc(p)
