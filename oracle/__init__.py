@@ -23,6 +23,7 @@ _lib = None
 NUM_BINS = 33
 PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock", 8: "twophase"}
 TP_SHIFT, TP_ITEMS, TP_PIECE_GROUPS = 14, 8192, 8192
+TP_PIECE_CAP, TP_PIECE_FLOOR, TP_WAVES = 16384, 2048, 2   # the library's rule for the piece size
 MAX_X_VECTORS = 1024
 MAX_PATTERN_RUNS, MAX_PATTERN_LEN = 4, 64
 SELL_HEIGHT = 64
@@ -112,6 +113,10 @@ def _load():
         _lib.oracle_csr_groups.restype = i32
         _lib.oracle_group_matrix.argtypes = [i64, i64, vp, vp, i32, vp, vp]
         _lib.oracle_group_matrix.restype = None
+        _lib.oracle_two_phase_piece_groups.argtypes = [i64, vp, i32, i32, i32, i32]
+        _lib.oracle_two_phase_piece_groups.restype = i32
+        _lib.oracle_grouped_two_phase_choice.argtypes = [i64, i64, i64, i32, i32, i32, i32, i32, i32, i64, i64]
+        _lib.oracle_grouped_two_phase_choice.restype = i32
         _lib.oracle_sell_slices.argtypes = [i64, vp, i64, vp]
         _lib.oracle_sell_slices.restype = i64
         _lib.oracle_sell_fill.argtypes = [i64, vp, vp, i64, vp, vp, vp]
@@ -406,6 +411,18 @@ def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece
     lib.oracle_two_phase_layout(m, n, _p(rowptr), _p(colidx), shift, items, piece_groups, *[_p(v) for v in out.values()])
     out.update(C=Cn, P=P, S=S, Q=Q)
     return out
+
+
+def two_phase_piece_groups(groups, resident, waves=TP_WAVES, cap=TP_PIECE_CAP, floor=TP_PIECE_FLOOR):
+    """The library's cap on a piece's groups; groups[c] = groups of four slots of column block c."""
+    g = np.ascontiguousarray(groups, dtype=np.int64)
+    return int(_load().oracle_two_phase_piece_groups(g.size, _p(g), resident, waves, cap, floor))
+
+
+def grouped_two_phase_choice(m, n, nnz, dtype, plan, group_aligned, vectors, entries, items=TP_ITEMS):
+    eb, ve = (4, 4) if dtype == "f32" else (2, 8)
+    return int(_load().oracle_grouped_two_phase_choice(m, n, nnz, eb, ve, plan, int(group_aligned), TP_GROUP_SHIFT[dtype], items,
+                                                       vectors, entries))
 
 
 def csr_groups(m, rowptr, colidx, width=TP_GROUP):

@@ -451,6 +451,41 @@ void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const 
     }
 }
 
+// The cap on a piece's groups that the library chooses for a device holding `resident` workgroups of the multiply pass
+// at once (groups[c] = groups of four slots of column block c).  pieces(t) = sum_c ceil(groups[c] / t).  The pass is cut
+// for k rounds of resident workgroups: k = waves when the matrix has waves * resident * floor groups or more, else 1, and
+// raised until pieces(cap) <= k * resident; the answer is the smallest t <= cap with pieces(t) <= k * resident, but never
+// below floor.
+int32_t oracle_two_phase_piece_groups(int64_t C, const int64_t* groups, int32_t resident, int32_t waves, int32_t cap, int32_t floor) {
+    int64_t total = 0;
+    for (int64_t c = 0; c < C; ++c) total += groups[c];
+    int64_t k = total >= static_cast<int64_t>(waves) * resident * floor ? waves : 1;
+    for (;; ++k)
+        for (int64_t t = 1; t <= cap; ++t) {
+            int64_t pieces = 0;
+            for (int64_t c = 0; c < C; ++c) pieces += (groups[c] + t - 1) / t;
+            if (pieces <= k * resident) return static_cast<int32_t>(t < floor ? floor : t);
+        }
+}
+
+// When AUTO takes the two-pass plan on groups of eight.  Candidates are group-aligned matrices that the row-length rule
+// sent to the adaptive or the merge plan.  Taken when x holds at least 1 MiB, the matrix of groups meets the two-pass
+// plan's own size conditions (3 * 2^21 entries, at most 65535 column blocks of 2^shift columns and 2^24 tiles, eight
+// entries or more per tile on average) and the groups are scattered: the counted row blocks touch at least three
+// distinct x vectors per four vectors their entries would fill (vec_elems entries each; vectors < 0: not counted, no).
+int32_t oracle_grouped_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t vec_elems, int32_t plan,
+                                        int32_t group_aligned, int32_t shift, int32_t items, int64_t vectors, int64_t entries) {
+    if (!(plan == 4 || plan == 5) || !group_aligned) return 0;
+    if (vectors < 0 || 4 * vec_elems * vectors < 3 * entries) return 0;
+    const int64_t ng = nnz / 8, ncol = (n + 7) / 8;
+    const int64_t C = (ncol + (int64_t{1} << shift) - 1) >> shift;
+    const int64_t P = (m + ng + items - 1) / items;
+    return (n * elem_bytes >= (int64_t{1} << 20) && ng >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 24) &&
+            8 * C * P <= ng)
+               ? 1
+               : 0;
+}
+
 // How scattered the columns are: the distinct x vectors of the row blocks (nv from oracle_x_windows), summed,
 // against the entries of the blocks that were counted (every block but a single row longer than block_nnz).
 void oracle_scatter_counts(int64_t nb, const int32_t* row_blocks, const int32_t* rowptr, int32_t block_nnz, const int32_t* nv,

@@ -514,6 +514,65 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
         assert np.allclose(y, want, rtol=0, atol=1e-12)
 
 
+def test_two_phase_piece_groups_worked_by_hand():
+    f = oracle.two_phase_piece_groups
+    # one block of 10 groups, 4 workgroups resident, 2 rounds wanted: 10 >= 2 * 4 * 1, so at most 8 pieces: t = 2 (5 pieces; t = 1: 10)
+    assert f([10], 4, waves=2, cap=100, floor=1) == 2
+    # pieces of 3 or more: 10 < 2 * 4 * 3, one round of 4: ceil(10 / 3) = 4 pieces, ceil(10 / 2) = 5
+    assert f([10], 4, waves=2, cap=100, floor=3) == 3
+    # 20 groups: fewer than 2 * 4 * 3, so one round of 4 although pieces of 3 would fill two: ceil(20 / 5) = 4, ceil(20 / 4) = 5
+    assert f([20], 4, waves=2, cap=100, floor=3) == 5
+    # the cap forces more rounds: three blocks of 5, cap 2: 9 pieces at best, 4 resident -> 3 rounds (12); t = 1 gives 15, t = 2 gives 9
+    assert f([5, 5, 5], 4, waves=1, cap=2, floor=1) == 2
+    # a small matrix: any t fills less than the device; the floor is the answer
+    assert f([100], 512, waves=2, cap=16384, floor=2048) == 2048
+    # thirty blocks of 130 000 groups and one of 64 000, 512 resident, two rounds (1024 pieces): 33 pieces per large block
+    # need t >= 3940 (130000 / 3940 = 32.99..), the small one then takes 17: 1007; 34 per large block (t >= 3824) would
+    # make 1020 + 17 = 1037
+    assert f([130_000] * 30 + [64_000], 512) == 3940
+    # empty blocks count for nothing
+    assert f([0, 10, 0], 4, waves=2, cap=100, floor=1) == 2
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_two_phase_piece_groups_is_the_smallest_cap_that_fits(seed):
+    rng = np.random.default_rng(seed)
+    groups = rng.integers(0, 40_000, size=int(rng.integers(1, 40)))
+    resident, waves, cap, floor = int(rng.integers(2, 64)), int(rng.integers(1, 4)), 4096, 16
+    t = oracle.two_phase_piece_groups(groups, resident, waves, cap, floor)
+    pieces = lambda c: int(np.sum(-(-groups // c)))
+    k = waves if groups.sum() >= waves * resident * floor else 1
+    while pieces(cap) > k * resident:
+        k += 1
+    assert floor <= t <= cap and pieces(t) <= k * resident
+    assert t == floor or pieces(t - 1) > k * resident
+    assert k == 1 or (k == waves and groups.sum() >= waves * resident * floor) or pieces(cap) > (k - 1) * resident
+
+
+def test_grouped_two_phase_choice_boundaries():
+    """Config 5 (1 M rows and columns, 16 M groups, bf16: x of 2.0 MB, 31 column blocks of 4096 groups, 2076 chunks) is
+    taken; each condition is then moved across its threshold, the figures worked by hand."""
+    m = n = 1_000_000
+    nnz = 128_000_000
+    E = nnz                                                               # all entries counted
+    yes = lambda **k: oracle.grouped_two_phase_choice(**{**dict(m=m, n=n, nnz=nnz, dtype="bf16", plan=5, group_aligned=1,
+                                                              vectors=15_970_000, entries=E), **k})
+    assert yes() == 1 and yes(plan=4) == 1
+    assert yes(plan=6) == 0 and yes(plan=1) == 0 and yes(group_aligned=0) == 0
+    assert yes(vectors=-1) == 0
+    assert yes(vectors=12_000_000) == 1 and yes(vectors=11_999_999) == 0   # 4 * 8 * v >= 3 * E  <=>  v >= 12 000 000
+    assert yes(dtype="f32", vectors=24_000_000) == 1 and yes(dtype="f32", vectors=23_999_999) == 0   # vectors of four
+    assert yes(n=524_288) == 1 and yes(n=524_287) == 0                    # x of exactly 1 MiB in bf16
+    assert yes(dtype="f32", n=262_144, vectors=24_000_000) == 1 and yes(dtype="f32", n=262_143, vectors=24_000_000) == 0
+    ng = 3 * 2 ** 21                                                       # 6 291 456 groups
+    assert yes(nnz=8 * ng, entries=8 * ng, vectors=ng) == 1 and yes(nnz=8 * ng - 8, entries=8 * ng - 8, vectors=ng) == 0
+    # tiles of eight groups: C = ceil(ceil(n / 8) / 4096), P = ceil((m + ng) / 8192); n = 64 M columns -> C = 1954,
+    # m = 1 M, ng = 16 M -> P = 2076: C * P = 4 056 504 tiles, 8 * that = 32 452 032 > 16 M groups
+    assert yes(n=64_000_000) == 0
+    # n = 32 M -> C = 977: 8 * 977 * 2076 = 16 226 016 > 16 000 000; n = 31 M -> C = 947: 8 * 947 * 2076 = 15 727 776 <= 16 M
+    assert yes(n=32_000_000) == 0 and yes(n=31_000_000) == 1
+
+
 def test_two_phase_choice_rule():
     def f(m, n, nnz, dtype, plan, vectors=None, entries=None):       # scattered unless said otherwise: a vector per entry
         return oracle.two_phase_choice(m, n, nnz, dtype, plan, nnz if vectors is None else vectors, nnz if entries is None else entries)

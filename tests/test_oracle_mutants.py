@@ -55,6 +55,13 @@ MUTANTS = [
     ("analysis_oracle.cpp", "if (nnz < 8) return 0;\n    for (int64_t b = 0; b < nb; ++b)\n        if (rowptr[row_blocks[b]] % 8", "if (nnz < 0) return 0;\n    for (int64_t b = 0; b < nb; ++b)\n        if (rowptr[row_blocks[b]] % 8", "grouped positions: fewer than eight entries accepted"),
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;  // clustered", "column block rule: scatter threshold off by one"),
     ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;  // clustered", "if (4 * vectors < 3 * entries) return 0;  // clustered", "column block rule: uncounted windows taken for scattered"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vec_elems * vectors < 3 * entries) return 0;", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;", "two-pass on groups: scatter measured per entry"),
+    ("analysis_oracle.cpp", "n * elem_bytes >= (int64_t{1} << 20) && ng >= 3", "n * elem_bytes > (int64_t{1} << 20) && ng >= 3", "two-pass on groups: x threshold off by one"),
+    ("analysis_oracle.cpp", "C * P <= (int64_t{1} << 24) &&\n            8 * C * P <= ng)", "C * P <= (int64_t{1} << 24) &&\n            8 * C * P <= nnz)", "two-pass on groups: tiles measured in entries"),
+    ("analysis_oracle.cpp", "if (!(plan == 4 || plan == 5) || !group_aligned) return 0;", "if (!group_aligned) return 0;", "two-pass on groups: taken from any plan"),
+    ("analysis_oracle.cpp", "int64_t k = total >= static_cast<int64_t>(waves) * resident * floor ? waves : 1;", "int64_t k = waves;", "piece size: small matrices cut for several rounds too"),
+    ("analysis_oracle.cpp", "if (pieces <= k * resident) return static_cast<int32_t>(t < floor ? floor : t);", "if (pieces <= k * resident) return static_cast<int32_t>(t);", "piece size: no floor"),
+    ("analysis_oracle.cpp", "for (int64_t c = 0; c < C; ++c) pieces += (groups[c] + t - 1) / t;", "for (int64_t c = 0; c < C; ++c) pieces += groups[c] / t;", "piece size: a block's last, shorter piece not counted"),
     ("analysis_oracle.cpp", "col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));", "col[s1] = static_cast<uint16_t>(colidx[k]);", "two-pass: column not made relative to its block"),
     ("analysis_oracle.cpp", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp] + 1);", "two-pass: position in the chunk off by one"),
     ("analysis_oracle.cpp", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s1 / 4);", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s2 / 4);", "two-pass: products fetched as if they lay in the reduce order"),
