@@ -130,6 +130,8 @@ typedef struct {
     int64_t sell_slots;                /* slots of the sliced copy, padding included (a multiple of 64)          */
     int32_t sell_num_slices;           /* ns = ceil(m / 64): sell_ptr holds ns+1 entries                          */
     int32_t tp_group;                  /* TWOPHASE plan: entries a slot stands for, 1 or 8 (see analyze); 0 otherwise */
+    int32_t tp_piece_groups;           /* TWOPHASE plan: most groups of four slots in a piece of the multiply pass     */
+    int32_t tp_resident;               /* ... and the workgroups of that pass the device holds at once, for which it was chosen */
 } spmv_analysis_info_t;
 
 /* Caller-allocated HOST buffers for spmv_csr_get_analysis(); a NULL member is skipped. */
@@ -252,8 +254,13 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     (column - c * 2^tp_col_shift; padding: 2^tp_col_shift), tp_src (position k in colidx / vals;
  *     padding: -1) and a copy of the value (padding: 0).  Per slot of the reduce order: tp_pos =
  *     k - tp_nz[p] (padding: 0xFFFF); per group of four slots of the reduce order tp_from, the
- *     number of the same group in the multiply order.  Column block c's groups are cut evenly into the fewest pieces of at most
- *     8192 groups: q = ceil(groups / 8192) pieces of ceil(groups / q), the last one shorter
+ *     number of the same group in the multiply order.  Column block c's groups are cut evenly into
+ *     the fewest pieces of at most t = tp_piece_groups groups: q = ceil(groups / t) pieces of
+ *     ceil(groups / q), the last one shorter.  t is chosen for the device: with R = tp_resident
+ *     workgroups of the multiply pass held at once (two per compute unit), t is the smallest cap
+ *     with which the pieces number at most k R, k the fewest rounds that a cap of 16384 allows, at
+ *     least 2 when the matrix has 2 * 2048 * R groups or more; t is never below 2048.  (A launch of
+ *     slightly more than a whole number of rounds leaves the device idle while the last pieces run.)
  *     (tp_piece_c, tp_piece_g; pieces are contiguous, tp_piece_g[Q] = S/4); tp_chunk_g[p] = first
  *     group of chunk p in the reduce order.  run() multiplies piece by piece with the block of x
  *     in LDS and writes the products, in the multiply order, to a scratch array of S floats owned
@@ -275,7 +282,11 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     colidx[8g] / 8 - by the rules above, with column blocks of 2^12 (bf16) or 2^11 (binary32) groups' columns
  *     (64 KB of x either way): tp_src holds group numbers, tp_pos group positions within the chunk, a slot's value copy
  *     the group's eight values, and the product written for a slot is the dot product of those eight with their run of
- *     x.  An eighth of the slots; every size limit above then applies to the matrix of groups.
+ *     x.  An eighth of the slots; every size limit above then applies to the matrix of groups.  AUTO takes this
+ *     form - ahead of the x windows, which are then not built - for a group-aligned matrix that the row lengths sent to
+ *     ADAPTIVE or MERGE when x holds 1 MiB or more, the matrix of groups has 3 * 2^21 entries or more, C2 <= 65535,
+ *     C2 * P2 <= 2^24, 8 * C2 * P2 <= nnz / 8, and the groups are scattered: 4 * VE * sum_b nv_b >= 3 * E (VE = x values per
+ *     16-byte vector, nv_b and E as above).
  *   - the sliced ELL copy (plan SELL only; AUTO never picks it: on every matrix it measured the windowed or the
  *     tile kernel did better).  The ELL storage of paper App. C task 14 - rows of one width, col_id -1 marking
  *     padding - applied to slices of SPMV_SELL_HEIGHT = 64 consecutive rows (rows from m on count as

@@ -325,13 +325,49 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
 
 int two_phase_group_shift(spmv_dtype_t dtype) { return dtype == SPMV_BF16 ? 12 : 11; }
 
-void two_phase_pieces(int64_t C, const int32_t* block_first, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g) {
+bool grouped_two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, bool group_aligned,
+                              int64_t x_vectors_counted, int64_t entries_counted) {
+    if (!(plan == SPMV_PLAN_ADAPTIVE || plan == SPMV_PLAN_MERGE) || !group_aligned) return false;
+    const int64_t elem_bytes = dtype == SPMV_F32 ? 4 : 2, vec_elems = 16 / elem_bytes;
+    if (x_vectors_counted < 0 || 4 * vec_elems * x_vectors_counted < 3 * entries_counted) return false;
+    const int shift = two_phase_group_shift(dtype);
+    const int64_t groups = nnz / kTpGroup, cols = (n + kTpGroup - 1) / kTpGroup;
+    const int64_t C = (cols + (int64_t{1} << shift) - 1) >> shift;
+    const int64_t P = (m + groups + kTwoPhaseItems - 1) / kTwoPhaseItems;
+    return n * elem_bytes >= (int64_t{1} << 20) && groups >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= kTwoPhaseMaxTiles &&
+           8 * C * P <= groups;
+}
+
+int32_t two_phase_piece_groups(int64_t C, const int32_t* block_first, int32_t resident, int32_t waves) {
+    const int64_t total = block_first[C] / 4;
+    auto pieces_at = [&](int64_t cap) {
+        int64_t q = 0;
+        for (int64_t c = 0; c < C; ++c) q += (block_first[c + 1] / 4 - block_first[c] / 4 + cap - 1) / cap;
+        return q;
+    };
+    if (resident < 1) resident = 1;
+    int64_t k = total >= static_cast<int64_t>(waves) * resident * kTwoPhasePieceFloor ? waves : 1;
+    while (pieces_at(kTwoPhasePieceGroups) > k * resident) ++k;
+    // pieces_at falls as the cap grows: the smallest cap that keeps within k rounds
+    int64_t lo = 1, hi = kTwoPhasePieceGroups;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) / 2;
+        if (pieces_at(mid) <= k * resident)
+            hi = mid;
+        else
+            lo = mid + 1;
+    }
+    return static_cast<int32_t>(lo < kTwoPhasePieceFloor ? kTwoPhasePieceFloor : lo);
+}
+
+void two_phase_pieces(int64_t C, const int32_t* block_first, int32_t piece_groups, std::vector<int32_t>* piece_c,
+                      std::vector<int32_t>* piece_g) {
     piece_c->clear();
     piece_g->clear();
     for (int64_t c = 0; c < C; ++c) {
         // the block's groups in the fewest pieces the cap allows, all of one size (the last may be shorter)
         const int64_t first_group = block_first[c] / 4, groups = block_first[c + 1] / 4 - first_group;
-        const int64_t pieces = (groups + kTwoPhasePieceGroups - 1) / kTwoPhasePieceGroups;
+        const int64_t pieces = (groups + piece_groups - 1) / piece_groups;
         const int64_t size = pieces > 0 ? (groups + pieces - 1) / pieces : 1;
         for (int64_t g = first_group; g < first_group + groups; g += size) {
             piece_c->push_back(static_cast<int32_t>(c));

@@ -26,6 +26,10 @@ struct Analysis {
     // (all but single rows longer than block_nnz).
     int64_t x_vectors_counted = -1;
     int64_t entries_counted = 0;
+    // AUTO found the matrix group-aligned and takes the two-pass plan on its groups: the groups' columns (device memory,
+    // nnz / 8 numbers, released once the plan is built)
+    bool two_phase_on_groups = false;
+    int32_t* d_group_cols = nullptr;
 };
 
 // Range-checks the parameters and fills in the defaults that do not depend on the matrix
@@ -59,7 +63,9 @@ void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ip
 
 // The two-pass plan.
 constexpr int kTwoPhaseItems = 8192;               // merge-path steps per chunk of the reduce pass
-constexpr int kTwoPhasePieceGroups = 8192;         // most groups of four slots a workgroup of the multiply pass takes
+constexpr int kTwoPhasePieceGroups = 16384;        // most groups of four slots a workgroup of the multiply pass takes
+constexpr int kTwoPhasePieceFloor = 2048;          // pieces are not made smaller than this to fill the device
+constexpr int kTwoPhaseWaves = 2;                  // rounds of resident workgroups the multiply pass is cut for, where the matrix is large enough
 constexpr int64_t kTwoPhaseMaxTiles = 1 << 24;     // most (column block, chunk) pairs
 int two_phase_shift(int64_t n);                    // log2 of the columns per block
 // Sizes alone: x of 2 MiB or more, 3 * 2^21 entries or more, tiles few and dense enough.
@@ -69,13 +75,25 @@ bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype);
 bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, int64_t x_vectors_counted,
                       int64_t entries_counted);
 // The pieces of the multiply pass from where the column blocks start in the multiply order (block_first[C+1], in slots,
-// the last entry = all slots): every block's groups cut evenly into the fewest pieces of at most kTwoPhasePieceGroups.
+// the last entry = all slots): every block's groups cut evenly into the fewest pieces of at most piece_groups.
 // The two-pass plan on groups of eight entries (a group-aligned matrix: every row starts at a multiple of eight entries and
 // every group of eight is an aligned run of eight consecutive columns).  The matrix of groups has m rows, ceil(n / 8)
 // columns and nnz / 8 entries; its column blocks hold 2^two_phase_group_shift columns (64 KB of x either way).
 constexpr int kTpGroup = 8;
 int two_phase_group_shift(spmv_dtype_t dtype);
-void two_phase_pieces(int64_t C, const int32_t* block_first, std::vector<int32_t>* piece_c, std::vector<int32_t>* piece_g);
+void two_phase_pieces(int64_t C, const int32_t* block_first, int32_t piece_groups, std::vector<int32_t>* piece_c,
+                      std::vector<int32_t>* piece_g);
+// AUTO's rule for the two-pass plan on groups of eight (a group-aligned matrix; plan = what the row-length rule chose):
+// x of 1 MiB or more, the matrix of groups within the two-pass plan's size conditions, scattered groups (three distinct
+// x vectors or more per four that the counted entries would fill).
+bool grouped_two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int32_t plan, bool group_aligned,
+                              int64_t x_vectors_counted, int64_t entries_counted);
+// The cap on a piece's groups for a device that keeps `resident` workgroups of the multiply pass at once.  A launch of a
+// few more pieces than that leaves the device nearly idle while the last ones run (519 pieces on 512 places: 92 us
+// instead of 71 on the 1 M-row block-clustered matrix), so the cap is the smallest one with which the column blocks make
+// at most k * resident pieces, k the fewest rounds that kTwoPhasePieceGroups allows - at least `waves` rounds where
+// pieces of kTwoPhasePieceFloor groups or more remain; never below kTwoPhasePieceFloor.
+int32_t two_phase_piece_groups(int64_t C, const int32_t* block_first, int32_t resident, int32_t waves);
 
 // Sums and maximises the blocks' x vector counts; true when the automatic plan should serve x
 // from the windows: every block within SPMV_MAX_X_VECTORS, and the fixed-stride address lists

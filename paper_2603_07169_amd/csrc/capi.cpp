@@ -185,6 +185,8 @@ spmv::MatrixView view_of(const spmv_csr_s* h) {
 // Counts the x vectors of every row block on the device, settles the plan (AUTO: ADAPTIVE or
 // WINDOWED) and, for WINDOWED, builds xv_ptr / xv_start / lidx.  Needs d_block_nz.
 // count_only: stop after the count (it also says how scattered the columns are).
+spmv_status_t check_groups(spmv_csr_s* h, const std::vector<int32_t>& rowptr_host, bool* aligned, int32_t** d_gcol);
+
 spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, bool count_only, const std::vector<int32_t>& rowptr_host,
                               spmv::Analysis* a) {
     const int64_t nb = a->info.num_row_blocks;
@@ -215,6 +217,17 @@ spmv_status_t build_x_windows(spmv_csr_s* h, bool forced, bool count_only, const
         const int64_t entries = static_cast<int64_t>(rowptr_host[static_cast<size_t>(a->row_blocks[static_cast<size_t>(b) + 1])]) -
                                 rowptr_host[static_cast<size_t>(a->row_blocks[static_cast<size_t>(b)])];
         if (entries <= a->info.block_nnz) a->entries_counted += entries;
+    }
+    // AUTO: a group-aligned matrix with scattered groups goes through the two passes on its groups instead (the windows
+    // are then not built); the sizes are looked at first, the columns only when they allow it
+    if (!forced && spmv::grouped_two_phase_choice(h->m, h->n, h->nnz, h->dtype, a->info.plan, true, total, a->entries_counted)) {
+        bool aligned = false;
+        const spmv_status_t gs = check_groups(h, rowptr_host, &aligned, &a->d_group_cols);
+        if (gs != SPMV_OK) return gs;
+        if (aligned) {
+            a->two_phase_on_groups = true;
+            return SPMV_OK;
+        }
     }
     if (count_only) return SPMV_OK;
     if (forced && largest > SPMV_MAX_X_VECTORS) return SPMV_ERR_UNSUPPORTED;
@@ -469,7 +482,14 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
         return SPMV_ERR_HIP;
     }
     const int64_t slots = block_first[static_cast<size_t>(C)];
-    spmv::two_phase_pieces(C, block_first.data(), &piece_c, &piece_g);
+    // the multiply pass keeps two workgroups of 1024 lanes (64 KB of LDS each) on a compute unit
+    int dev = 0, cus = 0;
+    if (hip_failed(hipGetDevice(&dev)) || hip_failed(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev))) {
+        release();
+        return SPMV_ERR_HIP;
+    }
+    const int32_t piece_groups = spmv::two_phase_piece_groups(C, block_first.data(), 2 * cus, spmv::kTwoPhaseWaves);
+    spmv::two_phase_pieces(C, block_first.data(), piece_groups, &piece_c, &piece_g);
     const size_t S = static_cast<size_t>(slots);
     st = upload(piece_c, &h->d_tp_piece_c);
     if (st == SPMV_OK) st = upload(piece_g, &h->d_tp_piece_g);
@@ -496,6 +516,8 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const std::vector<int32_t>& rowptr_
     a->info.tp_slots = slots;
     a->info.tp_col_shift = shift;
     a->info.tp_items = spmv::kTwoPhaseItems;
+    a->info.tp_piece_groups = piece_groups;
+    a->info.tp_resident = 2 * cus;
     a->info.tp_num_col_blocks = static_cast<int32_t>(C);
     a->info.tp_num_chunks = static_cast<int32_t>(P);
     a->info.tp_num_pieces = static_cast<int32_t>(piece_c.size());
@@ -697,22 +719,26 @@ spmv_status_t spmv_csr_analyze(spmv_handle_t h, const spmv_analyze_params_t* par
         // a matrix headed for the merge plan is counted too where a regrouping plan could take it: is it scattered?
         const bool count_only = p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_MERGE &&
                                 (spmv::two_phase_sizes_ok(h->m, h->n, h->nnz, h->dtype) ||
-                                 spmv::column_block_sizes_ok(h->n, h->nnz, h->dtype));
+                                 spmv::column_block_sizes_ok(h->n, h->nnz, h->dtype) ||
+                                 spmv::grouped_two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan, true, 1, 0));
         if (forced || count_only || (p.plan == SPMV_PLAN_AUTO && a.info.plan == SPMV_PLAN_ADAPTIVE))
             st = build_x_windows(h, forced, count_only, rowptr_host, &a);
     }
     if (st == SPMV_OK) {
-        const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan,
-                                                                                  a.x_vectors_counted, a.entries_counted);
+        const bool automatic = p.plan == SPMV_PLAN_AUTO &&
+                               (a.two_phase_on_groups || spmv::two_phase_choice(h->m, h->n, h->nnz, h->dtype, a.info.plan,
+                                                                                a.x_vectors_counted, a.entries_counted));
         if (p.plan == SPMV_PLAN_TWOPHASE || automatic) {
             // a group-aligned matrix is laid out over its groups of eight entries: an eighth of the slots
             bool aligned = false;
-            int32_t* d_gcol = nullptr;
-            st = check_groups(h, rowptr_host, &aligned, &d_gcol);
-            if (st == SPMV_OK) st = build_two_phase(h, rowptr_host, &a, d_gcol);
-            if (d_gcol) (void)hipFree(d_gcol);
+            if (!a.d_group_cols) st = check_groups(h, rowptr_host, &aligned, &a.d_group_cols);
+            if (st == SPMV_OK) st = build_two_phase(h, rowptr_host, &a, a.d_group_cols);
             if (automatic && st == SPMV_ERR_UNSUPPORTED) st = SPMV_OK;  // too many padded slots: the plan stays what it was
         }
+    }
+    if (a.d_group_cols) {
+        (void)hipFree(a.d_group_cols);
+        a.d_group_cols = nullptr;
     }
     if (st == SPMV_OK) {
         const bool automatic = p.plan == SPMV_PLAN_AUTO && spmv::column_block_choice(h->n, h->nnz, h->dtype, a.info.plan,

@@ -51,7 +51,7 @@ class spmv_analysis_info_t(C.Structure):
                 ("tp_items", C.c_int32), ("tp_num_col_blocks", C.c_int32), ("tp_num_chunks", C.c_int32),
                 ("tp_num_pieces", C.c_int32), ("lidx_grouped", C.c_int32), ("lidx_patterned", C.c_int32),
                 ("pat_cap", C.c_int32), ("pat_entries", C.c_int64), ("sell_slots", C.c_int64), ("sell_num_slices", C.c_int32),
-                ("tp_group", C.c_int32)]
+                ("tp_group", C.c_int32), ("tp_piece_groups", C.c_int32), ("tp_resident", C.c_int32)]
 
     def as_dict(self):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}

@@ -26,6 +26,12 @@ def expected_auto_plan(p, info):
     """The plan AUTO must arrive at, from the oracle's rules."""
     st = oracle.row_stats(p.rowptr)
     plan = oracle.plan(p.m, p.nnz, st["max_len"], info.block_nnz)
+    if plan in (s.SPMV_PLAN_ADAPTIVE, s.SPMV_PLAN_MERGE) and p.nnz >= 3 << 24:     # fewer than 3 * 2^21 groups: the rule says no anyway
+        rb = oracle.row_blocks(p.rowptr, info.block_nnz, info.rows_max)
+        nv, _, _, _ = oracle.x_windows(p.rowptr, p.colidx, rb, info.block_nnz, 8 if p.dtype == "bf16" else 4)
+        vectors, entries = oracle.scatter_counts(p.rowptr, rb, info.block_nnz, nv)
+        if oracle.grouped_two_phase_choice(p.m, p.n, p.nnz, p.dtype, plan, oracle.csr_groups(p.m, p.rowptr, p.colidx), vectors, entries):
+            return s.SPMV_PLAN_TWOPHASE                                            # on groups of eight: looked at before the windows
     if plan == s.SPMV_PLAN_ADAPTIVE:
         rb = oracle.row_blocks(p.rowptr, info.block_nnz, info.rows_max)
         nv, _, _, _ = oracle.x_windows(p.rowptr, p.colidx, rb, info.block_nnz, 8 if p.dtype == "bf16" else 4)
@@ -40,6 +46,13 @@ def expected_auto_plan(p, info):
         elif oracle.column_block_choice(p.n, p.nnz, p.dtype, plan, vectors, entries):
             plan = s.SPMV_PLAN_COLBLOCK
     return plan
+
+
+def check_piece_rule(L, info):
+    """The size of the multiply pass's pieces that the handle reports is the one the oracle's rule gives for the device's
+    count of resident workgroups; L = the oracle's layout made with that size."""
+    groups = np.bincount(L["tp_piece_c"], weights=np.diff(L["tp_piece_g"]), minlength=L["C"]).astype(np.int64)
+    assert info.tp_resident > 0 and info.tp_piece_groups == oracle.two_phase_piece_groups(groups, info.tp_resident)
 
 
 def to_dev(a: np.ndarray, offset_elems: int = 0) -> torch.Tensor:

@@ -7,7 +7,7 @@ import pytest
 import oracle
 import paper_2603_07169_amd as s
 import workloads as w
-from gpu_util import DeviceProblem, assert_close, reference, unpack_run_desc
+from gpu_util import DeviceProblem, assert_close, check_piece_rule, reference, unpack_run_desc
 
 pytestmark = pytest.mark.gpu
 
@@ -16,7 +16,7 @@ EXPECT = {   # nnz, algorithmic bytes, plan chosen by analyze
     2: (5238784, 58687492, "windowed"),
     3: (55742968, 355429332, "windowed"),
     4: (None, None, "twophase"),
-    5: (128000000, 778000004, "windowed"),
+    5: (128000000, 778000004, "twophase"),
 }
 
 
@@ -44,10 +44,11 @@ def test_full_config_matches_oracle(k):
     assert np.array_equal(got["mp_row"], mr) and np.array_equal(got["mp_nz"], mz)
     cnt, off, rows = oracle.row_bins(p.rowptr)
     assert np.array_equal(got["bin_count"], cnt) and np.array_equal(got["bin_rows"], rows)
-    if plan == "twophase":
+    if plan == "twophase" and k == 4:
         assert A.info.tp_group == 1
         # the two-pass regrouping, bit for bit
-        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, piece_groups=A.info.tp_piece_groups)
+        check_piece_rule(L, A.info)
         assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
         for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):
             assert np.array_equal(got[name], L[name]), name
@@ -64,7 +65,26 @@ def test_full_config_matches_oracle(k):
         A.close()
         A = d.matrix(dict(plan=s.SPMV_PLAN_MERGE))      # the merge plan, which AUTO no longer picks here
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full merge")
-    if plan == "windowed":
+    if plan == "twophase" and k == 5:
+        # group-aligned with scattered groups: AUTO takes the two passes on the 16 M groups of eight entries; the regrouping of
+        # the matrix of groups bit for bit
+        assert A.info.tp_group == 8 and oracle.csr_groups(p.m, p.rowptr, p.colidx) == 1
+        assert s.spmv_csr_main_kernel_name(A.handle) == "tp_multiply_group_kernel"
+        rg, cg = oracle.group_matrix(p.m, p.rowptr, p.colidx)
+        L = oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype], piece_groups=A.info.tp_piece_groups)
+        check_piece_rule(L, A.info)
+        assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
+        assert L["Q"] <= 2 * A.info.tp_resident                 # two rounds of resident workgroups, none left over
+        for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):
+            assert np.array_equal(got[name], L[name]), name
+        del L, rg, cg
+        A.close()
+        # the windowed plan, which AUTO no longer picks here: product, grouped positions, windows (below)
+        A = d.matrix(dict(plan=s.SPMV_PLAN_WINDOWED))
+        assert A.info.plan == s.SPMV_PLAN_WINDOWED
+        got = A.analysis()
+        assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full windowed")
+    if A.info.plan == s.SPMV_PLAN_WINDOWED:
         assert A.info.lidx_grouped == (1 if k == 5 else 0)      # config 5's rows are aligned runs of eight columns
         assert A.info.lidx_patterned == (1 if k in (2, 3) else 0)  # the stencils: runs of rows instead of positions
         if A.info.lidx_patterned:
@@ -92,24 +112,9 @@ def test_full_config_matches_oracle(k):
                 assert np.array_equal(got["pat_pad"][b * cap:b * cap + want["pat"].size], want["pat"]), b
                 assert not got["pat_pad"][b * cap + want["pat"].size:(b + 1) * cap].any(), b
         A.close()
-        # the tile kernel (global x gathers) on the same matrix, which AUTO no longer picks here
+        # the tile kernel (global x gathers) on the same matrix, which AUTO does not pick here
         A = d.matrix(dict(plan=s.SPMV_PLAN_ADAPTIVE))
         assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full adaptive")
-        if k == 5:
-            # group-aligned: a forced two-pass plan works on the 16 M groups of eight entries; the regrouping of the matrix of
-            # groups bit for bit, and the product
-            A.close()
-            A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
-            assert A.info.plan == s.SPMV_PLAN_TWOPHASE and A.info.tp_group == 8 and oracle.csr_groups(p.m, p.rowptr, p.colidx) == 1
-            assert s.spmv_csr_main_kernel_name(A.handle) == "tp_multiply_group_kernel"
-            rg, cg = oracle.group_matrix(p.m, p.rowptr, p.colidx)
-            L = oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype])
-            assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
-            got = A.analysis()
-            for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):
-                assert np.array_equal(got[name], L[name]), name
-            del L, rg, cg
-            assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta, strict=True, what="full two-pass on groups")
     A.close()
     if k != 4:
         # the sliced ELL plan (forced; AUTO never picks it) on the near-uniform configs: product, and on the Laplacian the copy itself

@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2603_07169_amd as s
 import workloads as w
-from gpu_util import DeviceProblem, assert_close, reference
+from gpu_util import DeviceProblem, assert_close, check_piece_rule, reference
 
 pytestmark = pytest.mark.gpu
 
@@ -20,11 +20,20 @@ def test_more_than_2_to_30_entries_every_plan():
     y_ref, S_ref = reference(p)
     d = DeviceProblem(p)
 
+    # group-aligned, the runs of a block of rows all at different places: AUTO takes the two passes on the 142 M groups
     A = d.matrix()
     print("  analyzed: plan", s.PLAN_NAMES[A.info.plan], flush=True)
-    assert s.PLAN_NAMES[A.info.plan] == "windowed"
+    assert s.PLAN_NAMES[A.info.plan] == "twophase" and A.info.tp_group == 8 and A.info.tp_slots >= p.nnz // 8
     y = d.run(A)
     worst = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict=True, what="auto")
+    print(f"  two-pass on groups: max |err| / sum|a x| = {worst:.3e}", flush=True)
+    assert np.array_equal(d.run(A), y)
+    A.close()
+
+    A = d.matrix(dict(plan=s.SPMV_PLAN_WINDOWED))
+    assert A.info.plan == s.SPMV_PLAN_WINDOWED and A.info.lidx_grouped == 1
+    y = d.run(A)
+    worst = assert_close(p, y, y_ref, S_ref, p.alpha, p.beta, strict=True, what="windowed")
     print(f"  windowed: max |err| / sum|a x| = {worst:.3e}", flush=True)
     assert np.array_equal(d.run(A), y)
 
@@ -75,7 +84,8 @@ def test_two_pass_plan_on_many_scattered_entries(log2_rows):
     d = DeviceProblem(p)
     A = d.matrix()
     assert A.info.plan == s.SPMV_PLAN_TWOPHASE
-    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, piece_groups=A.info.tp_piece_groups)
+    check_piece_rule(L, A.info)
     assert (A.info.tp_num_col_blocks, A.info.tp_num_chunks, A.info.tp_slots, A.info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
     got = A.analysis()
     for name in ("tp_row", "tp_nz", "tp_piece_c", "tp_piece_g", "tp_chunk_g", "tp_col", "tp_src", "tp_from", "tp_pos"):

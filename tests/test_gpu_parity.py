@@ -8,7 +8,7 @@ import torch
 import oracle
 import paper_2603_07169_amd as s
 import workloads as w
-from gpu_util import (check_patterns_equal_oracle, ALL_PLANS, DeviceProblem, assert_close, check_problem, expected_auto_plan, plan_params, reference,
+from gpu_util import (check_patterns_equal_oracle, check_piece_rule, ALL_PLANS, DeviceProblem, assert_close, check_problem, expected_auto_plan, plan_params, reference,
                       to_dev)
 
 pytestmark = pytest.mark.gpu
@@ -378,7 +378,8 @@ def test_two_phase_layout_equals_oracle_and_multiplies(dtype, n):
     A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
     info = A.info
     assert info.plan == s.SPMV_PLAN_TWOPHASE and info.tp_col_shift == oracle.TP_SHIFT and info.tp_items == oracle.TP_ITEMS
-    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, piece_groups=info.tp_piece_groups)
+    check_piece_rule(L, info)
     assert (info.tp_num_col_blocks, info.tp_num_chunks, info.tp_slots, info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
     got = A.analysis()
     for k in TP_ARRAYS:
@@ -441,7 +442,8 @@ def test_two_phase_seeded_random_shapes(seed):
     if p.nnz == 0:
         assert A.info.plan == s.SPMV_PLAN_SCALAR
     else:
-        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, piece_groups=A.info.tp_piece_groups)
+        check_piece_rule(L, A.info)
         got = A.analysis()
         for k in TP_ARRAYS:
             assert np.array_equal(got[k], L[k]), k
@@ -461,7 +463,8 @@ def test_two_phase_more_column_blocks_than_one_ranking_pass():
     d = DeviceProblem(p)
     A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
     assert A.info.plan == s.SPMV_PLAN_TWOPHASE and A.info.tp_num_col_blocks == (n + (1 << oracle.TP_SHIFT) - 1) >> oracle.TP_SHIFT > 2048
-    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx)
+    L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, piece_groups=A.info.tp_piece_groups)
+    check_piece_rule(L, A.info)
     got = A.analysis()
     for k in TP_ARRAYS:
         assert np.array_equal(got[k], L[k]), k
@@ -519,10 +522,12 @@ def test_sell_does_not_carry_nan_from_x0_into_padded_rows():
     A.close()
 
 
-def group_layout(p):
-    """The two-pass layout of the matrix of groups (what a group-aligned matrix is laid out as)."""
+def group_layout(p, info):
+    """The two-pass layout of the matrix of groups (what a group-aligned matrix is laid out as), pieces as the handle cut them."""
     rg, cg = oracle.group_matrix(p.m, p.rowptr, p.colidx)
-    return oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype])
+    L = oracle.two_phase_layout(p.m, (p.n + 7) // 8, rg, cg, shift=oracle.TP_GROUP_SHIFT[p.dtype], piece_groups=info.tp_piece_groups)
+    check_piece_rule(L, info)
+    return L
 
 
 @pytest.mark.parametrize("dtype,m,n,offset", [("bf16", 20_000, 300_000, 0), ("f32", 9_000, 70_000, 0), ("bf16", 3_000, 40_004, 1),
@@ -540,7 +545,7 @@ def test_two_phase_on_groups_layout_equals_oracle_and_multiplies(dtype, m, n, of
     info = A.info
     assert info.plan == s.SPMV_PLAN_TWOPHASE and info.tp_group == 8 and info.tp_col_shift == oracle.TP_GROUP_SHIFT[dtype]
     assert s.spmv_csr_main_kernel_name(A.handle) == "tp_multiply_group_kernel"
-    L = group_layout(p)
+    L = group_layout(p, A.info)
     assert (info.tp_num_col_blocks, info.tp_num_chunks, info.tp_slots, info.tp_num_pieces) == (L["C"], L["P"], L["S"], L["Q"])
     got = A.analysis()
     for k in TP_ARRAYS:
@@ -573,7 +578,7 @@ def test_two_phase_stays_on_entries_when_a_group_is_broken():
         d = DeviceProblem(q)
         A = d.matrix(dict(plan=s.SPMV_PLAN_TWOPHASE))
         assert A.info.plan == s.SPMV_PLAN_TWOPHASE and A.info.tp_group == 1
-        L = oracle.two_phase_layout(q.m, q.n, q.rowptr, q.colidx)
+        L = oracle.two_phase_layout(q.m, q.n, q.rowptr, q.colidx, piece_groups=A.info.tp_piece_groups)
         got = A.analysis()
         for k in TP_ARRAYS:
             assert np.array_equal(got[k], L[k]), k
