@@ -496,6 +496,12 @@ def main():
         _, r = measure_problem(big, args, params)
         del big
         line["supplementary"] = r
+        # not a config either: config 4's generator with the power law read literally (type-I Pareto, mean row length 2.6)
+        lit = w.powerlaw(4_000_000, literal=True)
+        lit.name = "supplementary_powerlaw_literal_4M_f32"
+        _, r = measure_problem(lit, args, params)
+        del lit
+        line["supplementary_literal"] = r
         line["paper_sweep"] = paper_sweep(args)
         line["spmm_csr"] = spmm_sweep(args)
         line["formats"] = formats_sweep(args)
