@@ -275,7 +275,8 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     a stencil too wide for the x windows - stay with the row-wise plans, whose gathers then
  *     share cache lines.  A forced TWOPHASE plan fails with UNSUPPORTED
  *     when C2 > 65535, C2 * P2 > 2^24 or nnz + 3 * C2 * P2 > SPMV_MAX_SIZE (a bound on S); with m == 0 or nnz == 0 it runs as
- *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own.
+ *     SCALAR.  The library holds 13 + (4 or 2) bytes per slot of its own
+ *     (13 + 8 * (4 or 2) per slot on groups, where a slot stands for eight entries).
  *     On groups (tp_group = 8).  A matrix is group-aligned when every row starts at a multiple of eight entries and every
  *     group of entries 8g .. 8g+7 has the columns c, c+1, .., c+7 with c a multiple of eight.  The two-pass plan is then
  *     laid out over the matrix of groups - m rows, ceil(n / 8) columns, nnz / 8 entries with rowptr / 8 and
