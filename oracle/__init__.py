@@ -23,6 +23,7 @@ _lib = None
 NUM_BINS = 33
 PLAN_NAMES = {1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock", 8: "twophase"}
 TP_SHIFT, TP_ITEMS, TP_PIECE_GROUPS = 14, 8192, 8192
+TP_SNAP = 512            # rows of at most this many entries are never cut by a chunk of the two-pass plan
 TP_PIECE_CAP, TP_PIECE_FLOOR, TP_WAVES = 16384, 2048, 2   # the library's rule for the piece size
 MAX_X_VECTORS = 1024
 MAX_PATTERN_RUNS, MAX_PATTERN_LEN = 4, 64
@@ -101,9 +102,11 @@ def _load():
         _lib.oracle_column_block_width.restype = i64
         _lib.oracle_column_block_choice.argtypes = [i64, i64, i32, i32, i64, i64]
         _lib.oracle_column_block_choice.restype = i32
-        _lib.oracle_two_phase_sizes.argtypes = [i64, i64, vp, vp, i32, i32, i32, vp, vp, vp, vp]
+        _lib.oracle_two_phase_sizes.argtypes = [i64, i64, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp]
         _lib.oracle_two_phase_sizes.restype = None
-        _lib.oracle_two_phase_layout.argtypes = [i64, i64, vp, vp, i32, i32, i32] + [vp] * 9
+        _lib.oracle_two_phase_layout.argtypes = [i64, i64, vp, vp, i32, i32, i32, i32] + [vp] * 9
+        _lib.oracle_merge_path_snapped.argtypes = [i64, i64, vp, i32, i32, vp, vp]
+        _lib.oracle_merge_path_snapped.restype = i64
         _lib.oracle_two_phase_layout.restype = None
         _lib.oracle_two_phase_choice.argtypes = [i64, i64, i64, i32, i32, i32, i32, i64, i64]
         _lib.oracle_scatter_counts.argtypes = [i64, vp, vp, i32, vp, vp, vp]
@@ -397,18 +400,28 @@ def column_block_choice(n, nnz, dtype, plan, vectors, entries):
     return bool(_load().oracle_column_block_choice(n, nnz, 4 if dtype == "f32" else 2, plan, vectors, entries))
 
 
-def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece_groups=TP_PIECE_GROUPS):
+def merge_path_snapped(rowptr, ipc, snap):
+    """Splits of the two-pass plan's chunks: (row, nz), each of P + 1 entries."""
+    m = rowptr.size - 1
+    nnz = int(rowptr[-1])
+    room = (m + nnz) // (ipc - snap) + 2
+    row, nz = np.zeros(room, np.int32), np.zeros(room, np.int32)
+    P = _load().oracle_merge_path_snapped(m, nnz, _p(_chk(rowptr, np.int32)), ipc, snap, _p(row), _p(nz))
+    return row[:P + 1].copy(), nz[:P + 1].copy()
+
+
+def two_phase_layout(m, n, rowptr, colidx, shift=TP_SHIFT, items=TP_ITEMS, piece_groups=TP_PIECE_GROUPS, snap=TP_SNAP):
     """The two-pass plan's regrouping: dict with C, P, S, Q and the arrays tp_row, tp_nz, tp_piece_c, tp_piece_g,
     tp_chunk_g, tp_col, tp_src, tp_from, tp_pos."""
     lib = _load()
     _chk(rowptr, np.int32, m + 1), _chk(colidx, np.int32)
     sizes = [C.c_int64() for _ in range(4)]
-    lib.oracle_two_phase_sizes(m, n, _p(rowptr), _p(colidx), shift, items, piece_groups, *[C.byref(v) for v in sizes])
+    lib.oracle_two_phase_sizes(m, n, _p(rowptr), _p(colidx), shift, items, snap, piece_groups, *[C.byref(v) for v in sizes])
     S, Q, P, Cn = (int(v.value) for v in sizes)
     out = dict(tp_row=np.zeros(P + 1, np.int32), tp_nz=np.zeros(P + 1, np.int32), tp_piece_c=np.zeros(Q, np.int32),
                tp_piece_g=np.zeros(Q + 1, np.int32), tp_chunk_g=np.zeros(P + 1, np.int32), tp_col=np.zeros(S, np.uint16),
                tp_src=np.zeros(S, np.int32), tp_from=np.zeros(S // 4, np.int32), tp_pos=np.zeros(S, np.uint16))
-    lib.oracle_two_phase_layout(m, n, _p(rowptr), _p(colidx), shift, items, piece_groups, *[_p(v) for v in out.values()])
+    lib.oracle_two_phase_layout(m, n, _p(rowptr), _p(colidx), shift, items, snap, piece_groups, *[_p(v) for v in out.values()])
     out.update(C=Cn, P=P, S=S, Q=Q)
     return out
 

@@ -114,6 +114,35 @@ int64_t oracle_merge_path(int64_t m, int64_t nnz, const int32_t* rowptr, int32_t
     return P;
 }
 
+// The chunks of the two-pass plan: the same walk, cut every ipc steps, except that a cut which falls inside a row of at
+// most `snap` entries - some of its entries taken, the row not finished - is moved back to that row's first entry: the
+// chunk ends there, and the next ipc steps are counted from there.  A chunk then cuts only rows longer than snap
+// (snap = 0: the plain merge path; snap < ipc, so every chunk moves forward).  Writes the splits to row[], nz[] (room for
+// (m + nnz) / (ipc - snap) + 2 entries); returns P, the number of chunks.
+int64_t oracle_merge_path_snapped(int64_t m, int64_t nnz, const int32_t* rowptr, int32_t ipc, int32_t snap, int32_t* row,
+                                  int32_t* nz) {
+    const int64_t T = m + nnz;
+    int64_t i = 0, j = 0, p = 0, in_chunk = 0;
+    row[0] = 0;
+    nz[0] = 0;
+    while (i + j < T) {
+        if (i < m && j < nnz && rowptr[i + 1] > j)
+            ++j;
+        else
+            ++i;
+        ++in_chunk;
+        if (in_chunk == ipc || i + j == T) {
+            // inside row i: back to its first entry (the next chunk walks those steps again)
+            if (i < m && rowptr[i] < j && j <= rowptr[i + 1] && rowptr[i + 1] - rowptr[i] <= snap) j = rowptr[i];
+            ++p;
+            row[p] = static_cast<int32_t>(i);
+            nz[p] = static_cast<int32_t>(j);
+            in_chunk = 0;
+        }
+    }
+    return p;
+}
+
 // ---- default row-block shape ---------------------------------------------------------
 // Used when the caller leaves block_nnz / rows_max at 0.  Matrices of at most 2^20 entries
 // (or no rows): 1024 entries, 64 rows.  Otherwise, with mean = ceil(nnz / m) and G the
@@ -355,17 +384,17 @@ int32_t oracle_pattern_choice(int64_t nnz, int64_t covered) { return (nnz > 0 &&
 
 // ---- the two-pass layout ---------------------------------------------------------------
 // Column blocks of 2^shift columns (C of them); chunks = the stretches of the CSR entry list
-// between consecutive merge-path splits taken every `items` steps (P of them).  Tile (c, p) =
+// between consecutive splits of oracle_merge_path_snapped (every `items` steps, rows of at most `snap` entries kept whole; P of them).  Tile (c, p) =
 // the entries of column block c in chunk p, in CSR order, padded to a multiple of four slots.
 // Multiply order: tiles by (c, p); reduce order: tiles by (p, c).  Sizes first: S = padded slots,
 // Q = pieces (every column block's groups of four slots cut evenly into the fewest runs of at most piece_groups).
 void oracle_two_phase_sizes(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int32_t shift, int32_t items,
-                            int32_t piece_groups, int64_t* S, int64_t* Q, int64_t* P_out, int64_t* C_out) {
+                            int32_t snap, int32_t piece_groups, int64_t* S, int64_t* Q, int64_t* P_out, int64_t* C_out) {
     const int64_t nnz = rowptr[m];
     const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
-    const int64_t P = (m + nnz + items - 1) / items;
-    std::vector<int32_t> sr(static_cast<size_t>(P + 1)), sz(static_cast<size_t>(P + 1));
-    oracle_merge_path(m, nnz, rowptr, items, sr.data(), sz.data());
+    const size_t room = static_cast<size_t>((m + nnz) / (items - snap) + 2);
+    std::vector<int32_t> sr(room), sz(room);
+    const int64_t P = oracle_merge_path_snapped(m, nnz, rowptr, items, snap, sr.data(), sz.data());
     std::vector<int64_t> cnt(static_cast<size_t>(C * P), 0);
     int64_t p = 0;
     for (int64_t k = 0; k < nnz; ++k) {
@@ -385,15 +414,16 @@ void oracle_two_phase_sizes(int64_t m, int64_t n, const int32_t* rowptr, const i
     *C_out = C;
 }
 
-// Fills tp_row[P+1], tp_nz[P+1], piece_c[Q], piece_g[Q+1], chunk_g[P+1], col[S], src[S], from[S/4], pos[S].
+// Fills tp_row[P+1], tp_nz[P+1] (room for (m + nnz) / (items - snap) + 2), piece_c[Q], piece_g[Q+1], chunk_g[P+1], col[S],
+// src[S], from[S/4], pos[S].
 // from[g] = the group of the multiply order whose four slots are group g of the reduce order (the products stay where
 // the multiply pass made them; the reduce pass fetches them).
 void oracle_two_phase_layout(int64_t m, int64_t n, const int32_t* rowptr, const int32_t* colidx, int32_t shift, int32_t items,
-                             int32_t piece_groups, int32_t* tp_row, int32_t* tp_nz, int32_t* piece_c, int32_t* piece_g,
+                             int32_t snap, int32_t piece_groups, int32_t* tp_row, int32_t* tp_nz, int32_t* piece_c, int32_t* piece_g,
                              int32_t* chunk_g, uint16_t* col, int32_t* src, int32_t* from, uint16_t* pos) {
     const int64_t nnz = rowptr[m];
     const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
-    const int64_t P = oracle_merge_path(m, nnz, rowptr, items, tp_row, tp_nz);
+    const int64_t P = oracle_merge_path_snapped(m, nnz, rowptr, items, snap, tp_row, tp_nz);
     std::vector<int64_t> cnt(static_cast<size_t>(C * P), 0), start1(static_cast<size_t>(C * P)), start2(static_cast<size_t>(C * P));
     std::vector<int64_t> chunk_of(static_cast<size_t>(nnz));
     int64_t p = 0;

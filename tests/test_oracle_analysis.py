@@ -433,11 +433,49 @@ def test_pattern_choice_rule():
 
 
 
+def test_merge_path_snapped_handworked(golden_dir):
+    for g in json.loads((golden_dir / "merge_path_snapped_handworked.json").read_text())["cases"]:
+        rowptr = np.array(g["rowptr"], np.int32)
+        row, nz = oracle.merge_path_snapped(rowptr, g["ipc"], g["snap"])
+        assert row.tolist() == g["row"] and nz.tolist() == g["nz"], g["_note"]
+        row, nz = oracle.merge_path_snapped(rowptr, g["ipc"], 0)
+        assert row.tolist() == g["plain_row"] and nz.tolist() == g["plain_nz"]
+        mr, mz = oracle.merge_path(rowptr, g["ipc"])
+        assert mr.tolist() == g["plain_row"] and mz.tolist() == g["plain_nz"]
+
+
+@pytest.mark.parametrize("ipc,snap", [(16, 4), (64, 63), (256, 32), (8192, 512), (5, 0)])
+def test_merge_path_snapped_properties(ipc, snap):
+    """From the splits alone: they start at (0, 0) and end at (m, nnz), move forward, no chunk is longer than ipc steps, only
+    the last is shorter than ipc - snap + 1, a row of at most snap entries is never cut, a longer one is cut exactly where
+    the count of steps says; snap = 0 is the plain merge path."""
+    for p in (w.powerlaw(3000, n=900), w.uniform_rows(500, 4000, 7), w.from_row_lengths([0, 0, 900, 1, 0, 77, 3000, 0, 5, 5, 5], 3001, seed=5),
+              w.from_row_lengths([0, 0, 0], 10), w.from_row_lengths([snap + 1] * 40 if snap else [3] * 40, 5000, seed=6),
+              w.from_row_lengths([max(snap, 1)] * 60, 5000, seed=7)):
+        rp = p.rowptr.astype(np.int64)
+        row, nz = oracle.merge_path_snapped(p.rowptr, ipc, snap)
+        assert (row[0], nz[0]) == (0, 0) and (row[-1], nz[-1]) == (p.m, p.nnz)
+        d = row.astype(np.int64) + nz
+        steps = np.diff(d)
+        assert np.all(steps > 0) and np.all(steps <= ipc) and np.all(steps[:-1] >= ipc - snap)
+        assert np.all(np.diff(row) >= 0) and np.all(np.diff(nz) >= 0)
+        inner = np.arange(1, row.size - 1)
+        r, k = row[inner].astype(np.int64), nz[inner].astype(np.int64)
+        assert np.all(rp[r] <= k) and np.all(k <= rp[np.minimum(r + 1, p.m)])            # a split lies in the row after the finished ones
+        cut = (rp[r] < k)                                                                  # entries of row r taken, row r not finished
+        lens = rp[np.minimum(r + 1, p.m)] - rp[r]
+        assert np.all(lens[cut] > snap)                                                    # short rows are whole
+        assert np.all(steps[:-1][cut[: steps.size - 1]] == ipc) if cut.size else True      # a kept cut sits exactly ipc steps on
+        if snap == 0:
+            mr, mz = oracle.merge_path(p.rowptr, ipc)
+            assert np.array_equal(row, mr) and np.array_equal(nz, mz)
+
+
 def test_two_phase_layout_handworked(golden_dir):
     both = json.loads((golden_dir / "two_phase_handworked.json").read_text())
     for g in (both, both["second"]):
         L = oracle.two_phase_layout(g["m"], g["n"], np.array(g["rowptr"], np.int32), np.array(g["colidx"], np.int32),
-                                    g["shift"], g["items"], g["piece_groups"])
+                                    g["shift"], g["items"], g["piece_groups"], snap=0)
         for k in ("C", "P", "S", "Q"):
             assert L[k] == g[k], k
         for k in TP_ARRAYS:
@@ -450,9 +488,10 @@ def test_two_phase_layout_properties(shift, items, piece_groups):
     rng = np.random.default_rng(shift)
     for p in (w.powerlaw(2500, n=700), w.uniform_rows(300, 5000, 9), w.from_row_lengths([0, 0, 900, 1, 0, 77, 3000, 0], 3001, seed=5),
               w.from_row_lengths([0, 0, 0], 10)):
-        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, shift, items, piece_groups)
+        snap = items // 4
+        L = oracle.two_phase_layout(p.m, p.n, p.rowptr, p.colidx, shift, items, piece_groups, snap=snap)
         C, P, S = L["C"], L["P"], L["S"]
-        mp_row, mp_nz = oracle.merge_path(p.rowptr, items)
+        mp_row, mp_nz = oracle.merge_path_snapped(p.rowptr, items, snap)
         assert np.array_equal(L["tp_row"], mp_row) and np.array_equal(L["tp_nz"], mp_nz)
         assert C == -(-p.n // (1 << shift)) and S % 4 == 0 and S >= p.nnz
         src, col, pos, frm = L["tp_src"], L["tp_col"], L["tp_pos"], L["tp_from"]

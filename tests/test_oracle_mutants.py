@@ -62,6 +62,10 @@ MUTANTS = [
     ("analysis_oracle.cpp", "int64_t k = total >= static_cast<int64_t>(waves) * resident * floor ? waves : 1;", "int64_t k = waves;", "piece size: small matrices cut for several rounds too"),
     ("analysis_oracle.cpp", "if (pieces <= k * resident) return static_cast<int32_t>(t < floor ? floor : t);", "if (pieces <= k * resident) return static_cast<int32_t>(t);", "piece size: no floor"),
     ("analysis_oracle.cpp", "for (int64_t c = 0; c < C; ++c) pieces += (groups[c] + t - 1) / t;", "for (int64_t c = 0; c < C; ++c) pieces += groups[c] / t;", "piece size: a block's last, shorter piece not counted"),
+    ("analysis_oracle.cpp", "if (i < m && rowptr[i] < j && j <= rowptr[i + 1] && rowptr[i + 1] - rowptr[i] <= snap) j = rowptr[i];", "if (i < m && rowptr[i] < j && j < rowptr[i + 1] && rowptr[i + 1] - rowptr[i] <= snap) j = rowptr[i];", "two-pass chunks: a row whose entries are all taken but which is not finished is left cut"),
+    ("analysis_oracle.cpp", "if (i < m && rowptr[i] < j && j <= rowptr[i + 1] && rowptr[i + 1] - rowptr[i] <= snap) j = rowptr[i];", "if (i < m && rowptr[i] < j && j <= rowptr[i + 1] && rowptr[i + 1] - rowptr[i] < snap) j = rowptr[i];", "two-pass chunks: rows of exactly snap entries cut"),
+    ("analysis_oracle.cpp", "if (i < m && rowptr[i] < j && j <= rowptr[i + 1] && rowptr[i + 1] - rowptr[i] <= snap) j = rowptr[i];", "if (i < m && rowptr[i] < j && j <= rowptr[i + 1] && rowptr[i + 1] - rowptr[i] <= snap) j = rowptr[i + 1];", "two-pass chunks: the cut moved forward instead of back"),
+    ("analysis_oracle.cpp", "const int64_t P = oracle_merge_path_snapped(m, nnz, rowptr, items, snap, tp_row, tp_nz);", "const int64_t P = oracle_merge_path_snapped(m, nnz, rowptr, items, 0, tp_row, tp_nz);", "two-pass layout: chunks not snapped"),
     ("analysis_oracle.cpp", "col[s1] = static_cast<uint16_t>(colidx[k] - (c << shift));", "col[s1] = static_cast<uint16_t>(colidx[k]);", "two-pass: column not made relative to its block"),
     ("analysis_oracle.cpp", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp]);", "pos[s2] = static_cast<uint16_t>(k - tp_nz[pp] + 1);", "two-pass: position in the chunk off by one"),
     ("analysis_oracle.cpp", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s1 / 4);", "if (o % 4 == 0) from[s2 / 4] = static_cast<int32_t>(s2 / 4);", "two-pass: products fetched as if they lay in the reduce order"),
