@@ -80,6 +80,8 @@ typedef enum {
 } spmv_plan_t;
 
 #define SPMV_SELL_HEIGHT 64 /* rows per slice of the SELL plan */
+/* Rows of at most this many entries (groups, on a group-aligned matrix) are never cut by a chunk of the two-pass plan. */
+#define SPMV_TP_SNAP 512
 
 #define SPMV_MAX_X_VECTORS 1024 /* most 16-byte x vectors in one row block's window */
 
@@ -247,8 +249,12 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     plan fails with UNSUPPORTED when there would be more than 16 blocks.
  *   - the two-pass layout (plan TWOPHASE, or plan AUTO where the rule below holds; built on the
  *     device).  Columns are cut into C2 blocks of 2^tp_col_shift (= 16384) columns; the CSR entry
- *     list is cut by merge-path splits every tp_items (= 8192) steps into P2 chunks (tp_row /
- *     tp_nz, defined like mp_row / mp_nz).  Tile (c, p) = the entries of column block c in chunk
+ *     list is cut into P2 chunks (tp_row / tp_nz: rows finished and entries taken at every cut) by
+ *     walking the merge path as for mp_row / mp_nz and cutting every tp_items (= 8192) steps, except
+ *     that a cut which falls inside a row of at most SPMV_TP_SNAP entries - some of its entries
+ *     taken, the row not finished - is moved back to that row's first entry, and the next tp_items
+ *     steps are counted from there: a chunk cuts only rows longer than SPMV_TP_SNAP, and where no
+ *     row is cut at all, run() launches no fix-up kernel.  Tile (c, p) = the entries of column block c in chunk
  *     p, in CSR order, padded to a multiple of four slots.  The multiply order lists the tiles by
  *     (c, p), the reduce order by (p, c); S slots each.  Per slot of the multiply order: tp_col
  *     (column - c * 2^tp_col_shift; padding: 2^tp_col_shift), tp_src (position k in colidx / vals;

@@ -138,6 +138,41 @@ void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ip
     });
 }
 
+bool merge_path_splits_snapped(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ipc, int64_t snap, std::vector<int32_t>* rows,
+                               std::vector<int32_t>* entries) {
+    const int64_t T = m + nnz;
+    rows->clear();
+    entries->clear();
+    rows->push_back(0);
+    entries->push_back(0);
+    bool cuts = false;
+    int64_t i = 0, j = 0;
+    while (i + j < T) {
+        // the point ipc steps on: the rows finished there lie within ipc rows of the split before (a bisection as in
+        // merge_path_splits)
+        const int64_t d = std::min(i + j + ipc, T);
+        int64_t a = std::max<int64_t>(i, d - nnz), b = std::min<int64_t>({d, m, i + ipc});
+        while (a < b) {
+            const int64_t mid = a + (b - a) / 2;
+            if (static_cast<int64_t>(rowptr[mid + 1]) + mid > d - 1)
+                b = mid;
+            else
+                a = mid + 1;
+        }
+        i = a;
+        j = d - i;
+        if (i < m && rowptr[i] < j) {  // entries of row i taken, row i not finished
+            if (static_cast<int64_t>(rowptr[i + 1]) - rowptr[i] <= snap)
+                j = rowptr[i];
+            else
+                cuts = true;
+        }
+        rows->push_back(static_cast<int32_t>(i));
+        entries->push_back(static_cast<int32_t>(j));
+    }
+    return cuts;
+}
+
 void bin_rows_of(int64_t m, const int32_t* rowptr, std::vector<int32_t>* rows) {
     // a stable counting sort, in one thread: the lengths are counted per bin, then every row goes behind the rows
     // before it in its bin

@@ -63,6 +63,7 @@ void merge_path_splits(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ip
 
 // The two-pass plan.
 constexpr int kTwoPhaseItems = 8192;               // merge-path steps per chunk of the reduce pass
+constexpr int kTwoPhaseSnap = SPMV_TP_SNAP;         // rows of at most this many entries are never cut by a chunk
 constexpr int kTwoPhasePieceGroups = 16384;        // most groups of four slots a workgroup of the multiply pass takes
 constexpr int kTwoPhasePieceFloor = 2048;          // pieces are not made smaller than this to fill the device
 constexpr int kTwoPhaseWaves = 2;                  // rounds of resident workgroups the multiply pass is cut for, where the matrix is large enough
@@ -81,6 +82,11 @@ bool two_phase_choice(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype, int
 // columns and nnz / 8 entries; its column blocks hold 2^two_phase_group_shift columns (64 KB of x either way).
 constexpr int kTpGroup = 8;
 int two_phase_group_shift(spmv_dtype_t dtype);
+// The chunks of the two-pass plan: the merge path cut every ipc steps, a cut that falls inside a row of at most snap
+// entries (some of its entries taken, the row not finished) moved back to that row's first entry, the next ipc steps
+// counted from there (snap < ipc).  Returns whether any chunk still cuts a row: without one there are no carries.
+bool merge_path_splits_snapped(int64_t m, int64_t nnz, const int32_t* rowptr, int64_t ipc, int64_t snap, std::vector<int32_t>* rows,
+                               std::vector<int32_t>* entries);
 void two_phase_pieces(int64_t C, const int32_t* block_first, int32_t piece_groups, std::vector<int32_t>* piece_c,
                       std::vector<int32_t>* piece_g);
 // AUTO's rule for the two-pass plan on groups of eight (a group-aligned matrix; plan = what the row-length rule chose):

@@ -80,6 +80,7 @@ struct spmv_csr_s {
     float* d_tp_carry_val = nullptr;
     size_t tp_reduce_lds = 0;
     std::vector<int32_t> tp_row, tp_nz;  // host copies for the read-back
+    bool tp_carries = true;              // some chunk of the two-pass plan cuts a row
     // The MERGE and TWOPHASE plans keep scratch in the handle (carries, products): a run on another stream while one is
     // still in flight would share it.  An event recorded behind every such run tells.
     hipEvent_t scratch_free = nullptr;
@@ -488,7 +489,7 @@ spmv_status_t build_two_phase(spmv_csr_s* h, const HostRowptr& rowptr_host, spmv
         for (size_t i = 0; i < rowptr_host.size(); ++i) rowptr_groups[i] = rowptr_host[i] / group;
     }
     const int32_t* const rowptr_used = d_gcol ? rowptr_groups.data() : rowptr_host.data();
-    spmv::merge_path_splits(h->m, nent, rowptr_used, spmv::kTwoPhaseItems, &h->tp_row, &h->tp_nz);
+    h->tp_carries = spmv::merge_path_splits_snapped(h->m, nent, rowptr_used, spmv::kTwoPhaseItems, spmv::kTwoPhaseSnap, &h->tp_row, &h->tp_nz);
     const int64_t P = static_cast<int64_t>(h->tp_row.size()) - 1;
     if (C > 65535 || C * P > spmv::kTwoPhaseMaxTiles) return SPMV_ERR_UNSUPPORTED;
     spmv::MatrixView A = view_of(h);
@@ -637,6 +638,7 @@ spmv::TwoPhase two_phase_of(const spmv_csr_s* h) {
     t.group = h->info.tp_group > 1 ? h->info.tp_group : 1;
     t.num_pieces = h->info.tp_num_pieces;
     t.num_chunks = h->info.tp_num_chunks;
+    t.carries = h->tp_carries;
     t.reduce_lds = h->tp_reduce_lds;
     t.piece_c = h->d_tp_piece_c;
     t.piece_g = h->d_tp_piece_g;

@@ -138,6 +138,7 @@ struct TwoPhase {
     int32_t group;              // 1, or 8: a slot stands for a group of eight entries (group-aligned matrix)
     int32_t num_pieces;         // multiply pass: workgroups
     int32_t num_chunks;         // reduce pass: merge-path chunks
+    bool carries;               // some chunk cuts a row: the fix-up kernel has to run
     size_t reduce_lds;          // two_phase_reduce_lds() of the largest chunk
     const int32_t* piece_c;     // [num_pieces]   column block of each piece
     const int32_t* piece_g;     // [num_pieces+1] first group of each piece (pieces are contiguous)

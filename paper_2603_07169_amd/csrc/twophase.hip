@@ -674,6 +674,8 @@ hipError_t launch_two_phase(const TwoPhase& t, const MatrixView& A, const void* 
     if ((e = allow_lds(k, t.reduce_lds, &allowed)) != hipSuccess) return e;
     hipLaunchKernelGGL(k, dim3(t.num_chunks), dim3(kTpRedWG), t.reduce_lds, st, a);
     if ((e = hipGetLastError()) != hipSuccess) return e;
+    // no chunk cuts a row (rows of up to kTwoPhaseSnap entries are kept whole): every carry is empty
+    if (!t.carries) return hipSuccess;
     return launch_merge_fixup(t.carry_row, t.carry_val, t.num_chunks, y, s.alpha, st);
 }
 

@@ -22,6 +22,7 @@ SPMV_OK = 0
 PLAN_NAMES = {0: "auto", 1: "scalar", 2: "vector", 3: "binned", 4: "adaptive", 5: "merge", 6: "windowed", 7: "colblock",
               8: "twophase", 9: "sell"}
 SPMV_SELL_HEIGHT = 64
+SPMV_TP_SNAP = 512
 SPMV_NUM_BINS = 33
 SPMV_MAX_X_VECTORS = 1024
 SPMV_MAX_SIZE = 2 ** 31 - 2 ** 22

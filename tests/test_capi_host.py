@@ -221,6 +221,7 @@ def test_struct_layouts_of_the_binding_match_the_header(tmp_path):
         for field, _ in cls._fields_:
             lines.append(f'  printf("{name} {field} %zu\\n", offsetof({name}, {field}));')
     lines += ['  printf("SPMV_MAX_SIZE %lld\\n", (long long)SPMV_MAX_SIZE);', '  printf("SPMV_SPMM_WINDOW %d\\n", SPMV_SPMM_WINDOW);',
+              '  printf("SPMV_TP_SNAP %d\\n", SPMV_TP_SNAP);', '  printf("SPMV_SELL_HEIGHT %d\\n", SPMV_SELL_HEIGHT);',
               '  return 0;', '}']
     src = tmp_path / "layout.c"
     src.write_text("\n".join(lines))
@@ -237,3 +238,4 @@ def test_struct_layouts_of_the_binding_match_the_header(tmp_path):
             assert seen[(name, field)] == getattr(cls, field).offset, (name, field)
         assert len([k for k in seen if k[0] == name]) == len(cls._fields_) + 1
     assert seen[("SPMV_MAX_SIZE",)] == s.SPMV_MAX_SIZE and seen[("SPMV_SPMM_WINDOW",)] == 4096
+    assert seen[("SPMV_TP_SNAP",)] == s.SPMV_TP_SNAP == oracle.TP_SNAP and seen[("SPMV_SELL_HEIGHT",)] == s.SPMV_SELL_HEIGHT == oracle.SELL_HEIGHT
