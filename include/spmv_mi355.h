@@ -273,8 +273,9 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     by the handle (runs of one handle with this plan must therefore not overlap), then sums
  *     chunk by chunk, fetching every group of the chunk through tp_from; sums are
  *     taken in a fixed order, so results are reproducible bit for bit.  AUTO picks TWOPHASE ahead
- *     of COLBLOCK when 2 n >= W (W as above: x of 2 MiB or more), nnz >= 3 * 2^21, C2 * P2 <= 2^24,
- *     8 * C2 * P2 <= nnz (tiles of eight entries or more on average) and the columns are scattered:
+ *     of COLBLOCK when 2 n >= W (W as above: x of 2 MiB or more), nnz >= 3 * 2^21, C2 * P' <= 2^24,
+ *     8 * C2 * P' <= nnz (tiles of eight entries or more on average; the rule takes P' = ceil((m +
+ *     nnz) / tp_items), the chunk count before any cut is moved) and the columns are scattered:
  *     4 * sum_b nv_b >= 3 * E, with nv_b the distinct x vectors of row block b (the count pass of
  *     the x windows, which AUTO then also runs on a matrix headed for MERGE) and E the entries of
  *     the blocks counted (all but single rows longer than block_nnz).  Clustered columns - a band,
@@ -292,7 +293,7 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     x.  An eighth of the slots; every size limit above then applies to the matrix of groups.  AUTO takes this
  *     form - ahead of the x windows, which are then not built - for a group-aligned matrix that the row lengths sent to
  *     ADAPTIVE or MERGE when x holds 1 MiB or more, the matrix of groups has 3 * 2^21 entries or more, C2 <= 65535,
- *     C2 * P2 <= 2^24, 8 * C2 * P2 <= nnz / 8, and the groups are scattered: 4 * VE * sum_b nv_b >= 3 * E (VE = x values per
+ *     C2 * P' <= 2^24, 8 * C2 * P' <= nnz / 8 (P' = ceil((m + nnz / 8) / tp_items)), and the groups are scattered: 4 * VE * sum_b nv_b >= 3 * E (VE = x values per
  *     16-byte vector, nv_b and E as above).
  *   - the sliced ELL copy (plan SELL only; AUTO never picks it: on every matrix it measured the windowed or the
  *     tile kernel did better).  The ELL storage of paper App. C task 14 - rows of one width, col_id -1 marking
