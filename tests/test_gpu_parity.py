@@ -765,6 +765,42 @@ def test_two_handles_on_two_streams_and_one_handle_refusing_a_second_stream():
         A1.close(), A2.close()
 
 
+def test_analyses_running_at_the_same_time_in_threads():
+    """Four threads analyse four different matrices at once, several times over (the host copy of rowptr goes through one
+    pinned staging buffer that only one analysis can hold; the others take pageable memory of their own): every handle's
+    analysis equals the one made alone, and every product the oracle's."""
+    import threading
+    probs = [w.powerlaw(300_000 + 1000 * i, seed=50 + i) for i in range(4)]
+    devs = [DeviceProblem(p) for p in probs]
+    alone = []
+    for d in devs:
+        A = d.matrix()
+        alone.append((A.info.as_dict(), A.analysis()))
+        A.close()
+    for rep in range(3):
+        log("case analyses in threads", rep)
+        made, errors = [None] * 4, []
+
+        def work(i):
+            try:
+                made[i] = devs[i].matrix()
+            except Exception as e:                   # noqa: BLE001 - reported below, in the main thread
+                errors.append((i, repr(e)))
+
+        threads = [threading.Thread(target=work, args=(i,)) for i in range(4)]
+        [t.start() for t in threads]
+        [t.join() for t in threads]
+        assert not errors, errors
+        for i, A in enumerate(made):
+            info, got = alone[i]
+            assert A.info.as_dict() == info
+            now = A.analysis()
+            assert now.keys() == got.keys() and all(np.array_equal(now[k], got[k]) for k in got), i
+            y_ref, S_ref = reference(probs[i])
+            assert_close(probs[i], devs[i].run(A), y_ref, S_ref, probs[i].alpha, probs[i].beta, what="threads")
+            A.close()
+
+
 def test_column_block_refresh_with_columns_the_caller_did_not_check():
     """skip_validation with a column outside the matrix: the regrouping drops that entry, and refreshing the value copy
     must not read through the slot it left unfilled."""
