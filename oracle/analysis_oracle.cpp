@@ -529,8 +529,8 @@ void oracle_scatter_counts(int64_t nb, const int32_t* row_blocks, const int32_t*
     }
 }
 
-// AUTO takes the two-pass plan (ahead of the column-blocked one) when x holds at least half a column
-// block of the column-blocked plan's width (2 MiB), there are at least 3 * 2^21 entries, at most 65535
+// AUTO takes the two-pass plan (ahead of the column-blocked one) when x holds at least a sixteenth of a column
+// block of the column-blocked plan's width (256 KiB), there are at least 3 * 2^21 entries, at most 65535
 // column blocks and 2^24 tiles, the tiles hold eight entries or more on average, and the columns are
 // scattered: at least three distinct x vectors per four counted entries (vectors < 0: not counted, no).
 int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_bytes, int32_t plan, int32_t shift, int32_t items,
@@ -539,7 +539,7 @@ int32_t oracle_two_phase_choice(int64_t m, int64_t n, int64_t nnz, int32_t elem_
     const int64_t C = (n + (int64_t{1} << shift) - 1) >> shift;
     const int64_t P = (m + nnz + items - 1) / items;
     if (vectors < 0 || 4 * vectors < 3 * entries) return 0;
-    return ((plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 24) &&
+    return ((plan == 4 || plan == 5) && 16 * n >= width && nnz >= 3 * (int64_t{1} << 21) && C <= 65535 && C * P <= (int64_t{1} << 24) &&
             8 * C * P <= nnz)
                ? 1
                : 0;

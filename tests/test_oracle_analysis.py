@@ -619,9 +619,9 @@ def test_two_phase_choice_rule():
     assert f(M, M, 31_913_584, "f32", 5)                       # 245 column blocks x 4384 chunks, 30 entries a tile
     assert f(M, M, 31_913_584, "f32", 4)
     assert not f(M, M, 31_913_584, "f32", 6)                   # only from the adaptive or the merge plan
-    assert not f(M, (1 << 19) - 1, 31_913_584, "f32", 5)       # x smaller than 2 MiB: 2^19 floats ...
-    assert f(M, 1 << 19, 31_913_584, "f32", 5)
-    assert not f(M, (1 << 20) - 1, 31_913_584, "bf16", 5) and f(M, 1 << 20, 31_913_584, "bf16", 5)   # ... 2^20 bf16
+    assert not f(M, (1 << 16) - 1, 31_913_584, "f32", 5)       # x smaller than 256 KiB: 2^16 floats ...
+    assert f(M, 1 << 16, 31_913_584, "f32", 5)
+    assert not f(M, (1 << 17) - 1, 31_913_584, "bf16", 5) and f(M, 1 << 17, 31_913_584, "bf16", 5)   # ... 2^17 bf16
     assert not f(M, M, 3 * (1 << 21) - 1, "f32", 5) and f(1 << 20, M, 3 * (1 << 21), "f32", 5)
     # tiles of fewer than eight entries on average: C = 245, P = ceil((m + nnz) / 8192)
     nnz = 8 * 245 * 4000

@@ -76,12 +76,13 @@ MUTANTS = [
     ("analysis_oracle.cpp", "const int64_t pieces = (groups + piece_groups - 1) / piece_groups;\n        for (int64_t i = 0; i < pieces; ++i) {", "const int64_t pieces = groups / piece_groups + 1;\n        for (int64_t i = 0; i < pieces; ++i) {", "two-pass: one piece too many when the cap divides the block"),
     ("analysis_oracle.cpp", "8 * C * P <= nnz)", "8 * C * P < nnz)", "two-pass rule off by one"),
     ("analysis_oracle.cpp", "C * P <= (int64_t{1} << 24) &&", "C * P < (int64_t{1} << 24) &&", "two-pass rule: tile limit off by one"),
-    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "two-pass rule: scatter threshold off by one"),
-    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "if (4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 2 * n", "two-pass rule: uncounted windows taken for scattered"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 16 * n", "if (vectors < 0 || 4 * vectors <= 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 16 * n", "two-pass rule: scatter threshold off by one"),
+    ("analysis_oracle.cpp", "if (vectors < 0 || 4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 16 * n", "if (4 * vectors < 3 * entries) return 0;\n    return ((plan == 4 || plan == 5) && 16 * n", "two-pass rule: uncounted windows taken for scattered"),
     ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "*entries += in_block;", "scatter counts: over-long rows counted"),
     ("analysis_oracle.cpp", "if (in_block <= block_nnz) *entries += in_block;", "if (in_block < block_nnz) *entries += in_block;", "scatter counts: full blocks left out"),
     ("analysis_oracle.cpp", "nnz >= 3 * (int64_t{1} << 21) && C <= 65535", "nnz > 3 * (int64_t{1} << 21) && C <= 65535", "two-pass rule: entry threshold off by one"),
-    ("analysis_oracle.cpp", "(plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3", "(plan == 4 || plan == 5) && 2 * n > width && nnz >= 3", "two-pass rule: width threshold off by one"),
+    ("analysis_oracle.cpp", "(plan == 4 || plan == 5) && 16 * n >= width && nnz >= 3", "(plan == 4 || plan == 5) && 16 * n > width && nnz >= 3", "two-pass rule: width threshold off by one"),
+    ("analysis_oracle.cpp", "(plan == 4 || plan == 5) && 16 * n >= width && nnz >= 3", "(plan == 4 || plan == 5) && 2 * n >= width && nnz >= 3", "two-pass rule: x of 2 MiB asked for"),
     ("analysis_oracle.cpp", "if (rows_so_far == 1) {\n                    joins = true;", "if (rows_so_far >= 1) {\n                    joins = true;", "row patterns: every step accepted as the run's stride"),
     ("analysis_oracle.cpp", "} else if (step == stride.back()) {", "} else if (step >= stride.back()) {", "row patterns: a larger step joins the run"),
     ("analysis_oracle.cpp", "if (!start.empty() && rel[i] == rel[i - 1]) {", "if (!start.empty() && rel[i].size() == rel[i - 1].size()) {", "row patterns: only the lengths compared"),
