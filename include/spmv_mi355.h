@@ -273,7 +273,7 @@ spmv_status_t spmv_csr_create(spmv_handle_t* out, int64_t m, int64_t n, int64_t 
  *     by the handle (runs of one handle with this plan must therefore not overlap), then sums
  *     chunk by chunk, fetching every group of the chunk through tp_from; sums are
  *     taken in a fixed order, so results are reproducible bit for bit.  AUTO picks TWOPHASE ahead
- *     of COLBLOCK when 2 n >= W (W as above: x of 2 MiB or more), nnz >= 3 * 2^21, C2 * P' <= 2^24,
+ *     of COLBLOCK when 16 n >= W (W as above: x of 256 KiB or more), nnz >= 3 * 2^21, C2 * P' <= 2^24,
  *     8 * C2 * P' <= nnz (tiles of eight entries or more on average; the rule takes P' = ceil((m +
  *     nnz) / tp_items), the chunk count before any cut is moved) and the columns are scattered:
  *     4 * sum_b nv_b >= 3 * E, with nv_b the distinct x vectors of row block b (the count pass of

@@ -341,9 +341,10 @@ int two_phase_shift(int64_t n) {
 }
 
 bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype) {
-    // x of 2 MiB or more and 1.5 * 2^22 entries: below either, the row-wise kernels' gathers (one address-unit slot
-    // each, x out of the L2s) cost less than writing the products out and reading them back
-    if (2 * n < column_block_width(dtype) || nnz < 3 * (int64_t{1} << 21)) return false;
+    // 1.5 * 2^22 entries or more: below that the row-wise kernels' gathers (one address-unit slot each, wherever x
+    // lies) cost less than writing the products out and reading them back over three launches; x of 256 KiB or more
+    // (measured down to there: 80 against 64 us on 16.8 M entries)
+    if (16 * n < column_block_width(dtype) || nnz < 3 * (int64_t{1} << 21)) return false;
     const int64_t C = (n + (int64_t{1} << two_phase_shift(n)) - 1) >> two_phase_shift(n);
     const int64_t P = (m + nnz + kTwoPhaseItems - 1) / kTwoPhaseItems;
     // tiles of at least eight entries on average: the padding to whole groups of four then stays below a fifth

@@ -391,9 +391,9 @@ def test_two_phase_layout_equals_oracle_and_multiplies(dtype, n):
     A.close()
 
 
-@pytest.mark.parametrize("which", ["wide_bf16", "powerlaw_1M_f32", "too_few_entries", "x_too_small", "banded", "banded_wide"])
+@pytest.mark.parametrize("which", ["wide_bf16", "powerlaw_1M_f32", "too_few_entries", "x_too_small", "x_just_enough", "banded", "banded_wide"])
 def test_auto_and_the_two_pass_plan(which):
-    """AUTO = TWOPHASE from x of 2 MiB and 1.5 * 2^22 entries on (tiles of eight entries or more), not below."""
+    """AUTO = TWOPHASE from x of 256 KiB and 1.5 * 2^22 entries on (tiles of eight entries or more), not below."""
     rng = np.random.default_rng(5)
     if which == "wide_bf16":            # 4.3 M bf16 columns, 5 M... entries: not enough; 7 M are
         p = w.from_row_lengths(rng.integers(4, 11, 1_000_000), 4_300_000, seed=9, dtype="bf16", alpha=-2.0, beta=1.0)
@@ -405,12 +405,14 @@ def test_auto_and_the_two_pass_plan(which):
         p = w.banded_random(2_200_000, 2048, 16)
     elif which == "banded":             # big enough, but the columns cluster (a band too wide for the x windows): row-wise gathers stay cheap
         p = w.banded_random(1 << 20, 2048, 16)
-    else:                               # one column short of 2 MiB
-        p = w.from_row_lengths(np.full(1_000_000, 7), 524_287, seed=4)
+    elif which == "x_just_enough":      # x of exactly 256 KiB, 7 M entries
+        p = w.from_row_lengths(np.full(1_000_000, 7), 65_536, seed=4)
+    else:                               # one column short of 256 KiB
+        p = w.from_row_lengths(np.full(1_000_000, 7), 65_535, seed=4)
     log("case auto two-pass", which, p.nnz)
     d = DeviceProblem(p)
     A = d.matrix()
-    want = s.SPMV_PLAN_TWOPHASE if which in ("wide_bf16", "powerlaw_1M_f32") else s.SPMV_PLAN_ADAPTIVE
+    want = s.SPMV_PLAN_TWOPHASE if which in ("wide_bf16", "powerlaw_1M_f32", "x_just_enough") else s.SPMV_PLAN_ADAPTIVE
     assert A.info.plan == want == expected_auto_plan(p, A.info)
     y_ref, S_ref = reference(p)
     assert_close(p, d.run(A), y_ref, S_ref, p.alpha, p.beta)
