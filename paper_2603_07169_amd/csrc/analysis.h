@@ -69,7 +69,7 @@ constexpr int kTwoPhasePieceFloor = 2048;          // pieces are not made smalle
 constexpr int kTwoPhaseWaves = 2;                  // rounds of resident workgroups the multiply pass is cut for, where the matrix is large enough
 constexpr int64_t kTwoPhaseMaxTiles = 1 << 24;     // most (column block, chunk) pairs
 int two_phase_shift(int64_t n);                    // log2 of the columns per block
-// Sizes alone: x of 2 MiB or more, 3 * 2^21 entries or more, tiles few and dense enough.
+// Sizes alone: x of 256 KiB or more, 3 * 2^21 entries or more, tiles few and dense enough.
 bool two_phase_sizes_ok(int64_t m, int64_t n, int64_t nnz, spmv_dtype_t dtype);
 // The whole rule: the sizes, a row-wise plan to replace, and scattered columns (at least three distinct x vectors
 // per four counted entries; x_vectors_counted < 0, nothing counted, says no).
