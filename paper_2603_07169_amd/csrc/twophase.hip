@@ -10,9 +10,10 @@
 //             where the first pass left them (a tile's products lie together, and the tiles of
 //             neighbouring chunks are neighbours, so the chunks a die works on at one time share
 //             their cache lines), drops each into LDS at its CSR position within the chunk
-//             (16-bit), and then runs the
-//             row phase of the tile kernels over them: teams of lanes add up one row each, the
-//             piece of a row that the chunk cuts off leaves as a carry.
+//             (16-bit), and then runs the row phase of the tile kernels over them: teams of lanes
+//             add up one row each, the piece of a row that the chunk cuts off leaves as a carry
+//             (chunks cut only rows of more than SPMV_TP_SNAP entries; where no row is cut the
+//             fix-up kernel that adds the carries is not launched).
 //
 // A tile is the set of entries that share a column block and a chunk.  Its entries keep their CSR
 // order, and every tile is padded to a multiple of four entries (value 0, column = the zero slot
